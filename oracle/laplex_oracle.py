@@ -1,0 +1,200 @@
+"""numpy front end of the CPU oracle (``laplex_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY.  Imported by ``tests/``, by the smoke check and by
+the benchmark's CPU-baseline leg; never by the product package, and it imports
+nothing of the product.  Inputs may be fp32 or fp64; they are widened to fp64
+before anything is computed (App. "Numerical accuracy": the reference is the
+fp64 evaluation of the same fp32 inputs).
+
+Conventions: ``a`` (length k) are output anchors, ``b`` (length n) input
+anchors, ``x`` is (n, batch), ``g`` is (k, batch), both batch-minor.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "laplex_oracle.c")
+_LIB = os.path.join(_HERE, "liblaplex_oracle.so")
+_lib = None
+
+_D = ctypes.POINTER(ctypes.c_double)
+_I = ctypes.c_int64
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (fp64, OpenMP, no fast-math)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall",
+             "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+    return _lib
+
+
+def _f64(v, ndim):
+    v = np.ascontiguousarray(np.asarray(v), dtype=np.float64)
+    if ndim == 2 and v.ndim == 1:
+        v = v.reshape(-1, 1)
+    assert v.ndim == ndim
+    return v
+
+
+def _p(v):
+    return None if v is None else v.ctypes.data_as(_D)
+
+
+# --------------------------------------------------------------------------
+# Route A: the definition.
+# --------------------------------------------------------------------------
+
+def apply_brute(a, b, x):
+    """y = L(a,b) x and the tolerance denominator sum_j L_ij |x_j|."""
+    a, b, x = _f64(a, 1), _f64(b, 1), _f64(x, 2)
+    k, n, batch = a.size, b.size, x.shape[1]
+    assert x.shape[0] == n
+    y = np.zeros((k, batch)); tol = np.zeros((k, batch))
+    _load().oracle_apply_brute(_p(a), _I(k), _p(b), _I(n), _p(x), _I(batch), _I(batch),
+                               _p(y), _p(tol), _I(batch))
+    return y, tol
+
+
+def apply_backward_brute(a, b, x, g):
+    """(gx, ga, gb) and their tolerance denominators (tgx, tga, tgb)."""
+    a, b, x, g = _f64(a, 1), _f64(b, 1), _f64(x, 2), _f64(g, 2)
+    k, n, batch = a.size, b.size, x.shape[1]
+    assert x.shape[0] == n and g.shape == (k, batch)
+    gx = np.zeros((n, batch)); tgx = np.zeros((n, batch))
+    ga = np.zeros(k); tga = np.zeros(k); gb = np.zeros(n); tgb = np.zeros(n)
+    _load().oracle_apply_backward_brute(
+        _p(a), _I(k), _p(b), _I(n), _p(x), _I(batch), _p(g), _I(batch), _I(batch),
+        _p(gx), _p(tgx), _I(batch), _p(ga), _p(tga), _p(gb), _p(tgb))
+    return (gx, ga, gb), (tgx, tga, tgb)
+
+
+def gram_brute(a, x):
+    a, x = _f64(a, 1), _f64(x, 2)
+    n, batch = a.size, x.shape[1]
+    assert x.shape[0] == n
+    y = np.zeros((n, batch)); tol = np.zeros((n, batch))
+    _load().oracle_gram_brute(_p(a), _I(n), _p(x), _I(batch), _I(batch), _p(y), _p(tol), _I(batch))
+    return y, tol
+
+
+def gram_backward_brute(a, x, g):
+    a, x, g = _f64(a, 1), _f64(x, 2), _f64(g, 2)
+    n, batch = a.size, x.shape[1]
+    assert x.shape == g.shape == (n, batch)
+    gx = np.zeros((n, batch)); tgx = np.zeros((n, batch)); ga = np.zeros(n); tga = np.zeros(n)
+    _load().oracle_gram_backward_brute(_p(a), _I(n), _p(x), _I(batch), _p(g), _I(batch), _I(batch),
+                                       _p(gx), _p(tgx), _I(batch), _p(ga), _p(tga))
+    return (gx, ga), (tgx, tga)
+
+
+# --------------------------------------------------------------------------
+# The merged order (stable sort of a followed by b; equal anchors keep the
+# order "outputs by index, then inputs by index").
+# --------------------------------------------------------------------------
+
+def merged_permutation(a, b=None):
+    """ids of the stable ascending sort of concat(a, b) (or of a alone).
+    numpy compares -0.0 == +0.0, so signed zeros tie, as intended."""
+    m = np.asarray(a, dtype=np.float32) if b is None else np.concatenate(
+        [np.asarray(a, dtype=np.float32), np.asarray(b, dtype=np.float32)])
+    return np.argsort(m, kind="stable").astype(np.uint32)
+
+
+# --------------------------------------------------------------------------
+# Route B: Theorem "Dual reduction via the b-axis".
+# --------------------------------------------------------------------------
+
+def _dual(src, val, q, use_abs=False, want=(True, True, True)):
+    """sort src (stable), carry val, evaluate the three sums at the queries."""
+    src, val, q = _f64(src, 1), _f64(val, 2), _f64(q, 1)
+    order = np.argsort(src, kind="stable")
+    s = np.ascontiguousarray(src[order]); v = np.ascontiguousarray(val[order])
+    batch = v.shape[1]
+    outs = [np.zeros((q.size, batch)) if w else None for w in want]
+    rc = _load().oracle_dual_sums(_p(s), _I(s.size), _p(v), _I(batch), _I(batch),
+                                  _p(q), _I(q.size), ctypes.c_int(1 if use_abs else 0),
+                                  _p(outs[0]), _p(outs[1]), _p(outs[2]), _I(batch))
+    if rc != 0:
+        raise MemoryError("oracle_dual_sums")
+    return outs
+
+
+def apply_scan(a, b, x, with_tol=True):
+    """y = L(a,b) x through the dual theorem; also the tolerance denominator."""
+    li, _, rs = _dual(b, x, a, want=(True, False, True))
+    y = li + rs
+    if not with_tol:
+        return y, None
+    li, _, rs = _dual(b, x, a, use_abs=True, want=(True, False, True))
+    return y, li + rs
+
+
+def apply_backward_scan(a, b, x, g):
+    """(gx, ga, gb), (tgx, tga, tgb) through the dual theorem, used twice:
+    inputs sorted / outputs queried for ga, outputs sorted / inputs queried
+    (the transposed operator L(b,a)) for gx and gb.  Strict sums drop ties."""
+    x64, g64 = _f64(x, 2), _f64(g, 2)
+    _, ls, rs = _dual(b, x64, a, want=(False, True, True))
+    ga = np.sum(g64 * (rs - ls), axis=1)
+    li, _, rs_abs = _dual(b, x64, a, use_abs=True, want=(True, False, True))
+    tga = np.sum(np.abs(g64) * (li + rs_abs), axis=1)
+    li, ls, rs = _dual(a, g64, b)
+    gx = li + rs
+    gb = np.sum(x64 * (rs - ls), axis=1)
+    li, _, rs = _dual(a, g64, b, use_abs=True, want=(True, False, True))
+    tgx = li + rs
+    tgb = np.sum(np.abs(x64) * tgx, axis=1)
+    return (gx, ga, gb), (tgx, tga, tgb)
+
+
+def gram_scan(a, x, with_tol=True):
+    li, _, rs = _dual(a, x, a, want=(True, False, True))
+    y = li + rs
+    if not with_tol:
+        return y, None
+    li, _, rs = _dual(a, x, a, use_abs=True, want=(True, False, True))
+    return y, li + rs
+
+
+def gram_backward_scan(a, x, g):
+    x64, g64 = _f64(x, 2), _f64(g, 2)
+    lig, lsg, rsg = _dual(a, g64, a)
+    _, lsx, rsx = _dual(a, x64, a, want=(False, True, True))
+    gx = lig + rsg
+    ga = np.sum(g64 * (rsx - lsx) + x64 * (rsg - lsg), axis=1)
+    li, _, rs = _dual(a, g64, a, use_abs=True, want=(True, False, True))
+    tgx = li + rs
+    li, _, rs = _dual(a, x64, a, use_abs=True, want=(True, False, True))
+    tga = np.sum(np.abs(g64) * (li + rs) + np.abs(x64) * tgx, axis=1)
+    return (gx, ga), (tgx, tga)
+
+
+# --------------------------------------------------------------------------
+# Route C: the definition inside a window, on sampled outputs (batch 1).
+# --------------------------------------------------------------------------
+
+def apply_window(a_sample, b, x, window=64.0):
+    """For each sampled output anchor: sum over inputs within ``window`` of it.
+    What is dropped is below exp(-window) * sum|x| (2e-28 * sum|x| at 64)."""
+    q, b, x = _f64(a_sample, 1), _f64(b, 1), _f64(x, 2)
+    order = np.argsort(b, kind="stable")
+    bs = np.ascontiguousarray(b[order]); xs = np.ascontiguousarray(x[order, :1])
+    y = np.zeros(q.size); tol = np.zeros(q.size)
+    _load().oracle_apply_window(_p(bs), _I(bs.size), _p(xs), _I(1), _p(q), _I(q.size),
+                                ctypes.c_double(window), _p(y), _p(tol))
+    return y, tol

@@ -1,0 +1,344 @@
+"""Pins of the CPU oracle against things other than itself: hand-derived exact
+rational examples, closed forms, invariants, textbook identities, central
+finite differences, and the agreement of its independent routes."""
+import math
+
+import numpy as np
+import pytest
+
+from conftest import read_golden
+
+
+def rng(seed):
+    return np.random.default_rng(seed)
+
+
+# ---------------------------------------------------------------- worked examples
+
+@pytest.mark.parametrize("name", ["apply_rational_3x2.txt", "apply_rational_ties_3x3.txt"])
+@pytest.mark.parametrize("route", ["brute", "scan"])
+def test_golden_apply(oracle, name, route):
+    gd = read_golden(name)
+    a = np.log(np.array(gd["exp_a"])); b = np.log(np.array(gd["exp_b"]))
+    x = np.array(gd["x"]).reshape(-1, 1); g = np.array(gd["g"]).reshape(-1, 1)
+    if route == "brute":
+        y, _ = oracle.apply_brute(a, b, x)
+        (gx, ga, gb), _ = oracle.apply_backward_brute(a, b, x, g)
+    else:
+        y, _ = oracle.apply_scan(a, b, x)
+        (gx, ga, gb), _ = oracle.apply_backward_scan(a, b, x, g)
+    np.testing.assert_allclose(y[:, 0], gd["y"], rtol=1e-14, atol=1e-14)
+    np.testing.assert_allclose(gx[:, 0], gd["gx"], rtol=1e-14, atol=1e-14)
+    np.testing.assert_allclose(ga, gd["ga"], rtol=1e-14, atol=1e-13)
+    np.testing.assert_allclose(gb, gd["gb"], rtol=1e-14, atol=1e-13)
+    perm = oracle.merged_permutation(a.astype(np.float32), b.astype(np.float32))
+    assert perm.tolist() == [int(v) for v in gd["perm"]]
+
+
+@pytest.mark.parametrize("route", ["brute", "scan"])
+def test_golden_gram(oracle, route):
+    gd = read_golden("gram_rational_3.txt")
+    a = np.log(np.array(gd["exp_a"]))
+    x = np.array(gd["x"]).reshape(-1, 1); g = np.array(gd["g"]).reshape(-1, 1)
+    if route == "brute":
+        y, _ = oracle.gram_brute(a, x)
+        (gx, ga), _ = oracle.gram_backward_brute(a, x, g)
+    else:
+        y, _ = oracle.gram_scan(a, x)
+        (gx, ga), _ = oracle.gram_backward_scan(a, x, g)
+    np.testing.assert_allclose(y[:, 0], gd["y"], rtol=1e-14)
+    np.testing.assert_allclose(gx[:, 0], gd["gx"], rtol=1e-14)
+    np.testing.assert_allclose(ga, gd["ga"], rtol=1e-14, atol=1e-13)
+    assert oracle.merged_permutation(a.astype(np.float32)).tolist() == [int(v) for v in gd["perm"]]
+
+
+# ---------------------------------------------------------------- closed forms
+
+@pytest.mark.parametrize("n", [1, 2, 9, 257])
+@pytest.mark.parametrize("route", ["brute", "scan"])
+def test_uniform_grid_geometric_closed_form(oracle, n, route):
+    """a_i = b_i = i*delta, x = 1: rows of the Toeplitz matrix rho^|i-j| sum to
+    (1 + rho - rho^(i+1) - rho^(n-i)) / (1 - rho)  (two geometric series)."""
+    delta = 1.0 / n
+    rho = math.exp(-delta)
+    a = np.arange(n) * delta
+    x = np.ones((n, 1))
+    y = (oracle.apply_brute if route == "brute" else oracle.apply_scan)(a, a, x)[0][:, 0]
+    i = np.arange(n)
+    want = (1 + rho - rho ** (i + 1) - rho ** (n - i)) / (1 - rho)
+    np.testing.assert_allclose(y, want, rtol=1e-12)
+    yg = (oracle.gram_brute if route == "brute" else oracle.gram_scan)(a, x)[0][:, 0]
+    np.testing.assert_allclose(yg, want, rtol=1e-12)
+
+
+def tridiagonal_inverse_apply(a_sorted, y):
+    """K^{-1} y for K_ij = exp(-|a_i-a_j|), a strictly increasing: the
+    Ornstein-Uhlenbeck / AR(1) precision matrix, tridiagonal with
+    rho_i = exp(-(a_{i+1}-a_i)), off-diagonals -rho_i/(1-rho_i^2), diagonal
+    1 + rho_{i-1}^2/(1-rho_{i-1}^2) + rho_i^2/(1-rho_i^2) (absent neighbours dropped)."""
+    n = a_sorted.size
+    rho = np.exp(-np.diff(a_sorted))
+    r2 = rho ** 2 / (1 - rho ** 2)
+    off = -rho / (1 - rho ** 2)
+    diag = np.ones(n)
+    diag[:-1] += r2
+    diag[1:] += r2
+    out = diag[:, None] * y
+    out[:-1] += off[:, None] * y[1:]
+    out[1:] += off[:, None] * y[:-1]
+    return out
+
+
+@pytest.mark.parametrize("route", ["brute", "scan"])
+def test_gram_tridiagonal_inverse_recovers_x(oracle, route):
+    r = rng(3)
+    n, batch = 200, 3
+    a_sorted = np.cumsum(r.uniform(0.05, 1.5, n))
+    p = r.permutation(n)
+    a = a_sorted[p]                              # oracle sees unsorted anchors
+    x = r.normal(size=(n, batch))
+    y = (oracle.gram_brute if route == "brute" else oracle.gram_scan)(a, x)[0]
+    inv = np.empty(n, dtype=int); inv[p] = np.arange(n)
+    x_back = tridiagonal_inverse_apply(a_sorted, y[inv])     # rows back in sorted order
+    np.testing.assert_allclose(x_back, x[inv], rtol=1e-9, atol=1e-9)
+
+
+@pytest.mark.parametrize("route", ["brute", "scan"])
+def test_countsketch_limit_is_exact_bucket_sum(oracle, route):
+    """App. A (Lemma 1 / Prop. 1): with anchors equal to well separated labels,
+    L(a,b) becomes the indicator of a_i == b_j, so y is a bucket sum."""
+    r = rng(4)
+    k, n, batch = 7, 60, 2
+    labels = 800.0 * np.arange(k)          # exp(-800) == 0 in fp64
+    h = r.integers(0, k, n)
+    x = r.normal(size=(n, batch))
+    f = oracle.apply_brute if route == "brute" else oracle.apply_scan
+    y = f(labels, labels[h], x)[0]
+    want = np.zeros((k, batch))
+    np.add.at(want, h, x)
+    np.testing.assert_allclose(y, want, rtol=1e-14, atol=1e-14)
+
+
+def test_one_hot_reads_matrix_entry(oracle):
+    r = rng(5)
+    a = r.uniform(-3, 3, 6); b = r.uniform(-3, 3, 5)
+    for j in range(5):
+        x = np.zeros((5, 1)); x[j] = 1.0
+        y = oracle.apply_scan(a, b, x)[0][:, 0]
+        for i in range(6):
+            assert y[i] == pytest.approx(math.exp(-abs(a[i] - b[j])), rel=1e-13)
+
+
+# ---------------------------------------------------------------- invariants
+
+def test_gram_symmetry_unit_diagonal_positive(oracle):
+    r = rng(6)
+    n = 40
+    a = r.normal(size=n) * 2
+    e = np.eye(n)
+    K = oracle.gram_scan(a, e)[0]                # columns of K
+    np.testing.assert_allclose(np.diag(K), 1.0, rtol=0, atol=1e-15)
+    np.testing.assert_allclose(K, K.T, rtol=1e-13)
+    assert np.linalg.eigvalsh((K + K.T) / 2).min() > 0
+    u = r.normal(size=(n, 1)); v = r.normal(size=(n, 1))
+    assert (u.T @ oracle.gram_brute(a, v)[0]).item() == pytest.approx(
+        (v.T @ oracle.gram_brute(a, u)[0]).item(), rel=1e-12)
+
+
+def test_permuting_anchors_permutes_result(oracle):
+    r = rng(7)
+    n = 33
+    a = np.round(r.normal(size=n) * 2, 1)        # duplicates
+    x = r.normal(size=(n, 2))
+    p = r.permutation(n)
+    y = oracle.gram_scan(a, x)[0]
+    np.testing.assert_allclose(oracle.gram_scan(a[p], x[p])[0], y[p], rtol=1e-12, atol=1e-13)
+
+
+@pytest.mark.parametrize("route", ["brute", "scan"])
+def test_translation_and_reflection(oracle, route):
+    r = rng(8)
+    a = r.uniform(0, 8, 11); b = r.uniform(0, 8, 17)
+    x = r.normal(size=(17, 2)); g = r.normal(size=(11, 2))
+    f = oracle.apply_brute if route == "brute" else oracle.apply_scan
+    fb = oracle.apply_backward_brute if route == "brute" else oracle.apply_backward_scan
+    y = f(a, b, x)[0]
+    np.testing.assert_allclose(f(a + 4.0, b + 4.0, x)[0], y, rtol=1e-12)
+    np.testing.assert_allclose(f(-a, -b, x)[0], y, rtol=1e-12)
+    (gx, ga, gb), _ = fb(a, b, x, g)
+    assert abs(ga.sum() + gb.sum()) < 1e-11 * (np.abs(ga).sum() + np.abs(gb).sum())
+    (gx2, ga2, gb2), _ = fb(-a, -b, x, g)        # reflection flips anchor gradients
+    np.testing.assert_allclose(gx2, gx, rtol=1e-12)
+    np.testing.assert_allclose(ga2, -ga, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(gb2, -gb, rtol=1e-11, atol=1e-12)
+
+
+def test_transpose_identity(oracle):
+    """L(a,b)^T = L(b,a): the input gradient is the apply with roles swapped."""
+    r = rng(9)
+    a = r.uniform(0, 5, 9); b = r.uniform(0, 5, 14)
+    x = r.normal(size=(14, 1)); g = r.normal(size=(9, 3))
+    (gx, _, _), _ = oracle.apply_backward_scan(a, b, np.repeat(x, 3, 1), g)
+    np.testing.assert_allclose(gx, oracle.apply_brute(b, a, g)[0], rtol=1e-12)
+
+
+# ---------------------------------------------------------------- dense library route
+
+def test_against_numpy_dense_matmul(oracle):
+    r = rng(10)
+    a = r.uniform(0, 20, 50); b = r.uniform(0, 20, 70)
+    x = r.normal(size=(70, 4))
+    dense = np.exp(-np.abs(a[:, None] - b[None, :]))
+    for f in (oracle.apply_brute, oracle.apply_scan):
+        y, tol = f(a, b, x)
+        np.testing.assert_allclose(y, dense @ x, rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(tol, dense @ np.abs(x), rtol=1e-12)
+
+
+# ---------------------------------------------------------------- finite differences
+
+def _loss(oracle, a, b, x, g):
+    return float(np.sum(g * oracle.apply_brute(a, b, x)[0]))
+
+
+@pytest.mark.parametrize("route", ["brute", "scan"])
+def test_apply_gradients_central_differences(oracle, route):
+    r = rng(11)
+    k, n, batch = 6, 8, 2
+    a = r.uniform(0, 4, k); b = r.uniform(0, 4, n)
+    x = r.normal(size=(n, batch)); g = r.normal(size=(k, batch))
+    fb = oracle.apply_backward_brute if route == "brute" else oracle.apply_backward_scan
+    (gx, ga, gb), _ = fb(a, b, x, g)
+    h = 1e-6
+    for i in range(k):
+        d = np.zeros(k); d[i] = h
+        fd = (_loss(oracle, a + d, b, x, g) - _loss(oracle, a - d, b, x, g)) / (2 * h)
+        assert ga[i] == pytest.approx(fd, rel=1e-6, abs=1e-8)
+    for j in range(n):
+        d = np.zeros(n); d[j] = h
+        fd = (_loss(oracle, a, b + d, x, g) - _loss(oracle, a, b - d, x, g)) / (2 * h)
+        assert gb[j] == pytest.approx(fd, rel=1e-6, abs=1e-8)
+        for t in range(batch):
+            dx = np.zeros_like(x); dx[j, t] = 1.0
+            assert gx[j, t] == pytest.approx(
+                _loss(oracle, a, b, x + dx, g) - _loss(oracle, a, b, x, g), rel=1e-9, abs=1e-10)
+
+
+@pytest.mark.parametrize("route", ["brute", "scan"])
+def test_anchor_gradient_at_exact_ties_is_central_difference(oracle, route):
+    """sgn(0) = 0: at a_i == b_j the two one-sided slopes cancel in the central
+    difference, and so they do in the analytic gradient."""
+    a = np.array([1.0, 2.0, 2.0, 3.5]); b = np.array([2.0, 1.0, 3.5, 2.0, 0.25])
+    r = rng(12)
+    x = r.normal(size=(5, 2)); g = r.normal(size=(4, 2))
+    fb = oracle.apply_backward_brute if route == "brute" else oracle.apply_backward_scan
+    (_, ga, gb), _ = fb(a, b, x, g)
+    h = 1e-6
+    for i in range(4):
+        d = np.zeros(4); d[i] = h
+        fd = (_loss(oracle, a + d, b, x, g) - _loss(oracle, a - d, b, x, g)) / (2 * h)
+        assert ga[i] == pytest.approx(fd, rel=1e-6, abs=1e-8)
+    for j in range(5):
+        d = np.zeros(5); d[j] = h
+        fd = (_loss(oracle, a, b + d, x, g) - _loss(oracle, a, b - d, x, g)) / (2 * h)
+        assert gb[j] == pytest.approx(fd, rel=1e-6, abs=1e-8)
+
+
+@pytest.mark.parametrize("route", ["brute", "scan"])
+def test_gram_gradients_central_differences(oracle, route):
+    r = rng(13)
+    n, batch = 7, 2
+    a = r.uniform(0, 3, n); a[4] = a[1]          # one duplicated anchor
+    x = r.normal(size=(n, batch)); g = r.normal(size=(n, batch))
+    fb = oracle.gram_backward_brute if route == "brute" else oracle.gram_backward_scan
+    (gx, ga), _ = fb(a, x, g)
+    np.testing.assert_allclose(gx, oracle.gram_brute(a, g)[0], rtol=1e-12)
+    h = 1e-6
+    loss = lambda aa: float(np.sum(g * oracle.gram_brute(aa, x)[0]))
+    for m in range(n):
+        d = np.zeros(n); d[m] = h
+        assert ga[m] == pytest.approx((loss(a + d) - loss(a - d)) / (2 * h), rel=1e-6, abs=1e-8)
+    assert abs(ga.sum()) < 1e-10 * np.abs(ga).sum()
+
+
+# ---------------------------------------------------------------- route against route
+
+CASES = {
+    "uniform": lambda r, k, n: (r.uniform(0, 30, k), r.uniform(0, 30, n)),
+    "ties": lambda r, k, n: (np.round(r.uniform(0, 8, k) * 4) / 4, np.round(r.uniform(0, 8, n) * 4) / 4),
+    "all_equal": lambda r, k, n: (np.full(k, 1.5), np.full(n, 1.5)),
+    "huge_gaps": lambda r, k, n: (r.integers(0, 6, k) * 900.0, r.integers(0, 6, n) * 900.0 + 0.5),
+    "negative": lambda r, k, n: (-r.uniform(0, 10, k), r.normal(size=n) * 3),
+    "outside": lambda r, k, n: (np.concatenate([[-50.0], r.uniform(0, 5, k - 2), [60.0]]), r.uniform(1, 4, n)),
+}
+
+
+@pytest.mark.parametrize("case", sorted(CASES))
+@pytest.mark.parametrize("k,n,batch", [(1, 1, 1), (5, 1, 2), (1, 6, 1), (37, 53, 3)])
+def test_scan_route_matches_brute_force(oracle, case, k, n, batch):
+    if case == "outside" and k < 3:
+        pytest.skip("needs k >= 3")
+    r = rng(100 + k + n)
+    a, b = CASES[case](r, k, n)
+    a = a.astype(np.float32); b = b.astype(np.float32)
+    x = r.normal(size=(n, batch)).astype(np.float32); g = r.normal(size=(k, batch)).astype(np.float32)
+    y0, t0 = oracle.apply_brute(a, b, x); y1, t1 = oracle.apply_scan(a, b, x)
+    assert np.all(np.abs(y0 - y1) <= 1e-12 * t0 + 1e-300)
+    np.testing.assert_allclose(t1, t0, rtol=1e-12)
+    (gx0, ga0, gb0), (tx0, ta0, tb0) = oracle.apply_backward_brute(a, b, x, g)
+    (gx1, ga1, gb1), (tx1, ta1, tb1) = oracle.apply_backward_scan(a, b, x, g)
+    assert np.all(np.abs(gx0 - gx1) <= 1e-12 * tx0 + 1e-300)
+    assert np.all(np.abs(ga0 - ga1) <= 1e-12 * ta0 + 1e-300)
+    assert np.all(np.abs(gb0 - gb1) <= 1e-12 * tb0 + 1e-300)
+    for u, v in ((tx0, tx1), (ta0, ta1), (tb0, tb1)):
+        np.testing.assert_allclose(v, u, rtol=1e-12, atol=1e-300)
+
+
+@pytest.mark.parametrize("case", ["uniform", "ties", "all_equal", "huge_gaps"])
+def test_gram_scan_route_matches_brute_force(oracle, case):
+    r = rng(200)
+    a, _ = CASES[case](r, 41, 1)
+    a = a.astype(np.float32)
+    x = r.normal(size=(41, 2)); g = r.normal(size=(41, 2))
+    y0, t0 = oracle.gram_brute(a, x); y1, t1 = oracle.gram_scan(a, x)
+    assert np.all(np.abs(y0 - y1) <= 1e-12 * t0)
+    (gx0, ga0), (tx0, ta0) = oracle.gram_backward_brute(a, x, g)
+    (gx1, ga1), (tx1, ta1) = oracle.gram_backward_scan(a, x, g)
+    assert np.all(np.abs(gx0 - gx1) <= 1e-12 * tx0)
+    assert np.all(np.abs(ga0 - ga1) <= 1e-12 * ta0 + 1e-300)
+    np.testing.assert_allclose(ta1, ta0, rtol=1e-12)
+
+
+def test_window_route_matches_brute_force(oracle):
+    r = rng(300)
+    b = r.uniform(0, 400, 3000).astype(np.float32); a = r.uniform(-10, 410, 200).astype(np.float32)
+    x = r.normal(size=(3000, 1)).astype(np.float32)
+    y0, t0 = oracle.apply_brute(a, b, x)
+    y1, t1 = oracle.apply_window(a, b, x, window=64.0)
+    bound = math.exp(-64.0) * np.abs(x).sum()
+    assert np.all(np.abs(y0[:, 0] - y1) <= 1e-13 * t0[:, 0] + bound)
+    assert np.all(np.abs(t0[:, 0] - t1) <= 1e-13 * t0[:, 0] + bound)
+
+
+def test_empty_input_side(oracle):
+    y, tol = oracle.apply_scan(np.array([1.0, 2.0]), np.zeros(0), np.zeros((0, 2)))
+    assert y.shape == (2, 2) and not y.any() and not tol.any()
+
+
+# ---------------------------------------------------------------- merged order
+
+def test_merged_permutation_is_stable_with_outputs_first(oracle):
+    a = np.array([2.0, -0.0, 1.0, 2.0], dtype=np.float32)
+    b = np.array([0.0, 2.0, -3.0, 1.0], dtype=np.float32)
+    # keys: -3(b2) | 0(a1), 0(b0) | 1(a2), 1(b3) | 2(a0), 2(a3), 2(b1); signed zeros tie
+    assert oracle.merged_permutation(a, b).tolist() == [6, 1, 4, 2, 7, 0, 3, 5]
+
+
+def test_merged_permutation_brute_force_rank(oracle):
+    r = rng(14)
+    m = np.round(r.normal(size=300) * 3).astype(np.float32)
+    perm = oracle.merged_permutation(m[:120], m[120:])
+    # rank of id i = #{j : m_j < m_i} + #{j < i : m_j == m_i}
+    rank = np.array([(m < m[i]).sum() + (m[:i] == m[i]).sum() for i in range(300)])
+    want = np.empty(300, dtype=np.int64); want[rank] = np.arange(300)
+    assert perm.tolist() == want.tolist()
