@@ -1,0 +1,172 @@
+/*
+ * liblaplex — the LAPLEX apply on one MI355X (gfx950), C ABI.
+ *
+ *   y = L(a,b) x,   L_ij = exp(-|a_i - b_j|),   i < k outputs, j < n inputs
+ *
+ * (Introduction: the Laplace-kernel matrix; Sec. 3: the exact reduction of the
+ * product to a sort and two decayed scans.)  Letters follow this library's
+ * convention, not the theorems': `a` holds the k OUTPUT anchors, `b` the n
+ * INPUT anchors, L is k x n.
+ *
+ * Common rules for every entry point
+ *  - Every pointer is a DEVICE pointer unless marked "host".  The caller owns
+ *    all buffers, including the workspace.  Inputs are const and untouched;
+ *    outputs are overwritten, never accumulated into.
+ *  - Batched data are batch-minor: element (row r, batch column t) of a matrix
+ *    with leading dimension ld lives at [r*ld + t], ld >= batch.  batch == 1
+ *    with ld == 1 is the plain-vector case.
+ *  - Calls only enqueue work on `stream`; they never synchronise, allocate or
+ *    free.  Two calls that share a workspace must be ordered by the caller
+ *    (same stream, or events).
+ *  - Return value: LAPLEX_OK or a negative LAPLEX_ERR_*.  Arguments are
+ *    checked on the host before the first HIP call, so an argument error
+ *    leaves every buffer untouched.  No exception crosses the boundary.
+ *  - Limits: 0 <= k, n, batch; k + n <= LAPLEX_MAX_MERGED; float pointers
+ *    4-byte aligned (16-byte aligned pointers with batch and ld multiples of 4
+ *    take the 128-bit access path of the same kernels); `ws` 256-byte aligned.
+ *  - Anchors must be finite.  NaN or infinite anchors give unspecified values
+ *    but never a hang or an out-of-bounds access.  -0.0 is treated as +0.0.
+ *  - Equal anchors are ordered "outputs by index, then inputs by index"
+ *    (stable sort of a followed by b; Thm 1's half-open intervals put an input
+ *    equal to an output after it).  The product does not depend on that order;
+ *    anchor gradients use sgn(0) = 0 at ties, i.e. tied pairs contribute
+ *    nothing to ga / gb (the paper prints no backward formula; this is the
+ *    central-difference limit of the definition).
+ *
+ * Workspace.  laplex_workspace_bytes(k, n, batch, ...) gives the size for the
+ * apply form; the Gram form of n anchors uses (k = 0, n, batch).  Its front
+ * holds the PLAN of the anchors: the sorted order (ids) and the decay between
+ * sorted neighbours.  The plan depends on the anchors only, so it stays valid
+ * across batches and across the forward / backward pair until the anchors
+ * change or the caller overwrites it (Sec. 3 "Complexity": the sorted order is
+ * reused across batches).  After the plan comes the saved-scan region written
+ * under LAPLEX_SAVE_SCANS, then scratch whose contents are undefined between
+ * calls.
+ */
+#ifndef LAPLEX_H
+#define LAPLEX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ihipStream_t* laplex_stream_t; /* a hipStream_t; NULL = the default stream */
+
+enum {
+    LAPLEX_OK = 0,
+    LAPLEX_ERR_NULL = -1,      /* a required pointer is NULL */
+    LAPLEX_ERR_SIZE = -2,      /* negative size, or k + n above LAPLEX_MAX_MERGED */
+    LAPLEX_ERR_LD = -3,        /* a leading dimension below batch */
+    LAPLEX_ERR_WORKSPACE = -4, /* ws_bytes below laplex_workspace_bytes(...) */
+    LAPLEX_ERR_FLAGS = -5,     /* unknown bit, or a bit that has no meaning for this call */
+    LAPLEX_ERR_HIP = -6,       /* a HIP launch failed; see laplex_last_hip_error() */
+    LAPLEX_ERR_ALIGN = -7      /* a float pointer not 4-byte, or ws not 256-byte, aligned */
+};
+
+enum {
+    /* The caller promises a / b ascending.  With both set (or A_SORTED for the
+     * Gram form) the radix sort is replaced by one merge-path pass.  A wrong
+     * promise gives wrong values, never a fault. */
+    LAPLEX_A_SORTED = 1u,
+    LAPLEX_B_SORTED = 2u,
+    /* The workspace already holds the plan of these same anchors (from an
+     * earlier call with the same k, n, batch): skip sort, merge and decay. */
+    LAPLEX_REUSE_PLAN = 4u,
+    /* Forward calls: also store, per output row and batch column, the signed
+     * difference of the strict right and left scans in the workspace.
+     * Backward calls: that region was stored by the forward call on the same
+     * (anchors, x); use it for the anchor gradient instead of re-scanning x. */
+    LAPLEX_SAVE_SCANS = 8u
+};
+
+#define LAPLEX_MAX_MERGED 4294967294LL /* ids are 32-bit; 2^32-1 positions plus a sentinel slot */
+
+/* Bytes of workspace for an apply with k outputs, n inputs and `batch`
+ * columns (Gram form: k = 0).  `out` is a host pointer.  Pure host arithmetic. */
+int laplex_workspace_bytes(int64_t k, int64_t n, int64_t batch, size_t* out);
+
+/*
+ * Forward apply (Sec. 3, Thm 1 / App. B "Matvec proofs"; computed here as one
+ * sort of the merged anchors and a forward plus a backward decayed scan
+ * s_j = exp(-(p_j - p_{j-1})) s_{j-1} + x_j over the merged sequence):
+ *   y[i*ldy + t] = sum_j exp(-|a[i]-b[j]|) * x[j*ldx + t],   i<k, j<n, t<batch.
+ * n == 0 writes zeros; k == 0 or batch == 0 does nothing.
+ * Flags: A_SORTED, B_SORTED, REUSE_PLAN, SAVE_SCANS.
+ */
+int laplex_apply(const float* a, int64_t k, const float* b, int64_t n,
+                 const float* x, int64_t ldx, int64_t batch,
+                 float* y, int64_t ldy,
+                 void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream);
+
+/*
+ * Backward of the apply for the loss sum_{i,t} gy[i*ldgy+t] * y[i*ldy+t]
+ * (Sec. 5 / App. "Matvec benchmark": exact gradients w.r.t. x, a, b at the cost
+ * of the forward's scans):
+ *   gx[j*ldgx+t] = sum_i L_ij gy[i,t]
+ *   ga[i] = -sum_t gy[i,t] sum_j sgn(a_i-b_j) L_ij x[j,t]
+ *   gb[j] = +sum_t x[j,t]  sum_i sgn(a_i-b_j) L_ij gy[i,t]        (sgn(0) = 0)
+ * Any of gx, ga, gb may be NULL (not wanted).  x may be NULL when both ga and
+ * gb are NULL.  Empty sides give zeros in whatever is wanted.
+ * Flags: A_SORTED, B_SORTED, REUSE_PLAN, SAVE_SCANS (see above).
+ */
+int laplex_apply_backward(const float* a, int64_t k, const float* b, int64_t n,
+                          const float* x, int64_t ldx,
+                          const float* gy, int64_t ldgy, int64_t batch,
+                          float* gx, int64_t ldgx, float* ga, float* gb,
+                          void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream);
+
+/*
+ * Square (Gram) form K = L(a,a) (Sec. 3 "Symmetric case": sorted a, a prefix
+ * and a suffix scan):  y[m*ldy+t] = sum_j exp(-|a[m]-a[j]|) x[j*ldx+t].
+ * Flags: A_SORTED, REUSE_PLAN, SAVE_SCANS.
+ */
+int laplex_gram(const float* a, int64_t n, const float* x, int64_t ldx, int64_t batch,
+                float* y, int64_t ldy,
+                void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream);
+
+/*
+ * Backward of the Gram form for the loss sum gy.y:
+ *   gx = K gy,
+ *   ga[m] = sum_t [ gy[m,t] sum_j s_mj K_mj x[j,t] + x[m,t] sum_i s_mi K_im gy[i,t] ],
+ *   s_mj = -sgn(a_m - a_j)   (duplicates and the diagonal contribute 0).
+ * gx or ga may be NULL.  Flags: A_SORTED, REUSE_PLAN, SAVE_SCANS.
+ */
+int laplex_gram_backward(const float* a, int64_t n, const float* x, int64_t ldx,
+                         const float* gy, int64_t ldgy, int64_t batch,
+                         float* gx, int64_t ldgx, float* ga,
+                         void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream);
+
+/*
+ * Verification hook: copy the first `count` sorted ids of the plan in `ws`
+ * (count = k + n for the apply form, n for the Gram form) to the device buffer
+ * perm_out.  id < k names output anchor a[id]; id >= k names input b[id-k].
+ */
+int laplex_get_perm(const void* ws, size_t ws_bytes, int64_t count, uint32_t* perm_out,
+                    laplex_stream_t stream);
+
+/* Host: static text for a status code. */
+const char* laplex_status_string(int status);
+
+/* Host: text of the last HIP error this thread's calls ran into ("" if none). */
+const char* laplex_last_hip_error(void);
+
+/*
+ * Diagnostics for benchmarks (not part of the method).  Between begin and end,
+ * every launch of the named kernel family ("make_keys", "radix_count",
+ * "table_scan", "radix_scatter", "merge", "decay", "scan_reduce", "scan_spine",
+ * "scan_down", "rowdot", "sum_slabs", "fill") is bracketed by a pair of HIP
+ * events on the stream it is launched on.  laplex_profile_end waits for those
+ * events and returns their summed elapsed time and the number of launches
+ * (host pointers).  Creates and destroys HIP events; process-wide; not for
+ * use under stream capture.
+ */
+int laplex_profile_begin(const char* family /* host string */);
+int laplex_profile_end(double* total_ms, int64_t* launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LAPLEX_H */

@@ -1,0 +1,158 @@
+"""ctypes binding of liblaplex (``include/laplex.h``): same names, argument
+marshalling only.  Tensors are torch tensors on the GPU (torch is used for
+device memory and streams, nothing else); every step of the path runs inside
+the library's kernels.  A missing or unloadable library raises; there is no
+fallback of any kind.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblaplex.so")
+
+LAPLEX_OK = 0
+LAPLEX_ERR_NULL = -1
+LAPLEX_ERR_SIZE = -2
+LAPLEX_ERR_LD = -3
+LAPLEX_ERR_WORKSPACE = -4
+LAPLEX_ERR_FLAGS = -5
+LAPLEX_ERR_HIP = -6
+LAPLEX_ERR_ALIGN = -7
+
+LAPLEX_A_SORTED = 1
+LAPLEX_B_SORTED = 2
+LAPLEX_REUSE_PLAN = 4
+LAPLEX_SAVE_SCANS = 8
+
+LAPLEX_MAX_MERGED = 4294967294
+
+EXPORTS = (
+    "laplex_workspace_bytes", "laplex_apply", "laplex_apply_backward", "laplex_gram",
+    "laplex_gram_backward", "laplex_get_perm", "laplex_status_string", "laplex_last_hip_error",
+    "laplex_profile_begin", "laplex_profile_end",
+)
+
+_lib = None
+_P, _I, _Z, _U = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t, ctypes.c_uint32
+
+
+class LaplexError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        msg = lib().laplex_status_string(status).decode()
+        if status == LAPLEX_ERR_HIP:
+            msg += ": " + lib().laplex_last_hip_error().decode()
+        super().__init__(f"liblaplex status {status}: {msg}")
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library (raw entry points, for tests of the error paths)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is not built; run `python -m paper_2605_24584_amd.build` "
+                "(or __graft_entry__.build()).  There is no fallback path.")
+        L = ctypes.CDLL(LIB_PATH)
+        L.laplex_workspace_bytes.argtypes = [_I, _I, _I, ctypes.POINTER(_Z)]
+        L.laplex_apply.argtypes = [_P, _I, _P, _I, _P, _I, _I, _P, _I, _P, _Z, _U, _P]
+        L.laplex_apply_backward.argtypes = [_P, _I, _P, _I, _P, _I, _P, _I, _I, _P, _I, _P, _P, _P, _Z, _U, _P]
+        L.laplex_gram.argtypes = [_P, _I, _P, _I, _I, _P, _I, _P, _Z, _U, _P]
+        L.laplex_gram_backward.argtypes = [_P, _I, _P, _I, _P, _I, _I, _P, _I, _P, _P, _Z, _U, _P]
+        L.laplex_get_perm.argtypes = [_P, _Z, _I, _P, _P]
+        L.laplex_status_string.argtypes = [ctypes.c_int]
+        L.laplex_status_string.restype = ctypes.c_char_p
+        L.laplex_last_hip_error.argtypes = []
+        L.laplex_last_hip_error.restype = ctypes.c_char_p
+        L.laplex_profile_begin.argtypes = [ctypes.c_char_p]
+        L.laplex_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+        for name in EXPORTS[:6] + EXPORTS[8:]:
+            getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _check(status: int) -> None:
+    if status != LAPLEX_OK:
+        raise LaplexError(status)
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _ld(t):
+    """leading dimension of a (rows, batch) tensor whose batch axis is contiguous"""
+    if t is None:
+        return 0
+    if t.dim() == 1:
+        return 1
+    assert t.dim() == 2 and (t.shape[1] <= 1 or t.stride(1) == 1), "batch axis must be contiguous"
+    return t.stride(0) if t.shape[0] > 1 else max(t.shape[1], 1)
+
+
+def _batch(t):
+    return 1 if t.dim() == 1 else t.shape[1]
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return getattr(stream, "cuda_stream", stream)
+
+
+def laplex_workspace_bytes(k: int, n: int, batch: int) -> int:
+    out = _Z(0)
+    _check(lib().laplex_workspace_bytes(k, n, batch, ctypes.byref(out)))
+    return out.value
+
+
+def laplex_apply(a, b, x, y, ws, flags: int = 0, stream=None) -> None:
+    """y (k, batch) <- L(a, b) x, x (n, batch); ws a uint8 workspace tensor."""
+    _check(lib().laplex_apply(_ptr(a), a.numel(), _ptr(b), b.numel(), _ptr(x), _ld(x), _batch(x),
+                              _ptr(y), _ld(y), _ptr(ws), ws.numel(), flags, _stream(stream)))
+
+
+def laplex_apply_backward(a, b, x, gy, gx, ga, gb, ws, flags: int = 0, stream=None) -> None:
+    """gx (n, batch), ga (k), gb (n) <- gradients of sum(gy * y); any may be None."""
+    _check(lib().laplex_apply_backward(
+        _ptr(a), a.numel(), _ptr(b), b.numel(), _ptr(x), _ld(x), _ptr(gy), _ld(gy), _batch(gy),
+        _ptr(gx), _ld(gx), _ptr(ga), _ptr(gb), _ptr(ws), ws.numel(), flags, _stream(stream)))
+
+
+def laplex_gram(a, x, y, ws, flags: int = 0, stream=None) -> None:
+    _check(lib().laplex_gram(_ptr(a), a.numel(), _ptr(x), _ld(x), _batch(x), _ptr(y), _ld(y),
+                             _ptr(ws), ws.numel(), flags, _stream(stream)))
+
+
+def laplex_gram_backward(a, x, gy, gx, ga, ws, flags: int = 0, stream=None) -> None:
+    _check(lib().laplex_gram_backward(
+        _ptr(a), a.numel(), _ptr(x), _ld(x), _ptr(gy), _ld(gy), _batch(gy),
+        _ptr(gx), _ld(gx), _ptr(ga), _ptr(ws), ws.numel(), flags, _stream(stream)))
+
+
+def laplex_get_perm(ws, count: int, perm_out, stream=None) -> None:
+    """perm_out: int32 tensor of `count` elements (bit pattern of the u32 ids)."""
+    _check(lib().laplex_get_perm(_ptr(ws), ws.numel(), count, _ptr(perm_out), _stream(stream)))
+
+
+def laplex_status_string(status: int) -> str:
+    return lib().laplex_status_string(status).decode()
+
+
+def laplex_last_hip_error() -> str:
+    return lib().laplex_last_hip_error().decode()
+
+
+def laplex_profile_begin(family: str) -> None:
+    _check(lib().laplex_profile_begin(family.encode()))
+
+
+def laplex_profile_end():
+    """(summed milliseconds, launches) of the family named at laplex_profile_begin."""
+    ms, cnt = ctypes.c_double(0.0), ctypes.c_int64(0)
+    _check(lib().laplex_profile_end(ctypes.byref(ms), ctypes.byref(cnt)))
+    return ms.value, cnt.value

@@ -1,0 +1,367 @@
+// Host side of liblaplex: argument checks (before any HIP call), workspace
+// carving, and the order in which the kernels are enqueued.  No arithmetic of the
+// method happens here.
+#include "../../include/laplex.h"
+#include "laplex_internal.h"
+
+#include <atomic>
+#include <mutex>
+#include <string>
+#include <utility>
+#include <vector>
+
+using namespace laplex;
+
+// ---------------------------------------------------------------------------
+// Kernel-family timing (diagnostics for benchmarks).
+// ---------------------------------------------------------------------------
+namespace {
+std::atomic<bool> g_prof_on{false};
+std::mutex g_prof_mutex;
+std::string g_prof_family;
+std::vector<std::pair<hipEvent_t, hipEvent_t>> g_prof_events;
+hipEvent_t g_prof_open = nullptr;
+}  // namespace
+
+void laplex::profile_before(const char* family, hipStream_t st)
+{
+    if (!g_prof_on.load(std::memory_order_relaxed)) return;
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    if (g_prof_family != family) return;
+    hipEvent_t e0 = nullptr;
+    if (hipEventCreate(&e0) != hipSuccess) return;
+    (void)hipEventRecord(e0, st);
+    g_prof_open = e0;
+}
+
+void laplex::profile_after(const char* family, hipStream_t st)
+{
+    if (!g_prof_on.load(std::memory_order_relaxed)) return;
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    if (g_prof_family != family || !g_prof_open) return;
+    hipEvent_t e1 = nullptr;
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(g_prof_open); g_prof_open = nullptr; return; }
+    (void)hipEventRecord(e1, st);
+    g_prof_events.emplace_back(g_prof_open, e1);
+    g_prof_open = nullptr;
+}
+
+namespace {
+
+thread_local std::string g_hip_error;
+
+int hip_fail(hipError_t e)
+{
+    g_hip_error = hipGetErrorString(e);
+    return LAPLEX_ERR_HIP;
+}
+
+#define LAPLEX_HIP(expr)                                   \
+    do {                                                   \
+        const hipError_t e_ = (expr);                      \
+        if (e_ != hipSuccess) return hip_fail(e_);         \
+    } while (0)
+
+bool misaligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+
+int check_sizes(int64_t k, int64_t n, int64_t batch)
+{
+    if (k < 0 || n < 0 || batch < 0) return LAPLEX_ERR_SIZE;
+    if (k > LAPLEX_MAX_MERGED || n > LAPLEX_MAX_MERGED || k + n > LAPLEX_MAX_MERGED) return LAPLEX_ERR_SIZE;
+    // a matrix must be addressable with 63-bit element offsets
+    const int64_t rows = k > n ? k : n;
+    if (batch > 0 && rows > (INT64_MAX / 8) / batch) return LAPLEX_ERR_SIZE;
+    return LAPLEX_OK;
+}
+
+int check_matrix(const float* p, int64_t rows, int64_t ld, int64_t batch, bool required)
+{
+    if (rows == 0 || batch == 0) return LAPLEX_OK;     // never dereferenced
+    if (!p) return required ? LAPLEX_ERR_NULL : LAPLEX_OK;
+    if (misaligned(p, 4)) return LAPLEX_ERR_ALIGN;
+    if (ld < batch) return LAPLEX_ERR_LD;
+    if (rows > (INT64_MAX / 8) / ld) return LAPLEX_ERR_SIZE;
+    return LAPLEX_OK;
+}
+
+int check_vector(const float* p, int64_t len, bool required)
+{
+    if (len == 0) return LAPLEX_OK;
+    if (!p) return required ? LAPLEX_ERR_NULL : LAPLEX_OK;
+    return misaligned(p, 4) ? LAPLEX_ERR_ALIGN : LAPLEX_OK;
+}
+
+int check_ws(const void* ws, size_t ws_bytes, const Layout& L)
+{
+    if (L.total == 0) return LAPLEX_OK;
+    if (!ws) return LAPLEX_ERR_NULL;
+    if (misaligned(ws, 256)) return LAPLEX_ERR_ALIGN;
+    if (ws_bytes < L.total) return LAPLEX_ERR_WORKSPACE;
+    return LAPLEX_OK;
+}
+
+#define LAPLEX_CHECK(expr)                       \
+    do {                                         \
+        const int rc_ = (expr);                  \
+        if (rc_ != LAPLEX_OK) return rc_;        \
+    } while (0)
+
+struct Plan {
+    uint32_t* ids; float* dh; float* z;
+};
+
+Plan plan_of(const Layout& L, char* ws)
+{
+    return Plan{reinterpret_cast<uint32_t*>(ws + L.off_ids), reinterpret_cast<float*>(ws + L.off_dh),
+                reinterpret_cast<float*>(ws + L.off_z)};
+}
+
+// Sort (or merge) the anchors and compute the neighbour decays, unless the plan is reused.
+int build_plan(const float* a, int64_t k, const float* b, int64_t n, const Layout& L, char* ws,
+               uint32_t flags, bool both_sorted, hipStream_t st)
+{
+    if (flags & LAPLEX_REUSE_PLAN) return LAPLEX_OK;
+    const Plan P = plan_of(L, ws);
+    uint32_t* keys0 = reinterpret_cast<uint32_t*>(ws + L.off_keys0);
+    if (both_sorted) {
+        LAPLEX_HIP(launch_merge(a, k, b, n, keys0, P.ids, st));
+    } else {
+        LAPLEX_HIP(launch_make_keys(a, k, b, n, keys0, P.ids, st));
+        LAPLEX_HIP(launch_radix_sort(keys0, P.ids, reinterpret_cast<uint32_t*>(ws + L.off_keys1),
+                                     reinterpret_cast<uint32_t*>(ws + L.off_ids1),
+                                     reinterpret_cast<uint32_t*>(ws + L.off_table),
+                                     reinterpret_cast<uint32_t*>(ws + L.off_chunks), L.N, st));
+    }
+    LAPLEX_HIP(launch_decay(keys0, P.dh, L.N, st));
+    return LAPLEX_OK;
+}
+
+ScanProblem problem(const Plan& P, const Layout& L)
+{
+    ScanProblem p{};
+    p.ids = P.ids; p.dh = P.dh; p.N = L.N; p.batch = L.batch;
+    return p;
+}
+
+}  // namespace
+
+extern "C" {
+
+int laplex_workspace_bytes(int64_t k, int64_t n, int64_t batch, size_t* out)
+{
+    if (!out) return LAPLEX_ERR_NULL;
+    LAPLEX_CHECK(check_sizes(k, n, batch));
+    // k == 0 is the Gram form: its saved-scan region has one row per anchor
+    *out = make_layout(k + n, k == 0 ? n : k, batch).total;
+    return LAPLEX_OK;
+}
+
+int laplex_apply(const float* a, int64_t k, const float* b, int64_t n,
+                 const float* x, int64_t ldx, int64_t batch, float* y, int64_t ldy,
+                 void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream)
+{
+    const uint32_t known = LAPLEX_A_SORTED | LAPLEX_B_SORTED | LAPLEX_REUSE_PLAN | LAPLEX_SAVE_SCANS;
+    if (flags & ~known) return LAPLEX_ERR_FLAGS;
+    LAPLEX_CHECK(check_sizes(k, n, batch));
+    LAPLEX_CHECK(check_vector(a, k, true));
+    LAPLEX_CHECK(check_vector(b, n, true));
+    LAPLEX_CHECK(check_matrix(x, n, ldx, batch, true));
+    LAPLEX_CHECK(check_matrix(y, k, ldy, batch, true));
+    if (k == 0 || batch == 0) return LAPLEX_OK;
+    const Layout L = make_layout(k + n, k, batch);
+    LAPLEX_CHECK(check_ws(ws, ws_bytes, L));
+    char* w = static_cast<char*>(ws);
+    const Plan P = plan_of(L, w);
+    hipStream_t st = stream;
+    if (n == 0) {
+        LAPLEX_HIP(launch_fill(y, k, batch, ldy, 0.0f, st));
+        if (flags & LAPLEX_SAVE_SCANS) LAPLEX_HIP(launch_fill(P.z, k, batch, batch, 0.0f, st));
+        return LAPLEX_OK;
+    }
+    const bool sorted = (flags & LAPLEX_A_SORTED) && (flags & LAPLEX_B_SORTED);
+    LAPLEX_CHECK(build_plan(a, k, b, n, L, w, flags, sorted, st));
+    ScanProblem p = problem(P, L);
+    p.inj = x; p.ld_inj = ldx; p.inj_lo = (uint32_t)k; p.inj_hi = (uint32_t)(k + n);
+    p.res_lo = 0; p.res_hi = (uint32_t)k;
+    p.out_p = y; p.ld_p = ldy;
+    p.out_z = (flags & LAPLEX_SAVE_SCANS) ? P.z : nullptr;
+    LAPLEX_HIP(launch_scan(p, L, w, st));
+    return LAPLEX_OK;
+}
+
+int laplex_apply_backward(const float* a, int64_t k, const float* b, int64_t n,
+                          const float* x, int64_t ldx, const float* gy, int64_t ldgy, int64_t batch,
+                          float* gx, int64_t ldgx, float* ga, float* gb,
+                          void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream)
+{
+    const uint32_t known = LAPLEX_A_SORTED | LAPLEX_B_SORTED | LAPLEX_REUSE_PLAN | LAPLEX_SAVE_SCANS;
+    if (flags & ~known) return LAPLEX_ERR_FLAGS;
+    LAPLEX_CHECK(check_sizes(k, n, batch));
+    LAPLEX_CHECK(check_vector(a, k, true));
+    LAPLEX_CHECK(check_vector(b, n, true));
+    LAPLEX_CHECK(check_matrix(x, n, ldx, batch, ga || gb));
+    LAPLEX_CHECK(check_matrix(gy, k, ldgy, batch, true));
+    LAPLEX_CHECK(check_matrix(gx, n, ldgx, batch, false));
+    LAPLEX_CHECK(check_vector(ga, k, false));
+    LAPLEX_CHECK(check_vector(gb, n, false));
+    const Layout L = make_layout(k + n, k, batch);
+    const bool degenerate = k == 0 || n == 0 || batch == 0;
+    if (!degenerate) LAPLEX_CHECK(check_ws(ws, ws_bytes, L));
+    hipStream_t st = stream;
+    if (degenerate) {   // one side is empty: every wanted gradient is zero
+        if (gx) LAPLEX_HIP(launch_fill(gx, n, batch, ldgx, 0.0f, st));
+        if (ga) LAPLEX_HIP(launch_fill(ga, k, 1, 1, 0.0f, st));
+        if (gb) LAPLEX_HIP(launch_fill(gb, n, 1, 1, 0.0f, st));
+        return LAPLEX_OK;
+    }
+    char* w = static_cast<char*>(ws);
+    const Plan P = plan_of(L, w);
+    const bool sorted = (flags & LAPLEX_A_SORTED) && (flags & LAPLEX_B_SORTED);
+    LAPLEX_CHECK(build_plan(a, k, b, n, L, w, flags, sorted, st));
+    if (ga) {
+        if (!(flags & LAPLEX_SAVE_SCANS)) {   // strict scans of x at the outputs, not kept by the forward
+            ScanProblem p = problem(P, L);
+            p.inj = x; p.ld_inj = ldx; p.inj_lo = (uint32_t)k; p.inj_hi = (uint32_t)(k + n);
+            p.res_lo = 0; p.res_hi = (uint32_t)k;
+            p.out_z = P.z;
+            LAPLEX_HIP(launch_scan(p, L, w, st));
+        }
+        LAPLEX_HIP(launch_rowdot(gy, ldgy, P.z, batch, k, batch, ga, st));
+    }
+    if (gx || gb) {
+        ScanProblem p = problem(P, L);
+        p.inj = gy; p.ld_inj = ldgy; p.inj_lo = 0; p.inj_hi = (uint32_t)k;
+        p.res_lo = (uint32_t)k; p.res_hi = (uint32_t)(k + n);
+        p.out_p = gx; p.ld_p = ldgx;
+        p.out_red = gb; p.w = x; p.ld_w = ldx;
+        LAPLEX_HIP(launch_scan(p, L, w, st));
+    }
+    return LAPLEX_OK;
+}
+
+int laplex_gram(const float* a, int64_t n, const float* x, int64_t ldx, int64_t batch,
+                float* y, int64_t ldy, void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream)
+{
+    const uint32_t known = LAPLEX_A_SORTED | LAPLEX_REUSE_PLAN | LAPLEX_SAVE_SCANS;
+    if (flags & ~known) return LAPLEX_ERR_FLAGS;
+    LAPLEX_CHECK(check_sizes(0, n, batch));
+    LAPLEX_CHECK(check_vector(a, n, true));
+    LAPLEX_CHECK(check_matrix(x, n, ldx, batch, true));
+    LAPLEX_CHECK(check_matrix(y, n, ldy, batch, true));
+    if (n == 0 || batch == 0) return LAPLEX_OK;
+    const Layout L = make_layout(n, n, batch);
+    LAPLEX_CHECK(check_ws(ws, ws_bytes, L));
+    char* w = static_cast<char*>(ws);
+    const Plan P = plan_of(L, w);
+    hipStream_t st = stream;
+    LAPLEX_CHECK(build_plan(a, n, nullptr, 0, L, w, flags, (flags & LAPLEX_A_SORTED) != 0, st));
+    ScanProblem p = problem(P, L);
+    p.inj = x; p.ld_inj = ldx; p.inj_lo = 0; p.inj_hi = (uint32_t)n;
+    p.res_lo = 0; p.res_hi = (uint32_t)n;
+    p.out_p = y; p.ld_p = ldy;
+    p.out_z = (flags & LAPLEX_SAVE_SCANS) ? P.z : nullptr;
+    LAPLEX_HIP(launch_scan(p, L, w, st));
+    return LAPLEX_OK;
+}
+
+int laplex_gram_backward(const float* a, int64_t n, const float* x, int64_t ldx,
+                         const float* gy, int64_t ldgy, int64_t batch, float* gx, int64_t ldgx, float* ga,
+                         void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream)
+{
+    const uint32_t known = LAPLEX_A_SORTED | LAPLEX_REUSE_PLAN | LAPLEX_SAVE_SCANS;
+    if (flags & ~known) return LAPLEX_ERR_FLAGS;
+    LAPLEX_CHECK(check_sizes(0, n, batch));
+    LAPLEX_CHECK(check_vector(a, n, true));
+    LAPLEX_CHECK(check_matrix(x, n, ldx, batch, ga != nullptr));
+    LAPLEX_CHECK(check_matrix(gy, n, ldgy, batch, true));
+    LAPLEX_CHECK(check_matrix(gx, n, ldgx, batch, false));
+    LAPLEX_CHECK(check_vector(ga, n, false));
+    if (n == 0) return LAPLEX_OK;
+    hipStream_t st = stream;
+    if (batch == 0) {
+        if (ga) LAPLEX_HIP(launch_fill(ga, n, 1, 1, 0.0f, st));
+        return LAPLEX_OK;
+    }
+    const Layout L = make_layout(n, n, batch);
+    LAPLEX_CHECK(check_ws(ws, ws_bytes, L));
+    char* w = static_cast<char*>(ws);
+    const Plan P = plan_of(L, w);
+    LAPLEX_CHECK(build_plan(a, n, nullptr, 0, L, w, flags, (flags & LAPLEX_A_SORTED) != 0, st));
+    if (ga && !(flags & LAPLEX_SAVE_SCANS)) {
+        ScanProblem p = problem(P, L);
+        p.inj = x; p.ld_inj = ldx; p.inj_lo = 0; p.inj_hi = (uint32_t)n;
+        p.res_lo = 0; p.res_hi = (uint32_t)n;
+        p.out_z = P.z;
+        LAPLEX_HIP(launch_scan(p, L, w, st));
+    }
+    if (gx || ga) {
+        ScanProblem p = problem(P, L);
+        p.inj = gy; p.ld_inj = ldgy; p.inj_lo = 0; p.inj_hi = (uint32_t)n;
+        p.res_lo = 0; p.res_hi = (uint32_t)n;
+        p.out_p = gx; p.ld_p = ldgx;
+        p.out_red = ga; p.w = x; p.ld_w = ldx; p.zs = ga ? P.z : nullptr;
+        LAPLEX_HIP(launch_scan(p, L, w, st));
+    }
+    return LAPLEX_OK;
+}
+
+int laplex_get_perm(const void* ws, size_t ws_bytes, int64_t count, uint32_t* perm_out, laplex_stream_t stream)
+{
+    if (count < 0 || count > LAPLEX_MAX_MERGED) return LAPLEX_ERR_SIZE;
+    if (count == 0) return LAPLEX_OK;
+    if (!ws || !perm_out) return LAPLEX_ERR_NULL;
+    if (misaligned(ws, 256) || misaligned(perm_out, 4)) return LAPLEX_ERR_ALIGN;
+    if (ws_bytes < sizeof(uint32_t) * (size_t)count) return LAPLEX_ERR_WORKSPACE;
+    LAPLEX_HIP(launch_copy_u32(static_cast<const uint32_t*>(ws), perm_out, count, stream));
+    return LAPLEX_OK;
+}
+
+const char* laplex_status_string(int status)
+{
+    switch (status) {
+        case LAPLEX_OK: return "ok";
+        case LAPLEX_ERR_NULL: return "a required pointer is NULL";
+        case LAPLEX_ERR_SIZE: return "a size is negative or too large";
+        case LAPLEX_ERR_LD: return "a leading dimension is smaller than batch";
+        case LAPLEX_ERR_WORKSPACE: return "workspace too small";
+        case LAPLEX_ERR_FLAGS: return "unknown or inapplicable flag";
+        case LAPLEX_ERR_HIP: return "a HIP call failed";
+        case LAPLEX_ERR_ALIGN: return "a pointer is misaligned";
+        default: return "unknown status";
+    }
+}
+
+const char* laplex_last_hip_error(void) { return g_hip_error.c_str(); }
+
+int laplex_profile_begin(const char* family)
+{
+    if (!family) return LAPLEX_ERR_NULL;
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    for (auto& ev : g_prof_events) { (void)hipEventDestroy(ev.first); (void)hipEventDestroy(ev.second); }
+    g_prof_events.clear();
+    g_prof_family = family;
+    g_prof_on.store(true);
+    return LAPLEX_OK;
+}
+
+int laplex_profile_end(double* total_ms, int64_t* launches)
+{
+    if (!total_ms || !launches) return LAPLEX_ERR_NULL;
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    g_prof_on.store(false);
+    double sum = 0.0;
+    int64_t count = 0;
+    int rc = LAPLEX_OK;
+    for (auto& ev : g_prof_events) {
+        float ms = 0.0f;
+        hipError_t e = hipEventSynchronize(ev.second);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev.first, ev.second);
+        if (e == hipSuccess) { sum += ms; ++count; } else rc = hip_fail(e);
+        (void)hipEventDestroy(ev.first); (void)hipEventDestroy(ev.second);
+    }
+    g_prof_events.clear();
+    *total_ms = sum; *launches = count;
+    return rc;
+}
+
+}  // extern "C"

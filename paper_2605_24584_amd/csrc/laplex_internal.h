@@ -1,0 +1,195 @@
+// Internal declarations shared by the host API and the kernel files of liblaplex.
+// Nothing here is part of the public boundary (that is include/laplex.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace laplex {
+
+// ----------------------------------------------------------------------------
+// Sort geometry (LSD radix sort, 8-bit digits, 4 passes over 32-bit keys).
+// ----------------------------------------------------------------------------
+constexpr int kRadixBits = 8;
+constexpr int kRadix = 1 << kRadixBits;
+constexpr int kSortPasses = 4;
+constexpr int kSortThreads = 512;                       // 8 wavefronts
+constexpr int kSortKeysPerThread = 16;
+constexpr int kSortTile = kSortThreads * kSortKeysPerThread;  // 8192 keys per workgroup
+constexpr int kTableScanThreads = 256;
+constexpr int kTableScanPerThread = 16;
+constexpr int kTableScanChunk = kTableScanThreads * kTableScanPerThread;
+constexpr int kMergeThreads = 256;
+constexpr int kMergePerThread = 8;
+constexpr int kMergeTile = kMergeThreads * kMergePerThread;
+
+// ----------------------------------------------------------------------------
+// Scan geometry.  A workgroup of kScanWaves wavefronts owns one tile of
+// consecutive merged positions ("rows").  A wavefront's 64 lanes are split into
+// bv lanes across the batch (each lane holds `vec` adjacent batch columns) times
+// rv = 64 / bv row-lanes; every row-lane walks `items` consecutive rows.
+// ----------------------------------------------------------------------------
+constexpr int kScanWaves = 8;
+constexpr int kScanThreads = kScanWaves * 64;
+constexpr int kItemsVec1 = 16;   // rows per row-lane when a lane holds 1 column
+constexpr int kItemsVec4 = 8;    // rows per row-lane when a lane holds 4 columns
+constexpr int kSpineThreads = 1024;
+
+struct ScanGeom {
+    int vec;          // 1 or 4 batch columns per lane
+    int items;        // rows per row-lane
+    int bv;           // lanes across the batch (power of two, <= 64)
+    int rv;           // row-lanes per wavefront
+    int slabs;        // ceil(batch / (bv * vec)): blockIdx.y
+    int tile_rows;    // kScanWaves * rv * items
+    int64_t tiles;    // ceil(N / tile_rows)
+};
+
+inline int pow2_at_least(int64_t v) { int p = 1; while (p < v) p <<= 1; return p; }
+
+inline ScanGeom scan_geom(int64_t N, int64_t batch, int vec)
+{
+    ScanGeom g;
+    g.vec = vec;
+    g.items = vec == 4 ? kItemsVec4 : kItemsVec1;
+    const int64_t groups = (batch + vec - 1) / vec;          // column groups of `vec`
+    g.bv = groups >= 64 ? 64 : pow2_at_least(groups < 1 ? 1 : groups);
+    g.rv = 64 / g.bv;
+    g.slabs = (int)((groups + g.bv - 1) / g.bv);
+    if (g.slabs < 1) g.slabs = 1;
+    g.tile_rows = kScanWaves * g.rv * g.items;
+    g.tiles = (N + g.tile_rows - 1) / g.tile_rows;
+    return g;
+}
+
+// ----------------------------------------------------------------------------
+// Workspace layout: a pure function of (merged length N, saved-scan rows,
+// batch).  Plan first (ids, decays), then the saved-scan region, then scratch,
+// which the sort and the scans use at different times and therefore share.
+// ----------------------------------------------------------------------------
+inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+struct Layout {
+    int64_t N = 0, zrows = 0, batch = 0, bpad = 0;
+    // plan
+    size_t off_ids = 0;      // u32[N]    sorted ids
+    size_t off_dh = 0;       // f32[N+1]  decay to the previous sorted key, < 0: same key
+    // saved scans
+    size_t off_z = 0;        // f32[zrows][batch]
+    size_t off_scratch = 0;
+    // scratch, sort view
+    size_t off_keys0 = 0, off_keys1 = 0, off_ids1 = 0, off_table = 0, off_chunks = 0;
+    int64_t sort_tiles = 0, table_len = 0, table_chunks = 0;
+    // scratch, scan view (sized for the larger of the two lane geometries)
+    size_t off_agg_scalar = 0;   // float4[2][tiles]            (D, C, H, -)
+    size_t off_agg_s = 0;        // f32[2][tiles][bpad]         S
+    size_t off_agg_q = 0;        // f32[2][tiles][bpad]         Q
+    size_t off_car_f = 0;        // f32[2][tiles][bpad]         carry F
+    size_t off_car_e = 0;        // f32[2][tiles][bpad]         carry E
+    size_t off_red = 0;          // f32[slabs][N]               per-slab partial row reductions
+    int64_t max_tiles = 0;
+    size_t total = 0;
+};
+
+inline Layout make_layout(int64_t N, int64_t zrows, int64_t batch)
+{
+    Layout L;
+    L.N = N; L.zrows = zrows; L.batch = batch;
+    L.bpad = (batch + 3) / 4 * 4;
+    size_t o = 0;
+    L.off_ids = o;  o = align_up(o + sizeof(uint32_t) * (size_t)N);
+    L.off_dh = o;   o = align_up(o + sizeof(float) * (size_t)(N + 1));
+    L.off_z = o;    o = align_up(o + sizeof(float) * (size_t)zrows * (size_t)batch);
+    L.off_scratch = o;
+
+    // sort view
+    size_t s = o;
+    L.sort_tiles = (N + kSortTile - 1) / kSortTile;
+    L.table_len = L.sort_tiles * kRadix;
+    L.table_chunks = (L.table_len + kTableScanChunk - 1) / kTableScanChunk;
+    L.off_keys0 = s;  s = align_up(s + sizeof(uint32_t) * (size_t)N);
+    L.off_keys1 = s;  s = align_up(s + sizeof(uint32_t) * (size_t)N);
+    L.off_ids1 = s;   s = align_up(s + sizeof(uint32_t) * (size_t)N);
+    L.off_table = s;  s = align_up(s + sizeof(uint32_t) * (size_t)L.table_len);
+    L.off_chunks = s; s = align_up(s + sizeof(uint32_t) * (size_t)(L.table_chunks + 1));
+
+    // scan view
+    size_t c = o;
+    const ScanGeom g1 = scan_geom(N, batch, 1), g4 = scan_geom(N, batch, 4);
+    L.max_tiles = g1.tiles > g4.tiles ? g1.tiles : g4.tiles;
+    const int max_slabs = g1.slabs > g4.slabs ? g1.slabs : g4.slabs;
+    const size_t per = sizeof(float) * 2 * (size_t)L.max_tiles * (size_t)L.bpad;
+    L.off_agg_scalar = c; c = align_up(c + sizeof(float) * 4 * 2 * (size_t)L.max_tiles);
+    L.off_agg_s = c;      c = align_up(c + per);
+    L.off_agg_q = c;      c = align_up(c + per);
+    L.off_car_f = c;      c = align_up(c + per);
+    L.off_car_e = c;      c = align_up(c + per);
+    L.off_red = c;
+    if (max_slabs > 1) c = align_up(c + sizeof(float) * (size_t)max_slabs * (size_t)N);
+
+    L.total = s > c ? s : c;
+    return L;
+}
+
+// ----------------------------------------------------------------------------
+// Optional timing of one kernel family with HIP events on the launch stream
+// (laplex_profile_begin / laplex_profile_end).  A no-op unless switched on.
+// ----------------------------------------------------------------------------
+void profile_before(const char* family, hipStream_t st);
+void profile_after(const char* family, hipStream_t st);
+#define LAPLEX_TIMED(family, st, launch)       \
+    do {                                       \
+        ::laplex::profile_before(family, st);  \
+        launch;                                \
+        ::laplex::profile_after(family, st);   \
+    } while (0)
+
+// ----------------------------------------------------------------------------
+// Launchers (each returns the hipError_t of its launches; none synchronises).
+// ----------------------------------------------------------------------------
+
+// keys0/ids0 <- order-preserving keys of a (ids 0..k) followed by b (ids k..k+n).
+hipError_t launch_make_keys(const float* a, int64_t k, const float* b, int64_t n,
+                            uint32_t* keys, uint32_t* ids, hipStream_t st);
+
+// Stable ascending LSD radix sort of (keys0, ids0), N pairs; result back in keys0/ids0.
+hipError_t launch_radix_sort(uint32_t* keys0, uint32_t* ids0, uint32_t* keys1, uint32_t* ids1,
+                             uint32_t* table, uint32_t* chunks, int64_t N, hipStream_t st);
+
+// Both inputs ascending: merged keys/ids in one pass (ties: a first).
+hipError_t launch_merge(const float* a, int64_t k, const float* b, int64_t n,
+                        uint32_t* keys, uint32_t* ids, hipStream_t st);
+
+// dh[j] = decay from sorted key j-1 to j (>= 0), or -1 if the two keys are equal;
+// dh[0] = dh[N] = 0 (nothing beyond either end).
+hipError_t launch_decay(const uint32_t* keys, float* dh, int64_t N, hipStream_t st);
+
+hipError_t launch_fill(float* p, int64_t rows, int64_t cols, int64_t ld, float v, hipStream_t st);
+hipError_t launch_copy_u32(const uint32_t* src, uint32_t* dst, int64_t count, hipStream_t st);
+
+// One scan problem over the merged sequence: inject rows of `inj` at positions
+// whose id lies in [inj_lo, inj_hi), run the decayed scan in both directions and
+// emit, at positions whose id lies in [res_lo, res_hi):
+//   out_p[(id-res_lo)*ld_p + t] = F + R - v              (both inclusive scans)
+//   out_z[(id-res_lo)*batch + t] = Z = E_right - E_left  (strict scans)
+//   out_red[id-res_lo] = sum_t ( w[(id-res_lo)*ld_w + t] * Z
+//                              + (zs ? v * zs[(id-res_lo)*batch + t] : 0) )
+// Any of out_p / out_z / out_red may be null; strict scans run only if out_z or
+// out_red is wanted.
+struct ScanProblem {
+    const uint32_t* ids; const float* dh; int64_t N;
+    const float* inj; int64_t ld_inj; uint32_t inj_lo, inj_hi;
+    uint32_t res_lo, res_hi;
+    float* out_p; int64_t ld_p;
+    float* out_z;
+    float* out_red; const float* w; int64_t ld_w; const float* zs;
+    int64_t batch;
+};
+hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStream_t st);
+
+// out[r] = sum_t u[r*ldu+t] * v[r*ldv+t]
+hipError_t launch_rowdot(const float* u, int64_t ldu, const float* v, int64_t ldv,
+                         int64_t rows, int64_t batch, float* out, hipStream_t st);
+
+}  // namespace laplex

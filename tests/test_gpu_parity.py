@@ -1,0 +1,352 @@
+"""Parity of the HIP path (through the C-ABI library) with the CPU oracle, on the
+same seeded fp32 inputs.
+
+Bars: permutation ids bit-exact; floating point
+    |gpu - ref| <= 1e-5 * T + 1e-7,
+T the same sum over absolute values of the summands (per output), the bound the
+task states for y and, in the same form, for every gradient.
+"""
+import numpy as np
+import pytest
+
+from paper_2605_24584_amd import binding as B
+from paper_2605_24584_amd import synth
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+RTOL, ATOL = 1e-5, 1e-7
+
+
+def dev(v):
+    return torch.from_numpy(np.ascontiguousarray(v)).cuda()
+
+
+def workspace(k, n, batch):
+    return torch.empty(B.laplex_workspace_bytes(k, n, batch), dtype=torch.uint8, device="cuda")
+
+
+def assert_close(name, got, ref, tol):
+    got = np.asarray(got, dtype=np.float64).reshape(ref.shape)
+    assert np.all(np.isfinite(got)), f"{name}: non-finite values"
+    ratio = np.abs(got - ref) / (RTOL * tol + ATOL)
+    worst = float(ratio.max()) if ratio.size else 0.0
+    assert worst <= 1.0, f"{name}: worst |err|/(1e-5 T + 1e-7) = {worst:.3g} at {np.unravel_index(ratio.argmax(), ratio.shape)}"
+    return worst
+
+
+def gpu_apply(a, b, x, flags=0, ws=None, ldx=None, ldy=None):
+    k, n, batch = a.size, b.size, x.shape[1]
+    ws = workspace(k, n, batch) if ws is None else ws
+    da, db = dev(a), dev(b)
+    if ldx is None:
+        dx = dev(x)
+    else:
+        dx = torch.zeros(n, ldx, device="cuda")[:, :batch]
+        dx.copy_(dev(x))
+    ybuf = torch.full((k, batch if ldy is None else ldy), float("nan"), device="cuda")
+    y = ybuf[:, :batch]
+    B.laplex_apply(da, db, dx, y, ws, flags)
+    torch.cuda.synchronize()
+    return y.cpu().numpy(), ws
+
+
+def gpu_backward(a, b, x, g, flags=0, ws=None, want=(True, True, True)):
+    k, n, batch = a.size, b.size, x.shape[1]
+    ws = workspace(k, n, batch) if ws is None else ws
+    gx = torch.full((n, batch), float("nan"), device="cuda") if want[0] else None
+    ga = torch.full((k,), float("nan"), device="cuda") if want[1] else None
+    gb = torch.full((n,), float("nan"), device="cuda") if want[2] else None
+    B.laplex_apply_backward(dev(a), dev(b), dev(x), dev(g), gx, ga, gb, ws, flags)
+    torch.cuda.synchronize()
+    return tuple(None if t is None else t.cpu().numpy() for t in (gx, ga, gb))
+
+
+def gpu_perm(ws, count):
+    out = torch.empty(count, dtype=torch.int32, device="cuda")
+    B.laplex_get_perm(ws, count, out)
+    torch.cuda.synchronize()
+    return out.cpu().numpy().view(np.uint32)
+
+
+def anchors(kind, r, k, n):
+    if kind == "uniform":
+        span = max(1.0, (k + n) / 128.0)
+        a, b = r.uniform(0, span, k), r.uniform(0, span, n)
+    elif kind == "ties":
+        span = max(1.0, (k + n) / 64.0)
+        a, b = np.round(r.uniform(0, span, k) * 4) / 4, np.round(r.uniform(0, span, n) * 4) / 4
+    elif kind == "all_equal":
+        a, b = np.full(k, -2.5), np.full(n, -2.5)
+    elif kind == "huge_gaps":
+        a, b = r.integers(0, 9, k) * 300.0, r.integers(0, 9, n) * 300.0 + r.integers(0, 2, n) * 0.5
+    elif kind == "clustered":
+        a, b = r.normal(size=k), r.normal(size=n)
+    elif kind == "signed":
+        a, b = r.normal(size=k) * 40, -r.uniform(0, 30, n)
+        a[: k // 7] = 0.0; b[: n // 5] = -0.0
+    else:
+        raise KeyError(kind)
+    return a.astype(np.float32), b.astype(np.float32)
+
+
+KINDS = ["uniform", "ties", "all_equal", "huge_gaps", "clustered", "signed"]
+# (k, n, batch): single elements, ragged tails, several tiles of both lane geometries, two slabs
+SHAPES = [(1, 1, 1), (5, 1, 2), (1, 6, 1), (37, 53, 3), (100, 9000, 1), (9000, 100, 5),
+          (3000, 21000, 1), (2500, 4000, 8), (513, 9000, 64), (300, 2100, 256), (70, 1500, 260),
+          (50, 1700, 67)]
+
+
+# ------------------------------------------------------------------ the sort
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("k,n", [(1, 1), (3, 0), (0, 5), (100, 157), (9000, 8000), (20000, 70001)])
+def test_permutation_bit_exact(oracle, kind, k, n):
+    if k == 0 or n == 0:
+        pytest.skip("apply with an empty side builds no plan")
+    r = np.random.default_rng(k * 7 + n)
+    a, b = anchors(kind, r, k, n)
+    x = r.normal(size=(n, 1)).astype(np.float32)
+    _, ws = gpu_apply(a, b, x)
+    assert np.array_equal(gpu_perm(ws, k + n), oracle.merged_permutation(a, b))
+
+
+@pytest.mark.parametrize("kind", ["uniform", "ties", "all_equal", "signed"])
+@pytest.mark.parametrize("k,n", [(1, 1), (100, 157), (5000, 3), (3, 5000), (20000, 70001)])
+def test_merge_path_when_both_sorted(oracle, kind, k, n):
+    r = np.random.default_rng(k + 3 * n)
+    a, b = anchors(kind, r, k, n)
+    a.sort(); b.sort()
+    x = r.normal(size=(n, 2)).astype(np.float32)
+    y, ws = gpu_apply(a, b, x, flags=B.LAPLEX_A_SORTED | B.LAPLEX_B_SORTED)
+    assert np.array_equal(gpu_perm(ws, k + n), oracle.merged_permutation(a, b))
+    ref, tol = oracle.apply_scan(a, b, x)
+    assert_close("y", y, ref, tol)
+
+
+# ------------------------------------------------------------------ forward and backward
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("k,n,batch", SHAPES)
+def test_apply_forward_backward(oracle, kind, k, n, batch):
+    r = np.random.default_rng(1000 + k + n + batch)
+    a, b = anchors(kind, r, k, n)
+    x = r.normal(size=(n, batch)).astype(np.float32)
+    g = r.normal(size=(k, batch)).astype(np.float32)
+    small = k * n * batch <= 4e7
+    ref, tol = (oracle.apply_brute if small else oracle.apply_scan)(a, b, x)
+    y, ws = gpu_apply(a, b, x, flags=B.LAPLEX_SAVE_SCANS)
+    assert_close("y", y, ref, tol)
+    (rgx, rga, rgb), (tgx, tga, tgb) = (oracle.apply_backward_brute if small else oracle.apply_backward_scan)(a, b, x, g)
+    # with the forward's saved scans and the plan kept ...
+    gx, ga, gb = gpu_backward(a, b, x, g, flags=B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN, ws=ws)
+    assert_close("gx", gx, rgx, tgx); assert_close("ga", ga, rga, tga); assert_close("gb", gb, rgb, tgb)
+    # ... and standing alone (sorts and re-scans x itself): the same bits
+    gx2, ga2, gb2 = gpu_backward(a, b, x, g)
+    assert np.array_equal(gx, gx2) and np.array_equal(ga, ga2) and np.array_equal(gb, gb2)
+
+
+def test_backward_subsets_and_plain_path(oracle):
+    r = np.random.default_rng(5)
+    a, b = anchors("ties", r, 700, 3000)
+    x = r.normal(size=(3000, 4)).astype(np.float32); g = r.normal(size=(700, 4)).astype(np.float32)
+    (rgx, rga, rgb), (tgx, tga, tgb) = oracle.apply_backward_scan(a, b, x, g)
+    gx, _, _ = gpu_backward(a, b, x, g, want=(True, False, False))
+    assert_close("gx", gx, rgx, tgx)
+    _, ga, _ = gpu_backward(a, b, x, g, want=(False, True, False))
+    assert_close("ga", ga, rga, tga)
+    _, _, gb = gpu_backward(a, b, x, g, want=(False, False, True))
+    assert_close("gb", gb, rgb, tgb)
+
+
+def test_plan_reuse_across_batches(oracle):
+    r = np.random.default_rng(6)
+    a, b = anchors("uniform", r, 800, 5000)
+    x1 = r.normal(size=(5000, 8)).astype(np.float32); x2 = r.normal(size=(5000, 8)).astype(np.float32)
+    y1, ws = gpu_apply(a, b, x1)
+    y2, _ = gpu_apply(a, b, x2, flags=B.LAPLEX_REUSE_PLAN, ws=ws)
+    y2_fresh, _ = gpu_apply(a, b, x2)
+    assert np.array_equal(y2, y2_fresh)
+    ref, tol = oracle.apply_scan(a, b, x2)
+    assert_close("y", y2, ref, tol)
+
+
+@pytest.mark.parametrize("batch,ldx,ldy", [(4, 5, 7), (8, 12, 8), (1, 3, 2), (64, 65, 64)])
+def test_leading_dimensions_and_scalar_lanes(oracle, batch, ldx, ldy):
+    r = np.random.default_rng(7)
+    a, b = anchors("uniform", r, 300, 2500)
+    x = r.normal(size=(2500, batch)).astype(np.float32)
+    y, _ = gpu_apply(a, b, x, ldx=ldx, ldy=ldy)
+    ref, tol = oracle.apply_scan(a, b, x)
+    assert_close("y", y, ref, tol)
+
+
+def test_results_are_deterministic():
+    r = np.random.default_rng(8)
+    a, b = anchors("clustered", r, 5000, 40000)
+    x = r.normal(size=(40000, 4)).astype(np.float32); g = r.normal(size=(5000, 4)).astype(np.float32)
+    y1, _ = gpu_apply(a, b, x); y2, _ = gpu_apply(a, b, x)
+    assert np.array_equal(y1, y2)
+    o1 = gpu_backward(a, b, x, g); o2 = gpu_backward(a, b, x, g)
+    assert all(np.array_equal(u, v) for u, v in zip(o1, o2))
+
+
+def test_countsketch_limit_exact_in_fp32():
+    """Anchors on well separated labels: decays are exactly 1 inside a label and
+    exactly 0 across labels, so the apply is an exact bucket sum."""
+    r = np.random.default_rng(9)
+    k, n = 50, 4000
+    labels = (300.0 * np.arange(k)).astype(np.float32)
+    h = r.integers(0, k, n)
+    x = r.integers(-8, 9, size=(n, 2)).astype(np.float32)      # sums exact in fp32
+    y, _ = gpu_apply(labels, labels[h], x)
+    want = np.zeros((k, 2)); np.add.at(want, h, x.astype(np.float64))
+    assert np.array_equal(y.astype(np.float64), want)
+
+
+# ------------------------------------------------------------------ empty sides
+
+def test_empty_sides():
+    a = np.array([1.0, 2.0, 3.0], dtype=np.float32)
+    e = np.zeros(0, dtype=np.float32)
+    y, _ = gpu_apply(a, e, np.zeros((0, 2), dtype=np.float32))
+    assert y.shape == (3, 2) and not y.any()
+    g = np.ones((3, 2), dtype=np.float32)
+    gx, ga, gb = gpu_backward(a, e, np.zeros((0, 2), dtype=np.float32), g)
+    assert ga.shape == (3,) and not ga.any() and gx.size == 0 and gb.size == 0
+    gx, ga, gb = gpu_backward(e, a, np.ones((3, 2), dtype=np.float32), np.zeros((0, 2), dtype=np.float32))
+    assert not gx.any() and not gb.any() and ga.size == 0
+
+
+# ------------------------------------------------------------------ Gram form
+
+def gpu_gram(a, x, flags=0, ws=None):
+    n, batch = a.size, x.shape[1]
+    ws = workspace(0, n, batch) if ws is None else ws
+    y = torch.full((n, batch), float("nan"), device="cuda")
+    B.laplex_gram(dev(a), dev(x), y, ws, flags)
+    torch.cuda.synchronize()
+    return y.cpu().numpy(), ws
+
+
+def gpu_gram_backward(a, x, g, flags=0, ws=None, want=(True, True)):
+    n, batch = a.size, x.shape[1]
+    ws = workspace(0, n, batch) if ws is None else ws
+    gx = torch.full((n, batch), float("nan"), device="cuda") if want[0] else None
+    ga = torch.full((n,), float("nan"), device="cuda") if want[1] else None
+    B.laplex_gram_backward(dev(a), dev(x), dev(g), gx, ga, ws, flags)
+    torch.cuda.synchronize()
+    return tuple(None if t is None else t.cpu().numpy() for t in (gx, ga))
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("n,batch", [(1, 1), (2, 3), (777, 1), (6000, 4), (20000, 64), (3000, 67)])
+def test_gram_forward_backward(oracle, kind, n, batch):
+    r = np.random.default_rng(2000 + n + batch)
+    a, _ = anchors(kind, r, n, 1)
+    x = r.normal(size=(n, batch)).astype(np.float32); g = r.normal(size=(n, batch)).astype(np.float32)
+    small = n * n * batch <= 4e7
+    ref, tol = (oracle.gram_brute if small else oracle.gram_scan)(a, x)
+    y, ws = gpu_gram(a, x, flags=B.LAPLEX_SAVE_SCANS)
+    assert_close("y", y, ref, tol)
+    assert np.array_equal(gpu_perm(ws, n), oracle.merged_permutation(a))
+    (rgx, rga), (tgx, tga) = (oracle.gram_backward_brute if small else oracle.gram_backward_scan)(a, x, g)
+    gx, ga = gpu_gram_backward(a, x, g, flags=B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN, ws=ws)
+    assert_close("gx", gx, rgx, tgx); assert_close("ga", ga, rga, tga)
+    gx2, ga2 = gpu_gram_backward(a, x, g)
+    assert np.array_equal(gx, gx2) and np.array_equal(ga, ga2)
+    _, ga3 = gpu_gram_backward(a, x, g, want=(False, True))
+    assert np.array_equal(ga, ga3)
+
+
+def test_gram_sorted_anchor_flag(oracle):
+    r = np.random.default_rng(11)
+    a = np.sort(r.uniform(0, 50, 5000)).astype(np.float32)
+    x = r.normal(size=(5000, 4)).astype(np.float32)
+    y, ws = gpu_gram(a, x, flags=B.LAPLEX_A_SORTED)
+    assert np.array_equal(gpu_perm(ws, 5000), np.arange(5000, dtype=np.uint32))
+    ref, tol = oracle.gram_scan(a, x)
+    assert_close("y", y, ref, tol)
+
+
+def test_gram_tridiagonal_inverse_recovers_x():
+    """Property that holds at any size: for distinct anchors K^-1 is tridiagonal
+    (Ornstein-Uhlenbeck precision), so applying it in fp64 to the GPU's y gives x back."""
+    r = np.random.default_rng(12)
+    n, batch = 200000, 4
+    a_sorted = np.cumsum(r.uniform(0.02, 0.5, n)).astype(np.float32)
+    assert np.all(np.diff(a_sorted) > 0)
+    p = r.permutation(n)
+    a = a_sorted[p]
+    x = r.normal(size=(n, batch)).astype(np.float32)
+    y, _ = gpu_gram(a, x)
+    inv = np.empty(n, dtype=np.int64); inv[p] = np.arange(n)
+    ys = y[inv].astype(np.float64); xs = x[inv].astype(np.float64)
+    a64 = a_sorted.astype(np.float64)
+    rho = np.exp(-np.diff(a64)); r2 = rho ** 2 / (1 - rho ** 2); off = -rho / (1 - rho ** 2)
+    diag = np.ones(n); diag[:-1] += r2; diag[1:] += r2
+    back = diag[:, None] * ys; back[:-1] += off[:, None] * ys[1:]; back[1:] += off[:, None] * ys[:-1]
+    # row tolerance: sum_j |Kinv_ij| * (1e-5 * T_j + 1e-7) with T_j <= sum_j K_ij |x_j| ~ a few dozen
+    tol_y = RTOL * 60.0 + ATOL
+    bound = (diag + np.r_[np.abs(off), 0] + np.r_[0, np.abs(off)]) * tol_y
+    assert np.all(np.abs(back - xs) <= bound[:, None])
+
+
+# ------------------------------------------------------------------ the five workloads
+
+def test_workload_square_4096_every_output(oracle):
+    w = synth.square_small()
+    ref, tol = oracle.apply_brute(w["a"], w["b"], w["x"])
+    y, ws = gpu_apply(w["a"], w["b"], w["x"])
+    worst = assert_close("y", y, ref, tol)
+    assert np.array_equal(gpu_perm(ws, 8192), oracle.merged_permutation(w["a"], w["b"]))
+    rel_inf = np.abs(y - ref).max() / np.abs(ref).max()
+    print(f"square 4096: worst tolerance ratio {worst:.3g}, rel linf {rel_inf:.3g}")
+    assert rel_inf < 5e-6
+
+
+@pytest.mark.parametrize("scale", [16, 64])
+def test_workload_projection_scaled(oracle, scale):
+    w = synth.projection_layer(scale=scale)
+    a, b, x, g = w["a"], w["b"], w["x"], w["g"]
+    ref, tol = oracle.apply_scan(a, b, x)
+    y, ws = gpu_apply(a, b, x, flags=B.LAPLEX_SAVE_SCANS)
+    assert_close("y", y, ref, tol)
+    (rgx, rga, rgb), (tgx, tga, tgb) = oracle.apply_backward_scan(a, b, x, g)
+    gx, ga, gb = gpu_backward(a, b, x, g, flags=B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN, ws=ws)
+    assert_close("gx", gx, rgx, tgx); assert_close("ga", ga, rga, tga); assert_close("gb", gb, rgb, tgb)
+
+
+def test_workload_tie_heavy_scaled(oracle):
+    w = synth.tie_heavy(scale=64)            # n = k = 2^18 on a 1/4 grid of 2^14 points
+    a, b, x, g = w["a"], w["b"], w["x"], w["g"]
+    y, ws = gpu_apply(a, b, x, flags=B.LAPLEX_SAVE_SCANS)
+    assert np.array_equal(gpu_perm(ws, a.size + b.size), oracle.merged_permutation(a, b))
+    ref, tol = oracle.apply_scan(a, b, x)
+    assert_close("y", y, ref, tol)
+    (rgx, rga, rgb), (tgx, tga, tgb) = oracle.apply_backward_scan(a, b, x, g)
+    gx, ga, gb = gpu_backward(a, b, x, g, flags=B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN, ws=ws)
+    assert_close("gx", gx, rgx, tgx); assert_close("ga", ga, rga, tga); assert_close("gb", gb, rgb, tgb)
+
+
+def test_workload_gram_images_scaled(oracle):
+    w = synth.gram_images(scale=32)          # n = 98304, batch 64
+    a, x, g = w["a"], w["x"], w["g"]
+    ref, tol = oracle.gram_scan(a, x)
+    y, ws = gpu_gram(a, x, flags=B.LAPLEX_SAVE_SCANS)
+    assert_close("y", y, ref, tol)
+    (rgx, rga), (tgx, tga) = oracle.gram_backward_scan(a, x, g)
+    gx, ga = gpu_gram_backward(a, x, g, flags=B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN, ws=ws)
+    assert_close("gx", gx, rgx, tgx); assert_close("ga", ga, rga, tga)
+
+
+def test_workload_billion_scaled(oracle):
+    w = synth.billion_square(scale=1024)     # n = k = 2^20, anchors U(0, 2^14)
+    a, b, x, g = w["a"], w["b"], w["x"], w["g"]
+    ref, tol = oracle.apply_scan(a, b, x)
+    y, ws = gpu_apply(a, b, x, flags=B.LAPLEX_SAVE_SCANS)
+    assert_close("y", y, ref, tol)
+    assert np.array_equal(gpu_perm(ws, a.size + b.size), oracle.merged_permutation(a, b))
+    (rgx, rga, rgb), (tgx, tga, tgb) = oracle.apply_backward_scan(a, b, x, g)
+    gx, ga, gb = gpu_backward(a, b, x, g, flags=B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN, ws=ws)
+    assert_close("gx", gx, rgx, tgx); assert_close("ga", ga, rga, tga); assert_close("gb", gb, rgb, tgb)

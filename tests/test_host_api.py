@@ -1,0 +1,148 @@
+"""Host logic of the C-ABI library, no GPU needed: the library loads, exports
+every symbol the header declares, and rejects bad arguments before any HIP call."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from conftest import ROOT
+from paper_2605_24584_amd import binding as B
+
+FAKE = 0x10000          # a non-null, 256-byte aligned "device pointer" that must never be touched
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2605_24584_amd import build
+        build.build()
+    return B.lib()
+
+
+def test_every_declared_symbol_is_exported(L):
+    header = open(os.path.join(ROOT, "include", "laplex.h")).read()
+    declared = set(re.findall(r"\b(laplex_[a-z_]+)\s*\(", header))
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_status_strings(L):
+    seen = {B.laplex_status_string(s) for s in range(0, -8, -1)}
+    assert len(seen) == 8 and "unknown status" not in seen
+    assert B.laplex_status_string(-99) == "unknown status"
+    assert B.laplex_last_hip_error() == ""
+
+
+def ws_bytes(L, k, n, batch):
+    out = ctypes.c_size_t(0)
+    rc = L.laplex_workspace_bytes(k, n, batch, ctypes.byref(out))
+    return rc, out.value
+
+
+def test_workspace_bytes(L):
+    assert L.laplex_workspace_bytes(1, 1, 1, None) == B.LAPLEX_ERR_NULL
+    assert ws_bytes(L, -1, 1, 1)[0] == B.LAPLEX_ERR_SIZE
+    assert ws_bytes(L, 1, -1, 1)[0] == B.LAPLEX_ERR_SIZE
+    assert ws_bytes(L, 1, 1, -1)[0] == B.LAPLEX_ERR_SIZE
+    assert ws_bytes(L, 1 << 31, 1 << 31, 1)[0] == B.LAPLEX_ERR_SIZE       # k + n = 2^32
+    rc, top = ws_bytes(L, (1 << 31) - 1, (1 << 31) - 1, 1)                 # the largest merged length
+    assert rc == 0 and top > 12 * ((1 << 32) - 2)
+    sizes = [ws_bytes(L, 1024, n, 256)[1] for n in (1 << 10, 1 << 16, 1 << 20)]
+    assert sizes == sorted(sizes) and sizes[0] > 0
+    assert ws_bytes(L, 4096, 4096, 1)[1] % 256 == 0
+    # plan (ids + decays) alone is 8 bytes per merged position
+    assert ws_bytes(L, 1 << 20, 1 << 20, 1)[1] >= 8 * (1 << 21)
+    assert ws_bytes(L, 0, 0, 0)[0] == 0
+
+
+def apply_args(k=8, n=8, batch=4, a=FAKE, b=FAKE, x=FAKE, ldx=None, y=FAKE, ldy=None,
+               ws=FAKE, wsb=1 << 40, flags=0):
+    return (a, k, b, n, x, batch if ldx is None else ldx, batch, y, batch if ldy is None else ldy,
+            ws, wsb, flags, None)
+
+
+def test_apply_rejects_bad_arguments_before_touching_the_gpu(L):
+    f = L.laplex_apply
+    assert f(*apply_args(a=None)) == B.LAPLEX_ERR_NULL
+    assert f(*apply_args(b=None)) == B.LAPLEX_ERR_NULL
+    assert f(*apply_args(x=None)) == B.LAPLEX_ERR_NULL
+    assert f(*apply_args(y=None)) == B.LAPLEX_ERR_NULL
+    assert f(*apply_args(ws=None)) == B.LAPLEX_ERR_NULL
+    assert f(*apply_args(k=-1)) == B.LAPLEX_ERR_SIZE
+    assert f(*apply_args(n=-2)) == B.LAPLEX_ERR_SIZE
+    assert f(*apply_args(batch=-1)) == B.LAPLEX_ERR_SIZE
+    assert f(*apply_args(k=1 << 31, n=1 << 31)) == B.LAPLEX_ERR_SIZE
+    assert f(*apply_args(ldx=3)) == B.LAPLEX_ERR_LD
+    assert f(*apply_args(ldy=0)) == B.LAPLEX_ERR_LD
+    assert f(*apply_args(flags=16)) == B.LAPLEX_ERR_FLAGS
+    assert f(*apply_args(flags=1 << 31)) == B.LAPLEX_ERR_FLAGS
+    assert f(*apply_args(a=FAKE + 2)) == B.LAPLEX_ERR_ALIGN
+    assert f(*apply_args(ws=FAKE + 64)) == B.LAPLEX_ERR_ALIGN
+    need = ws_bytes(L, 8, 8, 4)[1]
+    assert f(*apply_args(wsb=need - 1)) == B.LAPLEX_ERR_WORKSPACE
+    assert f(*apply_args(wsb=0)) == B.LAPLEX_ERR_WORKSPACE
+    # nothing to do: success without any launch (pointers are never looked at)
+    assert f(*apply_args(k=0, a=None, y=None, ws=None, wsb=0)) == B.LAPLEX_OK
+    assert f(*apply_args(batch=0, x=None, y=None, ws=None, wsb=0)) == B.LAPLEX_OK
+
+
+def bwd_args(k=8, n=8, batch=4, a=FAKE, b=FAKE, x=FAKE, gy=FAKE, gx=FAKE, ga=FAKE, gb=FAKE,
+             ldx=None, ldgy=None, ldgx=None, ws=FAKE, wsb=1 << 40, flags=0):
+    ld = lambda v: batch if v is None else v
+    return (a, k, b, n, x, ld(ldx), gy, ld(ldgy), batch, gx, ld(ldgx), ga, gb, ws, wsb, flags, None)
+
+
+def test_apply_backward_rejects_bad_arguments(L):
+    f = L.laplex_apply_backward
+    assert f(*bwd_args(gy=None)) == B.LAPLEX_ERR_NULL
+    assert f(*bwd_args(x=None)) == B.LAPLEX_ERR_NULL              # ga / gb wanted: x is needed
+    assert f(*bwd_args(x=None, ga=None, gb=None, ws=None)) == B.LAPLEX_ERR_NULL   # ... then only ws is missing
+    assert f(*bwd_args(ldgy=1)) == B.LAPLEX_ERR_LD
+    assert f(*bwd_args(ldgx=2)) == B.LAPLEX_ERR_LD
+    assert f(*bwd_args(flags=32)) == B.LAPLEX_ERR_FLAGS
+    assert f(*bwd_args(ga=FAKE + 1)) == B.LAPLEX_ERR_ALIGN
+    assert f(*bwd_args(wsb=100)) == B.LAPLEX_ERR_WORKSPACE
+    assert f(*bwd_args(n=-1)) == B.LAPLEX_ERR_SIZE
+
+
+def test_gram_rejects_bad_arguments(L):
+    g = L.laplex_gram
+    ok = dict(a=FAKE, n=8, x=FAKE, ldx=4, batch=4, y=FAKE, ldy=4, ws=FAKE, wsb=1 << 40, flags=0)
+    call = lambda **kw: g(*[{**ok, **kw}[key] for key in ("a", "n", "x", "ldx", "batch", "y", "ldy", "ws", "wsb", "flags")], None)
+    assert call(a=None) == B.LAPLEX_ERR_NULL
+    assert call(flags=B.LAPLEX_B_SORTED) == B.LAPLEX_ERR_FLAGS       # there is no b
+    assert call(ldy=3) == B.LAPLEX_ERR_LD
+    assert call(n=-1) == B.LAPLEX_ERR_SIZE
+    assert call(wsb=8) == B.LAPLEX_ERR_WORKSPACE
+    assert call(n=0, a=None, x=None, y=None, ws=None, wsb=0) == B.LAPLEX_OK
+    gb = L.laplex_gram_backward
+    assert gb(FAKE, 8, FAKE, 4, None, 4, 4, FAKE, 4, FAKE, FAKE, 1 << 40, 0, None) == B.LAPLEX_ERR_NULL
+    assert gb(FAKE, 8, None, 4, FAKE, 4, 4, FAKE, 4, FAKE, FAKE, 1 << 40, 0, None) == B.LAPLEX_ERR_NULL
+    assert gb(FAKE, 8, FAKE, 4, FAKE, 4, 4, FAKE, 4, FAKE, FAKE, 1 << 40, B.LAPLEX_B_SORTED, None) == B.LAPLEX_ERR_FLAGS
+
+
+def test_get_perm_rejects_bad_arguments(L):
+    f = L.laplex_get_perm
+    assert f(None, 100, 4, FAKE, None) == B.LAPLEX_ERR_NULL
+    assert f(FAKE, 100, 4, None, None) == B.LAPLEX_ERR_NULL
+    assert f(FAKE, 100, -1, FAKE, None) == B.LAPLEX_ERR_SIZE
+    assert f(FAKE, 15, 4, FAKE, None) == B.LAPLEX_ERR_WORKSPACE
+    assert f(FAKE, 0, 0, None, None) == B.LAPLEX_OK
+
+
+def test_binding_raises_with_status(L):
+    with pytest.raises(B.LaplexError) as e:
+        B.laplex_workspace_bytes(-1, 0, 0)
+    assert e.value.status == B.LAPLEX_ERR_SIZE
+
+
+def test_oracle_is_not_reachable_from_the_product():
+    """The product package must not import, load or link the oracle."""
+    pkg = os.path.join(ROOT, "paper_2605_24584_amd")
+    pat = re.compile(r"import\s+oracle|from\s+oracle|laplex_oracle|oracle/")
+    for dirpath, _, files in os.walk(pkg):
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".h", ".cpp")):
+                assert not pat.search(open(os.path.join(dirpath, fn)).read()), fn
