@@ -89,8 +89,11 @@ def _ld(t):
         return 0
     if t.dim() == 1:
         return 1
-    assert t.dim() == 2 and (t.shape[1] <= 1 or t.stride(1) == 1), "batch axis must be contiguous"
-    return t.stride(0) if t.shape[0] > 1 else max(t.shape[1], 1)
+    assert t.dim() == 2
+    if t.shape[0] <= 1 or t.shape[1] == 0:
+        return max(t.shape[1], 1)
+    assert t.shape[1] == 1 or t.stride(1) == 1, "batch axis must be contiguous"
+    return t.stride(0)
 
 
 def _batch(t):
