@@ -1,0 +1,169 @@
+#!/usr/bin/env python3
+"""Benchmark of the LAPLEX hot path on one MI355X.
+
+One step = one pass of the whole path over one batch of synthetic input:
+    laplex_apply          (key build, radix sort, decay, forward + backward scan, scatter)
+    laplex_apply_backward (gx, ga, gb; plan and saved scans of the forward reused)
+on the neural-projection workload (n = 2^20 inputs, k = 1024 outputs, batch 256,
+fp32), inputs resident in HBM before the timed region.
+
+Prints ONE JSON line: throughput in (n + k) * batch elements per second, the
+roofline of the dominant kernel (backward downsweep, timed with HIP events on
+its own stream during the timed steps) and the CPU oracle timed beside it on a
+bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+DOMINANT = "scan_down.bwd"
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--scale", type=int, default=1, help="shrink n and k by this factor (debug only)")
+    ap.add_argument("--batch", type=int, default=256)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-columns", type=int, default=256)
+    return ap.parse_args()
+
+
+def dominant_kernel_bytes(k, n, batch):
+    """Algorithmic bytes of one backward-downsweep launch: sorted ids and decays
+    (8 B per merged position), x read and gx written once each, gy read once,
+    gb written."""
+    N = k + n
+    return 8 * N + 4 * batch * n * 2 + 4 * batch * k + 4 * n
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only; multi-GPU runs are not part of it "
+              "(the path would shard by batch columns, see DESIGN.md).", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2605_24584_amd import binding as B
+    from paper_2605_24584_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    B.lib()   # fails loudly if the HIP library is not built
+
+    w = synth.projection_layer(scale=args.scale, batch=args.batch)
+    a, b, x, g = w["a"], w["b"], w["x"], w["g"]
+    k, n, batch = a.size, b.size, x.shape[1]
+    da, db = torch.from_numpy(a).cuda(), torch.from_numpy(b).cuda()
+    dx, dg = torch.from_numpy(x).cuda(), torch.from_numpy(g).cuda()
+    ws_bytes = B.laplex_workspace_bytes(k, n, batch)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    y = torch.empty(k, batch, device="cuda")
+    gx = torch.empty(n, batch, device="cuda")
+    ga = torch.empty(k, device="cuda")
+    gb = torch.empty(n, device="cuda")
+
+    def step():
+        B.laplex_apply(da, db, dx, y, ws, B.LAPLEX_SAVE_SCANS)
+        B.laplex_apply_backward(da, db, dx, dg, gx, ga, gb, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # the timed region: exactly --steps steps; the dominant kernel carries one HIP event pair per launch
+    B.laplex_profile_begin(DOMINANT)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    dom_ms, dom_launches = B.laplex_profile_end()
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    elements = (n + k) * batch
+    value = elements / (ms_per_step * 1e-3)
+
+    dom_avg_ms = dom_ms / max(dom_launches, 1)
+    dom_bytes = dominant_kernel_bytes(k, n, batch)
+    achieved = dom_bytes / (dom_avg_ms * 1e-3) / 1e9 if dom_launches else 0.0
+    roofline = {
+        "bound": "hbm", "kernel": "k_scan_down<4,true> (backward downsweep)",
+        "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+        "avg_kernel_ms": round(dom_avg_ms, 5), "launches": dom_launches, "algorithmic_bytes": dom_bytes,
+    }
+    traffic_file = os.path.join(ROOT, "profiles", "traffic_scan_down_bwd_projection.json")
+    if args.scale == 1 and args.batch == 256 and os.path.exists(traffic_file):
+        with open(traffic_file) as fh:
+            roofline["traffic"] = json.load(fh).get("hbm_bytes_per_launch")
+
+    # per-phase split of one step (separate loops, outside the timed region)
+    phases = {}
+    for name, fn in (
+        ("apply_ms", lambda: B.laplex_apply(da, db, dx, y, ws, B.LAPLEX_SAVE_SCANS)),
+        ("apply_reuse_plan_ms", lambda: B.laplex_apply(da, db, dx, y, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)),
+        ("backward_ms", lambda: B.laplex_apply_backward(da, db, dx, dg, gx, ga, gb, ws,
+                                                        B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)),
+    ):
+        reps = max(5, args.steps // 5)
+        torch.cuda.synchronize()
+        s0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        phases[name] = round((time.perf_counter() - s0) * 1e3 / reps, 4)
+
+    out = {
+        "metric": "LAPLEX fwd+bwd (n+k)*batch elements/s", "value": value, "unit": "elements/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w["name"] if args.scale == 1 and args.batch == 256 else f"{w['name']}/scaled",
+                   "k": k, "n": n, "batch": batch, "anchors": "U(0,2^14)", "pass": "forward+backward (gx, ga, gb)",
+                   "sort": "radix sort inside every step", "workspace_bytes": ws_bytes},
+        "roofline": roofline,
+        "phases": phases,
+        # compulsory HBM bytes of one step (x twice, gx once, gy, y, anchors and gradients) over the step time
+        "end_to_end_hbm_frac": round((4 * (n + k) * 2 + 4 * batch * (3 * n + 2 * k)) / (ms_per_step * 1e-3) / 1e9
+                                     / HBM_PEAK_GBS, 4),
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import laplex_oracle as oracle
+        oracle.build()
+        cols = min(args.cpu_sample_columns, batch)
+        xs = np.ascontiguousarray(x[:, :cols]); gs = np.ascontiguousarray(g[:, :cols])
+        c0 = time.perf_counter()
+        oracle.apply_scan(a, b, xs, with_tol=False)
+        # gradients without the tolerance denominators: the same scans the timed GPU step performs
+        x64 = xs.astype(np.float64); g64 = gs.astype(np.float64)
+        _, ls, rs = oracle._dual(b, x64, a, want=(False, True, True))
+        (g64 * (rs - ls)).sum(axis=1)
+        li, ls, rs = oracle._dual(a, g64, b)
+        (li + rs); (x64 * (rs - ls)).sum(axis=1)
+        c1 = time.perf_counter()
+        out["cpu_baseline"] = {
+            "value": (n + k) * cols / (c1 - c0), "unit": "elements/s",
+            "cores": min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)), cols),
+            "kind": "oracle",
+            "sample": f"fp64 sort + dual-theorem scans, forward + backward, all n and k, first {cols} of {batch} batch columns",
+            "seconds": round(c1 - c0, 3),
+        }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

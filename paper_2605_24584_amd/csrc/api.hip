@@ -185,6 +185,7 @@ int laplex_apply(const float* a, int64_t k, const float* b, int64_t n,
     p.res_lo = 0; p.res_hi = (uint32_t)k;
     p.out_p = y; p.ld_p = ldy;
     p.out_z = (flags & LAPLEX_SAVE_SCANS) ? P.z : nullptr;
+    p.tag = "fwd";
     LAPLEX_HIP(launch_scan(p, L, w, st));
     return LAPLEX_OK;
 }
@@ -224,6 +225,7 @@ int laplex_apply_backward(const float* a, int64_t k, const float* b, int64_t n,
             p.inj = x; p.ld_inj = ldx; p.inj_lo = (uint32_t)k; p.inj_hi = (uint32_t)(k + n);
             p.res_lo = 0; p.res_hi = (uint32_t)k;
             p.out_z = P.z;
+            p.tag = "rescan";
             LAPLEX_HIP(launch_scan(p, L, w, st));
         }
         LAPLEX_HIP(launch_rowdot(gy, ldgy, P.z, batch, k, batch, ga, st));
@@ -234,6 +236,7 @@ int laplex_apply_backward(const float* a, int64_t k, const float* b, int64_t n,
         p.res_lo = (uint32_t)k; p.res_hi = (uint32_t)(k + n);
         p.out_p = gx; p.ld_p = ldgx;
         p.out_red = gb; p.w = x; p.ld_w = ldx;
+        p.tag = "bwd";
         LAPLEX_HIP(launch_scan(p, L, w, st));
     }
     return LAPLEX_OK;
@@ -260,6 +263,7 @@ int laplex_gram(const float* a, int64_t n, const float* x, int64_t ldx, int64_t 
     p.res_lo = 0; p.res_hi = (uint32_t)n;
     p.out_p = y; p.ld_p = ldy;
     p.out_z = (flags & LAPLEX_SAVE_SCANS) ? P.z : nullptr;
+    p.tag = "fwd";
     LAPLEX_HIP(launch_scan(p, L, w, st));
     return LAPLEX_OK;
 }
@@ -292,6 +296,7 @@ int laplex_gram_backward(const float* a, int64_t n, const float* x, int64_t ldx,
         p.inj = x; p.ld_inj = ldx; p.inj_lo = 0; p.inj_hi = (uint32_t)n;
         p.res_lo = 0; p.res_hi = (uint32_t)n;
         p.out_z = P.z;
+        p.tag = "rescan";
         LAPLEX_HIP(launch_scan(p, L, w, st));
     }
     if (gx || ga) {
@@ -300,6 +305,7 @@ int laplex_gram_backward(const float* a, int64_t n, const float* x, int64_t ldx,
         p.res_lo = 0; p.res_hi = (uint32_t)n;
         p.out_p = gx; p.ld_p = ldgx;
         p.out_red = ga; p.w = x; p.ld_w = ldx; p.zs = ga ? P.z : nullptr;
+        p.tag = "bwd";
         LAPLEX_HIP(launch_scan(p, L, w, st));
     }
     return LAPLEX_OK;

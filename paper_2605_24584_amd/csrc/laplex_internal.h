@@ -185,6 +185,7 @@ struct ScanProblem {
     float* out_z;
     float* out_red; const float* w; int64_t ld_w; const float* zs;
     int64_t batch;
+    const char* tag;   // names the timing families: scan_reduce.<tag>, scan_spine.<tag>, scan_down.<tag>
 };
 hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStream_t st);
 

@@ -26,6 +26,8 @@
 // wavefront; each row-lane walks `items` consecutive rows sequentially.
 #include "laplex_internal.h"
 
+#include <string>
+
 namespace laplex {
 
 namespace {
@@ -525,13 +527,15 @@ hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStrea
     A.car_e = reinterpret_cast<float*>(ws + L.off_car_e);
     A.red_partial = reinterpret_cast<float*>(ws + L.off_red);
 
+    const std::string tag = p.tag ? p.tag : "scan";
+    const std::string fam_r = "scan_reduce." + tag, fam_s = "scan_spine." + tag, fam_d = "scan_down." + tag;
     const dim3 grid((unsigned)g.tiles, (unsigned)g.slabs), block(kScanThreads);
     const dim3 sgrid((unsigned)p.batch, 2), sblock(kSpineThreads);
 #define LAPLEX_LAUNCH3(V, S)                                                                    \
     do {                                                                                        \
-        LAPLEX_TIMED("scan_reduce", st, hipLaunchKernelGGL((k_scan_reduce<V, S>), grid, block, 0, st, A)); \
-        LAPLEX_TIMED("scan_spine", st, hipLaunchKernelGGL((k_scan_spine<S>), sgrid, sblock, 0, st, A));    \
-        LAPLEX_TIMED("scan_down", st, hipLaunchKernelGGL((k_scan_down<V, S>), grid, block, 0, st, A));     \
+        LAPLEX_TIMED(fam_r.c_str(), st, hipLaunchKernelGGL((k_scan_reduce<V, S>), grid, block, 0, st, A)); \
+        LAPLEX_TIMED(fam_s.c_str(), st, hipLaunchKernelGGL((k_scan_spine<S>), sgrid, sblock, 0, st, A));    \
+        LAPLEX_TIMED(fam_d.c_str(), st, hipLaunchKernelGGL((k_scan_down<V, S>), grid, block, 0, st, A));     \
     } while (0)
     if (v4) { if (strict) LAPLEX_LAUNCH3(4, true); else LAPLEX_LAUNCH3(4, false); }
     else    { if (strict) LAPLEX_LAUNCH3(1, true); else LAPLEX_LAUNCH3(1, false); }

@@ -19,13 +19,15 @@ density experiment, and the n ~ 2^29..2^30 end of the runtime curve (Fig. 1).
 """
 from __future__ import annotations
 
+import os
+
 import numpy as np
 
 _GOLDEN = np.uint64(0x9E3779B97F4A7C15)
 _M1 = np.uint64(0xBF58476D1CE4E5B9)
 _M2 = np.uint64(0x94D049BB133111EB)
 _BASE_SEED = 260524584 * 16
-_CHUNK = 1 << 22
+_CHUNK = 1 << 20
 
 STREAM_A, STREAM_B, STREAM_X, STREAM_G = 0, 1, 2, 3
 
@@ -50,26 +52,39 @@ def unit_uniform(seed: int, start: int, count: int) -> np.ndarray:
     return (_bits(seed, start, count) >> np.uint64(11)).astype(np.float64) * (1.0 / (1 << 53))
 
 
+def _chunks(count: int, fill) -> np.ndarray:
+    """fill(start, c) -> fp32 chunk; chunks are independent (counter based), so
+    large arrays are filled by a few threads (numpy releases the GIL)."""
+    out = np.empty(count, dtype=np.float32)
+    starts = range(0, count, _CHUNK)
+
+    def one(s):
+        c = min(_CHUNK, count - s)
+        out[s:s + c] = fill(s, c)
+
+    if count <= 4 * _CHUNK:
+        for s in starts:
+            one(s)
+    else:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as pool:
+            list(pool.map(one, starts))
+    return out
+
+
 def uniform(seed: int, count: int, lo: float, hi: float) -> np.ndarray:
     """fp32 array of ``count`` draws from U(lo, hi), scaled in fp64, rounded last."""
-    out = np.empty(count, dtype=np.float32)
-    for s in range(0, count, _CHUNK):
-        c = min(_CHUNK, count - s)
-        out[s:s + c] = (lo + (hi - lo) * unit_uniform(seed, s, c)).astype(np.float32)
-    return out
+    return _chunks(count, lambda s, c: (lo + (hi - lo) * unit_uniform(seed, s, c)).astype(np.float32))
 
 
 def normal(seed: int, count: int, sigma: float = 1.0) -> np.ndarray:
     """fp32 array of ``count`` draws from N(0, sigma^2) (Box-Muller in fp64)."""
-    out = np.empty(count, dtype=np.float32)
-    for s in range(0, count, _CHUNK):
-        c = min(_CHUNK, count - s)
+    def fill(s, c):
         u = unit_uniform(seed, 2 * s, 2 * c)
         u1 = 1.0 - u[0::2]            # (0, 1]: log is finite
         u2 = u[1::2]
-        z = np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
-        out[s:s + c] = (sigma * z).astype(np.float32)
-    return out
+        return (sigma * (np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2))).astype(np.float32)
+    return _chunks(count, fill)
 
 
 def quarter_grid(v: np.ndarray) -> np.ndarray:
