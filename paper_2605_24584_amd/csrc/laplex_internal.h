@@ -34,6 +34,7 @@ constexpr int kScanWaves = 8;
 constexpr int kScanThreads = kScanWaves * 64;
 constexpr int kItemsVec1 = 16;   // rows per row-lane when a lane holds 1 column
 constexpr int kItemsVec4 = 8;    // rows per row-lane when a lane holds 4 columns
+constexpr int kSpineItems = 8;    // tile summaries per row-lane in the chunked spine kernels
 constexpr int kSpineThreads = 1024;
 
 struct ScanGeom {
@@ -44,6 +45,8 @@ struct ScanGeom {
     int slabs;        // ceil(batch / (bv * vec)): blockIdx.y
     int tile_rows;    // kScanWaves * rv * items
     int64_t tiles;    // ceil(N / tile_rows)
+    int chunk_tiles;  // tiles summarised by one workgroup of the chunked spine: kScanWaves * rv * kSpineItems
+    int64_t chunks;   // ceil(tiles / chunk_tiles)
 };
 
 inline int pow2_at_least(int64_t v) { int p = 1; while (p < v) p <<= 1; return p; }
@@ -60,6 +63,8 @@ inline ScanGeom scan_geom(int64_t N, int64_t batch, int vec)
     if (g.slabs < 1) g.slabs = 1;
     g.tile_rows = kScanWaves * g.rv * g.items;
     g.tiles = (N + g.tile_rows - 1) / g.tile_rows;
+    g.chunk_tiles = kScanWaves * g.rv * kSpineItems;
+    g.chunks = (g.tiles + g.chunk_tiles - 1) / g.chunk_tiles;
     return g;
 }
 
@@ -88,7 +93,9 @@ struct Layout {
     size_t off_car_f = 0;        // f32[2][tiles][bpad]         carry F
     size_t off_car_e = 0;        // f32[2][tiles][bpad]         carry E
     size_t off_red = 0;          // f32[slabs][N]               per-slab partial row reductions
-    int64_t max_tiles = 0;
+    // second level of the spine: the same five arrays over chunks of tiles
+    size_t off_agg2_scalar = 0, off_agg2_s = 0, off_agg2_q = 0, off_car2_f = 0, off_car2_e = 0;
+    int64_t max_tiles = 0, max_chunks = 0;
     size_t total = 0;
 };
 
@@ -127,6 +134,13 @@ inline Layout make_layout(int64_t N, int64_t zrows, int64_t batch)
     L.off_car_e = c;      c = align_up(c + per);
     L.off_red = c;
     if (max_slabs > 1) c = align_up(c + sizeof(float) * (size_t)max_slabs * (size_t)N);
+    L.max_chunks = g1.chunks > g4.chunks ? g1.chunks : g4.chunks;
+    const size_t per2 = sizeof(float) * 2 * (size_t)L.max_chunks * (size_t)L.bpad;
+    L.off_agg2_scalar = c; c = align_up(c + sizeof(float) * 4 * 2 * (size_t)L.max_chunks);
+    L.off_agg2_s = c;      c = align_up(c + per2);
+    L.off_agg2_q = c;      c = align_up(c + per2);
+    L.off_car2_f = c;      c = align_up(c + per2);
+    L.off_car2_e = c;      c = align_up(c + per2);
 
     L.total = s > c ? s : c;
     return L;

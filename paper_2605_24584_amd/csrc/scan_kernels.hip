@@ -14,13 +14,19 @@
 //
 // A run of rows is summarised by (D, S) with F_out = D F_in + S, plus, for the
 // strict channel, (H, C, Q) with E_out = H ? C F_in + Q : E_in.  Summaries
-// compose associatively, so the work splits into three launches, with both
-// directions done together so that the injected matrix is read once per launch:
+// compose associatively, so the work splits into launches, with both directions
+// done together so that the injected matrix is read once per launch:
 //
-//   reduce     per tile: its forward and its backward summary
-//   spine      per batch column and direction: exclusive scan over tile summaries
-//   downsweep  per tile that holds result rows: re-read the tile, seed both
-//              walks with the carries, walk forward then backward and emit
+//   reduce        per tile: forward and backward summary, and whether the tile
+//                 holds injected rows / result rows
+//   spine         exclusive scan over the tile summaries, two levels: chunks of
+//                 tiles are summarised (coalesced over the batch), the chunk
+//                 summaries are scanned, and the carries are pushed back down
+//   downsweep     tiles with injected AND result rows: re-read the tile, seed
+//                 both walks with the carries, walk forward, then backward, emit
+//   downsweep_sparse  tiles with result rows but nothing injected: every row is
+//                 a closed form of the two carries (the two-term evaluation of
+//                 Thm "Dual reduction" inside a tile), streamed with no row state
 //
 // Lanes: bv lanes across the batch (vec columns each) x rv row-lanes per
 // wavefront; each row-lane walks `items` consecutive rows sequentially.
@@ -32,6 +38,15 @@ namespace laplex {
 
 namespace {
 
+struct Level {            // summaries of one level (tiles, or chunks of tiles) and the carries into them
+    float4* scalar;       // [2][count]        (D, C, H, flags)
+    float* s;             // [2][count][bpad]
+    float* q;             // [2][count][bpad]
+    float* car_f;         // [2][count][bpad]
+    float* car_e;         // [2][count][bpad]
+    int64_t count;
+};
+
 struct ScanArgs {
     const uint32_t* ids; const float* dh; int64_t N;
     const float* inj; int64_t ld_inj; uint32_t inj_lo, inj_hi;
@@ -39,11 +54,13 @@ struct ScanArgs {
     float* out_p; int64_t ld_p;
     float* out_z;
     float* out_red; const float* w; int64_t ld_w; const float* zs;
-    int64_t batch, bpad, tiles;
-    int bv, bv_log2, rv, tile_rows, slabs;
-    float4* agg_scalar; float* agg_s; float* agg_q; float* car_f; float* car_e;
+    int64_t batch, bpad;
+    int bv, bv_log2, rv, tile_rows, slabs, chunk_tiles;
+    Level l1, l2;
     float* red_partial;   // [slabs][res rows] when slabs > 1
 };
+
+constexpr int kFlagInj = 1, kFlagRes = 2;
 
 template <int VEC, bool STRICT>
 struct Seg {
@@ -126,7 +143,7 @@ __device__ __forceinline__ void seg_apply(const Seg<VEC, STRICT>& s, float* F, f
     }
 }
 
-// Inclusive scan of the row-lanes of one wavefront, in forward (row-lane 0
+// Inclusive scan over the row-lanes of one wavefront, in forward (row-lane 0
 // first) or backward (last row-lane first) order.  Lanes with equal (lane & (bv-1))
 // hold the same batch columns.
 template <bool FWD, int VEC, bool STRICT>
@@ -141,15 +158,6 @@ __device__ __forceinline__ Seg<VEC, STRICT> wave_scan(Seg<VEC, STRICT> s, int la
     }
     return s;
 }
-
-template <int VEC>
-struct TileRows {
-    static constexpr int ITEMS = VEC == 4 ? kItemsVec4 : kItemsVec1;
-    float dh[ITEMS + 1];      // dh[i]: decay into row i from the left; dh[i+1]: from the right
-    uint32_t id[ITEMS];
-    bool live[ITEMS];
-    float v[ITEMS][VEC];
-};
 
 template <int VEC>
 __device__ __forceinline__ void load_vec(float* dst, const float* src)
@@ -170,8 +178,14 @@ __device__ __forceinline__ void store_vec(float* dst, const float* src)
 }
 
 template <int VEC>
-__device__ __forceinline__ void load_rows(const ScanArgs& A, int64_t row0, int64_t col0, bool col_ok,
-                                          TileRows<VEC>& T)
+struct TileRows {
+    static constexpr int ITEMS = VEC == 4 ? kItemsVec4 : kItemsVec1;
+    float dh[ITEMS + 1];      // dh[i]: decay into row i from the left; dh[i+1]: from the right
+    uint32_t id[ITEMS];       // 0xFFFFFFFF past the end of the sequence
+};
+
+template <int VEC>
+__device__ __forceinline__ void load_meta(const ScanArgs& A, int64_t row0, TileRows<VEC>& T)
 {
     constexpr int ITEMS = TileRows<VEC>::ITEMS;
 #pragma unroll
@@ -182,28 +196,29 @@ __device__ __forceinline__ void load_rows(const ScanArgs& A, int64_t row0, int64
 #pragma unroll
     for (int i = 0; i < ITEMS; ++i) {
         const int64_t j = row0 + i;
-        T.live[i] = j < A.N;
-        T.id[i] = T.live[i] ? A.ids[j] : 0xFFFFFFFFu;
-    }
-#pragma unroll
-    for (int i = 0; i < ITEMS; ++i) {
-        const bool inj = col_ok && T.id[i] >= A.inj_lo && T.id[i] < A.inj_hi;
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) T.v[i][e] = 0.0f;
-        if (inj) load_vec<VEC>(T.v[i], A.inj + (int64_t)(T.id[i] - A.inj_lo) * A.ld_inj + col0);
+        T.id[i] = j < A.N ? A.ids[j] : 0xFFFFFFFFu;
     }
 }
 
-template <int VEC, bool STRICT>
-__device__ __forceinline__ void local_segs(const TileRows<VEC>& T, Seg<VEC, STRICT>& f, Seg<VEC, STRICT>& b)
+// Row i starts a run of equal keys seen from the left / from the right.  Rows past
+// the end (id 0xFFFFFFFF) are neutral: no head, decay 1, nothing injected.
+template <int VEC>
+__device__ __forceinline__ bool head_f(const TileRows<VEC>& T, int i) { return T.id[i] != 0xFFFFFFFFu && T.dh[i] >= 0.0f; }
+template <int VEC>
+__device__ __forceinline__ bool head_b(const TileRows<VEC>& T, int i) { return T.id[i] != 0xFFFFFFFFu && T.dh[i + 1] >= 0.0f; }
+
+template <int VEC>
+__device__ __forceinline__ void load_injected(const ScanArgs& A, const TileRows<VEC>& T, int64_t col0, bool col_ok,
+                                              float (*v)[VEC])
 {
     constexpr int ITEMS = TileRows<VEC>::ITEMS;
-    f = seg_identity<VEC, STRICT>();
-    b = seg_identity<VEC, STRICT>();
 #pragma unroll
-    for (int i = 0; i < ITEMS; ++i) seg_push<VEC, STRICT>(f, T.live[i] && T.dh[i] >= 0.0f, T.dh[i], T.v[i]);
+    for (int i = 0; i < ITEMS; ++i) {
 #pragma unroll
-    for (int i = ITEMS - 1; i >= 0; --i) seg_push<VEC, STRICT>(b, T.live[i] && T.dh[i + 1] >= 0.0f, T.dh[i + 1], T.v[i]);
+        for (int e = 0; e < VEC; ++e) v[i][e] = 0.0f;
+        if (col_ok && T.id[i] >= A.inj_lo && T.id[i] < A.inj_hi)
+            load_vec<VEC>(v[i], A.inj + (int64_t)(T.id[i] - A.inj_lo) * A.ld_inj + col0);
+    }
 }
 
 // LDS exchange of per-wavefront summaries: [dir][wave] scalars and [dir][wave][column] vectors.
@@ -241,30 +256,81 @@ __device__ __forceinline__ Seg<VEC, STRICT> get_wave_seg(const WaveSegs<VEC>& W,
     return s;
 }
 
+// summary `idx` of direction `dir` at one level, for the VEC columns starting at col0
+template <int VEC, bool STRICT>
+__device__ __forceinline__ Seg<VEC, STRICT> load_level_seg(const Level& L, int dir, int64_t idx, int64_t bpad,
+                                                           int64_t col0, bool col_ok)
+{
+    Seg<VEC, STRICT> s = seg_identity<VEC, STRICT>();
+    const float4 sc = L.scalar[(int64_t)dir * L.count + idx];
+    s.D = sc.x;
+    if (STRICT) { s.C = sc.y; s.H = (int)sc.z; }
+    if (col_ok) {
+        const int64_t o = ((int64_t)dir * L.count + idx) * bpad + col0;
+        load_vec<VEC>(s.S, L.s + o);
+        if (STRICT) load_vec<VEC>(s.Q, L.q + o);
+    }
+    return s;
+}
+
+template <int VEC, bool STRICT>
+__device__ __forceinline__ void store_level_seg(const Level& L, int dir, int64_t idx, int64_t bpad, int64_t col0,
+                                                bool col_ok, bool scalar_writer, const Seg<VEC, STRICT>& s, float flags)
+{
+    if (scalar_writer) L.scalar[(int64_t)dir * L.count + idx] = make_float4(s.D, s.C, (float)s.H, flags);
+    if (col_ok) {
+        const int64_t o = ((int64_t)dir * L.count + idx) * bpad + col0;
+        store_vec<VEC>(L.s + o, s.S);
+        if (STRICT) store_vec<VEC>(L.q + o, s.Q);
+    }
+}
+
 // ---------------------------------------------------------------------------
-// reduce: forward and backward summary of every tile
+// reduce: forward and backward summary of every tile, and the tile's flags
 // ---------------------------------------------------------------------------
 template <int VEC, bool STRICT>
 __global__ void __launch_bounds__(kScanThreads)
 k_scan_reduce(const ScanArgs A)
 {
+    constexpr int ITEMS = TileRows<VEC>::ITEMS;
     __shared__ WaveSegs<VEC> W;
+    __shared__ int tile_flags;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int bv = A.bv, rv = A.rv;
     const int c = lane & (bv - 1), r = lane >> A.bv_log2;
     const int64_t tile = blockIdx.x;
-    const int64_t row0 = tile * A.tile_rows + (int64_t)(wave * rv + r) * TileRows<VEC>::ITEMS;
+    const int64_t row0 = tile * A.tile_rows + (int64_t)(wave * rv + r) * ITEMS;
     const int64_t col0 = ((int64_t)blockIdx.y * bv + c) * VEC;
     const bool col_ok = col0 < A.batch;
+    if (tid == 0) tile_flags = 0;
 
     TileRows<VEC> T;
-    load_rows<VEC>(A, row0, col0, col_ok, T);
-    Seg<VEC, STRICT> f, b;
-    local_segs<VEC, STRICT>(T, f, b);
-    f = wave_scan<true, VEC, STRICT>(f, lane, bv, rv);
-    b = wave_scan<false, VEC, STRICT>(b, lane, bv, rv);
-    if (r == rv - 1) put_wave_seg<VEC, STRICT>(W, 0, wave, c, f);
-    if (r == 0) put_wave_seg<VEC, STRICT>(W, 1, wave, c, b);
+    load_meta<VEC>(A, row0, T);
+    float v[ITEMS][VEC];
+    load_injected<VEC>(A, T, col0, col_ok, v);
+    int mine = 0;
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        if (T.id[i] >= A.inj_lo && T.id[i] < A.inj_hi) mine |= kFlagInj;
+        if (T.id[i] >= A.res_lo && T.id[i] < A.res_hi) mine |= kFlagRes;
+    }
+    __syncthreads();
+    if (c == 0 && mine) atomicOr(&tile_flags, mine);
+
+    {
+        Seg<VEC, STRICT> f = seg_identity<VEC, STRICT>();
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) seg_push<VEC, STRICT>(f, head_f<VEC>(T, i), T.dh[i], v[i]);
+        f = wave_scan<true, VEC, STRICT>(f, lane, bv, rv);
+        if (r == rv - 1) put_wave_seg<VEC, STRICT>(W, 0, wave, c, f);
+    }
+    {
+        Seg<VEC, STRICT> b = seg_identity<VEC, STRICT>();
+#pragma unroll
+        for (int i = ITEMS - 1; i >= 0; --i) seg_push<VEC, STRICT>(b, head_b<VEC>(T, i), T.dh[i + 1], v[i]);
+        b = wave_scan<false, VEC, STRICT>(b, lane, bv, rv);
+        if (r == 0) put_wave_seg<VEC, STRICT>(W, 1, wave, c, b);
+    }
     __syncthreads();
 
     if (tid < bv) {   // wavefront 0, row-lane 0: one lane per column group
@@ -273,27 +339,59 @@ k_scan_reduce(const ScanArgs A)
         for (int w = 0; w < kScanWaves; ++w) tf = seg_compose<VEC, STRICT>(tf, get_wave_seg<VEC, STRICT>(W, 0, w, c));
 #pragma unroll
         for (int w = kScanWaves - 1; w >= 0; --w) tb = seg_compose<VEC, STRICT>(tb, get_wave_seg<VEC, STRICT>(W, 1, w, c));
-        if (c == 0 && blockIdx.y == 0) {
-            A.agg_scalar[tile] = make_float4(tf.D, tf.C, (float)tf.H, 0.0f);
-            A.agg_scalar[A.tiles + tile] = make_float4(tb.D, tb.C, (float)tb.H, 0.0f);
-        }
-        if (col_ok) {
-            const int64_t o0 = tile * A.bpad + col0, o1 = (A.tiles + tile) * A.bpad + col0;
-            store_vec<VEC>(A.agg_s + o0, tf.S);
-            store_vec<VEC>(A.agg_s + o1, tb.S);
-            if (STRICT) { store_vec<VEC>(A.agg_q + o0, tf.Q); store_vec<VEC>(A.agg_q + o1, tb.Q); }
-        }
+        const bool sw = c == 0 && blockIdx.y == 0;
+        store_level_seg<VEC, STRICT>(A.l1, 0, tile, A.bpad, col0, col_ok, sw, tf, (float)tile_flags);
+        store_level_seg<VEC, STRICT>(A.l1, 1, tile, A.bpad, col0, col_ok, sw, tb, (float)tile_flags);
     }
 }
 
 // ---------------------------------------------------------------------------
-// spine: exclusive scan over the tile summaries, one workgroup per (column, direction).
-// Carries are the state a tile starts from when the sequence starts from zero:
-// F_in = S of everything before it, E_in = Q of everything before it (0 without a head).
+// spine, level 1 -> 2: summarise chunks of tile summaries (blockIdx.z = direction).
+// Index q counts tiles in scan order; tile = q forward, count-1-q backward.
+// ---------------------------------------------------------------------------
+template <int VEC, bool STRICT>
+__global__ void __launch_bounds__(kScanThreads)
+k_spine_reduce(const ScanArgs A)
+{
+    __shared__ WaveSegs<VEC> W;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int bv = A.bv, rv = A.rv;
+    const int c = lane & (bv - 1), r = lane >> A.bv_log2;
+    const int dir = blockIdx.z;
+    const int64_t chunk = blockIdx.x;
+    const int64_t q0 = chunk * A.chunk_tiles + (int64_t)(wave * rv + r) * kSpineItems;
+    const int64_t col0 = ((int64_t)blockIdx.y * bv + c) * VEC;
+    const bool col_ok = col0 < A.batch;
+
+    Seg<VEC, STRICT> m = seg_identity<VEC, STRICT>();
+#pragma unroll
+    for (int i = 0; i < kSpineItems; ++i) {
+        const int64_t q = q0 + i;
+        if (q < A.l1.count) {
+            const int64_t t = dir == 0 ? q : A.l1.count - 1 - q;
+            m = seg_compose<VEC, STRICT>(m, load_level_seg<VEC, STRICT>(A.l1, dir, t, A.bpad, col0, col_ok));
+        }
+    }
+    m = wave_scan<true, VEC, STRICT>(m, lane, bv, rv);
+    if (r == rv - 1) put_wave_seg<VEC, STRICT>(W, 0, wave, c, m);
+    __syncthreads();
+    if (tid < bv) {
+        Seg<VEC, STRICT> t = seg_identity<VEC, STRICT>();
+#pragma unroll
+        for (int w = 0; w < kScanWaves; ++w) t = seg_compose<VEC, STRICT>(t, get_wave_seg<VEC, STRICT>(W, 0, w, c));
+        store_level_seg<VEC, STRICT>(A.l2, dir, chunk, A.bpad, col0, col_ok, c == 0 && blockIdx.y == 0, t, 0.0f);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// spine, top: exclusive scan over the chunk summaries, one workgroup per
+// (column, direction).  Chunks are already numbered in scan order (chunk 0 of the
+// backward direction holds the last tiles).  Each entry receives the state the
+// sequence is in when it starts from zero: F_in = S, E_in = Q of all before it.
 // ---------------------------------------------------------------------------
 template <bool STRICT>
 __global__ void __launch_bounds__(kSpineThreads)
-k_scan_spine(const ScanArgs A)
+k_spine_top(const Level L, int64_t bpad)
 {
     constexpr int WAVES = kSpineThreads / 64;
     __shared__ float sD[WAVES], sC[WAVES], sS[WAVES], sQ[WAVES];
@@ -302,31 +400,18 @@ k_scan_spine(const ScanArgs A)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t col = blockIdx.x;
     const int dir = blockIdx.y;
-    const int64_t tiles = A.tiles;
-    const int64_t per = (tiles + kSpineThreads - 1) / kSpineThreads;
+    const int64_t count = L.count;
+    const int64_t per = (count + kSpineThreads - 1) / kSpineThreads;
     const int64_t q0 = (int64_t)tid * per;
-    const int64_t q1 = q0 + per < tiles ? q0 + per : tiles;
-    const float4* sc = A.agg_scalar + (int64_t)dir * tiles;
-    const float* as = A.agg_s + (int64_t)dir * tiles * A.bpad + col;
-    const float* aq = A.agg_q + (int64_t)dir * tiles * A.bpad + col;
-    float* cf = A.car_f + (int64_t)dir * tiles * A.bpad + col;
-    float* ce = A.car_e + (int64_t)dir * tiles * A.bpad + col;
+    const int64_t q1 = q0 + per < count ? q0 + per : count;
 
-    auto tile_seg = [&](int64_t q) {
-        const int64_t t = dir == 0 ? q : tiles - 1 - q;   // scan order -> tile index
-        S1 s;
-        const float4 v = sc[t];
-        s.D = v.x; s.C = v.y; s.H = STRICT ? (int)v.z : 0;
-        s.S[0] = as[t * A.bpad];
-        s.Q[0] = STRICT ? aq[t * A.bpad] : 0.0f;
-        return s;
-    };
+    auto entry = [&](int64_t q) { return q; };
 
     S1 mine = seg_identity<1, STRICT>();
-    for (int64_t q = q0; q < q1; ++q) mine = seg_compose<1, STRICT>(mine, tile_seg(q));
+    for (int64_t q = q0; q < q1; ++q)
+        mine = seg_compose<1, STRICT>(mine, load_level_seg<1, STRICT>(L, dir, entry(q), bpad, col, true));
 
-    // inclusive scan over the workgroup's threads
-    S1 inc = wave_scan<true, 1, STRICT>(mine, lane, 1, 64);
+    const S1 inc = wave_scan<true, 1, STRICT>(mine, lane, 1, 64);
     if (lane == 63) { sD[wave] = inc.D; sC[wave] = inc.C; sH[wave] = inc.H; sS[wave] = inc.S[0]; sQ[wave] = inc.Q[0]; }
     __syncthreads();
     S1 run = seg_identity<1, STRICT>();
@@ -334,19 +419,90 @@ k_scan_spine(const ScanArgs A)
         S1 o; o.D = sD[w]; o.C = sC[w]; o.H = sH[w]; o.S[0] = sS[w]; o.Q[0] = sQ[w];
         run = seg_compose<1, STRICT>(run, o);
     }
-    S1 prev = seg_shfl<1, STRICT>(inc, (lane - 1) & 63);
+    const S1 prev = seg_shfl<1, STRICT>(inc, (lane - 1) & 63);
     if (lane > 0) run = seg_compose<1, STRICT>(run, prev);
 
     for (int64_t q = q0; q < q1; ++q) {
-        const int64_t t = dir == 0 ? q : tiles - 1 - q;
-        cf[t * A.bpad] = run.S[0];
-        if (STRICT) ce[t * A.bpad] = run.H ? run.Q[0] : 0.0f;
-        run = seg_compose<1, STRICT>(run, tile_seg(q));
+        const int64_t o = ((int64_t)dir * count + entry(q)) * bpad + col;
+        L.car_f[o] = run.S[0];
+        if (STRICT) L.car_e[o] = run.H ? run.Q[0] : 0.0f;
+        run = seg_compose<1, STRICT>(run, load_level_seg<1, STRICT>(L, dir, entry(q), bpad, col, true));
     }
 }
 
 // ---------------------------------------------------------------------------
-// downsweep: walk every tile that holds result rows, forward then backward
+// spine, level 2 -> 1: push the chunk carries down to the tiles of each chunk
+// ---------------------------------------------------------------------------
+template <int VEC, bool STRICT>
+__global__ void __launch_bounds__(kScanThreads)
+k_spine_down(const ScanArgs A)
+{
+    __shared__ WaveSegs<VEC> W;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int bv = A.bv, rv = A.rv;
+    const int c = lane & (bv - 1), r = lane >> A.bv_log2;
+    const int dir = blockIdx.z;
+    const int64_t chunk = blockIdx.x;
+    const int64_t q0 = chunk * A.chunk_tiles + (int64_t)(wave * rv + r) * kSpineItems;
+    const int64_t col0 = ((int64_t)blockIdx.y * bv + c) * VEC;
+    const bool col_ok = col0 < A.batch;
+
+    Seg<VEC, STRICT> segs[kSpineItems];
+    Seg<VEC, STRICT> m = seg_identity<VEC, STRICT>();
+#pragma unroll
+    for (int i = 0; i < kSpineItems; ++i) {
+        const int64_t q = q0 + i;
+        segs[i] = seg_identity<VEC, STRICT>();
+        if (q < A.l1.count) {
+            const int64_t t = dir == 0 ? q : A.l1.count - 1 - q;
+            segs[i] = load_level_seg<VEC, STRICT>(A.l1, dir, t, A.bpad, col0, col_ok);
+        }
+        m = seg_compose<VEC, STRICT>(m, segs[i]);
+    }
+    const Seg<VEC, STRICT> inc = wave_scan<true, VEC, STRICT>(m, lane, bv, rv);
+    if (r == rv - 1) put_wave_seg<VEC, STRICT>(W, 0, wave, c, inc);
+    Seg<VEC, STRICT> exc = seg_shfl<VEC, STRICT>(inc, (lane - bv) & 63);
+    if (r == 0) exc = seg_identity<VEC, STRICT>();
+    __syncthreads();
+
+    float F[VEC], E[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) { F[e] = 0.0f; E[e] = 0.0f; }
+    if (col_ok) {
+        const int64_t o = ((int64_t)dir * A.l2.count + chunk) * A.bpad + col0;
+        load_vec<VEC>(F, A.l2.car_f + o);
+        if (STRICT) load_vec<VEC>(E, A.l2.car_e + o);
+    }
+    for (int w = 0; w < wave; ++w) seg_apply<VEC, STRICT>(get_wave_seg<VEC, STRICT>(W, 0, w, c), F, E);
+    seg_apply<VEC, STRICT>(exc, F, E);
+#pragma unroll
+    for (int i = 0; i < kSpineItems; ++i) {
+        const int64_t q = q0 + i;
+        if (q < A.l1.count) {
+            const int64_t t = dir == 0 ? q : A.l1.count - 1 - q;
+            if (col_ok) {
+                const int64_t o = ((int64_t)dir * A.l1.count + t) * A.bpad + col0;
+                store_vec<VEC>(A.l1.car_f + o, F);
+                if (STRICT) store_vec<VEC>(A.l1.car_e + o, E);
+            }
+            seg_apply<VEC, STRICT>(segs[i], F, E);
+        }
+    }
+}
+
+// Row reduction over the batch: sum over the bv lanes of a row-lane, then write.
+__device__ __forceinline__ void emit_row_sum(const ScanArgs& A, float acc, int bv, int c, bool is_res, int64_t rr,
+                                             int64_t res_rows)
+{
+    for (int m = 1; m < bv; m <<= 1) acc += __shfl_xor(acc, m);
+    if (is_res && c == 0) {
+        if (A.slabs == 1) A.out_red[rr] = acc;
+        else A.red_partial[(int64_t)blockIdx.y * res_rows + rr] = acc;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// downsweep: tiles that hold both injected and result rows
 // ---------------------------------------------------------------------------
 template <int VEC, bool STRICT>
 __global__ void __launch_bounds__(kScanThreads)
@@ -354,27 +510,21 @@ k_scan_down(const ScanArgs A)
 {
     constexpr int ITEMS = TileRows<VEC>::ITEMS;
     __shared__ WaveSegs<VEC> W;
+    const int64_t tile = blockIdx.x;
+    const int flags = (int)A.l1.scalar[tile].w;
+    if ((flags & (kFlagInj | kFlagRes)) != (kFlagInj | kFlagRes)) return;
+
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int bv = A.bv, rv = A.rv;
     const int c = lane & (bv - 1), r = lane >> A.bv_log2;
-    const int64_t tile = blockIdx.x;
     const int64_t row0 = tile * A.tile_rows + (int64_t)(wave * rv + r) * ITEMS;
     const int64_t col0 = ((int64_t)blockIdx.y * bv + c) * VEC;
     const bool col_ok = col0 < A.batch;
 
-    // Does this tile hold any result row?  (ids are cheap next to the data rows.)
-    {
-        int any = 0;
-#pragma unroll
-        for (int i = 0; i < ITEMS; ++i) {
-            const int64_t j = row0 + i;
-            if (j < A.N) { const uint32_t id = A.ids[j]; any |= (id >= A.res_lo && id < A.res_hi); }
-        }
-        if (!__syncthreads_or(any)) return;
-    }
-
     TileRows<VEC> T;
-    load_rows<VEC>(A, row0, col0, col_ok, T);
+    load_meta<VEC>(A, row0, T);
+    float v[ITEMS][VEC];
+    load_injected<VEC>(A, T, col0, col_ok, v);
 
     // weights of the row reduction, fetched early so the loads overlap the scans
     float wv[ITEMS][VEC];
@@ -387,29 +537,36 @@ k_scan_down(const ScanArgs A)
             load_vec<VEC>(wv[i], A.w + (int64_t)(T.id[i] - A.res_lo) * A.ld_w + col0);
     }
 
-    Seg<VEC, STRICT> f, b;
-    local_segs<VEC, STRICT>(T, f, b);
-    const Seg<VEC, STRICT> fi = wave_scan<true, VEC, STRICT>(f, lane, bv, rv);
-    const Seg<VEC, STRICT> bi = wave_scan<false, VEC, STRICT>(b, lane, bv, rv);
-    if (r == rv - 1) put_wave_seg<VEC, STRICT>(W, 0, wave, c, fi);
-    if (r == 0) put_wave_seg<VEC, STRICT>(W, 1, wave, c, bi);
-    // exclusive summaries inside the wavefront
-    Seg<VEC, STRICT> fe = seg_shfl<VEC, STRICT>(fi, (lane - bv) & 63);
-    Seg<VEC, STRICT> be = seg_shfl<VEC, STRICT>(bi, (lane + bv) & 63);
-    if (r == 0) fe = seg_identity<VEC, STRICT>();
-    if (r == rv - 1) be = seg_identity<VEC, STRICT>();
-    __syncthreads();
-
     // entering states: tile carry, then the wavefronts before this one, then the row-lanes before this one
     float F[VEC], E[VEC], R[VEC], G[VEC];
 #pragma unroll
     for (int e = 0; e < VEC; ++e) { F[e] = E[e] = R[e] = G[e] = 0.0f; }
     if (col_ok) {
-        const int64_t o0 = tile * A.bpad + col0, o1 = (A.tiles + tile) * A.bpad + col0;
-        load_vec<VEC>(F, A.car_f + o0);
-        load_vec<VEC>(R, A.car_f + o1);
-        if (STRICT) { load_vec<VEC>(E, A.car_e + o0); load_vec<VEC>(G, A.car_e + o1); }
+        const int64_t o0 = tile * A.bpad + col0, o1 = (A.l1.count + tile) * A.bpad + col0;
+        load_vec<VEC>(F, A.l1.car_f + o0);
+        load_vec<VEC>(R, A.l1.car_f + o1);
+        if (STRICT) { load_vec<VEC>(E, A.l1.car_e + o0); load_vec<VEC>(G, A.l1.car_e + o1); }
     }
+    Seg<VEC, STRICT> fe, be;
+    {
+        Seg<VEC, STRICT> f = seg_identity<VEC, STRICT>();
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) seg_push<VEC, STRICT>(f, head_f<VEC>(T, i), T.dh[i], v[i]);
+        f = wave_scan<true, VEC, STRICT>(f, lane, bv, rv);
+        if (r == rv - 1) put_wave_seg<VEC, STRICT>(W, 0, wave, c, f);
+        fe = seg_shfl<VEC, STRICT>(f, (lane - bv) & 63);
+        if (r == 0) fe = seg_identity<VEC, STRICT>();
+    }
+    {
+        Seg<VEC, STRICT> b = seg_identity<VEC, STRICT>();
+#pragma unroll
+        for (int i = ITEMS - 1; i >= 0; --i) seg_push<VEC, STRICT>(b, head_b<VEC>(T, i), T.dh[i + 1], v[i]);
+        b = wave_scan<false, VEC, STRICT>(b, lane, bv, rv);
+        if (r == 0) put_wave_seg<VEC, STRICT>(W, 1, wave, c, b);
+        be = seg_shfl<VEC, STRICT>(b, (lane + bv) & 63);
+        if (r == rv - 1) be = seg_identity<VEC, STRICT>();
+    }
+    __syncthreads();
     for (int w = 0; w < wave; ++w) seg_apply<VEC, STRICT>(get_wave_seg<VEC, STRICT>(W, 0, w, c), F, E);
     for (int w = kScanWaves - 1; w > wave; --w) seg_apply<VEC, STRICT>(get_wave_seg<VEC, STRICT>(W, 1, w, c), R, G);
     seg_apply<VEC, STRICT>(fe, F, E);
@@ -419,11 +576,11 @@ k_scan_down(const ScanArgs A)
     float Ff[ITEMS][VEC], Ef[ITEMS][VEC];
 #pragma unroll
     for (int i = 0; i < ITEMS; ++i) {
-        const bool h = T.live[i] && T.dh[i] >= 0.0f;
+        const bool h = head_f<VEC>(T, i);
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
-            if (h) { E[e] = T.dh[i] * F[e]; F[e] = E[e] + T.v[i][e]; }
-            else   { F[e] = F[e] + T.v[i][e]; }
+            if (h) { E[e] = T.dh[i] * F[e]; F[e] = E[e] + v[i][e]; }
+            else   { F[e] = F[e] + v[i][e]; }
             Ff[i][e] = F[e];
             Ef[i][e] = E[e];
         }
@@ -433,13 +590,13 @@ k_scan_down(const ScanArgs A)
     const int64_t res_rows = (int64_t)A.res_hi - (int64_t)A.res_lo;
 #pragma unroll
     for (int i = ITEMS - 1; i >= 0; --i) {
-        const bool h = T.live[i] && T.dh[i + 1] >= 0.0f;
+        const bool h = head_b<VEC>(T, i);
         float P[VEC], Z[VEC];
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
-            if (h) { G[e] = T.dh[i + 1] * R[e]; R[e] = G[e] + T.v[i][e]; }
-            else   { R[e] = R[e] + T.v[i][e]; }
-            P[e] = Ff[i][e] + R[e] - T.v[i][e];
+            if (h) { G[e] = T.dh[i + 1] * R[e]; R[e] = G[e] + v[i][e]; }
+            else   { R[e] = R[e] + v[i][e]; }
+            P[e] = Ff[i][e] + R[e] - v[i][e];
             Z[e] = G[e] - Ef[i][e];
         }
         const bool is_res = T.id[i] >= A.res_lo && T.id[i] < A.res_hi;
@@ -456,13 +613,132 @@ k_scan_down(const ScanArgs A)
                 for (int e = 0; e < VEC; ++e) zsv[e] = 0.0f;
                 if (A.zs) load_vec<VEC>(zsv, A.zs + rr * A.batch + col0);
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) acc += wv[i][e] * Z[e] + T.v[i][e] * zsv[e];
+                for (int e = 0; e < VEC; ++e) acc += wv[i][e] * Z[e] + v[i][e] * zsv[e];
             }
-            for (int m = 1; m < bv; m <<= 1) acc += __shfl_xor(acc, m);
-            if (is_res && c == 0) {
-                if (A.slabs == 1) A.out_red[rr] = acc;
-                else A.red_partial[(int64_t)blockIdx.y * res_rows + rr] = acc;
+            emit_row_sum(A, acc, bv, c, is_res, rr, res_rows);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// downsweep_sparse: tiles with result rows and nothing injected.  With no
+// injection inside the tile every row is a closed form of the two carries:
+//   F_j = cf_j F_in,           cf_j = product of the decays from the tile start to j
+//   E_j = F_j if a run head lies at or before j inside the tile, else E_in
+// and symmetrically from the right.  Only per-row scalars are scanned; the batch
+// columns are streamed.
+// ---------------------------------------------------------------------------
+struct DecaySeg { float D; int H; };
+
+template <bool FWD>
+__device__ __forceinline__ DecaySeg wave_scan_decay(DecaySeg s, int lane, int bv, int rv)
+{
+    const int r = lane / bv;
+    for (int step = 1; step < rv; step <<= 1) {
+        const int src = (FWD ? lane - step * bv : lane + step * bv) & 63;
+        const float oD = __shfl(s.D, src);
+        const int oH = __shfl(s.H, src);
+        const bool has = FWD ? (r >= step) : (r + step < rv);
+        if (has) { s.D *= oD; s.H |= oH; }
+    }
+    return s;
+}
+
+template <int VEC, bool STRICT>
+__global__ void __launch_bounds__(kScanThreads)
+k_scan_down_sparse(const ScanArgs A)
+{
+    constexpr int ITEMS = TileRows<VEC>::ITEMS;
+    __shared__ float wD[2][kScanWaves];
+    __shared__ int wH[2][kScanWaves];
+    const int64_t tile = blockIdx.x;
+    const int flags = (int)A.l1.scalar[tile].w;
+    if ((flags & (kFlagInj | kFlagRes)) != kFlagRes) return;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int bv = A.bv, rv = A.rv;
+    const int c = lane & (bv - 1), r = lane >> A.bv_log2;
+    const int64_t row0 = tile * A.tile_rows + (int64_t)(wave * rv + r) * ITEMS;
+    const int64_t col0 = ((int64_t)blockIdx.y * bv + c) * VEC;
+    const bool col_ok = col0 < A.batch;
+
+    TileRows<VEC> T;
+    load_meta<VEC>(A, row0, T);
+    const bool want_red = STRICT && A.out_red != nullptr;
+    float wv[ITEMS][VEC];
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) wv[i][e] = 0.0f;
+        if (want_red && col_ok && T.id[i] >= A.res_lo && T.id[i] < A.res_hi)
+            load_vec<VEC>(wv[i], A.w + (int64_t)(T.id[i] - A.res_lo) * A.ld_w + col0);
+    }
+    float Fin[VEC], Ein[VEC], Rin[VEC], Gin[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) { Fin[e] = Ein[e] = Rin[e] = Gin[e] = 0.0f; }
+    if (col_ok) {
+        const int64_t o0 = tile * A.bpad + col0, o1 = (A.l1.count + tile) * A.bpad + col0;
+        load_vec<VEC>(Fin, A.l1.car_f + o0);
+        load_vec<VEC>(Rin, A.l1.car_f + o1);
+        if (STRICT) { load_vec<VEC>(Ein, A.l1.car_e + o0); load_vec<VEC>(Gin, A.l1.car_e + o1); }
+    }
+
+    // per-row cumulative decays inside this row-lane, from the left and from the right
+    float cf[ITEMS], cb[ITEMS];
+    int hf = 0, hb = 0;               // bit i: a run head at or before (after) row i inside the row-lane
+    {
+        float p = 1.0f; int seen = 0;
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            if (head_f<VEC>(T, i)) { p *= T.dh[i]; seen = 1; }
+            cf[i] = p; hf |= seen << i;
+        }
+        p = 1.0f; seen = 0;
+#pragma unroll
+        for (int i = ITEMS - 1; i >= 0; --i) {
+            if (head_b<VEC>(T, i)) { p *= T.dh[i + 1]; seen = 1; }
+            cb[i] = p; hb |= seen << i;
+        }
+    }
+    DecaySeg fi = wave_scan_decay<true>(DecaySeg{cf[ITEMS - 1], (hf >> (ITEMS - 1)) & 1}, lane, bv, rv);
+    DecaySeg bi = wave_scan_decay<false>(DecaySeg{cb[0], hb & 1}, lane, bv, rv);
+    if (lane == 63) { wD[0][wave] = fi.D; wH[0][wave] = fi.H; }
+    if (lane == 0) { wD[1][wave] = bi.D; wH[1][wave] = bi.H; }
+    DecaySeg fe{__shfl(fi.D, (lane - bv) & 63), __shfl(fi.H, (lane - bv) & 63)};
+    DecaySeg be{__shfl(bi.D, (lane + bv) & 63), __shfl(bi.H, (lane + bv) & 63)};
+    if (r == 0) fe = DecaySeg{1.0f, 0};
+    if (r == rv - 1) be = DecaySeg{1.0f, 0};
+    __syncthreads();
+    float Df = 1.0f, Db = 1.0f; int Hf = 0, Hb = 0;      // everything in the tile before / after this row-lane
+    for (int w = 0; w < wave; ++w) { Df *= wD[0][w]; Hf |= wH[0][w]; }
+    for (int w = kScanWaves - 1; w > wave; --w) { Db *= wD[1][w]; Hb |= wH[1][w]; }
+    Df *= fe.D; Hf |= fe.H; Db *= be.D; Hb |= be.H;
+
+    const int64_t res_rows = (int64_t)A.res_hi - (int64_t)A.res_lo;
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        const bool is_res = T.id[i] >= A.res_lo && T.id[i] < A.res_hi;
+        const int64_t rr = (int64_t)T.id[i] - (int64_t)A.res_lo;
+        const float kf = Df * cf[i], kb = Db * cb[i];
+        const bool seen_f = Hf | ((hf >> i) & 1), seen_b = Hb | ((hb >> i) & 1);
+        float P[VEC], Z[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            const float Fj = kf * Fin[e], Rj = kb * Rin[e];
+            P[e] = Fj + Rj;
+            Z[e] = (seen_b ? Rj : Gin[e]) - (seen_f ? Fj : Ein[e]);
+        }
+        if (is_res && col_ok) {
+            if (A.out_p) store_vec<VEC>(A.out_p + rr * A.ld_p + col0, P);
+            if (STRICT && A.out_z) store_vec<VEC>(A.out_z + rr * A.batch + col0, Z);
+        }
+        if (want_red) {
+            float acc = 0.0f;
+            if (is_res && col_ok) {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) acc += wv[i][e] * Z[e];
             }
+            emit_row_sum(A, acc, bv, c, is_res, rr, res_rows);
         }
     }
 }
@@ -499,6 +775,23 @@ int ilog2(int v) { int l = 0; while ((1 << l) < v) ++l; return l; }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+template <int VEC, bool STRICT>
+void launch_all(const ScanArgs& A, const ScanGeom& g, const std::string& tag, hipStream_t st)
+{
+    const dim3 block(kScanThreads);
+    const dim3 grid((unsigned)g.tiles, (unsigned)g.slabs);
+    const dim3 cgrid((unsigned)g.chunks, (unsigned)g.slabs, 2);
+    const dim3 tgrid((unsigned)A.batch, 2);
+    const std::string fr = "scan_reduce." + tag, fs = "scan_spine." + tag, fd = "scan_down." + tag,
+                      fp = "scan_down_sparse." + tag;
+    LAPLEX_TIMED(fr.c_str(), st, hipLaunchKernelGGL((k_scan_reduce<VEC, STRICT>), grid, block, 0, st, A));
+    LAPLEX_TIMED(fs.c_str(), st, hipLaunchKernelGGL((k_spine_reduce<VEC, STRICT>), cgrid, block, 0, st, A));
+    LAPLEX_TIMED(fs.c_str(), st, hipLaunchKernelGGL((k_spine_top<STRICT>), tgrid, dim3(kSpineThreads), 0, st, A.l2, A.bpad));
+    LAPLEX_TIMED(fs.c_str(), st, hipLaunchKernelGGL((k_spine_down<VEC, STRICT>), cgrid, block, 0, st, A));
+    LAPLEX_TIMED(fd.c_str(), st, hipLaunchKernelGGL((k_scan_down<VEC, STRICT>), grid, block, 0, st, A));
+    LAPLEX_TIMED(fp.c_str(), st, hipLaunchKernelGGL((k_scan_down_sparse<VEC, STRICT>), grid, block, 0, st, A));
+}
+
 }  // namespace
 
 hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStream_t st)
@@ -518,28 +811,20 @@ hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStrea
     A.res_lo = p.res_lo; A.res_hi = p.res_hi;
     A.out_p = p.out_p; A.ld_p = p.ld_p; A.out_z = p.out_z;
     A.out_red = p.out_red; A.w = p.w; A.ld_w = p.ld_w; A.zs = p.zs;
-    A.batch = p.batch; A.bpad = L.bpad; A.tiles = g.tiles;
+    A.batch = p.batch; A.bpad = L.bpad;
     A.bv = g.bv; A.bv_log2 = ilog2(g.bv); A.rv = g.rv; A.tile_rows = g.tile_rows; A.slabs = g.slabs;
-    A.agg_scalar = reinterpret_cast<float4*>(ws + L.off_agg_scalar);
-    A.agg_s = reinterpret_cast<float*>(ws + L.off_agg_s);
-    A.agg_q = reinterpret_cast<float*>(ws + L.off_agg_q);
-    A.car_f = reinterpret_cast<float*>(ws + L.off_car_f);
-    A.car_e = reinterpret_cast<float*>(ws + L.off_car_e);
+    A.chunk_tiles = g.chunk_tiles;
+    A.l1 = Level{reinterpret_cast<float4*>(ws + L.off_agg_scalar), reinterpret_cast<float*>(ws + L.off_agg_s),
+                 reinterpret_cast<float*>(ws + L.off_agg_q), reinterpret_cast<float*>(ws + L.off_car_f),
+                 reinterpret_cast<float*>(ws + L.off_car_e), g.tiles};
+    A.l2 = Level{reinterpret_cast<float4*>(ws + L.off_agg2_scalar), reinterpret_cast<float*>(ws + L.off_agg2_s),
+                 reinterpret_cast<float*>(ws + L.off_agg2_q), reinterpret_cast<float*>(ws + L.off_car2_f),
+                 reinterpret_cast<float*>(ws + L.off_car2_e), g.chunks};
     A.red_partial = reinterpret_cast<float*>(ws + L.off_red);
 
     const std::string tag = p.tag ? p.tag : "scan";
-    const std::string fam_r = "scan_reduce." + tag, fam_s = "scan_spine." + tag, fam_d = "scan_down." + tag;
-    const dim3 grid((unsigned)g.tiles, (unsigned)g.slabs), block(kScanThreads);
-    const dim3 sgrid((unsigned)p.batch, 2), sblock(kSpineThreads);
-#define LAPLEX_LAUNCH3(V, S)                                                                    \
-    do {                                                                                        \
-        LAPLEX_TIMED(fam_r.c_str(), st, hipLaunchKernelGGL((k_scan_reduce<V, S>), grid, block, 0, st, A)); \
-        LAPLEX_TIMED(fam_s.c_str(), st, hipLaunchKernelGGL((k_scan_spine<S>), sgrid, sblock, 0, st, A));    \
-        LAPLEX_TIMED(fam_d.c_str(), st, hipLaunchKernelGGL((k_scan_down<V, S>), grid, block, 0, st, A));     \
-    } while (0)
-    if (v4) { if (strict) LAPLEX_LAUNCH3(4, true); else LAPLEX_LAUNCH3(4, false); }
-    else    { if (strict) LAPLEX_LAUNCH3(1, true); else LAPLEX_LAUNCH3(1, false); }
-#undef LAPLEX_LAUNCH3
+    if (v4) { if (strict) launch_all<4, true>(A, g, tag, st); else launch_all<4, false>(A, g, tag, st); }
+    else    { if (strict) launch_all<1, true>(A, g, tag, st); else launch_all<1, false>(A, g, tag, st); }
     if (p.out_red && g.slabs > 1) {
         const int64_t rows = (int64_t)p.res_hi - (int64_t)p.res_lo;
         int64_t gsz = (rows + 255) / 256; if (gsz > 65536) gsz = 65536; if (gsz < 1) gsz = 1;
