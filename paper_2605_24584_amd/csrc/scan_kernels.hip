@@ -86,11 +86,11 @@ template <int VEC, bool STRICT>
 __device__ __forceinline__ void seg_push(Seg<VEC, STRICT>& s, bool h, float d, const float* v)
 {
     const float dd = h ? d : 1.0f;
-    if (STRICT && h) {
-        s.C = dd * s.D;
-        s.H = 1;
+    if (STRICT) {               // selects, not branches: h differs between row-lanes
+        s.C = h ? dd * s.D : s.C;
+        s.H |= h ? 1 : 0;
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) s.Q[e] = dd * s.S[e];
+        for (int e = 0; e < VEC; ++e) s.Q[e] = h ? dd * s.S[e] : s.Q[e];
     }
 #pragma unroll
     for (int e = 0; e < VEC; ++e) s.S[e] = dd * s.S[e] + v[e];
@@ -138,7 +138,7 @@ __device__ __forceinline__ void seg_apply(const Seg<VEC, STRICT>& s, float* F, f
 {
 #pragma unroll
     for (int e = 0; e < VEC; ++e) {
-        if (STRICT && s.H) E[e] = s.C * F[e] + s.Q[e];
+        if (STRICT) E[e] = s.H ? s.C * F[e] + s.Q[e] : E[e];
         F[e] = s.D * F[e] + s.S[e];
     }
 }
@@ -177,6 +177,17 @@ __device__ __forceinline__ void store_vec(float* dst, const float* src)
     else dst[0] = src[0];
 }
 
+// dst <- ok ? base[off .. off+VEC) : 0, without a branch: a row that is not wanted
+// reads the first columns of row 0 (always valid, always cached) and is discarded.
+template <int VEC>
+__device__ __forceinline__ void load_vec_or_zero(float* dst, const float* base, int64_t off, bool ok)
+{
+    float t[VEC];
+    load_vec<VEC>(t, base + (ok ? off : 0));
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) dst[e] = ok ? t[e] : 0.0f;
+}
+
 template <int VEC>
 struct TileRows {
     static constexpr int ITEMS = VEC == 4 ? kItemsVec4 : kItemsVec1;
@@ -188,15 +199,18 @@ template <int VEC>
 __device__ __forceinline__ void load_meta(const ScanArgs& A, int64_t row0, TileRows<VEC>& T)
 {
     constexpr int ITEMS = TileRows<VEC>::ITEMS;
+    // clamped indices and selects: no branch around any load
 #pragma unroll
     for (int i = 0; i <= ITEMS; ++i) {
         const int64_t j = row0 + i;
-        T.dh[i] = j <= A.N ? A.dh[j] : -1.0f;
+        const float d = A.dh[j <= A.N ? j : A.N];
+        T.dh[i] = j <= A.N ? d : -1.0f;
     }
 #pragma unroll
     for (int i = 0; i < ITEMS; ++i) {
         const int64_t j = row0 + i;
-        T.id[i] = j < A.N ? A.ids[j] : 0xFFFFFFFFu;
+        const uint32_t id = A.ids[j < A.N ? j : A.N - 1];
+        T.id[i] = j < A.N ? id : 0xFFFFFFFFu;
     }
 }
 
@@ -214,10 +228,28 @@ __device__ __forceinline__ void load_injected(const ScanArgs& A, const TileRows<
     constexpr int ITEMS = TileRows<VEC>::ITEMS;
 #pragma unroll
     for (int i = 0; i < ITEMS; ++i) {
+        const bool ok = col_ok && T.id[i] >= A.inj_lo && T.id[i] < A.inj_hi;
+        load_vec_or_zero<VEC>(v[i], A.inj, (int64_t)(T.id[i] - A.inj_lo) * A.ld_inj + col0, ok);
+    }
+}
+
+// weights of the row reduction at the result rows (zero elsewhere, or when no reduction is wanted)
+template <int VEC>
+__device__ __forceinline__ void load_weights(const ScanArgs& A, const TileRows<VEC>& T, int64_t col0, bool col_ok,
+                                             bool want, float (*wv)[VEC])
+{
+    constexpr int ITEMS = TileRows<VEC>::ITEMS;
+    if (want) {     // uniform
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) v[i][e] = 0.0f;
-        if (col_ok && T.id[i] >= A.inj_lo && T.id[i] < A.inj_hi)
-            load_vec<VEC>(v[i], A.inj + (int64_t)(T.id[i] - A.inj_lo) * A.ld_inj + col0);
+        for (int i = 0; i < ITEMS; ++i) {
+            const bool ok = col_ok && T.id[i] >= A.res_lo && T.id[i] < A.res_hi;
+            load_vec_or_zero<VEC>(wv[i], A.w, (int64_t)(T.id[i] - A.res_lo) * A.ld_w + col0, ok);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) wv[i][e] = 0.0f;
     }
 }
 
@@ -306,16 +338,24 @@ k_scan_reduce(const ScanArgs A)
 
     TileRows<VEC> T;
     load_meta<VEC>(A, row0, T);
-    float v[ITEMS][VEC];
-    load_injected<VEC>(A, T, col0, col_ok, v);
     int mine = 0;
 #pragma unroll
     for (int i = 0; i < ITEMS; ++i) {
-        if (T.id[i] >= A.inj_lo && T.id[i] < A.inj_hi) mine |= kFlagInj;
-        if (T.id[i] >= A.res_lo && T.id[i] < A.res_hi) mine |= kFlagRes;
+        mine |= (T.id[i] >= A.inj_lo && T.id[i] < A.inj_hi) ? kFlagInj : 0;
+        mine |= (T.id[i] >= A.res_lo && T.id[i] < A.res_hi) ? kFlagRes : 0;
     }
     __syncthreads();
     if (c == 0 && mine) atomicOr(&tile_flags, mine);
+    __syncthreads();
+    float v[ITEMS][VEC];
+    if (tile_flags & kFlagInj) {     // uniform: a tile with nothing injected reads no data rows
+        load_injected<VEC>(A, T, col0, col_ok, v);
+    } else {
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) v[i][e] = 0.0f;
+    }
 
     {
         Seg<VEC, STRICT> f = seg_identity<VEC, STRICT>();
@@ -335,9 +375,9 @@ k_scan_reduce(const ScanArgs A)
 
     if (tid < bv) {   // wavefront 0, row-lane 0: one lane per column group
         Seg<VEC, STRICT> tf = seg_identity<VEC, STRICT>(), tb = seg_identity<VEC, STRICT>();
-#pragma unroll
+#pragma unroll 1   // sequential on purpose: unrolling would hold every wavefront's summary in registers at once
         for (int w = 0; w < kScanWaves; ++w) tf = seg_compose<VEC, STRICT>(tf, get_wave_seg<VEC, STRICT>(W, 0, w, c));
-#pragma unroll
+#pragma unroll 1
         for (int w = kScanWaves - 1; w >= 0; --w) tb = seg_compose<VEC, STRICT>(tb, get_wave_seg<VEC, STRICT>(W, 1, w, c));
         const bool sw = c == 0 && blockIdx.y == 0;
         store_level_seg<VEC, STRICT>(A.l1, 0, tile, A.bpad, col0, col_ok, sw, tf, (float)tile_flags);
@@ -377,7 +417,7 @@ k_spine_reduce(const ScanArgs A)
     __syncthreads();
     if (tid < bv) {
         Seg<VEC, STRICT> t = seg_identity<VEC, STRICT>();
-#pragma unroll
+#pragma unroll 1
         for (int w = 0; w < kScanWaves; ++w) t = seg_compose<VEC, STRICT>(t, get_wave_seg<VEC, STRICT>(W, 0, w, c));
         store_level_seg<VEC, STRICT>(A.l2, dir, chunk, A.bpad, col0, col_ok, c == 0 && blockIdx.y == 0, t, 0.0f);
     }
@@ -473,6 +513,7 @@ k_spine_down(const ScanArgs A)
         load_vec<VEC>(F, A.l2.car_f + o);
         if (STRICT) load_vec<VEC>(E, A.l2.car_e + o);
     }
+#pragma unroll 1
     for (int w = 0; w < wave; ++w) seg_apply<VEC, STRICT>(get_wave_seg<VEC, STRICT>(W, 0, w, c), F, E);
     seg_apply<VEC, STRICT>(exc, F, E);
 #pragma unroll
@@ -529,13 +570,7 @@ k_scan_down(const ScanArgs A)
     // weights of the row reduction, fetched early so the loads overlap the scans
     float wv[ITEMS][VEC];
     const bool want_red = STRICT && A.out_red != nullptr;
-#pragma unroll
-    for (int i = 0; i < ITEMS; ++i) {
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) wv[i][e] = 0.0f;
-        if (want_red && col_ok && T.id[i] >= A.res_lo && T.id[i] < A.res_hi)
-            load_vec<VEC>(wv[i], A.w + (int64_t)(T.id[i] - A.res_lo) * A.ld_w + col0);
-    }
+    load_weights<VEC>(A, T, col0, col_ok, want_red, wv);
 
     // entering states: tile carry, then the wavefronts before this one, then the row-lanes before this one
     float F[VEC], E[VEC], R[VEC], G[VEC];
@@ -567,7 +602,9 @@ k_scan_down(const ScanArgs A)
         if (r == rv - 1) be = seg_identity<VEC, STRICT>();
     }
     __syncthreads();
+#pragma unroll 1
     for (int w = 0; w < wave; ++w) seg_apply<VEC, STRICT>(get_wave_seg<VEC, STRICT>(W, 0, w, c), F, E);
+#pragma unroll 1
     for (int w = kScanWaves - 1; w > wave; --w) seg_apply<VEC, STRICT>(get_wave_seg<VEC, STRICT>(W, 1, w, c), R, G);
     seg_apply<VEC, STRICT>(fe, F, E);
     seg_apply<VEC, STRICT>(be, R, G);
@@ -579,8 +616,8 @@ k_scan_down(const ScanArgs A)
         const bool h = head_f<VEC>(T, i);
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
-            if (h) { E[e] = T.dh[i] * F[e]; F[e] = E[e] + v[i][e]; }
-            else   { F[e] = F[e] + v[i][e]; }
+            E[e] = h ? T.dh[i] * F[e] : E[e];
+            F[e] = (h ? E[e] : F[e]) + v[i][e];
             Ff[i][e] = F[e];
             Ef[i][e] = E[e];
         }
@@ -594,8 +631,8 @@ k_scan_down(const ScanArgs A)
         float P[VEC], Z[VEC];
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
-            if (h) { G[e] = T.dh[i + 1] * R[e]; R[e] = G[e] + v[i][e]; }
-            else   { R[e] = R[e] + v[i][e]; }
+            G[e] = h ? T.dh[i + 1] * R[e] : G[e];
+            R[e] = (h ? G[e] : R[e]) + v[i][e];
             P[e] = Ff[i][e] + R[e] - v[i][e];
             Z[e] = G[e] - Ef[i][e];
         }
@@ -607,14 +644,12 @@ k_scan_down(const ScanArgs A)
         }
         if (want_red) {
             float acc = 0.0f;
-            if (is_res && col_ok) {
-                float zsv[VEC];
+            float zsv[VEC];
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) zsv[e] = 0.0f;
-                if (A.zs) load_vec<VEC>(zsv, A.zs + rr * A.batch + col0);
+            for (int e = 0; e < VEC; ++e) zsv[e] = 0.0f;
+            if (A.zs) load_vec_or_zero<VEC>(zsv, A.zs, rr * A.batch + col0, is_res && col_ok);   // uniform branch
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) acc += wv[i][e] * Z[e] + v[i][e] * zsv[e];
-            }
+            for (int e = 0; e < VEC; ++e) acc += wv[i][e] * Z[e] + v[i][e] * zsv[e];     // wv, zsv are 0 off the result rows
             emit_row_sum(A, acc, bv, c, is_res, rr, res_rows);
         }
     }
@@ -666,13 +701,7 @@ k_scan_down_sparse(const ScanArgs A)
     load_meta<VEC>(A, row0, T);
     const bool want_red = STRICT && A.out_red != nullptr;
     float wv[ITEMS][VEC];
-#pragma unroll
-    for (int i = 0; i < ITEMS; ++i) {
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) wv[i][e] = 0.0f;
-        if (want_red && col_ok && T.id[i] >= A.res_lo && T.id[i] < A.res_hi)
-            load_vec<VEC>(wv[i], A.w + (int64_t)(T.id[i] - A.res_lo) * A.ld_w + col0);
-    }
+    load_weights<VEC>(A, T, col0, col_ok, want_red, wv);
     float Fin[VEC], Ein[VEC], Rin[VEC], Gin[VEC];
 #pragma unroll
     for (int e = 0; e < VEC; ++e) { Fin[e] = Ein[e] = Rin[e] = Gin[e] = 0.0f; }
@@ -690,13 +719,15 @@ k_scan_down_sparse(const ScanArgs A)
         float p = 1.0f; int seen = 0;
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) {
-            if (head_f<VEC>(T, i)) { p *= T.dh[i]; seen = 1; }
+            const bool h = head_f<VEC>(T, i);
+            p *= h ? T.dh[i] : 1.0f; seen |= h ? 1 : 0;
             cf[i] = p; hf |= seen << i;
         }
         p = 1.0f; seen = 0;
 #pragma unroll
         for (int i = ITEMS - 1; i >= 0; --i) {
-            if (head_b<VEC>(T, i)) { p *= T.dh[i + 1]; seen = 1; }
+            const bool h = head_b<VEC>(T, i);
+            p *= h ? T.dh[i + 1] : 1.0f; seen |= h ? 1 : 0;
             cb[i] = p; hb |= seen << i;
         }
     }
@@ -734,10 +765,8 @@ k_scan_down_sparse(const ScanArgs A)
         }
         if (want_red) {
             float acc = 0.0f;
-            if (is_res && col_ok) {
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) acc += wv[i][e] * Z[e];
-            }
+            for (int e = 0; e < VEC; ++e) acc += wv[i][e] * Z[e];      // wv is 0 off the result rows
             emit_row_sum(A, acc, bv, c, is_res, rr, res_rows);
         }
     }
