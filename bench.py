@@ -8,8 +8,8 @@ on the neural-projection workload (n = 2^20 inputs, k = 1024 outputs, batch 256,
 fp32), inputs resident in HBM before the timed region.
 
 Prints ONE JSON line: throughput in (n + k) * batch elements per second, the
-roofline of the dominant kernel (backward downsweep, timed with HIP events on
-its own stream during the timed steps) and the CPU oracle timed beside it on a
+roofline of the dominant kernel (the sparse backward downsweep, timed with HIP
+events on its own stream during the timed steps) and the CPU oracle timed beside it on a
 bounded sample of the same workload.
 """
 import argparse
@@ -23,7 +23,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-DOMINANT = "scan_down.bwd"
+DOMINANT = "scan_down_sparse.bwd"
 
 
 def parse():
@@ -38,12 +38,26 @@ def parse():
     return ap.parse_args()
 
 
-def dominant_kernel_bytes(k, n, batch):
-    """Algorithmic bytes of one backward-downsweep launch: sorted ids and decays
-    (8 B per merged position), x read and gx written once each, gy read once,
-    gb written."""
-    N = k + n
-    return 8 * N + 4 * batch * n * 2 + 4 * batch * k + 4 * n
+def dominant_kernel_bytes(a, b, batch, tile_rows):
+    """Algorithmic bytes of one launch of the dominant kernel, the sparse backward
+    downsweep.  It visits the tiles of the sorted merged sequence that hold no
+    output anchor (the other tiles go to the generic downsweep); per visited row:
+    sorted id and decay (8 B), the x row read and the gx row written (4 B per
+    batch column each), gb written (4 B); per visited tile: the four carry rows
+    (forward/backward, inclusive/strict) read (16 B per batch column).
+    Returns (bytes, visited rows, visited tiles, all tiles)."""
+    import numpy as np
+    k = a.size
+    order = np.argsort(np.concatenate([a, b]), kind="stable")
+    N = order.size
+    tiles = (N + tile_rows - 1) // tile_rows
+    has_output = np.zeros(tiles, dtype=bool)
+    has_output[np.nonzero(order < k)[0] // tile_rows] = True
+    rows_per_tile = np.full(tiles, tile_rows, dtype=np.int64)
+    rows_per_tile[-1] = N - (tiles - 1) * tile_rows
+    rows = int(rows_per_tile[~has_output].sum())
+    visited = int((~has_output).sum())
+    return rows * (8 + 8 * batch + 4) + visited * 16 * batch, rows, visited, int(tiles)
 
 
 def main():
@@ -97,15 +111,17 @@ def main():
     value = elements / (ms_per_step * 1e-3)
 
     dom_avg_ms = dom_ms / max(dom_launches, 1)
-    dom_bytes = dominant_kernel_bytes(k, n, batch)
+    tile_rows = B.laplex_scan_tile_rows(batch, batch % 4 == 0)
+    dom_bytes, dom_rows, dom_tiles, all_tiles = dominant_kernel_bytes(a, b, batch, tile_rows)
     achieved = dom_bytes / (dom_avg_ms * 1e-3) / 1e9 if dom_launches else 0.0
     roofline = {
-        "bound": "hbm", "kernel": "k_scan_down<4,true> (backward downsweep)",
+        "bound": "hbm", "kernel": "k_scan_down_sparse<4,true> (backward downsweep of the tiles without output anchors)",
         "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
         "avg_kernel_ms": round(dom_avg_ms, 5), "launches": dom_launches, "algorithmic_bytes": dom_bytes,
+        "rows_visited": dom_rows, "tiles_visited": dom_tiles, "tiles": all_tiles,
     }
-    traffic_file = os.path.join(ROOT, "profiles", "traffic_scan_down_bwd_projection.json")
+    traffic_file = os.path.join(ROOT, "profiles", "traffic_scan_down_sparse_bwd_projection.json")
     if args.scale == 1 and args.batch == 256 and os.path.exists(traffic_file):
         with open(traffic_file) as fh:
             roofline["traffic"] = json.load(fh).get("hbm_bytes_per_launch")

@@ -31,7 +31,7 @@ LAPLEX_MAX_MERGED = 4294967294
 EXPORTS = (
     "laplex_workspace_bytes", "laplex_apply", "laplex_apply_backward", "laplex_gram",
     "laplex_gram_backward", "laplex_get_perm", "laplex_status_string", "laplex_last_hip_error",
-    "laplex_profile_begin", "laplex_profile_end",
+    "laplex_profile_begin", "laplex_profile_end", "laplex_scan_tile_rows",
 )
 
 _lib = None
@@ -68,6 +68,7 @@ def lib() -> ctypes.CDLL:
         L.laplex_last_hip_error.restype = ctypes.c_char_p
         L.laplex_profile_begin.argtypes = [ctypes.c_char_p]
         L.laplex_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+        L.laplex_scan_tile_rows.argtypes = [_I, ctypes.c_int, ctypes.POINTER(_I)]
         for name in EXPORTS[:6] + EXPORTS[8:]:
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -159,3 +160,9 @@ def laplex_profile_end():
     ms, cnt = ctypes.c_double(0.0), ctypes.c_int64(0)
     _check(lib().laplex_profile_end(ctypes.byref(ms), ctypes.byref(cnt)))
     return ms.value, cnt.value
+
+
+def laplex_scan_tile_rows(batch: int, wide: bool) -> int:
+    rows = _I(0)
+    _check(lib().laplex_scan_tile_rows(batch, 1 if wide else 0, ctypes.byref(rows)))
+    return rows.value

@@ -339,6 +339,14 @@ const char* laplex_status_string(int status)
 
 const char* laplex_last_hip_error(void) { return g_hip_error.c_str(); }
 
+int laplex_scan_tile_rows(int64_t batch, int wide, int64_t* rows)
+{
+    if (!rows) return LAPLEX_ERR_NULL;
+    if (batch < 1 || (wide && batch % 4 != 0)) return LAPLEX_ERR_SIZE;
+    *rows = scan_geom(1, batch, wide ? 4 : 1).tile_rows;
+    return LAPLEX_OK;
+}
+
 int laplex_profile_begin(const char* family)
 {
     if (!family) return LAPLEX_ERR_NULL;

@@ -1,0 +1,205 @@
+"""Parity at the full sizes of the five workloads, in the launch configuration the
+benchmark times.  Where the oracle cannot produce every output in seconds, it
+produces sampled ones (brute force restricted to a window of 64 around the
+sampled anchors: what is dropped is below exp(-64) * sum|x|), and the
+permutation is checked through properties that pin it uniquely: it is a
+permutation, keys ascend along it, and equal keys keep ascending ids.
+
+The 2^30 workload needs ~76 GiB of HBM and 16 GiB of host arrays and takes about
+half a minute on the GPU machine; LAPLEX_SMALL_BILLION=1 shrinks it to n = k = 2^27.
+"""
+import os
+import sys
+import time
+
+import numpy as np
+import pytest
+
+from paper_2605_24584_amd import binding as B
+from paper_2605_24584_amd import synth
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+RTOL, ATOL = 1e-5, 1e-7
+
+
+def log(msg):
+    print(f"[full-size {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+
+def dev(v):
+    return torch.from_numpy(np.ascontiguousarray(v)).cuda()
+
+
+def worst_ratio(got, ref, tol):
+    got = np.asarray(got, dtype=np.float64).reshape(ref.shape)
+    assert np.all(np.isfinite(got))
+    return float((np.abs(got - ref) / (RTOL * tol + ATOL)).max())
+
+
+def check_permutation_properties(perm_i32, merged_dev):
+    """perm: int32 device tensor holding u32 ids; merged_dev: fp32 anchors a ++ b."""
+    N = merged_dev.numel()
+    ids = perm_i32.to(torch.int64) & 0xFFFFFFFF
+    assert int(ids.min()) == 0 and int(ids.max()) == N - 1
+    seen = torch.zeros(N, dtype=torch.bool, device="cuda")
+    seen[ids] = True
+    assert bool(seen.all()), "not a permutation"
+    del seen
+    m = merged_dev[ids]
+    step_ok = (m[1:] > m[:-1]) | ((m[1:] == m[:-1]) & (ids[1:] > ids[:-1]))
+    assert bool(step_ok.all()), "keys do not ascend, or equal keys lost their order"
+
+
+def window_samples(a, b, centers, core=4.0, halo=64.0):
+    """For each centre c: outputs with a in [c, c+core), inputs with b in the halo
+    around that range, and the converse (inputs in the core, outputs in the halo)."""
+    out = []
+    for c in centers:
+        a_core = np.nonzero((a >= c) & (a < c + core))[0]
+        b_halo = np.nonzero((b >= c - halo) & (b < c + core + halo))[0]
+        b_core = np.nonzero((b >= c) & (b < c + core))[0]
+        a_halo = np.nonzero((a >= c - halo) & (a < c + core + halo))[0]
+        out.append((a_core, b_halo, b_core, a_halo))
+    return out
+
+
+def check_windows(oracle, a, b, x, g, y, gx, ga, gb, centers, core=4.0):
+    worst = {"y": 0.0, "gx": 0.0, "ga": 0.0, "gb": 0.0}
+    checked = 0
+    for a_core, b_halo, b_core, a_halo in window_samples(a, b, centers, core=core):
+        if a_core.size and b_halo.size:
+            ref, tol = oracle.apply_brute(a[a_core], b[b_halo], x[b_halo])
+            worst["y"] = max(worst["y"], worst_ratio(y[a_core], ref, tol))
+            if ga is not None:
+                (_, rga, _), (_, tga, _) = oracle.apply_backward_brute(a[a_core], b[b_halo], x[b_halo], g[a_core])
+                worst["ga"] = max(worst["ga"], worst_ratio(ga[a_core], rga, tga))
+            checked += a_core.size
+        if gx is not None and b_core.size and a_halo.size:
+            (rgx, _, rgb), (tgx, _, tgb) = oracle.apply_backward_brute(a[a_halo], b[b_core], x[b_core], g[a_halo])
+            worst["gx"] = max(worst["gx"], worst_ratio(gx[b_core], rgx, tgx))
+            worst["gb"] = max(worst["gb"], worst_ratio(gb[b_core], rgb, tgb))
+            checked += b_core.size
+    return worst, checked
+
+
+# ------------------------------------------------------------------ projection layer, the benchmark's workload
+
+def test_projection_full_size_sampled(oracle):
+    w = synth.projection_layer()
+    a, b, x, g = w["a"], w["b"], w["x"], w["g"]
+    k, n, batch = a.size, b.size, x.shape[1]
+    ws = torch.empty(B.laplex_workspace_bytes(k, n, batch), dtype=torch.uint8, device="cuda")
+    da, db, dx, dg = dev(a), dev(b), dev(x), dev(g)
+    y = torch.empty(k, batch, device="cuda"); gx = torch.empty(n, batch, device="cuda")
+    ga = torch.empty(k, device="cuda"); gb = torch.empty(n, device="cuda")
+    B.laplex_apply(da, db, dx, y, ws, B.LAPLEX_SAVE_SCANS)
+    B.laplex_apply_backward(da, db, dx, dg, gx, ga, gb, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
+    perm = torch.empty(k + n, dtype=torch.int32, device="cuda")
+    B.laplex_get_perm(ws, k + n, perm)
+    torch.cuda.synchronize()
+    assert np.array_equal(perm.cpu().numpy().view(np.uint32), oracle.merged_permutation(a, b))
+    y, gx, ga, gb = y.cpu().numpy(), gx.cpu().numpy(), ga.cpu().numpy(), gb.cpu().numpy()
+    # every output of 16 sampled batch columns through the dual-theorem route ...
+    cols = np.arange(0, batch, 16)
+    ref, tol = oracle.apply_scan(a, b, x[:, cols])
+    r_y = worst_ratio(y[:, cols], ref, tol)
+    # ... and sampled rows through windows (all batch columns; ga and gb sum over the batch)
+    centers = [0.0, 1017.25, 4100.5, 8191.0, 12000.75, 16384.0 - 256.0]
+    worst, checked = check_windows(oracle, a, b, x, g, y, gx, ga, gb, centers, core=256.0)
+    log(f"projection full: y ratio {r_y:.3g} (16 columns, all outputs); windows {worst} over {checked} rows")
+    assert r_y <= 1.0 and max(worst.values()) <= 1.0 and checked > 1000
+
+
+# ------------------------------------------------------------------ tie-heavy square apply, n = k = 2^24
+
+def test_tie_heavy_full_size(oracle):
+    w = synth.tie_heavy()
+    a, b, x, g = w["a"], w["b"], w["x"], w["g"]
+    k, n = a.size, b.size
+    ws = torch.empty(B.laplex_workspace_bytes(k, n, 1), dtype=torch.uint8, device="cuda")
+    da, db, dx, dg = dev(a), dev(b), dev(x), dev(g)
+    y = torch.empty(k, 1, device="cuda"); gx = torch.empty(n, 1, device="cuda")
+    ga = torch.empty(k, device="cuda"); gb = torch.empty(n, device="cuda")
+    B.laplex_apply(da, db, dx, y, ws, B.LAPLEX_SAVE_SCANS)
+    B.laplex_apply_backward(da, db, dx, dg, gx, ga, gb, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
+    perm = torch.empty(k + n, dtype=torch.int32, device="cuda")
+    B.laplex_get_perm(ws, k + n, perm)
+    torch.cuda.synchronize()
+    assert np.array_equal(perm.cpu().numpy().view(np.uint32), oracle.merged_permutation(a, b))   # bit-exact
+    ref, tol = oracle.apply_scan(a, b, x)
+    r_y = worst_ratio(y.cpu().numpy(), ref, tol)
+    (rgx, rga, rgb), (tgx, tga, tgb) = oracle.apply_backward_scan(a, b, x, g)
+    r = (r_y, worst_ratio(gx.cpu().numpy(), rgx, tgx), worst_ratio(ga.cpu().numpy(), rga, tga),
+         worst_ratio(gb.cpu().numpy(), rgb, tgb))
+    log(f"tie-heavy 2^24: worst ratios y, gx, ga, gb = {r}")
+    assert max(r) <= 1.0
+
+
+# ------------------------------------------------------------------ Gram form on n = 3 * 2^20, batch 64
+
+def test_gram_images_full_size(oracle):
+    w = synth.gram_images()
+    a, x, g = w["a"], w["x"], w["g"]
+    n, batch = a.size, x.shape[1]
+    ws = torch.empty(B.laplex_workspace_bytes(0, n, batch), dtype=torch.uint8, device="cuda")
+    da, dx, dg = dev(a), dev(x), dev(g)
+    y = torch.empty(n, batch, device="cuda"); gx = torch.empty(n, batch, device="cuda"); ga = torch.empty(n, device="cuda")
+    B.laplex_gram(da, dx, y, ws, B.LAPLEX_SAVE_SCANS)
+    B.laplex_gram_backward(da, dx, dg, gx, ga, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
+    perm = torch.empty(n, dtype=torch.int32, device="cuda")
+    B.laplex_get_perm(ws, n, perm)
+    torch.cuda.synchronize()
+    assert np.array_equal(perm.cpu().numpy().view(np.uint32), oracle.merged_permutation(a))
+    cols = np.arange(0, batch, 8)        # 8 of the 64 columns, every row, for y and gx
+    ref, tol = oracle.gram_scan(a, x[:, cols])
+    r_y = worst_ratio(y.cpu().numpy()[:, cols], ref, tol)
+    refg, tolg = oracle.gram_scan(a, g[:, cols])
+    r_gx = worst_ratio(gx.cpu().numpy()[:, cols], refg, tolg)
+    (_, rga), (_, tga) = oracle.gram_backward_scan(a, x, g)      # ga sums over all 64 columns
+    r_ga = worst_ratio(ga.cpu().numpy(), rga, tga)
+    dup = n - np.unique(a).size
+    log(f"gram 3*2^20 x 64: worst ratios y, gx, ga = {(r_y, r_gx, r_ga)}; {dup} duplicated anchors")
+    assert max(r_y, r_gx, r_ga) <= 1.0
+
+
+# ------------------------------------------------------------------ billion-scale square apply
+
+def test_billion_scale(oracle):
+    full = os.environ.get("LAPLEX_SMALL_BILLION") != "1"
+    scale = 1 if full else 8
+    log(f"billion workload at n = k = 2^{30 - (0 if full else 3)}: generating inputs")
+    w = synth.billion_square(scale=scale)
+    a, b, x, g = w["a"], w["b"], w["x"], w["g"]
+    k, n = a.size, b.size
+    ws_bytes = B.laplex_workspace_bytes(k, n, 1)
+    log(f"workspace {ws_bytes / 2**30:.1f} GiB; uploading")
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    da, db, dx, dg = dev(a), dev(b), dev(x), dev(g)
+    y = torch.empty(k, 1, device="cuda"); gx = torch.empty(n, 1, device="cuda")
+    ga = torch.empty(k, device="cuda"); gb = torch.empty(n, device="cuda")
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    B.laplex_apply(da, db, dx, y, ws, B.LAPLEX_SAVE_SCANS)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    B.laplex_apply_backward(da, db, dx, dg, gx, ga, gb, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    peak = torch.cuda.max_memory_allocated()
+    log(f"forward {1e3 * (t1 - t0):.1f} ms (sort included), backward {1e3 * (t2 - t1):.1f} ms, "
+        f"device footprint {peak / 2**30:.1f} GiB")
+    perm = torch.empty(k + n, dtype=torch.int32, device="cuda")
+    B.laplex_get_perm(ws, k + n, perm)
+    torch.cuda.synchronize()
+    del ws
+    check_permutation_properties(perm, torch.cat([da, db]))
+    log("permutation properties hold")
+    y, gx, ga, gb = y.cpu().numpy(), gx.cpu().numpy(), ga.cpu().numpy(), gb.cpu().numpy()
+    hi = float(1 << 24) / scale
+    # windows at both ends, in the dense-fraction region and where fp32 spacing is 0.5 / 1.0 (many exact ties)
+    centers = [0.0, 3.5, hi / 1024, hi / 16 + 0.25, hi / 4, hi / 2 + 1.0, 0.75 * hi, hi - 70.0, hi - 4.0]
+    worst, checked = check_windows(oracle, a, b, x, g, y, gx, ga, gb, centers)
+    log(f"billion workload: window ratios {worst} over {checked} rows")
+    assert max(worst.values()) <= 1.0 and checked > 2000
