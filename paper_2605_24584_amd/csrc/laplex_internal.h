@@ -93,6 +93,7 @@ struct Layout {
     size_t off_car_f = 0;        // f32[2][tiles][bpad]         carry F
     size_t off_car_e = 0;        // f32[2][tiles][bpad]         carry E
     size_t off_red = 0;          // f32[slabs][N]               per-slab partial row reductions
+    size_t off_lists = 0;        // u32[2][tiles] tile lists + u32[64] counters (sparse problems)
     // second level of the spine: the same five arrays over chunks of tiles
     size_t off_agg2_scalar = 0, off_agg2_s = 0, off_agg2_q = 0, off_car2_f = 0, off_car2_e = 0;
     int64_t max_tiles = 0, max_chunks = 0;
@@ -134,6 +135,7 @@ inline Layout make_layout(int64_t N, int64_t zrows, int64_t batch)
     L.off_car_e = c;      c = align_up(c + per);
     L.off_red = c;
     if (max_slabs > 1) c = align_up(c + sizeof(float) * (size_t)max_slabs * (size_t)N);
+    L.off_lists = c; c = align_up(c + sizeof(uint32_t) * (2 * (size_t)L.max_tiles + 64));
     L.max_chunks = g1.chunks > g4.chunks ? g1.chunks : g4.chunks;
     const size_t per2 = sizeof(float) * 2 * (size_t)L.max_chunks * (size_t)L.bpad;
     L.off_agg2_scalar = c; c = align_up(c + sizeof(float) * 4 * 2 * (size_t)L.max_chunks);

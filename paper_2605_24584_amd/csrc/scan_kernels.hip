@@ -58,6 +58,12 @@ struct ScanArgs {
     int bv, bv_log2, rv, tile_rows, slabs, chunk_tiles;
     Level l1, l2;
     float* red_partial;   // [slabs][res rows] when slabs > 1
+    // sparse problems (few injected or few result rows): the metadata kernel lists the tiles that need
+    // the heavy kernels, which then launch one workgroup per list entry instead of one per tile
+    uint32_t* list_inj;   // tiles that hold injected rows
+    uint32_t* list_both;  // tiles that hold injected and result rows
+    uint32_t* counters;   // [0] = entries of list_inj, [1] = entries of list_both
+    int reduce_from_list, down_from_list;
 };
 
 constexpr int kFlagInj = 1, kFlagRes = 2;
@@ -289,7 +295,7 @@ __device__ __forceinline__ Seg<VEC, STRICT> get_wave_seg(const WaveSegs<VEC>& W,
 }
 
 // summary `idx` of direction `dir` at one level, for the VEC columns starting at col0
-template <int VEC, bool STRICT>
+template <int VEC, bool STRICT, bool FLAGGED>
 __device__ __forceinline__ Seg<VEC, STRICT> load_level_seg(const Level& L, int dir, int64_t idx, int64_t bpad,
                                                            int64_t col0, bool col_ok)
 {
@@ -301,6 +307,11 @@ __device__ __forceinline__ Seg<VEC, STRICT> load_level_seg(const Level& L, int d
         const int64_t o = ((int64_t)dir * L.count + idx) * bpad + col0;
         load_vec<VEC>(s.S, L.s + o);
         if (STRICT) load_vec<VEC>(s.Q, L.q + o);
+    }
+    if (FLAGGED) {   // level 1: a tile with nothing injected has S = Q = 0; its rows may never have been written
+        const bool inj = ((int)sc.w & kFlagInj) != 0;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) { s.S[e] = inj ? s.S[e] : 0.0f; s.Q[e] = inj ? s.Q[e] : 0.0f; }
     }
     return s;
 }
@@ -318,6 +329,54 @@ __device__ __forceinline__ void store_level_seg(const Level& L, int dir, int64_t
 }
 
 // ---------------------------------------------------------------------------
+// metadata pass for sparse problems: one wavefront per tile, one lane per row
+// (coalesced).  Writes, for every tile, its flags and the summary it has if
+// nothing is injected in it (S = Q = 0, C = D: only the decays and the run heads
+// matter), and lists the tiles the heavy kernels must visit.  Tiles that do hold
+// injected rows get their summary overwritten by k_scan_reduce.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+k_scan_meta(const ScanArgs A)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t tile = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (tile >= A.l1.count) return;
+    float Df = 1.0f, Db = 1.0f;
+    int Hf = 0, Hb = 0, fl = 0;
+    const int64_t base = tile * A.tile_rows;
+    for (int o = 0; o < A.tile_rows; o += 64) {
+        const int64_t j = base + o + lane;
+        const bool live = j < A.N;
+        const int64_t jc = live ? j : A.N - 1;
+        const uint32_t id = A.ids[jc];
+        const float df = A.dh[jc], db = A.dh[jc + 1];
+        const bool hf = live && df >= 0.0f, hb = live && db >= 0.0f;
+        Df *= hf ? df : 1.0f; Db *= hb ? db : 1.0f;
+        Hf |= hf ? 1 : 0; Hb |= hb ? 1 : 0;
+        fl |= (live && id >= A.inj_lo && id < A.inj_hi) ? kFlagInj : 0;
+        fl |= (live && id >= A.res_lo && id < A.res_hi) ? kFlagRes : 0;
+    }
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) {
+        Df *= __shfl_xor(Df, m); Db *= __shfl_xor(Db, m);
+        Hf |= __shfl_xor(Hf, m); Hb |= __shfl_xor(Hb, m); fl |= __shfl_xor(fl, m);
+    }
+    if (lane == 0) {
+        A.l1.scalar[tile] = make_float4(Df, Df, (float)Hf, (float)fl);
+        A.l1.scalar[A.l1.count + tile] = make_float4(Db, Db, (float)Hb, (float)fl);
+        // a list is built only when its kernel will be driven by it (then it is short by construction)
+        if (A.reduce_from_list && (fl & kFlagInj)) A.list_inj[atomicAdd(&A.counters[0], 1u)] = (uint32_t)tile;
+        if (A.down_from_list && (fl & (kFlagInj | kFlagRes)) == (kFlagInj | kFlagRes))
+            A.list_both[atomicAdd(&A.counters[1], 1u)] = (uint32_t)tile;
+    }
+}
+
+__global__ void k_zero_counters(uint32_t* counters)
+{
+    if (threadIdx.x < 64) counters[threadIdx.x] = 0u;
+}
+
+// ---------------------------------------------------------------------------
 // reduce: forward and backward summary of every tile, and the tile's flags
 // ---------------------------------------------------------------------------
 template <int VEC, bool STRICT>
@@ -330,7 +389,8 @@ k_scan_reduce(const ScanArgs A)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int bv = A.bv, rv = A.rv;
     const int c = lane & (bv - 1), r = lane >> A.bv_log2;
-    const int64_t tile = blockIdx.x;
+    if (A.reduce_from_list && blockIdx.x >= A.counters[0]) return;
+    const int64_t tile = A.reduce_from_list ? A.list_inj[blockIdx.x] : blockIdx.x;
     const int64_t row0 = tile * A.tile_rows + (int64_t)(wave * rv + r) * ITEMS;
     const int64_t col0 = ((int64_t)blockIdx.y * bv + c) * VEC;
     const bool col_ok = col0 < A.batch;
@@ -409,7 +469,7 @@ k_spine_reduce(const ScanArgs A)
         const int64_t q = q0 + i;
         if (q < A.l1.count) {
             const int64_t t = dir == 0 ? q : A.l1.count - 1 - q;
-            m = seg_compose<VEC, STRICT>(m, load_level_seg<VEC, STRICT>(A.l1, dir, t, A.bpad, col0, col_ok));
+            m = seg_compose<VEC, STRICT>(m, load_level_seg<VEC, STRICT, true>(A.l1, dir, t, A.bpad, col0, col_ok));
         }
     }
     m = wave_scan<true, VEC, STRICT>(m, lane, bv, rv);
@@ -449,7 +509,7 @@ k_spine_top(const Level L, int64_t bpad)
 
     S1 mine = seg_identity<1, STRICT>();
     for (int64_t q = q0; q < q1; ++q)
-        mine = seg_compose<1, STRICT>(mine, load_level_seg<1, STRICT>(L, dir, entry(q), bpad, col, true));
+        mine = seg_compose<1, STRICT>(mine, load_level_seg<1, STRICT, false>(L, dir, entry(q), bpad, col, true));
 
     const S1 inc = wave_scan<true, 1, STRICT>(mine, lane, 1, 64);
     if (lane == 63) { sD[wave] = inc.D; sC[wave] = inc.C; sH[wave] = inc.H; sS[wave] = inc.S[0]; sQ[wave] = inc.Q[0]; }
@@ -466,7 +526,7 @@ k_spine_top(const Level L, int64_t bpad)
         const int64_t o = ((int64_t)dir * count + entry(q)) * bpad + col;
         L.car_f[o] = run.S[0];
         if (STRICT) L.car_e[o] = run.H ? run.Q[0] : 0.0f;
-        run = seg_compose<1, STRICT>(run, load_level_seg<1, STRICT>(L, dir, entry(q), bpad, col, true));
+        run = seg_compose<1, STRICT>(run, load_level_seg<1, STRICT, false>(L, dir, entry(q), bpad, col, true));
     }
 }
 
@@ -495,7 +555,7 @@ k_spine_down(const ScanArgs A)
         segs[i] = seg_identity<VEC, STRICT>();
         if (q < A.l1.count) {
             const int64_t t = dir == 0 ? q : A.l1.count - 1 - q;
-            segs[i] = load_level_seg<VEC, STRICT>(A.l1, dir, t, A.bpad, col0, col_ok);
+            segs[i] = load_level_seg<VEC, STRICT, true>(A.l1, dir, t, A.bpad, col0, col_ok);
         }
         m = seg_compose<VEC, STRICT>(m, segs[i]);
     }
@@ -551,7 +611,8 @@ k_scan_down(const ScanArgs A)
 {
     constexpr int ITEMS = TileRows<VEC>::ITEMS;
     __shared__ WaveSegs<VEC> W;
-    const int64_t tile = blockIdx.x;
+    if (A.down_from_list && blockIdx.x >= A.counters[1]) return;
+    const int64_t tile = A.down_from_list ? A.list_both[blockIdx.x] : blockIdx.x;
     const int flags = (int)A.l1.scalar[tile].w;
     if ((flags & (kFlagInj | kFlagRes)) != (kFlagInj | kFlagRes)) return;
 
@@ -800,6 +861,19 @@ k_rowdot(const float* __restrict__ u, int64_t ldu, const float* __restrict__ v, 
     }
 }
 
+// the same for a narrow batch: one thread per row
+__global__ void __launch_bounds__(256)
+k_rowdot_narrow(const float* __restrict__ u, int64_t ldu, const float* __restrict__ v, int64_t ldv,
+                int64_t rows, int64_t batch, float* __restrict__ out)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < rows; r += stride) {
+        float s = 0.0f;
+        for (int64_t t = 0; t < batch; ++t) s += u[r * ldu + t] * v[r * ldv + t];
+        out[r] = s;
+    }
+}
+
 int ilog2(int v) { int l = 0; while ((1 << l) < v) ++l; return l; }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -809,15 +883,27 @@ void launch_all(const ScanArgs& A, const ScanGeom& g, const std::string& tag, hi
 {
     const dim3 block(kScanThreads);
     const dim3 grid((unsigned)g.tiles, (unsigned)g.slabs);
+    // heavy kernels driven by the tile lists visit at most one tile per injected (and per result) row
+    const int64_t inj_rows = (int64_t)A.inj_hi - A.inj_lo, res_rows = (int64_t)A.res_hi - A.res_lo;
+    const int64_t rcap = inj_rows < g.tiles ? inj_rows : g.tiles;
+    const int64_t both_rows = inj_rows < res_rows ? inj_rows : res_rows;
+    const int64_t dcap = both_rows < g.tiles ? both_rows : g.tiles;
+    const dim3 rgrid((unsigned)(A.reduce_from_list ? rcap : g.tiles), (unsigned)g.slabs);
+    const dim3 dgrid((unsigned)(A.down_from_list ? dcap : g.tiles), (unsigned)g.slabs);
+    if (A.reduce_from_list || A.down_from_list) {
+        const std::string fm = "scan_meta." + tag;
+        LAPLEX_TIMED(fm.c_str(), st, hipLaunchKernelGGL(k_zero_counters, dim3(1), dim3(64), 0, st, A.counters));
+        LAPLEX_TIMED(fm.c_str(), st, hipLaunchKernelGGL(k_scan_meta, dim3((unsigned)((g.tiles + 3) / 4)), dim3(256), 0, st, A));
+    }
     const dim3 cgrid((unsigned)g.chunks, (unsigned)g.slabs, 2);
     const dim3 tgrid((unsigned)A.batch, 2);
     const std::string fr = "scan_reduce." + tag, fs = "scan_spine." + tag, fd = "scan_down." + tag,
                       fp = "scan_down_sparse." + tag;
-    LAPLEX_TIMED(fr.c_str(), st, hipLaunchKernelGGL((k_scan_reduce<VEC, STRICT>), grid, block, 0, st, A));
+    LAPLEX_TIMED(fr.c_str(), st, hipLaunchKernelGGL((k_scan_reduce<VEC, STRICT>), rgrid, block, 0, st, A));
     LAPLEX_TIMED(fs.c_str(), st, hipLaunchKernelGGL((k_spine_reduce<VEC, STRICT>), cgrid, block, 0, st, A));
     LAPLEX_TIMED(fs.c_str(), st, hipLaunchKernelGGL((k_spine_top<STRICT>), tgrid, dim3(kSpineThreads), 0, st, A.l2, A.bpad));
     LAPLEX_TIMED(fs.c_str(), st, hipLaunchKernelGGL((k_spine_down<VEC, STRICT>), cgrid, block, 0, st, A));
-    LAPLEX_TIMED(fd.c_str(), st, hipLaunchKernelGGL((k_scan_down<VEC, STRICT>), grid, block, 0, st, A));
+    LAPLEX_TIMED(fd.c_str(), st, hipLaunchKernelGGL((k_scan_down<VEC, STRICT>), dgrid, block, 0, st, A));
     LAPLEX_TIMED(fp.c_str(), st, hipLaunchKernelGGL((k_scan_down_sparse<VEC, STRICT>), grid, block, 0, st, A));
 }
 
@@ -850,6 +936,17 @@ hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStrea
                  reinterpret_cast<float*>(ws + L.off_agg2_q), reinterpret_cast<float*>(ws + L.off_car2_f),
                  reinterpret_cast<float*>(ws + L.off_car2_e), g.chunks};
     A.red_partial = reinterpret_cast<float*>(ws + L.off_red);
+    A.list_inj = reinterpret_cast<uint32_t*>(ws + L.off_lists);
+    A.list_both = A.list_inj + L.max_tiles;
+    A.counters = A.list_both + L.max_tiles;
+    {   // list-driven launches pay off when the rows that force a heavy tile are few next to the tiles
+        const int64_t inj_rows = (int64_t)p.inj_hi - p.inj_lo, res_rows = (int64_t)p.res_hi - p.res_lo;
+        const int64_t both = inj_rows < res_rows ? inj_rows : res_rows;
+        A.reduce_from_list = inj_rows * 4 <= g.tiles;
+        A.down_from_list = both * 4 <= g.tiles;
+        // (the metadata pass runs before the reduce; with a dense injection the reduce then visits every
+        //  tile and overwrites the provisional summaries, with a sparse one only the listed tiles)
+    }
 
     const std::string tag = p.tag ? p.tag : "scan";
     if (v4) { if (strict) launch_all<4, true>(A, g, tag, st); else launch_all<4, false>(A, g, tag, st); }
@@ -867,6 +964,11 @@ hipError_t launch_rowdot(const float* u, int64_t ldu, const float* v, int64_t ld
                          int64_t rows, int64_t batch, float* out, hipStream_t st)
 {
     if (rows <= 0) return hipSuccess;
+    if (batch <= 8) {
+        int64_t g = (rows + 255) / 256; if (g > 65536) g = 65536;
+        LAPLEX_TIMED("rowdot", st, hipLaunchKernelGGL(k_rowdot_narrow, dim3((unsigned)g), dim3(256), 0, st, u, ldu, v, ldv, rows, batch, out));
+        return hipGetLastError();
+    }
     int64_t gsz = (rows + 3) / 4; if (gsz > 65536) gsz = 65536;
     LAPLEX_TIMED("rowdot", st, hipLaunchKernelGGL(k_rowdot, dim3((unsigned)gsz), dim3(256), 0, st, u, ldu, v, ldv, rows, batch, out));
     return hipGetLastError();
