@@ -35,6 +35,8 @@ def parse():
     ap.add_argument("--batch", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-columns", type=int, default=256)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="instead of the benchmark: time a plain device copy of 1 GiB (counter calibration)")
     return ap.parse_args()
 
 
@@ -75,6 +77,21 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
     B.lib()   # fails loudly if the HIP library is not built
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(20):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / 20
+        print(json.dumps({"copy_bytes_read": 4 << 28, "copy_bytes_written": 4 << 28, "ms": dt * 1e3,
+                          "GBps_read_plus_write": 2 * (4 << 28) / dt / 1e9}), flush=True)
+        return
 
     w = synth.projection_layer(scale=args.scale, batch=args.batch)
     a, b, x, g = w["a"], w["b"], w["x"], w["g"]
