@@ -155,9 +155,9 @@ const char* laplex_last_hip_error(void);
 
 /*
  * Diagnostics for benchmarks (not part of the method).  Between begin and end,
- * every launch of the named kernel family ("make_keys", "radix_count",
- * "table_scan", "radix_scatter", "merge", "decay", "rowdot", "sum_slabs", "fill",
- * and "scan_reduce.T", "scan_spine.T", "scan_down.T" with T = "fwd" for the
+ * every launch of the named kernel family ("sort_hist", "radix_scatter", "merge",
+ * "decay", "rowdot", "sum_slabs", "fill", and "scan_meta.T", "scan_reduce.T",
+ * "scan_spine.T", "scan_down.T", "scan_down_sparse.T" with T = "fwd" for the
  * forward scans of x, "bwd" for the backward scans of gy, "rescan" for the
  * backward's repeat of the forward scans when they were not saved) is bracketed by a pair of HIP
  * events on the stream it is launched on.  laplex_profile_end waits for those

@@ -126,11 +126,10 @@ int build_plan(const float* a, int64_t k, const float* b, int64_t n, const Layou
     if (both_sorted) {
         LAPLEX_HIP(launch_merge(a, k, b, n, keys0, P.ids, st));
     } else {
-        LAPLEX_HIP(launch_make_keys(a, k, b, n, keys0, P.ids, st));
-        LAPLEX_HIP(launch_radix_sort(keys0, P.ids, reinterpret_cast<uint32_t*>(ws + L.off_keys1),
-                                     reinterpret_cast<uint32_t*>(ws + L.off_ids1),
-                                     reinterpret_cast<uint32_t*>(ws + L.off_table),
-                                     reinterpret_cast<uint32_t*>(ws + L.off_chunks), L.N, st));
+        LAPLEX_HIP(launch_onesweep_sort(a, k, b, n, keys0, P.ids, reinterpret_cast<uint32_t*>(ws + L.off_keys1),
+                                        reinterpret_cast<uint32_t*>(ws + L.off_ids1),
+                                        reinterpret_cast<uint32_t*>(ws + L.off_sort_small),
+                                        reinterpret_cast<unsigned long long*>(ws + L.off_status), st));
     }
     LAPLEX_HIP(launch_decay(keys0, P.dh, L.N, st));
     return LAPLEX_OK;

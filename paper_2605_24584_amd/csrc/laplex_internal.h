@@ -17,9 +17,6 @@ constexpr int kSortPasses = 4;
 constexpr int kSortThreads = 512;                       // 8 wavefronts
 constexpr int kSortKeysPerThread = 16;
 constexpr int kSortTile = kSortThreads * kSortKeysPerThread;  // 8192 keys per workgroup
-constexpr int kTableScanThreads = 256;
-constexpr int kTableScanPerThread = 16;
-constexpr int kTableScanChunk = kTableScanThreads * kTableScanPerThread;
 constexpr int kMergeThreads = 256;
 constexpr int kMergePerThread = 8;
 constexpr int kMergeTile = kMergeThreads * kMergePerThread;
@@ -84,8 +81,8 @@ struct Layout {
     size_t off_z = 0;        // f32[zrows][batch]
     size_t off_scratch = 0;
     // scratch, sort view
-    size_t off_keys0 = 0, off_keys1 = 0, off_ids1 = 0, off_table = 0, off_chunks = 0;
-    int64_t sort_tiles = 0, table_len = 0, table_chunks = 0;
+    size_t off_keys0 = 0, off_keys1 = 0, off_ids1 = 0, off_status = 0, off_sort_small = 0;
+    int64_t sort_tiles = 0, status_words = 0;
     // scratch, scan view (sized for the larger of the two lane geometries)
     size_t off_agg_scalar = 0;   // float4[2][tiles]            (D, C, H, -)
     size_t off_agg_s = 0;        // f32[2][tiles][bpad]         S
@@ -114,13 +111,12 @@ inline Layout make_layout(int64_t N, int64_t zrows, int64_t batch)
     // sort view
     size_t s = o;
     L.sort_tiles = (N + kSortTile - 1) / kSortTile;
-    L.table_len = L.sort_tiles * kRadix;
-    L.table_chunks = (L.table_len + kTableScanChunk - 1) / kTableScanChunk;
+    L.status_words = L.sort_tiles * kRadix;
     L.off_keys0 = s;  s = align_up(s + sizeof(uint32_t) * (size_t)N);
     L.off_keys1 = s;  s = align_up(s + sizeof(uint32_t) * (size_t)N);
     L.off_ids1 = s;   s = align_up(s + sizeof(uint32_t) * (size_t)N);
-    L.off_table = s;  s = align_up(s + sizeof(uint32_t) * (size_t)L.table_len);
-    L.off_chunks = s; s = align_up(s + sizeof(uint32_t) * (size_t)(L.table_chunks + 1));
+    L.off_status = s;     s = align_up(s + sizeof(uint64_t) * 2 * (size_t)L.status_words);   // look-back words, two passes' worth
+    L.off_sort_small = s; s = align_up(s + sizeof(uint32_t) * 1040);                       // global histogram, tickets, error
 
     // scan view
     size_t c = o;
@@ -165,13 +161,11 @@ void profile_after(const char* family, hipStream_t st);
 // Launchers (each returns the hipError_t of its launches; none synchronises).
 // ----------------------------------------------------------------------------
 
-// keys0/ids0 <- order-preserving keys of a (ids 0..k) followed by b (ids k..k+n).
-hipError_t launch_make_keys(const float* a, int64_t k, const float* b, int64_t n,
-                            uint32_t* keys, uint32_t* ids, hipStream_t st);
-
-// Stable ascending LSD radix sort of (keys0, ids0), N pairs; result back in keys0/ids0.
-hipError_t launch_radix_sort(uint32_t* keys0, uint32_t* ids0, uint32_t* keys1, uint32_t* ids1,
-                             uint32_t* table, uint32_t* chunks, int64_t N, hipStream_t st);
+// Stable ascending sort of the anchors a ++ b by one-sweep LSD passes; keys and ids end in keys0/ids0.
+// small: u32[1040] (global histogram, tickets, error word); status: u64[2][tiles*256] look-back words.
+hipError_t launch_onesweep_sort(const float* a, int64_t k, const float* b, int64_t n,
+                                uint32_t* keys0, uint32_t* ids0, uint32_t* keys1, uint32_t* ids1,
+                                uint32_t* small, unsigned long long* status, hipStream_t st);
 
 // Both inputs ascending: merged keys/ids in one pass (ties: a first).
 hipError_t launch_merge(const float* a, int64_t k, const float* b, int64_t n,

@@ -2,12 +2,15 @@
 // O(n log n)"; App. B "Combined complexity").  Hand-written for gfx950:
 // 64-wide wavefronts, ballot-based stable ranking, LDS-staged scatter.
 //
-//   make_keys   a ++ b  ->  order-preserving u32 keys + ids
-//   radix sort  4 LSD passes of 8 bits: per-tile digit counts, an exclusive scan
-//               of the digit-major count table, and a stable scatter
+//   radix sort  one-sweep LSD sort, 4 passes of 8 bits: one histogram kernel (key
+//               build fused: a ++ b -> order-preserving u32 keys, ids = positions),
+//               then per pass one read and one write of the pairs, tile offsets
+//               from a chained look-back over per-tile status words
 //   merge       one merge-path pass when both anchor sets arrive sorted
 //   decay       exp(-(p_j - p_{j-1})) between sorted neighbours, once per plan
 #include "laplex_internal.h"
+
+#include <type_traits>
 
 namespace laplex {
 
@@ -28,46 +31,7 @@ __device__ __forceinline__ float key_to_float(uint32_t key)
 __device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & 63); }
 
 // ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(256)
-k_make_keys(const float* __restrict__ a, int64_t k, const float* __restrict__ b, int64_t n,
-            uint32_t* __restrict__ keys, uint32_t* __restrict__ ids)
-{
-    const int64_t N = k + n;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < N; i += stride) {
-        const float f = i < k ? a[i] : b[i - k];
-        keys[i] = float_to_key(f);
-        ids[i] = (uint32_t)i;
-    }
-}
-
-// ---------------------------------------------------------------------------
-// Pass step 1: digit counts of one tile -> table[digit * tiles + tile].
-__global__ void __launch_bounds__(kSortThreads)
-k_radix_count(const uint32_t* __restrict__ keys, int64_t N, int shift,
-              uint32_t* __restrict__ table, int64_t tiles)
-{
-    __shared__ uint32_t hist[kSortThreads / 64][kRadix];
-    const int tid = threadIdx.x, wave = tid >> 6;
-    for (int i = tid; i < (kSortThreads / 64) * kRadix; i += kSortThreads) (&hist[0][0])[i] = 0u;
-    __syncthreads();
-    const int64_t base = (int64_t)blockIdx.x * kSortTile;
-#pragma unroll
-    for (int i = 0; i < kSortKeysPerThread; ++i) {
-        const int64_t pos = base + (int64_t)i * kSortThreads + tid;
-        if (pos < N) atomicAdd(&hist[wave][(keys[pos] >> shift) & (kRadix - 1)], 1u);
-    }
-    __syncthreads();
-    if (tid < kRadix) {
-        uint32_t c = 0;
-#pragma unroll
-        for (int w = 0; w < kSortThreads / 64; ++w) c += hist[w][tid];
-        table[(int64_t)tid * tiles + blockIdx.x] = c;
-    }
-}
-
-// ---------------------------------------------------------------------------
-// Exclusive scan of the count table (u32), three small kernels.
+// Workgroup-wide exclusive scan of one u32 per thread.
 __device__ __forceinline__ uint32_t wave_inclusive_scan_u32(uint32_t v)
 {
     const int lane = lane_id();
@@ -101,69 +65,95 @@ __device__ __forceinline__ uint32_t block_exclusive_scan_u32(uint32_t v, uint32_
     return r;
 }
 
-__global__ void __launch_bounds__(kTableScanThreads)
-k_table_chunk_sums(const uint32_t* __restrict__ table, int64_t len, uint32_t* __restrict__ chunks)
-{
-    const int64_t base = (int64_t)blockIdx.x * kTableScanChunk;
-    uint32_t s = 0;
-#pragma unroll
-    for (int i = 0; i < kTableScanPerThread; ++i) {
-        const int64_t p = base + (int64_t)i * kTableScanThreads + threadIdx.x;
-        if (p < len) s += table[p];
-    }
-    uint32_t total;
-    block_exclusive_scan_u32<kTableScanThreads>(s, &total);
-    if (threadIdx.x == 0) chunks[blockIdx.x] = total;
-}
+// ---------------------------------------------------------------------------
+// Ranking inside a tile (used by every pass).  A wavefront owns 64 * KPT
+// consecutive keys, item-major (item i of lane l is key i*64 + l of the wavefront's
+// range), so the order (wave, item, lane) is the input order.  The lanes that hold
+// the same digit find each other with eight ballots; the lowest of them bumps the
+// wavefront's digit counter in LDS and hands the old value to its peers.  The tile
+// is then laid out in LDS in sorted order and written out so that each digit's run
+// goes to consecutive addresses.
+// ---------------------------------------------------------------------------
+// One-sweep LSD sort.  k_sort_hist reads the anchors once and builds the global
+// histogram of all four digits (the key build is fused: keys are computed from
+// a and b on the fly, ids are positions).  Each of the four passes then reads its
+// input once and writes it once: a tile learns how many keys with each digit lie
+// in the tiles before it from a chained look-back over per-tile status words
+// instead of a count pass and a table scan.
+//
+// Look-back protocol.  Tiles are numbered by a ticket taken when the workgroup
+// starts, so every predecessor of a running tile is itself running and publishes
+// its own digit counts (state 1) before it waits for anything; a tile that has
+// found its prefix publishes the inclusive prefix (state 2).  A status word is a
+// single 64-bit value (state in the top two bits, count below), written and read
+// with agent-scope atomics, so no other memory depends on its ordering.  The
+// spin is bounded: if a predecessor never shows up the tile records an error and
+// goes on with what it has (the stores stay inside the buffers), so a lost wake-up
+// can corrupt a result but never hang the device.
+// ---------------------------------------------------------------------------
+constexpr int kSpinLimit = 1 << 24;
+
+// Status word: state in the top two bits, a key count below.  32-bit words serve up to 2^30 keys.
+template <typename WORD> struct StatusBits;
+template <> struct StatusBits<uint32_t> { static constexpr int shift = 30; };
+template <> struct StatusBits<unsigned long long> { static constexpr int shift = 62; };
 
 __global__ void __launch_bounds__(1024)
-k_table_chunk_scan(uint32_t* __restrict__ chunks, int64_t count)
+k_sort_reset(uint32_t* small)   // [0..1024) global histogram, [1024..1028) tickets, [1028] error
 {
-    // one workgroup; each thread owns a run of consecutive chunk sums
-    const int64_t per = (count + 1023) / 1024;
-    const int64_t lo = (int64_t)threadIdx.x * per;
-    const int64_t hi = lo + per < count ? lo + per : count;
-    uint32_t s = 0;
-    for (int64_t i = lo; i < hi; ++i) s += chunks[i];
-    uint32_t run = block_exclusive_scan_u32<1024>(s, nullptr);
-    for (int64_t i = lo; i < hi; ++i) { const uint32_t t = chunks[i]; chunks[i] = run; run += t; }
+    for (int i = threadIdx.x; i < 1040; i += 1024) small[i] = 0u;
 }
 
-__global__ void __launch_bounds__(kTableScanThreads)
-k_table_scan_apply(uint32_t* __restrict__ table, int64_t len, const uint32_t* __restrict__ chunks)
+__device__ __forceinline__ uint32_t anchor_key(const float* __restrict__ a, int64_t k,
+                                               const float* __restrict__ b, int64_t pos)
 {
-    // thread owns kTableScanPerThread consecutive entries (blocked), so the scan order is the array order
-    const int64_t base = (int64_t)blockIdx.x * kTableScanChunk + (int64_t)threadIdx.x * kTableScanPerThread;
-    uint32_t v[kTableScanPerThread];
-    uint32_t s = 0;
-#pragma unroll
-    for (int i = 0; i < kTableScanPerThread; ++i) {
-        v[i] = base + i < len ? table[base + i] : 0u;
-        s += v[i];
-    }
-    uint32_t run = block_exclusive_scan_u32<kTableScanThreads>(s, nullptr) + chunks[blockIdx.x];
-#pragma unroll
-    for (int i = 0; i < kTableScanPerThread; ++i) {
-        if (base + i < len) table[base + i] = run;
-        run += v[i];
-    }
+    return float_to_key(pos < k ? a[pos] : b[pos - k]);
 }
 
-// ---------------------------------------------------------------------------
-// Pass step 3: stable scatter of one tile.
-//
-// A wavefront owns 64 * KPT consecutive keys, item-major (item i of lane l is
-// key i*64 + l of the wavefront's range), so the order (wave, item, lane) is
-// the input order.  Ranking inside a wavefront: the lanes that hold the same
-// digit find each other with eight ballots; the lowest of them bumps the
-// wavefront's digit counter in LDS and hands the old value to its peers.
-// The tile is then laid out in LDS in sorted order and written out so that
-// each digit's run goes to consecutive addresses.
 __global__ void __launch_bounds__(kSortThreads)
-k_radix_scatter(const uint32_t* __restrict__ keys_in, const uint32_t* __restrict__ ids_in,
-                uint32_t* __restrict__ keys_out, uint32_t* __restrict__ ids_out,
-                int64_t N, int shift, const uint32_t* __restrict__ table, int64_t tiles)
+k_sort_hist(const float* __restrict__ a, int64_t k, const float* __restrict__ b, int64_t n,
+            uint32_t* __restrict__ ghist, unsigned long long* __restrict__ status0, int64_t status_words)
 {
+    __shared__ uint32_t h[kSortPasses][kRadix];
+    for (int i = threadIdx.x; i < kSortPasses * kRadix; i += kSortThreads) (&h[0][0])[i] = 0u;
+    __syncthreads();
+    const int64_t N = k + n;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t first = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (int64_t i = first; i < N; i += stride) {
+        const uint32_t key = anchor_key(a, k, b, i);
+#pragma unroll
+        for (int p = 0; p < kSortPasses - 1; ++p) atomicAdd(&h[p][(key >> (p * kRadixBits)) & (kRadix - 1)], 1u);
+        // the top digit (sign and high exponent bits) takes few values: count it once per distinct value
+        // in the wavefront instead of letting 64 lanes queue on one LDS word
+        const uint32_t top = key >> ((kSortPasses - 1) * kRadixBits);
+        uint64_t todo = __ballot(1);
+        while (todo) {
+            const int first = __ffsll((long long)todo) - 1;
+            const uint32_t v = __shfl(top, first);
+            const uint64_t same = __ballot(top == v) & todo;
+            if ((int)(threadIdx.x & 63) == first) atomicAdd(&h[kSortPasses - 1][v], (uint32_t)__popcll(same));
+            todo &= ~same;
+        }
+    }
+    for (int64_t i = first; i < status_words; i += stride) status0[i] = 0ull;   // look-back words of pass 0
+    __syncthreads();
+    for (int i = threadIdx.x; i < kSortPasses * kRadix; i += kSortThreads) {
+        const uint32_t c = (&h[0][0])[i];
+        if (c) atomicAdd(&ghist[i], c);
+    }
+}
+
+template <bool FIRST, typename WORD>
+__global__ void __launch_bounds__(kSortThreads)
+k_onesweep_pass(const uint32_t* __restrict__ keys_in, const uint32_t* __restrict__ ids_in,
+                const float* __restrict__ a, int64_t k, const float* __restrict__ b,
+                uint32_t* __restrict__ keys_out, uint32_t* __restrict__ ids_out,
+                int64_t N, int pass, const uint32_t* __restrict__ ghist, uint32_t* __restrict__ small,
+                WORD* status, WORD* status_next)
+{
+    constexpr int SH = StatusBits<WORD>::shift;
+    constexpr WORD kMask = (WORD(1) << SH) - WORD(1);
     constexpr int WAVES = kSortThreads / 64;
     constexpr int KPT = kSortKeysPerThread;
     __shared__ uint32_t whist[WAVES][kRadix];     // per-wave digit counts, then offsets
@@ -171,12 +161,17 @@ k_radix_scatter(const uint32_t* __restrict__ keys_in, const uint32_t* __restrict
     __shared__ uint32_t delta[kRadix];            // global slot of digit d = delta[d] + local slot
     __shared__ uint32_t skeys[kSortTile];
     __shared__ uint32_t sids[kSortTile];
+    __shared__ uint32_t s_tile;
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
+    const int shift = pass * kRadixBits;
+    if (tid == 0) s_tile = atomicAdd(&small[1024 + pass], 1u);
     for (int i = tid; i < WAVES * kRadix; i += kSortThreads) (&whist[0][0])[i] = 0u;
     __syncthreads();
+    const int64_t tile = s_tile;
+    if (status_next && tid < kRadix) status_next[tile * kRadix + tid] = WORD(0);   // words of the pass after this one
 
-    const int64_t tile_base = (int64_t)blockIdx.x * kSortTile;
+    const int64_t tile_base = tile * kSortTile;
     const int64_t wave_base = tile_base + (int64_t)wave * (64 * KPT);
     const int64_t remaining = N - tile_base;
     const uint32_t valid = remaining < kSortTile ? (uint32_t)remaining : (uint32_t)kSortTile;
@@ -186,8 +181,11 @@ k_radix_scatter(const uint32_t* __restrict__ keys_in, const uint32_t* __restrict
     for (int i = 0; i < KPT; ++i) {
         const int64_t pos = wave_base + i * 64 + lane;
         const bool ok = pos < N;
-        key[i] = ok ? keys_in[pos] : 0xFFFFFFFFu;   // padding sorts last inside the tile
-        id[i] = ok ? ids_in[pos] : 0u;
+        const int64_t pc = ok ? pos : N - 1;
+        const uint32_t kk = FIRST ? anchor_key(a, k, b, pc) : keys_in[pc];
+        const uint32_t ii = FIRST ? (uint32_t)pc : ids_in[pc];
+        key[i] = ok ? kk : 0xFFFFFFFFu;             // padding sorts last inside the tile
+        id[i] = ii;
     }
     const uint64_t lt_mask = (1ull << lane) - 1ull;
 #pragma unroll
@@ -208,16 +206,52 @@ k_radix_scatter(const uint32_t* __restrict__ keys_in, const uint32_t* __restrict
     }
     __syncthreads();
 
-    // per digit: exclusive offsets over the wavefronts, tile-level digit starts, global deltas
+    // per digit: exclusive offsets over the wavefronts and the tile's count (padding keys excluded)
     uint32_t digit_total = 0;
     if (tid < kRadix) {
 #pragma unroll
         for (int w = 0; w < WAVES; ++w) { const uint32_t c = whist[w][tid]; whist[w][tid] = digit_total; digit_total += c; }
     }
     const uint32_t start = block_exclusive_scan_u32<kSortThreads>(tid < kRadix ? digit_total : 0u, nullptr);
+    const uint32_t gbase = block_exclusive_scan_u32<kSortThreads>(tid < kRadix ? ghist[pass * kRadix + tid] : 0u, nullptr);
     if (tid < kRadix) {
+        uint32_t mine = digit_total;
+        if (tid == kRadix - 1) mine -= (uint32_t)kSortTile - valid;        // the padding all has digit 255
+        WORD* word = status + tile * kRadix + tid;
+        __hip_atomic_store(word, WORD((tile == 0 ? WORD(2) << SH : WORD(1) << SH) | WORD(mine)), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+        WORD before = 0;
+        // walk back over the predecessors, kLook status words in flight at a time (their loads are independent)
+        constexpr int kLook = 8;
+        bool done = false;
+        for (int64_t t0 = tile - 1; t0 >= 0 && !done; t0 -= kLook) {
+            WORD v[kLook];
+#pragma unroll
+            for (int j = 0; j < kLook; ++j) {
+                const int64_t t = t0 - j >= 0 ? t0 - j : 0;
+                v[j] = __hip_atomic_load(status + t * kRadix + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+#pragma unroll
+            for (int j = 0; j < kLook; ++j) {
+                const int64_t t = t0 - j;
+                if (done || t < 0) continue;
+                WORD x = v[j];
+                int spins = 0;
+                while ((x >> SH) == 0 && spins < kSpinLimit) {       // not published yet: wait for it
+                    __builtin_amdgcn_s_sleep(1);
+                    x = __hip_atomic_load(status + t * kRadix + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    ++spins;
+                }
+                if ((x >> SH) == 0) { small[1028] = 1u; done = true; continue; }   // gave up: flag it, never hang
+                before += x & kMask;
+                if ((x >> SH) == 2) done = true;
+            }
+        }
+        if (tile != 0)
+            __hip_atomic_store(word, WORD((WORD(2) << SH) | (before + WORD(mine))), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
         tile_start[tid] = start;
-        delta[tid] = table[(int64_t)tid * tiles + blockIdx.x] - start;
+        delta[tid] = gbase + (uint32_t)before - start;
     }
     __syncthreads();
 
@@ -236,7 +270,7 @@ k_radix_scatter(const uint32_t* __restrict__ keys_in, const uint32_t* __restrict
         if (slot < valid) {
             const uint32_t kk = skeys[slot];
             const uint32_t dst = delta[(kk >> shift) & (kRadix - 1)] + slot;
-            if ((int64_t)dst < N) {   // always true for a consistent count table; keeps a fault impossible
+            if ((int64_t)dst < N) {   // always true for consistent offsets; keeps a fault impossible
                 keys_out[dst] = kk;
                 ids_out[dst] = sids[slot];
             }
@@ -351,34 +385,39 @@ inline unsigned grid_for(int64_t work, int threads, int64_t cap = 1 << 16)
 
 }  // namespace
 
-hipError_t launch_make_keys(const float* a, int64_t k, const float* b, int64_t n,
-                            uint32_t* keys, uint32_t* ids, hipStream_t st)
+hipError_t launch_onesweep_sort(const float* a, int64_t k, const float* b, int64_t n,
+                                uint32_t* keys0, uint32_t* ids0, uint32_t* keys1, uint32_t* ids1,
+                                uint32_t* small, unsigned long long* status, hipStream_t st)
 {
-    LAPLEX_TIMED("make_keys", st, hipLaunchKernelGGL(k_make_keys, dim3(grid_for(k + n, 256)), dim3(256), 0, st, a, k, b, n, keys, ids));
-    return hipGetLastError();
-}
-
-hipError_t launch_radix_sort(uint32_t* keys0, uint32_t* ids0, uint32_t* keys1, uint32_t* ids1,
-                             uint32_t* table, uint32_t* chunks, int64_t N, hipStream_t st)
-{
+    const int64_t N = k + n;
     const int64_t tiles = (N + kSortTile - 1) / kSortTile;
-    const int64_t len = tiles * kRadix;
-    const int64_t nchunks = (len + kTableScanChunk - 1) / kTableScanChunk;
-    uint32_t* kin = keys0; uint32_t* iin = ids0; uint32_t* kout = keys1; uint32_t* iout = ids1;
-    for (int pass = 0; pass < kSortPasses; ++pass) {
-        const int shift = pass * kRadixBits;
-        LAPLEX_TIMED("radix_count", st, hipLaunchKernelGGL(k_radix_count, dim3((unsigned)tiles), dim3(kSortThreads), 0, st,
-                           (const uint32_t*)kin, N, shift, table, tiles));
-        LAPLEX_TIMED("table_scan", st, hipLaunchKernelGGL(k_table_chunk_sums, dim3((unsigned)nchunks), dim3(kTableScanThreads), 0, st,
-                           (const uint32_t*)table, len, chunks));
-        LAPLEX_TIMED("table_scan", st, hipLaunchKernelGGL(k_table_chunk_scan, dim3(1), dim3(1024), 0, st, chunks, nchunks));
-        LAPLEX_TIMED("table_scan", st, hipLaunchKernelGGL(k_table_scan_apply, dim3((unsigned)nchunks), dim3(kTableScanThreads), 0, st,
-                           table, len, (const uint32_t*)chunks));
-        LAPLEX_TIMED("radix_scatter", st, hipLaunchKernelGGL(k_radix_scatter, dim3((unsigned)tiles), dim3(kSortThreads), 0, st,
-                           (const uint32_t*)kin, (const uint32_t*)iin, kout, iout, N, shift,
-                           (const uint32_t*)table, tiles));
-        uint32_t* t = kin; kin = kout; kout = t;
-        t = iin; iin = iout; iout = t;
+    const int64_t words = tiles * kRadix;
+    unsigned long long* region[2] = {status, status + words};
+    LAPLEX_TIMED("sort_hist", st, hipLaunchKernelGGL(k_sort_reset, dim3(1), dim3(1024), 0, st, small));
+    int64_t hgrid = (N + kSortTile - 1) / kSortTile;
+    if (hgrid > 2048) hgrid = 2048;
+    LAPLEX_TIMED("sort_hist", st, hipLaunchKernelGGL(k_sort_hist, dim3((unsigned)hgrid), dim3(kSortThreads), 0, st,
+                                                     a, k, b, n, small, region[0], words));
+    const dim3 grid((unsigned)tiles), block(kSortThreads);
+    auto passes = [&](auto* r0, auto* r1) {
+        using WORD = std::remove_pointer_t<decltype(r0)>;
+        const uint32_t* kin[4] = {nullptr, keys1, keys0, keys1};
+        const uint32_t* iin[4] = {nullptr, ids1, ids0, ids1};
+        uint32_t* kout[4] = {keys1, keys0, keys1, keys0};
+        uint32_t* iout[4] = {ids1, ids0, ids1, ids0};
+        WORD* cur[4] = {r0, r1, r0, r1};
+        WORD* nxt[4] = {r1, r0, r1, nullptr};
+        LAPLEX_TIMED("radix_scatter", st, hipLaunchKernelGGL((k_onesweep_pass<true, WORD>), grid, block, 0, st,
+                     kin[0], iin[0], a, k, b, kout[0], iout[0], N, 0, (const uint32_t*)small, small, cur[0], nxt[0]));
+        for (int p = 1; p < kSortPasses; ++p)
+            LAPLEX_TIMED("radix_scatter", st, hipLaunchKernelGGL((k_onesweep_pass<false, WORD>), grid, block, 0, st,
+                         kin[p], iin[p], a, k, b, kout[p], iout[p], N, p, (const uint32_t*)small, small, cur[p], nxt[p]));
+    };
+    if (N <= (int64_t(1) << 30)) {
+        uint32_t* r = reinterpret_cast<uint32_t*>(status);
+        passes(r, r + words);
+    } else {
+        passes(region[0], region[1]);
     }
     return hipGetLastError();
 }
