@@ -108,12 +108,17 @@ int check_ws(const void* ws, size_t ws_bytes, const Layout& L)
 
 struct Plan {
     uint32_t* ids; float* dh; float* z;
+    float* xs;      // saved region: the forward's injected rows in sorted order (narrow batches, else null)
+    float* stage;   // scratch: the current problem's injected rows in sorted order (narrow batches, else null)
 };
 
 Plan plan_of(const Layout& L, char* ws)
 {
+    const bool narrow = L.batch <= kStageMaxBatch;
     return Plan{reinterpret_cast<uint32_t*>(ws + L.off_ids), reinterpret_cast<float*>(ws + L.off_dh),
-                reinterpret_cast<float*>(ws + L.off_z)};
+                reinterpret_cast<float*>(ws + L.off_z),
+                narrow ? reinterpret_cast<float*>(ws + L.off_xs) : nullptr,
+                narrow ? reinterpret_cast<float*>(ws + L.off_stage) : nullptr};
 }
 
 // Sort (or merge) the anchors and compute the neighbour decays, unless the plan is reused.
@@ -184,6 +189,7 @@ int laplex_apply(const float* a, int64_t k, const float* b, int64_t n,
     p.res_lo = 0; p.res_hi = (uint32_t)k;
     p.out_p = y; p.ld_p = ldy;
     p.out_z = (flags & LAPLEX_SAVE_SCANS) ? P.z : nullptr;
+    p.stage = (flags & LAPLEX_SAVE_SCANS) ? P.xs : P.stage;   // kept for the backward's weights when saving
     p.tag = "fwd";
     LAPLEX_HIP(launch_scan(p, L, w, st));
     return LAPLEX_OK;
@@ -224,17 +230,22 @@ int laplex_apply_backward(const float* a, int64_t k, const float* b, int64_t n,
             p.inj = x; p.ld_inj = ldx; p.inj_lo = (uint32_t)k; p.inj_hi = (uint32_t)(k + n);
             p.res_lo = 0; p.res_hi = (uint32_t)k;
             p.out_z = P.z;
+            p.stage = P.xs;
             p.tag = "rescan";
             LAPLEX_HIP(launch_scan(p, L, w, st));
         }
         LAPLEX_HIP(launch_rowdot(gy, ldgy, P.z, batch, k, batch, ga, st));
     }
+    // sorted-order x is in the saved region if the forward kept it or the re-scan above just wrote it
+    const bool have_xs = (flags & LAPLEX_SAVE_SCANS) || ga;
     if (gx || gb) {
         ScanProblem p = problem(P, L);
         p.inj = gy; p.ld_inj = ldgy; p.inj_lo = 0; p.inj_hi = (uint32_t)k;
         p.res_lo = (uint32_t)k; p.res_hi = (uint32_t)(k + n);
         p.out_p = gx; p.ld_p = ldgx;
         p.out_red = gb; p.w = x; p.ld_w = ldx;
+        p.stage = P.stage;
+        p.wstage = (gb && have_xs) ? P.xs : nullptr;
         p.tag = "bwd";
         LAPLEX_HIP(launch_scan(p, L, w, st));
     }
@@ -262,6 +273,7 @@ int laplex_gram(const float* a, int64_t n, const float* x, int64_t ldx, int64_t 
     p.res_lo = 0; p.res_hi = (uint32_t)n;
     p.out_p = y; p.ld_p = ldy;
     p.out_z = (flags & LAPLEX_SAVE_SCANS) ? P.z : nullptr;
+    p.stage = (flags & LAPLEX_SAVE_SCANS) ? P.xs : P.stage;
     p.tag = "fwd";
     LAPLEX_HIP(launch_scan(p, L, w, st));
     return LAPLEX_OK;
@@ -295,6 +307,7 @@ int laplex_gram_backward(const float* a, int64_t n, const float* x, int64_t ldx,
         p.inj = x; p.ld_inj = ldx; p.inj_lo = 0; p.inj_hi = (uint32_t)n;
         p.res_lo = 0; p.res_hi = (uint32_t)n;
         p.out_z = P.z;
+        p.stage = P.xs;
         p.tag = "rescan";
         LAPLEX_HIP(launch_scan(p, L, w, st));
     }
@@ -304,6 +317,8 @@ int laplex_gram_backward(const float* a, int64_t n, const float* x, int64_t ldx,
         p.res_lo = 0; p.res_hi = (uint32_t)n;
         p.out_p = gx; p.ld_p = ldgx;
         p.out_red = ga; p.w = x; p.ld_w = ldx; p.zs = ga ? P.z : nullptr;
+        p.stage = P.stage;
+        p.wstage = ga ? P.xs : nullptr;     // kept by the forward (SAVE_SCANS) or just written by the re-scan
         p.tag = "bwd";
         LAPLEX_HIP(launch_scan(p, L, w, st));
     }

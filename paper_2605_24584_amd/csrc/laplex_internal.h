@@ -31,6 +31,9 @@ constexpr int kScanWaves = 8;
 constexpr int kScanThreads = kScanWaves * 64;
 constexpr int kItemsVec1 = 16;   // rows per row-lane when a lane holds 1 column
 constexpr int kItemsVec4 = 8;    // rows per row-lane when a lane holds 4 columns
+// A batch row narrower than this many floats is gathered once per problem and staged in sorted
+// order: a random read of a few bytes costs a whole 128-byte line of HBM traffic.
+constexpr int kStageMaxBatch = 8;
 constexpr int kSpineItems = 8;    // tile summaries per row-lane in the chunked spine kernels
 constexpr int kSpineThreads = 1024;
 
@@ -79,6 +82,7 @@ struct Layout {
     size_t off_dh = 0;       // f32[N+1]  decay to the previous sorted key, < 0: same key
     // saved scans
     size_t off_z = 0;        // f32[zrows][batch]
+    size_t off_xs = 0;       // f32[N][batch], narrow batches only: the forward's injected rows in sorted order
     size_t off_scratch = 0;
     // scratch, sort view
     size_t off_keys0 = 0, off_keys1 = 0, off_ids1 = 0, off_status = 0, off_sort_small = 0;
@@ -91,6 +95,7 @@ struct Layout {
     size_t off_car_e = 0;        // f32[2][tiles][bpad]         carry E
     size_t off_red = 0;          // f32[slabs][N]               per-slab partial row reductions
     size_t off_lists = 0;        // u32[2][tiles] tile lists + u32[64] counters (sparse problems)
+    size_t off_stage = 0;        // f32[N][batch], narrow batches only: this problem's injected rows in sorted order
     // second level of the spine: the same five arrays over chunks of tiles
     size_t off_agg2_scalar = 0, off_agg2_s = 0, off_agg2_q = 0, off_car2_f = 0, off_car2_e = 0;
     int64_t max_tiles = 0, max_chunks = 0;
@@ -106,6 +111,8 @@ inline Layout make_layout(int64_t N, int64_t zrows, int64_t batch)
     L.off_ids = o;  o = align_up(o + sizeof(uint32_t) * (size_t)N);
     L.off_dh = o;   o = align_up(o + sizeof(float) * (size_t)(N + 1));
     L.off_z = o;    o = align_up(o + sizeof(float) * (size_t)zrows * (size_t)batch);
+    const size_t stage_bytes = batch <= kStageMaxBatch ? sizeof(float) * (size_t)N * (size_t)batch : 0;
+    L.off_xs = o;   o = align_up(o + stage_bytes);
     L.off_scratch = o;
 
     // sort view
@@ -132,6 +139,7 @@ inline Layout make_layout(int64_t N, int64_t zrows, int64_t batch)
     L.off_red = c;
     if (max_slabs > 1) c = align_up(c + sizeof(float) * (size_t)max_slabs * (size_t)N);
     L.off_lists = c; c = align_up(c + sizeof(uint32_t) * (2 * (size_t)L.max_tiles + 64));
+    L.off_stage = c; c = align_up(c + stage_bytes);
     L.max_chunks = g1.chunks > g4.chunks ? g1.chunks : g4.chunks;
     const size_t per2 = sizeof(float) * 2 * (size_t)L.max_chunks * (size_t)L.bpad;
     L.off_agg2_scalar = c; c = align_up(c + sizeof(float) * 4 * 2 * (size_t)L.max_chunks);
@@ -195,6 +203,8 @@ struct ScanProblem {
     float* out_z;
     float* out_red; const float* w; int64_t ld_w; const float* zs;
     int64_t batch;
+    float* stage;          // narrow batches: the reduce writes the injected rows here in sorted order, the downsweep reads them back
+    const float* wstage;   // narrow batches: the weights w in sorted order (an earlier problem's stage), or null
     const char* tag;   // names the timing families: scan_reduce.<tag>, scan_spine.<tag>, scan_down.<tag>
 };
 hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStream_t st);

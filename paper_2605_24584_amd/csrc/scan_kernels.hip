@@ -54,6 +54,7 @@ struct ScanArgs {
     float* out_p; int64_t ld_p;
     float* out_z;
     float* out_red; const float* w; int64_t ld_w; const float* zs;
+    float* stage; const float* wstage;   // sorted-order copies of the injected rows / of the weights (narrow batches)
     int64_t batch, bpad;
     int bv, bv_log2, rv, tile_rows, slabs, chunk_tiles;
     Level l1, l2;
@@ -241,11 +242,17 @@ __device__ __forceinline__ void load_injected(const ScanArgs& A, const TileRows<
 
 // weights of the row reduction at the result rows (zero elsewhere, or when no reduction is wanted)
 template <int VEC>
-__device__ __forceinline__ void load_weights(const ScanArgs& A, const TileRows<VEC>& T, int64_t col0, bool col_ok,
-                                             bool want, float (*wv)[VEC])
+__device__ __forceinline__ void load_weights(const ScanArgs& A, const TileRows<VEC>& T, int64_t row0, int64_t col0,
+                                             bool col_ok, bool want, float (*wv)[VEC])
 {
     constexpr int ITEMS = TileRows<VEC>::ITEMS;
-    if (want) {     // uniform
+    if (want && A.wstage) {     // uniform: sorted-order copy, read in place of a random gather
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            const bool ok = col_ok && T.id[i] >= A.res_lo && T.id[i] < A.res_hi;
+            load_vec_or_zero<VEC>(wv[i], A.wstage, (row0 + i) * A.batch + col0, ok);
+        }
+    } else if (want) {
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) {
             const bool ok = col_ok && T.id[i] >= A.res_lo && T.id[i] < A.res_hi;
@@ -410,6 +417,11 @@ k_scan_reduce(const ScanArgs A)
     float v[ITEMS][VEC];
     if (tile_flags & kFlagInj) {     // uniform: a tile with nothing injected reads no data rows
         load_injected<VEC>(A, T, col0, col_ok, v);
+        if (A.stage && col_ok) {     // uniform in A.stage
+#pragma unroll
+            for (int i = 0; i < ITEMS; ++i)
+                if (T.id[i] != 0xFFFFFFFFu) store_vec<VEC>(A.stage + (row0 + i) * A.batch + col0, v[i]);
+        }
     } else {
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i)
@@ -626,12 +638,18 @@ k_scan_down(const ScanArgs A)
     TileRows<VEC> T;
     load_meta<VEC>(A, row0, T);
     float v[ITEMS][VEC];
-    load_injected<VEC>(A, T, col0, col_ok, v);
+    if (A.stage) {      // uniform: the reduce left this tile's injected rows in sorted order (zeros elsewhere)
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i)
+            load_vec_or_zero<VEC>(v[i], A.stage, (row0 + i) * A.batch + col0, col_ok && T.id[i] != 0xFFFFFFFFu);
+    } else {
+        load_injected<VEC>(A, T, col0, col_ok, v);
+    }
 
     // weights of the row reduction, fetched early so the loads overlap the scans
     float wv[ITEMS][VEC];
     const bool want_red = STRICT && A.out_red != nullptr;
-    load_weights<VEC>(A, T, col0, col_ok, want_red, wv);
+    load_weights<VEC>(A, T, row0, col0, col_ok, want_red, wv);
 
     // entering states: tile carry, then the wavefronts before this one, then the row-lanes before this one
     float F[VEC], E[VEC], R[VEC], G[VEC];
@@ -762,7 +780,7 @@ k_scan_down_sparse(const ScanArgs A)
     load_meta<VEC>(A, row0, T);
     const bool want_red = STRICT && A.out_red != nullptr;
     float wv[ITEMS][VEC];
-    load_weights<VEC>(A, T, col0, col_ok, want_red, wv);
+    load_weights<VEC>(A, T, row0, col0, col_ok, want_red, wv);
     float Fin[VEC], Ein[VEC], Rin[VEC], Gin[VEC];
 #pragma unroll
     for (int e = 0; e < VEC; ++e) { Fin[e] = Ein[e] = Rin[e] = Gin[e] = 0.0f; }
@@ -926,6 +944,7 @@ hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStrea
     A.res_lo = p.res_lo; A.res_hi = p.res_hi;
     A.out_p = p.out_p; A.ld_p = p.ld_p; A.out_z = p.out_z;
     A.out_red = p.out_red; A.w = p.w; A.ld_w = p.ld_w; A.zs = p.zs;
+    A.stage = p.stage; A.wstage = p.wstage;
     A.batch = p.batch; A.bpad = L.bpad;
     A.bv = g.bv; A.bv_log2 = ilog2(g.bv); A.rv = g.rv; A.tile_rows = g.tile_rows; A.slabs = g.slabs;
     A.chunk_tiles = g.chunk_tiles;
