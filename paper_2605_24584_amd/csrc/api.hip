@@ -107,7 +107,7 @@ int check_ws(const void* ws, size_t ws_bytes, const Layout& L)
     } while (0)
 
 struct Plan {
-    uint32_t* ids; float* dh; float* z;
+    uint32_t* ids; float* dh; float* pk; float* z;
     float* xs;      // saved region: the forward's injected rows in sorted order (narrow batches, else null)
     float* stage;   // scratch: the current problem's injected rows in sorted order (narrow batches, else null)
 };
@@ -116,7 +116,7 @@ Plan plan_of(const Layout& L, char* ws)
 {
     const bool narrow = L.batch <= kStageMaxBatch;
     return Plan{reinterpret_cast<uint32_t*>(ws + L.off_ids), reinterpret_cast<float*>(ws + L.off_dh),
-                reinterpret_cast<float*>(ws + L.off_z),
+                reinterpret_cast<float*>(ws + L.off_pk), reinterpret_cast<float*>(ws + L.off_z),
                 narrow ? reinterpret_cast<float*>(ws + L.off_xs) : nullptr,
                 narrow ? reinterpret_cast<float*>(ws + L.off_stage) : nullptr};
 }
@@ -136,14 +136,14 @@ int build_plan(const float* a, int64_t k, const float* b, int64_t n, const Layou
                                         reinterpret_cast<uint32_t*>(ws + L.off_sort_small),
                                         reinterpret_cast<unsigned long long*>(ws + L.off_status), st));
     }
-    LAPLEX_HIP(launch_decay(keys0, P.dh, L.N, st));
+    LAPLEX_HIP(launch_decay(keys0, P.dh, P.pk, L.N, st));
     return LAPLEX_OK;
 }
 
 ScanProblem problem(const Plan& P, const Layout& L)
 {
     ScanProblem p{};
-    p.ids = P.ids; p.dh = P.dh; p.N = L.N; p.batch = L.batch;
+    p.ids = P.ids; p.dh = P.dh; p.pk = P.pk; p.N = L.N; p.batch = L.batch;
     return p;
 }
 

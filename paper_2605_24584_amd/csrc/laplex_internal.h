@@ -80,6 +80,7 @@ struct Layout {
     // plan
     size_t off_ids = 0;      // u32[N]    sorted ids
     size_t off_dh = 0;       // f32[N+1]  decay to the previous sorted key, < 0: same key
+    size_t off_pk = 0;       // f32[N+2]  sorted anchors, shifted by one, between -inf and +inf sentinels
     // saved scans
     size_t off_z = 0;        // f32[zrows][batch]
     size_t off_xs = 0;       // f32[N][batch], narrow batches only: the forward's injected rows in sorted order
@@ -110,6 +111,7 @@ inline Layout make_layout(int64_t N, int64_t zrows, int64_t batch)
     size_t o = 0;
     L.off_ids = o;  o = align_up(o + sizeof(uint32_t) * (size_t)N);
     L.off_dh = o;   o = align_up(o + sizeof(float) * (size_t)(N + 1));
+    L.off_pk = o;   o = align_up(o + sizeof(float) * (size_t)(N + 2));
     L.off_z = o;    o = align_up(o + sizeof(float) * (size_t)zrows * (size_t)batch);
     const size_t stage_bytes = batch <= kStageMaxBatch ? sizeof(float) * (size_t)N * (size_t)batch : 0;
     L.off_xs = o;   o = align_up(o + stage_bytes);
@@ -180,8 +182,8 @@ hipError_t launch_merge(const float* a, int64_t k, const float* b, int64_t n,
                         uint32_t* keys, uint32_t* ids, hipStream_t st);
 
 // dh[j] = decay from sorted key j-1 to j (>= 0), or -1 if the two keys are equal;
-// dh[0] = dh[N] = 0 (nothing beyond either end).
-hipError_t launch_decay(const uint32_t* keys, float* dh, int64_t N, hipStream_t st);
+// dh[0] = dh[N] = 0 (nothing beyond either end).  pk[j+1] = sorted anchor j, pk[0] = -inf, pk[N+1] = +inf.
+hipError_t launch_decay(const uint32_t* keys, float* dh, float* pk, int64_t N, hipStream_t st);
 
 hipError_t launch_fill(float* p, int64_t rows, int64_t cols, int64_t ld, float v, hipStream_t st);
 hipError_t launch_copy_u32(const uint32_t* src, uint32_t* dst, int64_t count, hipStream_t st);
@@ -196,7 +198,7 @@ hipError_t launch_copy_u32(const uint32_t* src, uint32_t* dst, int64_t count, hi
 // Any of out_p / out_z / out_red may be null; strict scans run only if out_z or
 // out_red is wanted.
 struct ScanProblem {
-    const uint32_t* ids; const float* dh; int64_t N;
+    const uint32_t* ids; const float* dh; const float* pk; int64_t N;
     const float* inj; int64_t ld_inj; uint32_t inj_lo, inj_hi;
     uint32_t res_lo, res_hi;
     float* out_p; int64_t ld_p;

@@ -13,7 +13,8 @@
 //      anchor gradients, where tied pairs must drop out (sgn(0) = 0).
 //
 // A run of rows is summarised by (D, S) with F_out = D F_in + S, plus, for the
-// strict channel, (H, C, Q) with E_out = H ? C F_in + Q : E_in.  Summaries
+// strict channel, (H, Q) with E_out = H ? D F_in + Q : E_in (the decay up to the
+// last run head is D itself, since the rows after it have decay 1).  Summaries
 // compose associatively, so the work splits into launches, with both directions
 // done together so that the injected matrix is read once per launch:
 //
@@ -48,7 +49,7 @@ struct Level {            // summaries of one level (tiles, or chunks of tiles) 
 };
 
 struct ScanArgs {
-    const uint32_t* ids; const float* dh; int64_t N;
+    const uint32_t* ids; const float* dh; const float* pk; int64_t N;
     const float* inj; int64_t ld_inj; uint32_t inj_lo, inj_hi;
     uint32_t res_lo, res_hi;
     float* out_p; int64_t ld_p;
@@ -112,9 +113,9 @@ __device__ __forceinline__ Seg<VEC, STRICT> seg_compose(const Seg<VEC, STRICT>& 
     r.D = x.D * y.D;
     if (STRICT) {
         r.H = x.H | y.H;
-        r.C = y.H ? y.C * x.D : x.C;
+        r.C = r.D;       // the decay up to the last run head equals the whole decay: rows after it have decay 1
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) r.Q[e] = y.H ? y.C * x.S[e] + y.Q[e] : x.Q[e];
+        for (int e = 0; e < VEC; ++e) r.Q[e] = y.H ? y.D * x.S[e] + y.Q[e] : x.Q[e];
     } else {
         r.H = 0; r.C = 0.0f;
 #pragma unroll
@@ -145,7 +146,7 @@ __device__ __forceinline__ void seg_apply(const Seg<VEC, STRICT>& s, float* F, f
 {
 #pragma unroll
     for (int e = 0; e < VEC; ++e) {
-        if (STRICT) E[e] = s.H ? s.C * F[e] + s.Q[e] : E[e];
+        if (STRICT) E[e] = s.H ? s.D * F[e] + s.Q[e] : E[e];
         F[e] = s.D * F[e] + s.S[e];
     }
 }
@@ -227,6 +228,62 @@ template <int VEC>
 __device__ __forceinline__ bool head_f(const TileRows<VEC>& T, int i) { return T.id[i] != 0xFFFFFFFFu && T.dh[i] >= 0.0f; }
 template <int VEC>
 __device__ __forceinline__ bool head_b(const TileRows<VEC>& T, int i) { return T.id[i] != 0xFFFFFFFFu && T.dh[i + 1] >= 0.0f; }
+
+// Total decay over the rows [row0, row0 + count) in the forward sense (from the anchor before
+// row0 to the last of the rows) and in the backward sense (from the anchor after the rows to row0),
+// taken from the anchors themselves: exp(-(p_end - p_start)), one rounding whatever the count.
+// pk is shifted by one between -inf / +inf sentinels, so the ends of the sequence give exactly 0;
+// rows past the end do not count.
+// (Branch-free: indices are clamped and an empty span is selected away afterwards, so the loads
+//  are issued unconditionally next to the kernel's other loads.)
+__device__ __forceinline__ float span_decay_f(const ScanArgs& A, int64_t row0, int64_t count)
+{
+    const int64_t lo = row0 < A.N ? row0 : A.N;
+    int64_t hi = row0 + (count > 0 ? count : 0);
+    hi = hi < A.N ? hi : A.N;                                        // one past the last live row
+    const float d = expf(-(A.pk[hi] - A.pk[lo]));
+    return hi > lo ? d : 1.0f;
+}
+__device__ __forceinline__ float span_decay_b(const ScanArgs& A, int64_t row0, int64_t count)
+{
+    const int64_t lo = row0 < A.N ? row0 : A.N;
+    int64_t hi = row0 + (count > 0 ? count : 0);
+    hi = hi < A.N ? hi : A.N;
+    const float d = expf(-(A.pk[hi + 1] - A.pk[lo + 1]));
+    return hi > lo ? d : 1.0f;
+}
+
+// Is there a run head among the rows [row0, row0 + count), seen from the left / from the right?
+// Sorted anchors change somewhere in the span iff its two ends differ.
+__device__ __forceinline__ bool span_head_f(const ScanArgs& A, int64_t row0, int64_t count)
+{
+    const int64_t lo = row0 < A.N ? row0 : A.N;
+    int64_t hi = row0 + (count > 0 ? count : 0);
+    hi = hi < A.N ? hi : A.N;
+    return hi > lo && A.pk[hi] != A.pk[lo];
+}
+__device__ __forceinline__ bool span_head_b(const ScanArgs& A, int64_t row0, int64_t count)
+{
+    const int64_t lo = row0 < A.N ? row0 : A.N;
+    int64_t hi = row0 + (count > 0 ? count : 0);
+    hi = hi < A.N ? hi : A.N;
+    return hi > lo && A.pk[hi + 1] != A.pk[lo + 1];
+}
+
+// State a row-lane starts from, given the carry into its tile (Fc, Ec), the summary of the rows of the
+// tile that precede it applied to a ZERO state (F0 = their S, E0 = their Q), and the direct decay D /
+// head flag H over those preceding rows: the carry is decayed by ONE exponential of an anchor
+// difference instead of by the product of all the summaries' decays.
+template <int VEC, bool STRICT>
+__device__ __forceinline__ void enter_state(float* F, float* E, const float* Fc, const float* Ec, float D, bool H)
+{
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+        const float carried = D * Fc[e];
+        if (STRICT) E[e] = H ? E[e] + carried : Ec[e];
+        F[e] = F[e] + carried;
+    }
+}
 
 template <int VEC>
 __device__ __forceinline__ void load_injected(const ScanArgs& A, const TileRows<VEC>& T, int64_t col0, bool col_ok,
@@ -348,9 +405,9 @@ k_scan_meta(const ScanArgs A)
     const int lane = threadIdx.x & 63;
     const int64_t tile = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (tile >= A.l1.count) return;
-    float Df = 1.0f, Db = 1.0f;
     int Hf = 0, Hb = 0, fl = 0;
     const int64_t base = tile * A.tile_rows;
+    const float Df = span_decay_f(A, base, A.tile_rows), Db = span_decay_b(A, base, A.tile_rows);
     for (int o = 0; o < A.tile_rows; o += 64) {
         const int64_t j = base + o + lane;
         const bool live = j < A.N;
@@ -358,14 +415,12 @@ k_scan_meta(const ScanArgs A)
         const uint32_t id = A.ids[jc];
         const float df = A.dh[jc], db = A.dh[jc + 1];
         const bool hf = live && df >= 0.0f, hb = live && db >= 0.0f;
-        Df *= hf ? df : 1.0f; Db *= hb ? db : 1.0f;
         Hf |= hf ? 1 : 0; Hb |= hb ? 1 : 0;
         fl |= (live && id >= A.inj_lo && id < A.inj_hi) ? kFlagInj : 0;
         fl |= (live && id >= A.res_lo && id < A.res_hi) ? kFlagRes : 0;
     }
 #pragma unroll
     for (int m = 32; m >= 1; m >>= 1) {
-        Df *= __shfl_xor(Df, m); Db *= __shfl_xor(Db, m);
         Hf |= __shfl_xor(Hf, m); Hb |= __shfl_xor(Hb, m); fl |= __shfl_xor(fl, m);
     }
     if (lane == 0) {
@@ -398,10 +453,19 @@ k_scan_reduce(const ScanArgs A)
     const int c = lane & (bv - 1), r = lane >> A.bv_log2;
     if (A.reduce_from_list && blockIdx.x >= A.counters[0]) return;
     const int64_t tile = A.reduce_from_list ? A.list_inj[blockIdx.x] : blockIdx.x;
-    const int64_t row0 = tile * A.tile_rows + (int64_t)(wave * rv + r) * ITEMS;
+    const int64_t wave_row0 = tile * A.tile_rows + (int64_t)(wave * rv) * ITEMS;
+    const int64_t row0 = wave_row0 + (int64_t)r * ITEMS;
     const int64_t col0 = ((int64_t)blockIdx.y * bv + c) * VEC;
     const bool col_ok = col0 < A.batch;
     if (tid == 0) tile_flags = 0;
+
+    // decays over this row-lane's rows, this wavefront's rows and the whole tile, from the anchors
+    // (not products of the rows' decays: see k_decay); asked for first so the loads go out early
+    const float lane_df = span_decay_f(A, row0, ITEMS), lane_db = span_decay_b(A, row0, ITEMS);
+    const float wave_df = rv == 1 ? lane_df : span_decay_f(A, wave_row0, rv * ITEMS);
+    const float wave_db = rv == 1 ? lane_db : span_decay_b(A, wave_row0, rv * ITEMS);
+    const float tile_df = span_decay_f(A, tile * A.tile_rows, A.tile_rows);
+    const float tile_db = span_decay_b(A, tile * A.tile_rows, A.tile_rows);
 
     TileRows<VEC> T;
     load_meta<VEC>(A, row0, T);
@@ -433,15 +497,23 @@ k_scan_reduce(const ScanArgs A)
         Seg<VEC, STRICT> f = seg_identity<VEC, STRICT>();
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) seg_push<VEC, STRICT>(f, head_f<VEC>(T, i), T.dh[i], v[i]);
+        f.D = lane_df;
         f = wave_scan<true, VEC, STRICT>(f, lane, bv, rv);
-        if (r == rv - 1) put_wave_seg<VEC, STRICT>(W, 0, wave, c, f);
+        if (r == rv - 1) {
+            f.D = wave_df;
+            put_wave_seg<VEC, STRICT>(W, 0, wave, c, f);
+        }
     }
     {
         Seg<VEC, STRICT> b = seg_identity<VEC, STRICT>();
 #pragma unroll
         for (int i = ITEMS - 1; i >= 0; --i) seg_push<VEC, STRICT>(b, head_b<VEC>(T, i), T.dh[i + 1], v[i]);
+        b.D = lane_db;
         b = wave_scan<false, VEC, STRICT>(b, lane, bv, rv);
-        if (r == 0) put_wave_seg<VEC, STRICT>(W, 1, wave, c, b);
+        if (r == 0) {
+            b.D = wave_db;
+            put_wave_seg<VEC, STRICT>(W, 1, wave, c, b);
+        }
     }
     __syncthreads();
 
@@ -451,6 +523,8 @@ k_scan_reduce(const ScanArgs A)
         for (int w = 0; w < kScanWaves; ++w) tf = seg_compose<VEC, STRICT>(tf, get_wave_seg<VEC, STRICT>(W, 0, w, c));
 #pragma unroll 1
         for (int w = kScanWaves - 1; w >= 0; --w) tb = seg_compose<VEC, STRICT>(tb, get_wave_seg<VEC, STRICT>(W, 1, w, c));
+        tf.D = tf.C = tile_df;
+        tb.D = tb.C = tile_db;
         const bool sw = c == 0 && blockIdx.y == 0;
         store_level_seg<VEC, STRICT>(A.l1, 0, tile, A.bpad, col0, col_ok, sw, tf, (float)tile_flags);
         store_level_seg<VEC, STRICT>(A.l1, 1, tile, A.bpad, col0, col_ok, sw, tb, (float)tile_flags);
@@ -491,6 +565,15 @@ k_spine_reduce(const ScanArgs A)
         Seg<VEC, STRICT> t = seg_identity<VEC, STRICT>();
 #pragma unroll 1
         for (int w = 0; w < kScanWaves; ++w) t = seg_compose<VEC, STRICT>(t, get_wave_seg<VEC, STRICT>(W, 0, w, c));
+        // the chunk's total decay from the anchors, not from the product of its tiles' decays
+        const int64_t tiles_here = A.l1.count - chunk * A.chunk_tiles < A.chunk_tiles ? A.l1.count - chunk * A.chunk_tiles
+                                                                                      : A.chunk_tiles;
+        if (dir == 0) {
+            t.D = span_decay_f(A, chunk * A.chunk_tiles * A.tile_rows, tiles_here * A.tile_rows);
+        } else {
+            const int64_t t_hi = A.l1.count - 1 - chunk * A.chunk_tiles;          // first tile in scan order
+            t.D = span_decay_b(A, (t_hi + 1 - tiles_here) * A.tile_rows, tiles_here * A.tile_rows);
+        }
         store_level_seg<VEC, STRICT>(A.l2, dir, chunk, A.bpad, col0, col_ok, c == 0 && blockIdx.y == 0, t, 0.0f);
     }
 }
@@ -577,17 +660,30 @@ k_spine_down(const ScanArgs A)
     if (r == 0) exc = seg_identity<VEC, STRICT>();
     __syncthreads();
 
-    float F[VEC], E[VEC];
+    float F[VEC], E[VEC], Fc[VEC], Ec[VEC];
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) { F[e] = 0.0f; E[e] = 0.0f; }
+    for (int e = 0; e < VEC; ++e) { F[e] = E[e] = Fc[e] = Ec[e] = 0.0f; }
     if (col_ok) {
         const int64_t o = ((int64_t)dir * A.l2.count + chunk) * A.bpad + col0;
-        load_vec<VEC>(F, A.l2.car_f + o);
-        if (STRICT) load_vec<VEC>(E, A.l2.car_e + o);
+        load_vec<VEC>(Fc, A.l2.car_f + o);
+        if (STRICT) load_vec<VEC>(Ec, A.l2.car_e + o);
     }
 #pragma unroll 1
     for (int w = 0; w < wave; ++w) seg_apply<VEC, STRICT>(get_wave_seg<VEC, STRICT>(W, 0, w, c), F, E);
     seg_apply<VEC, STRICT>(exc, F, E);
+    // the chunk's carry reaches this row-lane's first tile through one exponential of an anchor difference
+    if (q0 < A.l1.count) {
+        const int64_t before = q0 - chunk * A.chunk_tiles;               // tiles of the chunk ahead of q0 in scan order
+        if (dir == 0) {
+            const int64_t r0 = chunk * A.chunk_tiles * A.tile_rows;
+            enter_state<VEC, STRICT>(F, E, Fc, Ec, span_decay_f(A, r0, before * A.tile_rows),
+                                     span_head_f(A, r0, before * A.tile_rows));
+        } else {
+            const int64_t r0 = (A.l1.count - q0) * A.tile_rows;           // first row after this row-lane's first tile
+            enter_state<VEC, STRICT>(F, E, Fc, Ec, span_decay_b(A, r0, before * A.tile_rows),
+                                     span_head_b(A, r0, before * A.tile_rows));
+        }
+    }
 #pragma unroll
     for (int i = 0; i < kSpineItems; ++i) {
         const int64_t q = q0 + i;
@@ -622,7 +718,13 @@ __global__ void __launch_bounds__(kScanThreads)
 k_scan_down(const ScanArgs A)
 {
     constexpr int ITEMS = TileRows<VEC>::ITEMS;
-    __shared__ WaveSegs<VEC> W;
+    // One LDS buffer, used twice: first for the exchange of wavefront summaries, then (strict scans only)
+    // for the per-row strict forward values, which would otherwise cost ITEMS * VEC registers per lane.
+    constexpr size_t kEfBytes = STRICT ? sizeof(float) * ITEMS * kScanThreads * VEC : 0;
+    constexpr size_t kSmem = sizeof(WaveSegs<VEC>) > kEfBytes ? sizeof(WaveSegs<VEC>) : kEfBytes;
+    __shared__ __align__(16) unsigned char smem[kSmem];
+    WaveSegs<VEC>& W = *reinterpret_cast<WaveSegs<VEC>*>(smem);
+    float* const ef = reinterpret_cast<float*>(smem) + (size_t)threadIdx.x * VEC;   // row i at ef[i * kScanThreads * VEC]
     if (A.down_from_list && blockIdx.x >= A.counters[1]) return;
     const int64_t tile = A.down_from_list ? A.list_both[blockIdx.x] : blockIdx.x;
     const int flags = (int)A.l1.scalar[tile].w;
@@ -631,9 +733,21 @@ k_scan_down(const ScanArgs A)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int bv = A.bv, rv = A.rv;
     const int c = lane & (bv - 1), r = lane >> A.bv_log2;
-    const int64_t row0 = tile * A.tile_rows + (int64_t)(wave * rv + r) * ITEMS;
+    const int64_t wave_row0 = tile * A.tile_rows + (int64_t)(wave * rv) * ITEMS;
+    const int64_t row0 = wave_row0 + (int64_t)r * ITEMS;
     const int64_t col0 = ((int64_t)blockIdx.y * bv + c) * VEC;
     const bool col_ok = col0 < A.batch;
+
+    // decays from the anchors (see k_decay), asked for first so their loads go out with the others:
+    // over this row-lane's rows, over this wavefront's rows, and from the tile's ends to this row-lane
+    const float lane_df = span_decay_f(A, row0, ITEMS), lane_db = span_decay_b(A, row0, ITEMS);
+    const float wave_df = rv == 1 ? lane_df : span_decay_f(A, wave_row0, rv * ITEMS);
+    const float wave_db = rv == 1 ? lane_db : span_decay_b(A, wave_row0, rv * ITEMS);
+    const int64_t tile_base = tile * A.tile_rows, rows_after = row0 + ITEMS;
+    const float enter_df = span_decay_f(A, tile_base, row0 - tile_base);
+    const float enter_db = span_decay_b(A, rows_after, tile_base + A.tile_rows - rows_after);
+    const bool enter_hf = span_head_f(A, tile_base, row0 - tile_base);
+    const bool enter_hb = span_head_b(A, rows_after, tile_base + A.tile_rows - rows_after);
 
     TileRows<VEC> T;
     load_meta<VEC>(A, row0, T);
@@ -646,28 +760,43 @@ k_scan_down(const ScanArgs A)
         load_injected<VEC>(A, T, col0, col_ok, v);
     }
 
-    // weights of the row reduction, fetched early so the loads overlap the scans
-    float wv[ITEMS][VEC];
     const bool want_red = STRICT && A.out_red != nullptr;
-    load_weights<VEC>(A, T, row0, col0, col_ok, want_red, wv);
-
-    // entering states: tile carry, then the wavefronts before this one, then the row-lanes before this one
-    float F[VEC], E[VEC], R[VEC], G[VEC];
+    // weights of the row reduction and the saved strict scans are fetched one row ahead of their use in
+    // the backward walk (holding all rows of both would cost 2 * ITEMS * VEC registers)
+    auto fetch_row = [&](int i, float* wrow, float* zrow) {
+        const bool ok = col_ok && T.id[i] >= A.res_lo && T.id[i] < A.res_hi;
+        const int64_t rr = (int64_t)T.id[i] - (int64_t)A.res_lo;
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) { F[e] = E[e] = R[e] = G[e] = 0.0f; }
+        for (int e = 0; e < VEC; ++e) { wrow[e] = 0.0f; zrow[e] = 0.0f; }
+        if (want_red) {                                  // uniform branches
+            if (A.wstage) load_vec_or_zero<VEC>(wrow, A.wstage, (row0 + i) * A.batch + col0, ok);
+            else load_vec_or_zero<VEC>(wrow, A.w, rr * A.ld_w + col0, ok);
+            if (A.zs) load_vec_or_zero<VEC>(zrow, A.zs, rr * A.batch + col0, ok);
+        }
+    };
+
+    // carries into the tile
+    float Fc[VEC], Ec[VEC], Rc[VEC], Gc[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) { Fc[e] = Ec[e] = Rc[e] = Gc[e] = 0.0f; }
     if (col_ok) {
         const int64_t o0 = tile * A.bpad + col0, o1 = (A.l1.count + tile) * A.bpad + col0;
-        load_vec<VEC>(F, A.l1.car_f + o0);
-        load_vec<VEC>(R, A.l1.car_f + o1);
-        if (STRICT) { load_vec<VEC>(E, A.l1.car_e + o0); load_vec<VEC>(G, A.l1.car_e + o1); }
+        load_vec<VEC>(Fc, A.l1.car_f + o0);
+        load_vec<VEC>(Rc, A.l1.car_f + o1);
+        if (STRICT) { load_vec<VEC>(Ec, A.l1.car_e + o0); load_vec<VEC>(Gc, A.l1.car_e + o1); }
     }
     Seg<VEC, STRICT> fe, be;
     {
         Seg<VEC, STRICT> f = seg_identity<VEC, STRICT>();
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) seg_push<VEC, STRICT>(f, head_f<VEC>(T, i), T.dh[i], v[i]);
+        f.D = lane_df;
         f = wave_scan<true, VEC, STRICT>(f, lane, bv, rv);
-        if (r == rv - 1) put_wave_seg<VEC, STRICT>(W, 0, wave, c, f);
+        if (r == rv - 1) {
+            Seg<VEC, STRICT> tot = f;
+            tot.D = wave_df;
+            put_wave_seg<VEC, STRICT>(W, 0, wave, c, tot);
+        }
         fe = seg_shfl<VEC, STRICT>(f, (lane - bv) & 63);
         if (r == 0) fe = seg_identity<VEC, STRICT>();
     }
@@ -675,21 +804,35 @@ k_scan_down(const ScanArgs A)
         Seg<VEC, STRICT> b = seg_identity<VEC, STRICT>();
 #pragma unroll
         for (int i = ITEMS - 1; i >= 0; --i) seg_push<VEC, STRICT>(b, head_b<VEC>(T, i), T.dh[i + 1], v[i]);
+        b.D = lane_db;
         b = wave_scan<false, VEC, STRICT>(b, lane, bv, rv);
-        if (r == 0) put_wave_seg<VEC, STRICT>(W, 1, wave, c, b);
+        if (r == 0) {
+            Seg<VEC, STRICT> tot = b;
+            tot.D = wave_db;
+            put_wave_seg<VEC, STRICT>(W, 1, wave, c, tot);
+        }
         be = seg_shfl<VEC, STRICT>(b, (lane + bv) & 63);
         if (r == rv - 1) be = seg_identity<VEC, STRICT>();
     }
     __syncthreads();
+    // entering states: what the earlier rows of the tile contribute (their summaries applied to zero) ...
+    float F[VEC], E[VEC], R[VEC], G[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) { F[e] = E[e] = R[e] = G[e] = 0.0f; }
 #pragma unroll 1
     for (int w = 0; w < wave; ++w) seg_apply<VEC, STRICT>(get_wave_seg<VEC, STRICT>(W, 0, w, c), F, E);
 #pragma unroll 1
     for (int w = kScanWaves - 1; w > wave; --w) seg_apply<VEC, STRICT>(get_wave_seg<VEC, STRICT>(W, 1, w, c), R, G);
     seg_apply<VEC, STRICT>(fe, F, E);
     seg_apply<VEC, STRICT>(be, R, G);
+    // ... plus the tile's carries, decayed over those rows by one exponential of an anchor difference
+    enter_state<VEC, STRICT>(F, E, Fc, Ec, enter_df, enter_hf);
+    enter_state<VEC, STRICT>(R, G, Rc, Gc, enter_db, enter_hb);
 
-    // forward walk: keep F (and E) of every row
-    float Ff[ITEMS][VEC], Ef[ITEMS][VEC];
+    if (STRICT) __syncthreads();      // every wavefront is done with the summaries: the buffer now holds E per row
+
+    // forward walk: keep F of every row in registers, E of every row in LDS
+    float Ff[ITEMS][VEC];
 #pragma unroll
     for (int i = 0; i < ITEMS; ++i) {
         const bool h = head_f<VEC>(T, i);
@@ -698,22 +841,31 @@ k_scan_down(const ScanArgs A)
             E[e] = h ? T.dh[i] * F[e] : E[e];
             F[e] = (h ? E[e] : F[e]) + v[i][e];
             Ff[i][e] = F[e];
-            Ef[i][e] = E[e];
         }
+        if (STRICT) store_vec<VEC>(ef + (size_t)i * kScanThreads * VEC, E);
     }
 
     // backward walk with emission
     const int64_t res_rows = (int64_t)A.res_hi - (int64_t)A.res_lo;
+    float wnext[VEC], znext[VEC];
+    fetch_row(ITEMS - 1, wnext, znext);
 #pragma unroll
     for (int i = ITEMS - 1; i >= 0; --i) {
+        float wrow[VEC], zsv[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) { wrow[e] = wnext[e]; zsv[e] = znext[e]; }
+        if (i > 0) fetch_row(i - 1, wnext, znext);
         const bool h = head_b<VEC>(T, i);
-        float P[VEC], Z[VEC];
+        float P[VEC], Z[VEC], Efi[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) Efi[e] = 0.0f;
+        if (STRICT) load_vec<VEC>(Efi, ef + (size_t)i * kScanThreads * VEC);
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
             G[e] = h ? T.dh[i + 1] * R[e] : G[e];
             R[e] = (h ? G[e] : R[e]) + v[i][e];
             P[e] = Ff[i][e] + R[e] - v[i][e];
-            Z[e] = G[e] - Ef[i][e];
+            Z[e] = G[e] - Efi[e];
         }
         const bool is_res = T.id[i] >= A.res_lo && T.id[i] < A.res_hi;
         const int64_t rr = (int64_t)T.id[i] - (int64_t)A.res_lo;
@@ -723,12 +875,8 @@ k_scan_down(const ScanArgs A)
         }
         if (want_red) {
             float acc = 0.0f;
-            float zsv[VEC];
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) zsv[e] = 0.0f;
-            if (A.zs) load_vec_or_zero<VEC>(zsv, A.zs, rr * A.batch + col0, is_res && col_ok);   // uniform branch
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) acc += wv[i][e] * Z[e] + v[i][e] * zsv[e];     // wv, zsv are 0 off the result rows
+            for (int e = 0; e < VEC; ++e) acc += wrow[e] * Z[e] + v[i][e] * zsv[e];     // wrow, zsv are 0 off the result rows
             emit_row_sum(A, acc, bv, c, is_res, rr, res_rows);
         }
     }
@@ -739,32 +887,14 @@ k_scan_down(const ScanArgs A)
 // injection inside the tile every row is a closed form of the two carries:
 //   F_j = cf_j F_in,           cf_j = product of the decays from the tile start to j
 //   E_j = F_j if a run head lies at or before j inside the tile, else E_in
-// and symmetrically from the right.  Only per-row scalars are scanned; the batch
-// columns are streamed.
+// and symmetrically from the right.  The decays come from the anchors directly, so
+// the kernel has no scan, no LDS and no barrier; the batch columns are streamed.
 // ---------------------------------------------------------------------------
-struct DecaySeg { float D; int H; };
-
-template <bool FWD>
-__device__ __forceinline__ DecaySeg wave_scan_decay(DecaySeg s, int lane, int bv, int rv)
-{
-    const int r = lane / bv;
-    for (int step = 1; step < rv; step <<= 1) {
-        const int src = (FWD ? lane - step * bv : lane + step * bv) & 63;
-        const float oD = __shfl(s.D, src);
-        const int oH = __shfl(s.H, src);
-        const bool has = FWD ? (r >= step) : (r + step < rv);
-        if (has) { s.D *= oD; s.H |= oH; }
-    }
-    return s;
-}
-
 template <int VEC, bool STRICT>
 __global__ void __launch_bounds__(kScanThreads)
 k_scan_down_sparse(const ScanArgs A)
 {
     constexpr int ITEMS = TileRows<VEC>::ITEMS;
-    __shared__ float wD[2][kScanWaves];
-    __shared__ int wH[2][kScanWaves];
     const int64_t tile = blockIdx.x;
     const int flags = (int)A.l1.scalar[tile].w;
     if ((flags & (kFlagInj | kFlagRes)) != kFlagRes) return;
@@ -775,6 +905,12 @@ k_scan_down_sparse(const ScanArgs A)
     const int64_t row0 = tile * A.tile_rows + (int64_t)(wave * rv + r) * ITEMS;
     const int64_t col0 = ((int64_t)blockIdx.y * bv + c) * VEC;
     const bool col_ok = col0 < A.batch;
+
+    // everything in the tile before / after this row-lane: one exponential of an anchor difference each,
+    // so no scan over the row-lanes and no LDS are needed (asked for first: the loads go out early)
+    const int64_t tile_base = tile * A.tile_rows, after = row0 + ITEMS, tile_end = tile_base + A.tile_rows;
+    const float Df = span_decay_f(A, tile_base, row0 - tile_base), Db = span_decay_b(A, after, tile_end - after);
+    const int Hf = span_head_f(A, tile_base, row0 - tile_base) ? 1 : 0, Hb = span_head_b(A, after, tile_end - after) ? 1 : 0;
 
     TileRows<VEC> T;
     load_meta<VEC>(A, row0, T);
@@ -791,7 +927,7 @@ k_scan_down_sparse(const ScanArgs A)
         if (STRICT) { load_vec<VEC>(Ein, A.l1.car_e + o0); load_vec<VEC>(Gin, A.l1.car_e + o1); }
     }
 
-    // per-row cumulative decays inside this row-lane, from the left and from the right
+    // per-row cumulative decays inside this row-lane, from the left and from the right (at most ITEMS factors)
     float cf[ITEMS], cb[ITEMS];
     int hf = 0, hb = 0;               // bit i: a run head at or before (after) row i inside the row-lane
     {
@@ -810,20 +946,6 @@ k_scan_down_sparse(const ScanArgs A)
             cb[i] = p; hb |= seen << i;
         }
     }
-    DecaySeg fi = wave_scan_decay<true>(DecaySeg{cf[ITEMS - 1], (hf >> (ITEMS - 1)) & 1}, lane, bv, rv);
-    DecaySeg bi = wave_scan_decay<false>(DecaySeg{cb[0], hb & 1}, lane, bv, rv);
-    if (lane == 63) { wD[0][wave] = fi.D; wH[0][wave] = fi.H; }
-    if (lane == 0) { wD[1][wave] = bi.D; wH[1][wave] = bi.H; }
-    DecaySeg fe{__shfl(fi.D, (lane - bv) & 63), __shfl(fi.H, (lane - bv) & 63)};
-    DecaySeg be{__shfl(bi.D, (lane + bv) & 63), __shfl(bi.H, (lane + bv) & 63)};
-    if (r == 0) fe = DecaySeg{1.0f, 0};
-    if (r == rv - 1) be = DecaySeg{1.0f, 0};
-    __syncthreads();
-    float Df = 1.0f, Db = 1.0f; int Hf = 0, Hb = 0;      // everything in the tile before / after this row-lane
-    for (int w = 0; w < wave; ++w) { Df *= wD[0][w]; Hf |= wH[0][w]; }
-    for (int w = kScanWaves - 1; w > wave; --w) { Db *= wD[1][w]; Hb |= wH[1][w]; }
-    Df *= fe.D; Hf |= fe.H; Db *= be.D; Hb |= be.H;
-
     const int64_t res_rows = (int64_t)A.res_hi - (int64_t)A.res_lo;
 #pragma unroll
     for (int i = 0; i < ITEMS; ++i) {
@@ -939,7 +1061,7 @@ hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStrea
     const ScanGeom g = scan_geom(p.N, p.batch, v4 ? 4 : 1);
 
     ScanArgs A;
-    A.ids = p.ids; A.dh = p.dh; A.N = p.N;
+    A.ids = p.ids; A.dh = p.dh; A.pk = p.pk; A.N = p.N;
     A.inj = p.inj; A.ld_inj = p.ld_inj; A.inj_lo = p.inj_lo; A.inj_hi = p.inj_hi;
     A.res_lo = p.res_lo; A.res_hi = p.res_hi;
     A.out_p = p.out_p; A.ld_p = p.ld_p; A.out_z = p.out_z;

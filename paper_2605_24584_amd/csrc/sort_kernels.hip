@@ -345,8 +345,15 @@ k_merge(const float* __restrict__ a, int64_t k, const float* __restrict__ b, int
 // y_{i+1} = x_{i+1} + exp(a_i - a_{i+1}) y_i).  A negative entry marks "same key
 // as the predecessor": the decay is exactly 1 and the position does not start
 // a new run of equal anchors (needed for the strict sums of the gradients).
+//
+// The sorted anchors themselves are kept too (pk, shifted by one between a -inf and a
+// +inf sentinel): a decay over more than a handful of rows is never taken as a product
+// of these per-row decays but as exp(-(p_end - p_start)).  fp32 anchors make the gaps
+// lattice-valued, so the rounding of the per-row decays has a systematic sign and a
+// product of tens of thousands of them drifts by 1e-4 and more; key differences
+// telescope exactly.  (App. B.1's pair operator adds log-decays for the same reason.)
 __global__ void __launch_bounds__(256)
-k_decay(const uint32_t* __restrict__ keys, float* __restrict__ dh, int64_t N)
+k_decay(const uint32_t* __restrict__ keys, float* __restrict__ dh, float* __restrict__ pk, int64_t N)
 {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j <= N; j += stride) {
@@ -356,6 +363,8 @@ k_decay(const uint32_t* __restrict__ keys, float* __restrict__ dh, int64_t N)
             d = k1 == k0 ? -1.0f : expf(-(key_to_float(k1) - key_to_float(k0)));
         }
         dh[j] = d;
+        pk[j + 1] = j < N ? key_to_float(keys[j]) : __uint_as_float(0x7F800000u);
+        if (j == 0) pk[0] = __uint_as_float(0xFF800000u);
     }
 }
 
@@ -431,9 +440,9 @@ hipError_t launch_merge(const float* a, int64_t k, const float* b, int64_t n,
     return hipGetLastError();
 }
 
-hipError_t launch_decay(const uint32_t* keys, float* dh, int64_t N, hipStream_t st)
+hipError_t launch_decay(const uint32_t* keys, float* dh, float* pk, int64_t N, hipStream_t st)
 {
-    LAPLEX_TIMED("decay", st, hipLaunchKernelGGL(k_decay, dim3(grid_for(N + 1, 256)), dim3(256), 0, st, keys, dh, N));
+    LAPLEX_TIMED("decay", st, hipLaunchKernelGGL(k_decay, dim3(grid_for(N + 1, 256)), dim3(256), 0, st, keys, dh, pk, N));
     return hipGetLastError();
 }
 

@@ -94,7 +94,9 @@ KINDS = ["uniform", "ties", "all_equal", "huge_gaps", "clustered", "signed"]
 # (k, n, batch): single elements, ragged tails, several tiles of both lane geometries, two slabs
 SHAPES = [(1, 1, 1), (5, 1, 2), (1, 6, 1), (37, 53, 3), (100, 9000, 1), (9000, 100, 5),
           (3000, 21000, 1), (2500, 4000, 8), (513, 9000, 64), (300, 2100, 256), (70, 1500, 260),
-          (50, 1700, 67)]
+          (50, 1700, 67),
+          # very few outputs / very few inputs: tile lists drive the heavy kernels
+          (3, 70000, 1), (70000, 3, 1), (2, 40000, 8), (5, 30000, 64)]
 
 
 # ------------------------------------------------------------------ the sort
