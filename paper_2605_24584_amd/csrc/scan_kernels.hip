@@ -532,6 +532,103 @@ k_scan_reduce(const ScanArgs A)
 }
 
 // ---------------------------------------------------------------------------
+// reduce, wide batches (64 lanes across the batch, 4 columns each): one WAVEFRONT
+// per tile.  It folds the tile's rows chunk by chunk, so the summary needs no LDS
+// and no barrier, and many independent wavefronts keep loads in flight.  Same
+// outputs as k_scan_reduce.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ float uniform_f(float v) { return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v))); }
+__device__ __forceinline__ uint32_t uniform_u(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
+
+template <bool STRICT>
+__global__ void __launch_bounds__(kScanThreads)
+k_scan_reduce_wide(const ScanArgs A)
+{
+    constexpr int VEC = 4, ITEMS = kItemsVec4;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int64_t slot = (int64_t)blockIdx.x * kScanWaves + wave;
+    if (A.reduce_from_list ? slot >= A.counters[0] : slot >= A.l1.count) return;
+    const int64_t tile = A.reduce_from_list ? (int64_t)uniform_u(A.list_inj[slot]) : slot;
+    const int64_t col0 = ((int64_t)blockIdx.y * 64 + lane) * VEC;
+    const bool col_ok = col0 < A.batch;
+    const int64_t tile_base = tile * A.tile_rows;
+    const float tile_df = span_decay_f(A, tile_base, A.tile_rows), tile_db = span_decay_b(A, tile_base, A.tile_rows);
+
+    // Every lane of the wavefront works on the same rows (its own 4 columns), so the rows' ids, decays and
+    // head flags are wavefront-uniform: they are made scalar, and what depends on them branches uniformly.
+    Seg<VEC, STRICT> tf = seg_identity<VEC, STRICT>(), tb = seg_identity<VEC, STRICT>();
+    int flags = 0;
+    TileRows<VEC> Tnext;
+    load_meta<VEC>(A, tile_base, Tnext);
+    for (int64_t row0 = tile_base; row0 < tile_base + A.tile_rows; row0 += ITEMS) {
+        uint32_t id[ITEMS];
+        float dh[ITEMS + 1];
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) id[i] = uniform_u(Tnext.id[i]);
+#pragma unroll
+        for (int i = 0; i <= ITEMS; ++i) dh[i] = uniform_f(Tnext.dh[i]);
+        load_meta<VEC>(A, row0 + ITEMS, Tnext);     // one chunk ahead (clamped past the end; unused after the last chunk)
+
+        float v[ITEMS][VEC];
+        bool inj[ITEMS];
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            inj[i] = id[i] >= A.inj_lo && id[i] < A.inj_hi;
+            flags |= inj[i] ? kFlagInj : 0;
+            flags |= (id[i] >= A.res_lo && id[i] < A.res_hi) ? kFlagRes : 0;
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) v[i][e] = 0.0f;
+            if (inj[i] && col_ok) load_vec<VEC>(v[i], A.inj + (int64_t)(id[i] - A.inj_lo) * A.ld_inj + col0);
+        }
+        // forward: rows in order
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            const bool h = id[i] != 0xFFFFFFFFu && dh[i] >= 0.0f;
+            if (h) {
+                if (STRICT) {
+                    tf.H = 1;
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) tf.Q[e] = dh[i] * tf.S[e];
+                }
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) tf.S[e] = dh[i] * tf.S[e] + v[i][e];
+            } else if (inj[i]) {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) tf.S[e] += v[i][e];
+            }
+        }
+        // backward: this chunk's rows in reverse, then prepended to what the earlier chunks gave
+        Seg<VEC, STRICT> cb = seg_identity<VEC, STRICT>();
+        float cbD = 1.0f;
+#pragma unroll
+        for (int i = ITEMS - 1; i >= 0; --i) {
+            const bool h = id[i] != 0xFFFFFFFFu && dh[i + 1] >= 0.0f;
+            if (h) {
+                if (STRICT) {
+                    cb.H = 1;
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) cb.Q[e] = dh[i + 1] * cb.S[e];
+                }
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) cb.S[e] = dh[i + 1] * cb.S[e] + v[i][e];
+                cbD *= dh[i + 1];
+            } else if (inj[i]) {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) cb.S[e] += v[i][e];
+            }
+        }
+        cb.D = cbD;
+        tb = seg_compose<VEC, STRICT>(cb, tb);      // backward order: these (later) rows come before the earlier ones
+    }
+    tf.D = tf.C = tile_df;      // the tile's decay from the anchors, not the product of 64 row decays
+    tb.D = tb.C = tile_db;
+    const bool sw = lane == 0 && blockIdx.y == 0;
+    store_level_seg<VEC, STRICT>(A.l1, 0, tile, A.bpad, col0, col_ok, sw, tf, (float)flags);
+    store_level_seg<VEC, STRICT>(A.l1, 1, tile, A.bpad, col0, col_ok, sw, tb, (float)flags);
+}
+
+// ---------------------------------------------------------------------------
 // spine, level 1 -> 2: summarise chunks of tile summaries (blockIdx.z = direction).
 // Index q counts tiles in scan order; tile = q forward, count-1-q backward.
 // ---------------------------------------------------------------------------
@@ -1039,7 +1136,13 @@ void launch_all(const ScanArgs& A, const ScanGeom& g, const std::string& tag, hi
     const dim3 tgrid((unsigned)A.batch, 2);
     const std::string fr = "scan_reduce." + tag, fs = "scan_spine." + tag, fd = "scan_down." + tag,
                       fp = "scan_down_sparse." + tag;
-    LAPLEX_TIMED(fr.c_str(), st, hipLaunchKernelGGL((k_scan_reduce<VEC, STRICT>), rgrid, block, 0, st, A));
+    if (VEC == 4 && g.bv == 64) {     // one wavefront per tile
+        const int64_t slots = A.reduce_from_list ? rcap : g.tiles;
+        const dim3 wgrid((unsigned)((slots + kScanWaves - 1) / kScanWaves), (unsigned)g.slabs);
+        LAPLEX_TIMED(fr.c_str(), st, hipLaunchKernelGGL((k_scan_reduce_wide<STRICT>), wgrid, block, 0, st, A));
+    } else {
+        LAPLEX_TIMED(fr.c_str(), st, hipLaunchKernelGGL((k_scan_reduce<VEC, STRICT>), rgrid, block, 0, st, A));
+    }
     LAPLEX_TIMED(fs.c_str(), st, hipLaunchKernelGGL((k_spine_reduce<VEC, STRICT>), cgrid, block, 0, st, A));
     LAPLEX_TIMED(fs.c_str(), st, hipLaunchKernelGGL((k_spine_top<STRICT>), tgrid, dim3(kSpineThreads), 0, st, A.l2, A.bpad));
     LAPLEX_TIMED(fs.c_str(), st, hipLaunchKernelGGL((k_spine_down<VEC, STRICT>), cgrid, block, 0, st, A));
