@@ -35,6 +35,10 @@ def parse():
     ap.add_argument("--batch", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-columns", type=int, default=256)
+    ap.add_argument("--workload", default="projection",
+                    choices=["projection", "square", "tie_heavy", "gram", "billion"],
+                    help="projection is the benchmark; the others time one forward+backward step of the "
+                         "other workloads (for profiles; no roofline object, no CPU baseline)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="instead of the benchmark: time a plain device copy of 1 GiB (counter calibration)")
     return ap.parse_args()
@@ -60,6 +64,55 @@ def dominant_kernel_bytes(a, b, batch, tile_rows):
     rows = int(rows_per_tile[~has_output].sum())
     visited = int((~has_output).sum())
     return rows * (8 + 8 * batch + 4) + visited * 16 * batch, rows, visited, int(tiles)
+
+
+def other_workload(args, torch, np, B, synth):
+    """One forward + backward step of a workload other than the benchmark's, timed the same way."""
+    dev = lambda v: torch.from_numpy(np.ascontiguousarray(v)).cuda()
+    if args.workload == "gram":
+        w = synth.gram_images(scale=args.scale)
+        a, x, g = w["a"], w["x"], w["g"]
+        n, batch = a.size, x.shape[1]
+        k = 0
+        ws = torch.empty(B.laplex_workspace_bytes(0, n, batch), dtype=torch.uint8, device="cuda")
+        da, dx, dg = dev(a), dev(x), dev(g)
+        y = torch.empty(n, batch, device="cuda"); gx = torch.empty(n, batch, device="cuda"); ga = torch.empty(n, device="cuda")
+
+        def step():
+            B.laplex_gram(da, dx, y, ws, B.LAPLEX_SAVE_SCANS)
+            B.laplex_gram_backward(da, dx, dg, gx, ga, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
+        elements = n * batch
+    else:
+        make = {"square": synth.square_small, "tie_heavy": synth.tie_heavy, "billion": synth.billion_square}[args.workload]
+        w = make(scale=args.scale)
+        a, b, x = w["a"], w["b"], w["x"]
+        g = w.get("g", np.ones((a.size, 1), dtype=np.float32))
+        k, n, batch = a.size, b.size, 1
+        ws = torch.empty(B.laplex_workspace_bytes(k, n, 1), dtype=torch.uint8, device="cuda")
+        da, db, dx, dg = dev(a), dev(b), dev(x), dev(g)
+        y = torch.empty(k, 1, device="cuda"); gx = torch.empty(n, 1, device="cuda")
+        ga = torch.empty(k, device="cuda"); gb = torch.empty(n, device="cuda")
+
+        def step():
+            B.laplex_apply(da, db, dx, y, ws, B.LAPLEX_SAVE_SCANS)
+            B.laplex_apply_backward(da, db, dx, dg, gx, ga, gb, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
+        elements = (n + k) * batch
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    print(json.dumps({
+        "metric": "LAPLEX fwd+bwd (n+k)*batch elements/s", "value": elements / (ms * 1e-3), "unit": "elements/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w["name"] + ("" if args.scale == 1 else "/scaled"), "k": k, "n": n, "batch": batch,
+                   "pass": "forward+backward, sort inside every step", "workspace_bytes": ws.numel(),
+                   "device_bytes_peak": torch.cuda.max_memory_allocated()},
+    }), flush=True)
 
 
 def main():
@@ -91,6 +144,10 @@ def main():
         dt = (time.perf_counter() - t0) / 20
         print(json.dumps({"copy_bytes_read": 4 << 28, "copy_bytes_written": 4 << 28, "ms": dt * 1e3,
                           "GBps_read_plus_write": 2 * (4 << 28) / dt / 1e9}), flush=True)
+        return
+
+    if args.workload != "projection":
+        other_workload(args, torch, np, B, synth)
         return
 
     w = synth.projection_layer(scale=args.scale, batch=args.batch)

@@ -352,3 +352,45 @@ def test_workload_billion_scaled(oracle):
     (rgx, rga, rgb), (tgx, tga, tgb) = oracle.apply_backward_scan(a, b, x, g)
     gx, ga, gb = gpu_backward(a, b, x, g, flags=B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN, ws=ws)
     assert_close("gx", gx, rgx, tgx); assert_close("ga", ga, rga, tga); assert_close("gb", gb, rgb, tgb)
+
+
+# ------------------------------------------------------------------ stream capture
+
+def test_hip_graph_replays_match_eager():
+    """The calls only enqueue kernels (no allocation, no synchronisation, no memset), so a
+    forward + backward pair can be captured in a HIP graph.  Every replay, with fresh inputs
+    copied into the captured buffers and eager work in between, must give the eager bits."""
+    r = np.random.default_rng(21)
+    k, n, batch = 300, 20000, 16
+    a, b = anchors("uniform", r, k, n)
+    da, db = dev(a), dev(b)
+    dx = torch.empty(n, batch, device="cuda"); dg = torch.empty(k, batch, device="cuda")
+    y = torch.empty(k, batch, device="cuda"); gx = torch.empty(n, batch, device="cuda")
+    ga = torch.empty(k, device="cuda"); gb = torch.empty(n, device="cuda")
+    ws = workspace(k, n, batch)
+
+    def run():
+        B.laplex_apply(da, db, dx, y, ws, B.LAPLEX_SAVE_SCANS)
+        B.laplex_apply_backward(da, db, dx, dg, gx, ga, gb, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
+
+    dx.normal_(); dg.normal_()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run()                                   # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        run()
+    for rep in range(4):
+        xs = torch.from_numpy(r.normal(size=(n, batch)).astype(np.float32)).cuda()
+        gs = torch.from_numpy(r.normal(size=(k, batch)).astype(np.float32)).cuda()
+        dx.copy_(xs); dg.copy_(gs)
+        run(); torch.cuda.synchronize()
+        want = [t.clone() for t in (y, gx, ga, gb)]
+        for t in (y, gx, ga, gb):
+            t.fill_(float("nan"))
+        graph.replay(); torch.cuda.synchronize()
+        for name, got, ref in zip(("y", "gx", "ga", "gb"), (y, gx, ga, gb), want):
+            assert torch.equal(got, ref), f"replay {rep}: {name} differs from the eager result"
