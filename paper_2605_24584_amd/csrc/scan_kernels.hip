@@ -367,13 +367,15 @@ __device__ __forceinline__ Seg<VEC, STRICT> load_level_seg(const Level& L, int d
     const float4 sc = L.scalar[(int64_t)dir * L.count + idx];
     s.D = sc.x;
     if (STRICT) { s.C = sc.y; s.H = (int)sc.z; }
+    // level 1: a tile with nothing injected has S = Q = 0 and its rows may never have been written; its
+    // loads are pointed at entry 0 instead (branch-free, always cached) and the values discarded
+    const bool inj = !FLAGGED || ((int)sc.w & kFlagInj) != 0;
     if (col_ok) {
-        const int64_t o = ((int64_t)dir * L.count + idx) * bpad + col0;
+        const int64_t o = inj ? ((int64_t)dir * L.count + idx) * bpad + col0 : col0;
         load_vec<VEC>(s.S, L.s + o);
         if (STRICT) load_vec<VEC>(s.Q, L.q + o);
     }
-    if (FLAGGED) {   // level 1: a tile with nothing injected has S = Q = 0; its rows may never have been written
-        const bool inj = ((int)sc.w & kFlagInj) != 0;
+    if (FLAGGED) {
 #pragma unroll
         for (int e = 0; e < VEC; ++e) { s.S[e] = inj ? s.S[e] : 0.0f; s.Q[e] = inj ? s.Q[e] : 0.0f; }
     }
