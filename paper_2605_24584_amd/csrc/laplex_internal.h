@@ -17,6 +17,12 @@ constexpr int kSortPasses = 4;
 constexpr int kSortThreads = 512;                       // 8 wavefronts
 constexpr int kSortKeysPerThread = 16;
 constexpr int kSortTile = kSortThreads * kSortKeysPerThread;  // 8192 keys per workgroup
+// Small state of one sort, u32 words: [0, 1024) histogram of the four digits; then the per-pass tile
+// tickets and the error flag in one cache line, and the mask of the passes that run in a line of its own.
+constexpr int kSortTicketWord = 1024;
+constexpr int kSortErrorWord = 1028;
+constexpr int kSortMaskWord = 1056;
+constexpr int kSortSmallWords = 1088;
 constexpr int kMergeThreads = 256;
 constexpr int kMergePerThread = 8;
 constexpr int kMergeTile = kMergeThreads * kMergePerThread;
@@ -125,7 +131,7 @@ inline Layout make_layout(int64_t N, int64_t zrows, int64_t batch)
     L.off_keys1 = s;  s = align_up(s + sizeof(uint32_t) * (size_t)N);
     L.off_ids1 = s;   s = align_up(s + sizeof(uint32_t) * (size_t)N);
     L.off_status = s;     s = align_up(s + sizeof(uint64_t) * 2 * (size_t)L.status_words);   // look-back words, two passes' worth
-    L.off_sort_small = s; s = align_up(s + sizeof(uint32_t) * 1040);                       // global histogram, tickets, error
+    L.off_sort_small = s; s = align_up(s + sizeof(uint32_t) * kSortSmallWords);            // global histogram, tickets, error, pass mask
 
     // scan view
     size_t c = o;
@@ -172,7 +178,7 @@ void profile_after(const char* family, hipStream_t st);
 // ----------------------------------------------------------------------------
 
 // Stable ascending sort of the anchors a ++ b by one-sweep LSD passes; keys and ids end in keys0/ids0.
-// small: u32[1040] (global histogram, tickets, error word); status: u64[2][tiles*256] look-back words.
+// small: u32[kSortSmallWords] (global histogram, tickets, error word, pass mask); status: u64[2][tiles*256] look-back words.
 hipError_t launch_onesweep_sort(const float* a, int64_t k, const float* b, int64_t n,
                                 uint32_t* keys0, uint32_t* ids0, uint32_t* keys1, uint32_t* ids1,
                                 uint32_t* small, unsigned long long* status, hipStream_t st);
@@ -183,7 +189,11 @@ hipError_t launch_merge(const float* a, int64_t k, const float* b, int64_t n,
 
 // dh[j] = decay from sorted key j-1 to j (>= 0), or -1 if the two keys are equal;
 // dh[0] = dh[N] = 0 (nothing beyond either end).  pk[j+1] = sorted anchor j, pk[0] = -inf, pk[N+1] = +inf.
-hipError_t launch_decay(const uint32_t* keys, float* dh, float* pk, int64_t N, hipStream_t st);
+// The sorted pairs are in (keys0, ids0), or, after an odd number of radix passes (ghist tells), in
+// (keys1, ids1); in that case the ids are also copied to ids0, where the plan keeps them.
+// ghist == nullptr: the pairs are in buffer 0 (merge path).
+hipError_t launch_decay(const uint32_t* keys0, const uint32_t* keys1, uint32_t* ids0, const uint32_t* ids1,
+                        const uint32_t* ghist, float* dh, float* pk, int64_t N, hipStream_t st);
 
 hipError_t launch_fill(float* p, int64_t rows, int64_t cols, int64_t ld, float v, hipStream_t st);
 hipError_t launch_copy_u32(const uint32_t* src, uint32_t* dst, int64_t count, hipStream_t st);

@@ -2,7 +2,8 @@
 // O(n log n)"; App. B "Combined complexity").  Hand-written for gfx950:
 // 64-wide wavefronts, ballot-based stable ranking, LDS-staged scatter.
 //
-//   radix sort  one-sweep LSD sort, 4 passes of 8 bits: one histogram kernel (key
+//   radix sort  one-sweep LSD sort, up to 4 passes of 8 bits (a pass whose digit is the same
+//               for every key is skipped): one histogram kernel (key
 //               build fused: a ++ b -> order-preserving u32 keys, ids = positions),
 //               then per pass one read and one write of the pairs, tile offsets
 //               from a chained look-back over per-tile status words
@@ -99,9 +100,9 @@ template <> struct StatusBits<uint32_t> { static constexpr int shift = 30; };
 template <> struct StatusBits<unsigned long long> { static constexpr int shift = 62; };
 
 __global__ void __launch_bounds__(1024)
-k_sort_reset(uint32_t* small)   // [0..1024) global histogram, [1024..1028) tickets, [1028] error
+k_sort_reset(uint32_t* small)
 {
-    for (int i = threadIdx.x; i < 1040; i += 1024) small[i] = 0u;
+    for (int i = threadIdx.x; i < kSortSmallWords; i += 1024) small[i] = 0u;
 }
 
 __device__ __forceinline__ uint32_t anchor_key(const float* __restrict__ a, int64_t k,
@@ -144,11 +145,31 @@ k_sort_hist(const float* __restrict__ a, int64_t k, const float* __restrict__ b,
     }
 }
 
-template <bool FIRST, typename WORD>
+// A pass whose digit takes one value over all keys would move every pair to where it already is
+// (relative to the others): it is skipped.  k_sort_plan derives the set of passes that run from the
+// global histogram, once: bit p of small[kSortMaskWord] = pass p runs.  If no pass would run (all keys equal)
+// the last one runs anyway, so that the output buffers get written.
+__global__ void __launch_bounds__(1024)
+k_sort_plan(uint32_t* __restrict__ small, int64_t N)
+{
+    __shared__ uint32_t constant_mask;
+    if (threadIdx.x == 0) constant_mask = 0u;
+    __syncthreads();
+    for (int i = threadIdx.x; i < kSortPasses * kRadix; i += blockDim.x)
+        if ((int64_t)small[i] == N) atomicOr(&constant_mask, 1u << (i / kRadix));
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t active = ~constant_mask & ((1u << kSortPasses) - 1u);
+        if (active == 0u) active = 1u << (kSortPasses - 1);
+        small[kSortMaskWord] = active;
+    }
+}
+
+template <typename WORD>
 __global__ void __launch_bounds__(kSortThreads)
-k_onesweep_pass(const uint32_t* __restrict__ keys_in, const uint32_t* __restrict__ ids_in,
-                const float* __restrict__ a, int64_t k, const float* __restrict__ b,
-                uint32_t* __restrict__ keys_out, uint32_t* __restrict__ ids_out,
+k_onesweep_pass(const float* __restrict__ a, int64_t k, const float* __restrict__ b,
+                uint32_t* __restrict__ keys0, uint32_t* __restrict__ ids0,      // four distinct buffers
+                uint32_t* __restrict__ keys1, uint32_t* __restrict__ ids1,
                 int64_t N, int pass, const uint32_t* __restrict__ ghist, uint32_t* __restrict__ small,
                 WORD* status, WORD* status_next)
 {
@@ -161,13 +182,34 @@ k_onesweep_pass(const uint32_t* __restrict__ keys_in, const uint32_t* __restrict
     __shared__ uint32_t delta[kRadix];            // global slot of digit d = delta[d] + local slot
     __shared__ uint32_t skeys[kSortTile];
     __shared__ uint32_t sids[kSortTile];
-    __shared__ uint32_t s_tile;
+    __shared__ uint32_t s_tile, s_active;
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
     const int shift = pass * kRadixBits;
-    if (tid == 0) s_tile = atomicAdd(&small[1024 + pass], 1u);
+    // One lane takes the ticket and fetches the pass mask for the workgroup.  (The mask has a cache line
+    // of its own: a line that thousands of workgroups update with atomics is slow to read, and a load of
+    // it by every wavefront cost more than the rest of the pass.)  A skipped pass takes tickets nobody
+    // reads: the counters are per pass and reset with every sort.
+    if (tid == 0) {
+        s_tile = atomicAdd(&small[kSortTicketWord + pass], 1u);
+        s_active = small[kSortMaskWord];
+    }
     for (int i = tid; i < WAVES * kRadix; i += kSortThreads) (&whist[0][0])[i] = 0u;
     __syncthreads();
+    const uint32_t active = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_active);   // uniform: scalar branches and addresses
+    if (!((active >> pass) & 1u)) {     // skipped: only the words of the pass after this one are cleared
+        if (status_next && tid < kRadix) status_next[(int64_t)blockIdx.x * kRadix + tid] = WORD(0);
+        return;
+    }
+    // Buffers: the first pass that runs reads the anchors themselves and writes buffer 1, the next
+    // reads buffer 1 and writes buffer 0, and so on (k_decay knows from the same rule where the result is).
+    const int before = __popc(active & ((1u << pass) - 1u));
+    const bool first = before == 0;
+    const uint32_t* __restrict__ keys_in = (before & 1) ? keys1 : keys0;
+    const uint32_t* __restrict__ ids_in = (before & 1) ? ids1 : ids0;
+    uint32_t* __restrict__ keys_out = (before & 1) ? keys0 : keys1;
+    uint32_t* __restrict__ ids_out = (before & 1) ? ids0 : ids1;
+
     const int64_t tile = s_tile;
     if (status_next && tid < kRadix) status_next[tile * kRadix + tid] = WORD(0);   // words of the pass after this one
 
@@ -177,15 +219,29 @@ k_onesweep_pass(const uint32_t* __restrict__ keys_in, const uint32_t* __restrict
     const uint32_t valid = remaining < kSortTile ? (uint32_t)remaining : (uint32_t)kSortTile;
 
     uint32_t key[KPT], id[KPT], rank[KPT];
+    // two copies of the load loop, chosen once: inside one loop the choice would sit between the loads
+    // and keep them from being issued back to back
+    if (first) {
 #pragma unroll
-    for (int i = 0; i < KPT; ++i) {
-        const int64_t pos = wave_base + i * 64 + lane;
-        const bool ok = pos < N;
-        const int64_t pc = ok ? pos : N - 1;
-        const uint32_t kk = FIRST ? anchor_key(a, k, b, pc) : keys_in[pc];
-        const uint32_t ii = FIRST ? (uint32_t)pc : ids_in[pc];
-        key[i] = ok ? kk : 0xFFFFFFFFu;             // padding sorts last inside the tile
-        id[i] = ii;
+        for (int i = 0; i < KPT; ++i) {
+            const int64_t pos = wave_base + i * 64 + lane;
+            const bool ok = pos < N;
+            const int64_t pc = ok ? pos : N - 1;
+            const uint32_t kk = anchor_key(a, k, b, pc);
+            key[i] = ok ? kk : 0xFFFFFFFFu;         // padding sorts last inside the tile
+            id[i] = (uint32_t)pc;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < KPT; ++i) {
+            const int64_t pos = wave_base + i * 64 + lane;
+            const bool ok = pos < N;
+            const int64_t pc = ok ? pos : N - 1;
+            const uint32_t kk = keys_in[pc];
+            const uint32_t ii = ids_in[pc];
+            key[i] = ok ? kk : 0xFFFFFFFFu;
+            id[i] = ii;
+        }
     }
     const uint64_t lt_mask = (1ull << lane) - 1ull;
 #pragma unroll
@@ -242,7 +298,7 @@ k_onesweep_pass(const uint32_t* __restrict__ keys_in, const uint32_t* __restrict
                     x = __hip_atomic_load(status + t * kRadix + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     ++spins;
                 }
-                if ((x >> SH) == 0) { small[1028] = 1u; done = true; continue; }   // gave up: flag it, never hang
+                if ((x >> SH) == 0) { small[kSortErrorWord] = 1u; done = true; continue; }   // gave up: flag it, never hang
                 before += x & kMask;
                 if ((x >> SH) == 2) done = true;
             }
@@ -307,8 +363,17 @@ k_merge(const float* __restrict__ a, int64_t k, const float* __restrict__ b, int
     if (threadIdx.x < 2) split[threadIdx.x] = merge_split(a, k, b, n, threadIdx.x == 0 ? d0 : d1);
     __syncthreads();
     const int64_t ia0 = split[0], ia1 = split[1];
-    const int64_t ib0 = d0 - ia0, ib1 = d1 - ia1;
-    const int na = (int)(ia1 - ia0), nb = (int)(ib1 - ib0);
+    const int64_t ib0 = d0 - ia0;
+    // sorted inputs give 0 <= na, nb and na + nb = d1 - d0; inputs that are not ascending (the caller's
+    // flags were wrong, or NaN anchors) can give anything, so the counts are forced into that range
+    // (the result is then meaningless, but every access stays inside the arrays)
+    const int span = (int)(d1 - d0);
+    int na = (int)((ia1 - ia0) < 0 ? 0 : ((ia1 - ia0) > span ? span : (ia1 - ia0)));
+    const int nb = span - na;
+    for (int i = threadIdx.x; i < kMergeTile; i += kMergeThreads) {    // slots no rank lands on keep a valid id
+        okey[i] = 0xFFFFFFFFu;
+        oid[i] = (uint32_t)(d0 + i < N ? d0 + i : 0);
+    }
     for (int i = threadIdx.x; i < na + nb; i += kMergeThreads)
         stage[i] = i < na ? a[ia0 + i] : b[ib0 + (i - na)];
     __syncthreads();
@@ -353,8 +418,13 @@ k_merge(const float* __restrict__ a, int64_t k, const float* __restrict__ b, int
 // product of tens of thousands of them drifts by 1e-4 and more; key differences
 // telescope exactly.  (App. B.1's pair operator adds log-decays for the same reason.)
 __global__ void __launch_bounds__(256)
-k_decay(const uint32_t* __restrict__ keys, float* __restrict__ dh, float* __restrict__ pk, int64_t N)
+k_decay(const uint32_t* __restrict__ keys0, const uint32_t* __restrict__ keys1,
+        uint32_t* __restrict__ ids0, const uint32_t* __restrict__ ids1,
+        const uint32_t* __restrict__ ghist, float* __restrict__ dh, float* __restrict__ pk, int64_t N)
 {
+    // after an odd number of passes the sorted pairs sit in buffer 1 (ghist == nullptr: merge path, buffer 0)
+    const bool in1 = ghist != nullptr && (__popc(ghist[kSortMaskWord]) & 1);
+    const uint32_t* __restrict__ keys = in1 ? keys1 : keys0;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j <= N; j += stride) {
         float d = 0.0f;
@@ -365,6 +435,7 @@ k_decay(const uint32_t* __restrict__ keys, float* __restrict__ dh, float* __rest
         dh[j] = d;
         pk[j + 1] = j < N ? key_to_float(keys[j]) : __uint_as_float(0x7F800000u);
         if (j == 0) pk[0] = __uint_as_float(0xFF800000u);
+        if (in1 && j < N) ids0[j] = ids1[j];      // the plan's ids live in buffer 0
     }
 }
 
@@ -407,20 +478,15 @@ hipError_t launch_onesweep_sort(const float* a, int64_t k, const float* b, int64
     if (hgrid > 2048) hgrid = 2048;
     LAPLEX_TIMED("sort_hist", st, hipLaunchKernelGGL(k_sort_hist, dim3((unsigned)hgrid), dim3(kSortThreads), 0, st,
                                                      a, k, b, n, small, region[0], words));
+    LAPLEX_TIMED("sort_hist", st, hipLaunchKernelGGL(k_sort_plan, dim3(1), dim3(1024), 0, st, small, N));
     const dim3 grid((unsigned)tiles), block(kSortThreads);
     auto passes = [&](auto* r0, auto* r1) {
         using WORD = std::remove_pointer_t<decltype(r0)>;
-        const uint32_t* kin[4] = {nullptr, keys1, keys0, keys1};
-        const uint32_t* iin[4] = {nullptr, ids1, ids0, ids1};
-        uint32_t* kout[4] = {keys1, keys0, keys1, keys0};
-        uint32_t* iout[4] = {ids1, ids0, ids1, ids0};
         WORD* cur[4] = {r0, r1, r0, r1};
         WORD* nxt[4] = {r1, r0, r1, nullptr};
-        LAPLEX_TIMED("radix_scatter", st, hipLaunchKernelGGL((k_onesweep_pass<true, WORD>), grid, block, 0, st,
-                     kin[0], iin[0], a, k, b, kout[0], iout[0], N, 0, (const uint32_t*)small, small, cur[0], nxt[0]));
-        for (int p = 1; p < kSortPasses; ++p)
-            LAPLEX_TIMED("radix_scatter", st, hipLaunchKernelGGL((k_onesweep_pass<false, WORD>), grid, block, 0, st,
-                         kin[p], iin[p], a, k, b, kout[p], iout[p], N, p, (const uint32_t*)small, small, cur[p], nxt[p]));
+        for (int p = 0; p < kSortPasses; ++p)
+            LAPLEX_TIMED("radix_scatter", st, hipLaunchKernelGGL((k_onesweep_pass<WORD>), grid, block, 0, st,
+                         a, k, b, keys0, ids0, keys1, ids1, N, p, (const uint32_t*)small, small, cur[p], nxt[p]));
     };
     if (N <= (int64_t(1) << 30)) {
         uint32_t* r = reinterpret_cast<uint32_t*>(status);
@@ -440,9 +506,11 @@ hipError_t launch_merge(const float* a, int64_t k, const float* b, int64_t n,
     return hipGetLastError();
 }
 
-hipError_t launch_decay(const uint32_t* keys, float* dh, float* pk, int64_t N, hipStream_t st)
+hipError_t launch_decay(const uint32_t* keys0, const uint32_t* keys1, uint32_t* ids0, const uint32_t* ids1,
+                        const uint32_t* ghist, float* dh, float* pk, int64_t N, hipStream_t st)
 {
-    LAPLEX_TIMED("decay", st, hipLaunchKernelGGL(k_decay, dim3(grid_for(N + 1, 256)), dim3(256), 0, st, keys, dh, pk, N));
+    LAPLEX_TIMED("decay", st, hipLaunchKernelGGL(k_decay, dim3(grid_for(N + 1, 256)), dim3(256), 0, st,
+                                                 keys0, keys1, ids0, ids1, ghist, dh, pk, N));
     return hipGetLastError();
 }
 

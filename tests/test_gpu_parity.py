@@ -85,12 +85,17 @@ def anchors(kind, r, k, n):
     elif kind == "signed":
         a, b = r.normal(size=k) * 40, -r.uniform(0, 30, n)
         a[: k // 7] = 0.0; b[: n // 5] = -0.0
+    elif kind == "narrow":          # all in [1, 2): the top key byte is the same for every anchor
+        a, b = 1.0 + r.uniform(0, 1, k), 1.0 + r.uniform(0, 1, n)
+    elif kind == "small_ints":      # few mantissa bits: the two low key bytes are zero for every anchor
+        a, b = r.integers(0, 8, k).astype(np.float64), r.integers(0, 8, n).astype(np.float64)
     else:
         raise KeyError(kind)
     return a.astype(np.float32), b.astype(np.float32)
 
 
-KINDS = ["uniform", "ties", "all_equal", "huge_gaps", "clustered", "signed"]
+# "all_equal", "narrow" and "small_ints" have key bytes that are constant over all anchors: sort passes are skipped
+KINDS = ["uniform", "ties", "all_equal", "huge_gaps", "clustered", "signed", "narrow", "small_ints"]
 # (k, n, batch): single elements, ragged tails, several tiles of both lane geometries, two slabs
 SHAPES = [(1, 1, 1), (5, 1, 2), (1, 6, 1), (37, 53, 3), (100, 9000, 1), (9000, 100, 5),
           (3000, 21000, 1), (2500, 4000, 8), (513, 9000, 64), (300, 2100, 256), (70, 1500, 260),
@@ -394,3 +399,28 @@ def test_hip_graph_replays_match_eager():
         graph.replay(); torch.cuda.synchronize()
         for name, got, ref in zip(("y", "gx", "ga", "gb"), (y, gx, ga, gb), want):
             assert torch.equal(got, ref), f"replay {rep}: {name} differs from the eager result"
+
+
+# ------------------------------------------------------------------ non-finite anchors
+
+@pytest.mark.parametrize("sorted_flags", [0, B.LAPLEX_A_SORTED | B.LAPLEX_B_SORTED])
+def test_non_finite_anchors_do_not_fault(oracle, sorted_flags):
+    """NaN and infinite anchors are unsupported: values are unspecified, but the calls must run
+    to completion without touching memory out of bounds, and the library must work afterwards."""
+    r = np.random.default_rng(31)
+    k, n, batch = 700, 9000, 4
+    a, b = anchors("uniform", r, k, n)
+    a[::50] = np.nan; a[7] = np.inf; a[9] = -np.inf
+    b[::333] = np.nan; b[5] = np.inf; b[11] = -np.inf
+    x = r.normal(size=(n, batch)).astype(np.float32); g = r.normal(size=(k, batch)).astype(np.float32)
+    y, ws = gpu_apply(a, b, x, flags=sorted_flags | B.LAPLEX_SAVE_SCANS)
+    gpu_backward(a, b, x, g, flags=B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN, ws=ws)
+    gpu_gram(a, np.ascontiguousarray(x[:k]))
+    perm = gpu_perm(ws, k + n)
+    if sorted_flags == 0:                      # the radix sort still yields a permutation of all ids
+        assert np.array_equal(np.sort(perm), np.arange(k + n, dtype=np.uint32))
+    # and a clean problem right after is still exact
+    a2, b2 = anchors("uniform", r, k, n)
+    y2, _ = gpu_apply(a2, b2, x, ws=ws)
+    ref, tol = oracle.apply_scan(a2, b2, x)
+    assert_close("y", y2, ref, tol)
