@@ -535,99 +535,134 @@ k_scan_reduce(const ScanArgs A)
 
 // ---------------------------------------------------------------------------
 // reduce, wide batches (64 lanes across the batch, 4 columns each): one WAVEFRONT
-// per tile.  It folds the tile's rows chunk by chunk, so the summary needs no LDS
-// and no barrier, and many independent wavefronts keep loads in flight.  Same
-// outputs as k_scan_reduce.
+// per tile of 64 rows, no LDS, no barrier.  Same outputs as k_scan_reduce.
+//
+// Lane l first looks at row l of the tile: its id, its decays, and the two weights
+//   wf_l = exp(-(p_last - p_l))    (row l's share in the forward summary, decayed to the tile's last row)
+//   wb_l = exp(-(p_l - p_first))   (its share in the backward summary, decayed to the tile's first row)
+// taken from the anchors with one exponential each, so the summaries are plain weighted sums
+//   S_f = sum_l wf_l v_l,   S_b = sum_l wb_l v_l
+// with no dependence from row to row (the recurrence of Sec. 3 unrolled; App. B.1's pair operator
+// summed in closed form), and the strict sums are the part of them before the tile's last run head
+// (after its first one, seen from the right).  Ballots turn the per-row flags into wavefront-uniform
+// masks; ids and weights reach the scalar unit with readlane.  The data rows are then streamed with
+// every lane on its own 4 columns, eight rows in flight while the eight before them are folded in.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ float uniform_f(float v) { return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v))); }
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float lane_f(float v, int l) { return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l)); }
+__device__ __forceinline__ uint32_t lane_u(uint32_t v, int l) { return (uint32_t)__builtin_amdgcn_readlane((int)v, l); }
 __device__ __forceinline__ uint32_t uniform_u(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
 
+constexpr int kWideWaves = 4;     // wavefronts per workgroup of the wide reduce
+
+// What lane l knows about row l of a tile (loaded by WideMeta::fetch, no arithmetic yet).
+struct WideMeta {
+    uint32_t id;                                  // 0xFFFFFFFF past the end of the sequence
+    float dl, dr;                                 // decay into the row from the left / from the right
+    float p, p_first, p_last, p_before, p_after;  // anchors: own, the tile's first and last, the neighbours outside
+    bool live;
+    __device__ __forceinline__ void fetch(const ScanArgs& A, int64_t tile, int lane)
+    {
+        const int64_t tile_base = tile * 64, j = tile_base + lane;
+        live = j < A.N;
+        const int64_t jc = live ? j : A.N - 1;
+        const int64_t last = tile_base + 64 <= A.N ? tile_base + 63 : A.N - 1;     // the tile's last live row
+        id = A.ids[jc];
+        dl = A.dh[jc]; dr = A.dh[jc + 1];
+        p = A.pk[jc + 1]; p_first = A.pk[tile_base + 1]; p_last = A.pk[last + 1];   // pk is shifted by one
+        p_before = A.pk[tile_base]; p_after = A.pk[last + 2];
+    }
+};
+
 template <bool STRICT>
-__global__ void __launch_bounds__(kScanThreads)
+__global__ void __launch_bounds__(kWideWaves * 64)
 k_scan_reduce_wide(const ScanArgs A)
 {
-    constexpr int VEC = 4, ITEMS = kItemsVec4;
+    constexpr int VEC = 4, ROWS = 64, CH = 8;
+    static_assert(kScanWaves * kItemsVec4 == ROWS, "the wide geometry (one row-lane per wavefront) has 64 rows per tile");
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int64_t slot = (int64_t)blockIdx.x * kScanWaves + wave;
-    if (A.reduce_from_list ? slot >= A.counters[0] : slot >= A.l1.count) return;
-    const int64_t tile = A.reduce_from_list ? (int64_t)uniform_u(A.list_inj[slot]) : slot;
     const int64_t col0 = ((int64_t)blockIdx.y * 64 + lane) * VEC;
     const bool col_ok = col0 < A.batch;
-    const int64_t tile_base = tile * A.tile_rows;
-    const float tile_df = span_decay_f(A, tile_base, A.tile_rows), tile_db = span_decay_b(A, tile_base, A.tile_rows);
+    const float* const base = A.inj + (col_ok ? col0 : 0);     // lanes past the last column read (and drop) columns 0..3
 
-    // Every lane of the wavefront works on the same rows (its own 4 columns), so the rows' ids, decays and
-    // head flags are wavefront-uniform: they are made scalar, and what depends on them branches uniformly.
-    Seg<VEC, STRICT> tf = seg_identity<VEC, STRICT>(), tb = seg_identity<VEC, STRICT>();
-    int flags = 0;
-    TileRows<VEC> Tnext;
-    load_meta<VEC>(A, tile_base, Tnext);
-    for (int64_t row0 = tile_base; row0 < tile_base + A.tile_rows; row0 += ITEMS) {
-        uint32_t id[ITEMS];
-        float dh[ITEMS + 1];
-#pragma unroll
-        for (int i = 0; i < ITEMS; ++i) id[i] = uniform_u(Tnext.id[i]);
-#pragma unroll
-        for (int i = 0; i <= ITEMS; ++i) dh[i] = uniform_f(Tnext.dh[i]);
-        load_meta<VEC>(A, row0 + ITEMS, Tnext);     // one chunk ahead (clamped past the end; unused after the last chunk)
+    const int64_t slot = (int64_t)blockIdx.x * kWideWaves + wave;
+    if (A.reduce_from_list ? slot >= A.counters[0] : slot >= A.l1.count) return;
+    const int64_t tile = A.reduce_from_list ? (int64_t)uniform_u(A.list_inj[slot]) : slot;
+    WideMeta M;
+    M.fetch(A, tile, lane);
+    {
+        const uint32_t idv = M.live ? M.id : 0xFFFFFFFFu;
+        const float wf = expf(-(M.p_last - M.p)), wb = expf(-(M.p - M.p_first));
+        const float tile_df = expf(-(M.p_last - M.p_before)), tile_db = expf(-(M.p_after - M.p_first));
+        const bool inj = idv >= A.inj_lo && idv < A.inj_hi;       // never for rows past the end (id 0xFFFFFFFF)
+        const bool res = idv >= A.res_lo && idv < A.res_hi;
+        const uint64_t inj_mask = __ballot(inj);
+        const uint64_t hf_mask = __ballot(M.live && M.dl >= 0.0f), hb_mask = __ballot(M.live && M.dr >= 0.0f);
+        const int flags = (inj_mask ? kFlagInj : 0) | (__ballot(res) ? kFlagRes : 0);
+        // strict sums: rows before the last run head seen from the left / after the first one seen from the right
+        const int cut_f = hf_mask ? 63 - __clzll((long long)hf_mask) : 0;      // rows i < cut_f count
+        const int cut_b = hb_mask ? __ffsll((long long)hb_mask) - 1 : 63;      // rows i > cut_b count
 
-        float v[ITEMS][VEC];
-        bool inj[ITEMS];
+        // the strict sums as weighted sums of their own: the same weights, zero outside their rows
+        const float wqf = lane < cut_f ? wf : 0.0f, wqb = lane > cut_b ? wb : 0.0f;
+
+        float Sf[VEC], Qf[VEC], Sb[VEC], Qb[VEC];
 #pragma unroll
-        for (int i = 0; i < ITEMS; ++i) {
-            inj[i] = id[i] >= A.inj_lo && id[i] < A.inj_hi;
-            flags |= inj[i] ? kFlagInj : 0;
-            flags |= (id[i] >= A.res_lo && id[i] < A.res_hi) ? kFlagRes : 0;
+        for (int e = 0; e < VEC; ++e) { Sf[e] = Qf[e] = Sb[e] = Qb[e] = 0.0f; }
+
+        if (inj_mask) {
+            // Straight-line code: no branch around any load (a row that is not injected reads row 0 and
+            // its bits are masked away), so the loads of the next eight rows stay in flight while the
+            // last eight are folded in.
+            v4f buf[2][CH];
+            auto issue = [&](int c0, v4f* dst) {
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) v[i][e] = 0.0f;
-            if (inj[i] && col_ok) load_vec<VEC>(v[i], A.inj + (int64_t)(id[i] - A.inj_lo) * A.ld_inj + col0);
-        }
-        // forward: rows in order
-#pragma unroll
-        for (int i = 0; i < ITEMS; ++i) {
-            const bool h = id[i] != 0xFFFFFFFFu && dh[i] >= 0.0f;
-            if (h) {
-                if (STRICT) {
-                    tf.H = 1;
-#pragma unroll
-                    for (int e = 0; e < VEC; ++e) tf.Q[e] = dh[i] * tf.S[e];
+                for (int i = 0; i < CH; ++i) {
+                    const int row = c0 + i;
+                    const uint32_t id = lane_u(idv, row);
+                    const int64_t r = ((inj_mask >> row) & 1ull) ? (int64_t)(id - A.inj_lo) : 0;
+                    dst[i] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(base + r * A.ld_inj));
                 }
+            };
+            auto fold = [&](int c0, const v4f* src) {
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) tf.S[e] = dh[i] * tf.S[e] + v[i][e];
-            } else if (inj[i]) {
+                for (int i = 0; i < CH; ++i) {
+                    const int row = c0 + i;
+                    const uint32_t keep = ((inj_mask >> row) & 1ull) ? 0xFFFFFFFFu : 0u;     // scalar
+                    const float f = lane_f(wf, row), b = lane_f(wb, row);
+                    float x[VEC];
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) tf.S[e] += v[i][e];
+                    for (int e = 0; e < VEC; ++e) x[e] = __uint_as_float(__float_as_uint(src[i][e]) & keep);
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) { Sf[e] += f * x[e]; Sb[e] += b * x[e]; }
+                    if (STRICT) {
+                        const float qf = lane_f(wqf, row), qb = lane_f(wqb, row);
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) { Qf[e] += qf * x[e]; Qb[e] += qb * x[e]; }
+                    }
+                }
+            };
+            // (groups of eight rows with nothing injected are skipped: uniform branches)
+            if (inj_mask & 0xFFull) issue(0, buf[0]);
+#pragma unroll
+            for (int c = 0; c < ROWS / CH; ++c) {
+                if (c + 1 < ROWS / CH) { if ((inj_mask >> ((c + 1) * CH)) & 0xFFull) issue((c + 1) * CH, buf[(c + 1) & 1]); }
+                if ((inj_mask >> (c * CH)) & 0xFFull) fold(c * CH, buf[c & 1]);
             }
         }
-        // backward: this chunk's rows in reverse, then prepended to what the earlier chunks gave
-        Seg<VEC, STRICT> cb = seg_identity<VEC, STRICT>();
-        float cbD = 1.0f;
+
+        Seg<VEC, STRICT> tf = seg_identity<VEC, STRICT>(), tb = seg_identity<VEC, STRICT>();
 #pragma unroll
-        for (int i = ITEMS - 1; i >= 0; --i) {
-            const bool h = id[i] != 0xFFFFFFFFu && dh[i + 1] >= 0.0f;
-            if (h) {
-                if (STRICT) {
-                    cb.H = 1;
-#pragma unroll
-                    for (int e = 0; e < VEC; ++e) cb.Q[e] = dh[i + 1] * cb.S[e];
-                }
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) cb.S[e] = dh[i + 1] * cb.S[e] + v[i][e];
-                cbD *= dh[i + 1];
-            } else if (inj[i]) {
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) cb.S[e] += v[i][e];
-            }
-        }
-        cb.D = cbD;
-        tb = seg_compose<VEC, STRICT>(cb, tb);      // backward order: these (later) rows come before the earlier ones
+        for (int e = 0; e < VEC; ++e) { tf.S[e] = Sf[e]; tb.S[e] = Sb[e]; if (STRICT) { tf.Q[e] = Qf[e]; tb.Q[e] = Qb[e]; } }
+        tf.D = tf.C = tile_df;      // the tile's decay from the anchors
+        tb.D = tb.C = tile_db;
+        if (STRICT) { tf.H = hf_mask ? 1 : 0; tb.H = hb_mask ? 1 : 0; }
+        const bool sw = lane == 0 && blockIdx.y == 0;
+        store_level_seg<VEC, STRICT>(A.l1, 0, tile, A.bpad, col0, col_ok, sw, tf, (float)flags);
+        store_level_seg<VEC, STRICT>(A.l1, 1, tile, A.bpad, col0, col_ok, sw, tb, (float)flags);
     }
-    tf.D = tf.C = tile_df;      // the tile's decay from the anchors, not the product of 64 row decays
-    tb.D = tb.C = tile_db;
-    const bool sw = lane == 0 && blockIdx.y == 0;
-    store_level_seg<VEC, STRICT>(A.l1, 0, tile, A.bpad, col0, col_ok, sw, tf, (float)flags);
-    store_level_seg<VEC, STRICT>(A.l1, 1, tile, A.bpad, col0, col_ok, sw, tb, (float)flags);
 }
 
 // ---------------------------------------------------------------------------
@@ -1140,8 +1175,8 @@ void launch_all(const ScanArgs& A, const ScanGeom& g, const std::string& tag, hi
                       fp = "scan_down_sparse." + tag;
     if (VEC == 4 && g.bv == 64) {     // one wavefront per tile
         const int64_t slots = A.reduce_from_list ? rcap : g.tiles;
-        const dim3 wgrid((unsigned)((slots + kScanWaves - 1) / kScanWaves), (unsigned)g.slabs);
-        LAPLEX_TIMED(fr.c_str(), st, hipLaunchKernelGGL((k_scan_reduce_wide<STRICT>), wgrid, block, 0, st, A));
+        const dim3 wgrid((unsigned)((slots + kWideWaves - 1) / kWideWaves), (unsigned)g.slabs);
+        LAPLEX_TIMED(fr.c_str(), st, hipLaunchKernelGGL((k_scan_reduce_wide<STRICT>), wgrid, dim3(kWideWaves * 64), 0, st, A));
     } else {
         LAPLEX_TIMED(fr.c_str(), st, hipLaunchKernelGGL((k_scan_reduce<VEC, STRICT>), rgrid, block, 0, st, A));
     }
