@@ -43,14 +43,22 @@ constexpr int kStageMaxBatch = 8;
 constexpr int kSpineItems = 8;    // tile summaries per row-lane in the chunked spine kernels
 constexpr int kSpineThreads = 1024;
 
+// The rows a downsweep workgroup owns are a "block" (tile_rows of them).  The spine works on
+// "tiles": one block each, except in the wide geometry (64 lanes across the batch, 4 columns per
+// lane, 64 rows per block), where a tile is 2^kWideSubShift consecutive blocks: a summary or a carry
+// is then 4 * batch bytes per 64 * 4 * batch bytes of data, and fewer, larger ones are cheaper.
+constexpr int kWideSubShift = 3;
+
 struct ScanGeom {
     int vec;          // 1 or 4 batch columns per lane
     int items;        // rows per row-lane
     int bv;           // lanes across the batch (power of two, <= 64)
     int rv;           // row-lanes per wavefront
     int slabs;        // ceil(batch / (bv * vec)): blockIdx.y
-    int tile_rows;    // kScanWaves * rv * items
-    int64_t tiles;    // ceil(N / tile_rows)
+    int tile_rows;    // rows per block: kScanWaves * rv * items
+    int sub_shift;    // log2(blocks per tile)
+    int64_t blocks;   // ceil(N / tile_rows)
+    int64_t tiles;    // ceil(blocks / 2^sub_shift)
     int chunk_tiles;  // tiles summarised by one workgroup of the chunked spine: kScanWaves * rv * kSpineItems
     int64_t chunks;   // ceil(tiles / chunk_tiles)
 };
@@ -68,7 +76,9 @@ inline ScanGeom scan_geom(int64_t N, int64_t batch, int vec)
     g.slabs = (int)((groups + g.bv - 1) / g.bv);
     if (g.slabs < 1) g.slabs = 1;
     g.tile_rows = kScanWaves * g.rv * g.items;
-    g.tiles = (N + g.tile_rows - 1) / g.tile_rows;
+    g.sub_shift = (vec == 4 && g.bv == 64) ? kWideSubShift : 0;
+    g.blocks = (N + g.tile_rows - 1) / g.tile_rows;
+    g.tiles = (g.blocks + (int64_t(1) << g.sub_shift) - 1) >> g.sub_shift;
     g.chunk_tiles = kScanWaves * g.rv * kSpineItems;
     g.chunks = (g.tiles + g.chunk_tiles - 1) / g.chunk_tiles;
     return g;
@@ -101,11 +111,14 @@ struct Layout {
     size_t off_car_f = 0;        // f32[2][tiles][bpad]         carry F
     size_t off_car_e = 0;        // f32[2][tiles][bpad]         carry E
     size_t off_red = 0;          // f32[slabs][N]               per-slab partial row reductions
-    size_t off_lists = 0;        // u32[2][tiles] tile lists + u32[64] counters (sparse problems)
+    size_t off_lists = 0;        // u32[tiles] tile list, u32[blocks] block list, u32[64] counters (sparse problems)
+    size_t off_blk_flags = 0;    // u32[blocks]                 what each block holds (injected rows, result rows)
+    size_t off_blk_f = 0;        // f32[2][blocks][bpad]        carry F into a block from the start of its tile (wide geometry)
+    size_t off_blk_e = 0;        // f32[2][blocks][bpad]        the same, strict
     size_t off_stage = 0;        // f32[N][batch], narrow batches only: this problem's injected rows in sorted order
     // second level of the spine: the same five arrays over chunks of tiles
     size_t off_agg2_scalar = 0, off_agg2_s = 0, off_agg2_q = 0, off_car2_f = 0, off_car2_e = 0;
-    int64_t max_tiles = 0, max_chunks = 0;
+    int64_t max_tiles = 0, max_blocks = 0, max_chunks = 0;
     size_t total = 0;
 };
 
@@ -137,6 +150,8 @@ inline Layout make_layout(int64_t N, int64_t zrows, int64_t batch)
     size_t c = o;
     const ScanGeom g1 = scan_geom(N, batch, 1), g4 = scan_geom(N, batch, 4);
     L.max_tiles = g1.tiles > g4.tiles ? g1.tiles : g4.tiles;
+    L.max_blocks = g1.blocks > g4.blocks ? g1.blocks : g4.blocks;
+    const size_t per_blk = sizeof(float) * 2 * (size_t)L.max_blocks * (size_t)L.bpad;
     const int max_slabs = g1.slabs > g4.slabs ? g1.slabs : g4.slabs;
     const size_t per = sizeof(float) * 2 * (size_t)L.max_tiles * (size_t)L.bpad;
     L.off_agg_scalar = c; c = align_up(c + sizeof(float) * 4 * 2 * (size_t)L.max_tiles);
@@ -146,7 +161,10 @@ inline Layout make_layout(int64_t N, int64_t zrows, int64_t batch)
     L.off_car_e = c;      c = align_up(c + per);
     L.off_red = c;
     if (max_slabs > 1) c = align_up(c + sizeof(float) * (size_t)max_slabs * (size_t)N);
-    L.off_lists = c; c = align_up(c + sizeof(uint32_t) * (2 * (size_t)L.max_tiles + 64));
+    L.off_lists = c; c = align_up(c + sizeof(uint32_t) * ((size_t)L.max_tiles + (size_t)L.max_blocks + 64));
+    L.off_blk_flags = c; c = align_up(c + sizeof(uint32_t) * (size_t)L.max_blocks);
+    L.off_blk_f = c;     c = align_up(c + per_blk);
+    L.off_blk_e = c;     c = align_up(c + per_blk);
     L.off_stage = c; c = align_up(c + stage_bytes);
     L.max_chunks = g1.chunks > g4.chunks ? g1.chunks : g4.chunks;
     const size_t per2 = sizeof(float) * 2 * (size_t)L.max_chunks * (size_t)L.bpad;

@@ -58,13 +58,20 @@ struct ScanArgs {
     float* stage; const float* wstage;   // sorted-order copies of the injected rows / of the weights (narrow batches)
     int64_t batch, bpad;
     int bv, bv_log2, rv, tile_rows, slabs, chunk_tiles;
+    // A downsweep workgroup owns a block of tile_rows rows; the spine's tiles (level 1) are
+    // 2^sub_shift consecutive blocks, spine_rows rows (sub_shift > 0 in the wide geometry only).
+    int sub_shift; int64_t spine_rows, blocks;
+    uint32_t* blk_flags;  // [blocks] kFlagInj | kFlagRes
+    float* blk_f;         // [2][blocks][bpad] state entering a block when its tile starts from zero (sub_shift > 0)
+    float* blk_e;         // [2][blocks][bpad] the same, strict channel
     Level l1, l2;
     float* red_partial;   // [slabs][res rows] when slabs > 1
     // sparse problems (few injected or few result rows): the metadata kernel lists the tiles that need
     // the heavy kernels, which then launch one workgroup per list entry instead of one per tile
     uint32_t* list_inj;   // tiles that hold injected rows
-    uint32_t* list_both;  // tiles that hold injected and result rows
+    uint32_t* list_both;  // blocks that hold injected and result rows
     uint32_t* counters;   // [0] = entries of list_inj, [1] = entries of list_both
+    // list_inj is written by the metadata pass; list_both by the metadata pass if it runs, else by the reduce
     int reduce_from_list, down_from_list;
 };
 
@@ -408,30 +415,34 @@ k_scan_meta(const ScanArgs A)
     const int64_t tile = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (tile >= A.l1.count) return;
     int Hf = 0, Hb = 0, fl = 0;
-    const int64_t base = tile * A.tile_rows;
-    const float Df = span_decay_f(A, base, A.tile_rows), Db = span_decay_b(A, base, A.tile_rows);
-    for (int o = 0; o < A.tile_rows; o += 64) {
+    const int64_t base = tile * A.spine_rows;
+    const float Df = span_decay_f(A, base, A.spine_rows), Db = span_decay_b(A, base, A.spine_rows);
+    for (int64_t o = 0; o < A.spine_rows && base + o < A.N; o += 64) {
         const int64_t j = base + o + lane;
         const bool live = j < A.N;
         const int64_t jc = live ? j : A.N - 1;
         const uint32_t id = A.ids[jc];
         const float df = A.dh[jc], db = A.dh[jc + 1];
-        const bool hf = live && df >= 0.0f, hb = live && db >= 0.0f;
-        Hf |= hf ? 1 : 0; Hb |= hb ? 1 : 0;
-        fl |= (live && id >= A.inj_lo && id < A.inj_hi) ? kFlagInj : 0;
-        fl |= (live && id >= A.res_lo && id < A.res_hi) ? kFlagRes : 0;
-    }
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) {
-        Hf |= __shfl_xor(Hf, m); Hb |= __shfl_xor(Hb, m); fl |= __shfl_xor(fl, m);
+        Hf |= __ballot(live && df >= 0.0f) ? 1 : 0;
+        Hb |= __ballot(live && db >= 0.0f) ? 1 : 0;
+        const int here = (__ballot(live && id >= A.inj_lo && id < A.inj_hi) ? kFlagInj : 0) |
+                         (__ballot(live && id >= A.res_lo && id < A.res_hi) ? kFlagRes : 0);
+        fl |= here;
+        if (A.sub_shift && lane == 0) {     // wide geometry: these 64 rows are one block
+            const int64_t blk = (base + o) >> 6;
+            A.blk_flags[blk] = (uint32_t)here;
+            if (A.down_from_list && here == (kFlagInj | kFlagRes)) A.list_both[atomicAdd(&A.counters[1], 1u)] = (uint32_t)blk;
+        }
     }
     if (lane == 0) {
         A.l1.scalar[tile] = make_float4(Df, Df, (float)Hf, (float)fl);
         A.l1.scalar[A.l1.count + tile] = make_float4(Db, Db, (float)Hb, (float)fl);
         // a list is built only when its kernel will be driven by it (then it is short by construction)
         if (A.reduce_from_list && (fl & kFlagInj)) A.list_inj[atomicAdd(&A.counters[0], 1u)] = (uint32_t)tile;
-        if (A.down_from_list && (fl & (kFlagInj | kFlagRes)) == (kFlagInj | kFlagRes))
-            A.list_both[atomicAdd(&A.counters[1], 1u)] = (uint32_t)tile;
+        if (!A.sub_shift) {                 // block = tile
+            A.blk_flags[tile] = (uint32_t)fl;
+            if (A.down_from_list && fl == (kFlagInj | kFlagRes)) A.list_both[atomicAdd(&A.counters[1], 1u)] = (uint32_t)tile;
+        }
     }
 }
 
@@ -480,6 +491,11 @@ k_scan_reduce(const ScanArgs A)
     __syncthreads();
     if (c == 0 && mine) atomicOr(&tile_flags, mine);
     __syncthreads();
+    if (tid == 0 && blockIdx.y == 0) {      // in this geometry a tile is one block
+        A.blk_flags[tile] = (uint32_t)tile_flags;
+        if (A.down_from_list && !A.reduce_from_list && tile_flags == (kFlagInj | kFlagRes))
+            A.list_both[atomicAdd(&A.counters[1], 1u)] = (uint32_t)tile;
+    }
     float v[ITEMS][VEC];
     if (tile_flags & kFlagInj) {     // uniform: a tile with nothing injected reads no data rows
         load_injected<VEC>(A, T, col0, col_ok, v);
@@ -534,88 +550,95 @@ k_scan_reduce(const ScanArgs A)
 }
 
 // ---------------------------------------------------------------------------
-// reduce, wide batches (64 lanes across the batch, 4 columns each): one WAVEFRONT
-// per tile of 64 rows, no LDS, no barrier.  Same outputs as k_scan_reduce.
+// reduce, wide batches (64 lanes across the batch, 4 columns each): a workgroup per tile of
+// eight 64-row blocks, one WAVEFRONT per block.  Same outputs as k_scan_reduce, plus, for the blocks
+// that hold result rows, the state the block starts from when its tile starts from zero (the
+// downsweeps add the tile's carry, decayed to the block by one exponential).
 //
-// Lane l first looks at row l of the tile: its id, its decays, and the two weights
-//   wf_l = exp(-(p_last - p_l))    (row l's share in the forward summary, decayed to the tile's last row)
-//   wb_l = exp(-(p_l - p_first))   (its share in the backward summary, decayed to the tile's first row)
+// Lane l first looks at row l of the block: its id, its decays, and the two weights
+//   wf_l = exp(-(p_last - p_l))    (row l's share in the forward summary, decayed to the block's last row)
+//   wb_l = exp(-(p_l - p_first))   (its share in the backward summary, decayed to the block's first row)
 // taken from the anchors with one exponential each, so the summaries are plain weighted sums
 //   S_f = sum_l wf_l v_l,   S_b = sum_l wb_l v_l
 // with no dependence from row to row (the recurrence of Sec. 3 unrolled; App. B.1's pair operator
-// summed in closed form), and the strict sums are the part of them before the tile's last run head
+// summed in closed form), and the strict sums are the part of them before the block's last run head
 // (after its first one, seen from the right).  Ballots turn the per-row flags into wavefront-uniform
 // masks; ids and weights reach the scalar unit with readlane.  The data rows are then streamed with
-// every lane on its own 4 columns, eight rows in flight while the eight before them are folded in.
+// every lane on its own 4 columns.  A summary written to memory costs far more than its share of the
+// bytes (writes interleaved with a read stream), hence one per eight blocks and not one per block.
 // ---------------------------------------------------------------------------
 typedef float v4f __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float lane_f(float v, int l) { return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l)); }
 __device__ __forceinline__ uint32_t lane_u(uint32_t v, int l) { return (uint32_t)__builtin_amdgcn_readlane((int)v, l); }
-__device__ __forceinline__ uint32_t uniform_u(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
 
-constexpr int kWideWaves = 4;     // wavefronts per workgroup of the wide reduce
-
-// What lane l knows about row l of a tile (loaded by WideMeta::fetch, no arithmetic yet).
+// What lane l knows about row l of a 64-row block (loads only, no arithmetic yet).
 struct WideMeta {
-    uint32_t id;                                  // 0xFFFFFFFF past the end of the sequence
+    uint32_t id;
     float dl, dr;                                 // decay into the row from the left / from the right
-    float p, p_first, p_last, p_before, p_after;  // anchors: own, the tile's first and last, the neighbours outside
-    bool live;
-    __device__ __forceinline__ void fetch(const ScanArgs& A, int64_t tile, int lane)
+    float p, p_first, p_last, p_before, p_after;  // anchors: own, the block's first and last, the neighbours outside
+    bool live;                                    // false past the end of the sequence
+    __device__ __forceinline__ void fetch(const ScanArgs& A, int64_t blk, int lane)
     {
-        const int64_t tile_base = tile * 64, j = tile_base + lane;
+        const int64_t blk_base = blk * 64, j = blk_base + lane;
         live = j < A.N;
         const int64_t jc = live ? j : A.N - 1;
-        const int64_t last = tile_base + 64 <= A.N ? tile_base + 63 : A.N - 1;     // the tile's last live row
+        const int64_t last = blk_base + 64 <= A.N ? blk_base + 63 : A.N - 1;     // the block's last live row
         id = A.ids[jc];
         dl = A.dh[jc]; dr = A.dh[jc + 1];
-        p = A.pk[jc + 1]; p_first = A.pk[tile_base + 1]; p_last = A.pk[last + 1];   // pk is shifted by one
-        p_before = A.pk[tile_base]; p_after = A.pk[last + 2];
+        p = A.pk[jc + 1]; p_first = A.pk[blk_base + 1]; p_last = A.pk[last + 1];   // pk is shifted by one
+        p_before = A.pk[blk_base]; p_after = A.pk[last + 2];
     }
 };
 
 template <bool STRICT>
-__global__ void __launch_bounds__(kWideWaves * 64)
+__global__ void __launch_bounds__(kScanThreads)
 k_scan_reduce_wide(const ScanArgs A)
 {
     constexpr int VEC = 4, ROWS = 64, CH = 8;
-    static_assert(kScanWaves * kItemsVec4 == ROWS, "the wide geometry (one row-lane per wavefront) has 64 rows per tile");
+    static_assert(kScanWaves * kItemsVec4 == ROWS, "the wide geometry (one row-lane per wavefront) has 64 rows per block");
+    static_assert(kScanWaves == 1 << kWideSubShift, "one wavefront per block of the tile");
+    __shared__ WaveSegs<VEC> W;
+    __shared__ int tile_flags;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int64_t col0 = ((int64_t)blockIdx.y * 64 + lane) * VEC;
     const bool col_ok = col0 < A.batch;
     const float* const base = A.inj + (col_ok ? col0 : 0);     // lanes past the last column read (and drop) columns 0..3
 
-    const int64_t slot = (int64_t)blockIdx.x * kWideWaves + wave;
-    if (A.reduce_from_list ? slot >= A.counters[0] : slot >= A.l1.count) return;
-    const int64_t tile = A.reduce_from_list ? (int64_t)uniform_u(A.list_inj[slot]) : slot;
-    WideMeta M;
-    M.fetch(A, tile, lane);
-    {
+    if (A.reduce_from_list && blockIdx.x >= A.counters[0]) return;
+    const int64_t tile = A.reduce_from_list ? (int64_t)A.list_inj[blockIdx.x] : (int64_t)blockIdx.x;
+    const int64_t blk = (tile << kWideSubShift) + wave;         // this wavefront's block
+    const bool blk_live = blk < A.blocks;
+    if (threadIdx.x == 0) tile_flags = 0;
+    __syncthreads();
+
+    float Sf[VEC], Qf[VEC], Sb[VEC], Qb[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) { Sf[e] = Qf[e] = Sb[e] = Qb[e] = 0.0f; }
+    float blk_df = 1.0f, blk_db = 1.0f;
+    int Hf = 0, Hb = 0, flags = 0;
+    if (blk_live) {
+        WideMeta M;
+        M.fetch(A, blk, lane);
         const uint32_t idv = M.live ? M.id : 0xFFFFFFFFu;
         const float wf = expf(-(M.p_last - M.p)), wb = expf(-(M.p - M.p_first));
-        const float tile_df = expf(-(M.p_last - M.p_before)), tile_db = expf(-(M.p_after - M.p_first));
+        blk_df = expf(-(M.p_last - M.p_before)); blk_db = expf(-(M.p_after - M.p_first));
         const bool inj = idv >= A.inj_lo && idv < A.inj_hi;       // never for rows past the end (id 0xFFFFFFFF)
         const bool res = idv >= A.res_lo && idv < A.res_hi;
         const uint64_t inj_mask = __ballot(inj);
         const uint64_t hf_mask = __ballot(M.live && M.dl >= 0.0f), hb_mask = __ballot(M.live && M.dr >= 0.0f);
-        const int flags = (inj_mask ? kFlagInj : 0) | (__ballot(res) ? kFlagRes : 0);
+        flags = (inj_mask ? kFlagInj : 0) | (__ballot(res) ? kFlagRes : 0);
+        Hf = hf_mask ? 1 : 0; Hb = hb_mask ? 1 : 0;
         // strict sums: rows before the last run head seen from the left / after the first one seen from the right
         const int cut_f = hf_mask ? 63 - __clzll((long long)hf_mask) : 0;      // rows i < cut_f count
         const int cut_b = hb_mask ? __ffsll((long long)hb_mask) - 1 : 63;      // rows i > cut_b count
-
         // the strict sums as weighted sums of their own: the same weights, zero outside their rows
         const float wqf = lane < cut_f ? wf : 0.0f, wqb = lane > cut_b ? wb : 0.0f;
 
-        float Sf[VEC], Qf[VEC], Sb[VEC], Qb[VEC];
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) { Sf[e] = Qf[e] = Sb[e] = Qb[e] = 0.0f; }
-
         if (inj_mask) {
-            // Straight-line code: no branch around any load (a row that is not injected reads row 0 and
-            // its bits are masked away), so the loads of the next eight rows stay in flight while the
-            // last eight are folded in.
+            // Straight-line code inside a group of eight rows: no branch around a load (a row that is not
+            // injected reads row 0 and its bits are masked away).
             v4f buf[2][CH];
             auto issue = [&](int c0, v4f* dst) {
 #pragma unroll
@@ -652,16 +675,68 @@ k_scan_reduce_wide(const ScanArgs A)
                 if ((inj_mask >> (c * CH)) & 0xFFull) fold(c * CH, buf[c & 1]);
             }
         }
+        if (lane == 0 && blockIdx.y == 0) {
+            A.blk_flags[blk] = (uint32_t)flags;
+            if (A.down_from_list && !A.reduce_from_list && flags == (kFlagInj | kFlagRes))
+                A.list_both[atomicAdd(&A.counters[1], 1u)] = (uint32_t)blk;
+        }
+        if (lane == 0 && flags) atomicOr(&tile_flags, flags);
+    }
 
-        Seg<VEC, STRICT> tf = seg_identity<VEC, STRICT>(), tb = seg_identity<VEC, STRICT>();
+    // The eight block summaries meet in LDS: each wavefront folds the ones before (after) its own into
+    // the state its block starts from when the tile starts from zero; the last (first) one also takes
+    // the tile's summary.
+    Seg<VEC, STRICT> mf = seg_identity<VEC, STRICT>(), mb = seg_identity<VEC, STRICT>();
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) { tf.S[e] = Sf[e]; tb.S[e] = Sb[e]; if (STRICT) { tf.Q[e] = Qf[e]; tb.Q[e] = Qb[e]; } }
-        tf.D = tf.C = tile_df;      // the tile's decay from the anchors
-        tb.D = tb.C = tile_db;
-        if (STRICT) { tf.H = hf_mask ? 1 : 0; tb.H = hb_mask ? 1 : 0; }
-        const bool sw = lane == 0 && blockIdx.y == 0;
-        store_level_seg<VEC, STRICT>(A.l1, 0, tile, A.bpad, col0, col_ok, sw, tf, (float)flags);
-        store_level_seg<VEC, STRICT>(A.l1, 1, tile, A.bpad, col0, col_ok, sw, tb, (float)flags);
+    for (int e = 0; e < VEC; ++e) { mf.S[e] = Sf[e]; mb.S[e] = Sb[e]; if (STRICT) { mf.Q[e] = Qf[e]; mb.Q[e] = Qb[e]; } }
+    mf.D = mf.C = blk_df; mb.D = mb.C = blk_db;
+    if (STRICT) { mf.H = Hf; mb.H = Hb; }
+    put_wave_seg<VEC, STRICT>(W, 0, wave, lane, mf);
+    put_wave_seg<VEC, STRICT>(W, 1, wave, lane, mb);
+    __syncthreads();
+    const int tflags = tile_flags;
+
+    float F[VEC], E[VEC], R[VEC], G[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) { F[e] = E[e] = R[e] = G[e] = 0.0f; }
+    const bool want_local = blk_live && (flags & kFlagRes) && (tflags & kFlagInj);     // uniform per wavefront
+    if (want_local || wave == kScanWaves - 1) {
+#pragma unroll 1
+        for (int w = 0; w < wave; ++w) seg_apply<VEC, STRICT>(get_wave_seg<VEC, STRICT>(W, 0, w, lane), F, E);
+    }
+    if (want_local || wave == 0) {
+#pragma unroll 1
+        for (int w = kScanWaves - 1; w > wave; --w) seg_apply<VEC, STRICT>(get_wave_seg<VEC, STRICT>(W, 1, w, lane), R, G);
+    }
+    if (want_local && col_ok) {
+        const int64_t o0 = blk * A.bpad + col0, o1 = (A.blocks + blk) * A.bpad + col0;
+        store_vec<VEC>(A.blk_f + o0, F);
+        store_vec<VEC>(A.blk_f + o1, R);
+        if (STRICT) { store_vec<VEC>(A.blk_e + o0, E); store_vec<VEC>(A.blk_e + o1, G); }
+    }
+    const int64_t tile_base = tile * A.spine_rows;
+    const bool sw = lane == 0 && blockIdx.y == 0;
+    if (wave == kScanWaves - 1) {           // the tile's forward summary = the state after the last block, from zero
+        int Ht = 0;
+        if (STRICT) { for (int w = 0; w < kScanWaves; ++w) Ht |= W.H[0][w]; }
+        seg_apply<VEC, STRICT>(mf, F, E);
+        Seg<VEC, STRICT> tf = seg_identity<VEC, STRICT>();
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) { tf.S[e] = F[e]; if (STRICT) tf.Q[e] = E[e]; }
+        tf.D = tf.C = span_decay_f(A, tile_base, A.spine_rows);     // from the anchors
+        if (STRICT) tf.H = Ht;
+        store_level_seg<VEC, STRICT>(A.l1, 0, tile, A.bpad, col0, col_ok, sw, tf, (float)tflags);
+    }
+    if (wave == 0) {
+        int Ht = 0;
+        if (STRICT) { for (int w = 0; w < kScanWaves; ++w) Ht |= W.H[1][w]; }
+        seg_apply<VEC, STRICT>(mb, R, G);
+        Seg<VEC, STRICT> tb = seg_identity<VEC, STRICT>();
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) { tb.S[e] = R[e]; if (STRICT) tb.Q[e] = G[e]; }
+        tb.D = tb.C = span_decay_b(A, tile_base, A.spine_rows);
+        if (STRICT) tb.H = Ht;
+        store_level_seg<VEC, STRICT>(A.l1, 1, tile, A.bpad, col0, col_ok, sw, tb, (float)tflags);
     }
 }
 
@@ -703,10 +778,10 @@ k_spine_reduce(const ScanArgs A)
         const int64_t tiles_here = A.l1.count - chunk * A.chunk_tiles < A.chunk_tiles ? A.l1.count - chunk * A.chunk_tiles
                                                                                       : A.chunk_tiles;
         if (dir == 0) {
-            t.D = span_decay_f(A, chunk * A.chunk_tiles * A.tile_rows, tiles_here * A.tile_rows);
+            t.D = span_decay_f(A, chunk * A.chunk_tiles * A.spine_rows, tiles_here * A.spine_rows);
         } else {
             const int64_t t_hi = A.l1.count - 1 - chunk * A.chunk_tiles;          // first tile in scan order
-            t.D = span_decay_b(A, (t_hi + 1 - tiles_here) * A.tile_rows, tiles_here * A.tile_rows);
+            t.D = span_decay_b(A, (t_hi + 1 - tiles_here) * A.spine_rows, tiles_here * A.spine_rows);
         }
         store_level_seg<VEC, STRICT>(A.l2, dir, chunk, A.bpad, col0, col_ok, c == 0 && blockIdx.y == 0, t, 0.0f);
     }
@@ -809,13 +884,13 @@ k_spine_down(const ScanArgs A)
     if (q0 < A.l1.count) {
         const int64_t before = q0 - chunk * A.chunk_tiles;               // tiles of the chunk ahead of q0 in scan order
         if (dir == 0) {
-            const int64_t r0 = chunk * A.chunk_tiles * A.tile_rows;
-            enter_state<VEC, STRICT>(F, E, Fc, Ec, span_decay_f(A, r0, before * A.tile_rows),
-                                     span_head_f(A, r0, before * A.tile_rows));
+            const int64_t r0 = chunk * A.chunk_tiles * A.spine_rows;
+            enter_state<VEC, STRICT>(F, E, Fc, Ec, span_decay_f(A, r0, before * A.spine_rows),
+                                     span_head_f(A, r0, before * A.spine_rows));
         } else {
-            const int64_t r0 = (A.l1.count - q0) * A.tile_rows;           // first row after this row-lane's first tile
-            enter_state<VEC, STRICT>(F, E, Fc, Ec, span_decay_b(A, r0, before * A.tile_rows),
-                                     span_head_b(A, r0, before * A.tile_rows));
+            const int64_t r0 = (A.l1.count - q0) * A.spine_rows;           // first row after this row-lane's first tile
+            enter_state<VEC, STRICT>(F, E, Fc, Ec, span_decay_b(A, r0, before * A.spine_rows),
+                                     span_head_b(A, r0, before * A.spine_rows));
         }
     }
 #pragma unroll
@@ -844,6 +919,47 @@ __device__ __forceinline__ void emit_row_sum(const ScanArgs& A, float acc, int b
     }
 }
 
+// Carries into a block, forward (Fc, Ec) and backward (Rc, Gc).  A block that is a tile of its own
+// reads them as the spine left them.  In the wide geometry the spine's carries belong to the tile of
+// 2^sub_shift blocks: the block's carry is the tile's, decayed to the block by one exponential of an
+// anchor difference, plus the state the reduce found for the block with the tile starting from zero
+// (kept only for tiles that hold injected rows; zero otherwise).
+template <int VEC, bool STRICT>
+__device__ __forceinline__ void load_block_carries(const ScanArgs& A, int64_t blk, int64_t col0, bool col_ok,
+                                                   float* Fc, float* Ec, float* Rc, float* Gc)
+{
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) { Fc[e] = Ec[e] = Rc[e] = Gc[e] = 0.0f; }
+    const int64_t tile = blk >> A.sub_shift;
+    float Ft[VEC], Et[VEC], Rt[VEC], Gt[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) { Ft[e] = Et[e] = Rt[e] = Gt[e] = 0.0f; }
+    if (col_ok) {
+        const int64_t o0 = tile * A.bpad + col0, o1 = (A.l1.count + tile) * A.bpad + col0;
+        load_vec<VEC>(Ft, A.l1.car_f + o0);
+        load_vec<VEC>(Rt, A.l1.car_f + o1);
+        if (STRICT) { load_vec<VEC>(Et, A.l1.car_e + o0); load_vec<VEC>(Gt, A.l1.car_e + o1); }
+    }
+    if (A.sub_shift == 0) {         // uniform
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) { Fc[e] = Ft[e]; Ec[e] = Et[e]; Rc[e] = Rt[e]; Gc[e] = Gt[e]; }
+        return;
+    }
+    const bool tile_inj = ((int)A.l1.scalar[tile].w & kFlagInj) != 0;
+    if (tile_inj && col_ok) {
+        const int64_t o0 = blk * A.bpad + col0, o1 = (A.blocks + blk) * A.bpad + col0;
+        load_vec<VEC>(Fc, A.blk_f + o0);
+        load_vec<VEC>(Rc, A.blk_f + o1);
+        if (STRICT) { load_vec<VEC>(Ec, A.blk_e + o0); load_vec<VEC>(Gc, A.blk_e + o1); }
+    }
+    const int64_t tile_base = tile * A.spine_rows, blk_base = blk * A.tile_rows;
+    const int64_t blk_end = blk_base + A.tile_rows, tile_end = tile_base + A.spine_rows;
+    enter_state<VEC, STRICT>(Fc, Ec, Ft, Et, span_decay_f(A, tile_base, blk_base - tile_base),
+                             span_head_f(A, tile_base, blk_base - tile_base));
+    enter_state<VEC, STRICT>(Rc, Gc, Rt, Gt, span_decay_b(A, blk_end, tile_end - blk_end),
+                             span_head_b(A, blk_end, tile_end - blk_end));
+}
+
 // ---------------------------------------------------------------------------
 // downsweep: tiles that hold both injected and result rows
 // ---------------------------------------------------------------------------
@@ -860,8 +976,8 @@ k_scan_down(const ScanArgs A)
     WaveSegs<VEC>& W = *reinterpret_cast<WaveSegs<VEC>*>(smem);
     float* const ef = reinterpret_cast<float*>(smem) + (size_t)threadIdx.x * VEC;   // row i at ef[i * kScanThreads * VEC]
     if (A.down_from_list && blockIdx.x >= A.counters[1]) return;
-    const int64_t tile = A.down_from_list ? A.list_both[blockIdx.x] : blockIdx.x;
-    const int flags = (int)A.l1.scalar[tile].w;
+    const int64_t tile = A.down_from_list ? A.list_both[blockIdx.x] : blockIdx.x;     // the block this workgroup owns
+    const int flags = (int)A.blk_flags[tile];
     if ((flags & (kFlagInj | kFlagRes)) != (kFlagInj | kFlagRes)) return;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -909,16 +1025,9 @@ k_scan_down(const ScanArgs A)
         }
     };
 
-    // carries into the tile
+    // carries into the block
     float Fc[VEC], Ec[VEC], Rc[VEC], Gc[VEC];
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) { Fc[e] = Ec[e] = Rc[e] = Gc[e] = 0.0f; }
-    if (col_ok) {
-        const int64_t o0 = tile * A.bpad + col0, o1 = (A.l1.count + tile) * A.bpad + col0;
-        load_vec<VEC>(Fc, A.l1.car_f + o0);
-        load_vec<VEC>(Rc, A.l1.car_f + o1);
-        if (STRICT) { load_vec<VEC>(Ec, A.l1.car_e + o0); load_vec<VEC>(Gc, A.l1.car_e + o1); }
-    }
+    load_block_carries<VEC, STRICT>(A, tile, col0, col_ok, Fc, Ec, Rc, Gc);
     Seg<VEC, STRICT> fe, be;
     {
         Seg<VEC, STRICT> f = seg_identity<VEC, STRICT>();
@@ -1029,8 +1138,8 @@ __global__ void __launch_bounds__(kScanThreads)
 k_scan_down_sparse(const ScanArgs A)
 {
     constexpr int ITEMS = TileRows<VEC>::ITEMS;
-    const int64_t tile = blockIdx.x;
-    const int flags = (int)A.l1.scalar[tile].w;
+    const int64_t tile = blockIdx.x;                // the block this workgroup owns
+    const int flags = (int)A.blk_flags[tile];
     if ((flags & (kFlagInj | kFlagRes)) != kFlagRes) return;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -1052,14 +1161,7 @@ k_scan_down_sparse(const ScanArgs A)
     float wv[ITEMS][VEC];
     load_weights<VEC>(A, T, row0, col0, col_ok, want_red, wv);
     float Fin[VEC], Ein[VEC], Rin[VEC], Gin[VEC];
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) { Fin[e] = Ein[e] = Rin[e] = Gin[e] = 0.0f; }
-    if (col_ok) {
-        const int64_t o0 = tile * A.bpad + col0, o1 = (A.l1.count + tile) * A.bpad + col0;
-        load_vec<VEC>(Fin, A.l1.car_f + o0);
-        load_vec<VEC>(Rin, A.l1.car_f + o1);
-        if (STRICT) { load_vec<VEC>(Ein, A.l1.car_e + o0); load_vec<VEC>(Gin, A.l1.car_e + o1); }
-    }
+    load_block_carries<VEC, STRICT>(A, tile, col0, col_ok, Fin, Ein, Rin, Gin);
 
     // per-row cumulative decays inside this row-lane, from the left and from the right (at most ITEMS factors)
     float cf[ITEMS], cb[ITEMS];
@@ -1156,27 +1258,27 @@ template <int VEC, bool STRICT>
 void launch_all(const ScanArgs& A, const ScanGeom& g, const std::string& tag, hipStream_t st)
 {
     const dim3 block(kScanThreads);
-    const dim3 grid((unsigned)g.tiles, (unsigned)g.slabs);
-    // heavy kernels driven by the tile lists visit at most one tile per injected (and per result) row
+    const dim3 grid((unsigned)g.blocks, (unsigned)g.slabs);
+    // heavy kernels driven by the lists visit at most one tile per injected row (reduce) and one block
+    // per injected and per result row (downsweep)
     const int64_t inj_rows = (int64_t)A.inj_hi - A.inj_lo, res_rows = (int64_t)A.res_hi - A.res_lo;
     const int64_t rcap = inj_rows < g.tiles ? inj_rows : g.tiles;
     const int64_t both_rows = inj_rows < res_rows ? inj_rows : res_rows;
-    const int64_t dcap = both_rows < g.tiles ? both_rows : g.tiles;
+    const int64_t dcap = both_rows < g.blocks ? both_rows : g.blocks;
     const dim3 rgrid((unsigned)(A.reduce_from_list ? rcap : g.tiles), (unsigned)g.slabs);
-    const dim3 dgrid((unsigned)(A.down_from_list ? dcap : g.tiles), (unsigned)g.slabs);
+    const dim3 dgrid((unsigned)(A.down_from_list ? dcap : g.blocks), (unsigned)g.slabs);
     if (A.reduce_from_list || A.down_from_list) {
         const std::string fm = "scan_meta." + tag;
         LAPLEX_TIMED(fm.c_str(), st, hipLaunchKernelGGL(k_zero_counters, dim3(1), dim3(64), 0, st, A.counters));
-        LAPLEX_TIMED(fm.c_str(), st, hipLaunchKernelGGL(k_scan_meta, dim3((unsigned)((g.tiles + 3) / 4)), dim3(256), 0, st, A));
+        if (A.reduce_from_list)     // else the reduce sees every tile itself and lists the blocks for the downsweep
+            LAPLEX_TIMED(fm.c_str(), st, hipLaunchKernelGGL(k_scan_meta, dim3((unsigned)((g.tiles + 3) / 4)), dim3(256), 0, st, A));
     }
     const dim3 cgrid((unsigned)g.chunks, (unsigned)g.slabs, 2);
     const dim3 tgrid((unsigned)A.batch, 2);
     const std::string fr = "scan_reduce." + tag, fs = "scan_spine." + tag, fd = "scan_down." + tag,
                       fp = "scan_down_sparse." + tag;
-    if (VEC == 4 && g.bv == 64) {     // one wavefront per tile
-        const int64_t slots = A.reduce_from_list ? rcap : g.tiles;
-        const dim3 wgrid((unsigned)((slots + kWideWaves - 1) / kWideWaves), (unsigned)g.slabs);
-        LAPLEX_TIMED(fr.c_str(), st, hipLaunchKernelGGL((k_scan_reduce_wide<STRICT>), wgrid, dim3(kWideWaves * 64), 0, st, A));
+    if (VEC == 4 && g.sub_shift) {    // wide geometry: a workgroup per tile, a wavefront per block
+        LAPLEX_TIMED(fr.c_str(), st, hipLaunchKernelGGL((k_scan_reduce_wide<STRICT>), rgrid, block, 0, st, A));
     } else {
         LAPLEX_TIMED(fr.c_str(), st, hipLaunchKernelGGL((k_scan_reduce<VEC, STRICT>), rgrid, block, 0, st, A));
     }
@@ -1210,6 +1312,10 @@ hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStrea
     A.batch = p.batch; A.bpad = L.bpad;
     A.bv = g.bv; A.bv_log2 = ilog2(g.bv); A.rv = g.rv; A.tile_rows = g.tile_rows; A.slabs = g.slabs;
     A.chunk_tiles = g.chunk_tiles;
+    A.sub_shift = g.sub_shift; A.spine_rows = (int64_t)g.tile_rows << g.sub_shift; A.blocks = g.blocks;
+    A.blk_flags = reinterpret_cast<uint32_t*>(ws + L.off_blk_flags);
+    A.blk_f = reinterpret_cast<float*>(ws + L.off_blk_f);
+    A.blk_e = reinterpret_cast<float*>(ws + L.off_blk_e);
     A.l1 = Level{reinterpret_cast<float4*>(ws + L.off_agg_scalar), reinterpret_cast<float*>(ws + L.off_agg_s),
                  reinterpret_cast<float*>(ws + L.off_agg_q), reinterpret_cast<float*>(ws + L.off_car_f),
                  reinterpret_cast<float*>(ws + L.off_car_e), g.tiles};
@@ -1219,12 +1325,12 @@ hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStrea
     A.red_partial = reinterpret_cast<float*>(ws + L.off_red);
     A.list_inj = reinterpret_cast<uint32_t*>(ws + L.off_lists);
     A.list_both = A.list_inj + L.max_tiles;
-    A.counters = A.list_both + L.max_tiles;
+    A.counters = A.list_both + L.max_blocks;
     {   // list-driven launches pay off when the rows that force a heavy tile are few next to the tiles
         const int64_t inj_rows = (int64_t)p.inj_hi - p.inj_lo, res_rows = (int64_t)p.res_hi - p.res_lo;
         const int64_t both = inj_rows < res_rows ? inj_rows : res_rows;
         A.reduce_from_list = inj_rows * 4 <= g.tiles;
-        A.down_from_list = both * 4 <= g.tiles;
+        A.down_from_list = both * 4 <= g.blocks;
         // (the metadata pass runs before the reduce; with a dense injection the reduce then visits every
         //  tile and overwrites the provisional summaries, with a sparse one only the listed tiles)
     }
