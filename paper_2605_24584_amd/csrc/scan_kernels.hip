@@ -73,9 +73,15 @@ struct ScanArgs {
     uint32_t* counters;   // [0] = entries of list_inj, [1] = entries of list_both
     // list_inj is written by the metadata pass; list_both by the metadata pass if it runs, else by the reduce
     int reduce_from_list, down_from_list;
+    int few_inj_ok, few_res_ok;   // the block flags kFlagFewInj / kFlagFewRes may be set
 };
 
 constexpr int kFlagInj = 1, kFlagRes = 2;
+// Block flags only (wide geometry, injected and result rows from different matrices): the block holds
+// injected (result) rows, but at most kFewRows of them.  Such a block does not need the scan inside
+// it: each result row is the carries' closed form plus a handful of direct terms exp(-|p_i - p_s|) v_s.
+constexpr int kFlagFewInj = 4, kFlagFewRes = 8;
+constexpr int kFewRows = 4;
 
 template <int VEC, bool STRICT>
 struct Seg {
@@ -401,6 +407,21 @@ __device__ __forceinline__ void store_level_seg(const Level& L, int dir, int64_t
     }
 }
 
+// Flags of a 64-row block of the wide geometry, from the masks of its injected and result rows.
+__device__ __forceinline__ int block_flags(const ScanArgs& A, uint64_t inj_mask, uint64_t res_mask)
+{
+    int f = (inj_mask ? kFlagInj : 0) | (res_mask ? kFlagRes : 0);
+    if (A.few_inj_ok && inj_mask && __popcll(inj_mask) <= kFewRows) f |= kFlagFewInj;
+    if (A.few_res_ok && res_mask && __popcll(res_mask) <= kFewRows) f |= kFlagFewRes;
+    return f;
+}
+// Does the block go on the list of the downsweeps that read the injected rows again?  (A block with
+// few injected rows is handled by the streaming downsweep.)
+__device__ __forceinline__ bool listed_block(int f)
+{
+    return (f & (kFlagInj | kFlagRes | kFlagFewInj)) == (kFlagInj | kFlagRes);
+}
+
 // ---------------------------------------------------------------------------
 // metadata pass for sparse problems: one wavefront per tile, one lane per row
 // (coalesced).  Writes, for every tile, its flags and the summary it has if
@@ -425,13 +446,15 @@ k_scan_meta(const ScanArgs A)
         const float df = A.dh[jc], db = A.dh[jc + 1];
         Hf |= __ballot(live && df >= 0.0f) ? 1 : 0;
         Hb |= __ballot(live && db >= 0.0f) ? 1 : 0;
-        const int here = (__ballot(live && id >= A.inj_lo && id < A.inj_hi) ? kFlagInj : 0) |
-                         (__ballot(live && id >= A.res_lo && id < A.res_hi) ? kFlagRes : 0);
+        const uint64_t inj_mask = __ballot(live && id >= A.inj_lo && id < A.inj_hi);
+        const uint64_t res_mask = __ballot(live && id >= A.res_lo && id < A.res_hi);
+        const int here = (inj_mask ? kFlagInj : 0) | (res_mask ? kFlagRes : 0);
         fl |= here;
         if (A.sub_shift && lane == 0) {     // wide geometry: these 64 rows are one block
             const int64_t blk = (base + o) >> 6;
-            A.blk_flags[blk] = (uint32_t)here;
-            if (A.down_from_list && here == (kFlagInj | kFlagRes)) A.list_both[atomicAdd(&A.counters[1], 1u)] = (uint32_t)blk;
+            const int bf = block_flags(A, inj_mask, res_mask);
+            A.blk_flags[blk] = (uint32_t)bf;
+            if (A.down_from_list && listed_block(bf)) A.list_both[atomicAdd(&A.counters[1], 1u)] = (uint32_t)blk;
         }
     }
     if (lane == 0) {
@@ -628,7 +651,7 @@ k_scan_reduce_wide(const ScanArgs A)
         const bool res = idv >= A.res_lo && idv < A.res_hi;
         const uint64_t inj_mask = __ballot(inj);
         const uint64_t hf_mask = __ballot(M.live && M.dl >= 0.0f), hb_mask = __ballot(M.live && M.dr >= 0.0f);
-        flags = (inj_mask ? kFlagInj : 0) | (__ballot(res) ? kFlagRes : 0);
+        flags = block_flags(A, inj_mask, __ballot(res));
         Hf = hf_mask ? 1 : 0; Hb = hb_mask ? 1 : 0;
         // strict sums: rows before the last run head seen from the left / after the first one seen from the right
         const int cut_f = hf_mask ? 63 - __clzll((long long)hf_mask) : 0;      // rows i < cut_f count
@@ -677,10 +700,10 @@ k_scan_reduce_wide(const ScanArgs A)
         }
         if (lane == 0 && blockIdx.y == 0) {
             A.blk_flags[blk] = (uint32_t)flags;
-            if (A.down_from_list && !A.reduce_from_list && flags == (kFlagInj | kFlagRes))
+            if (A.down_from_list && !A.reduce_from_list && listed_block(flags))
                 A.list_both[atomicAdd(&A.counters[1], 1u)] = (uint32_t)blk;
         }
-        if (lane == 0 && flags) atomicOr(&tile_flags, flags);
+        if (lane == 0 && flags) atomicOr(&tile_flags, flags & (kFlagInj | kFlagRes));
     }
 
     // The eight block summaries meet in LDS: each wavefront folds the ones before (after) its own into
@@ -978,7 +1001,7 @@ k_scan_down(const ScanArgs A)
     if (A.down_from_list && blockIdx.x >= A.counters[1]) return;
     const int64_t tile = A.down_from_list ? A.list_both[blockIdx.x] : blockIdx.x;     // the block this workgroup owns
     const int flags = (int)A.blk_flags[tile];
-    if ((flags & (kFlagInj | kFlagRes)) != (kFlagInj | kFlagRes)) return;
+    if ((flags & (kFlagInj | kFlagRes | kFlagFewInj | kFlagFewRes)) != (kFlagInj | kFlagRes)) return;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int bv = A.bv, rv = A.rv;
@@ -1140,7 +1163,8 @@ k_scan_down_sparse(const ScanArgs A)
     constexpr int ITEMS = TileRows<VEC>::ITEMS;
     const int64_t tile = blockIdx.x;                // the block this workgroup owns
     const int flags = (int)A.blk_flags[tile];
-    if ((flags & (kFlagInj | kFlagRes)) != kFlagRes) return;
+    // result rows, and nothing injected or (wide geometry) at most kFewRows injected rows
+    if (!(flags & kFlagRes) || ((flags & kFlagInj) && !(flags & kFlagFewInj))) return;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int bv = A.bv, rv = A.rv;
@@ -1162,6 +1186,37 @@ k_scan_down_sparse(const ScanArgs A)
     load_weights<VEC>(A, T, row0, col0, col_ok, want_red, wv);
     float Fin[VEC], Ein[VEC], Rin[VEC], Gin[VEC];
     load_block_carries<VEC, STRICT>(A, tile, col0, col_ok, Fin, Ein, Rin, Gin);
+
+    // The few rows injected inside the block (wide geometry: every lane sees the same rows, its own
+    // columns): row i gets exp(-|p_i - p_s|) v_s from source s directly, on both channels (the strict
+    // one with the sign of p_s - p_i, nothing at a tie).  Lane 8 i + s holds the weight of (row i of this
+    // wavefront, source s).
+    float vs[kFewRows][VEC], w_src = 0.0f, wz_src = 0.0f;
+    const bool sources = VEC == 4 && (flags & kFlagFewInj);      // uniform
+    if (VEC == 4 && sources) {
+        const int64_t jb = tile * 64 + lane;
+        const bool live = jb < A.N;
+        const int64_t jc = live ? jb : A.N - 1;
+        const uint32_t idl = A.ids[jc];
+        const float pl = A.pk[jc + 1];
+        uint64_t m = __ballot(live && idl >= A.inj_lo && idl < A.inj_hi);
+        const float pi = __shfl(pl, wave * 8 + (lane >> 3));
+        float ps = 0.0f; bool valid = false;
+#pragma unroll
+        for (int q = 0; q < kFewRows; ++q) {
+            const bool have = m != 0;
+            const int rs = have ? __ffsll((long long)m) - 1 : 0;
+            m &= m - 1;
+            const float pq = lane_f(pl, rs);
+            const uint32_t idq = lane_u(idl, rs);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) vs[q][e] = 0.0f;
+            if (have && col_ok) load_vec<VEC>(vs[q], A.inj + (int64_t)(idq - A.inj_lo) * A.ld_inj + col0);
+            if ((lane & 7) == q) { ps = pq; valid = have; }
+        }
+        w_src = valid ? expf(-fabsf(pi - ps)) : 0.0f;
+        wz_src = ps > pi ? w_src : (ps < pi ? -w_src : 0.0f);
+    }
 
     // per-row cumulative decays inside this row-lane, from the left and from the right (at most ITEMS factors)
     float cf[ITEMS], cb[ITEMS];
@@ -1196,6 +1251,14 @@ k_scan_down_sparse(const ScanArgs A)
             P[e] = Fj + Rj;
             Z[e] = (seen_b ? Rj : Gin[e]) - (seen_f ? Fj : Ein[e]);
         }
+        if (VEC == 4 && sources) {
+#pragma unroll
+            for (int q = 0; q < kFewRows; ++q) {
+                const float a = lane_f(w_src, i * 8 + q), z = lane_f(wz_src, i * 8 + q);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) { P[e] += a * vs[q][e]; Z[e] += z * vs[q][e]; }
+            }
+        }
         if (is_res && col_ok) {
             if (A.out_p) store_vec<VEC>(A.out_p + rr * A.ld_p + col0, P);
             if (STRICT && A.out_z) store_vec<VEC>(A.out_z + rr * A.batch + col0, Z);
@@ -1205,6 +1268,133 @@ k_scan_down_sparse(const ScanArgs A)
 #pragma unroll
             for (int e = 0; e < VEC; ++e) acc += wv[i][e] * Z[e];      // wv is 0 off the result rows
             emit_row_sum(A, acc, bv, c, is_res, rr, res_rows);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// downsweep, wide geometry, blocks with injected rows and at most kFewRows result rows (an apply
+// with few outputs): one WAVEFRONT per block.  Result row r is
+//   P_r = D_f Fc + D_b Rc + sum_l exp(-|p_r - p_l|) v_l          (Sec. 1: the definition, inside the block)
+//   Z_r = (strict carries) + sum_l sgn(p_l - p_r) exp(-|p_r - p_l|) v_l
+// so the block's injected rows are streamed once, with one weight vector per result row (lane l
+// holds the weights of row l), as in the wide reduce.  No LDS, no barrier.
+// ---------------------------------------------------------------------------
+constexpr int kFewWaves = 4;
+
+template <bool STRICT>
+__global__ void __launch_bounds__(kFewWaves * 64)
+k_scan_down_fewres(const ScanArgs A)
+{
+    constexpr int VEC = 4, ROWS = 64, CH = 8, NR = kFewRows;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int64_t slot = (int64_t)blockIdx.x * kFewWaves + wave;
+    if (A.down_from_list ? slot >= (int64_t)A.counters[1] : slot >= A.blocks) return;
+    const int64_t blk = A.down_from_list ? (int64_t)lane_u(A.list_both[slot], 0) : slot;
+    const int flags = (int)A.blk_flags[blk];
+    if ((flags & (kFlagInj | kFlagRes | kFlagFewInj | kFlagFewRes)) != (kFlagInj | kFlagRes | kFlagFewRes)) return;
+    const int64_t col0 = ((int64_t)blockIdx.y * 64 + lane) * VEC;
+    const bool col_ok = col0 < A.batch;
+    const float* const base = A.inj + (col_ok ? col0 : 0);
+
+    WideMeta M;
+    M.fetch(A, blk, lane);
+    float Fc[VEC], Ec[VEC], Rc[VEC], Gc[VEC];
+    load_block_carries<VEC, STRICT>(A, blk, col0, col_ok, Fc, Ec, Rc, Gc);
+    const uint32_t idv = M.live ? M.id : 0xFFFFFFFFu;
+    const bool inj = idv >= A.inj_lo && idv < A.inj_hi;
+    const uint64_t inj_mask = __ballot(inj);
+    uint64_t res_mask = __ballot(idv >= A.res_lo && idv < A.res_hi);
+    const uint64_t hf_mask = __ballot(M.live && M.dl >= 0.0f), hb_mask = __ballot(M.live && M.dr >= 0.0f);
+    // decay of the carries to row `lane`
+    const float df = expf(-(M.p - M.p_before)), db = expf(-(M.p_after - M.p));
+
+    int rrow[NR]; bool have[NR];
+    float wP[NR], wZ[NR];           // lane l: weight of injected row l for result row q
+#pragma unroll
+    for (int q = 0; q < NR; ++q) {
+        have[q] = res_mask != 0;
+        rrow[q] = have[q] ? __ffsll((long long)res_mask) - 1 : 0;
+        res_mask &= res_mask - 1;
+        const float pr = lane_f(M.p, rrow[q]);
+        wP[q] = (have[q] && inj) ? expf(-fabsf(M.p - pr)) : 0.0f;
+        wZ[q] = M.p > pr ? wP[q] : (M.p < pr ? -wP[q] : 0.0f);
+    }
+    float aP[NR][VEC], aZ[NR][VEC];
+#pragma unroll
+    for (int q = 0; q < NR; ++q)
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) { aP[q][e] = 0.0f; aZ[q][e] = 0.0f; }
+
+    {
+        v4f buf[2][CH];
+        auto issue = [&](int c0, v4f* dst) {
+#pragma unroll
+            for (int i = 0; i < CH; ++i) {
+                const int row = c0 + i;
+                const uint32_t id = lane_u(idv, row);
+                const int64_t r = ((inj_mask >> row) & 1ull) ? (int64_t)(id - A.inj_lo) : 0;
+                dst[i] = *reinterpret_cast<const v4f*>(base + r * A.ld_inj);
+            }
+        };
+        auto fold = [&](int c0, const v4f* src) {
+#pragma unroll
+            for (int i = 0; i < CH; ++i) {
+                const int row = c0 + i;
+                const uint32_t keep = ((inj_mask >> row) & 1ull) ? 0xFFFFFFFFu : 0u;
+                float x[VEC];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) x[e] = __uint_as_float(__float_as_uint(src[i][e]) & keep);
+#pragma unroll
+                for (int q = 0; q < NR; ++q) {
+                    const float a = lane_f(wP[q], row);
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) aP[q][e] += a * x[e];
+                    if (STRICT) {
+                        const float z = lane_f(wZ[q], row);
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) aZ[q][e] += z * x[e];
+                    }
+                }
+            }
+        };
+        if (inj_mask & 0xFFull) issue(0, buf[0]);
+#pragma unroll
+        for (int c = 0; c < ROWS / CH; ++c) {
+            if (c + 1 < ROWS / CH) { if ((inj_mask >> ((c + 1) * CH)) & 0xFFull) issue((c + 1) * CH, buf[(c + 1) & 1]); }
+            if ((inj_mask >> (c * CH)) & 0xFFull) fold(c * CH, buf[c & 1]);
+        }
+    }
+
+    const bool want_red = STRICT && A.out_red != nullptr;
+    const int64_t res_rows = (int64_t)A.res_hi - (int64_t)A.res_lo;
+#pragma unroll
+    for (int q = 0; q < NR; ++q) {
+        if (!have[q]) continue;                                     // uniform
+        const int r = rrow[q];
+        const float kf = lane_f(df, r), kb = lane_f(db, r);
+        const bool seen_f = (hf_mask & ((2ull << r) - 1ull)) != 0;   // a run head at or before row r inside the block
+        const bool seen_b = (hb_mask >> r) != 0;                     // ... at or after it, seen from the right
+        const int64_t rr = (int64_t)lane_u(idv, r) - (int64_t)A.res_lo;
+        float P[VEC], Z[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            const float Fj = kf * Fc[e], Rj = kb * Rc[e];
+            P[e] = aP[q][e] + Fj + Rj;
+            Z[e] = aZ[q][e] + ((seen_b ? Rj : Gc[e]) - (seen_f ? Fj : Ec[e]));
+        }
+        if (col_ok) {
+            if (A.out_p) store_vec<VEC>(A.out_p + rr * A.ld_p + col0, P);
+            if (STRICT && A.out_z) store_vec<VEC>(A.out_z + rr * A.batch + col0, Z);
+        }
+        if (want_red) {
+            float wrow[VEC];
+            load_vec_or_zero<VEC>(wrow, A.w, rr * A.ld_w + col0, col_ok);
+            float acc = 0.0f;
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc += wrow[e] * Z[e];
+            emit_row_sum(A, acc, 64, lane, true, rr, res_rows);
         }
     }
 }
@@ -1285,6 +1475,11 @@ void launch_all(const ScanArgs& A, const ScanGeom& g, const std::string& tag, hi
     LAPLEX_TIMED(fs.c_str(), st, hipLaunchKernelGGL((k_spine_reduce<VEC, STRICT>), cgrid, block, 0, st, A));
     LAPLEX_TIMED(fs.c_str(), st, hipLaunchKernelGGL((k_spine_top<STRICT>), tgrid, dim3(kSpineThreads), 0, st, A.l2, A.bpad));
     LAPLEX_TIMED(fs.c_str(), st, hipLaunchKernelGGL((k_spine_down<VEC, STRICT>), cgrid, block, 0, st, A));
+    if (VEC == 4 && A.few_res_ok) {
+        const std::string ff = "scan_down_fewres." + tag;
+        const dim3 fgrid((dgrid.x + kFewWaves - 1) / kFewWaves, dgrid.y);
+        LAPLEX_TIMED(ff.c_str(), st, hipLaunchKernelGGL((k_scan_down_fewres<STRICT>), fgrid, dim3(kFewWaves * 64), 0, st, A));
+    }
     LAPLEX_TIMED(fd.c_str(), st, hipLaunchKernelGGL((k_scan_down<VEC, STRICT>), dgrid, block, 0, st, A));
     LAPLEX_TIMED(fp.c_str(), st, hipLaunchKernelGGL((k_scan_down_sparse<VEC, STRICT>), grid, block, 0, st, A));
 }
@@ -1331,6 +1526,11 @@ hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStrea
         const int64_t both = inj_rows < res_rows ? inj_rows : res_rows;
         A.reduce_from_list = inj_rows * 4 <= g.tiles;
         A.down_from_list = both * 4 <= g.blocks;
+        // blocks with a handful of injected (result) rows skip the scan inside the block: wide geometry,
+        // injected and result rows from different matrices, and few such rows overall
+        const bool disjoint = p.inj_hi <= p.res_lo || p.res_hi <= p.inj_lo;
+        A.few_inj_ok = g.sub_shift && disjoint && inj_rows * 4 <= g.blocks;
+        A.few_res_ok = g.sub_shift && disjoint && res_rows * 4 <= g.blocks;
         // (the metadata pass runs before the reduce; with a dense injection the reduce then visits every
         //  tile and overwrites the provisional summaries, with a sparse one only the listed tiles)
     }

@@ -101,7 +101,9 @@ SHAPES = [(1, 1, 1), (5, 1, 2), (1, 6, 1), (37, 53, 3), (100, 9000, 1), (9000, 1
           (3000, 21000, 1), (2500, 4000, 8), (513, 9000, 64), (300, 2100, 256), (70, 1500, 260),
           (50, 1700, 67),
           # very few outputs / very few inputs: tile lists drive the heavy kernels
-          (3, 70000, 1), (70000, 3, 1), (2, 40000, 8), (5, 30000, 64)]
+          (3, 70000, 1), (70000, 3, 1), (2, 40000, 8), (5, 30000, 64),
+          # wide batches with few outputs / few inputs: blocks with a handful of result (injected) rows
+          (20, 6000, 256), (6000, 20, 256), (3, 2000, 512)]
 
 
 # ------------------------------------------------------------------ the sort
