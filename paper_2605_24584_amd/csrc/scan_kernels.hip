@@ -1399,6 +1399,151 @@ k_scan_down_fewres(const ScanArgs A)
     }
 }
 
+// ---------------------------------------------------------------------------
+// downsweep_sparse for the wide geometry: one WAVEFRONT per 64-row block (every lane on its own 4
+// columns), so the block's carries are read once and not once per wavefront of a workgroup.  Same
+// closed forms as k_scan_down_sparse, with the per-row factors taken from the anchors by the lane
+// that looks at the row (kf_l = exp(-(p_l - p_before)), kb_l = exp(-(p_after - p_l))) and handed to
+// the scalar unit with readlane; the few rows injected inside the block add their direct terms.
+// The batch reduction of eight rows at a time is a butterfly: 10 cross-lane steps for 8 row sums.
+// ---------------------------------------------------------------------------
+constexpr int kStreamWaves = 4;
+
+template <bool STRICT>
+__global__ void __launch_bounds__(kStreamWaves * 64)
+k_scan_down_sparse_wide(const ScanArgs A)
+{
+    constexpr int VEC = 4, ROWS = 64, CH = 8, NS = kFewRows;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int64_t blk = (int64_t)blockIdx.x * kStreamWaves + wave;
+    if (blk >= A.blocks) return;
+    const int flags = (int)A.blk_flags[blk];
+    // result rows, and nothing injected or at most kFewRows injected rows
+    if (!(flags & kFlagRes) || ((flags & kFlagInj) && !(flags & kFlagFewInj))) return;
+    const int64_t col0 = ((int64_t)blockIdx.y * 64 + lane) * VEC;
+    const bool col_ok = col0 < A.batch;
+    const int64_t colc = col_ok ? col0 : 0;      // lanes past the last column read (and drop) columns 0..3
+
+    WideMeta M;
+    M.fetch(A, blk, lane);
+    float Fin[VEC], Ein[VEC], Rin[VEC], Gin[VEC];
+    load_block_carries<VEC, STRICT>(A, blk, col0, col_ok, Fin, Ein, Rin, Gin);
+    const uint32_t idv = M.live ? M.id : 0xFFFFFFFFu;
+    const uint64_t res_mask = __ballot(idv >= A.res_lo && idv < A.res_hi);
+    const uint64_t hf_mask = __ballot(M.live && M.dl >= 0.0f), hb_mask = __ballot(M.live && M.dr >= 0.0f);
+    const float kf = expf(-(M.p - M.p_before)), kb = expf(-(M.p_after - M.p));
+
+    // the few rows injected inside the block: lane l holds the weight of source q for row l
+    const bool sources = (flags & kFlagFewInj) != 0;       // uniform
+    float vs[NS][VEC], ws[NS], wz[NS];
+#pragma unroll
+    for (int q = 0; q < NS; ++q) {
+        ws[q] = wz[q] = 0.0f;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) vs[q][e] = 0.0f;
+    }
+    if (sources) {
+        uint64_t m = __ballot(idv >= A.inj_lo && idv < A.inj_hi);
+#pragma unroll
+        for (int q = 0; q < NS; ++q) {
+            const bool have = m != 0;
+            const int rs = have ? __ffsll((long long)m) - 1 : 0;
+            m &= m - 1;
+            const float pq = lane_f(M.p, rs);
+            const uint32_t idq = lane_u(idv, rs);
+            if (have && col_ok) load_vec<VEC>(vs[q], A.inj + (int64_t)(idq - A.inj_lo) * A.ld_inj + col0);
+            ws[q] = have ? expf(-fabsf(M.p - pq)) : 0.0f;
+            wz[q] = pq > M.p ? ws[q] : (pq < M.p ? -ws[q] : 0.0f);
+        }
+    }
+
+    const bool want_red = STRICT && A.out_red != nullptr;
+    const int64_t res_rows = (int64_t)A.res_hi - (int64_t)A.res_lo;
+#pragma unroll
+    for (int c = 0; c < ROWS / CH; ++c) {
+        if (!((res_mask >> (c * CH)) & 0xFFull)) continue;          // uniform: no result row among these eight
+        v4f x[CH];
+        if (want_red) {     // weights of the row reduction (no branch around a load: rows that are not wanted read row 0)
+#pragma unroll
+            for (int i = 0; i < CH; ++i) {
+                const int row = c * CH + i;
+                const int64_t rr = ((res_mask >> row) & 1ull) ? (int64_t)(lane_u(idv, row) - A.res_lo) : 0;
+                x[i] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(A.w + rr * A.ld_w + colc));
+            }
+        }
+        float part[CH];
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int row = c * CH + i;
+            const bool is_res = ((res_mask >> row) & 1ull) != 0;                  // uniform
+            const float f = lane_f(kf, row), b = lane_f(kb, row);
+            const bool seen_f = (hf_mask & ((2ull << row) - 1ull)) != 0;          // a run head at or before the row
+            const bool seen_b = (hb_mask >> row) != 0;                            // ... at or after it, seen from the right
+            float P[VEC], Z[VEC];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                const float Fj = f * Fin[e], Rj = b * Rin[e];
+                P[e] = Fj + Rj;
+                Z[e] = (seen_b ? Rj : Gin[e]) - (seen_f ? Fj : Ein[e]);
+            }
+            if (sources) {
+#pragma unroll
+                for (int q = 0; q < NS; ++q) {
+                    const float a = lane_f(ws[q], row), z = lane_f(wz[q], row);
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) { P[e] += a * vs[q][e]; Z[e] += z * vs[q][e]; }
+                }
+            }
+            if (is_res && col_ok) {
+                const int64_t rr = (int64_t)(lane_u(idv, row) - A.res_lo);
+                // the result matrix is written once and not read again by this call: streaming stores
+                if (A.out_p)
+                    __builtin_nontemporal_store((v4f){P[0], P[1], P[2], P[3]}, reinterpret_cast<v4f*>(A.out_p + rr * A.ld_p + col0));
+                if (STRICT && A.out_z) store_vec<VEC>(A.out_z + rr * A.batch + col0, Z);
+            }
+            part[i] = 0.0f;
+            if (want_red && is_res && col_ok) {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) part[i] += x[i][e] * Z[e];
+            }
+        }
+        if (want_red) {
+            // eight row sums over the 64 lanes: three butterfly steps leave lane l with the sum of row
+            // (l & 7) over its group of eight lanes, three more add the groups up
+            float h4[4], h2[2];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const bool up = (lane & 4) != 0;
+                const float keep = up ? part[j + 4] : part[j], send = up ? part[j] : part[j + 4];
+                h4[j] = keep + __shfl_xor(send, 4);
+            }
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const bool up = (lane & 2) != 0;
+                const float keep = up ? h4[j + 2] : h4[j], send = up ? h4[j] : h4[j + 2];
+                h2[j] = keep + __shfl_xor(send, 2);
+            }
+            float sum;
+            {
+                const bool up = (lane & 1) != 0;
+                const float keep = up ? h2[1] : h2[0], send = up ? h2[0] : h2[1];
+                sum = keep + __shfl_xor(send, 1);
+            }
+            sum += __shfl_xor(sum, 8);
+            sum += __shfl_xor(sum, 16);
+            sum += __shfl_xor(sum, 32);
+            const int row = c * CH + (lane & 7);
+            const uint32_t idr = __shfl(idv, row);
+            if (lane < 8 && ((res_mask >> row) & 1ull)) {
+                const int64_t rr = (int64_t)(idr - A.res_lo);
+                if (A.slabs == 1) A.out_red[rr] = sum;
+                else A.red_partial[(int64_t)blockIdx.y * res_rows + rr] = sum;
+            }
+        }
+    }
+}
+
 __global__ void __launch_bounds__(256)
 k_sum_slabs(const float* __restrict__ partial, int64_t rows, int slabs, float* __restrict__ out)
 {
@@ -1481,7 +1626,12 @@ void launch_all(const ScanArgs& A, const ScanGeom& g, const std::string& tag, hi
         LAPLEX_TIMED(ff.c_str(), st, hipLaunchKernelGGL((k_scan_down_fewres<STRICT>), fgrid, dim3(kFewWaves * 64), 0, st, A));
     }
     LAPLEX_TIMED(fd.c_str(), st, hipLaunchKernelGGL((k_scan_down<VEC, STRICT>), dgrid, block, 0, st, A));
-    LAPLEX_TIMED(fp.c_str(), st, hipLaunchKernelGGL((k_scan_down_sparse<VEC, STRICT>), grid, block, 0, st, A));
+    if (VEC == 4 && g.sub_shift) {
+        const dim3 sgrid((unsigned)((g.blocks + kStreamWaves - 1) / kStreamWaves), (unsigned)g.slabs);
+        LAPLEX_TIMED(fp.c_str(), st, hipLaunchKernelGGL((k_scan_down_sparse_wide<STRICT>), sgrid, dim3(kStreamWaves * 64), 0, st, A));
+    } else {
+        LAPLEX_TIMED(fp.c_str(), st, hipLaunchKernelGGL((k_scan_down_sparse<VEC, STRICT>), grid, block, 0, st, A));
+    }
 }
 
 }  // namespace
