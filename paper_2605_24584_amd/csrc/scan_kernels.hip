@@ -614,13 +614,15 @@ struct WideMeta {
     }
 };
 
+constexpr int kWideWaves = 1 << kWideSubShift;     // one wavefront per block of the tile
+static_assert(kWideWaves <= kScanWaves, "the LDS exchange has room for kScanWaves summaries");
+
 template <bool STRICT>
-__global__ void __launch_bounds__(kScanThreads)
+__global__ void __launch_bounds__(kWideWaves * 64)
 k_scan_reduce_wide(const ScanArgs A)
 {
     constexpr int VEC = 4, ROWS = 64, CH = 8;
     static_assert(kScanWaves * kItemsVec4 == ROWS, "the wide geometry (one row-lane per wavefront) has 64 rows per block");
-    static_assert(kScanWaves == 1 << kWideSubShift, "one wavefront per block of the tile");
     __shared__ WaveSegs<VEC> W;
     __shared__ int tile_flags;
     const int lane = threadIdx.x & 63;
@@ -723,13 +725,13 @@ k_scan_reduce_wide(const ScanArgs A)
 #pragma unroll
     for (int e = 0; e < VEC; ++e) { F[e] = E[e] = R[e] = G[e] = 0.0f; }
     const bool want_local = blk_live && (flags & kFlagRes) && (tflags & kFlagInj);     // uniform per wavefront
-    if (want_local || wave == kScanWaves - 1) {
+    if (want_local || wave == kWideWaves - 1) {
 #pragma unroll 1
         for (int w = 0; w < wave; ++w) seg_apply<VEC, STRICT>(get_wave_seg<VEC, STRICT>(W, 0, w, lane), F, E);
     }
     if (want_local || wave == 0) {
 #pragma unroll 1
-        for (int w = kScanWaves - 1; w > wave; --w) seg_apply<VEC, STRICT>(get_wave_seg<VEC, STRICT>(W, 1, w, lane), R, G);
+        for (int w = kWideWaves - 1; w > wave; --w) seg_apply<VEC, STRICT>(get_wave_seg<VEC, STRICT>(W, 1, w, lane), R, G);
     }
     if (want_local && col_ok) {
         const int64_t o0 = blk * A.bpad + col0, o1 = (A.blocks + blk) * A.bpad + col0;
@@ -739,9 +741,9 @@ k_scan_reduce_wide(const ScanArgs A)
     }
     const int64_t tile_base = tile * A.spine_rows;
     const bool sw = lane == 0 && blockIdx.y == 0;
-    if (wave == kScanWaves - 1) {           // the tile's forward summary = the state after the last block, from zero
+    if (wave == kWideWaves - 1) {           // the tile's forward summary = the state after the last block, from zero
         int Ht = 0;
-        if (STRICT) { for (int w = 0; w < kScanWaves; ++w) Ht |= W.H[0][w]; }
+        if (STRICT) { for (int w = 0; w < kWideWaves; ++w) Ht |= W.H[0][w]; }
         seg_apply<VEC, STRICT>(mf, F, E);
         Seg<VEC, STRICT> tf = seg_identity<VEC, STRICT>();
 #pragma unroll
@@ -752,7 +754,7 @@ k_scan_reduce_wide(const ScanArgs A)
     }
     if (wave == 0) {
         int Ht = 0;
-        if (STRICT) { for (int w = 0; w < kScanWaves; ++w) Ht |= W.H[1][w]; }
+        if (STRICT) { for (int w = 0; w < kWideWaves; ++w) Ht |= W.H[1][w]; }
         seg_apply<VEC, STRICT>(mb, R, G);
         Seg<VEC, STRICT> tb = seg_identity<VEC, STRICT>();
 #pragma unroll
@@ -1613,7 +1615,7 @@ void launch_all(const ScanArgs& A, const ScanGeom& g, const std::string& tag, hi
     const std::string fr = "scan_reduce." + tag, fs = "scan_spine." + tag, fd = "scan_down." + tag,
                       fp = "scan_down_sparse." + tag;
     if (VEC == 4 && g.sub_shift) {    // wide geometry: a workgroup per tile, a wavefront per block
-        LAPLEX_TIMED(fr.c_str(), st, hipLaunchKernelGGL((k_scan_reduce_wide<STRICT>), rgrid, block, 0, st, A));
+        LAPLEX_TIMED(fr.c_str(), st, hipLaunchKernelGGL((k_scan_reduce_wide<STRICT>), rgrid, dim3(kWideWaves * 64), 0, st, A));
     } else {
         LAPLEX_TIMED(fr.c_str(), st, hipLaunchKernelGGL((k_scan_reduce<VEC, STRICT>), rgrid, block, 0, st, A));
     }

@@ -268,46 +268,28 @@ k_onesweep_pass(const float* __restrict__ a, int64_t k, const float* __restrict_
 #pragma unroll
         for (int w = 0; w < WAVES; ++w) { const uint32_t c = whist[w][tid]; whist[w][tid] = digit_total; digit_total += c; }
     }
-    const uint32_t start = block_exclusive_scan_u32<kSortThreads>(tid < kRadix ? digit_total : 0u, nullptr);
-    const uint32_t gbase = block_exclusive_scan_u32<kSortThreads>(tid < kRadix ? ghist[pass * kRadix + tid] : 0u, nullptr);
+    // Publish this tile's digit counts as soon as they are known (the tiles after this one wait for them).
+    constexpr int kLook = 4;      // status words in flight per lane (more cost registers, and with them occupancy)
+    uint32_t mine = digit_total;
+    WORD* const word = status + tile * kRadix + (tid < kRadix ? tid : 0);
     if (tid < kRadix) {
-        uint32_t mine = digit_total;
         if (tid == kRadix - 1) mine -= (uint32_t)kSortTile - valid;        // the padding all has digit 255
-        WORD* word = status + tile * kRadix + tid;
         __hip_atomic_store(word, WORD((tile == 0 ? WORD(2) << SH : WORD(1) << SH) | WORD(mine)), __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_AGENT);
-        WORD before = 0;
-        // walk back over the predecessors, kLook status words in flight at a time (their loads are independent)
-        constexpr int kLook = 8;
-        bool done = false;
-        for (int64_t t0 = tile - 1; t0 >= 0 && !done; t0 -= kLook) {
-            WORD v[kLook];
-#pragma unroll
-            for (int j = 0; j < kLook; ++j) {
-                const int64_t t = t0 - j >= 0 ? t0 - j : 0;
-                v[j] = __hip_atomic_load(status + t * kRadix + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-#pragma unroll
-            for (int j = 0; j < kLook; ++j) {
-                const int64_t t = t0 - j;
-                if (done || t < 0) continue;
-                WORD x = v[j];
-                int spins = 0;
-                while ((x >> SH) == 0 && spins < kSpinLimit) {       // not published yet: wait for it
-                    __builtin_amdgcn_s_sleep(1);
-                    x = __hip_atomic_load(status + t * kRadix + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    ++spins;
-                }
-                if ((x >> SH) == 0) { small[kSortErrorWord] = 1u; done = true; continue; }   // gave up: flag it, never hang
-                before += x & kMask;
-                if ((x >> SH) == 2) done = true;
-            }
-        }
-        if (tile != 0)
-            __hip_atomic_store(word, WORD((WORD(2) << SH) | (before + WORD(mine))), __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
+    }
+    const uint32_t start = block_exclusive_scan_u32<kSortThreads>(tid < kRadix ? digit_total : 0u, nullptr);
+    const uint32_t gbase = block_exclusive_scan_u32<kSortThreads>(tid < kRadix ? ghist[pass * kRadix + tid] : 0u, nullptr);
+    // Ask for the status words of the tiles before this one now: the answers travel while the tile is
+    // laid out in LDS (a status word crosses the whole device, and with two workgroups per compute unit
+    // nothing else would hide that latency).
+    WORD ahead[kLook];
+    if (tid < kRadix) {
         tile_start[tid] = start;
-        delta[tid] = gbase + (uint32_t)before - start;
+#pragma unroll
+        for (int j = 0; j < kLook; ++j) {
+            const int64_t t = tile - 1 - j >= 0 ? tile - 1 - j : 0;
+            ahead[j] = __hip_atomic_load(status + t * kRadix + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
     __syncthreads();
 
@@ -317,6 +299,44 @@ k_onesweep_pass(const float* __restrict__ a, int64_t k, const float* __restrict_
         const uint32_t slot = tile_start[d] + whist[wave][d] + rank[i];
         skeys[slot] = key[i];
         sids[slot] = id[i];
+    }
+
+    if (tid < kRadix) {
+        WORD before = 0;
+        bool done = false;
+        // one batch of status words, newest tile first; a word not published yet is waited for
+        auto take = [&](int64_t t0, const WORD* v) {
+#pragma unroll
+            for (int j = 0; j < kLook; ++j) {
+                const int64_t t = t0 - j;
+                if (done || t < 0) continue;
+                WORD x = v[j];
+                int spins = 0;
+                while ((x >> SH) == 0 && spins < kSpinLimit) {
+                    __builtin_amdgcn_s_sleep(1);
+                    x = __hip_atomic_load(status + t * kRadix + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    ++spins;
+                }
+                if ((x >> SH) == 0) { small[kSortErrorWord] = 1u; done = true; continue; }   // gave up: flag it, never hang
+                before += x & kMask;
+                if ((x >> SH) == 2) done = true;
+            }
+        };
+        take(tile - 1, ahead);
+        // further back, kLook status words in flight at a time (their loads are independent)
+        for (int64_t t0 = tile - 1 - kLook; t0 >= 0 && !done; t0 -= kLook) {
+            WORD v[kLook];
+#pragma unroll
+            for (int j = 0; j < kLook; ++j) {
+                const int64_t t = t0 - j >= 0 ? t0 - j : 0;
+                v[j] = __hip_atomic_load(status + t * kRadix + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            take(t0, v);
+        }
+        if (tile != 0)
+            __hip_atomic_store(word, WORD((WORD(2) << SH) | (before + WORD(mine))), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        delta[tid] = gbase + (uint32_t)before - start;
     }
     __syncthreads();
 
