@@ -121,20 +121,33 @@ k_sort_hist(const float* __restrict__ a, int64_t k, const float* __restrict__ b,
     const int64_t N = k + n;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const int64_t first = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    for (int64_t i = first; i < N; i += stride) {
-        const uint32_t key = anchor_key(a, k, b, i);
+    constexpr int U = 8;          // keys in flight per lane
+    for (int64_t i0 = first; i0 < N; i0 += U * stride) {
+        uint32_t keys[U];
 #pragma unroll
-        for (int p = 0; p < kSortPasses - 1; ++p) atomicAdd(&h[p][(key >> (p * kRadixBits)) & (kRadix - 1)], 1u);
-        // the top digit (sign and high exponent bits) takes few values: count it once per distinct value
-        // in the wavefront instead of letting 64 lanes queue on one LDS word
-        const uint32_t top = key >> ((kSortPasses - 1) * kRadixBits);
-        uint64_t todo = __ballot(1);
-        while (todo) {
-            const int first = __ffsll((long long)todo) - 1;
-            const uint32_t v = __shfl(top, first);
-            const uint64_t same = __ballot(top == v) & todo;
-            if ((int)(threadIdx.x & 63) == first) atomicAdd(&h[kSortPasses - 1][v], (uint32_t)__popcll(same));
-            todo &= ~same;
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = i0 + u * stride;
+            keys[u] = anchor_key(a, k, b, i < N ? i : N - 1);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const bool ok = i0 + u * stride < N;          // false only at the end, for whole wavefronts or their upper lanes
+            const uint32_t key = keys[u];
+            if (ok) {
+#pragma unroll
+                for (int p = 0; p < kSortPasses - 1; ++p) atomicAdd(&h[p][(key >> (p * kRadixBits)) & (kRadix - 1)], 1u);
+            }
+            // the top digit (sign and high exponent bits) takes few values: count it once per distinct value
+            // in the wavefront instead of letting 64 lanes queue on one LDS word
+            const uint32_t top = key >> ((kSortPasses - 1) * kRadixBits);
+            uint64_t todo = __ballot(ok);
+            while (todo) {
+                const int leader = __ffsll((long long)todo) - 1;
+                const uint32_t v = __shfl(top, leader);
+                const uint64_t same = __ballot(ok && top == v) & todo;
+                if ((int)(threadIdx.x & 63) == leader) atomicAdd(&h[kSortPasses - 1][v], (uint32_t)__popcll(same));
+                todo &= ~same;
+            }
         }
     }
     for (int64_t i = first; i < status_words; i += stride) status0[i] = 0ull;   // look-back words of pass 0
