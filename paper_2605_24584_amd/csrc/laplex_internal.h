@@ -28,13 +28,18 @@ constexpr int kMergePerThread = 8;
 constexpr int kMergeTile = kMergeThreads * kMergePerThread;
 
 // ----------------------------------------------------------------------------
-// Scan geometry.  A workgroup of kScanWaves wavefronts owns one tile of
+// Scan geometry.  A workgroup of up to kScanWaves wavefronts owns one tile of
 // consecutive merged positions ("rows").  A wavefront's 64 lanes are split into
 // bv lanes across the batch (each lane holds `vec` adjacent batch columns) times
 // rv = 64 / bv row-lanes; every row-lane walks `items` consecutive rows.
 // ----------------------------------------------------------------------------
-constexpr int kScanWaves = 8;
+constexpr int kScanWaves = 8;     // wavefronts of a workgroup in the wide geometry and in the spine kernels
 constexpr int kScanThreads = kScanWaves * 64;
+// With 4 columns per lane and fewer than 64 lanes across the batch a block is owned by fewer wavefronts:
+// the downsweep holds its rows in registers and fits one workgroup of eight per compute unit, two of
+// four, and the smaller ones overlap each other's phases better (measured: 9 % on the Gram workload;
+// with one column per lane it made no difference).
+constexpr int kBlockWavesNarrow = 4;
 constexpr int kItemsVec1 = 16;   // rows per row-lane when a lane holds 1 column
 constexpr int kItemsVec4 = 8;    // rows per row-lane when a lane holds 4 columns
 // A batch row narrower than this many floats is gathered once per problem and staged in sorted
@@ -55,7 +60,8 @@ struct ScanGeom {
     int bv;           // lanes across the batch (power of two, <= 64)
     int rv;           // row-lanes per wavefront
     int slabs;        // ceil(batch / (bv * vec)): blockIdx.y
-    int tile_rows;    // rows per block: kScanWaves * rv * items
+    int waves;        // wavefronts per block workgroup
+    int tile_rows;    // rows per block: waves * rv * items
     int sub_shift;    // log2(blocks per tile)
     int64_t blocks;   // ceil(N / tile_rows)
     int64_t tiles;    // ceil(blocks / 2^sub_shift)
@@ -75,8 +81,9 @@ inline ScanGeom scan_geom(int64_t N, int64_t batch, int vec)
     g.rv = 64 / g.bv;
     g.slabs = (int)((groups + g.bv - 1) / g.bv);
     if (g.slabs < 1) g.slabs = 1;
-    g.tile_rows = kScanWaves * g.rv * g.items;
     g.sub_shift = (vec == 4 && g.bv == 64) ? kWideSubShift : 0;
+    g.waves = (vec == 4 && !g.sub_shift) ? kBlockWavesNarrow : kScanWaves;
+    g.tile_rows = g.waves * g.rv * g.items;
     g.blocks = (N + g.tile_rows - 1) / g.tile_rows;
     g.tiles = (g.blocks + (int64_t(1) << g.sub_shift) - 1) >> g.sub_shift;
     g.chunk_tiles = kScanWaves * g.rv * kSpineItems;

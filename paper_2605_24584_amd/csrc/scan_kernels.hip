@@ -61,6 +61,7 @@ struct ScanArgs {
     // A downsweep workgroup owns a block of tile_rows rows; the spine's tiles (level 1) are
     // 2^sub_shift consecutive blocks, spine_rows rows (sub_shift > 0 in the wide geometry only).
     int sub_shift; int64_t spine_rows, blocks;
+    int waves;            // wavefronts per workgroup of the block kernels (reduce, downsweeps)
     uint32_t* blk_flags;  // [blocks] kFlagInj | kFlagRes
     float* blk_f;         // [2][blocks][bpad] state entering a block when its tile starts from zero (sub_shift > 0)
     float* blk_e;         // [2][blocks][bpad] the same, strict channel
@@ -561,9 +562,9 @@ k_scan_reduce(const ScanArgs A)
     if (tid < bv) {   // wavefront 0, row-lane 0: one lane per column group
         Seg<VEC, STRICT> tf = seg_identity<VEC, STRICT>(), tb = seg_identity<VEC, STRICT>();
 #pragma unroll 1   // sequential on purpose: unrolling would hold every wavefront's summary in registers at once
-        for (int w = 0; w < kScanWaves; ++w) tf = seg_compose<VEC, STRICT>(tf, get_wave_seg<VEC, STRICT>(W, 0, w, c));
+        for (int w = 0; w < A.waves; ++w) tf = seg_compose<VEC, STRICT>(tf, get_wave_seg<VEC, STRICT>(W, 0, w, c));
 #pragma unroll 1
-        for (int w = kScanWaves - 1; w >= 0; --w) tb = seg_compose<VEC, STRICT>(tb, get_wave_seg<VEC, STRICT>(W, 1, w, c));
+        for (int w = A.waves - 1; w >= 0; --w) tb = seg_compose<VEC, STRICT>(tb, get_wave_seg<VEC, STRICT>(W, 1, w, c));
         tf.D = tf.C = tile_df;
         tb.D = tb.C = tile_db;
         const bool sw = c == 0 && blockIdx.y == 0;
@@ -999,7 +1000,8 @@ k_scan_down(const ScanArgs A)
     constexpr size_t kSmem = sizeof(WaveSegs<VEC>) > kEfBytes ? sizeof(WaveSegs<VEC>) : kEfBytes;
     __shared__ __align__(16) unsigned char smem[kSmem];
     WaveSegs<VEC>& W = *reinterpret_cast<WaveSegs<VEC>*>(smem);
-    float* const ef = reinterpret_cast<float*>(smem) + (size_t)threadIdx.x * VEC;   // row i at ef[i * kScanThreads * VEC]
+    float* const ef = reinterpret_cast<float*>(smem) + (size_t)threadIdx.x * VEC;   // row i at ef[i * ef_stride]
+    const size_t ef_stride = (size_t)A.waves * 64 * VEC;
     if (A.down_from_list && blockIdx.x >= A.counters[1]) return;
     const int64_t tile = A.down_from_list ? A.list_both[blockIdx.x] : blockIdx.x;     // the block this workgroup owns
     const int flags = (int)A.blk_flags[tile];
@@ -1090,7 +1092,7 @@ k_scan_down(const ScanArgs A)
 #pragma unroll 1
     for (int w = 0; w < wave; ++w) seg_apply<VEC, STRICT>(get_wave_seg<VEC, STRICT>(W, 0, w, c), F, E);
 #pragma unroll 1
-    for (int w = kScanWaves - 1; w > wave; --w) seg_apply<VEC, STRICT>(get_wave_seg<VEC, STRICT>(W, 1, w, c), R, G);
+    for (int w = A.waves - 1; w > wave; --w) seg_apply<VEC, STRICT>(get_wave_seg<VEC, STRICT>(W, 1, w, c), R, G);
     seg_apply<VEC, STRICT>(fe, F, E);
     seg_apply<VEC, STRICT>(be, R, G);
     // ... plus the tile's carries, decayed over those rows by one exponential of an anchor difference
@@ -1110,7 +1112,7 @@ k_scan_down(const ScanArgs A)
             F[e] = (h ? E[e] : F[e]) + v[i][e];
             Ff[i][e] = F[e];
         }
-        if (STRICT) store_vec<VEC>(ef + (size_t)i * kScanThreads * VEC, E);
+        if (STRICT) store_vec<VEC>(ef + (size_t)i * ef_stride, E);
     }
 
     // backward walk with emission
@@ -1127,7 +1129,7 @@ k_scan_down(const ScanArgs A)
         float P[VEC], Z[VEC], Efi[VEC];
 #pragma unroll
         for (int e = 0; e < VEC; ++e) Efi[e] = 0.0f;
-        if (STRICT) load_vec<VEC>(Efi, ef + (size_t)i * kScanThreads * VEC);
+        if (STRICT) load_vec<VEC>(Efi, ef + (size_t)i * ef_stride);
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
             G[e] = h ? T.dh[i + 1] * R[e] : G[e];
@@ -1594,7 +1596,8 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 template <int VEC, bool STRICT>
 void launch_all(const ScanArgs& A, const ScanGeom& g, const std::string& tag, hipStream_t st)
 {
-    const dim3 block(kScanThreads);
+    const dim3 block(kScanThreads);                 // spine kernels
+    const dim3 bblock((unsigned)g.waves * 64);      // block kernels
     const dim3 grid((unsigned)g.blocks, (unsigned)g.slabs);
     // heavy kernels driven by the lists visit at most one tile per injected row (reduce) and one block
     // per injected and per result row (downsweep)
@@ -1617,7 +1620,7 @@ void launch_all(const ScanArgs& A, const ScanGeom& g, const std::string& tag, hi
     if (VEC == 4 && g.sub_shift) {    // wide geometry: a workgroup per tile, a wavefront per block
         LAPLEX_TIMED(fr.c_str(), st, hipLaunchKernelGGL((k_scan_reduce_wide<STRICT>), rgrid, dim3(kWideWaves * 64), 0, st, A));
     } else {
-        LAPLEX_TIMED(fr.c_str(), st, hipLaunchKernelGGL((k_scan_reduce<VEC, STRICT>), rgrid, block, 0, st, A));
+        LAPLEX_TIMED(fr.c_str(), st, hipLaunchKernelGGL((k_scan_reduce<VEC, STRICT>), rgrid, bblock, 0, st, A));
     }
     LAPLEX_TIMED(fs.c_str(), st, hipLaunchKernelGGL((k_spine_reduce<VEC, STRICT>), cgrid, block, 0, st, A));
     LAPLEX_TIMED(fs.c_str(), st, hipLaunchKernelGGL((k_spine_top<STRICT>), tgrid, dim3(kSpineThreads), 0, st, A.l2, A.bpad));
@@ -1627,12 +1630,12 @@ void launch_all(const ScanArgs& A, const ScanGeom& g, const std::string& tag, hi
         const dim3 fgrid((dgrid.x + kFewWaves - 1) / kFewWaves, dgrid.y);
         LAPLEX_TIMED(ff.c_str(), st, hipLaunchKernelGGL((k_scan_down_fewres<STRICT>), fgrid, dim3(kFewWaves * 64), 0, st, A));
     }
-    LAPLEX_TIMED(fd.c_str(), st, hipLaunchKernelGGL((k_scan_down<VEC, STRICT>), dgrid, block, 0, st, A));
+    LAPLEX_TIMED(fd.c_str(), st, hipLaunchKernelGGL((k_scan_down<VEC, STRICT>), dgrid, bblock, 0, st, A));
     if (VEC == 4 && g.sub_shift) {
         const dim3 sgrid((unsigned)((g.blocks + kStreamWaves - 1) / kStreamWaves), (unsigned)g.slabs);
         LAPLEX_TIMED(fp.c_str(), st, hipLaunchKernelGGL((k_scan_down_sparse_wide<STRICT>), sgrid, dim3(kStreamWaves * 64), 0, st, A));
     } else {
-        LAPLEX_TIMED(fp.c_str(), st, hipLaunchKernelGGL((k_scan_down_sparse<VEC, STRICT>), grid, block, 0, st, A));
+        LAPLEX_TIMED(fp.c_str(), st, hipLaunchKernelGGL((k_scan_down_sparse<VEC, STRICT>), grid, bblock, 0, st, A));
     }
 }
 
@@ -1659,6 +1662,7 @@ hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStrea
     A.batch = p.batch; A.bpad = L.bpad;
     A.bv = g.bv; A.bv_log2 = ilog2(g.bv); A.rv = g.rv; A.tile_rows = g.tile_rows; A.slabs = g.slabs;
     A.chunk_tiles = g.chunk_tiles;
+    A.waves = g.waves;
     A.sub_shift = g.sub_shift; A.spine_rows = (int64_t)g.tile_rows << g.sub_shift; A.blocks = g.blocks;
     A.blk_flags = reinterpret_cast<uint32_t*>(ws + L.off_blk_flags);
     A.blk_f = reinterpret_cast<float*>(ws + L.off_blk_f);
