@@ -989,19 +989,20 @@ __device__ __forceinline__ void load_block_carries(const ScanArgs& A, int64_t bl
 // ---------------------------------------------------------------------------
 // downsweep: tiles that hold both injected and result rows
 // ---------------------------------------------------------------------------
-template <int VEC, bool STRICT>
-__global__ void __launch_bounds__(kScanThreads)
+// WAVES: wavefronts of the workgroup (sizes the LDS buffer); RED: the row reduction is wanted (out_red).
+template <int VEC, bool STRICT, int WAVES, bool RED>
+__global__ void __launch_bounds__(WAVES * 64)
 k_scan_down(const ScanArgs A)
 {
     constexpr int ITEMS = TileRows<VEC>::ITEMS;
     // One LDS buffer, used twice: first for the exchange of wavefront summaries, then (strict scans only)
     // for the per-row strict forward values, which would otherwise cost ITEMS * VEC registers per lane.
-    constexpr size_t kEfBytes = STRICT ? sizeof(float) * ITEMS * kScanThreads * VEC : 0;
+    constexpr size_t kEfBytes = STRICT ? sizeof(float) * ITEMS * WAVES * 64 * VEC : 0;
     constexpr size_t kSmem = sizeof(WaveSegs<VEC>) > kEfBytes ? sizeof(WaveSegs<VEC>) : kEfBytes;
     __shared__ __align__(16) unsigned char smem[kSmem];
     WaveSegs<VEC>& W = *reinterpret_cast<WaveSegs<VEC>*>(smem);
     float* const ef = reinterpret_cast<float*>(smem) + (size_t)threadIdx.x * VEC;   // row i at ef[i * ef_stride]
-    const size_t ef_stride = (size_t)A.waves * 64 * VEC;
+    constexpr size_t ef_stride = (size_t)WAVES * 64 * VEC;
     if (A.down_from_list && blockIdx.x >= A.counters[1]) return;
     const int64_t tile = A.down_from_list ? A.list_both[blockIdx.x] : blockIdx.x;     // the block this workgroup owns
     const int flags = (int)A.blk_flags[tile];
@@ -1037,7 +1038,7 @@ k_scan_down(const ScanArgs A)
         load_injected<VEC>(A, T, col0, col_ok, v);
     }
 
-    const bool want_red = STRICT && A.out_red != nullptr;
+    constexpr bool want_red = STRICT && RED;
     // weights of the row reduction and the saved strict scans are fetched one row ahead of their use in
     // the backward walk (holding all rows of both would cost 2 * ITEMS * VEC registers)
     auto fetch_row = [&](int i, float* wrow, float* zrow) {
@@ -1092,7 +1093,7 @@ k_scan_down(const ScanArgs A)
 #pragma unroll 1
     for (int w = 0; w < wave; ++w) seg_apply<VEC, STRICT>(get_wave_seg<VEC, STRICT>(W, 0, w, c), F, E);
 #pragma unroll 1
-    for (int w = A.waves - 1; w > wave; --w) seg_apply<VEC, STRICT>(get_wave_seg<VEC, STRICT>(W, 1, w, c), R, G);
+    for (int w = WAVES - 1; w > wave; --w) seg_apply<VEC, STRICT>(get_wave_seg<VEC, STRICT>(W, 1, w, c), R, G);
     seg_apply<VEC, STRICT>(fe, F, E);
     seg_apply<VEC, STRICT>(be, R, G);
     // ... plus the tile's carries, decayed over those rows by one exponential of an anchor difference
@@ -1630,7 +1631,12 @@ void launch_all(const ScanArgs& A, const ScanGeom& g, const std::string& tag, hi
         const dim3 fgrid((dgrid.x + kFewWaves - 1) / kFewWaves, dgrid.y);
         LAPLEX_TIMED(ff.c_str(), st, hipLaunchKernelGGL((k_scan_down_fewres<STRICT>), fgrid, dim3(kFewWaves * 64), 0, st, A));
     }
-    LAPLEX_TIMED(fd.c_str(), st, hipLaunchKernelGGL((k_scan_down<VEC, STRICT>), dgrid, bblock, 0, st, A));
+    {
+        const bool red = STRICT && A.out_red != nullptr;
+        auto go = [&](auto kernel) { LAPLEX_TIMED(fd.c_str(), st, hipLaunchKernelGGL(kernel, dgrid, bblock, 0, st, A)); };
+        if (g.waves == kScanWaves) { if (red) go(k_scan_down<VEC, STRICT, kScanWaves, STRICT>); else go(k_scan_down<VEC, STRICT, kScanWaves, false>); }
+        else { if (red) go(k_scan_down<VEC, STRICT, kBlockWavesNarrow, STRICT>); else go(k_scan_down<VEC, STRICT, kBlockWavesNarrow, false>); }
+    }
     if (VEC == 4 && g.sub_shift) {
         const dim3 sgrid((unsigned)((g.blocks + kStreamWaves - 1) / kStreamWaves), (unsigned)g.slabs);
         LAPLEX_TIMED(fp.c_str(), st, hipLaunchKernelGGL((k_scan_down_sparse_wide<STRICT>), sgrid, dim3(kStreamWaves * 64), 0, st, A));
