@@ -35,6 +35,7 @@
 
 #include <string>
 
+
 namespace laplex {
 
 namespace {
@@ -181,6 +182,8 @@ __device__ __forceinline__ Seg<VEC, STRICT> wave_scan(Seg<VEC, STRICT> s, int la
     return s;
 }
 
+typedef float v4f __attribute__((ext_vector_type(4)));
+
 template <int VEC>
 __device__ __forceinline__ void load_vec(float* dst, const float* src)
 {
@@ -199,13 +202,37 @@ __device__ __forceinline__ void store_vec(float* dst, const float* src)
     else dst[0] = src[0];
 }
 
+// The same for data that is read (written) once and not again soon: streaming accesses, which do not
+// displace what the caches hold.  Used where a lane moves 16 bytes of a row; with one column per lane
+// (batches of one to three columns, random 4-byte accesses) the caches are what makes the gathers
+// affordable, and streaming them cost 60 % on the tie-heavy workload.
+template <int VEC> constexpr bool kStreamRows = VEC == 4;
+template <int VEC>
+__device__ __forceinline__ void load_vec_stream(float* dst, const float* src)
+{
+    if (VEC == 4) {
+        const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(src));
+        dst[0] = t.x; dst[1] = t.y; dst[2] = t.z; dst[3] = t.w;
+    } else {
+        dst[0] = __builtin_nontemporal_load(src);
+    }
+}
+
+template <int VEC>
+__device__ __forceinline__ void store_vec_stream(float* dst, const float* src)
+{
+    if (VEC == 4) __builtin_nontemporal_store((v4f){src[0], src[1], src[2], src[3]}, reinterpret_cast<v4f*>(dst));
+    else __builtin_nontemporal_store(src[0], dst);
+}
+
 // dst <- ok ? base[off .. off+VEC) : 0, without a branch: a row that is not wanted
 // reads the first columns of row 0 (always valid, always cached) and is discarded.
-template <int VEC>
+template <int VEC, bool STREAM = false>
 __device__ __forceinline__ void load_vec_or_zero(float* dst, const float* base, int64_t off, bool ok)
 {
     float t[VEC];
-    load_vec<VEC>(t, base + (ok ? off : 0));
+    if (STREAM) load_vec_stream<VEC>(t, base + (ok ? off : 0));
+    else load_vec<VEC>(t, base + (ok ? off : 0));
 #pragma unroll
     for (int e = 0; e < VEC; ++e) dst[e] = ok ? t[e] : 0.0f;
 }
@@ -299,7 +326,7 @@ __device__ __forceinline__ void enter_state(float* F, float* E, const float* Fc,
     }
 }
 
-template <int VEC>
+template <int VEC, bool STREAM = false>
 __device__ __forceinline__ void load_injected(const ScanArgs& A, const TileRows<VEC>& T, int64_t col0, bool col_ok,
                                               float (*v)[VEC])
 {
@@ -307,7 +334,7 @@ __device__ __forceinline__ void load_injected(const ScanArgs& A, const TileRows<
 #pragma unroll
     for (int i = 0; i < ITEMS; ++i) {
         const bool ok = col_ok && T.id[i] >= A.inj_lo && T.id[i] < A.inj_hi;
-        load_vec_or_zero<VEC>(v[i], A.inj, (int64_t)(T.id[i] - A.inj_lo) * A.ld_inj + col0, ok);
+        load_vec_or_zero<VEC, STREAM>(v[i], A.inj, (int64_t)(T.id[i] - A.inj_lo) * A.ld_inj + col0, ok);
     }
 }
 
@@ -522,7 +549,7 @@ k_scan_reduce(const ScanArgs A)
     }
     float v[ITEMS][VEC];
     if (tile_flags & kFlagInj) {     // uniform: a tile with nothing injected reads no data rows
-        load_injected<VEC>(A, T, col0, col_ok, v);
+        load_injected<VEC, kStreamRows<VEC>>(A, T, col0, col_ok, v);
         if (A.stage && col_ok) {     // uniform in A.stage
 #pragma unroll
             for (int i = 0; i < ITEMS; ++i)
@@ -591,7 +618,6 @@ k_scan_reduce(const ScanArgs A)
 // every lane on its own 4 columns.  A summary written to memory costs far more than its share of the
 // bytes (writes interleaved with a read stream), hence one per eight blocks and not one per block.
 // ---------------------------------------------------------------------------
-typedef float v4f __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float lane_f(float v, int l) { return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l)); }
 __device__ __forceinline__ uint32_t lane_u(uint32_t v, int l) { return (uint32_t)__builtin_amdgcn_readlane((int)v, l); }
@@ -1035,7 +1061,7 @@ k_scan_down(const ScanArgs A)
         for (int i = 0; i < ITEMS; ++i)
             load_vec_or_zero<VEC>(v[i], A.stage, (row0 + i) * A.batch + col0, col_ok && T.id[i] != 0xFFFFFFFFu);
     } else {
-        load_injected<VEC>(A, T, col0, col_ok, v);
+        load_injected<VEC, kStreamRows<VEC>>(A, T, col0, col_ok, v);
     }
 
     constexpr bool want_red = STRICT && RED;
@@ -1047,9 +1073,9 @@ k_scan_down(const ScanArgs A)
 #pragma unroll
         for (int e = 0; e < VEC; ++e) { wrow[e] = 0.0f; zrow[e] = 0.0f; }
         if (want_red) {                                  // uniform branches
-            if (A.wstage) load_vec_or_zero<VEC>(wrow, A.wstage, (row0 + i) * A.batch + col0, ok);
-            else load_vec_or_zero<VEC>(wrow, A.w, rr * A.ld_w + col0, ok);
-            if (A.zs) load_vec_or_zero<VEC>(zrow, A.zs, rr * A.batch + col0, ok);
+            if (A.wstage) load_vec_or_zero<VEC, kStreamRows<VEC>>(wrow, A.wstage, (row0 + i) * A.batch + col0, ok);
+            else load_vec_or_zero<VEC, kStreamRows<VEC>>(wrow, A.w, rr * A.ld_w + col0, ok);
+            if (A.zs) load_vec_or_zero<VEC, kStreamRows<VEC>>(zrow, A.zs, rr * A.batch + col0, ok);
         }
     };
 
@@ -1141,8 +1167,13 @@ k_scan_down(const ScanArgs A)
         const bool is_res = T.id[i] >= A.res_lo && T.id[i] < A.res_hi;
         const int64_t rr = (int64_t)T.id[i] - (int64_t)A.res_lo;
         if (is_res && col_ok) {
-            if (A.out_p) store_vec<VEC>(A.out_p + rr * A.ld_p + col0, P);
-            if (STRICT && A.out_z) store_vec<VEC>(A.out_z + rr * A.batch + col0, Z);
+            if (kStreamRows<VEC>) {
+                if (A.out_p) store_vec_stream<VEC>(A.out_p + rr * A.ld_p + col0, P);
+                if (STRICT && A.out_z) store_vec_stream<VEC>(A.out_z + rr * A.batch + col0, Z);
+            } else {
+                if (A.out_p) store_vec<VEC>(A.out_p + rr * A.ld_p + col0, P);
+                if (STRICT && A.out_z) store_vec<VEC>(A.out_z + rr * A.batch + col0, Z);
+            }
         }
         if (want_red) {
             float acc = 0.0f;
