@@ -44,26 +44,38 @@ def parse():
     return ap.parse_args()
 
 
-def dominant_kernel_bytes(a, b, batch, tile_rows):
-    """Algorithmic bytes of one launch of the dominant kernel, the sparse backward
-    downsweep.  It visits the tiles of the sorted merged sequence that hold no
-    output anchor (the other tiles go to the generic downsweep); per visited row:
-    sorted id and decay (8 B), the x row read and the gx row written (4 B per
-    batch column each), gb written (4 B); per visited tile: the four carry rows
-    (forward/backward, inclusive/strict) read (16 B per batch column).
-    Returns (bytes, visited rows, visited tiles, all tiles)."""
+def dominant_kernel_bytes(a, b, batch, block_rows, blocks_per_tile=8, few=4):
+    """Algorithmic bytes of one launch of the dominant kernel, the streaming backward
+    downsweep (one wavefront per block of `block_rows` sorted rows).  It visits the
+    blocks that hold at most `few` output anchors (blocks with more go to the generic
+    downsweep).  Per visited input row: sorted id, two decays' worth of metadata and
+    the sorted anchor (12 B), the x row read and the gx row written (4 B per batch
+    column each), gb written (4 B).  Per tile of `blocks_per_tile` blocks: the four
+    carry rows of the tile (forward/backward, inclusive/strict: 16 B per batch
+    column); per visited block of a tile that holds output anchors: the four rows of
+    the state the block starts from inside its tile (16 B per batch column) and, per
+    output anchor in the block, its gy row (4 B per batch column).
+    Returns (bytes, visited rows, visited blocks, all blocks)."""
     import numpy as np
     k = a.size
     order = np.argsort(np.concatenate([a, b]), kind="stable")
     N = order.size
-    tiles = (N + tile_rows - 1) // tile_rows
-    has_output = np.zeros(tiles, dtype=bool)
-    has_output[np.nonzero(order < k)[0] // tile_rows] = True
-    rows_per_tile = np.full(tiles, tile_rows, dtype=np.int64)
-    rows_per_tile[-1] = N - (tiles - 1) * tile_rows
-    rows = int(rows_per_tile[~has_output].sum())
-    visited = int((~has_output).sum())
-    return rows * (8 + 8 * batch + 4) + visited * 16 * batch, rows, visited, int(tiles)
+    blocks = (N + block_rows - 1) // block_rows
+    outputs = np.bincount(np.nonzero(order < k)[0] // block_rows, minlength=blocks)
+    rows_per_block = np.full(blocks, block_rows, dtype=np.int64)
+    rows_per_block[-1] = N - (blocks - 1) * block_rows
+    visited = outputs <= few
+    rows = int((rows_per_block - outputs)[visited].sum())
+    tiles = (blocks + blocks_per_tile - 1) // blocks_per_tile
+    pad = tiles * blocks_per_tile - blocks
+    tile_outputs = np.concatenate([outputs, np.zeros(pad, dtype=outputs.dtype)]).reshape(tiles, blocks_per_tile).sum(axis=1)
+    tile_visited = np.concatenate([visited, np.zeros(pad, dtype=bool)]).reshape(tiles, blocks_per_tile).any(axis=1)
+    in_output_tile = np.repeat(tile_outputs > 0, blocks_per_tile)[:blocks]
+    total = (rows * (12 + 8 * batch + 4)
+             + int(tile_visited.sum()) * 16 * batch
+             + int((visited & in_output_tile).sum()) * 16 * batch
+             + int(outputs[visited].sum()) * 4 * batch)
+    return total, rows, int(visited.sum()), int(blocks)
 
 
 def other_workload(args, torch, np, B, synth):
@@ -189,11 +201,11 @@ def main():
     dom_bytes, dom_rows, dom_tiles, all_tiles = dominant_kernel_bytes(a, b, batch, tile_rows)
     achieved = dom_bytes / (dom_avg_ms * 1e-3) / 1e9 if dom_launches else 0.0
     roofline = {
-        "bound": "hbm", "kernel": "k_scan_down_sparse<4,true> (backward downsweep of the tiles without output anchors)",
+        "bound": "hbm", "kernel": "k_scan_down_sparse_wide<true> (backward downsweep: reads x, writes gx and gb)",
         "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
         "avg_kernel_ms": round(dom_avg_ms, 5), "launches": dom_launches, "algorithmic_bytes": dom_bytes,
-        "rows_visited": dom_rows, "tiles_visited": dom_tiles, "tiles": all_tiles,
+        "rows_visited": dom_rows, "blocks_visited": dom_tiles, "blocks": all_tiles,
     }
     traffic_file = os.path.join(ROOT, "profiles", "traffic_scan_down_sparse_bwd_projection.json")
     if args.scale == 1 and args.batch == 256 and os.path.exists(traffic_file):
