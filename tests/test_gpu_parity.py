@@ -180,7 +180,9 @@ def test_plan_reuse_across_batches(oracle):
     assert_close("y", y2, ref, tol)
 
 
-@pytest.mark.parametrize("batch,ldx,ldy", [(4, 5, 7), (8, 12, 8), (1, 3, 2), (64, 65, 64)])
+@pytest.mark.parametrize("batch,ldx,ldy", [(4, 5, 7), (8, 12, 8), (1, 3, 2), (64, 65, 64),
+                                           # wide batches: padded rows with 4-column lanes, and with 1-column lanes
+                                           (256, 260, 264), (256, 257, 256), (300, 304, 300)])
 def test_leading_dimensions_and_scalar_lanes(oracle, batch, ldx, ldy):
     r = np.random.default_rng(7)
     a, b = anchors("uniform", r, 300, 2500)
@@ -188,6 +190,26 @@ def test_leading_dimensions_and_scalar_lanes(oracle, batch, ldx, ldy):
     y, _ = gpu_apply(a, b, x, ldx=ldx, ldy=ldy)
     ref, tol = oracle.apply_scan(a, b, x)
     assert_close("y", y, ref, tol)
+
+
+def test_wide_batch_padded_rows_backward(oracle):
+    """Backward with padded rows of x, gy and gx in the wide geometry (few outputs: the few-row kernels)."""
+    r = np.random.default_rng(17)
+    k, n, batch = 24, 7000, 256
+    a, b = anchors("ties", r, k, n)
+    x = r.normal(size=(n, batch)).astype(np.float32); g = r.normal(size=(k, batch)).astype(np.float32)
+    ws = workspace(k, n, batch)
+    dx = torch.zeros(n, batch + 8, device="cuda")[:, :batch]; dx.copy_(dev(x))
+    dg = torch.zeros(k, batch + 4, device="cuda")[:, :batch]; dg.copy_(dev(g))
+    gxbuf = torch.full((n, batch + 12), float("nan"), device="cuda"); gx = gxbuf[:, :batch]
+    ga = torch.full((k,), float("nan"), device="cuda"); gb = torch.full((n,), float("nan"), device="cuda")
+    B.laplex_apply_backward(dev(a), dev(b), dx, dg, gx, ga, gb, ws, 0)
+    torch.cuda.synchronize()
+    assert bool(torch.isnan(gxbuf[:, batch:]).all()), "the padding of gx was written"
+    (rgx, rga, rgb), (tgx, tga, tgb) = oracle.apply_backward_scan(a, b, x, g)
+    assert_close("gx", gx.cpu().numpy(), rgx, tgx)
+    assert_close("ga", ga.cpu().numpy(), rga, tga)
+    assert_close("gb", gb.cpu().numpy(), rgb, tgb)
 
 
 def test_results_are_deterministic():
