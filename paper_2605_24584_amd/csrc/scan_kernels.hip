@@ -595,8 +595,10 @@ k_scan_reduce(const ScanArgs A)
         tf.D = tf.C = tile_df;
         tb.D = tb.C = tile_db;
         const bool sw = c == 0 && blockIdx.y == 0;
-        store_level_seg<VEC, STRICT>(A.l1, 0, tile, A.bpad, col0, col_ok, sw, tf, (float)tile_flags);
-        store_level_seg<VEC, STRICT>(A.l1, 1, tile, A.bpad, col0, col_ok, sw, tb, (float)tile_flags);
+        // (the vectors of a tile with nothing injected are zero and never fetched: not written either)
+        const bool vec_ok = col_ok && (tile_flags & kFlagInj);
+        store_level_seg<VEC, STRICT>(A.l1, 0, tile, A.bpad, col0, vec_ok, sw, tf, (float)tile_flags);
+        store_level_seg<VEC, STRICT>(A.l1, 1, tile, A.bpad, col0, vec_ok, sw, tb, (float)tile_flags);
     }
 }
 
@@ -777,7 +779,7 @@ k_scan_reduce_wide(const ScanArgs A)
         for (int e = 0; e < VEC; ++e) { tf.S[e] = F[e]; if (STRICT) tf.Q[e] = E[e]; }
         tf.D = tf.C = span_decay_f(A, tile_base, A.spine_rows);     // from the anchors
         if (STRICT) tf.H = Ht;
-        store_level_seg<VEC, STRICT>(A.l1, 0, tile, A.bpad, col0, col_ok, sw, tf, (float)tflags);
+        store_level_seg<VEC, STRICT>(A.l1, 0, tile, A.bpad, col0, col_ok && (tflags & kFlagInj), sw, tf, (float)tflags);
     }
     if (wave == 0) {
         int Ht = 0;
@@ -788,7 +790,86 @@ k_scan_reduce_wide(const ScanArgs A)
         for (int e = 0; e < VEC; ++e) { tb.S[e] = R[e]; if (STRICT) tb.Q[e] = G[e]; }
         tb.D = tb.C = span_decay_b(A, tile_base, A.spine_rows);
         if (STRICT) tb.H = Ht;
-        store_level_seg<VEC, STRICT>(A.l1, 1, tile, A.bpad, col0, col_ok, sw, tb, (float)tflags);
+        store_level_seg<VEC, STRICT>(A.l1, 1, tile, A.bpad, col0, col_ok && (tflags & kFlagInj), sw, tb, (float)tflags);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// reduce, one WAVEFRONT per tile (batches that are not staged in sorted order, outside the wide
+// geometry): row-lane r walks its share of the tile's rows chunk by chunk, so the summary needs no
+// LDS and no barrier, and a workgroup is four independent wavefronts.  Same outputs as k_scan_reduce.
+// ---------------------------------------------------------------------------
+constexpr int kLoneWaves = 4;
+
+template <int VEC, bool STRICT>
+__global__ void __launch_bounds__(kLoneWaves * 64)
+k_scan_reduce_wave(const ScanArgs A)
+{
+    constexpr int ITEMS = TileRows<VEC>::ITEMS;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int bv = A.bv, rv = A.rv;
+    const int c = lane & (bv - 1), r = lane >> A.bv_log2;
+    const int64_t slot = (int64_t)blockIdx.x * kLoneWaves + wave;
+    if (A.reduce_from_list ? slot >= (int64_t)A.counters[0] : slot >= A.l1.count) return;
+    const int64_t tile = A.reduce_from_list ? (int64_t)lane_u(A.list_inj[slot], 0) : slot;
+    const int per = A.tile_rows / rv;                        // rows of a row-lane: a multiple of ITEMS
+    const int64_t tile_base = tile * A.tile_rows, lane_row0 = tile_base + (int64_t)r * per;
+    const int64_t col0 = ((int64_t)blockIdx.y * bv + c) * VEC;
+    const bool col_ok = col0 < A.batch;
+    const float lane_df = span_decay_f(A, lane_row0, per), lane_db = span_decay_b(A, lane_row0, per);
+    const float tile_df = span_decay_f(A, tile_base, A.tile_rows), tile_db = span_decay_b(A, tile_base, A.tile_rows);
+
+    Seg<VEC, STRICT> f = seg_identity<VEC, STRICT>(), b = seg_identity<VEC, STRICT>();
+    int mine = 0;
+    for (int k = 0; k < per; k += ITEMS) {
+        const int64_t row0 = lane_row0 + k;
+        TileRows<VEC> T;
+        load_meta<VEC>(A, row0, T);
+        int here = 0;
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            here |= (T.id[i] >= A.inj_lo && T.id[i] < A.inj_hi) ? kFlagInj : 0;
+            here |= (T.id[i] >= A.res_lo && T.id[i] < A.res_hi) ? kFlagRes : 0;
+        }
+        mine |= here;
+        float v[ITEMS][VEC];
+        if (__ballot(here & kFlagInj)) {                     // uniform: rows are read only where something is injected
+            load_injected<VEC, kStreamRows<VEC>>(A, T, col0, col_ok, v);
+        } else {
+#pragma unroll
+            for (int i = 0; i < ITEMS; ++i)
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) v[i][e] = 0.0f;
+        }
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) seg_push<VEC, STRICT>(f, head_f<VEC>(T, i), T.dh[i], v[i]);
+        // backward: this chunk's rows in reverse, then prepended to what the earlier chunks gave (whose
+        // total decay comes from the anchors, not from the product of their rows' decays)
+        Seg<VEC, STRICT> cb = seg_identity<VEC, STRICT>();
+#pragma unroll
+        for (int i = ITEMS - 1; i >= 0; --i) seg_push<VEC, STRICT>(cb, head_b<VEC>(T, i), T.dh[i + 1], v[i]);
+        if (k > 0) b.D = span_decay_b(A, lane_row0, k);
+        b = seg_compose<VEC, STRICT>(cb, b);
+    }
+    f.D = lane_df; b.D = lane_db;
+    f = wave_scan<true, VEC, STRICT>(f, lane, bv, rv);
+    b = wave_scan<false, VEC, STRICT>(b, lane, bv, rv);
+    const int tile_flags = (__ballot(mine & kFlagInj) ? kFlagInj : 0) | (__ballot(mine & kFlagRes) ? kFlagRes : 0);
+    if (lane == 0 && blockIdx.y == 0) {                       // in this geometry a tile is one block
+        A.blk_flags[tile] = (uint32_t)tile_flags;
+        if (A.down_from_list && !A.reduce_from_list && tile_flags == (kFlagInj | kFlagRes))
+            A.list_both[atomicAdd(&A.counters[1], 1u)] = (uint32_t)tile;
+    }
+    const bool sw = c == 0 && blockIdx.y == 0;
+    const bool vec_ok = col_ok && (tile_flags & kFlagInj);   // zero vectors are never fetched: not written either
+    if (r == rv - 1) {
+        f.D = f.C = tile_df;
+        store_level_seg<VEC, STRICT>(A.l1, 0, tile, A.bpad, col0, vec_ok, sw, f, (float)tile_flags);
+    }
+    if (r == 0) {
+        b.D = b.C = tile_db;
+        store_level_seg<VEC, STRICT>(A.l1, 1, tile, A.bpad, col0, vec_ok, sw, b, (float)tile_flags);
     }
 }
 
@@ -1651,6 +1732,9 @@ void launch_all(const ScanArgs& A, const ScanGeom& g, const std::string& tag, hi
                       fp = "scan_down_sparse." + tag;
     if (VEC == 4 && g.sub_shift) {    // wide geometry: a workgroup per tile, a wavefront per block
         LAPLEX_TIMED(fr.c_str(), st, hipLaunchKernelGGL((k_scan_reduce_wide<STRICT>), rgrid, dim3(kWideWaves * 64), 0, st, A));
+    } else if (!A.stage) {            // one wavefront per tile
+        const dim3 lgrid((rgrid.x + kLoneWaves - 1) / kLoneWaves, rgrid.y);
+        LAPLEX_TIMED(fr.c_str(), st, hipLaunchKernelGGL((k_scan_reduce_wave<VEC, STRICT>), lgrid, dim3(kLoneWaves * 64), 0, st, A));
     } else {
         LAPLEX_TIMED(fr.c_str(), st, hipLaunchKernelGGL((k_scan_reduce<VEC, STRICT>), rgrid, bblock, 0, st, A));
     }
