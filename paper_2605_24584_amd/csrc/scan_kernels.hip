@@ -1146,17 +1146,33 @@ k_scan_down(const ScanArgs A)
     }
 
     constexpr bool want_red = STRICT && RED;
-    // weights of the row reduction and the saved strict scans are fetched one row ahead of their use in
-    // the backward walk (holding all rows of both would cost 2 * ITEMS * VEC registers)
-    auto fetch_row = [&](int i, float* wrow, float* zrow) {
+    // The saved strict scans enter the row reduction only through sum_t v * zs, which needs nothing from
+    // the walks: their rows are asked for together with the injected rows and folded into one number per
+    // row.  The weights of the reduction are fetched one row ahead of their use in the backward walk
+    // (holding all rows of them would cost ITEMS * VEC registers).
+    float vz[ITEMS];
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) vz[i] = 0.0f;
+    if (want_red && A.zs) {                              // uniform
+        float zrow[ITEMS][VEC];
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            const bool ok = col_ok && T.id[i] >= A.res_lo && T.id[i] < A.res_hi;
+            load_vec_or_zero<VEC, kStreamRows<VEC>>(zrow[i], A.zs, ((int64_t)T.id[i] - (int64_t)A.res_lo) * A.batch + col0, ok);
+        }
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) vz[i] += v[i][e] * zrow[i][e];
+    }
+    auto fetch_row = [&](int i, float* wrow) {
         const bool ok = col_ok && T.id[i] >= A.res_lo && T.id[i] < A.res_hi;
         const int64_t rr = (int64_t)T.id[i] - (int64_t)A.res_lo;
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) { wrow[e] = 0.0f; zrow[e] = 0.0f; }
+        for (int e = 0; e < VEC; ++e) wrow[e] = 0.0f;
         if (want_red) {                                  // uniform branches
             if (A.wstage) load_vec_or_zero<VEC, kStreamRows<VEC>>(wrow, A.wstage, (row0 + i) * A.batch + col0, ok);
             else load_vec_or_zero<VEC, kStreamRows<VEC>>(wrow, A.w, rr * A.ld_w + col0, ok);
-            if (A.zs) load_vec_or_zero<VEC, kStreamRows<VEC>>(zrow, A.zs, rr * A.batch + col0, ok);
         }
     };
 
@@ -1225,14 +1241,14 @@ k_scan_down(const ScanArgs A)
 
     // backward walk with emission
     const int64_t res_rows = (int64_t)A.res_hi - (int64_t)A.res_lo;
-    float wnext[VEC], znext[VEC];
-    fetch_row(ITEMS - 1, wnext, znext);
+    float wnext[VEC];
+    fetch_row(ITEMS - 1, wnext);
 #pragma unroll
     for (int i = ITEMS - 1; i >= 0; --i) {
-        float wrow[VEC], zsv[VEC];
+        float wrow[VEC];
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) { wrow[e] = wnext[e]; zsv[e] = znext[e]; }
-        if (i > 0) fetch_row(i - 1, wnext, znext);
+        for (int e = 0; e < VEC; ++e) wrow[e] = wnext[e];
+        if (i > 0) fetch_row(i - 1, wnext);
         const bool h = head_b<VEC>(T, i);
         float P[VEC], Z[VEC], Efi[VEC];
 #pragma unroll
@@ -1257,9 +1273,9 @@ k_scan_down(const ScanArgs A)
             }
         }
         if (want_red) {
-            float acc = 0.0f;
+            float acc = vz[i];
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) acc += wrow[e] * Z[e] + v[i][e] * zsv[e];     // wrow, zsv are 0 off the result rows
+            for (int e = 0; e < VEC; ++e) acc += wrow[e] * Z[e];     // wrow is 0 off the result rows
             emit_row_sum(A, acc, bv, c, is_res, rr, res_rows);
         }
     }
