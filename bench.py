@@ -131,7 +131,7 @@ def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only; multi-GPU runs are not part of it "
-              "(the path would shard by batch columns, see DESIGN.md).", file=sys.stderr)
+              "(the path would shard by batch columns: anchors and plan replicated, one all-reduce of ga and gb).", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

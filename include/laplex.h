@@ -169,11 +169,12 @@ int laplex_profile_begin(const char* family /* host string */);
 int laplex_profile_end(double* total_ms, int64_t* launches);
 
 /*
- * Diagnostics: rows of the merged sequence that one workgroup of the scan
- * kernels owns ("tile") for a given batch, with 128-bit lanes (wide != 0: batch
- * and leading dimensions multiples of 4, 16-byte aligned pointers) or scalar
- * lanes.  Lets a benchmark count which tiles a launch visits.  `rows` is a host
- * pointer.
+ * Diagnostics: rows of the merged sequence that one workgroup (for batches of
+ * 253 columns and more with 128-bit lanes: one wavefront) of the downsweep
+ * kernels owns, a "block", for a given batch, with 128-bit lanes (wide != 0:
+ * batch and leading dimensions multiples of 4, 16-byte aligned pointers) or
+ * scalar lanes.  Lets a benchmark count which blocks a launch visits.  `rows`
+ * is a host pointer.
  */
 int laplex_scan_tile_rows(int64_t batch, int wide, int64_t* rows);
 
