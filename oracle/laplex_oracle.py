@@ -198,3 +198,72 @@ def apply_window(a_sample, b, x, window=64.0):
     _load().oracle_apply_window(_p(bs), _I(bs.size), _p(xs), _I(1), _p(q), _I(q.size),
                                 ctypes.c_double(window), _p(y), _p(tol))
     return y, tol
+
+
+# --------------------------------------------------------------------------
+# Phased kernel (Sec. 3, "Phased Laplace kernels"):
+#   P_ij = exp(-|a_i - b_j|) * cos(phi_i - psi_j),
+# phi on the output anchors, psi on the input anchors.
+# --------------------------------------------------------------------------
+
+def _phased_dense(a, phi, b, psi):
+    a, phi, b, psi = _f64(a, 1), _f64(phi, 1), _f64(b, 1), _f64(psi, 1)
+    assert a.size == phi.size and b.size == psi.size
+    diff = a[:, None] - b[None, :]
+    L = np.exp(-np.abs(diff))
+    ang = phi[:, None] - psi[None, :]
+    return L, np.cos(ang), np.sin(ang), np.sign(diff)
+
+
+def phased_apply_brute(a, phi, b, psi, x):
+    """The definition, as a dense k x n matrix: y = P x, and the tolerance
+    denominator sum_j L_ij |x_j| (|cos| <= 1)."""
+    L, C, _, _ = _phased_dense(a, phi, b, psi)
+    x = _f64(x, 2)
+    return (L * C) @ x, L @ np.abs(x)
+
+
+def phased_backward_brute(a, phi, b, psi, x, g):
+    """Gradients of sum(g * (P x)) by differentiating the definition entry by
+    entry (sgn(0) = 0 at ties): (gx, ga, gb, gphi, gpsi) and their tolerance
+    denominators."""
+    L, C, S, sgn = _phased_dense(a, phi, b, psi)
+    x, g = _f64(x, 2), _f64(g, 2)
+    M = g @ x.T                      # M_ij = sum_t g_it x_jt
+    Mabs = np.abs(g) @ np.abs(x).T
+    gx = (L * C).T @ g
+    ga = np.sum(-sgn * L * C * M, axis=1)
+    gb = np.sum(sgn * L * C * M, axis=0)
+    gphi = np.sum(-L * S * M, axis=1)
+    gpsi = np.sum(L * S * M, axis=0)
+    tgx = L.T @ np.abs(g)
+    trow = np.sum(L * Mabs, axis=1); tcol = np.sum(L * Mabs, axis=0)
+    return (gx, ga, gb, gphi, gpsi), (tgx, trow, tcol, trow, tcol)
+
+
+def phased_apply_scan(a, phi, b, psi, x):
+    """The same through the angle-sum identity
+    cos(phi - psi) = cos phi cos psi + sin phi sin psi: two non-phased products
+    of the dual-theorem route with modulated inputs (for sizes where the dense
+    matrix is too large)."""
+    phi, psi, x = _f64(phi, 1), _f64(psi, 1), _f64(x, 2)
+    yc, _ = apply_scan(a, b, x * np.cos(psi)[:, None], with_tol=False)
+    ys, _ = apply_scan(a, b, x * np.sin(psi)[:, None], with_tol=False)
+    _, tol = apply_scan(a, b, np.abs(x))
+    return np.cos(phi)[:, None] * yc + np.sin(phi)[:, None] * ys, tol
+
+
+def phased_backward_scan(a, phi, b, psi, x, g):
+    """Gradients through the same identity: one non-phased forward and backward
+    on the doubled batch [x cos psi | x sin psi], [g cos phi | g sin phi]."""
+    phi, psi, x, g = _f64(phi, 1), _f64(psi, 1), _f64(x, 2), _f64(g, 2)
+    B = x.shape[1]
+    cf, sf, cp, sp = np.cos(phi)[:, None], np.sin(phi)[:, None], np.cos(psi)[:, None], np.sin(psi)[:, None]
+    x2 = np.hstack([x * cp, x * sp]); g2 = np.hstack([g * cf, g * sf])
+    (gx2, ga, gb), _ = apply_backward_scan(a, b, x2, g2)
+    y2, _ = apply_scan(a, b, x2, with_tol=False)
+    gx = cp * gx2[:, :B] + sp * gx2[:, B:]
+    gphi = np.sum(g * (cf * y2[:, B:] - sf * y2[:, :B]), axis=1)
+    gpsi = np.sum(x * (cp * gx2[:, B:] - sp * gx2[:, :B]), axis=1)
+    _, (tgx, tga, tgb) = apply_backward_scan(a, b, x, g)
+    return (gx, ga, gb, gphi, gpsi), (tgx, tga, tgb, tga, tgb)

@@ -342,3 +342,116 @@ def test_merged_permutation_brute_force_rank(oracle):
     rank = np.array([(m < m[i]).sum() + (m[:i] == m[i]).sum() for i in range(300)])
     want = np.empty(300, dtype=np.int64); want[rank] = np.arange(300)
     assert perm.tolist() == want.tolist()
+
+
+# ---------------------------------------------------------------- phased kernel
+
+def _phased_routes(oracle, route):
+    if route == "brute":
+        return oracle.phased_apply_brute, oracle.phased_backward_brute
+    return oracle.phased_apply_scan, oracle.phased_backward_scan
+
+
+@pytest.mark.parametrize("route", ["brute", "scan"])
+def test_golden_phased(oracle, route):
+    gd = read_golden("phased_rational_3x2.txt")
+    a = np.log(np.array(gd["exp_a"])); b = np.log(np.array(gd["exp_b"]))
+    phi = np.array(gd["phi_thirds"]) * math.pi / 3; psi = np.array(gd["psi_thirds"]) * math.pi / 3
+    x = np.array(gd["x"]).reshape(-1, 1); g = np.array(gd["g"]).reshape(-1, 1)
+    fwd, bwd = _phased_routes(oracle, route)
+    y, _ = fwd(a, phi, b, psi, x)
+    (gx, ga, gb, gphi, gpsi), _ = bwd(a, phi, b, psi, x, g)
+    np.testing.assert_allclose(y[:, 0], gd["y"], rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(gx[:, 0], gd["gx"], rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(ga, gd["ga"], rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(gb, gd["gb"], rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(gphi / math.sqrt(3), gd["gphi_over_sqrt3"], rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(gpsi / math.sqrt(3), gd["gpsi_over_sqrt3"], rtol=1e-13, atol=1e-13)
+
+
+@pytest.mark.parametrize("route", ["brute", "scan"])
+def test_phased_with_zero_phases_is_the_plain_kernel(oracle, route):
+    r = rng(41)
+    k, n, batch = 9, 14, 3
+    a = np.round(r.uniform(0, 3, k) * 2) / 2; b = np.round(r.uniform(0, 3, n) * 2) / 2      # with ties
+    x = r.normal(size=(n, batch)); g = r.normal(size=(k, batch))
+    fwd, bwd = _phased_routes(oracle, route)
+    y, tol = fwd(a, np.zeros(k), b, np.zeros(n), x)
+    (gx, ga, gb, gphi, gpsi), _ = bwd(a, np.zeros(k), b, np.zeros(n), x, g)
+    y0, tol0 = oracle.apply_brute(a, b, x)
+    (gx0, ga0, gb0), _ = oracle.apply_backward_brute(a, b, x, g)
+    np.testing.assert_allclose(y, y0, atol=1e-13); np.testing.assert_allclose(tol, tol0, atol=1e-13)
+    np.testing.assert_allclose(gx, gx0, atol=1e-13)
+    np.testing.assert_allclose(ga, ga0, atol=1e-12); np.testing.assert_allclose(gb, gb0, atol=1e-12)
+    assert np.all(gphi == 0) and np.all(gpsi == 0)
+
+
+@pytest.mark.parametrize("route", ["brute", "scan"])
+def test_phased_closed_forms_and_invariances(oracle, route):
+    fwd, bwd = _phased_routes(oracle, route)
+    # one anchor each: the matrix entry itself
+    y, _ = fwd([0.3], [1.1], [1.0], [0.4], [[2.0]])
+    assert y[0, 0] == pytest.approx(2.0 * math.exp(-0.7) * math.cos(0.7), rel=1e-14)
+    r = rng(42)
+    k, n, batch = 8, 12, 2
+    a = r.uniform(0, 3, k); b = r.uniform(0, 3, n); phi = r.uniform(-3, 3, k); psi = r.uniform(-3, 3, n)
+    x = r.normal(size=(n, batch)); g = r.normal(size=(k, batch))
+    y, _ = fwd(a, phi, b, psi, x)
+    # quadrature: every phase difference pi/2 -> nothing passes
+    yq, tq = fwd(a, np.full(k, 0.25 + math.pi / 2), b, np.full(n, 0.25), x)
+    assert np.all(np.abs(yq) <= 1e-15 * tq + 1e-300)
+    # opposite phase: the plain product with the sign flipped
+    yo, _ = fwd(a, np.full(k, math.pi), b, np.zeros(n), x)
+    np.testing.assert_allclose(yo, -oracle.apply_brute(a, b, x)[0], atol=1e-13)
+    # a common shift of all phases changes nothing; the phase gradients sum to zero, the anchor gradients too
+    ys, _ = fwd(a, phi + 0.9, b, psi + 0.9, x)
+    np.testing.assert_allclose(ys, y, atol=1e-13)
+    (gx, ga, gb, gphi, gpsi), _ = bwd(a, phi, b, psi, x, g)
+    assert gphi.sum() + gpsi.sum() == pytest.approx(0.0, abs=1e-12)
+    assert ga.sum() + gb.sum() == pytest.approx(0.0, abs=1e-12)
+    # transposition: sum(g * P x) = sum(x * P^T g)
+    assert float(np.sum(g * y)) == pytest.approx(float(np.sum(x * gx)), rel=1e-12)
+
+
+@pytest.mark.parametrize("route", ["brute", "scan"])
+def test_phased_gradients_central_differences(oracle, route):
+    r = rng(43)
+    k, n, batch = 5, 7, 2
+    a = r.uniform(0, 4, k); b = r.uniform(0, 4, n); phi = r.uniform(-3, 3, k); psi = r.uniform(-3, 3, n)
+    x = r.normal(size=(n, batch)); g = r.normal(size=(k, batch))
+    _, bwd = _phased_routes(oracle, route)
+    (gx, ga, gb, gphi, gpsi), _ = bwd(a, phi, b, psi, x, g)
+
+    def loss(a_, phi_, b_, psi_, x_):
+        return float(np.sum(g * oracle.phased_apply_brute(a_, phi_, b_, psi_, x_)[0]))
+
+    h = 1e-6
+    for name, grad, idx in (("a", ga, 0), ("phi", gphi, 1), ("b", gb, 2), ("psi", gpsi, 3)):
+        args = [a, phi, b, psi, x]
+        for i in range(grad.size):
+            d = np.zeros(grad.size); d[i] = h
+            up = list(args); up[idx] = args[idx] + d
+            dn = list(args); dn[idx] = args[idx] - d
+            fd = (loss(*up) - loss(*dn)) / (2 * h)
+            assert grad[i] == pytest.approx(fd, rel=1e-6, abs=1e-8), name
+    for j in range(n):
+        for t in range(batch):
+            dx = np.zeros_like(x); dx[j, t] = 1.0
+            assert gx[j, t] == pytest.approx(loss(a, phi, b, psi, x + dx) - loss(a, phi, b, psi, x), rel=1e-9, abs=1e-10)
+
+
+def test_phased_scan_route_matches_brute_force(oracle):
+    r = rng(44)
+    k, n, batch = 300, 700, 3
+    a = np.round(r.uniform(0, 12, k) * 8) / 8; b = np.round(r.uniform(0, 12, n) * 8) / 8       # many exact ties
+    phi = r.uniform(-6, 6, k); psi = r.uniform(-6, 6, n)
+    x = r.normal(size=(n, batch)); g = r.normal(size=(k, batch))
+    y, tol = oracle.phased_apply_brute(a, phi, b, psi, x)
+    ys, tols = oracle.phased_apply_scan(a, phi, b, psi, x)
+    assert np.all(np.abs(y - ys) <= 1e-12 * tol + 1e-300)
+    np.testing.assert_allclose(tols, tol, rtol=1e-12)
+    G, T = oracle.phased_backward_brute(a, phi, b, psi, x, g)
+    Gs, Ts = oracle.phased_backward_scan(a, phi, b, psi, x, g)
+    for u, v, t, ts in zip(G, Gs, T, Ts):
+        assert np.all(np.abs(u - v) <= 1e-11 * t + 1e-300)
+        np.testing.assert_allclose(ts, t, rtol=1e-11)
