@@ -36,7 +36,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-columns", type=int, default=256)
     ap.add_argument("--workload", default="projection",
-                    choices=["projection", "square", "tie_heavy", "gram", "billion"],
+                    choices=["projection", "square", "tie_heavy", "gram", "billion", "phased"],
                     help="projection is the benchmark; the others time one forward+backward step of the "
                          "other workloads (for profiles; no roofline object, no CPU baseline)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -94,6 +94,21 @@ def other_workload(args, torch, np, B, synth):
             B.laplex_gram(da, dx, y, ws, B.LAPLEX_SAVE_SCANS)
             B.laplex_gram_backward(da, dx, dg, gx, ga, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
         elements = n * batch
+    elif args.workload == "phased":
+        w = synth.projection_layer_phased(scale=args.scale, batch=args.batch)
+        a, b, x, g = w["a"], w["b"], w["x"], w["g"]
+        k, n, batch = a.size, b.size, x.shape[1]
+        ws = torch.empty(B.laplex_phased_workspace_bytes(k, n, batch), dtype=torch.uint8, device="cuda")
+        da, db, dphi, dpsi, dx, dg = dev(a), dev(b), dev(w["phi"]), dev(w["psi"]), dev(x), dev(g)
+        y = torch.empty(k, batch, device="cuda"); gx = torch.empty(n, batch, device="cuda")
+        ga = torch.empty(k, device="cuda"); gb = torch.empty(n, device="cuda")
+        gphi = torch.empty(k, device="cuda"); gpsi = torch.empty(n, device="cuda")
+
+        def step():
+            B.laplex_phased_apply(da, dphi, db, dpsi, dx, y, ws, B.LAPLEX_SAVE_SCANS)
+            B.laplex_phased_apply_backward(da, dphi, db, dpsi, dx, dg, gx, ga, gb, gphi, gpsi, ws,
+                                           B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
+        elements = (n + k) * batch
     else:
         make = {"square": synth.square_small, "tie_heavy": synth.tie_heavy, "billion": synth.billion_square}[args.workload]
         w = make(scale=args.scale)

@@ -140,6 +140,44 @@ int laplex_gram_backward(const float* a, int64_t n, const float* x, int64_t ldx,
                          void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream);
 
 /*
+ * Phased kernel (Sec. 3, "Phased Laplace kernels"):
+ *
+ *   y[i*ldy + t] = sum_j exp(-|a[i] - b[j]|) * cos(phi[i] - psi[j]) * x[j*ldx + t]
+ *
+ * phi[k] are the phases of the output anchors, psi[n] those of the input
+ * anchors (radians).  By the angle-sum identity the product is two plain
+ * products on a doubled batch plus pointwise modulation, which is how it is
+ * computed: the workspace (laplex_phased_workspace_bytes) holds the plain
+ * workspace for batch 2*batch at its front (the plan, as above) and the cosine
+ * and sine halves of x, y, gy and gx behind it.  Same flags as laplex_apply;
+ * LAPLEX_SAVE_SCANS also keeps the halves of x and of the product for
+ * laplex_phased_apply_backward.  Limits as above with 2*batch for batch.
+ */
+int laplex_phased_workspace_bytes(int64_t k, int64_t n, int64_t batch, size_t* out /* host */);
+
+int laplex_phased_apply(const float* a, const float* phi, int64_t k,
+                        const float* b, const float* psi, int64_t n,
+                        const float* x, int64_t ldx, int64_t batch, float* y, int64_t ldy,
+                        void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream);
+
+/*
+ * Gradients of sum(gy * y) of the phased product: gx[n][batch], ga[k], gb[n],
+ * gphi[k], gpsi[n]; any of them may be NULL (= not wanted).  x may be NULL if
+ * only gx is wanted.  Anchor gradients follow the tie rule above (tied pairs
+ * contribute nothing); the phase gradients are
+ *   gphi[i] = -sum_t gy[i,t] sum_j exp(-|a_i - b_j|) sin(phi_i - psi_j) x[j,t]
+ *   gpsi[j] = +sum_t x[j,t]  sum_i exp(-|a_i - b_j|) sin(phi_i - psi_j) gy[i,t].
+ * With LAPLEX_SAVE_SCANS (and LAPLEX_REUSE_PLAN) the call continues a
+ * laplex_phased_apply on the same anchors, phases, x and workspace; without,
+ * it stands alone (and, if gphi is wanted, computes the forward product itself).
+ */
+int laplex_phased_apply_backward(const float* a, const float* phi, int64_t k,
+                                 const float* b, const float* psi, int64_t n,
+                                 const float* x, int64_t ldx, const float* gy, int64_t ldgy, int64_t batch,
+                                 float* gx, int64_t ldgx, float* ga, float* gb, float* gphi, float* gpsi,
+                                 void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream);
+
+/*
  * Verification hook: copy the first `count` sorted ids of the plan in `ws`
  * (count = k + n for the apply form, n for the Gram form) to the device buffer
  * perm_out.  id < k names output anchor a[id]; id >= k names input b[id-k].

@@ -32,6 +32,7 @@ EXPORTS = (
     "laplex_workspace_bytes", "laplex_apply", "laplex_apply_backward", "laplex_gram",
     "laplex_gram_backward", "laplex_get_perm", "laplex_status_string", "laplex_last_hip_error",
     "laplex_profile_begin", "laplex_profile_end", "laplex_scan_tile_rows",
+    "laplex_phased_workspace_bytes", "laplex_phased_apply", "laplex_phased_apply_backward",
 )
 
 _lib = None
@@ -69,6 +70,10 @@ def lib() -> ctypes.CDLL:
         L.laplex_profile_begin.argtypes = [ctypes.c_char_p]
         L.laplex_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
         L.laplex_scan_tile_rows.argtypes = [_I, ctypes.c_int, ctypes.POINTER(_I)]
+        L.laplex_phased_workspace_bytes.argtypes = [_I, _I, _I, ctypes.POINTER(_Z)]
+        L.laplex_phased_apply.argtypes = [_P, _P, _I, _P, _P, _I, _P, _I, _I, _P, _I, _P, _Z, _U, _P]
+        L.laplex_phased_apply_backward.argtypes = [_P, _P, _I, _P, _P, _I, _P, _I, _P, _I, _I,
+                                                   _P, _I, _P, _P, _P, _P, _P, _Z, _U, _P]
         for name in EXPORTS[:6] + EXPORTS[8:]:
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -166,3 +171,23 @@ def laplex_scan_tile_rows(batch: int, wide: bool) -> int:
     rows = _I(0)
     _check(lib().laplex_scan_tile_rows(batch, 1 if wide else 0, ctypes.byref(rows)))
     return rows.value
+
+
+def laplex_phased_workspace_bytes(k: int, n: int, batch: int) -> int:
+    out = _Z(0)
+    _check(lib().laplex_phased_workspace_bytes(k, n, batch, ctypes.byref(out)))
+    return out.value
+
+
+def laplex_phased_apply(a, phi, b, psi, x, y, ws, flags: int = 0, stream=None) -> None:
+    """y (k, batch) <- P x with P_ij = exp(-|a_i - b_j|) cos(phi_i - psi_j)."""
+    _check(lib().laplex_phased_apply(
+        _ptr(a), _ptr(phi), a.numel(), _ptr(b), _ptr(psi), b.numel(), _ptr(x), _ld(x), _batch(x),
+        _ptr(y), _ld(y), _ptr(ws), ws.numel(), flags, _stream(stream)))
+
+
+def laplex_phased_apply_backward(a, phi, b, psi, x, gy, gx, ga, gb, gphi, gpsi, ws, flags: int = 0, stream=None) -> None:
+    """gradients of sum(gy * y) of the phased product; any output may be None."""
+    _check(lib().laplex_phased_apply_backward(
+        _ptr(a), _ptr(phi), a.numel(), _ptr(b), _ptr(psi), b.numel(), _ptr(x), _ld(x), _ptr(gy), _ld(gy), _batch(gy),
+        _ptr(gx), _ld(gx), _ptr(ga), _ptr(gb), _ptr(gphi), _ptr(gpsi), _ptr(ws), ws.numel(), flags, _stream(stream)))

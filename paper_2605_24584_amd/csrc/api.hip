@@ -149,6 +149,32 @@ ScanProblem problem(const Plan& P, const Layout& L)
     return p;
 }
 
+// Workspace of the phased entry points: the workspace of the plain apply on the doubled batch
+// (so the plan stays at the front), then the cosine / sine halves of x, y, gy and gx.
+struct PhasedLayout {
+    size_t inner = 0, off_x2 = 0, off_y2 = 0, off_g2 = 0, off_gx2 = 0, total = 0;
+};
+
+PhasedLayout phased_layout(int64_t k, int64_t n, int64_t batch)
+{
+    PhasedLayout P;
+    P.inner = align_up(make_layout(k + n, k, 2 * batch).total);
+    size_t o = P.inner;
+    const size_t in_bytes = sizeof(float) * 2 * (size_t)batch * (size_t)n, out_bytes = sizeof(float) * 2 * (size_t)batch * (size_t)k;
+    P.off_x2 = o;  o = align_up(o + in_bytes);
+    P.off_y2 = o;  o = align_up(o + out_bytes);
+    P.off_g2 = o;  o = align_up(o + out_bytes);
+    P.off_gx2 = o; o = align_up(o + in_bytes);
+    P.total = o;
+    return P;
+}
+
+int check_phased_sizes(int64_t k, int64_t n, int64_t batch)
+{
+    if (batch < 0 || batch > INT64_MAX / 4) return LAPLEX_ERR_SIZE;
+    return check_sizes(k, n, 2 * batch);
+}
+
 }  // namespace
 
 extern "C" {
@@ -324,6 +350,101 @@ int laplex_gram_backward(const float* a, int64_t n, const float* x, int64_t ldx,
         p.tag = "bwd";
         LAPLEX_HIP(launch_scan(p, L, w, st));
     }
+    return LAPLEX_OK;
+}
+
+int laplex_phased_workspace_bytes(int64_t k, int64_t n, int64_t batch, size_t* out)
+{
+    if (!out) return LAPLEX_ERR_NULL;
+    LAPLEX_CHECK(check_phased_sizes(k, n, batch));
+    *out = phased_layout(k, n, batch).total;
+    return LAPLEX_OK;
+}
+
+int laplex_phased_apply(const float* a, const float* phi, int64_t k, const float* b, const float* psi, int64_t n,
+                        const float* x, int64_t ldx, int64_t batch, float* y, int64_t ldy,
+                        void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream)
+{
+    const uint32_t known = LAPLEX_A_SORTED | LAPLEX_B_SORTED | LAPLEX_REUSE_PLAN | LAPLEX_SAVE_SCANS;
+    if (flags & ~known) return LAPLEX_ERR_FLAGS;
+    LAPLEX_CHECK(check_phased_sizes(k, n, batch));
+    LAPLEX_CHECK(check_vector(a, k, true));
+    LAPLEX_CHECK(check_vector(phi, k, true));
+    LAPLEX_CHECK(check_vector(b, n, true));
+    LAPLEX_CHECK(check_vector(psi, n, true));
+    LAPLEX_CHECK(check_matrix(x, n, ldx, batch, true));
+    LAPLEX_CHECK(check_matrix(y, k, ldy, batch, true));
+    if (k == 0 || batch == 0) return LAPLEX_OK;
+    hipStream_t st = stream;
+    if (n == 0) {
+        LAPLEX_HIP(launch_fill(y, k, batch, ldy, 0.0f, st));
+        return LAPLEX_OK;
+    }
+    const PhasedLayout P = phased_layout(k, n, batch);
+    if (!ws) return LAPLEX_ERR_NULL;
+    if (misaligned(ws, 256)) return LAPLEX_ERR_ALIGN;
+    if (ws_bytes < P.total) return LAPLEX_ERR_WORKSPACE;
+    char* w = static_cast<char*>(ws);
+    float* x2 = reinterpret_cast<float*>(w + P.off_x2);
+    float* y2 = reinterpret_cast<float*>(w + P.off_y2);
+    LAPLEX_HIP(launch_phase_split(x, ldx, psi, n, batch, x2, st));
+    LAPLEX_CHECK(laplex_apply(a, k, b, n, x2, 2 * batch, 2 * batch, y2, 2 * batch, ws, P.inner, flags, stream));
+    LAPLEX_HIP(launch_phase_merge(y2, phi, k, batch, y, ldy, nullptr, 0, nullptr, st));
+    return LAPLEX_OK;
+}
+
+int laplex_phased_apply_backward(const float* a, const float* phi, int64_t k, const float* b, const float* psi, int64_t n,
+                                 const float* x, int64_t ldx, const float* gy, int64_t ldgy, int64_t batch,
+                                 float* gx, int64_t ldgx, float* ga, float* gb, float* gphi, float* gpsi,
+                                 void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream)
+{
+    const uint32_t known = LAPLEX_A_SORTED | LAPLEX_B_SORTED | LAPLEX_REUSE_PLAN | LAPLEX_SAVE_SCANS;
+    if (flags & ~known) return LAPLEX_ERR_FLAGS;
+    LAPLEX_CHECK(check_phased_sizes(k, n, batch));
+    LAPLEX_CHECK(check_vector(a, k, true));
+    LAPLEX_CHECK(check_vector(phi, k, true));
+    LAPLEX_CHECK(check_vector(b, n, true));
+    LAPLEX_CHECK(check_vector(psi, n, true));
+    const bool need_x = ga || gb || gphi || gpsi;
+    LAPLEX_CHECK(check_matrix(x, n, ldx, batch, need_x));
+    LAPLEX_CHECK(check_matrix(gy, k, ldgy, batch, true));
+    LAPLEX_CHECK(check_matrix(gx, n, ldgx, batch, false));
+    LAPLEX_CHECK(check_vector(ga, k, false));
+    LAPLEX_CHECK(check_vector(gb, n, false));
+    LAPLEX_CHECK(check_vector(gphi, k, false));
+    LAPLEX_CHECK(check_vector(gpsi, n, false));
+    hipStream_t st = stream;
+    if (k == 0 || n == 0 || batch == 0) {      // one side is empty: every wanted gradient is zero
+        if (gx) LAPLEX_HIP(launch_fill(gx, n, batch, ldgx, 0.0f, st));
+        if (ga) LAPLEX_HIP(launch_fill(ga, k, 1, 1, 0.0f, st));
+        if (gb) LAPLEX_HIP(launch_fill(gb, n, 1, 1, 0.0f, st));
+        if (gphi) LAPLEX_HIP(launch_fill(gphi, k, 1, 1, 0.0f, st));
+        if (gpsi) LAPLEX_HIP(launch_fill(gpsi, n, 1, 1, 0.0f, st));
+        return LAPLEX_OK;
+    }
+    const PhasedLayout P = phased_layout(k, n, batch);
+    if (!ws) return LAPLEX_ERR_NULL;
+    if (misaligned(ws, 256)) return LAPLEX_ERR_ALIGN;
+    if (ws_bytes < P.total) return LAPLEX_ERR_WORKSPACE;
+    char* w = static_cast<char*>(ws);
+    float* x2 = reinterpret_cast<float*>(w + P.off_x2);
+    float* y2 = reinterpret_cast<float*>(w + P.off_y2);
+    float* g2 = reinterpret_cast<float*>(w + P.off_g2);
+    float* gx2 = reinterpret_cast<float*>(w + P.off_gx2);
+    const bool saved = (flags & LAPLEX_SAVE_SCANS) != 0;      // the forward left x's halves, its product and its scans
+    if (x && !saved) LAPLEX_HIP(launch_phase_split(x, ldx, psi, n, batch, x2, st));
+    LAPLEX_HIP(launch_phase_split(gy, ldgy, phi, k, batch, g2, st));
+    uint32_t inner = flags;
+    if (gphi && !saved) {       // the phase gradient of the outputs needs the two halves of the product
+        LAPLEX_CHECK(laplex_apply(a, k, b, n, x2, 2 * batch, 2 * batch, y2, 2 * batch, ws, P.inner,
+                                  flags | LAPLEX_SAVE_SCANS, stream));
+        inner = flags | LAPLEX_SAVE_SCANS | LAPLEX_REUSE_PLAN;
+    }
+    const bool want_gx2 = gx || gpsi;
+    LAPLEX_CHECK(laplex_apply_backward(a, k, b, n, x ? x2 : nullptr, 2 * batch, g2, 2 * batch, 2 * batch,
+                                       want_gx2 ? gx2 : nullptr, 2 * batch, ga, gb, ws, P.inner, inner, stream));
+    if (want_gx2) LAPLEX_HIP(launch_phase_merge(gx2, psi, n, batch, gx, ldgx, x, ldx, gpsi, st));
+    if (gphi) LAPLEX_HIP(launch_phase_merge(y2, phi, k, batch, nullptr, 0, gy, ldgy, gphi, st));
     return LAPLEX_OK;
 }
 

@@ -246,6 +246,15 @@ struct ScanProblem {
 };
 hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStream_t st);
 
+// Phase modulation of the phased kernel (phase_kernels.hip): split a (rows, batch) matrix into its
+// cosine and sine halves, dst (rows, 2*batch) contiguous; merge two halves back and, if wanted, form
+//   gphase[r] = sum_t other[r][t] (cos(phase_r) src2[r][batch+t] - sin(phase_r) src2[r][t]).
+hipError_t launch_phase_split(const float* src, int64_t ld_src, const float* phase, int64_t rows, int64_t batch,
+                              float* dst, hipStream_t st);
+hipError_t launch_phase_merge(const float* src2, const float* phase, int64_t rows, int64_t batch,
+                              float* dst, int64_t ld_dst, const float* other, int64_t ld_other, float* gphase,
+                              hipStream_t st);
+
 // out[r] = sum_t u[r*ldu+t] * v[r*ldv+t]
 hipError_t launch_rowdot(const float* u, int64_t ldu, const float* v, int64_t ldv,
                          int64_t rows, int64_t batch, float* out, hipStream_t st);

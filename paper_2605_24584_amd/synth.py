@@ -129,6 +129,16 @@ def projection_layer(scale: int = 1, batch: int = 256):
     )
 
 
+def projection_layer_phased(scale: int = 1, batch: int = 256):
+    """The projection layer with phases on both anchor sets, phi (outputs) and
+    psi (inputs) ~ U(-pi, pi) (streams of their own, config slot 7)."""
+    w = projection_layer(scale=scale, batch=batch)
+    w["name"] = "projection_phased_n2^20_k1024_b256"
+    w["phi"] = uniform(stream_seed(7, STREAM_A), w["k"], -np.pi, np.pi)
+    w["psi"] = uniform(stream_seed(7, STREAM_B), w["n"], -np.pi, np.pi)
+    return w
+
+
 def tie_heavy(scale: int = 1):
     """n = k = 2^24, batch 1, anchors U(0, 2^18) rounded to a 1/4 grid."""
     n = k = _shrunk(1 << 24, scale)

@@ -448,3 +448,71 @@ def test_non_finite_anchors_do_not_fault(oracle, sorted_flags):
     y2, _ = gpu_apply(a2, b2, x, ws=ws)
     ref, tol = oracle.apply_scan(a2, b2, x)
     assert_close("y", y2, ref, tol)
+
+
+# ------------------------------------------------------------------ phased kernel
+
+def phased_workspace(k, n, batch):
+    return torch.empty(B.laplex_phased_workspace_bytes(k, n, batch), dtype=torch.uint8, device="cuda")
+
+
+def gpu_phased(a, phi, b, psi, x, g, flags_fwd=B.LAPLEX_SAVE_SCANS, flags_bwd=B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN,
+               want=(True, True, True, True, True), ws=None, forward=True):
+    k, n, batch = a.size, b.size, x.shape[1]
+    ws = phased_workspace(k, n, batch) if ws is None else ws
+    da, dphi, db, dpsi, dx, dg = dev(a), dev(phi), dev(b), dev(psi), dev(x), dev(g)
+    y = torch.full((k, batch), float("nan"), device="cuda")
+    if forward:
+        B.laplex_phased_apply(da, dphi, db, dpsi, dx, y, ws, flags_fwd)
+    outs = [torch.full(s, float("nan"), device="cuda") if w else None
+            for s, w in zip(((n, batch), (k,), (n,), (k,), (n,)), want)]
+    B.laplex_phased_apply_backward(da, dphi, db, dpsi, dx, dg, *outs, ws, flags_bwd)
+    torch.cuda.synchronize()
+    return y.cpu().numpy(), tuple(None if t is None else t.cpu().numpy() for t in outs), ws
+
+
+@pytest.mark.parametrize("kind", ["uniform", "ties"])
+@pytest.mark.parametrize("k,n,batch", [(5, 1, 2), (37, 53, 3), (2500, 4000, 8), (300, 2100, 64), (24, 7000, 128),
+                                       (700, 900, 130)])
+def test_phased_forward_backward(oracle, kind, k, n, batch):
+    r = np.random.default_rng(5000 + k + n + batch)
+    a, b = anchors(kind, r, k, n)
+    phi = r.uniform(-7, 7, k).astype(np.float32); psi = r.uniform(-7, 7, n).astype(np.float32)
+    x = r.normal(size=(n, batch)).astype(np.float32); g = r.normal(size=(k, batch)).astype(np.float32)
+    small = k * n <= 4e6
+    ref, tol = (oracle.phased_apply_brute if small else oracle.phased_apply_scan)(a, phi, b, psi, x)
+    want, tols = (oracle.phased_backward_brute if small else oracle.phased_backward_scan)(a, phi, b, psi, x, g)
+    y, grads, ws = gpu_phased(a, phi, b, psi, x, g)
+    assert_close("y", y, ref, tol)
+    for name, got, rv, tv in zip(("gx", "ga", "gb", "gphi", "gpsi"), grads, want, tols):
+        assert_close(name, got, rv, tv)
+    # standing alone (sorts, modulates and, for gphi, multiplies itself): the same bits
+    _, alone, _ = gpu_phased(a, phi, b, psi, x, g, flags_bwd=0, forward=False)
+    for name, u, v in zip(("gx", "ga", "gb", "gphi", "gpsi"), grads, alone):
+        assert np.array_equal(u, v), name
+
+
+def test_phased_subsets_and_empty_sides(oracle):
+    r = np.random.default_rng(77)
+    k, n, batch = 40, 300, 5
+    a, b = anchors("uniform", r, k, n)
+    phi = r.uniform(-3, 3, k).astype(np.float32); psi = r.uniform(-3, 3, n).astype(np.float32)
+    x = r.normal(size=(n, batch)).astype(np.float32); g = r.normal(size=(k, batch)).astype(np.float32)
+    want, tols = oracle.phased_backward_brute(a, phi, b, psi, x, g)
+    names = ("gx", "ga", "gb", "gphi", "gpsi")
+    for pick in ((True, False, False, False, False), (False, False, False, True, False),
+                 (False, True, False, False, True), (False, False, True, False, False)):
+        _, grads, _ = gpu_phased(a, phi, b, psi, x, g, flags_bwd=0, want=pick, forward=False)
+        for name, got, rv, tv, w in zip(names, grads, want, tols, pick):
+            if w:
+                assert_close(name, got, rv, tv)
+    # gx alone needs no x
+    ws = phased_workspace(k, n, batch)
+    gx = torch.full((n, batch), float("nan"), device="cuda")
+    B.laplex_phased_apply_backward(dev(a), dev(phi), dev(b), dev(psi), None, dev(g), gx, None, None, None, None, ws, 0)
+    torch.cuda.synchronize()
+    assert_close("gx", gx.cpu().numpy(), want[0], tols[0])
+    # no inputs: y = 0 and every gradient 0
+    e = np.zeros(0, dtype=np.float32)
+    y, grads, _ = gpu_phased(a, phi, e, e, np.zeros((0, batch), dtype=np.float32), g, flags_fwd=0, flags_bwd=0)
+    assert np.all(y == 0) and all(np.all(t == 0) for t in grads)

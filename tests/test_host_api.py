@@ -146,3 +146,43 @@ def test_oracle_is_not_reachable_from_the_product():
         for fn in files:
             if fn.endswith((".py", ".hip", ".h", ".cpp")):
                 assert not pat.search(open(os.path.join(dirpath, fn)).read()), fn
+
+
+# ------------------------------------------------------------------ phased entry points
+
+def phased_ws(L, k, n, batch):
+    out = ctypes.c_size_t(0)
+    rc = L.laplex_phased_workspace_bytes(k, n, batch, ctypes.byref(out))
+    return rc, out.value
+
+
+def test_phased_workspace_and_argument_checks(L):
+    assert L.laplex_phased_workspace_bytes(1, 1, 1, None) == B.LAPLEX_ERR_NULL
+    assert phased_ws(L, 1, 1, -1)[0] == B.LAPLEX_ERR_SIZE
+    rc, size = phased_ws(L, 64, 4096, 8)
+    plain = ctypes.c_size_t(0)
+    assert L.laplex_workspace_bytes(64, 4096, 16, ctypes.byref(plain)) == 0
+    # the plain workspace of the doubled batch plus the halves of x, gx (n rows) and y, gy (k rows)
+    assert rc == 0 and size % 256 == 0 and size >= plain.value + 4 * 16 * (2 * 4096 + 2 * 64)
+    k, n, batch = 8, 8, 4
+    good = [FAKE, FAKE, k, FAKE, FAKE, n, FAKE, batch, batch, FAKE, batch, FAKE, size, 0, None]
+    def call(**kw):
+        args = list(good)
+        for i, v in kw.items():
+            args[int(i[1:])] = v
+        return L.laplex_phased_apply(*args)
+    assert call(_1=None) == B.LAPLEX_ERR_NULL           # phi
+    assert call(_4=None) == B.LAPLEX_ERR_NULL           # psi
+    assert call(_6=None) == B.LAPLEX_ERR_NULL           # x
+    assert call(_7=batch - 1) == B.LAPLEX_ERR_LD
+    assert call(_11=None) == B.LAPLEX_ERR_NULL          # workspace
+    assert call(_12=16) == B.LAPLEX_ERR_WORKSPACE
+    assert call(_13=1 << 20) == B.LAPLEX_ERR_FLAGS
+    assert call(_3=FAKE + 2) == B.LAPLEX_ERR_ALIGN
+    assert call(_2=0) == B.LAPLEX_OK                     # k == 0: nothing to do, nothing touched
+    # backward: x may be missing only if gx alone is wanted
+    bgood = [FAKE, FAKE, k, FAKE, FAKE, n, None, batch, FAKE, batch, batch,
+             FAKE, batch, None, None, None, FAKE, FAKE, size, 0, None]
+    assert L.laplex_phased_apply_backward(*bgood) == B.LAPLEX_ERR_NULL      # gpsi wanted, x missing
+    bgood[8] = None; bgood[6] = FAKE
+    assert L.laplex_phased_apply_backward(*bgood) == B.LAPLEX_ERR_NULL      # gy missing
