@@ -267,3 +267,48 @@ def phased_backward_scan(a, phi, b, psi, x, g):
     gpsi = np.sum(x * (cp * gx2[:, B:] - sp * gx2[:, :B]), axis=1)
     _, (tgx, tga, tgb) = apply_backward_scan(a, b, x, g)
     return (gx, ga, gb, gphi, gpsi), (tgx, tga, tgb, tga, tgb)
+
+
+# --------------------------------------------------------------------------
+# Temperature (App. A "Expressivity"): L_t = [exp(-|a_i - b_j| / t)], with the
+# inverse temperature tau = 1/t of the experiments: L_tau = exp(-tau |a_i - b_j|).
+# --------------------------------------------------------------------------
+
+def tau_apply_dense(a, b, tau, x):
+    """The definition with the temperature inside the exponent (fp64 throughout)."""
+    a, b, x = _f64(a, 1), _f64(b, 1), _f64(x, 2)
+    L = np.exp(-float(tau) * np.abs(a[:, None] - b[None, :]))
+    return L @ x, L @ np.abs(x)
+
+
+def scaled_anchors(v, tau, fp32=True):
+    """tau * v: rounded to fp32 (one multiplication, as the library forms its
+    keys: the sorted order and the ties are those of the rounded products) or exact."""
+    if fp32:
+        return (np.float32(tau) * np.asarray(v, dtype=np.float32)).astype(np.float32)
+    return float(tau) * _f64(v, 1)
+
+
+def tau_apply(a, b, tau, x, fp32=True, brute=True):
+    f = apply_brute if brute else apply_scan
+    return f(scaled_anchors(a, tau, fp32), scaled_anchors(b, tau, fp32), x)
+
+
+def tau_backward(a, b, tau, x, g, fp32=True, brute=True):
+    """(gx, ga, gb, gtau) of sum(g * L_tau x) by the chain rule through the scaled
+    anchors: ga = tau ga', gb = tau gb', gtau = sum a ga' + sum b gb'."""
+    f = apply_backward_brute if brute else apply_backward_scan
+    (gx, gas, gbs), (tgx, tga, tgb) = f(scaled_anchors(a, tau, fp32), scaled_anchors(b, tau, fp32), x, g)
+    a64, b64 = _f64(a, 1), _f64(b, 1)
+    gtau = float(np.dot(a64, gas) + np.dot(b64, gbs))
+    ttau = float(np.dot(np.abs(a64), tga) + np.dot(np.abs(b64), tgb))
+    t = float(tau)
+    return (gx, t * gas, t * gbs, gtau), (tgx, t * tga, t * tgb, ttau)
+
+
+def tau_gram_backward(a, tau, x, g, fp32=True, brute=True):
+    f = gram_backward_brute if brute else gram_backward_scan
+    (gx, gas), (tgx, tga) = f(scaled_anchors(a, tau, fp32), x, g)
+    a64 = _f64(a, 1)
+    t = float(tau)
+    return (gx, t * gas, float(np.dot(a64, gas))), (tgx, t * tga, float(np.dot(np.abs(a64), tga)))

@@ -455,3 +455,65 @@ def test_phased_scan_route_matches_brute_force(oracle):
     for u, v, t, ts in zip(G, Gs, T, Ts):
         assert np.all(np.abs(u - v) <= 1e-11 * t + 1e-300)
         np.testing.assert_allclose(ts, t, rtol=1e-11)
+
+
+# ---------------------------------------------------------------- temperature
+
+def test_temperature_is_scaling_of_the_anchors(oracle):
+    r = rng(51)
+    k, n, batch = 7, 9, 2
+    a = r.uniform(0, 3, k); b = r.uniform(0, 3, n); x = r.normal(size=(n, batch))
+    for tau in (0.25, 1.0, 3.5):
+        y, tol = oracle.tau_apply_dense(a, b, tau, x)
+        ys, tols = oracle.tau_apply(a, b, tau, x, fp32=False)
+        np.testing.assert_allclose(ys, y, atol=1e-13); np.testing.assert_allclose(tols, tol, atol=1e-13)
+
+
+def test_zero_temperature_limit_is_equality_routing(oracle):
+    """App. A, Lemma "Zero-temperature limit": as t -> 0 the matrix tends to 1{a_i == b_j}."""
+    r = rng(52)
+    labels = np.arange(6, dtype=np.float64)
+    b = labels[r.integers(0, 6, 40)]; x = r.normal(size=(40, 3))
+    y, _ = oracle.tau_apply(labels, b, 800.0, x)
+    want = np.stack([x[b == c].sum(axis=0) for c in labels])
+    np.testing.assert_allclose(y, want, atol=1e-300, rtol=1e-15)
+
+
+@pytest.mark.parametrize("brute", [True, False])
+def test_temperature_gradients_central_differences(oracle, brute):
+    r = rng(53)
+    k, n, batch, tau = 5, 8, 2, 1.7
+    a = r.uniform(0, 3, k); b = r.uniform(0, 3, n)
+    x = r.normal(size=(n, batch)); g = r.normal(size=(k, batch))
+    (gx, ga, gb, gtau), _ = oracle.tau_backward(a, b, tau, x, g, fp32=False, brute=brute)
+
+    def loss(a_, b_, t_):
+        return float(np.sum(g * oracle.tau_apply_dense(a_, b_, t_, x)[0]))
+
+    h = 1e-6
+    assert gtau == pytest.approx((loss(a, b, tau + h) - loss(a, b, tau - h)) / (2 * h), rel=1e-6, abs=1e-8)
+    for i in range(k):
+        d = np.zeros(k); d[i] = h
+        assert ga[i] == pytest.approx((loss(a + d, b, tau) - loss(a - d, b, tau)) / (2 * h), rel=1e-6, abs=1e-8)
+    for j in range(n):
+        d = np.zeros(n); d[j] = h
+        assert gb[j] == pytest.approx((loss(a, b + d, tau) - loss(a, b - d, tau)) / (2 * h), rel=1e-6, abs=1e-8)
+    np.testing.assert_allclose(gx, oracle.tau_apply_dense(b, a, tau, g)[0], atol=1e-13)     # the transposed operator
+    # Euler: the kernel depends on tau * (a, b) only
+    assert gtau * tau == pytest.approx(float(np.dot(a, ga) + np.dot(b, gb)), rel=1e-12)
+
+
+def test_temperature_gram_gradient_central_difference(oracle):
+    r = rng(54)
+    n, batch, tau = 7, 2, 0.6
+    a = r.uniform(0, 5, n); x = r.normal(size=(n, batch)); g = r.normal(size=(n, batch))
+    (gx, ga, gtau), _ = oracle.tau_gram_backward(a, tau, x, g, fp32=False)
+
+    def loss(a_, t_):
+        return float(np.sum(g * oracle.tau_apply_dense(a_, a_, t_, x)[0]))
+
+    h = 1e-6
+    assert gtau == pytest.approx((loss(a, tau + h) - loss(a, tau - h)) / (2 * h), rel=1e-6, abs=1e-8)
+    for i in range(n):
+        d = np.zeros(n); d[i] = h
+        assert ga[i] == pytest.approx((loss(a + d, tau) - loss(a - d, tau)) / (2 * h), rel=1e-6, abs=1e-8)
