@@ -63,7 +63,8 @@ enum {
     LAPLEX_ERR_WORKSPACE = -4, /* ws_bytes below laplex_workspace_bytes(...) */
     LAPLEX_ERR_FLAGS = -5,     /* unknown bit, or a bit that has no meaning for this call */
     LAPLEX_ERR_HIP = -6,       /* a HIP launch failed; see laplex_last_hip_error() */
-    LAPLEX_ERR_ALIGN = -7      /* a float pointer not 4-byte, or ws not 256-byte, aligned */
+    LAPLEX_ERR_ALIGN = -7,     /* a float pointer not 4-byte, or ws not 256-byte, aligned */
+    LAPLEX_ERR_VALUE = -8      /* a scalar argument is out of range (inverse temperature not positive and finite) */
 };
 
 enum {
@@ -138,6 +139,34 @@ int laplex_gram_backward(const float* a, int64_t n, const float* x, int64_t ldx,
                          const float* gy, int64_t ldgy, int64_t batch,
                          float* gx, int64_t ldgx, float* ga,
                          void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream);
+
+/*
+ * Temperature (App. A, "Expressivity": the temperature-scaled kernel
+ * exp(-|a_i - b_j| / t); the experiments' inverse temperature tau = 1/t):
+ *
+ *   L_tau = [exp(-tau * |a_i - b_j|)],   tau > 0 and finite (host scalar)
+ *
+ * The four calls below are the four above on the anchors tau*a, tau*b, scaled
+ * in fp32 on the way into the sort (the sorted order and the tie rule are those
+ * of the scaled anchors); a plan is valid for the tau it was built with.
+ * Gradients are with respect to the caller's a, b; gtau (device, one float,
+ * may be NULL) receives d/d tau = sum_i a_i ga_i/tau + sum_j b_j gb_j/tau, in a
+ * fixed summation order; it is formed from ga and gb, which must then both be
+ * given (ga for the Gram form).  tau == 1 gives the bits of the plain calls.
+ */
+int laplex_apply_tau(const float* a, int64_t k, const float* b, int64_t n, float tau,
+                     const float* x, int64_t ldx, int64_t batch, float* y, int64_t ldy,
+                     void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream);
+int laplex_apply_backward_tau(const float* a, int64_t k, const float* b, int64_t n, float tau,
+                              const float* x, int64_t ldx, const float* gy, int64_t ldgy, int64_t batch,
+                              float* gx, int64_t ldgx, float* ga, float* gb, float* gtau,
+                              void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream);
+int laplex_gram_tau(const float* a, int64_t n, float tau, const float* x, int64_t ldx, int64_t batch,
+                    float* y, int64_t ldy, void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream);
+int laplex_gram_backward_tau(const float* a, int64_t n, float tau, const float* x, int64_t ldx,
+                             const float* gy, int64_t ldgy, int64_t batch, float* gx, int64_t ldgx,
+                             float* ga, float* gtau,
+                             void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream);
 
 /*
  * Phased kernel (Sec. 3, "Phased Laplace kernels"):

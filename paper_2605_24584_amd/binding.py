@@ -20,6 +20,7 @@ LAPLEX_ERR_WORKSPACE = -4
 LAPLEX_ERR_FLAGS = -5
 LAPLEX_ERR_HIP = -6
 LAPLEX_ERR_ALIGN = -7
+LAPLEX_ERR_VALUE = -8
 
 LAPLEX_A_SORTED = 1
 LAPLEX_B_SORTED = 2
@@ -33,6 +34,7 @@ EXPORTS = (
     "laplex_gram_backward", "laplex_get_perm", "laplex_status_string", "laplex_last_hip_error",
     "laplex_profile_begin", "laplex_profile_end", "laplex_scan_tile_rows",
     "laplex_phased_workspace_bytes", "laplex_phased_apply", "laplex_phased_apply_backward",
+    "laplex_apply_tau", "laplex_apply_backward_tau", "laplex_gram_tau", "laplex_gram_backward_tau",
 )
 
 _lib = None
@@ -74,6 +76,11 @@ def lib() -> ctypes.CDLL:
         L.laplex_phased_apply.argtypes = [_P, _P, _I, _P, _P, _I, _P, _I, _I, _P, _I, _P, _Z, _U, _P]
         L.laplex_phased_apply_backward.argtypes = [_P, _P, _I, _P, _P, _I, _P, _I, _P, _I, _I,
                                                    _P, _I, _P, _P, _P, _P, _P, _Z, _U, _P]
+        _F = ctypes.c_float
+        L.laplex_apply_tau.argtypes = [_P, _I, _P, _I, _F, _P, _I, _I, _P, _I, _P, _Z, _U, _P]
+        L.laplex_apply_backward_tau.argtypes = [_P, _I, _P, _I, _F, _P, _I, _P, _I, _I, _P, _I, _P, _P, _P, _P, _Z, _U, _P]
+        L.laplex_gram_tau.argtypes = [_P, _I, _F, _P, _I, _I, _P, _I, _P, _Z, _U, _P]
+        L.laplex_gram_backward_tau.argtypes = [_P, _I, _F, _P, _I, _P, _I, _I, _P, _I, _P, _P, _P, _Z, _U, _P]
         for name in EXPORTS[:6] + EXPORTS[8:]:
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -191,3 +198,26 @@ def laplex_phased_apply_backward(a, phi, b, psi, x, gy, gx, ga, gb, gphi, gpsi, 
     _check(lib().laplex_phased_apply_backward(
         _ptr(a), _ptr(phi), a.numel(), _ptr(b), _ptr(psi), b.numel(), _ptr(x), _ld(x), _ptr(gy), _ld(gy), _batch(gy),
         _ptr(gx), _ld(gx), _ptr(ga), _ptr(gb), _ptr(gphi), _ptr(gpsi), _ptr(ws), ws.numel(), flags, _stream(stream)))
+
+
+def laplex_apply_tau(a, b, tau: float, x, y, ws, flags: int = 0, stream=None) -> None:
+    """y <- L_tau(a, b) x with L_tau = exp(-tau |a_i - b_j|) (inverse temperature tau > 0)."""
+    _check(lib().laplex_apply_tau(_ptr(a), a.numel(), _ptr(b), b.numel(), tau, _ptr(x), _ld(x), _batch(x),
+                                  _ptr(y), _ld(y), _ptr(ws), ws.numel(), flags, _stream(stream)))
+
+
+def laplex_apply_backward_tau(a, b, tau: float, x, gy, gx, ga, gb, gtau, ws, flags: int = 0, stream=None) -> None:
+    _check(lib().laplex_apply_backward_tau(
+        _ptr(a), a.numel(), _ptr(b), b.numel(), tau, _ptr(x), _ld(x), _ptr(gy), _ld(gy), _batch(gy),
+        _ptr(gx), _ld(gx), _ptr(ga), _ptr(gb), _ptr(gtau), _ptr(ws), ws.numel(), flags, _stream(stream)))
+
+
+def laplex_gram_tau(a, tau: float, x, y, ws, flags: int = 0, stream=None) -> None:
+    _check(lib().laplex_gram_tau(_ptr(a), a.numel(), tau, _ptr(x), _ld(x), _batch(x), _ptr(y), _ld(y),
+                                 _ptr(ws), ws.numel(), flags, _stream(stream)))
+
+
+def laplex_gram_backward_tau(a, tau: float, x, gy, gx, ga, gtau, ws, flags: int = 0, stream=None) -> None:
+    _check(lib().laplex_gram_backward_tau(
+        _ptr(a), a.numel(), tau, _ptr(x), _ld(x), _ptr(gy), _ld(gy), _batch(gy),
+        _ptr(gx), _ld(gx), _ptr(ga), _ptr(gtau), _ptr(ws), ws.numel(), flags, _stream(stream)))

@@ -5,6 +5,7 @@
 #include "laplex_internal.h"
 
 #include <atomic>
+#include <cmath>
 #include <mutex>
 #include <string>
 #include <utility>
@@ -122,7 +123,7 @@ Plan plan_of(const Layout& L, char* ws)
 }
 
 // Sort (or merge) the anchors and compute the neighbour decays, unless the plan is reused.
-int build_plan(const float* a, int64_t k, const float* b, int64_t n, const Layout& L, char* ws,
+int build_plan(const float* a, int64_t k, const float* b, int64_t n, float tau, const Layout& L, char* ws,
                uint32_t flags, bool both_sorted, hipStream_t st)
 {
     if (flags & LAPLEX_REUSE_PLAN) return LAPLEX_OK;
@@ -132,10 +133,10 @@ int build_plan(const float* a, int64_t k, const float* b, int64_t n, const Layou
     uint32_t* ids1 = reinterpret_cast<uint32_t*>(ws + L.off_ids1);
     uint32_t* small = reinterpret_cast<uint32_t*>(ws + L.off_sort_small);
     if (both_sorted) {
-        LAPLEX_HIP(launch_merge(a, k, b, n, keys0, P.ids, st));
+        LAPLEX_HIP(launch_merge(a, k, b, n, tau, keys0, P.ids, st));
         LAPLEX_HIP(launch_decay(keys0, keys1, P.ids, ids1, nullptr, P.dh, P.pk, L.N, st));
     } else {
-        LAPLEX_HIP(launch_onesweep_sort(a, k, b, n, keys0, P.ids, keys1, ids1, small,
+        LAPLEX_HIP(launch_onesweep_sort(a, k, b, n, tau, keys0, P.ids, keys1, ids1, small,
                                         reinterpret_cast<unsigned long long*>(ws + L.off_status), st));
         LAPLEX_HIP(launch_decay(keys0, keys1, P.ids, ids1, small, P.dh, P.pk, L.N, st));
     }
@@ -188,9 +189,9 @@ int laplex_workspace_bytes(int64_t k, int64_t n, int64_t batch, size_t* out)
     return LAPLEX_OK;
 }
 
-int laplex_apply(const float* a, int64_t k, const float* b, int64_t n,
+static int apply_impl(const float* a, int64_t k, const float* b, int64_t n,
                  const float* x, int64_t ldx, int64_t batch, float* y, int64_t ldy,
-                 void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream)
+                 void* ws, size_t ws_bytes, uint32_t flags, float tau, laplex_stream_t stream)
 {
     const uint32_t known = LAPLEX_A_SORTED | LAPLEX_B_SORTED | LAPLEX_REUSE_PLAN | LAPLEX_SAVE_SCANS;
     if (flags & ~known) return LAPLEX_ERR_FLAGS;
@@ -211,7 +212,7 @@ int laplex_apply(const float* a, int64_t k, const float* b, int64_t n,
         return LAPLEX_OK;
     }
     const bool sorted = (flags & LAPLEX_A_SORTED) && (flags & LAPLEX_B_SORTED);
-    LAPLEX_CHECK(build_plan(a, k, b, n, L, w, flags, sorted, st));
+    LAPLEX_CHECK(build_plan(a, k, b, n, tau, L, w, flags, sorted, st));
     ScanProblem p = problem(P, L);
     p.inj = x; p.ld_inj = ldx; p.inj_lo = (uint32_t)k; p.inj_hi = (uint32_t)(k + n);
     p.res_lo = 0; p.res_hi = (uint32_t)k;
@@ -223,10 +224,10 @@ int laplex_apply(const float* a, int64_t k, const float* b, int64_t n,
     return LAPLEX_OK;
 }
 
-int laplex_apply_backward(const float* a, int64_t k, const float* b, int64_t n,
+static int apply_backward_impl(const float* a, int64_t k, const float* b, int64_t n,
                           const float* x, int64_t ldx, const float* gy, int64_t ldgy, int64_t batch,
                           float* gx, int64_t ldgx, float* ga, float* gb,
-                          void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream)
+                          void* ws, size_t ws_bytes, uint32_t flags, float tau, float* gtau, laplex_stream_t stream)
 {
     const uint32_t known = LAPLEX_A_SORTED | LAPLEX_B_SORTED | LAPLEX_REUSE_PLAN | LAPLEX_SAVE_SCANS;
     if (flags & ~known) return LAPLEX_ERR_FLAGS;
@@ -238,6 +239,8 @@ int laplex_apply_backward(const float* a, int64_t k, const float* b, int64_t n,
     LAPLEX_CHECK(check_matrix(gx, n, ldgx, batch, false));
     LAPLEX_CHECK(check_vector(ga, k, false));
     LAPLEX_CHECK(check_vector(gb, n, false));
+    LAPLEX_CHECK(check_vector(gtau, 1, false));
+    if (gtau && ((!ga && k > 0) || (!gb && n > 0))) return LAPLEX_ERR_NULL;   // the temperature gradient is formed from ga and gb
     const Layout L = make_layout(k + n, k, batch);
     const bool degenerate = k == 0 || n == 0 || batch == 0;
     if (!degenerate) LAPLEX_CHECK(check_ws(ws, ws_bytes, L));
@@ -246,12 +249,13 @@ int laplex_apply_backward(const float* a, int64_t k, const float* b, int64_t n,
         if (gx) LAPLEX_HIP(launch_fill(gx, n, batch, ldgx, 0.0f, st));
         if (ga) LAPLEX_HIP(launch_fill(ga, k, 1, 1, 0.0f, st));
         if (gb) LAPLEX_HIP(launch_fill(gb, n, 1, 1, 0.0f, st));
+        if (gtau) LAPLEX_HIP(launch_fill(gtau, 1, 1, 1, 0.0f, st));
         return LAPLEX_OK;
     }
     char* w = static_cast<char*>(ws);
     const Plan P = plan_of(L, w);
     const bool sorted = (flags & LAPLEX_A_SORTED) && (flags & LAPLEX_B_SORTED);
-    LAPLEX_CHECK(build_plan(a, k, b, n, L, w, flags, sorted, st));
+    LAPLEX_CHECK(build_plan(a, k, b, n, tau, L, w, flags, sorted, st));
     if (ga) {
         if (!(flags & LAPLEX_SAVE_SCANS)) {   // strict scans of x at the outputs, not kept by the forward
             ScanProblem p = problem(P, L);
@@ -277,11 +281,17 @@ int laplex_apply_backward(const float* a, int64_t k, const float* b, int64_t n,
         p.tag = "bwd";
         LAPLEX_HIP(launch_scan(p, L, w, st));
     }
+    // the scans gave the gradients with respect to the scaled anchors
+    if (gtau) LAPLEX_HIP(launch_tau_grad(a, ga, k, b, gb, n, reinterpret_cast<float*>(w + L.off_scratch), gtau, st));
+    if (tau != 1.0f) {
+        if (ga) LAPLEX_HIP(launch_scale(ga, k, tau, st));
+        if (gb) LAPLEX_HIP(launch_scale(gb, n, tau, st));
+    }
     return LAPLEX_OK;
 }
 
-int laplex_gram(const float* a, int64_t n, const float* x, int64_t ldx, int64_t batch,
-                float* y, int64_t ldy, void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream)
+static int gram_impl(const float* a, int64_t n, const float* x, int64_t ldx, int64_t batch,
+                float* y, int64_t ldy, void* ws, size_t ws_bytes, uint32_t flags, float tau, laplex_stream_t stream)
 {
     const uint32_t known = LAPLEX_A_SORTED | LAPLEX_REUSE_PLAN | LAPLEX_SAVE_SCANS;
     if (flags & ~known) return LAPLEX_ERR_FLAGS;
@@ -295,7 +305,7 @@ int laplex_gram(const float* a, int64_t n, const float* x, int64_t ldx, int64_t 
     char* w = static_cast<char*>(ws);
     const Plan P = plan_of(L, w);
     hipStream_t st = stream;
-    LAPLEX_CHECK(build_plan(a, n, nullptr, 0, L, w, flags, (flags & LAPLEX_A_SORTED) != 0, st));
+    LAPLEX_CHECK(build_plan(a, n, nullptr, 0, tau, L, w, flags, (flags & LAPLEX_A_SORTED) != 0, st));
     ScanProblem p = problem(P, L);
     p.inj = x; p.ld_inj = ldx; p.inj_lo = 0; p.inj_hi = (uint32_t)n;
     p.res_lo = 0; p.res_hi = (uint32_t)n;
@@ -307,9 +317,9 @@ int laplex_gram(const float* a, int64_t n, const float* x, int64_t ldx, int64_t 
     return LAPLEX_OK;
 }
 
-int laplex_gram_backward(const float* a, int64_t n, const float* x, int64_t ldx,
+static int gram_backward_impl(const float* a, int64_t n, const float* x, int64_t ldx,
                          const float* gy, int64_t ldgy, int64_t batch, float* gx, int64_t ldgx, float* ga,
-                         void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream)
+                         void* ws, size_t ws_bytes, uint32_t flags, float tau, float* gtau, laplex_stream_t stream)
 {
     const uint32_t known = LAPLEX_A_SORTED | LAPLEX_REUSE_PLAN | LAPLEX_SAVE_SCANS;
     if (flags & ~known) return LAPLEX_ERR_FLAGS;
@@ -319,17 +329,23 @@ int laplex_gram_backward(const float* a, int64_t n, const float* x, int64_t ldx,
     LAPLEX_CHECK(check_matrix(gy, n, ldgy, batch, true));
     LAPLEX_CHECK(check_matrix(gx, n, ldgx, batch, false));
     LAPLEX_CHECK(check_vector(ga, n, false));
-    if (n == 0) return LAPLEX_OK;
+    LAPLEX_CHECK(check_vector(gtau, 1, false));
+    if (gtau && !ga && n > 0) return LAPLEX_ERR_NULL;      // the temperature gradient is formed from ga
     hipStream_t st = stream;
+    if (n == 0) {
+        if (gtau) LAPLEX_HIP(launch_fill(gtau, 1, 1, 1, 0.0f, st));
+        return LAPLEX_OK;
+    }
     if (batch == 0) {
         if (ga) LAPLEX_HIP(launch_fill(ga, n, 1, 1, 0.0f, st));
+        if (gtau) LAPLEX_HIP(launch_fill(gtau, 1, 1, 1, 0.0f, st));
         return LAPLEX_OK;
     }
     const Layout L = make_layout(n, n, batch);
     LAPLEX_CHECK(check_ws(ws, ws_bytes, L));
     char* w = static_cast<char*>(ws);
     const Plan P = plan_of(L, w);
-    LAPLEX_CHECK(build_plan(a, n, nullptr, 0, L, w, flags, (flags & LAPLEX_A_SORTED) != 0, st));
+    LAPLEX_CHECK(build_plan(a, n, nullptr, 0, tau, L, w, flags, (flags & LAPLEX_A_SORTED) != 0, st));
     if (ga && !(flags & LAPLEX_SAVE_SCANS)) {
         ScanProblem p = problem(P, L);
         p.inj = x; p.ld_inj = ldx; p.inj_lo = 0; p.inj_hi = (uint32_t)n;
@@ -350,7 +366,72 @@ int laplex_gram_backward(const float* a, int64_t n, const float* x, int64_t ldx,
         p.tag = "bwd";
         LAPLEX_HIP(launch_scan(p, L, w, st));
     }
+    if (gtau) LAPLEX_HIP(launch_tau_grad(a, ga, n, nullptr, nullptr, 0, reinterpret_cast<float*>(w + L.off_scratch), gtau, st));
+    if (tau != 1.0f && ga) LAPLEX_HIP(launch_scale(ga, n, tau, st));
     return LAPLEX_OK;
+}
+
+// Inverse temperature must be a positive finite number.
+static int check_tau(float tau) { return (tau > 0.0f && tau < INFINITY) ? LAPLEX_OK : LAPLEX_ERR_VALUE; }
+
+int laplex_apply(const float* a, int64_t k, const float* b, int64_t n,
+                 const float* x, int64_t ldx, int64_t batch, float* y, int64_t ldy,
+                 void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream)
+{
+    return apply_impl(a, k, b, n, x, ldx, batch, y, ldy, ws, ws_bytes, flags, 1.0f, stream);
+}
+
+int laplex_apply_backward(const float* a, int64_t k, const float* b, int64_t n,
+                          const float* x, int64_t ldx, const float* gy, int64_t ldgy, int64_t batch,
+                          float* gx, int64_t ldgx, float* ga, float* gb,
+                          void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream)
+{
+    return apply_backward_impl(a, k, b, n, x, ldx, gy, ldgy, batch, gx, ldgx, ga, gb, ws, ws_bytes, flags, 1.0f, nullptr, stream);
+}
+
+int laplex_gram(const float* a, int64_t n, const float* x, int64_t ldx, int64_t batch,
+                float* y, int64_t ldy, void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream)
+{
+    return gram_impl(a, n, x, ldx, batch, y, ldy, ws, ws_bytes, flags, 1.0f, stream);
+}
+
+int laplex_gram_backward(const float* a, int64_t n, const float* x, int64_t ldx,
+                         const float* gy, int64_t ldgy, int64_t batch, float* gx, int64_t ldgx, float* ga,
+                         void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream)
+{
+    return gram_backward_impl(a, n, x, ldx, gy, ldgy, batch, gx, ldgx, ga, ws, ws_bytes, flags, 1.0f, nullptr, stream);
+}
+
+int laplex_apply_tau(const float* a, int64_t k, const float* b, int64_t n, float tau,
+                     const float* x, int64_t ldx, int64_t batch, float* y, int64_t ldy,
+                     void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream)
+{
+    LAPLEX_CHECK(check_tau(tau));
+    return apply_impl(a, k, b, n, x, ldx, batch, y, ldy, ws, ws_bytes, flags, tau, stream);
+}
+
+int laplex_apply_backward_tau(const float* a, int64_t k, const float* b, int64_t n, float tau,
+                              const float* x, int64_t ldx, const float* gy, int64_t ldgy, int64_t batch,
+                              float* gx, int64_t ldgx, float* ga, float* gb, float* gtau,
+                              void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream)
+{
+    LAPLEX_CHECK(check_tau(tau));
+    return apply_backward_impl(a, k, b, n, x, ldx, gy, ldgy, batch, gx, ldgx, ga, gb, ws, ws_bytes, flags, tau, gtau, stream);
+}
+
+int laplex_gram_tau(const float* a, int64_t n, float tau, const float* x, int64_t ldx, int64_t batch,
+                    float* y, int64_t ldy, void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream)
+{
+    LAPLEX_CHECK(check_tau(tau));
+    return gram_impl(a, n, x, ldx, batch, y, ldy, ws, ws_bytes, flags, tau, stream);
+}
+
+int laplex_gram_backward_tau(const float* a, int64_t n, float tau, const float* x, int64_t ldx,
+                             const float* gy, int64_t ldgy, int64_t batch, float* gx, int64_t ldgx, float* ga, float* gtau,
+                             void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream)
+{
+    LAPLEX_CHECK(check_tau(tau));
+    return gram_backward_impl(a, n, x, ldx, gy, ldgy, batch, gx, ldgx, ga, ws, ws_bytes, flags, tau, gtau, stream);
 }
 
 int laplex_phased_workspace_bytes(int64_t k, int64_t n, int64_t batch, size_t* out)
@@ -470,6 +551,7 @@ const char* laplex_status_string(int status)
         case LAPLEX_ERR_FLAGS: return "unknown or inapplicable flag";
         case LAPLEX_ERR_HIP: return "a HIP call failed";
         case LAPLEX_ERR_ALIGN: return "a pointer is misaligned";
+        case LAPLEX_ERR_VALUE: return "a scalar argument is out of range";
         default: return "unknown status";
     }
 }

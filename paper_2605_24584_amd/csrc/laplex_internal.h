@@ -202,14 +202,15 @@ void profile_after(const char* family, hipStream_t st);
 // Launchers (each returns the hipError_t of its launches; none synchronises).
 // ----------------------------------------------------------------------------
 
+// The anchors enter every plan scaled by the inverse temperature tau (1 = as they are).
 // Stable ascending sort of the anchors a ++ b by one-sweep LSD passes; keys and ids end in keys0/ids0.
 // small: u32[kSortSmallWords] (global histogram, tickets, error word, pass mask); status: u64[2][tiles*256] look-back words.
-hipError_t launch_onesweep_sort(const float* a, int64_t k, const float* b, int64_t n,
+hipError_t launch_onesweep_sort(const float* a, int64_t k, const float* b, int64_t n, float tau,
                                 uint32_t* keys0, uint32_t* ids0, uint32_t* keys1, uint32_t* ids1,
                                 uint32_t* small, unsigned long long* status, hipStream_t st);
 
 // Both inputs ascending: merged keys/ids in one pass (ties: a first).
-hipError_t launch_merge(const float* a, int64_t k, const float* b, int64_t n,
+hipError_t launch_merge(const float* a, int64_t k, const float* b, int64_t n, float tau,
                         uint32_t* keys, uint32_t* ids, hipStream_t st);
 
 // dh[j] = decay from sorted key j-1 to j (>= 0), or -1 if the two keys are equal;
@@ -254,6 +255,13 @@ hipError_t launch_phase_split(const float* src, int64_t ld_src, const float* pha
 hipError_t launch_phase_merge(const float* src2, const float* phase, int64_t rows, int64_t batch,
                               float* dst, int64_t ld_dst, const float* other, int64_t ld_other, float* gphase,
                               hipStream_t st);
+
+// Inverse temperature: gtau[0] = sum_i a_i ga_i + sum_j b_j gb_j (b, gb may be null with n = 0), in a fixed
+// order; `partial` is scratch for kTauPartials floats.  launch_scale: p[i] *= f.
+constexpr int kTauPartials = 1024;
+hipError_t launch_tau_grad(const float* a, const float* ga, int64_t k, const float* b, const float* gb, int64_t n,
+                           float* partial, float* gtau, hipStream_t st);
+hipError_t launch_scale(float* p, int64_t count, float f, hipStream_t st);
 
 // out[r] = sum_t u[r*ldu+t] * v[r*ldv+t]
 hipError_t launch_rowdot(const float* u, int64_t ldu, const float* v, int64_t ldv,

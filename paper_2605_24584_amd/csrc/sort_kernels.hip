@@ -105,14 +105,16 @@ k_sort_reset(uint32_t* small)
     for (int i = threadIdx.x; i < kSortSmallWords; i += 1024) small[i] = 0u;
 }
 
+// Key of merged position `pos`; the anchors are scaled by the inverse temperature tau on the way in
+// (App. A: the temperature-scaled kernel exp(-|a_i - b_j| / t); tau = 1/t; tau = 1 leaves them as they are).
 __device__ __forceinline__ uint32_t anchor_key(const float* __restrict__ a, int64_t k,
-                                               const float* __restrict__ b, int64_t pos)
+                                               const float* __restrict__ b, int64_t pos, float tau)
 {
-    return float_to_key(pos < k ? a[pos] : b[pos - k]);
+    return float_to_key(tau * (pos < k ? a[pos] : b[pos - k]));
 }
 
 __global__ void __launch_bounds__(kSortThreads)
-k_sort_hist(const float* __restrict__ a, int64_t k, const float* __restrict__ b, int64_t n,
+k_sort_hist(const float* __restrict__ a, int64_t k, const float* __restrict__ b, int64_t n, float tau,
             uint32_t* __restrict__ ghist, unsigned long long* __restrict__ status0, int64_t status_words)
 {
     __shared__ uint32_t h[kSortPasses][kRadix];
@@ -127,7 +129,7 @@ k_sort_hist(const float* __restrict__ a, int64_t k, const float* __restrict__ b,
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t i = i0 + u * stride;
-            keys[u] = anchor_key(a, k, b, i < N ? i : N - 1);
+            keys[u] = anchor_key(a, k, b, i < N ? i : N - 1, tau);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -180,7 +182,7 @@ k_sort_plan(uint32_t* __restrict__ small, int64_t N)
 
 template <typename WORD>
 __global__ void __launch_bounds__(kSortThreads)
-k_onesweep_pass(const float* __restrict__ a, int64_t k, const float* __restrict__ b,
+k_onesweep_pass(const float* __restrict__ a, int64_t k, const float* __restrict__ b, float tau,
                 uint32_t* __restrict__ keys0, uint32_t* __restrict__ ids0,      // four distinct buffers
                 uint32_t* __restrict__ keys1, uint32_t* __restrict__ ids1,
                 int64_t N, int pass, const uint32_t* __restrict__ ghist, uint32_t* __restrict__ small,
@@ -240,7 +242,7 @@ k_onesweep_pass(const float* __restrict__ a, int64_t k, const float* __restrict_
             const int64_t pos = wave_base + i * 64 + lane;
             const bool ok = pos < N;
             const int64_t pc = ok ? pos : N - 1;
-            const uint32_t kk = anchor_key(a, k, b, pc);
+            const uint32_t kk = anchor_key(a, k, b, pc, tau);
             key[i] = ok ? kk : 0xFFFFFFFFu;         // padding sorts last inside the tile
             id[i] = (uint32_t)pc;
         }
@@ -372,19 +374,19 @@ k_onesweep_pass(const float* __restrict__ a, int64_t k, const float* __restrict_
 // elements, how many come from a?  (a wins ties, so a[i] precedes b[j] iff
 // a[i] <= b[j].)
 __device__ __forceinline__ int64_t merge_split(const float* __restrict__ a, int64_t k,
-                                               const float* __restrict__ b, int64_t n, int64_t diag)
+                                               const float* __restrict__ b, int64_t n, int64_t diag, float tau)
 {
     int64_t lo = diag > n ? diag - n : 0;
     int64_t hi = diag < k ? diag : k;
     while (lo < hi) {
         const int64_t mid = lo + ((hi - lo) >> 1);
-        if (a[mid] <= b[diag - 1 - mid]) lo = mid + 1; else hi = mid;
+        if (tau * a[mid] <= tau * b[diag - 1 - mid]) lo = mid + 1; else hi = mid;     // the scaled anchors are what is merged
     }
     return lo;
 }
 
 __global__ void __launch_bounds__(kMergeThreads)
-k_merge(const float* __restrict__ a, int64_t k, const float* __restrict__ b, int64_t n,
+k_merge(const float* __restrict__ a, int64_t k, const float* __restrict__ b, int64_t n, float tau,
         uint32_t* __restrict__ keys, uint32_t* __restrict__ ids)
 {
     __shared__ float stage[kMergeTile];          // a-part then b-part of this tile
@@ -393,7 +395,7 @@ k_merge(const float* __restrict__ a, int64_t k, const float* __restrict__ b, int
     const int64_t N = k + n;
     const int64_t d0 = (int64_t)blockIdx.x * kMergeTile;
     const int64_t d1 = d0 + kMergeTile < N ? d0 + kMergeTile : N;
-    if (threadIdx.x < 2) split[threadIdx.x] = merge_split(a, k, b, n, threadIdx.x == 0 ? d0 : d1);
+    if (threadIdx.x < 2) split[threadIdx.x] = merge_split(a, k, b, n, threadIdx.x == 0 ? d0 : d1, tau);
     __syncthreads();
     const int64_t ia0 = split[0], ia1 = split[1];
     const int64_t ib0 = d0 - ia0;
@@ -408,7 +410,7 @@ k_merge(const float* __restrict__ a, int64_t k, const float* __restrict__ b, int
         oid[i] = (uint32_t)(d0 + i < N ? d0 + i : 0);
     }
     for (int i = threadIdx.x; i < na + nb; i += kMergeThreads)
-        stage[i] = i < na ? a[ia0 + i] : b[ib0 + (i - na)];
+        stage[i] = tau * (i < na ? a[ia0 + i] : b[ib0 + (i - na)]);
     __syncthreads();
     const float* sa = stage;
     const float* sb = stage + na;
@@ -498,7 +500,7 @@ inline unsigned grid_for(int64_t work, int threads, int64_t cap = 1 << 16)
 
 }  // namespace
 
-hipError_t launch_onesweep_sort(const float* a, int64_t k, const float* b, int64_t n,
+hipError_t launch_onesweep_sort(const float* a, int64_t k, const float* b, int64_t n, float tau,
                                 uint32_t* keys0, uint32_t* ids0, uint32_t* keys1, uint32_t* ids1,
                                 uint32_t* small, unsigned long long* status, hipStream_t st)
 {
@@ -510,7 +512,7 @@ hipError_t launch_onesweep_sort(const float* a, int64_t k, const float* b, int64
     int64_t hgrid = (N + kSortTile - 1) / kSortTile;
     if (hgrid > 2048) hgrid = 2048;
     LAPLEX_TIMED("sort_hist", st, hipLaunchKernelGGL(k_sort_hist, dim3((unsigned)hgrid), dim3(kSortThreads), 0, st,
-                                                     a, k, b, n, small, region[0], words));
+                                                     a, k, b, n, tau, small, region[0], words));
     LAPLEX_TIMED("sort_hist", st, hipLaunchKernelGGL(k_sort_plan, dim3(1), dim3(1024), 0, st, small, N));
     const dim3 grid((unsigned)tiles), block(kSortThreads);
     auto passes = [&](auto* r0, auto* r1) {
@@ -519,7 +521,7 @@ hipError_t launch_onesweep_sort(const float* a, int64_t k, const float* b, int64
         WORD* nxt[4] = {r1, r0, r1, nullptr};
         for (int p = 0; p < kSortPasses; ++p)
             LAPLEX_TIMED("radix_scatter", st, hipLaunchKernelGGL((k_onesweep_pass<WORD>), grid, block, 0, st,
-                         a, k, b, keys0, ids0, keys1, ids1, N, p, (const uint32_t*)small, small, cur[p], nxt[p]));
+                         a, k, b, tau, keys0, ids0, keys1, ids1, N, p, (const uint32_t*)small, small, cur[p], nxt[p]));
     };
     if (N <= (int64_t(1) << 30)) {
         uint32_t* r = reinterpret_cast<uint32_t*>(status);
@@ -530,12 +532,12 @@ hipError_t launch_onesweep_sort(const float* a, int64_t k, const float* b, int64
     return hipGetLastError();
 }
 
-hipError_t launch_merge(const float* a, int64_t k, const float* b, int64_t n,
+hipError_t launch_merge(const float* a, int64_t k, const float* b, int64_t n, float tau,
                         uint32_t* keys, uint32_t* ids, hipStream_t st)
 {
     const int64_t N = k + n;
     const int64_t tiles = (N + kMergeTile - 1) / kMergeTile;
-    LAPLEX_TIMED("merge", st, hipLaunchKernelGGL(k_merge, dim3((unsigned)tiles), dim3(kMergeThreads), 0, st, a, k, b, n, keys, ids));
+    LAPLEX_TIMED("merge", st, hipLaunchKernelGGL(k_merge, dim3((unsigned)tiles), dim3(kMergeThreads), 0, st, a, k, b, n, tau, keys, ids));
     return hipGetLastError();
 }
 

@@ -516,3 +516,74 @@ def test_phased_subsets_and_empty_sides(oracle):
     e = np.zeros(0, dtype=np.float32)
     y, grads, _ = gpu_phased(a, phi, e, e, np.zeros((0, batch), dtype=np.float32), g, flags_fwd=0, flags_bwd=0)
     assert np.all(y == 0) and all(np.all(t == 0) for t in grads)
+
+
+# ------------------------------------------------------------------ temperature
+
+@pytest.mark.parametrize("tau", [0.37, 1.0, 5.0])
+@pytest.mark.parametrize("kind", ["uniform", "ties", "signed"])
+@pytest.mark.parametrize("k,n,batch", [(5, 1, 2), (37, 53, 3), (3000, 21000, 1), (2500, 4000, 8), (300, 2100, 256),
+                                       (20, 6000, 256)])
+def test_temperature_forward_backward(oracle, tau, kind, k, n, batch):
+    """exp(-tau |a_i - b_j|): values, the permutation of the scaled anchors, all four gradients."""
+    r = np.random.default_rng(int(tau * 100) + k + n + batch)
+    a, b = anchors(kind, r, k, n)
+    x = r.normal(size=(n, batch)).astype(np.float32); g = r.normal(size=(k, batch)).astype(np.float32)
+    brute = k * n * batch <= 4e7
+    ref, tol = oracle.tau_apply(a, b, tau, x, brute=brute)
+    (rgx, rga, rgb, rgt), (tgx, tga, tgb, tgt) = oracle.tau_backward(a, b, tau, x, g, brute=brute)
+    ws = workspace(k, n, batch)
+    da, db, dx, dg = dev(a), dev(b), dev(x), dev(g)
+    y = torch.full((k, batch), float("nan"), device="cuda")
+    gx = torch.full((n, batch), float("nan"), device="cuda")
+    ga = torch.full((k,), float("nan"), device="cuda"); gb = torch.full((n,), float("nan"), device="cuda")
+    gt = torch.full((1,), float("nan"), device="cuda")
+    B.laplex_apply_tau(da, db, tau, dx, y, ws, B.LAPLEX_SAVE_SCANS)
+    B.laplex_apply_backward_tau(da, db, tau, dx, dg, gx, ga, gb, gt, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
+    torch.cuda.synchronize()
+    assert np.array_equal(gpu_perm(ws, k + n),
+                          oracle.merged_permutation(oracle.scaled_anchors(a, tau), oracle.scaled_anchors(b, tau)))
+    assert_close("y", y.cpu().numpy(), ref, tol)
+    assert_close("gx", gx.cpu().numpy(), rgx, tgx)
+    assert_close("ga", ga.cpu().numpy(), rga, tga)
+    assert_close("gb", gb.cpu().numpy(), rgb, tgb)
+    assert_close("gtau", gt.cpu().numpy(), np.array([rgt]), np.array([tgt]))
+    if tau == 1.0:                                          # the bits of the plain calls
+        y1, ws1 = gpu_apply(a, b, x, flags=B.LAPLEX_SAVE_SCANS)
+        g1 = gpu_backward(a, b, x, g, flags=B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN, ws=ws1)
+        for u, v in zip((y, gx, ga, gb), (y1,) + g1):
+            assert np.array_equal(u.cpu().numpy(), v)
+
+
+@pytest.mark.parametrize("tau", [0.25, 3.0])
+def test_temperature_merge_path_and_gram(oracle, tau):
+    r = np.random.default_rng(901)
+    k, n, batch = 700, 9000, 4
+    a, b = anchors("ties", r, k, n)
+    a.sort(); b.sort()
+    x = r.normal(size=(n, batch)).astype(np.float32)
+    ws = workspace(k, n, batch)
+    y = torch.full((k, batch), float("nan"), device="cuda")
+    B.laplex_apply_tau(dev(a), dev(b), tau, dev(x), y, ws, B.LAPLEX_A_SORTED | B.LAPLEX_B_SORTED)
+    torch.cuda.synchronize()
+    assert np.array_equal(gpu_perm(ws, k + n),
+                          oracle.merged_permutation(oracle.scaled_anchors(a, tau), oracle.scaled_anchors(b, tau)))
+    ref, tol = oracle.tau_apply(a, b, tau, x, brute=False)
+    assert_close("y", y.cpu().numpy(), ref, tol)
+    # Gram form with its temperature gradient
+    m = 5000
+    ag = (r.normal(size=m) * 30).astype(np.float32); ag[::9] = ag[3]
+    xg = r.normal(size=(m, batch)).astype(np.float32); gg = r.normal(size=(m, batch)).astype(np.float32)
+    wsg = workspace(0, m, batch)
+    yg = torch.full((m, batch), float("nan"), device="cuda"); gxg = torch.full((m, batch), float("nan"), device="cuda")
+    gag = torch.full((m,), float("nan"), device="cuda"); gt = torch.full((1,), float("nan"), device="cuda")
+    B.laplex_gram_tau(dev(ag), tau, dev(xg), yg, wsg, B.LAPLEX_SAVE_SCANS)
+    B.laplex_gram_backward_tau(dev(ag), tau, dev(xg), dev(gg), gxg, gag, gt, wsg, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
+    torch.cuda.synchronize()
+    sa = oracle.scaled_anchors(ag, tau)
+    refy, toly = oracle.gram_scan(sa, xg)
+    (rgx, rga, rgt), (tgx, tga, tgt) = oracle.tau_gram_backward(ag, tau, xg, gg, brute=False)
+    assert_close("gram y", yg.cpu().numpy(), refy, toly)
+    assert_close("gram gx", gxg.cpu().numpy(), rgx, tgx)
+    assert_close("gram ga", gag.cpu().numpy(), rga, tga)
+    assert_close("gram gtau", gt.cpu().numpy(), np.array([rgt]), np.array([tgt]))

@@ -29,8 +29,8 @@ def test_every_declared_symbol_is_exported(L):
 
 
 def test_status_strings(L):
-    seen = {B.laplex_status_string(s) for s in range(0, -8, -1)}
-    assert len(seen) == 8 and "unknown status" not in seen
+    seen = {B.laplex_status_string(s) for s in range(0, -9, -1)}
+    assert len(seen) == 9 and "unknown status" not in seen
     assert B.laplex_status_string(-99) == "unknown status"
     assert B.laplex_last_hip_error() == ""
 
@@ -186,3 +186,30 @@ def test_phased_workspace_and_argument_checks(L):
     assert L.laplex_phased_apply_backward(*bgood) == B.LAPLEX_ERR_NULL      # gpsi wanted, x missing
     bgood[8] = None; bgood[6] = FAKE
     assert L.laplex_phased_apply_backward(*bgood) == B.LAPLEX_ERR_NULL      # gy missing
+
+
+# ------------------------------------------------------------------ temperature entry points
+
+def test_temperature_calls_reject_bad_tau_and_bad_arguments(L):
+    F = ctypes.c_float
+    k = n = 8; batch = 4
+    fwd = lambda tau, **kw: L.laplex_apply_tau(*(lambda t: t[:4] + (F(tau),) + t[4:])(apply_args(**kw)))
+    for bad in (0.0, -1.0, float("inf"), float("nan")):
+        assert fwd(bad) == B.LAPLEX_ERR_VALUE
+    assert fwd(2.0, x=None) == B.LAPLEX_ERR_NULL
+    assert fwd(2.0, ldx=3) == B.LAPLEX_ERR_LD
+    assert fwd(2.0, wsb=0) == B.LAPLEX_ERR_WORKSPACE
+    assert fwd(0.5, k=0, a=None, y=None, ws=None, wsb=0) == B.LAPLEX_OK
+    bwd = L.laplex_apply_backward_tau
+    args = lambda tau, ga=FAKE, gb=FAKE, gtau=FAKE: (FAKE, k, FAKE, n, F(tau), FAKE, batch, FAKE, batch, batch,
+                                                     FAKE, batch, ga, gb, gtau, FAKE, 1 << 40, 0, None)
+    assert bwd(*args(0.0)) == B.LAPLEX_ERR_VALUE
+    assert bwd(*args(1.5, ga=None)) == B.LAPLEX_ERR_NULL          # gtau is formed from ga and gb
+    assert bwd(*args(1.5, gb=None)) == B.LAPLEX_ERR_NULL
+    assert bwd(*args(1.5, gtau=FAKE + 2)) == B.LAPLEX_ERR_ALIGN
+    g = L.laplex_gram_tau
+    assert g(FAKE, n, F(-2.0), FAKE, batch, batch, FAKE, batch, FAKE, 1 << 40, 0, None) == B.LAPLEX_ERR_VALUE
+    assert g(None, n, F(2.0), FAKE, batch, batch, FAKE, batch, FAKE, 1 << 40, 0, None) == B.LAPLEX_ERR_NULL
+    gb_ = L.laplex_gram_backward_tau
+    assert gb_(FAKE, n, F(float("nan")), FAKE, batch, FAKE, batch, batch, FAKE, batch, FAKE, FAKE, FAKE, 1 << 40, 0, None) == B.LAPLEX_ERR_VALUE
+    assert gb_(FAKE, n, F(2.0), FAKE, batch, FAKE, batch, batch, FAKE, batch, None, FAKE, FAKE, 1 << 40, 0, None) == B.LAPLEX_ERR_NULL
