@@ -312,3 +312,61 @@ def tau_gram_backward(a, tau, x, g, fp32=True, brute=True):
     a64 = _f64(a, 1)
     t = float(tau)
     return (gx, t * gas, float(np.dot(a64, gas))), (tgx, t * tga, float(np.dot(np.abs(a64), tga)))
+
+
+# --------------------------------------------------------------------------
+# Weighted Gram matrix (Sec. 3 "Computation of Gram matrix"; App. "Fast weighted
+# Gram matrix"):  M = A diag(d) A^T  with  A = L(a, b)  (k x n),  d in R^n:
+#     M_ij = sum_t d_t exp(-|a_i - b_t|) exp(-|a_j - b_t|).
+# In this repository's letters the Gram matrix is k x k (a: its k anchors) and
+# b, d are the n middle anchors and their weights.
+# --------------------------------------------------------------------------
+
+def wgram_dense(a, b, d):
+    """The definition, O(k^2 n): (M, T) with T the same sum over |d_t|."""
+    a, b, d = _f64(a, 1), _f64(b, 1), _f64(d, 1)
+    A = np.exp(-np.abs(a[:, None] - b[None, :]))
+    return (A * d[None, :]) @ A.T, (A * np.abs(d)[None, :]) @ A.T
+
+
+def _wgram_from_buckets(a, b, d):
+    """Theorem "Exact Gram decomposition" with interval statistics.  Sorted anchors
+    s_1 <= ... <= s_k cut the line into k + 1 intervals P_r = [s_{r-1}, s_r)
+    (s_0 = -inf, s_{k+1} = +inf).  Per interval: u_r = sum e^{2(b_t - s_r)} d_t
+    (relative to its right end), w_r = sum d_t, and the right-hand statistic taken
+    relative to the interval's LEFT end, v_r = sum e^{-2(b_t - s_{r-1})} d_t: the
+    theorem's e^{2(s_r - b_t)} has a positive exponent and overflows on wide
+    intervals, and its index range r = 1..k leaves out the last interval.  Then
+    U_j = sum_{r <= j} e^{-2(s_j - s_r)} u_r,  V_i = sum_{r > i} e^{-2(s_{r-1} - s_i)} v_r,
+    W_i = sum_{r <= i} w_r,  and for i >= j
+        M_ij = e^{s_j - s_i} (U_j + (W_i - W_j) + V_i)."""
+    k = a.size
+    order = np.argsort(a, kind="stable")
+    s = a[order]
+    bucket = np.searchsorted(s, b, side="right")          # number of anchors <= b_t: interval index r - 1, in 0..k
+    left = np.concatenate([[-np.inf], s])                 # left end of interval r - 1
+    right = np.concatenate([s, [np.inf]])
+    with np.errstate(invalid="ignore"):
+        eu = np.where(bucket < k, np.exp(2.0 * (b - right[bucket])), 0.0)     # the last interval has no right end
+        ev = np.where(bucket > 0, np.exp(-2.0 * (b - left[bucket])), 0.0)     # the first none on the left
+    u = np.bincount(bucket, weights=eu * d, minlength=k + 1)
+    v = np.bincount(bucket, weights=ev * d, minlength=k + 1)
+    w = np.bincount(bucket, weights=d, minlength=k + 1)
+    U = np.zeros(k); V = np.zeros(k)
+    for j in range(k):                                    # U_j = u_j + e^{-2(s_j - s_{j-1})} U_{j-1}
+        U[j] = u[j] + (np.exp(-2.0 * (s[j] - s[j - 1])) * U[j - 1] if j else 0.0)
+    for i in range(k - 1, -1, -1):                        # V_i = v_{i+1} + e^{-2(s_{i+1} - s_i)} V_{i+1}
+        V[i] = v[i + 1] + (np.exp(-2.0 * (s[i + 1] - s[i])) * V[i + 1] if i + 1 < k else 0.0)
+    W = np.cumsum(w[:k])
+    hi = np.maximum(np.arange(k)[:, None], np.arange(k)[None, :])
+    lo = np.minimum(np.arange(k)[:, None], np.arange(k)[None, :])
+    Ms = np.exp(s[lo] - s[hi]) * (U[lo] + (W[hi] - W[lo]) + V[hi])
+    M = np.empty_like(Ms)
+    M[np.ix_(order, order)] = Ms
+    return M
+
+
+def wgram_scan(a, b, d):
+    """(M, T) through the exact Gram decomposition, O(k^2 + n log k)."""
+    a, b, d = _f64(a, 1), _f64(b, 1), _f64(d, 1)
+    return _wgram_from_buckets(a, b, d), _wgram_from_buckets(a, b, np.abs(d))

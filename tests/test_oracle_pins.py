@@ -517,3 +517,81 @@ def test_temperature_gram_gradient_central_difference(oracle):
     for i in range(n):
         d = np.zeros(n); d[i] = h
         assert ga[i] == pytest.approx((loss(a + d, tau) - loss(a - d, tau)) / (2 * h), rel=1e-6, abs=1e-8)
+
+
+# ---------------------------------------------------------------- weighted Gram matrix
+
+@pytest.mark.parametrize("route", ["dense", "scan"])
+def test_golden_weighted_gram(oracle, route):
+    gd = read_golden("wgram_rational_2x3.txt")
+    a = np.log(np.array(gd["exp_a"])); b = np.log(np.array(gd["exp_b"])); d = np.array(gd["d"])
+    M, T = (oracle.wgram_dense if route == "dense" else oracle.wgram_scan)(a, b, d)
+    np.testing.assert_allclose(M, [gd["m_row0"], gd["m_row1"]], rtol=1e-14)
+    np.testing.assert_allclose(T, M, rtol=1e-14)                  # positive weights
+
+
+@pytest.mark.parametrize("route", ["dense", "scan"])
+def test_weighted_gram_is_the_composition_of_two_applies(oracle, route):
+    """M z = A (d * (A^T z)), with A z' and A^T z from the pinned apply (L(a,b)^T = L(b,a))."""
+    r = rng(61)
+    k, n = 9, 23
+    a = r.uniform(0, 4, k); b = r.uniform(-1, 5, n); d = r.normal(size=n); z = r.normal(size=(k, 2))
+    b[3] = a[2]; b[7] = a[2]; a[5] = a[2]                        # ties between and inside the two sets
+    M, _ = (oracle.wgram_dense if route == "dense" else oracle.wgram_scan)(a, b, d)
+    atz, _ = oracle.apply_brute(b, a, z)
+    want, _ = oracle.apply_brute(a, b, d[:, None] * atz)
+    np.testing.assert_allclose(M @ z, want, atol=1e-12)
+    np.testing.assert_allclose(M, M.T, atol=1e-14)
+
+
+@pytest.mark.parametrize("route", ["dense", "scan"])
+def test_weighted_gram_special_cases(oracle, route):
+    f = oracle.wgram_dense if route == "dense" else oracle.wgram_scan
+    r = rng(62)
+    k, n = 7, 15
+    a = r.uniform(0, 3, k); b = r.uniform(0, 3, n)
+    # one unit weight: the outer product of a column of A with itself
+    for t in (0, 6, n - 1):
+        d = np.zeros(n); d[t] = 1.0
+        col = np.exp(-np.abs(a - b[t]))
+        np.testing.assert_allclose(f(a, b, d)[0], np.outer(col, col), atol=1e-15)
+    # every middle anchor at one point c left of all a: M_ij = e^{-(a_i - c)} e^{-(a_j - c)} sum(d)
+    d = r.normal(size=n); c = -2.5
+    e = np.exp(-(a - c))
+    np.testing.assert_allclose(f(a, np.full(n, c), d)[0], np.outer(e, e) * d.sum(), atol=1e-14)
+    # one Gram anchor: the scalar sum_t d_t exp(-2 |a - b_t|), a plain apply on the doubled anchors
+    y, _ = oracle.apply_brute(2 * a[:1], 2 * b, d[:, None])
+    np.testing.assert_allclose(f(a[:1], b, d)[0], y, atol=1e-14)
+    # non-negative weights: positive semi-definite
+    M, T = f(a, b, np.abs(d))
+    assert np.linalg.eigvalsh(M).min() > -1e-12
+    np.testing.assert_allclose(T, M, rtol=1e-13)
+    # depends on differences only; reflection swaps left and right
+    M0 = f(a, b, d)[0]
+    np.testing.assert_allclose(f(a + 7.0, b + 7.0, d)[0], M0, atol=1e-13)
+    np.testing.assert_allclose(f(-a, -b, d)[0], M0, atol=1e-13)
+    # permuting the Gram anchors permutes rows and columns
+    p = r.permutation(k)
+    np.testing.assert_allclose(f(a[p], b, d)[0], M0[np.ix_(p, p)], atol=1e-14)
+
+
+@pytest.mark.parametrize("kind", ["uniform", "ties", "all_equal", "huge_gaps", "outside"])
+def test_weighted_gram_routes_agree(oracle, kind):
+    r = rng(63)
+    k, n = 40, 500
+    if kind == "uniform":
+        a, b = r.uniform(0, 8, k), r.uniform(0, 8, n)
+    elif kind == "ties":
+        a, b = np.round(r.uniform(0, 6, k) * 2) / 2, np.round(r.uniform(0, 6, n) * 2) / 2
+    elif kind == "all_equal":
+        a, b = np.full(k, 1.5), np.full(n, 1.5)
+    elif kind == "huge_gaps":      # intervals 600 wide: e^{2 * 600} would overflow, the decays underflow to 0
+        a, b = r.integers(0, 5, k) * 600.0, r.integers(0, 5, n) * 600.0 + r.integers(0, 3, n) * 0.25
+    else:                          # every middle anchor outside the range of a, on both sides
+        a, b = r.uniform(10, 12, k), np.concatenate([r.uniform(5, 9, n // 2), r.uniform(13, 20, n - n // 2)])
+    d = r.normal(size=n)
+    M, T = oracle.wgram_dense(a, b, d)
+    Ms, Ts = oracle.wgram_scan(a, b, d)
+    assert np.all(np.isfinite(Ms))
+    assert np.all(np.abs(M - Ms) <= 1e-12 * T + 1e-300)
+    np.testing.assert_allclose(Ts, T, rtol=1e-12, atol=1e-300)
