@@ -36,7 +36,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-columns", type=int, default=256)
     ap.add_argument("--workload", default="projection",
-                    choices=["projection", "square", "tie_heavy", "gram", "billion", "phased"],
+                    choices=["projection", "square", "tie_heavy", "gram", "billion", "phased", "wgram"],
                     help="projection is the benchmark; the others time one forward+backward step of the "
                          "other workloads (for profiles; no roofline object, no CPU baseline)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -94,6 +94,17 @@ def other_workload(args, torch, np, B, synth):
             B.laplex_gram(da, dx, y, ws, B.LAPLEX_SAVE_SCANS)
             B.laplex_gram_backward(da, dx, dg, gx, ga, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
         elements = n * batch
+    elif args.workload == "wgram":
+        w = synth.weighted_gram(scale=args.scale)
+        a, b, d = w["a"], w["b"], w["d"]
+        k, n, batch = a.size, b.size, 1
+        ws = torch.empty(B.laplex_wgram_workspace_bytes(k, n), dtype=torch.uint8, device="cuda")
+        da, db, dd = dev(a), dev(b), dev(d)
+        m = torch.empty(k, k, device="cuda")
+
+        def step():
+            B.laplex_wgram(da, db, dd, m, ws, 0)
+        elements = n + k
     elif args.workload == "phased":
         w = synth.projection_layer_phased(scale=args.scale, batch=args.batch)
         a, b, x, g = w["a"], w["b"], w["x"], w["g"]
@@ -137,7 +148,8 @@ def other_workload(args, torch, np, B, synth):
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": w["name"] + ("" if args.scale == 1 else "/scaled"), "k": k, "n": n, "batch": batch,
-                   "pass": "forward+backward, sort inside every step", "workspace_bytes": ws.numel(),
+                   "pass": ("weighted Gram matrix (k x k), sort inside every step" if args.workload == "wgram"
+                            else "forward+backward, sort inside every step"), "workspace_bytes": ws.numel(),
                    "device_bytes_peak": torch.cuda.max_memory_allocated()},
     }), flush=True)
 

@@ -83,6 +83,7 @@ enum {
     LAPLEX_SAVE_SCANS = 8u
 };
 
+#define LAPLEX_WGRAM_MAX_ANCHORS 1048576LL /* rows of the k x k weighted Gram matrix */
 #define LAPLEX_MAX_MERGED 4294967294LL /* ids are 32-bit; 2^32-1 positions plus a sentinel slot */
 
 /* Bytes of workspace for an apply with k outputs, n inputs and `batch`
@@ -205,6 +206,28 @@ int laplex_phased_apply_backward(const float* a, const float* phi, int64_t k,
                                  const float* x, int64_t ldx, const float* gy, int64_t ldgy, int64_t batch,
                                  float* gx, int64_t ldgx, float* ga, float* gb, float* gphi, float* gpsi,
                                  void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream);
+
+/*
+ * Weighted Gram matrix (Sec. 3, "Computation of Gram matrix"; App. "Fast weighted
+ * Gram matrix", Thm "Exact Gram decomposition"):
+ *
+ *   m[i*ldm + j] = sum_t d[t] * exp(-|a[i] - b[t]|) * exp(-|a[j] - b[t]|),   i, j < k, t < n
+ *
+ * i.e. M = A diag(d) A^T with A = L(a, b): a[k] are the anchors of the k x k
+ * result, b[n] the middle anchors that are summed over, d[n] their weights (any
+ * sign).  Cost O(k^2 + n log n): one sort of the doubled anchors, one forward and
+ * one backward decayed scan of d, one fp64 prefix sum of d, then the k x k fill;
+ * the full matrix is written (both triangles), rows ldm >= k floats apart.
+ * k <= LAPLEX_WGRAM_MAX_ANCHORS.  Flags: LAPLEX_A_SORTED | LAPLEX_B_SORTED (both
+ * set: merge instead of sort), LAPLEX_REUSE_PLAN (the workspace holds the plan of
+ * an earlier laplex_wgram call with the same a, b).  n == 0 gives M = 0.  The
+ * workspace is laplex_wgram_workspace_bytes(k, n); its front is a plan of the
+ * anchors 2a, 2b (laplex_get_perm reads it).  No gradients are provided.
+ */
+int laplex_wgram_workspace_bytes(int64_t k, int64_t n, size_t* out /* host */);
+
+int laplex_wgram(const float* a, int64_t k, const float* b, int64_t n, const float* d,
+                 float* m, int64_t ldm, void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream);
 
 /*
  * Verification hook: copy the first `count` sorted ids of the plan in `ws`

@@ -35,6 +35,7 @@ EXPORTS = (
     "laplex_profile_begin", "laplex_profile_end", "laplex_scan_tile_rows",
     "laplex_phased_workspace_bytes", "laplex_phased_apply", "laplex_phased_apply_backward",
     "laplex_apply_tau", "laplex_apply_backward_tau", "laplex_gram_tau", "laplex_gram_backward_tau",
+    "laplex_wgram_workspace_bytes", "laplex_wgram",
 )
 
 _lib = None
@@ -81,6 +82,8 @@ def lib() -> ctypes.CDLL:
         L.laplex_apply_backward_tau.argtypes = [_P, _I, _P, _I, _F, _P, _I, _P, _I, _I, _P, _I, _P, _P, _P, _P, _Z, _U, _P]
         L.laplex_gram_tau.argtypes = [_P, _I, _F, _P, _I, _I, _P, _I, _P, _Z, _U, _P]
         L.laplex_gram_backward_tau.argtypes = [_P, _I, _F, _P, _I, _P, _I, _I, _P, _I, _P, _P, _P, _Z, _U, _P]
+        L.laplex_wgram_workspace_bytes.argtypes = [_I, _I, ctypes.POINTER(ctypes.c_size_t)]
+        L.laplex_wgram.argtypes = [_P, _I, _P, _I, _P, _P, _I, _P, _Z, _U, _P]
         for name in EXPORTS[:6] + EXPORTS[8:]:
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -221,3 +224,15 @@ def laplex_gram_backward_tau(a, tau: float, x, gy, gx, ga, gtau, ws, flags: int 
     _check(lib().laplex_gram_backward_tau(
         _ptr(a), a.numel(), tau, _ptr(x), _ld(x), _ptr(gy), _ld(gy), _batch(gy),
         _ptr(gx), _ld(gx), _ptr(ga), _ptr(gtau), _ptr(ws), ws.numel(), flags, _stream(stream)))
+
+
+def laplex_wgram_workspace_bytes(k: int, n: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().laplex_wgram_workspace_bytes(k, n, ctypes.byref(out)))
+    return out.value
+
+
+def laplex_wgram(a, b, d, m, ws, flags: int = 0, stream=None) -> None:
+    """m (k, k) <- A diag(d) A^T with A = L(a, b): the weighted Gram matrix."""
+    _check(lib().laplex_wgram(_ptr(a), a.numel(), _ptr(b), b.numel(), _ptr(d), _ptr(m), _ld(m),
+                              _ptr(ws), ws.numel(), flags, _stream(stream)))

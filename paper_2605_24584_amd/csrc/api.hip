@@ -176,6 +176,34 @@ int check_phased_sizes(int64_t k, int64_t n, int64_t batch)
     return check_sizes(k, n, 2 * batch);
 }
 
+// ----------------------------------------------------------------------------
+// Weighted Gram matrix (gram_kernels.hip).  Workspace: the plain workspace for batch 1 with one saved
+// scan value per Gram anchor (the plan of the doubled anchors at its front; the backward scan V in the
+// saved-scan region), then U f32[k], W f64[k] and one f64 per tile of the prefix sum.
+// ----------------------------------------------------------------------------
+struct WgramLayout {
+    size_t inner = 0, off_u = 0, off_w = 0, off_tile = 0, total = 0;
+};
+
+WgramLayout wgram_layout(int64_t k, int64_t n)
+{
+    WgramLayout G;
+    G.inner = make_layout(k + n, k, 1).total;
+    size_t o = align_up(G.inner);
+    G.off_u = o;    o = align_up(o + sizeof(float) * (size_t)k);
+    G.off_w = o;    o = align_up(o + sizeof(double) * (size_t)k);
+    G.off_tile = o; o = align_up(o + sizeof(double) * (size_t)wgram_tiles(k + n));
+    G.total = o;
+    return G;
+}
+
+int check_wgram_sizes(int64_t k, int64_t n)
+{
+    LAPLEX_CHECK(check_sizes(k, n, 1));
+    if (k > LAPLEX_WGRAM_MAX_ANCHORS) return LAPLEX_ERR_SIZE;
+    return LAPLEX_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -526,6 +554,56 @@ int laplex_phased_apply_backward(const float* a, const float* phi, int64_t k, co
                                        want_gx2 ? gx2 : nullptr, 2 * batch, ga, gb, ws, P.inner, inner, stream));
     if (want_gx2) LAPLEX_HIP(launch_phase_merge(gx2, psi, n, batch, gx, ldgx, x, ldx, gpsi, st));
     if (gphi) LAPLEX_HIP(launch_phase_merge(y2, phi, k, batch, nullptr, 0, gy, ldgy, gphi, st));
+    return LAPLEX_OK;
+}
+
+int laplex_wgram_workspace_bytes(int64_t k, int64_t n, size_t* out)
+{
+    if (!out) return LAPLEX_ERR_NULL;
+    LAPLEX_CHECK(check_wgram_sizes(k, n));
+    *out = wgram_layout(k, n).total;
+    return LAPLEX_OK;
+}
+
+int laplex_wgram(const float* a, int64_t k, const float* b, int64_t n, const float* d,
+                 float* m, int64_t ldm, void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream)
+{
+    const uint32_t known = LAPLEX_A_SORTED | LAPLEX_B_SORTED | LAPLEX_REUSE_PLAN;
+    if (flags & ~known) return LAPLEX_ERR_FLAGS;
+    LAPLEX_CHECK(check_wgram_sizes(k, n));
+    LAPLEX_CHECK(check_vector(a, k, true));
+    LAPLEX_CHECK(check_vector(b, n, true));
+    LAPLEX_CHECK(check_vector(d, n, true));
+    LAPLEX_CHECK(check_matrix(m, k, ldm, k, true));
+    if (k == 0) return LAPLEX_OK;
+    hipStream_t st = stream;
+    if (n == 0) {
+        LAPLEX_HIP(launch_fill(m, k, k, ldm, 0.0f, st));
+        return LAPLEX_OK;
+    }
+    const WgramLayout G = wgram_layout(k, n);
+    if (!ws) return LAPLEX_ERR_NULL;
+    if (misaligned(ws, 256)) return LAPLEX_ERR_ALIGN;
+    if (ws_bytes < G.total) return LAPLEX_ERR_WORKSPACE;
+    char* w = static_cast<char*>(ws);
+    const Layout L = make_layout(k + n, k, 1);
+    const Plan P = plan_of(L, w);
+    float* U = reinterpret_cast<float*>(w + G.off_u);
+    float* V = P.z;
+    double* W = reinterpret_cast<double*>(w + G.off_w);
+    double* tile_sum = reinterpret_cast<double*>(w + G.off_tile);
+    // the plan of the doubled anchors: its decays are exp(-2 gap), the kernel K = L(2a) of the theorem
+    const bool sorted = (flags & LAPLEX_A_SORTED) && (flags & LAPLEX_B_SORTED);
+    LAPLEX_CHECK(build_plan(a, k, b, n, 2.0f, L, w, flags, sorted, st));
+    ScanProblem p = problem(P, L);
+    p.inj = d; p.ld_inj = 1; p.inj_lo = (uint32_t)k; p.inj_hi = (uint32_t)(k + n);
+    p.res_lo = 0; p.res_hi = (uint32_t)k;
+    p.out_p = U; p.ld_p = 1; p.out_z = V; p.one_sided = true;
+    p.stage = P.stage;
+    p.tag = "wgram";
+    LAPLEX_HIP(launch_scan(p, L, w, st));
+    LAPLEX_HIP(launch_wgram_prefix(P.ids, d, k, k + n, tile_sum, W, st));
+    LAPLEX_HIP(launch_wgram_fill(a, U, V, W, k, m, ldm, st));
     return LAPLEX_OK;
 }
 

@@ -139,6 +139,23 @@ def projection_layer_phased(scale: int = 1, batch: int = 256):
     return w
 
 
+def weighted_gram(scale: int = 1, k: int = 1024):
+    """Weighted Gram matrix with k = 1024 anchors (the result is k x k) and n = 2^20 middle
+    anchors, the large end of the paper's sweep of the inner dimension (App. "Weighted Gram
+    matrix": output dimension fixed at 1024, inner dimension 2^10 .. 2^20).  Anchors as in the
+    projection layer, U(0, 2^14); weights d = 1/2 + |N(0, 1)|, positive like the variances of
+    the density model (config slot 8)."""
+    n = _shrunk(1 << 20, scale)
+    k = _shrunk(k, scale)
+    hi = float(1 << 14) / scale
+    return dict(
+        name="weighted_gram_k1024_n2^20", config=8, k=k, n=n, batch=1,
+        a=uniform(stream_seed(8, STREAM_A), k, 0.0, hi),
+        b=uniform(stream_seed(8, STREAM_B), n, 0.0, hi),
+        d=(np.abs(normal(stream_seed(8, STREAM_X), n)) + np.float32(0.5)).astype(np.float32),
+    )
+
+
 def tie_heavy(scale: int = 1):
     """n = k = 2^24, batch 1, anchors U(0, 2^18) rounded to a 1/4 grid."""
     n = k = _shrunk(1 << 24, scale)

@@ -203,3 +203,30 @@ def test_billion_scale(oracle):
     worst, checked = check_windows(oracle, a, b, x, g, y, gx, ga, gb, centers)
     log(f"billion workload: window ratios {worst} over {checked} rows")
     assert max(worst.values()) <= 1.0 and checked > 2000
+
+
+def test_weighted_gram_full_size(oracle):
+    """k = 1024 Gram anchors, n = 2^20 middle anchors, positive weights: every entry of the
+    1024 x 1024 matrix against the oracle's decomposition route, and a sample of 24 rows against
+    the definition itself."""
+    w = synth.weighted_gram()
+    a, b, d = w["a"], w["b"], w["d"]
+    k, n = a.size, b.size
+    ws = torch.empty(B.laplex_wgram_workspace_bytes(k, n), dtype=torch.uint8, device="cuda")
+    m = torch.full((k, k), float("nan"), device="cuda")
+    log(f"weighted Gram: k={k} n={n}, workspace {ws.numel() / 2**20:.0f} MiB")
+    B.laplex_wgram(dev(a), dev(b), dev(d), m, ws, 0)
+    torch.cuda.synchronize()
+    got = m.cpu().numpy()
+    ref, tol = oracle.wgram_scan(a, b, d)
+    worst = worst_ratio(got, ref, tol)
+    log(f"weighted Gram: worst |err| / (1e-5 T + 1e-7) = {worst:.3g} over {k * k} entries")
+    assert worst <= 1.0
+    # sampled rows against the definition, restricted to the middle anchors within 64 of the row's
+    # anchor (what is dropped is below exp(-64) * sum|d|)
+    a64, b64, d64 = a.astype(np.float64), b.astype(np.float64), d.astype(np.float64)
+    for i in np.random.default_rng(8).choice(k, 24, replace=False):
+        near = np.abs(b64 - a64[i]) <= 64.0
+        col = d64[near] * np.exp(-np.abs(a64[i] - b64[near]))
+        A = np.exp(-np.abs(a64[:, None] - b64[near][None, :]))
+        assert worst_ratio(got[i], A @ col, A @ np.abs(col)) <= 1.0

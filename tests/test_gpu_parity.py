@@ -587,3 +587,59 @@ def test_temperature_merge_path_and_gram(oracle, tau):
     assert_close("gram gx", gxg.cpu().numpy(), rgx, tgx)
     assert_close("gram ga", gag.cpu().numpy(), rga, tga)
     assert_close("gram gtau", gt.cpu().numpy(), np.array([rgt]), np.array([tgt]))
+
+
+# ------------------------------------------------------------------ weighted Gram matrix
+
+def gpu_wgram(a, b, d, flags=0, ws=None, ldm=None):
+    k, n = a.size, b.size
+    ws = torch.empty(B.laplex_wgram_workspace_bytes(k, n), dtype=torch.uint8, device="cuda") if ws is None else ws
+    mbuf = torch.full((k, k if ldm is None else ldm), float("nan"), device="cuda")
+    m = mbuf[:, :k]
+    B.laplex_wgram(dev(a), dev(b), dev(d), m, ws, flags)
+    torch.cuda.synchronize()
+    return m.cpu().numpy(), ws
+
+
+WGRAM_SHAPES = [(1, 1), (2, 3), (5, 1), (1, 700), (37, 53), (100, 9000), (9000 // 8, 100), (1024, 40000), (333, 70001),
+                (700, 700), (3, 150000)]
+
+
+@pytest.mark.parametrize("weights", ["signed", "positive"])
+@pytest.mark.parametrize("kind", ["uniform", "ties", "all_equal", "huge_gaps", "clustered", "signed"])
+@pytest.mark.parametrize("k,n", WGRAM_SHAPES)
+def test_weighted_gram_matrix(oracle, weights, kind, k, n):
+    """M = A diag(d) A^T: every entry against the oracle, |err| <= 1e-5 T + 1e-7 with
+    T_ij = sum_t |d_t| A_it A_jt; the plan is that of the doubled anchors."""
+    r = np.random.default_rng(11 * k + n + len(kind))
+    a, b = anchors(kind, r, k, n)
+    d = r.normal(size=n).astype(np.float32)
+    if weights == "positive":
+        d = np.abs(d) + np.float32(0.5)
+    ref, tol = (oracle.wgram_dense if k * k * n <= 3e8 else oracle.wgram_scan)(a, b, d)
+    m, ws = gpu_wgram(a, b, d)
+    assert_close("M", m, ref, tol)
+    assert np.array_equal(m, m.T), "the two triangles must hold the same bits"
+    two = np.float32(2)
+    assert np.array_equal(gpu_perm(ws, k + n), oracle.merged_permutation(two * a, two * b))
+
+
+def test_weighted_gram_options(oracle):
+    r = np.random.default_rng(404)
+    k, n = 300, 20000
+    a, b = anchors("ties", r, k, n)
+    d = r.normal(size=n).astype(np.float32)
+    ref, tol = oracle.wgram_scan(a, b, d)
+    m, ws = gpu_wgram(a, b, d, ldm=k + 5)                          # padded rows: scalar stores
+    assert_close("M (padded)", m, ref, tol)
+    d2 = r.normal(size=n).astype(np.float32)                       # new weights on the kept plan
+    ref2, tol2 = oracle.wgram_scan(a, b, d2)
+    m2, _ = gpu_wgram(a, b, d2, flags=B.LAPLEX_REUSE_PLAN, ws=ws)
+    assert_close("M (plan reused)", m2, ref2, tol2)
+    sa, sb_order = np.sort(a), np.argsort(b, kind="stable")        # both sorted: the merge path
+    m3, _ = gpu_wgram(sa, b[sb_order], d[sb_order], flags=B.LAPLEX_A_SORTED | B.LAPLEX_B_SORTED)
+    ref3, tol3 = oracle.wgram_scan(sa, b[sb_order], d[sb_order])
+    assert_close("M (merge path)", m3, ref3, tol3)
+    e = np.zeros(0, dtype=np.float32)                              # nothing to sum over
+    m4, _ = gpu_wgram(a, e, e)
+    assert np.all(m4 == 0)

@@ -213,3 +213,31 @@ def test_temperature_calls_reject_bad_tau_and_bad_arguments(L):
     gb_ = L.laplex_gram_backward_tau
     assert gb_(FAKE, n, F(float("nan")), FAKE, batch, FAKE, batch, batch, FAKE, batch, FAKE, FAKE, FAKE, 1 << 40, 0, None) == B.LAPLEX_ERR_VALUE
     assert gb_(FAKE, n, F(2.0), FAKE, batch, FAKE, batch, batch, FAKE, batch, None, FAKE, FAKE, 1 << 40, 0, None) == B.LAPLEX_ERR_NULL
+
+
+# ------------------------------------------------------------------ weighted Gram matrix
+
+def test_weighted_gram_argument_checks(L):
+    out = ctypes.c_size_t(0)
+    assert L.laplex_wgram_workspace_bytes(8, 8, None) == B.LAPLEX_ERR_NULL
+    assert L.laplex_wgram_workspace_bytes(-1, 8, ctypes.byref(out)) == B.LAPLEX_ERR_SIZE
+    assert L.laplex_wgram_workspace_bytes((1 << 20) + 1, 8, ctypes.byref(out)) == B.LAPLEX_ERR_SIZE
+    assert L.laplex_wgram_workspace_bytes(1024, 1 << 20, ctypes.byref(out)) == 0
+    plain = ctypes.c_size_t(0)
+    assert L.laplex_workspace_bytes(1024, 1 << 20, 1, ctypes.byref(plain)) == 0
+    assert out.value % 256 == 0 and out.value >= plain.value + 12 * 1024       # + U (4 B) and W (8 B) per anchor
+    k, n = 8, 16
+    good = dict(a=FAKE, k=k, b=FAKE, n=n, d=FAKE, m=FAKE, ldm=k, ws=FAKE, wsb=1 << 40, flags=0)
+    call = lambda **kw: L.laplex_wgram(*[{**good, **kw}[key] for key in
+                                         ("a", "k", "b", "n", "d", "m", "ldm", "ws", "wsb", "flags")], None)
+    assert call(a=None) == B.LAPLEX_ERR_NULL
+    assert call(b=None) == B.LAPLEX_ERR_NULL
+    assert call(d=None) == B.LAPLEX_ERR_NULL
+    assert call(m=None) == B.LAPLEX_ERR_NULL
+    assert call(ws=None) == B.LAPLEX_ERR_NULL
+    assert call(ldm=k - 1) == B.LAPLEX_ERR_LD
+    assert call(k=-1) == B.LAPLEX_ERR_SIZE
+    assert call(flags=B.LAPLEX_SAVE_SCANS) == B.LAPLEX_ERR_FLAGS
+    assert call(wsb=64) == B.LAPLEX_ERR_WORKSPACE
+    assert call(d=FAKE + 2) == B.LAPLEX_ERR_ALIGN
+    assert call(k=0, a=None, m=None, ws=None, wsb=0) == B.LAPLEX_OK
