@@ -370,3 +370,42 @@ def wgram_scan(a, b, d):
     """(M, T) through the exact Gram decomposition, O(k^2 + n log k)."""
     a, b, d = _f64(a, 1), _f64(b, 1), _f64(d, 1)
     return _wgram_from_buckets(a, b, d), _wgram_from_buckets(a, b, np.abs(d))
+
+
+# --------------------------------------------------------------------------
+# LAPLEX^(r): a weighted sum of r Laplace-kernel operators with independent anchor
+# pairs (Sec. 7 "Learned anchor geometry in neural heads"):  y = sum_q w_q L(a_q, b_q) x.
+# a is (r, k), b is (r, n), w is (r,).
+# --------------------------------------------------------------------------
+
+def mix_apply(a, b, w, x, brute=True):
+    """(y, T): the sum written out, one operator at a time; T sums |w_q| L_q |x|."""
+    a, b, w = np.asarray(a), np.asarray(b), _f64(w, 1)
+    f = apply_brute if brute else apply_scan
+    y = tol = 0.0
+    for q in range(w.size):
+        yq, tq = f(a[q], b[q], x)
+        y = y + w[q] * yq
+        tol = tol + abs(w[q]) * tq
+    return y, tol
+
+
+def mix_backward(a, b, w, x, g, brute=True):
+    """Gradients of sum(g * y): (gx, ga (r, k), gb (r, n), gw (r,)) and their tolerance
+    denominators.  y is linear in every w_q L_q x, so gx = sum_q w_q L_q^T g, the anchor
+    gradients of operator q are w_q times those of L_q alone, and gw_q = <g, L_q x>."""
+    a, b, w = np.asarray(a), np.asarray(b), _f64(w, 1)
+    g64 = _f64(g, 2)
+    fb = apply_backward_brute if brute else apply_backward_scan
+    ff = apply_brute if brute else apply_scan
+    gx = tgx = 0.0
+    ga, gb, tga, tgb, gw, tgw = [], [], [], [], [], []
+    for q in range(w.size):
+        (gxq, gaq, gbq), (tgxq, tgaq, tgbq) = fb(a[q], b[q], x, g)
+        yq, tq = ff(a[q], b[q], x)
+        gx = gx + w[q] * gxq; tgx = tgx + abs(w[q]) * tgxq
+        ga.append(w[q] * gaq); gb.append(w[q] * gbq)
+        tga.append(abs(w[q]) * tgaq); tgb.append(abs(w[q]) * tgbq)
+        gw.append(float(np.sum(g64 * yq))); tgw.append(float(np.sum(np.abs(g64) * tq)))
+    return ((gx, np.stack(ga), np.stack(gb), np.array(gw)),
+            (tgx, np.stack(tga), np.stack(tgb), np.array(tgw)))

@@ -595,3 +595,52 @@ def test_weighted_gram_routes_agree(oracle, kind):
     assert np.all(np.isfinite(Ms))
     assert np.all(np.abs(M - Ms) <= 1e-12 * T + 1e-300)
     np.testing.assert_allclose(Ts, T, rtol=1e-12, atol=1e-300)
+
+
+# ---------------------------------------------------------------- LAPLEX^(r): weighted sums of operators
+
+def _mix_case(seed, r=3, k=5, n=7, batch=2):
+    q = rng(seed)
+    a = q.uniform(0, 3, (r, k)); b = q.uniform(0, 3, (r, n)); w = q.normal(size=r)
+    x = q.normal(size=(n, batch)); g = q.normal(size=(k, batch))
+    return a, b, w, x, g
+
+
+def test_mix_is_the_dense_weighted_sum(oracle):
+    a, b, w, x, g = _mix_case(71)
+    dense = sum(w[q] * np.exp(-np.abs(a[q][:, None] - b[q][None, :])) for q in range(w.size))
+    for brute in (True, False):
+        y, tol = oracle.mix_apply(a, b, w, x, brute=brute)
+        np.testing.assert_allclose(y, dense @ x, atol=1e-13)
+        (gx, ga, gb, gw), _ = oracle.mix_backward(a, b, w, x, g, brute=brute)
+        np.testing.assert_allclose(gx, dense.T @ g, atol=1e-13)
+    # one operator with weight 1 is the plain apply; the golden example, doubled and negated, cancels
+    y1, _ = oracle.mix_apply(a[:1], b[:1], [1.0], x)
+    np.testing.assert_array_equal(y1, oracle.apply_brute(a[0], b[0], x)[0])
+    gd = read_golden("apply_rational_3x2.txt")
+    ea = np.log(np.array(gd["exp_a"])); eb = np.log(np.array(gd["exp_b"])); ex = np.array(gd["x"]).reshape(-1, 1)
+    y2, _ = oracle.mix_apply(np.stack([ea, ea]), np.stack([eb, eb]), [2.0, -0.5], ex)
+    np.testing.assert_allclose(y2[:, 0], 1.5 * np.array(gd["y"]), rtol=1e-14)
+
+
+def test_mix_gradients_central_differences(oracle):
+    a, b, w, x, g = _mix_case(72)
+    (gx, ga, gb, gw), _ = oracle.mix_backward(a, b, w, x, g)
+
+    def loss(a_, b_, w_):
+        dense = sum(w_[q] * np.exp(-np.abs(a_[q][:, None] - b_[q][None, :])) for q in range(w_.size))
+        return float(np.sum(g * (dense @ x)))
+
+    h = 1e-6
+    for q in range(w.size):
+        d = np.zeros_like(w); d[q] = h
+        assert gw[q] == pytest.approx((loss(a, b, w + d) - loss(a, b, w - d)) / (2 * h), rel=1e-7, abs=1e-9)
+        for i in range(a.shape[1]):
+            d = np.zeros_like(a); d[q, i] = h
+            assert ga[q, i] == pytest.approx((loss(a + d, b, w) - loss(a - d, b, w)) / (2 * h), rel=1e-6, abs=1e-8)
+        for j in range(b.shape[1]):
+            d = np.zeros_like(b); d[q, j] = h
+            assert gb[q, j] == pytest.approx((loss(a, b + d, w) - loss(a, b - d, w)) / (2 * h), rel=1e-6, abs=1e-8)
+    (gxs, gas, gbs, gws), _ = oracle.mix_backward(a, b, w, x, g, brute=False)
+    for u, v in ((gx, gxs), (ga, gas), (gb, gbs), (gw, gws)):
+        np.testing.assert_allclose(u, v, atol=1e-12)
