@@ -36,7 +36,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-columns", type=int, default=256)
     ap.add_argument("--workload", default="projection",
-                    choices=["projection", "square", "tie_heavy", "gram", "billion", "phased", "wgram"],
+                    choices=["projection", "square", "tie_heavy", "gram", "billion", "phased", "wgram", "mix"],
                     help="projection is the benchmark; the others time one forward+backward step of the "
                          "other workloads (for profiles; no roofline object, no CPU baseline)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -105,6 +105,19 @@ def other_workload(args, torch, np, B, synth):
         def step():
             B.laplex_wgram(da, db, dd, m, ws, 0)
         elements = n + k
+    elif args.workload == "mix":
+        w = synth.mix_head(scale=args.scale)
+        a, b, x, g = w["a"], w["b"], w["x"], w["g"]
+        r, k, n, batch = w["r"], w["k"], w["n"], w["batch"]
+        ws = torch.empty(B.laplex_mix_workspace_bytes(r, k, n, batch), dtype=torch.uint8, device="cuda")
+        da, db, dw, dx, dg = dev(a), dev(b), dev(w["w"]), dev(x), dev(g)
+        y = torch.empty(k, batch, device="cuda"); gx = torch.empty(n, batch, device="cuda")
+        ga = torch.empty(r, k, device="cuda"); gb = torch.empty(r, n, device="cuda"); gw = torch.empty(r, device="cuda")
+
+        def step():
+            B.laplex_mix_apply(da, db, dw, dx, y, ws, B.LAPLEX_SAVE_SCANS)
+            B.laplex_mix_apply_backward(da, db, dw, dx, dg, gx, ga, gb, gw, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
+        elements = r * (n + k) * batch
     elif args.workload == "phased":
         w = synth.projection_layer_phased(scale=args.scale, batch=args.batch)
         a, b, x, g = w["a"], w["b"], w["x"], w["g"]

@@ -83,6 +83,7 @@ enum {
     LAPLEX_SAVE_SCANS = 8u
 };
 
+#define LAPLEX_MIX_MAX_OPERATORS 4096LL    /* operators summed by the laplex_mix_* calls */
 #define LAPLEX_WGRAM_MAX_ANCHORS 1048576LL /* rows of the k x k weighted Gram matrix */
 #define LAPLEX_MAX_MERGED 4294967294LL /* ids are 32-bit; 2^32-1 positions plus a sentinel slot */
 
@@ -206,6 +207,35 @@ int laplex_phased_apply_backward(const float* a, const float* phi, int64_t k,
                                  const float* x, int64_t ldx, const float* gy, int64_t ldgy, int64_t batch,
                                  float* gx, int64_t ldgx, float* ga, float* gb, float* gphi, float* gpsi,
                                  void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream);
+
+/*
+ * LAPLEX^(r): a weighted sum of r operators with independent anchor pairs
+ * (Sec. 7, "Learned anchor geometry in neural heads"):
+ *
+ *   y[i*ldy + t] = sum_q w[q] * sum_j exp(-|a[q*k + i] - b[q*n + j]|) * x[j*ldx + t]
+ *
+ * a[r][k], b[r][n] contiguous, w[r] in DEVICE memory (the mixing weights are
+ * trained like the anchors), r <= LAPLEX_MIX_MAX_OPERATORS.  Computed as r plain
+ * applies whose products are combined in a fixed order.  The workspace
+ * (laplex_mix_workspace_bytes) holds r plain workspaces back to back (operator q's
+ * plan sits at q * (their common size); the flags act on every operator alike),
+ * then the r products and the scratch of the backward call.
+ * laplex_mix_apply_backward: gradients of sum(gy * y): gx[n][batch], ga[r][k],
+ * gb[r][n] (tie rule as above), gw[r] = <gy, L_q x>; any may be NULL.  With
+ * LAPLEX_SAVE_SCANS the forward call (same flag, same workspace) has left what the
+ * backward needs; without it the products needed for gw are recomputed.  x may be
+ * NULL if only gx is wanted.  r == 0 gives y = 0.
+ */
+int laplex_mix_workspace_bytes(int64_t r, int64_t k, int64_t n, int64_t batch, size_t* out /* host */);
+
+int laplex_mix_apply(const float* a, const float* b, const float* w, int64_t r, int64_t k, int64_t n,
+                     const float* x, int64_t ldx, int64_t batch, float* y, int64_t ldy,
+                     void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream);
+
+int laplex_mix_apply_backward(const float* a, const float* b, const float* w, int64_t r, int64_t k, int64_t n,
+                              const float* x, int64_t ldx, const float* gy, int64_t ldgy, int64_t batch,
+                              float* gx, int64_t ldgx, float* ga, float* gb, float* gw,
+                              void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream);
 
 /*
  * Weighted Gram matrix (Sec. 3, "Computation of Gram matrix"; App. "Fast weighted

@@ -36,6 +36,7 @@ EXPORTS = (
     "laplex_phased_workspace_bytes", "laplex_phased_apply", "laplex_phased_apply_backward",
     "laplex_apply_tau", "laplex_apply_backward_tau", "laplex_gram_tau", "laplex_gram_backward_tau",
     "laplex_wgram_workspace_bytes", "laplex_wgram",
+    "laplex_mix_workspace_bytes", "laplex_mix_apply", "laplex_mix_apply_backward",
 )
 
 _lib = None
@@ -84,6 +85,10 @@ def lib() -> ctypes.CDLL:
         L.laplex_gram_backward_tau.argtypes = [_P, _I, _F, _P, _I, _P, _I, _I, _P, _I, _P, _P, _P, _Z, _U, _P]
         L.laplex_wgram_workspace_bytes.argtypes = [_I, _I, ctypes.POINTER(ctypes.c_size_t)]
         L.laplex_wgram.argtypes = [_P, _I, _P, _I, _P, _P, _I, _P, _Z, _U, _P]
+        L.laplex_mix_workspace_bytes.argtypes = [_I, _I, _I, _I, ctypes.POINTER(ctypes.c_size_t)]
+        L.laplex_mix_apply.argtypes = [_P, _P, _P, _I, _I, _I, _P, _I, _I, _P, _I, _P, _Z, _U, _P]
+        L.laplex_mix_apply_backward.argtypes = [_P, _P, _P, _I, _I, _I, _P, _I, _P, _I, _I, _P, _I, _P, _P, _P,
+                                                _P, _Z, _U, _P]
         for name in EXPORTS[:6] + EXPORTS[8:]:
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -236,3 +241,21 @@ def laplex_wgram(a, b, d, m, ws, flags: int = 0, stream=None) -> None:
     """m (k, k) <- A diag(d) A^T with A = L(a, b): the weighted Gram matrix."""
     _check(lib().laplex_wgram(_ptr(a), a.numel(), _ptr(b), b.numel(), _ptr(d), _ptr(m), _ld(m),
                               _ptr(ws), ws.numel(), flags, _stream(stream)))
+
+
+def laplex_mix_workspace_bytes(r: int, k: int, n: int, batch: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().laplex_mix_workspace_bytes(r, k, n, batch, ctypes.byref(out)))
+    return out.value
+
+
+def laplex_mix_apply(a, b, w, x, y, ws, flags: int = 0, stream=None) -> None:
+    """y <- sum_q w[q] L(a[q], b[q]) x;  a (r, k), b (r, n) contiguous, w (r,) on the device."""
+    _check(lib().laplex_mix_apply(_ptr(a), _ptr(b), _ptr(w), a.shape[0], a.shape[1], b.shape[1],
+                                  _ptr(x), _ld(x), _batch(x), _ptr(y), _ld(y), _ptr(ws), ws.numel(), flags, _stream(stream)))
+
+
+def laplex_mix_apply_backward(a, b, w, x, gy, gx, ga, gb, gw, ws, flags: int = 0, stream=None) -> None:
+    _check(lib().laplex_mix_apply_backward(
+        _ptr(a), _ptr(b), _ptr(w), a.shape[0], a.shape[1], b.shape[1], _ptr(x), _ld(x), _ptr(gy), _ld(gy), _batch(gy),
+        _ptr(gx), _ld(gx), _ptr(ga), _ptr(gb), _ptr(gw), _ptr(ws), ws.numel(), flags, _stream(stream)))

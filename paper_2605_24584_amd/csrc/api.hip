@@ -204,6 +204,35 @@ int check_wgram_sizes(int64_t k, int64_t n)
     return LAPLEX_OK;
 }
 
+
+// ----------------------------------------------------------------------------
+// LAPLEX^(r): r plain workspaces back to back (each operator keeps its own plan and saved scans), then
+// the r products L_q x (kept for the gradient of the mixing weights), the scaled upstream gradient of
+// the operator at hand, its gx, and the partial sums of the inner products.
+// ----------------------------------------------------------------------------
+struct MixLayout {
+    size_t inner = 0, off_parts = 0, off_gyq = 0, off_gxq = 0, off_partial = 0, total = 0;
+};
+
+MixLayout mix_layout(int64_t r, int64_t k, int64_t n, int64_t batch)
+{
+    MixLayout M;
+    M.inner = align_up(make_layout(k + n, k, batch).total);
+    size_t o = M.inner * (size_t)r;
+    M.off_parts = o;   o = align_up(o + sizeof(float) * (size_t)r * (size_t)k * (size_t)batch);
+    M.off_gyq = o;     o = align_up(o + sizeof(float) * (size_t)k * (size_t)batch);
+    M.off_gxq = o;     o = align_up(o + sizeof(float) * (size_t)n * (size_t)batch);
+    M.off_partial = o; o = align_up(o + sizeof(float) * kTauPartials);
+    M.total = o;
+    return M;
+}
+
+int check_mix_sizes(int64_t r, int64_t k, int64_t n, int64_t batch)
+{
+    if (r < 0 || r > LAPLEX_MIX_MAX_OPERATORS) return LAPLEX_ERR_SIZE;
+    return check_sizes(k, n, batch);
+}
+
 }  // namespace
 
 extern "C" {
@@ -604,6 +633,106 @@ int laplex_wgram(const float* a, int64_t k, const float* b, int64_t n, const flo
     LAPLEX_HIP(launch_scan(p, L, w, st));
     LAPLEX_HIP(launch_wgram_prefix(P.ids, d, k, k + n, tile_sum, W, st));
     LAPLEX_HIP(launch_wgram_fill(a, U, V, W, k, m, ldm, st));
+    return LAPLEX_OK;
+}
+
+int laplex_mix_workspace_bytes(int64_t r, int64_t k, int64_t n, int64_t batch, size_t* out)
+{
+    if (!out) return LAPLEX_ERR_NULL;
+    LAPLEX_CHECK(check_mix_sizes(r, k, n, batch));
+    *out = mix_layout(r, k, n, batch).total;
+    return LAPLEX_OK;
+}
+
+int laplex_mix_apply(const float* a, const float* b, const float* w, int64_t r, int64_t k, int64_t n,
+                     const float* x, int64_t ldx, int64_t batch, float* y, int64_t ldy,
+                     void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream)
+{
+    const uint32_t known = LAPLEX_A_SORTED | LAPLEX_B_SORTED | LAPLEX_REUSE_PLAN | LAPLEX_SAVE_SCANS;
+    if (flags & ~known) return LAPLEX_ERR_FLAGS;
+    LAPLEX_CHECK(check_mix_sizes(r, k, n, batch));
+    if (r > 0) {
+        LAPLEX_CHECK(check_vector(a, k, true));
+        LAPLEX_CHECK(check_vector(b, n, true));
+        LAPLEX_CHECK(check_vector(w, r, true));
+    }
+    LAPLEX_CHECK(check_matrix(x, n, ldx, batch, r > 0));
+    LAPLEX_CHECK(check_matrix(y, k, ldy, batch, true));
+    if (k == 0 || batch == 0) return LAPLEX_OK;
+    hipStream_t st = stream;
+    if (n == 0 || r == 0) {
+        LAPLEX_HIP(launch_fill(y, k, batch, ldy, 0.0f, st));
+        return LAPLEX_OK;
+    }
+    const MixLayout M = mix_layout(r, k, n, batch);
+    if (!ws) return LAPLEX_ERR_NULL;
+    if (misaligned(ws, 256)) return LAPLEX_ERR_ALIGN;
+    if (ws_bytes < M.total) return LAPLEX_ERR_WORKSPACE;
+    char* base = static_cast<char*>(ws);
+    float* parts = reinterpret_cast<float*>(base + M.off_parts);
+    for (int64_t q = 0; q < r; ++q)
+        LAPLEX_CHECK(laplex_apply(a + q * k, k, b + q * n, n, x, ldx, batch, parts + q * k * batch, batch,
+                                  base + (size_t)q * M.inner, M.inner, flags, stream));
+    LAPLEX_HIP(launch_mix_combine(parts, w, r, k, batch, y, ldy, st));
+    return LAPLEX_OK;
+}
+
+int laplex_mix_apply_backward(const float* a, const float* b, const float* w, int64_t r, int64_t k, int64_t n,
+                              const float* x, int64_t ldx, const float* gy, int64_t ldgy, int64_t batch,
+                              float* gx, int64_t ldgx, float* ga, float* gb, float* gw,
+                              void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream)
+{
+    const uint32_t known = LAPLEX_A_SORTED | LAPLEX_B_SORTED | LAPLEX_REUSE_PLAN | LAPLEX_SAVE_SCANS;
+    if (flags & ~known) return LAPLEX_ERR_FLAGS;
+    LAPLEX_CHECK(check_mix_sizes(r, k, n, batch));
+    if (r > 0) {
+        LAPLEX_CHECK(check_vector(a, k, true));
+        LAPLEX_CHECK(check_vector(b, n, true));
+        LAPLEX_CHECK(check_vector(w, r, true));
+    }
+    const bool need_x = r > 0 && (ga || gb || gw);
+    LAPLEX_CHECK(check_matrix(x, n, ldx, batch, need_x));
+    LAPLEX_CHECK(check_matrix(gy, k, ldgy, batch, r > 0));
+    LAPLEX_CHECK(check_matrix(gx, n, ldgx, batch, false));
+    LAPLEX_CHECK(check_vector(ga, r > 0 ? k : 0, false));
+    LAPLEX_CHECK(check_vector(gb, r > 0 ? n : 0, false));
+    LAPLEX_CHECK(check_vector(gw, r, false));
+    hipStream_t st = stream;
+    if (r == 0 || k == 0 || n == 0 || batch == 0) {      // nothing is summed: every wanted gradient is zero
+        if (gx) LAPLEX_HIP(launch_fill(gx, n, batch, ldgx, 0.0f, st));
+        if (ga) LAPLEX_HIP(launch_fill(ga, r * k, 1, 1, 0.0f, st));
+        if (gb) LAPLEX_HIP(launch_fill(gb, r * n, 1, 1, 0.0f, st));
+        if (gw) LAPLEX_HIP(launch_fill(gw, r, 1, 1, 0.0f, st));
+        return LAPLEX_OK;
+    }
+    const MixLayout M = mix_layout(r, k, n, batch);
+    if (!ws) return LAPLEX_ERR_NULL;
+    if (misaligned(ws, 256)) return LAPLEX_ERR_ALIGN;
+    if (ws_bytes < M.total) return LAPLEX_ERR_WORKSPACE;
+    char* base = static_cast<char*>(ws);
+    float* parts = reinterpret_cast<float*>(base + M.off_parts);
+    float* gyq = reinterpret_cast<float*>(base + M.off_gyq);
+    float* gxq = reinterpret_cast<float*>(base + M.off_gxq);
+    float* partial = reinterpret_cast<float*>(base + M.off_partial);
+    const bool saved = (flags & LAPLEX_SAVE_SCANS) != 0;      // the forward left every operator's product and scans
+    for (int64_t q = 0; q < r; ++q) {
+        char* wq = base + (size_t)q * M.inner;
+        float* part = parts + q * k * batch;
+        uint32_t inner = flags;
+        if (gw && !saved) {        // the weight's gradient needs the operator's own product
+            LAPLEX_CHECK(laplex_apply(a + q * k, k, b + q * n, n, x, ldx, batch, part, batch, wq, M.inner,
+                                      flags | LAPLEX_SAVE_SCANS, stream));
+            inner = flags | LAPLEX_SAVE_SCANS | LAPLEX_REUSE_PLAN;
+        }
+        if (gx || ga || gb) {      // the operator's gradients are linear in the upstream gradient: scale it by w_q
+            LAPLEX_HIP(launch_scale_by_device_scalar(gy, ldgy, w + q, k, batch, gyq, st));
+            LAPLEX_CHECK(laplex_apply_backward(a + q * k, k, b + q * n, n, x, ldx, gyq, batch, batch,
+                                               gx ? gxq : nullptr, batch, ga ? ga + q * k : nullptr,
+                                               gb ? gb + q * n : nullptr, wq, M.inner, inner, stream));
+            if (gx) LAPLEX_HIP(launch_accumulate(gxq, n, batch, gx, ldgx, q == 0, st));
+        }
+        if (gw) LAPLEX_HIP(launch_dot(gy, ldgy, part, k, batch, partial, gw + q, st));
+    }
     return LAPLEX_OK;
 }
 

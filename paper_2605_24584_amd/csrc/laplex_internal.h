@@ -265,6 +265,18 @@ hipError_t launch_tau_grad(const float* a, const float* ga, int64_t k, const flo
                            float* partial, float* gtau, hipStream_t st);
 hipError_t launch_scale(float* p, int64_t count, float f, hipStream_t st);
 
+// LAPLEX^(r) helpers (phase_kernels.hip).  parts: r contiguous (rows, batch) matrices; w, scale: device memory.
+//   combine: y = sum_q w[q] parts[q];  scale: dst (contiguous) = scale[0] * src;  accumulate: dst (+)= src (contiguous);
+//   dot: out[0] = sum u .* v (v contiguous), fixed order, `partial` = kTauPartials floats of scratch.
+hipError_t launch_mix_combine(const float* parts, const float* w, int64_t r, int64_t rows, int64_t batch,
+                              float* y, int64_t ldy, hipStream_t st);
+hipError_t launch_scale_by_device_scalar(const float* src, int64_t ld_src, const float* scale, int64_t rows, int64_t batch,
+                                         float* dst, hipStream_t st);
+hipError_t launch_accumulate(const float* src, int64_t rows, int64_t batch, float* dst, int64_t ld_dst, bool first,
+                             hipStream_t st);
+hipError_t launch_dot(const float* u, int64_t ldu, const float* v, int64_t rows, int64_t batch,
+                      float* partial, float* out, hipStream_t st);
+
 // Weighted Gram matrix (gram_kernels.hip).  launch_wgram_prefix: W[id] (fp64) = sum of d over the middle anchors
 // (ids >= k) that precede Gram anchor `id` in the merged order; tile_sum: scratch, wgram_tiles(N) doubles.
 // launch_wgram_fill: M[i*ldm + j] = exp(-|a_i - a_j|) (U[lo] + (W[hi] - W[lo]) + V[hi]), lo / hi the pair in sorted order.

@@ -109,6 +109,77 @@ k_scale(float* __restrict__ p, int64_t count, float f)
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) p[i] *= f;
 }
 
+
+// ---------------------------------------------------------------------------
+// LAPLEX^(r) = sum_q w_q L(a_q, b_q)  (Sec. 7 "Learned anchor geometry in neural heads"): r plain operators
+// with independent anchor pairs and scalar mixing weights w (device memory: they are trained).  The products
+// of the r operators are combined in a fixed order; the gradient of w_q is the inner product <gy, L_q x>.
+// y[i][t] = sum_q w[q] parts[q][i][t]    (parts: r contiguous (rows, batch) matrices)
+__global__ void __launch_bounds__(256)
+k_mix_combine(const float* __restrict__ parts, const float* __restrict__ w, int64_t r, int64_t rows, int64_t batch,
+              float* __restrict__ y, int64_t ldy)
+{
+    const int64_t total = rows * batch;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += stride) {
+        float acc = 0.0f;
+        for (int64_t q = 0; q < r; ++q) acc += w[q] * parts[q * total + e];
+        y[(e / batch) * ldy + (e % batch)] = acc;
+    }
+}
+
+// dst[i][t] (contiguous) = scale[0] * src[i*ld_src + t]
+__global__ void __launch_bounds__(256)
+k_scale_by_device_scalar(const float* __restrict__ src, int64_t ld_src, const float* __restrict__ scale,
+                         int64_t rows, int64_t batch, float* __restrict__ dst)
+{
+    const float f = scale[0];
+    const int64_t total = rows * batch;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += stride)
+        dst[e] = f * src[(e / batch) * ld_src + (e % batch)];
+}
+
+// dst[i*ld_dst + t] = (first ? 0 : dst[...]) + src[i][t] (src contiguous)
+__global__ void __launch_bounds__(256)
+k_accumulate(const float* __restrict__ src, int64_t rows, int64_t batch, float* __restrict__ dst, int64_t ld_dst, int first)
+{
+    const int64_t total = rows * batch;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += stride) {
+        float* p = dst + (e / batch) * ld_dst + (e % batch);
+        *p = first ? src[e] : *p + src[e];
+    }
+}
+
+// partial[g] = sum over workgroup g's share of u[i*ldu + t] * v[i][t] (v contiguous); k_tau_final adds the partials
+__global__ void __launch_bounds__(256)
+k_dot_partial(const float* __restrict__ u, int64_t ldu, const float* __restrict__ v, int64_t rows, int64_t batch,
+              float* __restrict__ partial)
+{
+    __shared__ float red[256];
+    const int64_t total = rows * batch;
+    const int64_t per = (total + gridDim.x - 1) / gridDim.x;
+    const int64_t lo = per * blockIdx.x, hi = lo + per < total ? lo + per : total;
+    float acc = 0.0f;
+    for (int64_t e = lo + threadIdx.x; e < hi; e += 256) acc += u[(e / batch) * ldu + (e % batch)] * v[e];
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    for (int s = 128; s >= 1; s >>= 1) {
+        if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) partial[blockIdx.x] = red[0];
+}
+
+inline unsigned flat_grid(int64_t total)
+{
+    int64_t g = (total + 255) / 256;
+    if (g < 1) g = 1;
+    if (g > 65536) g = 65536;
+    return (unsigned)g;
+}
+
 inline unsigned rows_grid(int64_t rows)
 {
     int64_t g = (rows + 3) / 4;          // four wavefronts (rows) per workgroup
@@ -155,6 +226,41 @@ hipError_t launch_scale(float* p, int64_t count, float f, hipStream_t st)
     int64_t g = (count + 255) / 256;
     if (g > 65536) g = 65536;
     LAPLEX_TIMED("tau", st, hipLaunchKernelGGL(k_scale, dim3((unsigned)g), dim3(256), 0, st, p, count, f));
+    return hipGetLastError();
+}
+
+hipError_t launch_mix_combine(const float* parts, const float* w, int64_t r, int64_t rows, int64_t batch,
+                              float* y, int64_t ldy, hipStream_t st)
+{
+    LAPLEX_TIMED("mix", st, hipLaunchKernelGGL(k_mix_combine, dim3(flat_grid(rows * batch)), dim3(256), 0, st,
+                                               parts, w, r, rows, batch, y, ldy));
+    return hipGetLastError();
+}
+
+hipError_t launch_scale_by_device_scalar(const float* src, int64_t ld_src, const float* scale, int64_t rows, int64_t batch,
+                                         float* dst, hipStream_t st)
+{
+    LAPLEX_TIMED("mix", st, hipLaunchKernelGGL(k_scale_by_device_scalar, dim3(flat_grid(rows * batch)), dim3(256), 0, st,
+                                               src, ld_src, scale, rows, batch, dst));
+    return hipGetLastError();
+}
+
+hipError_t launch_accumulate(const float* src, int64_t rows, int64_t batch, float* dst, int64_t ld_dst, bool first,
+                             hipStream_t st)
+{
+    LAPLEX_TIMED("mix", st, hipLaunchKernelGGL(k_accumulate, dim3(flat_grid(rows * batch)), dim3(256), 0, st,
+                                               src, rows, batch, dst, ld_dst, first ? 1 : 0));
+    return hipGetLastError();
+}
+
+hipError_t launch_dot(const float* u, int64_t ldu, const float* v, int64_t rows, int64_t batch,
+                      float* partial, float* out, hipStream_t st)
+{
+    int64_t groups = (rows * batch + 8191) / 8192;
+    if (groups < 1) groups = 1;
+    if (groups > kTauPartials) groups = kTauPartials;
+    LAPLEX_TIMED("mix", st, hipLaunchKernelGGL(k_dot_partial, dim3((unsigned)groups), dim3(256), 0, st, u, ldu, v, rows, batch, partial));
+    LAPLEX_TIMED("mix", st, hipLaunchKernelGGL(k_tau_final, dim3(1), dim3(256), 0, st, (const float*)partial, (int)groups, out));
     return hipGetLastError();
 }
 

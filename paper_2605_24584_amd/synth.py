@@ -156,6 +156,22 @@ def weighted_gram(scale: int = 1, k: int = 1024):
     )
 
 
+def mix_head(scale: int = 1, r: int = 16, batch: int = 256):
+    """LAPLEX^(r) classification head (Sec. 7): r = 16 operators of shape classes x features =
+    1000 x 2048, batch 256; anchors U(0, 48) (about 64 anchors per unit, as in the other workloads),
+    mixing weights, x and the upstream gradient ~ N(0, 1) (config slot 9)."""
+    k = _shrunk(1000, scale); n = _shrunk(2048, scale)
+    hi = 48.0 / scale
+    return dict(
+        name="mix_head_r16_k1000_n2048_b256", config=9, r=r, k=k, n=n, batch=batch,
+        a=uniform(stream_seed(9, STREAM_A), r * k, 0.0, hi).reshape(r, k),
+        b=uniform(stream_seed(9, STREAM_B), r * n, 0.0, hi).reshape(r, n),
+        w=normal(stream_seed(9, STREAM_G) + 1, r),
+        x=normal(stream_seed(9, STREAM_X), n * batch).reshape(n, batch),
+        g=normal(stream_seed(9, STREAM_G), k * batch).reshape(k, batch),
+    )
+
+
 def tie_heavy(scale: int = 1):
     """n = k = 2^24, batch 1, anchors U(0, 2^18) rounded to a 1/4 grid."""
     n = k = _shrunk(1 << 24, scale)

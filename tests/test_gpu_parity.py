@@ -643,3 +643,64 @@ def test_weighted_gram_options(oracle):
     e = np.zeros(0, dtype=np.float32)                              # nothing to sum over
     m4, _ = gpu_wgram(a, e, e)
     assert np.all(m4 == 0)
+
+
+# ------------------------------------------------------------------ LAPLEX^(r): weighted sums of operators
+
+def gpu_mix(a, b, w, x, g, flags_fwd, flags_bwd, want=(True, True, True, True), forward=True):
+    r, k = a.shape; n = b.shape[1]; batch = x.shape[1]
+    ws = torch.empty(B.laplex_mix_workspace_bytes(r, k, n, batch), dtype=torch.uint8, device="cuda")
+    da, db, dw, dx, dg = dev(a), dev(b), dev(w), dev(x), dev(g)
+    y = torch.full((k, batch), float("nan"), device="cuda")
+    if forward:
+        B.laplex_mix_apply(da, db, dw, dx, y, ws, flags_fwd)
+    outs = [torch.full(s, float("nan"), device="cuda") if wnt else None
+            for s, wnt in zip(((n, batch), (r, k), (r, n), (r,)), want)]
+    B.laplex_mix_apply_backward(da, db, dw, dx, dg, *outs, ws, flags_bwd)
+    torch.cuda.synchronize()
+    return y.cpu().numpy(), tuple(None if t is None else t.cpu().numpy() for t in outs)
+
+
+@pytest.mark.parametrize("kind", ["uniform", "ties"])
+@pytest.mark.parametrize("r,k,n,batch", [(1, 5, 1, 2), (3, 37, 53, 3), (4, 10, 512, 64), (16, 100, 768, 128),
+                                         (2, 1000, 2048, 256), (5, 300, 2100, 1)])
+def test_mix_forward_backward(oracle, kind, r, k, n, batch):
+    """y = sum_q w_q L(a_q, b_q) x and the gradients (gx, ga, gb, gw), the classification-head shapes
+    (classes x features) among them."""
+    q = np.random.default_rng(9000 + r + k + n + batch)
+    ab = [anchors(kind, q, k, n) for _ in range(r)]
+    a = np.stack([u for u, _ in ab]); b = np.stack([v for _, v in ab])
+    w = q.normal(size=r).astype(np.float32)
+    x = q.normal(size=(n, batch)).astype(np.float32); g = q.normal(size=(k, batch)).astype(np.float32)
+    brute = r * k * n * batch <= 6e7
+    ref, tol = oracle.mix_apply(a, b, w, x, brute=brute)
+    want, tols = oracle.mix_backward(a, b, w, x, g, brute=brute)
+    y, grads = gpu_mix(a, b, w, x, g, B.LAPLEX_SAVE_SCANS, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
+    assert_close("y", y, ref, tol)
+    for name, got, rv, tv in zip(("gx", "ga", "gb", "gw"), grads, want, tols):
+        assert_close(name, got, rv, tv)
+    # the backward standing alone (sorts and recomputes the products itself): the same bits
+    _, alone = gpu_mix(a, b, w, x, g, 0, 0, forward=False)
+    for name, u, v in zip(("gx", "ga", "gb", "gw"), grads, alone):
+        assert np.array_equal(u, v), name
+
+
+def test_mix_subsets_and_empty(oracle):
+    q = np.random.default_rng(9100)
+    r, k, n, batch = 3, 20, 150, 6
+    ab = [anchors("uniform", q, k, n) for _ in range(r)]
+    a = np.stack([u for u, _ in ab]); b = np.stack([v for _, v in ab])
+    w = q.normal(size=r).astype(np.float32)
+    x = q.normal(size=(n, batch)).astype(np.float32); g = q.normal(size=(k, batch)).astype(np.float32)
+    want, tols = oracle.mix_backward(a, b, w, x, g)
+    names = ("gx", "ga", "gb", "gw")
+    for pick in ((True, False, False, False), (False, False, False, True), (False, True, True, False)):
+        _, grads = gpu_mix(a, b, w, x, g, 0, 0, want=pick, forward=False)
+        for name, got, rv, tv, wnt in zip(names, grads, want, tols, pick):
+            if wnt:
+                assert_close(name, got, rv, tv)
+    # no operators: y = 0 and gx = 0
+    e = np.zeros((0, k), dtype=np.float32)
+    y, grads = gpu_mix(e, np.zeros((0, n), dtype=np.float32), np.zeros(0, dtype=np.float32), x, g, 0, 0,
+                       want=(True, False, False, False))
+    assert np.all(y == 0) and np.all(grads[0] == 0)

@@ -241,3 +241,37 @@ def test_weighted_gram_argument_checks(L):
     assert call(wsb=64) == B.LAPLEX_ERR_WORKSPACE
     assert call(d=FAKE + 2) == B.LAPLEX_ERR_ALIGN
     assert call(k=0, a=None, m=None, ws=None, wsb=0) == B.LAPLEX_OK
+
+
+# ------------------------------------------------------------------ LAPLEX^(r)
+
+def test_mix_argument_checks(L):
+    out = ctypes.c_size_t(0)
+    assert L.laplex_mix_workspace_bytes(2, 8, 8, 4, None) == B.LAPLEX_ERR_NULL
+    assert L.laplex_mix_workspace_bytes(-1, 8, 8, 4, ctypes.byref(out)) == B.LAPLEX_ERR_SIZE
+    assert L.laplex_mix_workspace_bytes(4097, 8, 8, 4, ctypes.byref(out)) == B.LAPLEX_ERR_SIZE
+    assert L.laplex_mix_workspace_bytes(3, 64, 4096, 8, ctypes.byref(out)) == 0
+    plain = ctypes.c_size_t(0)
+    assert L.laplex_workspace_bytes(64, 4096, 8, ctypes.byref(plain)) == 0
+    assert out.value % 256 == 0 and out.value >= 3 * plain.value + 4 * 8 * (3 * 64 + 64 + 4096)
+    r, k, n, batch = 2, 8, 8, 4
+    good = [FAKE, FAKE, FAKE, r, k, n, FAKE, batch, batch, FAKE, batch, FAKE, 1 << 40, 0, None]
+    def call(**kw):
+        args = list(good)
+        for i, v in kw.items():
+            args[int(i[1:])] = v
+        return L.laplex_mix_apply(*args)
+    assert call(_0=None) == B.LAPLEX_ERR_NULL            # a
+    assert call(_2=None) == B.LAPLEX_ERR_NULL            # w
+    assert call(_6=None) == B.LAPLEX_ERR_NULL            # x
+    assert call(_7=batch - 1) == B.LAPLEX_ERR_LD
+    assert call(_11=None) == B.LAPLEX_ERR_NULL           # workspace
+    assert call(_12=64) == B.LAPLEX_ERR_WORKSPACE
+    assert call(_13=1 << 9) == B.LAPLEX_ERR_FLAGS
+    assert call(_3=-1) == B.LAPLEX_ERR_SIZE
+    assert call(_4=0, _9=None, _11=None, _12=0) == B.LAPLEX_OK        # k == 0: nothing to do
+    bgood = [FAKE, FAKE, FAKE, r, k, n, None, batch, FAKE, batch, batch, FAKE, batch, None, None, FAKE,
+             FAKE, 1 << 40, 0, None]
+    assert L.laplex_mix_apply_backward(*bgood) == B.LAPLEX_ERR_NULL                 # gw wanted, x missing
+    bgood[6] = FAKE; bgood[8] = None
+    assert L.laplex_mix_apply_backward(*bgood) == B.LAPLEX_ERR_NULL                 # gy missing
