@@ -143,6 +143,18 @@ int build_plan(const float* a, int64_t k, const float* b, int64_t n, float tau, 
     return LAPLEX_OK;
 }
 
+// Arguments of the one-launch path for small problems (one operator; callers add problems and strides).
+SmallArgs small_args(const float* a, int64_t k, const float* b, int64_t n, float tau, const Plan& P, const Layout& L,
+                     uint32_t flags)
+{
+    SmallArgs S{};
+    S.a = a; S.b = b; S.k = k; S.n = n; S.tau = tau;
+    S.ids = P.ids; S.dh = P.dh; S.pk = P.pk;
+    S.reuse_plan = (flags & LAPLEX_REUSE_PLAN) ? 1 : 0;
+    S.batch = L.batch; S.cols = small_cols(L.batch);
+    return S;
+}
+
 ScanProblem problem(const Plan& P, const Layout& L)
 {
     ScanProblem p{};
@@ -268,6 +280,17 @@ static int apply_impl(const float* a, int64_t k, const float* b, int64_t n,
         if (flags & LAPLEX_SAVE_SCANS) LAPLEX_HIP(launch_fill(P.z, k, batch, batch, 0.0f, st));
         return LAPLEX_OK;
     }
+    if (L.N <= kSmallMax) {        // sort, decays, both scans and the scatter in one launch
+        SmallArgs S = small_args(a, k, b, n, tau, P, L, flags);
+        S.nprob = 1;
+        SmallProblem& q = S.prob[0];
+        q.inj = x; q.ld_inj = ldx; q.inj_lo = (uint32_t)k; q.inj_hi = (uint32_t)(k + n);
+        q.res_lo = 0; q.res_hi = (uint32_t)k;
+        q.out_p = y; q.ld_p = ldy;
+        q.out_z = (flags & LAPLEX_SAVE_SCANS) ? P.z : nullptr;
+        LAPLEX_HIP(launch_small(S, 1, st));
+        return LAPLEX_OK;
+    }
     const bool sorted = (flags & LAPLEX_A_SORTED) && (flags & LAPLEX_B_SORTED);
     LAPLEX_CHECK(build_plan(a, k, b, n, tau, L, w, flags, sorted, st));
     ScanProblem p = problem(P, L);
@@ -311,6 +334,32 @@ static int apply_backward_impl(const float* a, int64_t k, const float* b, int64_
     }
     char* w = static_cast<char*>(ws);
     const Plan P = plan_of(L, w);
+    if (L.N <= kSmallMax) {        // one launch for the sort and both scan problems, then the two row reductions
+        SmallArgs S = small_args(a, k, b, n, tau, P, L, flags);
+        float* zg = reinterpret_cast<float*>(w + L.off_small);
+        if (ga && !(flags & LAPLEX_SAVE_SCANS)) {     // strict scans of x at the outputs, not kept by the forward
+            SmallProblem& q = S.prob[S.nprob++];
+            q.inj = x; q.ld_inj = ldx; q.inj_lo = (uint32_t)k; q.inj_hi = (uint32_t)(k + n);
+            q.res_lo = 0; q.res_hi = (uint32_t)k;
+            q.out_z = P.z;
+        }
+        if (gx || gb) {
+            SmallProblem& q = S.prob[S.nprob++];
+            q.inj = gy; q.ld_inj = ldgy; q.inj_lo = 0; q.inj_hi = (uint32_t)k;
+            q.res_lo = (uint32_t)k; q.res_hi = (uint32_t)(k + n);
+            q.out_p = gx; q.ld_p = ldgx;
+            q.out_z = gb ? zg : nullptr;
+        }
+        if (S.nprob > 0) LAPLEX_HIP(launch_small(S, 1, st));
+        if (ga) LAPLEX_HIP(launch_rowdot(gy, ldgy, P.z, batch, k, batch, ga, st));
+        if (gb) LAPLEX_HIP(launch_rowdot(x, ldx, zg, batch, n, batch, gb, st));
+        if (gtau) LAPLEX_HIP(launch_tau_grad(a, ga, k, b, gb, n, reinterpret_cast<float*>(w + L.off_scratch), gtau, st));
+        if (tau != 1.0f) {
+            if (ga) LAPLEX_HIP(launch_scale(ga, k, tau, st));
+            if (gb) LAPLEX_HIP(launch_scale(gb, n, tau, st));
+        }
+        return LAPLEX_OK;
+    }
     const bool sorted = (flags & LAPLEX_A_SORTED) && (flags & LAPLEX_B_SORTED);
     LAPLEX_CHECK(build_plan(a, k, b, n, tau, L, w, flags, sorted, st));
     if (ga) {

@@ -26,6 +26,8 @@ constexpr int kSortSmallWords = 1088;
 constexpr int kMergeThreads = 256;
 constexpr int kMergePerThread = 8;
 constexpr int kMergeTile = kMergeThreads * kMergePerThread;
+// Problems with at most this many merged positions run in one launch, sorted and scanned inside one workgroup.
+constexpr int kSmallMax = 8192;
 
 // ----------------------------------------------------------------------------
 // Scan geometry.  A workgroup of up to kScanWaves wavefronts owns one tile of
@@ -126,6 +128,8 @@ struct Layout {
     // second level of the spine: the same five arrays over chunks of tiles
     size_t off_agg2_scalar = 0, off_agg2_s = 0, off_agg2_q = 0, off_car2_f = 0, off_car2_e = 0;
     int64_t max_tiles = 0, max_blocks = 0, max_chunks = 0;
+    // small problems (N <= kSmallMax): f32[N][batch], the strict scans of the backward's second problem
+    size_t off_small = 0;
     size_t total = 0;
 };
 
@@ -182,6 +186,8 @@ inline Layout make_layout(int64_t N, int64_t zrows, int64_t batch)
     L.off_car2_e = c;      c = align_up(c + per2);
 
     L.total = s > c ? s : c;
+    L.off_small = align_up(L.total);
+    if (N <= kSmallMax) L.total = align_up(L.off_small + sizeof(float) * (size_t)N * (size_t)batch);
     return L;
 }
 
@@ -264,6 +270,28 @@ constexpr int kTauPartials = 1024;
 hipError_t launch_tau_grad(const float* a, const float* ga, int64_t k, const float* b, const float* gb, int64_t n,
                            float* partial, float* gtau, hipStream_t st);
 hipError_t launch_scale(float* p, int64_t count, float f, hipStream_t st);
+
+// Small problems (small_kernels.hip): at most kSmallMax merged positions are sorted by one launch (ranks by counting)
+// and scanned by one workgroup per (slab of `cols` batch columns, operator) in a second.  A SmallProblem is a ScanProblem restricted to
+// out_p / out_z; pointers move by the op_* strides (in elements; op_ws in bytes) from one operator to the next.
+struct SmallProblem {
+    const float* inj; int64_t ld_inj; uint32_t inj_lo, inj_hi;
+    uint32_t res_lo, res_hi;
+    float* out_p; int64_t ld_p;     // F + R - v at the result rows, or null
+    float* out_z;                   // (res rows, batch) contiguous: E_right - E_left, or null
+    int64_t op_inj, op_p, op_z;
+};
+struct SmallArgs {
+    const float* a; const float* b; int64_t k, n; float tau;
+    uint32_t* ids; float* dh; float* pk;       // the plan in the workspace: written (slab 0), or read if reuse_plan
+    int64_t op_a, op_b, op_ws;
+    int reuse_plan;                            // the workspace holds the plan: no sort
+    int write_dh;                              // set by the launcher: the decays are stored beside the plan
+    int64_t batch; int cols;                   // cols: power of two <= 16
+    int nprob; SmallProblem prob[2];
+};
+hipError_t launch_small(const SmallArgs& A, int64_t operators, hipStream_t st);
+inline int small_cols(int64_t batch) { int c = 1; while (c < batch && c < 16) c <<= 1; return c; }
 
 // LAPLEX^(r) helpers (phase_kernels.hip).  parts: r contiguous (rows, batch) matrices; w, scale: device memory.
 //   combine: y = sum_q w[q] parts[q];  scale: dst (contiguous) = scale[0] * src;  accumulate: dst (+)= src (contiguous);
