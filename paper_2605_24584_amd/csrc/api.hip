@@ -232,9 +232,11 @@ MixLayout mix_layout(int64_t r, int64_t k, int64_t n, int64_t batch)
     M.inner = align_up(make_layout(k + n, k, batch).total);
     size_t o = M.inner * (size_t)r;
     M.off_parts = o;   o = align_up(o + sizeof(float) * (size_t)r * (size_t)k * (size_t)batch);
-    M.off_gyq = o;     o = align_up(o + sizeof(float) * (size_t)k * (size_t)batch);
-    M.off_gxq = o;     o = align_up(o + sizeof(float) * (size_t)n * (size_t)batch);
-    M.off_partial = o; o = align_up(o + sizeof(float) * kTauPartials);
+    // small problems run all operators in one launch and need these per operator
+    const size_t per_op = (k + n <= kSmallMax) ? (size_t)r : 1;
+    M.off_gyq = o;     o = align_up(o + sizeof(float) * per_op * (size_t)k * (size_t)batch);
+    M.off_gxq = o;     o = align_up(o + sizeof(float) * per_op * (size_t)n * (size_t)batch);
+    M.off_partial = o; o = align_up(o + sizeof(float) * (kTauPartials > (size_t)r * kDotGroups ? kTauPartials : (size_t)r * kDotGroups));
     M.total = o;
     return M;
 }
@@ -719,9 +721,23 @@ int laplex_mix_apply(const float* a, const float* b, const float* w, int64_t r, 
     if (ws_bytes < M.total) return LAPLEX_ERR_WORKSPACE;
     char* base = static_cast<char*>(ws);
     float* parts = reinterpret_cast<float*>(base + M.off_parts);
-    for (int64_t q = 0; q < r; ++q)
-        LAPLEX_CHECK(laplex_apply(a + q * k, k, b + q * n, n, x, ldx, batch, parts + q * k * batch, batch,
-                                  base + (size_t)q * M.inner, M.inner, flags, stream));
+    if (k + n <= kSmallMax) {      // every operator in the same two launches
+        const Layout L = make_layout(k + n, k, batch);
+        const Plan P = plan_of(L, base);
+        SmallArgs S = small_args(a, k, b, n, 1.0f, P, L, flags);
+        S.op_a = k; S.op_b = n; S.op_ws = (int64_t)M.inner;
+        S.nprob = 1;
+        SmallProblem& q = S.prob[0];
+        q.inj = x; q.ld_inj = ldx; q.inj_lo = (uint32_t)k; q.inj_hi = (uint32_t)(k + n);
+        q.res_lo = 0; q.res_hi = (uint32_t)k;
+        q.out_p = parts; q.ld_p = batch; q.op_p = k * batch;
+        q.out_z = (flags & LAPLEX_SAVE_SCANS) ? P.z : nullptr; q.op_z = (int64_t)(M.inner / sizeof(float));
+        LAPLEX_HIP(launch_small(S, r, st));
+    } else {
+        for (int64_t q = 0; q < r; ++q)
+            LAPLEX_CHECK(laplex_apply(a + q * k, k, b + q * n, n, x, ldx, batch, parts + q * k * batch, batch,
+                                      base + (size_t)q * M.inner, M.inner, flags, stream));
+    }
     LAPLEX_HIP(launch_mix_combine(parts, w, r, k, batch, y, ldy, st));
     return LAPLEX_OK;
 }
@@ -764,6 +780,50 @@ int laplex_mix_apply_backward(const float* a, const float* b, const float* w, in
     float* gxq = reinterpret_cast<float*>(base + M.off_gxq);
     float* partial = reinterpret_cast<float*>(base + M.off_partial);
     const bool saved = (flags & LAPLEX_SAVE_SCANS) != 0;      // the forward left every operator's product and scans
+    if (k + n <= kSmallMax) {      // every operator in the same launches
+        const Layout L = make_layout(k + n, k, batch);
+        const Plan P = plan_of(L, base);
+        const int64_t op_f = (int64_t)(M.inner / sizeof(float));
+        float* zg = reinterpret_cast<float*>(base + L.off_small);
+        bool have_plan = (flags & LAPLEX_REUSE_PLAN) != 0;
+        bool have_z = saved;
+        if (gw && !saved) {        // the weights' gradients need the operators' own products (and leave the strict scans)
+            SmallArgs S = small_args(a, k, b, n, 1.0f, P, L, flags);
+            S.op_a = k; S.op_b = n; S.op_ws = (int64_t)M.inner;
+            S.nprob = 1;
+            SmallProblem& q = S.prob[0];
+            q.inj = x; q.ld_inj = ldx; q.inj_lo = (uint32_t)k; q.inj_hi = (uint32_t)(k + n);
+            q.res_lo = 0; q.res_hi = (uint32_t)k;
+            q.out_p = parts; q.ld_p = batch; q.op_p = k * batch;
+            q.out_z = P.z; q.op_z = op_f;
+            LAPLEX_HIP(launch_small(S, r, st));
+            have_plan = true; have_z = true;
+        }
+        if (gx || ga || gb) {
+            LAPLEX_HIP(launch_scale_ops(gy, ldgy, w, r, k, batch, gyq, st));      // gyq[q] = w_q gy
+            SmallArgs S = small_args(a, k, b, n, 1.0f, P, L, have_plan ? (flags | LAPLEX_REUSE_PLAN) : flags);
+            S.op_a = k; S.op_b = n; S.op_ws = (int64_t)M.inner;
+            if (ga && !have_z) {
+                SmallProblem& q = S.prob[S.nprob++];
+                q.inj = x; q.ld_inj = ldx; q.inj_lo = (uint32_t)k; q.inj_hi = (uint32_t)(k + n);
+                q.res_lo = 0; q.res_hi = (uint32_t)k;
+                q.out_z = P.z; q.op_z = op_f;
+            }
+            if (gx || gb) {
+                SmallProblem& q = S.prob[S.nprob++];
+                q.inj = gyq; q.ld_inj = batch; q.op_inj = k * batch; q.inj_lo = 0; q.inj_hi = (uint32_t)k;
+                q.res_lo = (uint32_t)k; q.res_hi = (uint32_t)(k + n);
+                q.out_p = gx ? gxq : nullptr; q.ld_p = batch; q.op_p = n * batch;
+                q.out_z = gb ? zg : nullptr; q.op_z = op_f;
+            }
+            if (S.nprob > 0) LAPLEX_HIP(launch_small(S, r, st));
+            if (ga) LAPLEX_HIP(launch_rowdot_ops(gyq, batch, k * batch, P.z, batch, op_f, k, batch, ga, k, r, st));
+            if (gb) LAPLEX_HIP(launch_rowdot_ops(x, ldx, 0, zg, batch, op_f, n, batch, gb, n, r, st));
+            if (gx) LAPLEX_HIP(launch_mix_combine(gxq, nullptr, r, n, batch, gx, ldgx, st));
+        }
+        if (gw) LAPLEX_HIP(launch_dot_ops(gy, ldgy, parts, r, k, batch, partial, gw, st));
+        return LAPLEX_OK;
+    }
     for (int64_t q = 0; q < r; ++q) {
         char* wq = base + (size_t)q * M.inner;
         float* part = parts + q * k * batch;

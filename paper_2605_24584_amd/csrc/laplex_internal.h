@@ -304,6 +304,13 @@ hipError_t launch_accumulate(const float* src, int64_t rows, int64_t batch, floa
                              hipStream_t st);
 hipError_t launch_dot(const float* u, int64_t ldu, const float* v, int64_t rows, int64_t batch,
                       float* partial, float* out, hipStream_t st);
+// for r operators at once: scale_ops: dst[q] (contiguous) = w[q] * src;  dot_ops: out[q] = sum u .* v[q] (v[q] contiguous,
+// one after the other), partial = r * kDotGroups floats of scratch
+constexpr int kDotGroups = 64;
+hipError_t launch_scale_ops(const float* src, int64_t ld_src, const float* w, int64_t r, int64_t rows, int64_t batch,
+                            float* dst, hipStream_t st);
+hipError_t launch_dot_ops(const float* u, int64_t ldu, const float* v, int64_t r, int64_t rows, int64_t batch,
+                          float* partial, float* out, hipStream_t st);
 
 // Weighted Gram matrix (gram_kernels.hip).  launch_wgram_prefix: W[id] (fp64) = sum of d over the middle anchors
 // (ids >= k) that precede Gram anchor `id` in the merged order; tile_sum: scratch, wgram_tiles(N) doubles.
@@ -315,6 +322,9 @@ hipError_t launch_wgram_fill(const float* a, const float* U, const float* V, con
                              float* M, int64_t ldm, hipStream_t st);
 
 // out[r] = sum_t u[r*ldu+t] * v[r*ldv+t]
+// ... for `operators` problems at once, their matrices op_u / op_v / op_out elements apart
+hipError_t launch_rowdot_ops(const float* u, int64_t ldu, int64_t op_u, const float* v, int64_t ldv, int64_t op_v,
+                             int64_t rows, int64_t batch, float* out, int64_t op_out, int64_t operators, hipStream_t st);
 hipError_t launch_rowdot(const float* u, int64_t ldu, const float* v, int64_t ldv,
                          int64_t rows, int64_t batch, float* out, hipStream_t st);
 

@@ -114,7 +114,7 @@ k_scale(float* __restrict__ p, int64_t count, float f)
 // LAPLEX^(r) = sum_q w_q L(a_q, b_q)  (Sec. 7 "Learned anchor geometry in neural heads"): r plain operators
 // with independent anchor pairs and scalar mixing weights w (device memory: they are trained).  The products
 // of the r operators are combined in a fixed order; the gradient of w_q is the inner product <gy, L_q x>.
-// y[i][t] = sum_q w[q] parts[q][i][t]    (parts: r contiguous (rows, batch) matrices)
+// y[i][t] = sum_q w[q] parts[q][i][t]    (parts: r contiguous (rows, batch) matrices; w == null: plain sum)
 __global__ void __launch_bounds__(256)
 k_mix_combine(const float* __restrict__ parts, const float* __restrict__ w, int64_t r, int64_t rows, int64_t batch,
               float* __restrict__ y, int64_t ldy)
@@ -123,7 +123,7 @@ k_mix_combine(const float* __restrict__ parts, const float* __restrict__ w, int6
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += stride) {
         float acc = 0.0f;
-        for (int64_t q = 0; q < r; ++q) acc += w[q] * parts[q * total + e];
+        for (int64_t q = 0; q < r; ++q) acc += (w ? w[q] : 1.0f) * parts[q * total + e];
         y[(e / batch) * ldy + (e % batch)] = acc;
     }
 }
@@ -170,6 +170,50 @@ k_dot_partial(const float* __restrict__ u, int64_t ldu, const float* __restrict_
         __syncthreads();
     }
     if (threadIdx.x == 0) partial[blockIdx.x] = red[0];
+}
+
+// dst[q][i][t] = w[q] * src[i*ld_src + t] for the r operators (blockIdx.y)
+__global__ void __launch_bounds__(256)
+k_scale_ops(const float* __restrict__ src, int64_t ld_src, const float* __restrict__ w, int64_t rows, int64_t batch,
+            float* __restrict__ dst)
+{
+    const float f = w[blockIdx.y];
+    const int64_t total = rows * batch;
+    float* out = dst + (int64_t)blockIdx.y * total;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += stride)
+        out[e] = f * src[(e / batch) * ld_src + (e % batch)];
+}
+
+// partial[q][g] = workgroup g's share of sum u .* v[q]; then out[q] = sum_g partial[q][g]   (blockIdx.y = q)
+__global__ void __launch_bounds__(256)
+k_dot_ops_partial(const float* __restrict__ u, int64_t ldu, const float* __restrict__ v, int64_t rows, int64_t batch,
+                  float* __restrict__ partial)
+{
+    __shared__ float red[256];
+    const int64_t total = rows * batch;
+    const float* vq = v + (int64_t)blockIdx.y * total;
+    const int64_t per = (total + gridDim.x - 1) / gridDim.x;
+    const int64_t lo = per * blockIdx.x, hi = lo + per < total ? lo + per : total;
+    float acc = 0.0f;
+    for (int64_t e = lo + threadIdx.x; e < hi; e += 256) acc += u[(e / batch) * ldu + (e % batch)] * vq[e];
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    for (int s = 128; s >= 1; s >>= 1) {
+        if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) partial[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = red[0];
+}
+
+__global__ void __launch_bounds__(64)
+k_dot_ops_final(const float* __restrict__ partial, int groups, float* __restrict__ out)
+{
+    float acc = 0.0f;
+    for (int g = threadIdx.x; g < groups; g += 64) acc += partial[(int64_t)blockIdx.x * groups + g];
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) acc += __shfl_xor(acc, m);
+    if (threadIdx.x == 0) out[blockIdx.x] = acc;
 }
 
 inline unsigned flat_grid(int64_t total)
@@ -261,6 +305,27 @@ hipError_t launch_dot(const float* u, int64_t ldu, const float* v, int64_t rows,
     if (groups > kTauPartials) groups = kTauPartials;
     LAPLEX_TIMED("mix", st, hipLaunchKernelGGL(k_dot_partial, dim3((unsigned)groups), dim3(256), 0, st, u, ldu, v, rows, batch, partial));
     LAPLEX_TIMED("mix", st, hipLaunchKernelGGL(k_tau_final, dim3(1), dim3(256), 0, st, (const float*)partial, (int)groups, out));
+    return hipGetLastError();
+}
+
+hipError_t launch_scale_ops(const float* src, int64_t ld_src, const float* w, int64_t r, int64_t rows, int64_t batch,
+                            float* dst, hipStream_t st)
+{
+    unsigned g = flat_grid(rows * batch);
+    if (g > 1024) g = 1024;
+    LAPLEX_TIMED("mix", st, hipLaunchKernelGGL(k_scale_ops, dim3(g, (unsigned)r), dim3(256), 0, st, src, ld_src, w, rows, batch, dst));
+    return hipGetLastError();
+}
+
+hipError_t launch_dot_ops(const float* u, int64_t ldu, const float* v, int64_t r, int64_t rows, int64_t batch,
+                          float* partial, float* out, hipStream_t st)
+{
+    int64_t groups = (rows * batch + 2047) / 2048;
+    if (groups < 1) groups = 1;
+    if (groups > kDotGroups) groups = kDotGroups;
+    LAPLEX_TIMED("mix", st, hipLaunchKernelGGL(k_dot_ops_partial, dim3((unsigned)groups, (unsigned)r), dim3(256), 0, st,
+                                               u, ldu, v, rows, batch, partial));
+    LAPLEX_TIMED("mix", st, hipLaunchKernelGGL(k_dot_ops_final, dim3((unsigned)r), dim3(64), 0, st, (const float*)partial, (int)groups, out));
     return hipGetLastError();
 }
 

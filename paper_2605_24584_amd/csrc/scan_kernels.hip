@@ -1689,11 +1689,13 @@ k_sum_slabs(const float* __restrict__ partial, int64_t rows, int slabs, float* _
     }
 }
 
-// out[r] = sum_t u[r, t] * v[r, t]: one wavefront per row, fixed summation order
+// out[r] = sum_t u[r, t] * v[r, t]: one wavefront per row, fixed summation order; blockIdx.y counts operators,
+// whose matrices lie op_u / op_v / op_out elements apart
 __global__ void __launch_bounds__(256)
-k_rowdot(const float* __restrict__ u, int64_t ldu, const float* __restrict__ v, int64_t ldv,
-         int64_t rows, int64_t batch, float* __restrict__ out)
+k_rowdot(const float* __restrict__ u, int64_t ldu, int64_t op_u, const float* __restrict__ v, int64_t ldv, int64_t op_v,
+         int64_t rows, int64_t batch, float* __restrict__ out, int64_t op_out)
 {
+    u += (int64_t)blockIdx.y * op_u; v += (int64_t)blockIdx.y * op_v; out += (int64_t)blockIdx.y * op_out;
     const int lane = threadIdx.x & 63;
     const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
@@ -1708,9 +1710,10 @@ k_rowdot(const float* __restrict__ u, int64_t ldu, const float* __restrict__ v, 
 
 // the same for a narrow batch: one thread per row
 __global__ void __launch_bounds__(256)
-k_rowdot_narrow(const float* __restrict__ u, int64_t ldu, const float* __restrict__ v, int64_t ldv,
-                int64_t rows, int64_t batch, float* __restrict__ out)
+k_rowdot_narrow(const float* __restrict__ u, int64_t ldu, int64_t op_u, const float* __restrict__ v, int64_t ldv, int64_t op_v,
+                int64_t rows, int64_t batch, float* __restrict__ out, int64_t op_out)
 {
+    u += (int64_t)blockIdx.y * op_u; v += (int64_t)blockIdx.y * op_v; out += (int64_t)blockIdx.y * op_out;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < rows; r += stride) {
         float s = 0.0f;
@@ -1841,18 +1844,26 @@ hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStrea
     return hipGetLastError();
 }
 
-hipError_t launch_rowdot(const float* u, int64_t ldu, const float* v, int64_t ldv,
-                         int64_t rows, int64_t batch, float* out, hipStream_t st)
+hipError_t launch_rowdot_ops(const float* u, int64_t ldu, int64_t op_u, const float* v, int64_t ldv, int64_t op_v,
+                             int64_t rows, int64_t batch, float* out, int64_t op_out, int64_t operators, hipStream_t st)
 {
-    if (rows <= 0) return hipSuccess;
+    if (rows <= 0 || operators <= 0) return hipSuccess;
     if (batch <= 8) {
         int64_t g = (rows + 255) / 256; if (g > 65536) g = 65536;
-        LAPLEX_TIMED("rowdot", st, hipLaunchKernelGGL(k_rowdot_narrow, dim3((unsigned)g), dim3(256), 0, st, u, ldu, v, ldv, rows, batch, out));
+        LAPLEX_TIMED("rowdot", st, hipLaunchKernelGGL(k_rowdot_narrow, dim3((unsigned)g, (unsigned)operators), dim3(256), 0, st,
+                                                      u, ldu, op_u, v, ldv, op_v, rows, batch, out, op_out));
         return hipGetLastError();
     }
     int64_t gsz = (rows + 3) / 4; if (gsz > 65536) gsz = 65536;
-    LAPLEX_TIMED("rowdot", st, hipLaunchKernelGGL(k_rowdot, dim3((unsigned)gsz), dim3(256), 0, st, u, ldu, v, ldv, rows, batch, out));
+    LAPLEX_TIMED("rowdot", st, hipLaunchKernelGGL(k_rowdot, dim3((unsigned)gsz, (unsigned)operators), dim3(256), 0, st,
+                                                  u, ldu, op_u, v, ldv, op_v, rows, batch, out, op_out));
     return hipGetLastError();
+}
+
+hipError_t launch_rowdot(const float* u, int64_t ldu, const float* v, int64_t ldv,
+                         int64_t rows, int64_t batch, float* out, hipStream_t st)
+{
+    return launch_rowdot_ops(u, ldu, 0, v, ldv, 0, rows, batch, out, 0, 1, st);
 }
 
 }  // namespace laplex

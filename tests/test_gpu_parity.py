@@ -663,7 +663,9 @@ def gpu_mix(a, b, w, x, g, flags_fwd, flags_bwd, want=(True, True, True, True), 
 
 @pytest.mark.parametrize("kind", ["uniform", "ties"])
 @pytest.mark.parametrize("r,k,n,batch", [(1, 5, 1, 2), (3, 37, 53, 3), (4, 10, 512, 64), (16, 100, 768, 128),
-                                         (2, 1000, 2048, 256), (5, 300, 2100, 1)])
+                                         (2, 1000, 2048, 256), (5, 300, 2100, 1),
+                                         # more than 8192 merged positions: one operator after the other on the large path
+                                         (2, 500, 9000, 4), (3, 40, 8200, 64)])
 def test_mix_forward_backward(oracle, kind, r, k, n, batch):
     """y = sum_q w_q L(a_q, b_q) x and the gradients (gx, ga, gb, gw), the classification-head shapes
     (classes x features) among them."""
