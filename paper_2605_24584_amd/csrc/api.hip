@@ -413,6 +413,17 @@ static int gram_impl(const float* a, int64_t n, const float* x, int64_t ldx, int
     char* w = static_cast<char*>(ws);
     const Plan P = plan_of(L, w);
     hipStream_t st = stream;
+    if (L.N <= kSmallMax) {        // the two-launch path for small problems
+        SmallArgs S = small_args(a, n, nullptr, 0, tau, P, L, flags);
+        S.nprob = 1;
+        SmallProblem& q = S.prob[0];
+        q.inj = x; q.ld_inj = ldx; q.inj_lo = 0; q.inj_hi = (uint32_t)n;
+        q.res_lo = 0; q.res_hi = (uint32_t)n;
+        q.out_p = y; q.ld_p = ldy;
+        q.out_z = (flags & LAPLEX_SAVE_SCANS) ? P.z : nullptr;
+        LAPLEX_HIP(launch_small(S, 1, st));
+        return LAPLEX_OK;
+    }
     LAPLEX_CHECK(build_plan(a, n, nullptr, 0, tau, L, w, flags, (flags & LAPLEX_A_SORTED) != 0, st));
     ScanProblem p = problem(P, L);
     p.inj = x; p.ld_inj = ldx; p.inj_lo = 0; p.inj_hi = (uint32_t)n;
@@ -453,6 +464,28 @@ static int gram_backward_impl(const float* a, int64_t n, const float* x, int64_t
     LAPLEX_CHECK(check_ws(ws, ws_bytes, L));
     char* w = static_cast<char*>(ws);
     const Plan P = plan_of(L, w);
+    if (L.N <= kSmallMax) {        // the two-launch path for small problems, then one row reduction
+        SmallArgs S = small_args(a, n, nullptr, 0, tau, P, L, flags);
+        float* zg = reinterpret_cast<float*>(w + L.off_small);
+        if (ga && !(flags & LAPLEX_SAVE_SCANS)) {
+            SmallProblem& q = S.prob[S.nprob++];
+            q.inj = x; q.ld_inj = ldx; q.inj_lo = 0; q.inj_hi = (uint32_t)n;
+            q.res_lo = 0; q.res_hi = (uint32_t)n;
+            q.out_z = P.z;
+        }
+        if (gx || ga) {
+            SmallProblem& q = S.prob[S.nprob++];
+            q.inj = gy; q.ld_inj = ldgy; q.inj_lo = 0; q.inj_hi = (uint32_t)n;
+            q.res_lo = 0; q.res_hi = (uint32_t)n;
+            q.out_p = gx; q.ld_p = ldgx;
+            q.out_z = ga ? zg : nullptr;
+        }
+        if (S.nprob > 0) LAPLEX_HIP(launch_small(S, 1, st));
+        if (ga) LAPLEX_HIP(launch_rowdot2(gy, ldgy, P.z, batch, x, ldx, zg, batch, n, batch, ga, st));
+        if (gtau) LAPLEX_HIP(launch_tau_grad(a, ga, n, nullptr, nullptr, 0, reinterpret_cast<float*>(w + L.off_scratch), gtau, st));
+        if (tau != 1.0f && ga) LAPLEX_HIP(launch_scale(ga, n, tau, st));
+        return LAPLEX_OK;
+    }
     LAPLEX_CHECK(build_plan(a, n, nullptr, 0, tau, L, w, flags, (flags & LAPLEX_A_SORTED) != 0, st));
     if (ga && !(flags & LAPLEX_SAVE_SCANS)) {
         ScanProblem p = problem(P, L);

@@ -322,6 +322,10 @@ hipError_t launch_wgram_fill(const float* a, const float* U, const float* V, con
                              float* M, int64_t ldm, hipStream_t st);
 
 // out[r] = sum_t u[r*ldu+t] * v[r*ldv+t]
+// out[r] = sum_t (u1 v1 + u2 v2)[r, t]
+hipError_t launch_rowdot2(const float* u1, int64_t ldu1, const float* v1, int64_t ldv1,
+                          const float* u2, int64_t ldu2, const float* v2, int64_t ldv2,
+                          int64_t rows, int64_t batch, float* out, hipStream_t st);
 // ... for `operators` problems at once, their matrices op_u / op_v / op_out elements apart
 hipError_t launch_rowdot_ops(const float* u, int64_t ldu, int64_t op_u, const float* v, int64_t ldv, int64_t op_v,
                              int64_t rows, int64_t batch, float* out, int64_t op_out, int64_t operators, hipStream_t st);

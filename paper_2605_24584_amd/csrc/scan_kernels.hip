@@ -1722,6 +1722,24 @@ k_rowdot_narrow(const float* __restrict__ u, int64_t ldu, int64_t op_u, const fl
     }
 }
 
+// out[r] = sum_t (u1[r, t] * v1[r, t] + u2[r, t] * v2[r, t]): one wavefront per row, fixed summation order
+__global__ void __launch_bounds__(256)
+k_rowdot2(const float* __restrict__ u1, int64_t ldu1, const float* __restrict__ v1, int64_t ldv1,
+          const float* __restrict__ u2, int64_t ldu2, const float* __restrict__ v2, int64_t ldv2,
+          int64_t rows, int64_t batch, float* __restrict__ out)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    for (int64_t r = wave; r < rows; r += nwaves) {
+        float s = 0.0f;
+        for (int64_t t = lane; t < batch; t += 64) s += u1[r * ldu1 + t] * v1[r * ldv1 + t] + u2[r * ldu2 + t] * v2[r * ldv2 + t];
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) s += __shfl_xor(s, m);
+        if (lane == 0) out[r] = s;
+    }
+}
+
 int ilog2(int v) { int l = 0; while ((1 << l) < v) ++l; return l; }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -1857,6 +1875,17 @@ hipError_t launch_rowdot_ops(const float* u, int64_t ldu, int64_t op_u, const fl
     int64_t gsz = (rows + 3) / 4; if (gsz > 65536) gsz = 65536;
     LAPLEX_TIMED("rowdot", st, hipLaunchKernelGGL(k_rowdot, dim3((unsigned)gsz, (unsigned)operators), dim3(256), 0, st,
                                                   u, ldu, op_u, v, ldv, op_v, rows, batch, out, op_out));
+    return hipGetLastError();
+}
+
+hipError_t launch_rowdot2(const float* u1, int64_t ldu1, const float* v1, int64_t ldv1,
+                          const float* u2, int64_t ldu2, const float* v2, int64_t ldv2,
+                          int64_t rows, int64_t batch, float* out, hipStream_t st)
+{
+    if (rows <= 0) return hipSuccess;
+    int64_t gsz = (rows + 3) / 4; if (gsz > 65536) gsz = 65536;
+    LAPLEX_TIMED("rowdot", st, hipLaunchKernelGGL(k_rowdot2, dim3((unsigned)gsz), dim3(256), 0, st,
+                                                  u1, ldu1, v1, ldv1, u2, ldu2, v2, ldv2, rows, batch, out));
     return hipGetLastError();
 }
 
