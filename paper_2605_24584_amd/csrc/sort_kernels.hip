@@ -262,13 +262,16 @@ k_onesweep_pass(const float* __restrict__ a, int64_t k, const float* __restrict_
 #pragma unroll
     for (int i = 0; i < KPT; ++i) {
         const uint32_t d = (key[i] >> shift) & (kRadix - 1);
-        uint64_t peers = ~0ull;
+        // lanes whose digit differs from this lane's in some bit: per bit, the ballot of the bit XOR this lane's own bit
+        uint32_t diff_lo = 0u, diff_hi = 0u;
 #pragma unroll
         for (int bit = 0; bit < kRadixBits; ++bit) {
-            const bool one = (d >> bit) & 1u;
-            const uint64_t m = __ballot(one);
-            peers &= one ? m : ~m;
+            const uint32_t mine = (uint32_t)(((int32_t)(d << (31 - bit))) >> 31);      // 0 or all ones
+            const uint64_t m = __ballot(mine != 0u);
+            diff_lo |= (uint32_t)m ^ mine;
+            diff_hi |= (uint32_t)(m >> 32) ^ mine;
         }
+        const uint64_t peers = ~(((uint64_t)diff_hi << 32) | diff_lo);
         const int leader = __ffsll((long long)peers) - 1;
         uint32_t old = 0;
         if (lane == leader) old = atomicAdd(&whist[wave][d], (uint32_t)__popcll(peers));
