@@ -36,7 +36,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-columns", type=int, default=256)
     ap.add_argument("--workload", default="projection",
-                    choices=["projection", "square", "tie_heavy", "gram", "billion", "phased", "wgram", "mix"],
+                    choices=["projection", "square", "tie_heavy", "gram", "billion", "phased", "wgram", "wgram64", "mix"],
                     help="projection is the benchmark; the others time one forward+backward step of the "
                          "other workloads (for profiles; no roofline object, no CPU baseline)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -105,6 +105,17 @@ def other_workload(args, torch, np, B, synth):
         def step():
             B.laplex_wgram(da, db, dd, m, ws, 0)
         elements = n + k
+    elif args.workload == "wgram64":
+        w = synth.weighted_gram(scale=args.scale)
+        a, b, d = w["a"], w["b"], w["d"].astype(np.float64)
+        k, n, batch = a.size, b.size, 1
+        ws = torch.empty(B.laplex_wgram_f64_workspace_bytes(k, n), dtype=torch.uint8, device="cuda")
+        da, db, dd = dev(a), dev(b), dev(d)
+        m = torch.empty(k, k, dtype=torch.float64, device="cuda")
+
+        def step():
+            B.laplex_wgram_f64(da, db, dd, m, ws, 0)
+        elements = n + k
     elif args.workload == "mix":
         w = synth.mix_head(scale=args.scale)
         a, b, x, g = w["a"], w["b"], w["x"], w["g"]
@@ -159,9 +170,10 @@ def other_workload(args, torch, np, B, synth):
     print(json.dumps({
         "metric": "LAPLEX fwd+bwd (n+k)*batch elements/s", "value": elements / (ms * 1e-3), "unit": "elements/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": w["name"] + ("" if args.scale == 1 else "/scaled"), "k": k, "n": n, "batch": batch,
-                   "pass": ("weighted Gram matrix (k x k), sort inside every step" if args.workload == "wgram"
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64" if args.workload == "wgram64" else "f32", "data": "synthetic",
+        "config": {"workload": w["name"] + ("_fp64" if args.workload == "wgram64" else "") + ("" if args.scale == 1 else "/scaled"), "k": k, "n": n, "batch": batch,
+                   "pass": ("weighted Gram matrix (k x k), sort inside every step" if args.workload.startswith("wgram")
                             else "forward+backward, sort inside every step"), "workspace_bytes": ws.numel(),
                    "device_bytes_peak": torch.cuda.max_memory_allocated()},
     }), flush=True)

@@ -260,6 +260,19 @@ int laplex_wgram(const float* a, int64_t k, const float* b, int64_t n, const flo
                  float* m, int64_t ldm, void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream);
 
 /*
+ * The weighted Gram matrix in fp64 (App. "Density model": the Gram matrices run in
+ * fp64 through the same scan): fp32 anchors a[k], b[n]; fp64 weights d[n] and fp64
+ * result m (k x k, rows ldm doubles apart; d and m 8-byte aligned).  The sorted
+ * order and the ties are those of the fp32 anchors; every decay, product and sum is
+ * formed in fp64.  Same flags, limits and plan as laplex_wgram; the workspace is
+ * laplex_wgram_f64_workspace_bytes(k, n).
+ */
+int laplex_wgram_f64_workspace_bytes(int64_t k, int64_t n, size_t* out /* host */);
+
+int laplex_wgram_f64(const float* a, int64_t k, const float* b, int64_t n, const double* d,
+                     double* m, int64_t ldm, void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream);
+
+/*
  * Verification hook: copy the first `count` sorted ids of the plan in `ws`
  * (count = k + n for the apply form, n for the Gram form) to the device buffer
  * perm_out.  id < k names output anchor a[id]; id >= k names input b[id-k].

@@ -37,6 +37,7 @@ EXPORTS = (
     "laplex_apply_tau", "laplex_apply_backward_tau", "laplex_gram_tau", "laplex_gram_backward_tau",
     "laplex_wgram_workspace_bytes", "laplex_wgram",
     "laplex_mix_workspace_bytes", "laplex_mix_apply", "laplex_mix_apply_backward",
+    "laplex_wgram_f64_workspace_bytes", "laplex_wgram_f64",
 )
 
 _lib = None
@@ -85,6 +86,8 @@ def lib() -> ctypes.CDLL:
         L.laplex_gram_backward_tau.argtypes = [_P, _I, _F, _P, _I, _P, _I, _I, _P, _I, _P, _P, _P, _Z, _U, _P]
         L.laplex_wgram_workspace_bytes.argtypes = [_I, _I, ctypes.POINTER(ctypes.c_size_t)]
         L.laplex_wgram.argtypes = [_P, _I, _P, _I, _P, _P, _I, _P, _Z, _U, _P]
+        L.laplex_wgram_f64_workspace_bytes.argtypes = [_I, _I, ctypes.POINTER(ctypes.c_size_t)]
+        L.laplex_wgram_f64.argtypes = [_P, _I, _P, _I, _P, _P, _I, _P, _Z, _U, _P]
         L.laplex_mix_workspace_bytes.argtypes = [_I, _I, _I, _I, ctypes.POINTER(ctypes.c_size_t)]
         L.laplex_mix_apply.argtypes = [_P, _P, _P, _I, _I, _I, _P, _I, _I, _P, _I, _P, _Z, _U, _P]
         L.laplex_mix_apply_backward.argtypes = [_P, _P, _P, _I, _I, _I, _P, _I, _P, _I, _I, _P, _I, _P, _P, _P,
@@ -259,3 +262,15 @@ def laplex_mix_apply_backward(a, b, w, x, gy, gx, ga, gb, gw, ws, flags: int = 0
     _check(lib().laplex_mix_apply_backward(
         _ptr(a), _ptr(b), _ptr(w), a.shape[0], a.shape[1], b.shape[1], _ptr(x), _ld(x), _ptr(gy), _ld(gy), _batch(gy),
         _ptr(gx), _ld(gx), _ptr(ga), _ptr(gb), _ptr(gw), _ptr(ws), ws.numel(), flags, _stream(stream)))
+
+
+def laplex_wgram_f64_workspace_bytes(k: int, n: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().laplex_wgram_f64_workspace_bytes(k, n, ctypes.byref(out)))
+    return out.value
+
+
+def laplex_wgram_f64(a, b, d, m, ws, flags: int = 0, stream=None) -> None:
+    """m (k, k) fp64 <- A diag(d) A^T, fp32 anchors, fp64 weights and arithmetic."""
+    _check(lib().laplex_wgram_f64(_ptr(a), a.numel(), _ptr(b), b.numel(), _ptr(d), _ptr(m), _ld(m),
+                                  _ptr(ws), ws.numel(), flags, _stream(stream)))

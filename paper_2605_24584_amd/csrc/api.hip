@@ -189,22 +189,23 @@ int check_phased_sizes(int64_t k, int64_t n, int64_t batch)
 }
 
 // ----------------------------------------------------------------------------
-// Weighted Gram matrix (gram_kernels.hip).  Workspace: the plain workspace for batch 1 with one saved
-// scan value per Gram anchor (the plan of the doubled anchors at its front; the backward scan V in the
-// saved-scan region), then U f32[k], W f64[k] and one f64 per tile of the prefix sum.
+// Weighted Gram matrix (gram_kernels.hip).  Workspace: the plain workspace for batch 1 (the plan of the
+// doubled anchors at its front), then U, V, W f64[k] each and five f64 per tile of the scan.  The fp32 and
+// the fp64 entry point share it.
 // ----------------------------------------------------------------------------
-struct WgramLayout {
-    size_t inner = 0, off_u = 0, off_w = 0, off_tile = 0, total = 0;
+struct Wgram64Layout {
+    size_t inner = 0, off_u = 0, off_v = 0, off_w = 0, off_summ = 0, total = 0;
 };
 
-WgramLayout wgram_layout(int64_t k, int64_t n)
+Wgram64Layout wgram64_layout(int64_t k, int64_t n)
 {
-    WgramLayout G;
+    Wgram64Layout G;
     G.inner = make_layout(k + n, k, 1).total;
     size_t o = align_up(G.inner);
-    G.off_u = o;    o = align_up(o + sizeof(float) * (size_t)k);
+    G.off_u = o;    o = align_up(o + sizeof(double) * (size_t)k);
+    G.off_v = o;    o = align_up(o + sizeof(double) * (size_t)k);
     G.off_w = o;    o = align_up(o + sizeof(double) * (size_t)k);
-    G.off_tile = o; o = align_up(o + sizeof(double) * (size_t)wgram_tiles(k + n));
+    G.off_summ = o; o = align_up(o + sizeof(double) * 5 * (size_t)wgram_tiles(k + n));
     G.total = o;
     return G;
 }
@@ -674,7 +675,7 @@ int laplex_wgram_workspace_bytes(int64_t k, int64_t n, size_t* out)
 {
     if (!out) return LAPLEX_ERR_NULL;
     LAPLEX_CHECK(check_wgram_sizes(k, n));
-    *out = wgram_layout(k, n).total;
+    *out = wgram64_layout(k, n).total;
     return LAPLEX_OK;
 }
 
@@ -686,7 +687,7 @@ int laplex_wgram(const float* a, int64_t k, const float* b, int64_t n, const flo
     LAPLEX_CHECK(check_wgram_sizes(k, n));
     LAPLEX_CHECK(check_vector(a, k, true));
     LAPLEX_CHECK(check_vector(b, n, true));
-    LAPLEX_CHECK(check_vector(d, n, true));
+    LAPLEX_CHECK(check_vector(d, k > 0 ? n : 0, true));
     LAPLEX_CHECK(check_matrix(m, k, ldm, k, true));
     if (k == 0) return LAPLEX_OK;
     hipStream_t st = stream;
@@ -694,29 +695,65 @@ int laplex_wgram(const float* a, int64_t k, const float* b, int64_t n, const flo
         LAPLEX_HIP(launch_fill(m, k, k, ldm, 0.0f, st));
         return LAPLEX_OK;
     }
-    const WgramLayout G = wgram_layout(k, n);
+    const Wgram64Layout G = wgram64_layout(k, n);
     if (!ws) return LAPLEX_ERR_NULL;
     if (misaligned(ws, 256)) return LAPLEX_ERR_ALIGN;
     if (ws_bytes < G.total) return LAPLEX_ERR_WORKSPACE;
     char* w = static_cast<char*>(ws);
     const Layout L = make_layout(k + n, k, 1);
     const Plan P = plan_of(L, w);
-    float* U = reinterpret_cast<float*>(w + G.off_u);
-    float* V = P.z;
-    double* W = reinterpret_cast<double*>(w + G.off_w);
-    double* tile_sum = reinterpret_cast<double*>(w + G.off_tile);
     // the plan of the doubled anchors: its decays are exp(-2 gap), the kernel K = L(2a) of the theorem
     const bool sorted = (flags & LAPLEX_A_SORTED) && (flags & LAPLEX_B_SORTED);
     LAPLEX_CHECK(build_plan(a, k, b, n, 2.0f, L, w, flags, sorted, st));
-    ScanProblem p = problem(P, L);
-    p.inj = d; p.ld_inj = 1; p.inj_lo = (uint32_t)k; p.inj_hi = (uint32_t)(k + n);
-    p.res_lo = 0; p.res_hi = (uint32_t)k;
-    p.out_p = U; p.ld_p = 1; p.out_z = V; p.one_sided = true;
-    p.stage = P.stage;
-    p.tag = "wgram";
-    LAPLEX_HIP(launch_scan(p, L, w, st));
-    LAPLEX_HIP(launch_wgram_prefix(P.ids, d, k, k + n, tile_sum, W, st));
-    LAPLEX_HIP(launch_wgram_fill(a, U, V, W, k, m, ldm, st));
+    LAPLEX_HIP(launch_wgram_f32(P.ids, P.pk, a, d, k, k + n, reinterpret_cast<double*>(w + G.off_summ),
+                                reinterpret_cast<double*>(w + G.off_u), reinterpret_cast<double*>(w + G.off_v),
+                                reinterpret_cast<double*>(w + G.off_w), m, ldm, st));
+    return LAPLEX_OK;
+}
+
+int laplex_wgram_f64_workspace_bytes(int64_t k, int64_t n, size_t* out)
+{
+    if (!out) return LAPLEX_ERR_NULL;
+    LAPLEX_CHECK(check_wgram_sizes(k, n));
+    *out = wgram64_layout(k, n).total;
+    return LAPLEX_OK;
+}
+
+int laplex_wgram_f64(const float* a, int64_t k, const float* b, int64_t n, const double* d,
+                     double* m, int64_t ldm, void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream)
+{
+    const uint32_t known = LAPLEX_A_SORTED | LAPLEX_B_SORTED | LAPLEX_REUSE_PLAN;
+    if (flags & ~known) return LAPLEX_ERR_FLAGS;
+    LAPLEX_CHECK(check_wgram_sizes(k, n));
+    LAPLEX_CHECK(check_vector(a, k, true));
+    LAPLEX_CHECK(check_vector(b, n, true));
+    if (n > 0 && k > 0) {
+        if (!d) return LAPLEX_ERR_NULL;
+        if (misaligned(d, 8)) return LAPLEX_ERR_ALIGN;
+    }
+    if (k > 0) {
+        if (!m) return LAPLEX_ERR_NULL;
+        if (misaligned(m, 8)) return LAPLEX_ERR_ALIGN;
+        if (ldm < k) return LAPLEX_ERR_LD;
+    }
+    if (k == 0) return LAPLEX_OK;
+    hipStream_t st = stream;
+    if (n == 0) {        // nothing is summed: a zero matrix (as fp32 pairs of zeros)
+        LAPLEX_HIP(launch_fill(reinterpret_cast<float*>(m), k, 2 * k, 2 * ldm, 0.0f, st));
+        return LAPLEX_OK;
+    }
+    const Wgram64Layout G = wgram64_layout(k, n);
+    if (!ws) return LAPLEX_ERR_NULL;
+    if (misaligned(ws, 256)) return LAPLEX_ERR_ALIGN;
+    if (ws_bytes < G.total) return LAPLEX_ERR_WORKSPACE;
+    char* w = static_cast<char*>(ws);
+    const Layout L = make_layout(k + n, k, 1);
+    const Plan P = plan_of(L, w);
+    const bool sorted = (flags & LAPLEX_A_SORTED) && (flags & LAPLEX_B_SORTED);
+    LAPLEX_CHECK(build_plan(a, k, b, n, 2.0f, L, w, flags, sorted, st));
+    LAPLEX_HIP(launch_wgram_f64(P.ids, P.pk, a, d, k, k + n, reinterpret_cast<double*>(w + G.off_summ),
+                                reinterpret_cast<double*>(w + G.off_u), reinterpret_cast<double*>(w + G.off_v),
+                                reinterpret_cast<double*>(w + G.off_w), m, ldm, st));
     return LAPLEX_OK;
 }
 

@@ -238,8 +238,7 @@ hipError_t launch_copy_u32(const uint32_t* src, uint32_t* dst, int64_t count, hi
 //   out_red[id-res_lo] = sum_t ( w[(id-res_lo)*ld_w + t] * Z
 //                              + (zs ? v * zs[(id-res_lo)*batch + t] : 0) )
 // Any of out_p / out_z / out_red may be null; strict scans run only if out_z or
-// out_red is wanted.  one_sided: the two inclusive scans are emitted separately instead,
-//   out_p[...] = F (everything at or before the position), out_z[...] = R (at or after it).
+// out_red is wanted.
 struct ScanProblem {
     const uint32_t* ids; const float* dh; const float* pk; int64_t N;
     const float* inj; int64_t ld_inj; uint32_t inj_lo, inj_hi;
@@ -250,7 +249,6 @@ struct ScanProblem {
     int64_t batch;
     float* stage;          // narrow batches: the reduce writes the injected rows here in sorted order, the downsweep reads them back
     const float* wstage;   // narrow batches: the weights w in sorted order (an earlier problem's stage), or null
-    bool one_sided = false;  // out_p <- the forward inclusive scan alone, out_z <- the backward inclusive scan alone (both required)
     const char* tag;   // names the timing families: scan_reduce.<tag>, scan_spine.<tag>, scan_down.<tag>
 };
 hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStream_t st);
@@ -312,14 +310,14 @@ hipError_t launch_scale_ops(const float* src, int64_t ld_src, const float* w, in
 hipError_t launch_dot_ops(const float* u, int64_t ldu, const float* v, int64_t r, int64_t rows, int64_t batch,
                           float* partial, float* out, hipStream_t st);
 
-// Weighted Gram matrix (gram_kernels.hip).  launch_wgram_prefix: W[id] (fp64) = sum of d over the middle anchors
-// (ids >= k) that precede Gram anchor `id` in the merged order; tile_sum: scratch, wgram_tiles(N) doubles.
-// launch_wgram_fill: M[i*ldm + j] = exp(-|a_i - a_j|) (U[lo] + (W[hi] - W[lo]) + V[hi]), lo / hi the pair in sorted order.
+// Weighted Gram matrix (gram_kernels.hip): U, V, W (fp64, k each) by a scan of its own over the plan (ids, pk) of the
+// doubled anchors, then the fill  M[i*ldm + j] = exp(-|a_i - a_j|) (U[lo] + (W[hi] - W[lo]) + V[hi]),  lo / hi the pair
+// in sorted order.  summ: 5 * wgram_tiles(N) doubles of scratch.  _f32: fp32 weights and result, _f64: fp64.
 int64_t wgram_tiles(int64_t N);
-hipError_t launch_wgram_prefix(const uint32_t* ids, const float* d, int64_t k, int64_t N,
-                               double* tile_sum, double* W, hipStream_t st);
-hipError_t launch_wgram_fill(const float* a, const float* U, const float* V, const double* W, int64_t k,
-                             float* M, int64_t ldm, hipStream_t st);
+hipError_t launch_wgram_f32(const uint32_t* ids, const float* pk, const float* a, const float* d, int64_t k, int64_t N,
+                            double* summ, double* U, double* V, double* W, float* M, int64_t ldm, hipStream_t st);
+hipError_t launch_wgram_f64(const uint32_t* ids, const float* pk, const float* a, const double* d, int64_t k, int64_t N,
+                            double* summ, double* U, double* V, double* W, double* M, int64_t ldm, hipStream_t st);
 
 // out[r] = sum_t u[r*ldu+t] * v[r*ldv+t]
 // out[r] = sum_t (u1 v1 + u2 v2)[r, t]

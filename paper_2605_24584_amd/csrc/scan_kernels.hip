@@ -76,7 +76,6 @@ struct ScanArgs {
     // list_inj is written by the metadata pass; list_both by the metadata pass if it runs, else by the reduce
     int reduce_from_list, down_from_list;
     int few_inj_ok, few_res_ok;   // the block flags kFlagFewInj / kFlagFewRes may be set
-    int one_sided;                // out_p receives the forward scan alone, out_z the backward scan alone (both inclusive)
 };
 
 constexpr int kFlagInj = 1, kFlagRes = 2;
@@ -1259,8 +1258,8 @@ k_scan_down(const ScanArgs A)
         for (int e = 0; e < VEC; ++e) {
             G[e] = h ? T.dh[i + 1] * R[e] : G[e];
             R[e] = (h ? G[e] : R[e]) + v[i][e];
-            P[e] = A.one_sided ? Ff[i][e] : Ff[i][e] + R[e] - v[i][e];
-            Z[e] = A.one_sided ? R[e] : G[e] - Efi[e];
+            P[e] = Ff[i][e] + R[e] - v[i][e];
+            Z[e] = G[e] - Efi[e];
         }
         const bool is_res = T.id[i] >= A.res_lo && T.id[i] < A.res_hi;
         const int64_t rr = (int64_t)T.id[i] - (int64_t)A.res_lo;
@@ -1382,8 +1381,8 @@ k_scan_down_sparse(const ScanArgs A)
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
             const float Fj = kf * Fin[e], Rj = kb * Rin[e];
-            P[e] = A.one_sided ? Fj : Fj + Rj;
-            Z[e] = A.one_sided ? Rj : (seen_b ? Rj : Gin[e]) - (seen_f ? Fj : Ein[e]);
+            P[e] = Fj + Rj;
+            Z[e] = (seen_b ? Rj : Gin[e]) - (seen_f ? Fj : Ein[e]);
         }
         if (VEC == 4 && sources) {
 #pragma unroll
@@ -1804,7 +1803,7 @@ hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStrea
 {
     const bool strict = p.out_z != nullptr || p.out_red != nullptr;
     // 128-bit lanes need every row start of every matrix touched to be 16-byte aligned
-    bool v4 = p.batch % 4 == 0 && p.batch >= 4 && !p.one_sided;    // the one-sided emission exists in the 1-column kernels
+    bool v4 = p.batch % 4 == 0 && p.batch >= 4;
     v4 = v4 && aligned16(p.inj) && p.ld_inj % 4 == 0;
     if (p.out_p) v4 = v4 && aligned16(p.out_p) && p.ld_p % 4 == 0;
     if (p.out_z) v4 = v4 && aligned16(p.out_z);
@@ -1817,7 +1816,7 @@ hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStrea
     A.res_lo = p.res_lo; A.res_hi = p.res_hi;
     A.out_p = p.out_p; A.ld_p = p.ld_p; A.out_z = p.out_z;
     A.out_red = p.out_red; A.w = p.w; A.ld_w = p.ld_w; A.zs = p.zs;
-    A.stage = p.stage; A.wstage = p.wstage; A.one_sided = p.one_sided ? 1 : 0;
+    A.stage = p.stage; A.wstage = p.wstage;
     A.batch = p.batch; A.bpad = L.bpad;
     A.bv = g.bv; A.bv_log2 = ilog2(g.bv); A.rv = g.rv; A.tile_rows = g.tile_rows; A.slabs = g.slabs;
     A.chunk_tiles = g.chunk_tiles;

@@ -706,3 +706,27 @@ def test_mix_subsets_and_empty(oracle):
     y, grads = gpu_mix(e, np.zeros((0, n), dtype=np.float32), np.zeros(0, dtype=np.float32), x, g, 0, 0,
                        want=(True, False, False, False))
     assert np.all(y == 0) and np.all(grads[0] == 0)
+
+
+@pytest.mark.parametrize("weights", ["signed", "positive"])
+@pytest.mark.parametrize("kind", ["uniform", "ties", "all_equal", "huge_gaps", "clustered"])
+@pytest.mark.parametrize("k,n", [(1, 1), (5, 1), (37, 53), (100, 9000), (1024, 40000), (333, 70001), (3, 150000)])
+def test_weighted_gram_matrix_fp64(oracle, weights, kind, k, n):
+    """The fp64 instantiation: fp32 anchors, fp64 weights and arithmetic.  Tolerance 1e-12 T + 1e-300:
+    an entry sums a few thousand non-negligible terms, each a product of at most a few hundred fp64 decays
+    (16 per thread, 8 scan levels, the tiles of the spine) with one exp each."""
+    r = np.random.default_rng(13 * k + n + len(kind))
+    a, b = anchors(kind, r, k, n)
+    d = r.normal(size=n)
+    if weights == "positive":
+        d = np.abs(d) + 0.5
+    ref, tol = (oracle.wgram_dense if k * k * n <= 3e8 else oracle.wgram_scan)(a, b, d)
+    ws = torch.empty(B.laplex_wgram_f64_workspace_bytes(k, n), dtype=torch.uint8, device="cuda")
+    m = torch.full((k, k), float("nan"), dtype=torch.float64, device="cuda")
+    B.laplex_wgram_f64(dev(a), dev(b), dev(d), m, ws, 0)
+    torch.cuda.synchronize()
+    got = m.cpu().numpy()
+    assert np.all(np.isfinite(got))
+    ratio = np.abs(got - ref) / (1e-12 * tol + 1e-300)
+    assert ratio.max() <= 1.0, f"worst |err| / (1e-12 T) = {ratio.max():.3g}"
+    assert np.array_equal(got, got.T)

@@ -22,7 +22,7 @@ def L():
 
 def test_every_declared_symbol_is_exported(L):
     header = open(os.path.join(ROOT, "include", "laplex.h")).read()
-    declared = set(re.findall(r"\b(laplex_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(laplex_[a-z0-9_]+)\s*\(", header))
     assert declared == set(B.EXPORTS)
     for name in declared:
         assert getattr(L, name) is not None
@@ -275,3 +275,21 @@ def test_mix_argument_checks(L):
     assert L.laplex_mix_apply_backward(*bgood) == B.LAPLEX_ERR_NULL                 # gw wanted, x missing
     bgood[6] = FAKE; bgood[8] = None
     assert L.laplex_mix_apply_backward(*bgood) == B.LAPLEX_ERR_NULL                 # gy missing
+
+
+def test_weighted_gram_fp64_argument_checks(L):
+    out = ctypes.c_size_t(0)
+    assert L.laplex_wgram_f64_workspace_bytes(8, 8, None) == B.LAPLEX_ERR_NULL
+    assert L.laplex_wgram_f64_workspace_bytes(1024, 1 << 20, ctypes.byref(out)) == 0 and out.value % 256 == 0
+    k, n = 8, 16
+    good = dict(a=FAKE, k=k, b=FAKE, n=n, d=FAKE, m=FAKE, ldm=k, ws=FAKE, wsb=1 << 40, flags=0)
+    call = lambda **kw: L.laplex_wgram_f64(*[{**good, **kw}[key] for key in
+                                             ("a", "k", "b", "n", "d", "m", "ldm", "ws", "wsb", "flags")], None)
+    assert call(d=None) == B.LAPLEX_ERR_NULL
+    assert call(m=None) == B.LAPLEX_ERR_NULL
+    assert call(d=FAKE + 4) == B.LAPLEX_ERR_ALIGN          # doubles: 8-byte alignment
+    assert call(m=FAKE + 4) == B.LAPLEX_ERR_ALIGN
+    assert call(ldm=k - 1) == B.LAPLEX_ERR_LD
+    assert call(flags=B.LAPLEX_SAVE_SCANS) == B.LAPLEX_ERR_FLAGS
+    assert call(wsb=64) == B.LAPLEX_ERR_WORKSPACE
+    assert call(k=0, a=None, m=None, ws=None, wsb=0) == B.LAPLEX_OK
