@@ -39,6 +39,9 @@ def parse():
                     choices=["projection", "square", "tie_heavy", "gram", "billion", "phased", "wgram", "wgram64", "mix"],
                     help="projection is the benchmark; the others time one forward+backward step of the "
                          "other workloads (for profiles; no roofline object, no CPU baseline)")
+    ap.add_argument("--paper-sweep", action="store_true",
+                    help="instead of the benchmark: the paper's runtime sweep (App. 'GPU runtime'): square apply "
+                         "n = k = 2^10 .. 2^20 at batch 8, forward and forward + backward, one JSON line per size")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="instead of the benchmark: time a plain device copy of 1 GiB (counter calibration)")
     return ap.parse_args()
@@ -179,6 +182,47 @@ def other_workload(args, torch, np, B, synth):
     }), flush=True)
 
 
+def paper_sweep(args, torch, np, B, synth):
+    """Square apply n = k = 2^10 .. 2^20, batch 8 (the sizes of the paper's runtime figure), anchors
+    ~ U(0, n / 32) (64 merged anchors per unit, as in the other workloads), x, g ~ N(0, 1).
+    Timing as in the paper's protocol: warm-ups, then the best of 3 x 30 calls, sort inside every call."""
+    dev = lambda v: torch.from_numpy(np.ascontiguousarray(v)).cuda()
+    for e in range(10, 21):
+        n = k = 1 << e
+        batch = 8
+        a = synth.uniform(synth.stream_seed(10, synth.STREAM_A) + e, k, 0.0, n / 32.0)
+        b = synth.uniform(synth.stream_seed(10, synth.STREAM_B) + e, n, 0.0, n / 32.0)
+        x = synth.normal(synth.stream_seed(10, synth.STREAM_X) + e, n * batch).reshape(n, batch)
+        g = synth.normal(synth.stream_seed(10, synth.STREAM_G) + e, k * batch).reshape(k, batch)
+        ws = torch.empty(B.laplex_workspace_bytes(k, n, batch), dtype=torch.uint8, device="cuda")
+        da, db, dx, dg = dev(a), dev(b), dev(x), dev(g)
+        y = torch.empty(k, batch, device="cuda"); gx = torch.empty(n, batch, device="cuda")
+        ga = torch.empty(k, device="cuda"); gb = torch.empty(n, device="cuda")
+
+        def fwd():
+            B.laplex_apply(da, db, dx, y, ws, 0)
+
+        def both():
+            B.laplex_apply(da, db, dx, y, ws, B.LAPLEX_SAVE_SCANS)
+            B.laplex_apply_backward(da, db, dx, dg, gx, ga, gb, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
+
+        out = {"n": n, "k": k, "batch": batch}
+        for name, fn in (("forward_ms", fwd), ("forward_backward_ms", both)):
+            for _ in range(10):
+                fn()
+            best = float("inf")
+            for _ in range(3):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(30):
+                    fn()
+                torch.cuda.synchronize()
+                best = min(best, (time.perf_counter() - t0) * 1e3 / 30)
+            out[name] = round(best, 4)
+        out["elements_per_s_fwd_bwd"] = (n + k) * batch / (out["forward_backward_ms"] * 1e-3)
+        print(json.dumps(out), flush=True)
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -208,6 +252,10 @@ def main():
         dt = (time.perf_counter() - t0) / 20
         print(json.dumps({"copy_bytes_read": 4 << 28, "copy_bytes_written": 4 << 28, "ms": dt * 1e3,
                           "GBps_read_plus_write": 2 * (4 << 28) / dt / 1e9}), flush=True)
+        return
+
+    if args.paper_sweep:
+        paper_sweep(args, torch, np, B, synth)
         return
 
     if args.workload != "projection":
