@@ -36,7 +36,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-columns", type=int, default=256)
     ap.add_argument("--workload", default="projection",
-                    choices=["projection", "square", "tie_heavy", "gram", "billion", "phased", "wgram", "wgram64", "mix"],
+                    choices=["projection", "square", "tie_heavy", "gram", "billion", "phased", "wgram", "wgram64", "mix", "square_b8"],
                     help="projection is the benchmark; the others time one forward+backward step of the "
                          "other workloads (for profiles; no roofline object, no CPU baseline)")
     ap.add_argument("--paper-sweep", action="store_true",
@@ -148,14 +148,15 @@ def other_workload(args, torch, np, B, synth):
                                            B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
         elements = (n + k) * batch
     else:
-        make = {"square": synth.square_small, "tie_heavy": synth.tie_heavy, "billion": synth.billion_square}[args.workload]
+        make = {"square": synth.square_small, "tie_heavy": synth.tie_heavy, "billion": synth.billion_square,
+                "square_b8": lambda scale: synth.paper_square(20)}[args.workload]
         w = make(scale=args.scale)
         a, b, x = w["a"], w["b"], w["x"]
         g = w.get("g", np.ones((a.size, 1), dtype=np.float32))
-        k, n, batch = a.size, b.size, 1
-        ws = torch.empty(B.laplex_workspace_bytes(k, n, 1), dtype=torch.uint8, device="cuda")
+        k, n, batch = a.size, b.size, x.shape[1]
+        ws = torch.empty(B.laplex_workspace_bytes(k, n, batch), dtype=torch.uint8, device="cuda")
         da, db, dx, dg = dev(a), dev(b), dev(x), dev(g)
-        y = torch.empty(k, 1, device="cuda"); gx = torch.empty(n, 1, device="cuda")
+        y = torch.empty(k, batch, device="cuda"); gx = torch.empty(n, batch, device="cuda")
         ga = torch.empty(k, device="cuda"); gb = torch.empty(n, device="cuda")
 
         def step():
@@ -183,17 +184,13 @@ def other_workload(args, torch, np, B, synth):
 
 
 def paper_sweep(args, torch, np, B, synth):
-    """Square apply n = k = 2^10 .. 2^20, batch 8 (the sizes of the paper's runtime figure), anchors
-    ~ U(0, n / 32) (64 merged anchors per unit, as in the other workloads), x, g ~ N(0, 1).
-    Timing as in the paper's protocol: warm-ups, then the best of 3 x 30 calls, sort inside every call."""
+    """Square apply n = k = 2^10 .. 2^20, batch 8 (the sizes of the paper's runtime figure; inputs:
+    synth.paper_square).  Timing as in the paper's protocol: warm-ups, then the best of 3 x 30 calls, sort inside every call."""
     dev = lambda v: torch.from_numpy(np.ascontiguousarray(v)).cuda()
     for e in range(10, 21):
-        n = k = 1 << e
-        batch = 8
-        a = synth.uniform(synth.stream_seed(10, synth.STREAM_A) + e, k, 0.0, n / 32.0)
-        b = synth.uniform(synth.stream_seed(10, synth.STREAM_B) + e, n, 0.0, n / 32.0)
-        x = synth.normal(synth.stream_seed(10, synth.STREAM_X) + e, n * batch).reshape(n, batch)
-        g = synth.normal(synth.stream_seed(10, synth.STREAM_G) + e, k * batch).reshape(k, batch)
+        w = synth.paper_square(e)
+        a, b, x, g = w["a"], w["b"], w["x"], w["g"]
+        k, n, batch = w["k"], w["n"], w["batch"]
         ws = torch.empty(B.laplex_workspace_bytes(k, n, batch), dtype=torch.uint8, device="cuda")
         da, db, dx, dg = dev(a), dev(b), dev(x), dev(g)
         y = torch.empty(k, batch, device="cuda"); gx = torch.empty(n, batch, device="cuda")

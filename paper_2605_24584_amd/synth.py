@@ -172,6 +172,20 @@ def mix_head(scale: int = 1, r: int = 16, batch: int = 256):
     )
 
 
+def paper_square(exp: int = 20, batch: int = 8):
+    """The shape of the paper's runtime figure (App. "GPU runtime"): square apply n = k = 2^exp at
+    batch 8; anchors ~ U(0, n / 32) (64 merged anchors per unit, as in the other workloads),
+    x, g ~ N(0, 1) (config slot 10, one set of streams per size)."""
+    n = k = 1 << exp
+    return dict(
+        name=f"paper_square_n2^{exp}_b{batch}", config=10, k=k, n=n, batch=batch,
+        a=uniform(stream_seed(10, STREAM_A) + exp, k, 0.0, n / 32.0),
+        b=uniform(stream_seed(10, STREAM_B) + exp, n, 0.0, n / 32.0),
+        x=normal(stream_seed(10, STREAM_X) + exp, n * batch).reshape(n, batch),
+        g=normal(stream_seed(10, STREAM_G) + exp, k * batch).reshape(k, batch),
+    )
+
+
 def tie_heavy(scale: int = 1):
     """n = k = 2^24, batch 1, anchors U(0, 2^18) rounded to a 1/4 grid."""
     n = k = _shrunk(1 << 24, scale)
