@@ -42,6 +42,13 @@
  * reused across batches).  After the plan comes the saved-scan region written
  * under LAPLEX_SAVE_SCANS, then scratch whose contents are undefined between
  * calls.
+ *
+ * Small problems.  With k + n <= 8192 the apply and Gram calls (and the calls
+ * built on them) run in two launches: a sort by counting ranks over the whole
+ * device and one kernel that holds the plan in LDS for the scans.  Arguments,
+ * flags, workspace and results are the same (the sorted-input promises are then
+ * not needed and not used); values differ from the large path's in rounding
+ * only.
  */
 #ifndef LAPLEX_H
 #define LAPLEX_H
