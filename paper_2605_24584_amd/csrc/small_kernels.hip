@@ -6,9 +6,10 @@
 // n = 2^17 the paper's curves are flat at the cost of the launches.)  Several operators (the r anchor
 // pairs of a sum of operators) and several slabs of batch columns are separate workgroups of a launch.
 //
-// Layout of the work: a workgroup of 16 wavefronts handles C <= 16 batch columns; wavefront w works on
-// column w % C and is the (w / C)-th of WR = 16 / C wavefronts of that column, so a column has
-// RL = 64 * WR row-lanes, each walking 8 consecutive rows per sweep of RS = 8 * RL rows.  Inside a
+// Layout of the work: a workgroup of 16 wavefronts handles C <= 16 batch columns; lane l of a wavefront
+// works on column l % C and is row-lane l / C of the wavefront's 64 / C (adjacent lanes read adjacent
+// columns of one row), so a column has RL = 1024 / C row-lanes, each walking 8 consecutive rows per
+// sweep of RS = 8 * RL rows.  Inside a
 // row-lane decays are multiplied up (at most 8 factors); every longer decay is exp of an anchor
 // difference; row-lanes are combined by wavefront shuffles, wavefronts and sweeps through LDS.
 // The numbers carried are those of the large path: F (inclusive decayed sum) and E (the sum over
@@ -67,12 +68,12 @@ struct SmallShared {
 // (out_p <- F, out_z <- -E); the second adds its own and finishes them:  out_p = F + R - v,  out_z = G - E.
 template <int DIR, bool STRICT>
 __device__ __forceinline__ void small_pass(const SmallProblem& P, const SmallShared& sh, int64_t N, int64_t batch,
-                                           int C, int64_t col0, float* wtot /* [4][kSmallWaves] */)
+                                           int C, int64_t col0, float* wtot /* [4][256] */)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int WR = kSmallWaves / C;
-    const int c = wave % C, wr = wave / C;
-    const int RL = 64 * WR;
+    const int RPW = 64 / C;                     // row-lanes per wavefront
+    const int c = lane % C, rls = lane / C;     // adjacent lanes hold adjacent columns of a row: a load touches RPW rows
+    const int RL = kSmallWaves * RPW;
     const int64_t RS = (int64_t)RL * kSmallItems;
     const int64_t col = col0 + c;
     const bool col_ok = col < batch;
@@ -80,7 +81,7 @@ __device__ __forceinline__ void small_pass(const SmallProblem& P, const SmallSha
     auto pos = [&](int64_t q) -> float { return DIR ? -sh.p[N - q] : sh.p[q + 1]; };      // q in -1 .. N
     float Fc = 0.0f, Ec = 0.0f;                 // state at the end of the previous sweep
     for (int64_t s = 0; s < sweeps; ++s) {
-        const int64_t q0 = s * RS + (int64_t)(wr * 64 + lane) * kSmallItems;
+        const int64_t q0 = s * RS + (int64_t)(wave * RPW + rls) * kSmallItems;
         float v[kSmallItems], F0[kSmallItems], E0[kSmallItems], cf[kSmallItems];
         uint32_t idr[kSmallItems];
         int seen = 0;
@@ -114,30 +115,30 @@ __device__ __forceinline__ void small_pass(const SmallProblem& P, const SmallSha
             mine.Q = E0[kSmallItems - 1];
             mine.H = (seen >> (kSmallItems - 1)) & 1;
         }
-        // inclusive scan over the 64 row-lanes of the wavefront
+        // inclusive scan over the row-lanes of the wavefront (lanes C apart hold the same column)
         Seg inc = mine;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
+        for (int d = 1; d < RPW; d <<= 1) {
             Seg o;
-            o.D = __shfl_up(inc.D, d); o.S = __shfl_up(inc.S, d); o.Q = __shfl_up(inc.Q, d); o.H = __shfl_up(inc.H, d);
-            if (lane >= d) inc = seg_then(o, inc);
+            o.D = __shfl_up(inc.D, d * C); o.S = __shfl_up(inc.S, d * C); o.Q = __shfl_up(inc.Q, d * C); o.H = __shfl_up(inc.H, d * C);
+            if (rls >= d) inc = seg_then(o, inc);
         }
-        if (lane == 63) {
-            wtot[0 * kSmallWaves + wave] = inc.D; wtot[1 * kSmallWaves + wave] = inc.S;
-            wtot[2 * kSmallWaves + wave] = inc.Q; wtot[3 * kSmallWaves + wave] = __int_as_float(inc.H);
+        if (rls == RPW - 1) {
+            const int slot = wave * 16 + c;
+            wtot[0 * 256 + slot] = inc.D; wtot[1 * 256 + slot] = inc.S;
+            wtot[2 * 256 + slot] = inc.Q; wtot[3 * 256 + slot] = __int_as_float(inc.H);
         }
-        Seg before;                                                 // the lanes before this one in the wavefront
-        before.D = __shfl_up(inc.D, 1); before.S = __shfl_up(inc.S, 1); before.Q = __shfl_up(inc.Q, 1); before.H = __shfl_up(inc.H, 1);
-        if (lane == 0) { before.D = 1.0f; before.S = 0.0f; before.Q = 0.0f; before.H = 0; }
+        Seg before;                                                 // the row-lanes before this one in the wavefront
+        before.D = __shfl_up(inc.D, C); before.S = __shfl_up(inc.S, C); before.Q = __shfl_up(inc.Q, C); before.H = __shfl_up(inc.H, C);
+        if (rls == 0) { before.D = 1.0f; before.S = 0.0f; before.Q = 0.0f; before.H = 0; }
         __syncthreads();
-        // state entering this wavefront: the sweep's incoming state through the column's earlier wavefronts
+        // state entering this wavefront: the sweep's incoming state through the earlier wavefronts
         float Fin = Fc, Ein = Ec;
-        for (int u = 0; u < WR; ++u) {
-            const int w2 = u * C + c;
+        for (int u = 0; u < kSmallWaves; ++u) {
+            const int slot = u * 16 + c;
             Seg t;
-            t.D = wtot[0 * kSmallWaves + w2]; t.S = wtot[1 * kSmallWaves + w2];
-            t.Q = wtot[2 * kSmallWaves + w2]; t.H = __float_as_int(wtot[3 * kSmallWaves + w2]);
-            if (u == wr) { Fin = Fc; Ein = Ec; }
+            t.D = wtot[0 * 256 + slot]; t.S = wtot[1 * 256 + slot];
+            t.Q = wtot[2 * 256 + slot]; t.H = __float_as_int(wtot[3 * 256 + slot]);
+            if (u == wave) { Fin = Fc; Ein = Ec; }
             seg_apply(t, Fc, Ec);
         }
         __syncthreads();                                            // wtot is rewritten by the next sweep
@@ -170,13 +171,13 @@ __device__ __forceinline__ void small_pass(const SmallProblem& P, const SmallSha
 // a block of queries; each of its 16 wavefronts keeps 512 of the candidates in registers (8 per lane),
 // counts for every query how many of them lie below it, and the 16 partial counts are added per query.
 // Output: the plan's ids and sorted anchors (pk, between its two sentinels).
-constexpr int kRankQueries = 32;          // queries per workgroup
+constexpr int kRankQueriesMax = 256;      // queries per workgroup: 32 .. 256, chosen by the launcher
 
 __global__ void __launch_bounds__(kSmallThreads)
-k_small_rank(SmallArgs A)
+k_small_rank(SmallArgs A, int queries)
 {
-    __shared__ unsigned long long query[kRankQueries];
-    __shared__ uint32_t partial[kRankQueries][kSmallWaves];
+    __shared__ unsigned long long query[kRankQueriesMax];
+    __shared__ uint32_t partial[kRankQueriesMax][kSmallWaves];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t op = blockIdx.y;
     const int N = (int)(A.k + A.n);
@@ -189,17 +190,19 @@ k_small_rank(SmallArgs A)
         return ((unsigned long long)small_float_to_key(f) << 32) | (unsigned long long)(uint32_t)e;
     };
     // candidates of this wavefront: positions wave * 512 + r * 64 + lane; a position past the end never counts
+    // (one 64-bit compare per 64 candidates; splitting it into key and position compares with lane masks
+    //  was four times slower)
     unsigned long long cand[kSmallItems];
 #pragma unroll
     for (int r = 0; r < kSmallItems; ++r) {
         const int e = wave * 64 * kSmallItems + r * 64 + lane;
         cand[r] = e < N ? composite(e) : ~0ull;
     }
-    const int q0 = blockIdx.x * kRankQueries;
-    if (tid < kRankQueries) query[tid] = q0 + tid < N ? composite(q0 + tid) : 0ull;
+    const int q0 = blockIdx.x * queries;
+    if (tid < queries) query[tid] = q0 + tid < N ? composite(q0 + tid) : 0ull;
     __syncthreads();
     const bool any = wave * 64 * kSmallItems < N;                   // uniform: does this wavefront hold candidates at all
-    for (int q = 0; q < kRankQueries; ++q) {
+    for (int q = 0; q < queries; ++q) {
         const unsigned long long me = query[q];                     // the same for every lane
         uint32_t below = 0u;
         if (any) {
@@ -209,7 +212,7 @@ k_small_rank(SmallArgs A)
         if (lane == 0) partial[q][wave] = below;
     }
     __syncthreads();
-    if (tid < kRankQueries && q0 + tid < N) {
+    if (tid < queries && q0 + tid < N) {
         uint32_t rank = 0u;
 #pragma unroll
         for (int w = 0; w < kSmallWaves; ++w) rank += partial[tid][w];
@@ -225,7 +228,7 @@ k_small(SmallArgs A)
 {
     __shared__ unsigned long long comp[kSmallMax + 1];      // ids (first half), sorted keys / anchors (second half)
     __shared__ float sdh[kSmallMax + 1];
-    __shared__ float wtot[4 * kSmallWaves];
+    __shared__ float wtot[4 * 256];                          // per sweep: (D, S, Q, H) of wavefront w, column c at [w * 16 + c]
     const int tid = threadIdx.x;
     const int64_t op = blockIdx.y;
     const int64_t N = A.k + A.n;
@@ -274,18 +277,22 @@ k_small(SmallArgs A)
 hipError_t launch_small(const SmallArgs& A0, int64_t operators, hipStream_t st)
 {
     SmallArgs A = A0;
-    // Columns per workgroup: as few as still give the device a workgroup per compute unit or two (fewer
-    // columns = more row-lanes per column = fewer sweeps), at most 16.
+    // Columns per workgroup: as few as still give the device a workgroup per compute unit (fewer
+    // columns = more row-lanes per column = fewer sweeps, and with the device idle otherwise more workgroups beat
+    // wider rows: measured on five shapes), at most 16.
     int cols = 16;
-    while (cols > 1 && ((A.batch + cols - 1) / cols) * operators < 512) cols >>= 1;
+    while (cols > 1 && ((A.batch + cols - 1) / cols) * operators < 256) cols >>= 1;
     while (cols > 1 && cols / 2 >= A.batch) cols >>= 1;
     A.cols = cols;
     const int64_t slabs = (A.batch + A.cols - 1) / A.cols;
     const int64_t N = A.k + A.n;
     A.write_dh = A.reuse_plan ? 0 : 1;
-    if (!A.reuse_plan)
-        LAPLEX_TIMED("small_sort", st, hipLaunchKernelGGL(k_small_rank, dim3((unsigned)((N + kRankQueries - 1) / kRankQueries), (unsigned)operators),
-                                                          dim3(kSmallThreads), 0, st, A));
+    if (!A.reuse_plan) {
+        int queries = 32;          // per workgroup (more per workgroup measured slower until the grid gets very large)
+        while (queries < kRankQueriesMax && ((N + queries - 1) / queries) * operators > 8192) queries <<= 1;
+        LAPLEX_TIMED("small_sort", st, hipLaunchKernelGGL(k_small_rank, dim3((unsigned)((N + queries - 1) / queries), (unsigned)operators),
+                                                          dim3(kSmallThreads), 0, st, A, queries));
+    }
     if (A.nprob > 0)
         LAPLEX_TIMED("small", st, hipLaunchKernelGGL(k_small, dim3((unsigned)slabs, (unsigned)operators), dim3(kSmallThreads), 0, st, A));
     return hipGetLastError();
