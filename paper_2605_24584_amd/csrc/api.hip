@@ -210,6 +210,20 @@ Wgram64Layout wgram64_layout(int64_t k, int64_t n)
     return G;
 }
 
+// The plan (ids, sorted anchors) of the doubled anchors: few merged positions are ranked by counting in one
+// launch, more go through the radix sort (or the merge path).
+int build_wgram_plan(const float* a, int64_t k, const float* b, int64_t n, const Layout& L, const Plan& P, char* w,
+                     uint32_t flags, hipStream_t st)
+{
+    if (L.N <= kSmallMax) {
+        SmallArgs S = small_args(a, k, b, n, 2.0f, P, L, flags);      // no scan problem: the sort alone
+        LAPLEX_HIP(launch_small(S, 1, st));
+        return LAPLEX_OK;
+    }
+    const bool sorted = (flags & LAPLEX_A_SORTED) && (flags & LAPLEX_B_SORTED);
+    return build_plan(a, k, b, n, 2.0f, L, w, flags, sorted, st);
+}
+
 int check_wgram_sizes(int64_t k, int64_t n)
 {
     LAPLEX_CHECK(check_sizes(k, n, 1));
@@ -703,8 +717,7 @@ int laplex_wgram(const float* a, int64_t k, const float* b, int64_t n, const flo
     const Layout L = make_layout(k + n, k, 1);
     const Plan P = plan_of(L, w);
     // the plan of the doubled anchors: its decays are exp(-2 gap), the kernel K = L(2a) of the theorem
-    const bool sorted = (flags & LAPLEX_A_SORTED) && (flags & LAPLEX_B_SORTED);
-    LAPLEX_CHECK(build_plan(a, k, b, n, 2.0f, L, w, flags, sorted, st));
+    LAPLEX_CHECK(build_wgram_plan(a, k, b, n, L, P, w, flags, st));
     LAPLEX_HIP(launch_wgram_f32(P.ids, P.pk, a, d, k, k + n, reinterpret_cast<double*>(w + G.off_summ),
                                 reinterpret_cast<double*>(w + G.off_u), reinterpret_cast<double*>(w + G.off_v),
                                 reinterpret_cast<double*>(w + G.off_w), m, ldm, st));
@@ -749,8 +762,7 @@ int laplex_wgram_f64(const float* a, int64_t k, const float* b, int64_t n, const
     char* w = static_cast<char*>(ws);
     const Layout L = make_layout(k + n, k, 1);
     const Plan P = plan_of(L, w);
-    const bool sorted = (flags & LAPLEX_A_SORTED) && (flags & LAPLEX_B_SORTED);
-    LAPLEX_CHECK(build_plan(a, k, b, n, 2.0f, L, w, flags, sorted, st));
+    LAPLEX_CHECK(build_wgram_plan(a, k, b, n, L, P, w, flags, st));
     LAPLEX_HIP(launch_wgram_f64(P.ids, P.pk, a, d, k, k + n, reinterpret_cast<double*>(w + G.off_summ),
                                 reinterpret_cast<double*>(w + G.off_u), reinterpret_cast<double*>(w + G.off_v),
                                 reinterpret_cast<double*>(w + G.off_w), m, ldm, st));
