@@ -9,9 +9,9 @@
 // Layout of the work: a workgroup of 16 wavefronts handles C <= 16 batch columns; lane l of a wavefront
 // works on column l % C and is row-lane l / C of the wavefront's 64 / C (adjacent lanes read adjacent
 // columns of one row), so a column has RL = 1024 / C row-lanes, each walking 8 consecutive rows per
-// sweep of RS = 8 * RL rows.  Inside a
-// row-lane decays are multiplied up (at most 8 factors); every longer decay is exp of an anchor
-// difference; row-lanes are combined by wavefront shuffles, wavefronts and sweeps through LDS.
+// sweep of RS = 8 * RL rows.  Inside a row-lane decays are multiplied up (at most 8 factors); every
+// longer decay is exp of an anchor difference; row-lanes are combined by wavefront shuffles, wavefronts
+// and sweeps through LDS.
 // The numbers carried are those of the large path: F (inclusive decayed sum) and E (the sum over
 // strictly smaller keys), summarised per segment as (D, S, H, Q):
 //     F_out = D F_in + S,    E_out = H ? D F_in + Q : E_in.
