@@ -1714,9 +1714,20 @@ k_rowdot_narrow(const float* __restrict__ u, int64_t ldu, int64_t op_u, const fl
 {
     u += (int64_t)blockIdx.y * op_u; v += (int64_t)blockIdx.y * op_v; out += (int64_t)blockIdx.y * op_out;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    // rows of 4 or 8 floats that start on 16-byte boundaries are read with 128-bit loads (same summation order)
+    const bool v4 = batch % 4 == 0 && ldu % 4 == 0 && ldv % 4 == 0 &&
+                    ((reinterpret_cast<uintptr_t>(u) | reinterpret_cast<uintptr_t>(v)) & 15u) == 0;
     for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < rows; r += stride) {
         float s = 0.0f;
-        for (int64_t t = 0; t < batch; ++t) s += u[r * ldu + t] * v[r * ldv + t];
+        if (v4) {
+            for (int64_t t = 0; t < batch; t += 4) {
+                const float4 x = *reinterpret_cast<const float4*>(u + r * ldu + t);
+                const float4 y = *reinterpret_cast<const float4*>(v + r * ldv + t);
+                s += x.x * y.x; s += x.y * y.y; s += x.z * y.z; s += x.w * y.w;
+            }
+        } else {
+            for (int64_t t = 0; t < batch; ++t) s += u[r * ldu + t] * v[r * ldv + t];
+        }
         out[r] = s;
     }
 }
