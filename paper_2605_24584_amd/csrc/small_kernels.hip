@@ -37,26 +37,6 @@ __device__ __forceinline__ float small_key_to_float(uint32_t key)
     return __uint_as_float(key ^ ((key >> 31) ? 0x80000000u : 0xFFFFFFFFu));
 }
 
-struct Seg { float D, S, Q; int H; };     // summary of a run of rows
-
-// `first` followed by `second`
-__device__ __forceinline__ Seg seg_then(const Seg& first, const Seg& second)
-{
-    Seg r;
-    r.D = first.D * second.D;
-    r.S = second.D * first.S + second.S;
-    r.Q = second.H ? second.D * first.S + second.Q : first.Q;
-    r.H = first.H | second.H;
-    return r;
-}
-
-__device__ __forceinline__ void seg_apply(const Seg& s, float& F, float& E)
-{
-    const float f = s.D * F;
-    E = s.H ? f + s.Q : E;
-    F = f + s.S;
-}
-
 struct SmallShared {
     uint32_t* id;      // [N]      sorted ids
     float* p;          // [N + 2]  sorted anchors between -inf and +inf
@@ -67,21 +47,21 @@ struct SmallShared {
 // q counts rows in processing order.  The first direction parks its results at the result rows
 // (out_p <- F, out_z <- -E); the second adds its own and finishes them:  out_p = F + R - v,  out_z = G - E.
 template <int DIR, bool STRICT>
-__device__ __forceinline__ void small_pass(const SmallProblem& P, const SmallShared& sh, int64_t N, int64_t batch,
+__device__ __forceinline__ void small_pass(const SmallProblem& P, const SmallShared& sh, int N, int64_t batch,
                                            int C, int64_t col0, float* wtot /* [4][256] */)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int RPW = 64 / C;                     // row-lanes per wavefront
     const int c = lane % C, rls = lane / C;     // adjacent lanes hold adjacent columns of a row: a load touches RPW rows
     const int RL = kSmallWaves * RPW;
-    const int64_t RS = (int64_t)RL * kSmallItems;
+    const int RS = RL * kSmallItems;
     const int64_t col = col0 + c;
     const bool col_ok = col < batch;
-    const int64_t sweeps = (N + RS - 1) / RS;
-    auto pos = [&](int64_t q) -> float { return DIR ? -sh.p[N - q] : sh.p[q + 1]; };      // q in -1 .. N
+    const int sweeps = (N + RS - 1) / RS;
+    auto pos = [&](int q) -> float { return DIR ? -sh.p[N - q] : sh.p[q + 1]; };      // q in -1 .. N
     float Fc = 0.0f, Ec = 0.0f;                 // state at the end of the previous sweep
-    for (int64_t s = 0; s < sweeps; ++s) {
-        const int64_t q0 = s * RS + (int64_t)(wave * RPW + rls) * kSmallItems;
+    for (int s = 0; s < sweeps; ++s) {
+        const int q0 = s * RS + (wave * RPW + rls) * kSmallItems;
         float v[kSmallItems], F0[kSmallItems], E0[kSmallItems], cf[kSmallItems];
         uint32_t idr[kSmallItems];
         int seen = 0;
@@ -90,9 +70,9 @@ __device__ __forceinline__ void small_pass(const SmallProblem& P, const SmallSha
             int sn = 0;
 #pragma unroll
             for (int i = 0; i < kSmallItems; ++i) {
-                const int64_t q = q0 + i;
+                const int q = q0 + i;
                 const bool live = q < N;
-                const int64_t row = live ? (DIR ? N - 1 - q : q) : 0;
+                const int row = live ? (DIR ? N - 1 - q : q) : 0;
                 const uint32_t id = live ? sh.id[row] : 0xFFFFFFFFu;
                 const float d = live ? (DIR ? sh.dh[row + 1] : sh.dh[row]) : -1.0f;     // past the end: transparent
                 const bool h = d >= 0.0f;
@@ -106,43 +86,76 @@ __device__ __forceinline__ void small_pass(const SmallProblem& P, const SmallSha
                 seen |= sn << i;
             }
         }
-        // the row-lane's summary; its decay from the anchors
-        Seg mine;
-        {
-            const int64_t qe = q0 + kSmallItems - 1 < N ? q0 + kSmallItems - 1 : N - 1;
-            mine.D = q0 < N ? expf(-(pos(qe) - pos(q0 - 1))) : 1.0f;
-            mine.S = F0[kSmallItems - 1];
-            mine.Q = E0[kSmallItems - 1];
-            mine.H = (seen >> (kSmallItems - 1)) & 1;
-        }
-        // inclusive scan over the row-lanes of the wavefront (lanes C apart hold the same column)
-        Seg inc = mine;
+        // Everything beyond a row-lane is combined with decays taken from the anchors, never with products
+        // of decays (a product of m equal factors carries m times the factor's rounding error, and on a
+        // regular grid the factors ARE equal).  endq(r): the last row of row-lane r of this sweep.
+        auto endq = [&](int r) -> int { const int q = s * RS + (r + 1) * kSmallItems - 1; return q < N ? q : N - 1; };
+        const int rl = wave * RPW + rls;
+        // inclusive scan over the row-lanes of the wavefront (lanes C apart hold the same column): (S, Q, H) of
+        // the row-lanes rl - 2^j + 1 .. rl; the decay across them is exp(-(anchor at their end - anchor before them))
+        float S = F0[kSmallItems - 1], Q = E0[kSmallItems - 1];
+        int H = (seen >> (kSmallItems - 1)) & 1;
         for (int d = 1; d < RPW; d <<= 1) {
-            Seg o;
-            o.D = __shfl_up(inc.D, d * C); o.S = __shfl_up(inc.S, d * C); o.Q = __shfl_up(inc.Q, d * C); o.H = __shfl_up(inc.H, d * C);
-            if (rls >= d) inc = seg_then(o, inc);
+            const float So = __shfl_up(S, d * C), Qo = __shfl_up(Q, d * C);
+            const int Ho = __shfl_up(H, d * C);
+            if (rls >= d) {
+                const float Dl = expf(-(pos(endq(rl)) - pos(endq(rl - d))));
+                Q = H ? Dl * So + Q : Qo;
+                S = Dl * So + S;
+                H |= Ho;
+            }
         }
         if (rls == RPW - 1) {
             const int slot = wave * 16 + c;
-            wtot[0 * 256 + slot] = inc.D; wtot[1 * 256 + slot] = inc.S;
-            wtot[2 * 256 + slot] = inc.Q; wtot[3 * 256 + slot] = __int_as_float(inc.H);
+            wtot[1 * 256 + slot] = S; wtot[2 * 256 + slot] = Q; wtot[3 * 256 + slot] = __int_as_float(H);
         }
-        Seg before;                                                 // the row-lanes before this one in the wavefront
-        before.D = __shfl_up(inc.D, C); before.S = __shfl_up(inc.S, C); before.Q = __shfl_up(inc.Q, C); before.H = __shfl_up(inc.H, C);
-        if (rls == 0) { before.D = 1.0f; before.S = 0.0f; before.Q = 0.0f; before.H = 0; }
+        // the row-lanes before this one in the wavefront
+        float Sb = __shfl_up(S, C), Qb = __shfl_up(Q, C);
+        int Hb = __shfl_up(H, C);
+        if (rls == 0) { Sb = 0.0f; Qb = 0.0f; Hb = 0; }
+        // Decays from the end of wavefront u (lane u), and from the end of the previous sweep (lane 16), to the
+        // row before this wavefront's first (gw) and to the end of this sweep (ge); the same for every column.
+        float gw = 0.0f, ge = 0.0f;
+        {
+            const int q_before_wave = s * RS + wave * RPW * kSmallItems - 1;      // >= -1
+            const float target_w = pos(q_before_wave < N ? q_before_wave : N - 1);
+            const float target_e = pos(endq(RL - 1));
+            if (lane <= kSmallWaves) {
+                const float from = lane < kSmallWaves ? pos(endq((lane + 1) * RPW - 1)) : pos(s * RS - 1);
+                // (the first wavefront of the first sweep has nothing before it: both anchors are the -inf sentinel)
+                gw = (lane < wave || lane == kSmallWaves) && q_before_wave >= 0 ? expf(-(target_w - from)) : 0.0f;
+                ge = expf(-(target_e - from));
+            }
+        }
         __syncthreads();
-        // state entering this wavefront: the sweep's incoming state through the earlier wavefronts
-        float Fin = Fc, Ein = Ec;
+        // state entering this wavefront (Fin, Ein) and state at the end of the sweep (Fc, Ec): sums over the
+        // wavefronts' summaries, each decayed to the target directly
+        auto lane_value = [](float x, int l) -> float { return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), l)); };
+        float Fin = lane_value(gw, kSmallWaves) * Fc, Ein = Ec;
+        float Fe = lane_value(ge, kSmallWaves) * Fc, Ee = Ec;
+#pragma unroll
         for (int u = 0; u < kSmallWaves; ++u) {
             const int slot = u * 16 + c;
-            Seg t;
-            t.D = wtot[0 * 256 + slot]; t.S = wtot[1 * 256 + slot];
-            t.Q = wtot[2 * 256 + slot]; t.H = __float_as_int(wtot[3 * 256 + slot]);
-            if (u == wave) { Fin = Fc; Ein = Ec; }
-            seg_apply(t, Fc, Ec);
+            const float tS = wtot[1 * 256 + slot], tQ = wtot[2 * 256 + slot];
+            const int tH = __float_as_int(wtot[3 * 256 + slot]);
+            const float gwu = lane_value(gw, u), geu = lane_value(ge, u);
+            if (u < wave) {
+                if (tH) Ein = Fin + tQ;       // a run head inside u: everything before u, decayed, plus u's own strict sum
+                Fin += gwu * tS;
+            }
+            if (tH) Ee = Fe + tQ;
+            Fe += geu * tS;
         }
+        Fc = Fe; Ec = Ee;
         __syncthreads();                                            // wtot is rewritten by the next sweep
-        seg_apply(before, Fin, Ein);
+        // ... and through the row-lanes before this one
+        {
+            const int qw = s * RS + wave * RPW * kSmallItems - 1;
+            const float Dwl = rls == 0 ? 1.0f : expf(-(pos(q0 - 1 < N ? q0 - 1 : N - 1) - pos(qw < N ? qw : N - 1)));
+            const float f = Dwl * Fin;
+            Ein = Hb ? f + Qb : Ein;
+            Fin = f + Sb;
+        }
         // the rows
 #pragma unroll
         for (int i = 0; i < kSmallItems; ++i) {
@@ -260,13 +273,13 @@ k_small(SmallArgs A)
         if (P.out_p) P.out_p += op * P.op_p;
         if (P.out_z) P.out_z += op * P.op_z;
         if (P.out_z) {
-            small_pass<0, true>(P, sh, N, A.batch, A.cols, col0, wtot);
+            small_pass<0, true>(P, sh, (int)N, A.batch, A.cols, col0, wtot);
             __syncthreads();          // a row's two directions are walked by different threads: what the first parked must be visible
-            small_pass<1, true>(P, sh, N, A.batch, A.cols, col0, wtot);
+            small_pass<1, true>(P, sh, (int)N, A.batch, A.cols, col0, wtot);
         } else {
-            small_pass<0, false>(P, sh, N, A.batch, A.cols, col0, wtot);
+            small_pass<0, false>(P, sh, (int)N, A.batch, A.cols, col0, wtot);
             __syncthreads();
-            small_pass<1, false>(P, sh, N, A.batch, A.cols, col0, wtot);
+            small_pass<1, false>(P, sh, (int)N, A.batch, A.cols, col0, wtot);
         }
         __syncthreads();
     }

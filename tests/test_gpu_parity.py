@@ -731,3 +731,49 @@ def test_weighted_gram_matrix_fp64(oracle, weights, kind, k, n):
     ratio = np.abs(got - ref) / (1e-12 * tol + 1e-300)
     assert ratio.max() <= 1.0, f"worst |err| / (1e-12 T) = {ratio.max():.3g}"
     assert np.array_equal(got, got.T)
+
+
+# ------------------------------------------------------------------ the paper's accuracy experiments
+
+@pytest.mark.parametrize("grid", ["irregular", "uniform"])
+def test_accuracy_levels_of_the_paper(oracle, grid, capsys):
+    """App. "Numerical accuracy" and "Numerical accuracy on a uniform-grid (Toeplitz) problem": square
+    kernel, batch 8, n = 2^10 .. 2^14, fp32 inputs widened to fp64 for the dense reference.  The paper
+    reports, for its own fp32 path, relative l_inf errors below 5e-7 and relative l_2 errors around
+    1.5e-7 (4.2e-7 l_inf on the uniform grid a_i = b_i = i / n at n = 2^14).  A sanity band, with a
+    factor two of slack: the acceptance bar of this repository is the per-output tolerance above."""
+    r = np.random.default_rng(1234)
+    for e in range(10, 15):
+        n = 1 << e
+        if grid == "uniform":
+            a = b = (np.arange(n) / n).astype(np.float32)
+        else:
+            a = r.uniform(0, n / 32.0, n).astype(np.float32); b = r.uniform(0, n / 32.0, n).astype(np.float32)
+        x = r.normal(size=(n, 8)).astype(np.float32)
+        y, _ = gpu_apply(a, b, x)
+        ref = np.exp(-np.abs(a.astype(np.float64)[:, None] - b.astype(np.float64)[None, :])) @ x.astype(np.float64)
+        linf = np.abs(y - ref).max() / np.abs(ref).max()
+        l2 = np.linalg.norm(y - ref) / np.linalg.norm(ref)
+        with capsys.disabled():
+            print(f"[accuracy {grid} n=2^{e}] rel l_inf = {linf:.3g}, rel l_2 = {l2:.3g}", flush=True)
+        assert linf < 1e-5 and l2 < 3e-6
+
+
+@pytest.mark.parametrize("gap", [1.0 / 4096, 3.1e-4, 1.3e-3])
+@pytest.mark.parametrize("k,n,batch", [(4096, 4096, 1), (1000, 3000, 8), (3000, 5000, 64), (20000, 20000, 1)])
+def test_regular_grid_equal_decays(oracle, gap, k, n, batch):
+    """Anchors on a regular grid: every neighbour decay is the same number with the same rounding error, so
+    a decay over m rows formed as a product is off by m times that error, systematically; all weights
+    stay large (the whole grid spans a few units), so every output feels it.  Both paths take decays over
+    more than a handful of rows from anchor differences instead."""
+    r = np.random.default_rng(k + n + batch)
+    a = (np.arange(k) * (gap * n / k)).astype(np.float32)
+    b = (np.arange(n) * gap).astype(np.float32)
+    x = r.normal(size=(n, batch)).astype(np.float32); g = r.normal(size=(k, batch)).astype(np.float32)
+    brute = k * n * batch <= 4e7
+    ref, tol = (oracle.apply_brute if brute else oracle.apply_scan)(a, b, x)
+    (rgx, rga, rgb), (tgx, tga, tgb) = (oracle.apply_backward_brute if brute else oracle.apply_backward_scan)(a, b, x, g)
+    y, ws = gpu_apply(a, b, x, flags=B.LAPLEX_SAVE_SCANS)
+    gx, ga, gb = gpu_backward(a, b, x, g, flags=B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN, ws=ws)
+    assert_close("y", y, ref, tol)
+    assert_close("gx", gx, rgx, tgx); assert_close("ga", ga, rga, tga); assert_close("gb", gb, rgb, tgb)
