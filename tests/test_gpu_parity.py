@@ -740,8 +740,10 @@ def test_accuracy_levels_of_the_paper(oracle, grid, capsys):
     """App. "Numerical accuracy" and "Numerical accuracy on a uniform-grid (Toeplitz) problem": square
     kernel, batch 8, n = 2^10 .. 2^14, fp32 inputs widened to fp64 for the dense reference.  The paper
     reports, for its own fp32 path, relative l_inf errors below 5e-7 and relative l_2 errors around
-    1.5e-7 (4.2e-7 l_inf on the uniform grid a_i = b_i = i / n at n = 2^14).  A sanity band, with a
-    factor two of slack: the acceptance bar of this repository is the per-output tolerance above."""
+    1.5e-7 (4.2e-7 l_inf on the uniform grid a_i = b_i = i / n at n = 2^14).  A sanity band (this path:
+    1.9e-7 .. 9.5e-7 l_inf, the largest on the uniform grid at n = 2^14, where every output is a running
+    sum of 16384 terms of like size rounded in fp32 at every step); the acceptance bar of this repository
+    is the per-output tolerance above."""
     r = np.random.default_rng(1234)
     for e in range(10, 15):
         n = 1 << e
@@ -756,7 +758,7 @@ def test_accuracy_levels_of_the_paper(oracle, grid, capsys):
         l2 = np.linalg.norm(y - ref) / np.linalg.norm(ref)
         with capsys.disabled():
             print(f"[accuracy {grid} n=2^{e}] rel l_inf = {linf:.3g}, rel l_2 = {l2:.3g}", flush=True)
-        assert linf < 1e-5 and l2 < 3e-6
+        assert linf < 1.5e-6 and l2 < 1e-6
 
 
 @pytest.mark.parametrize("gap", [1.0 / 4096, 3.1e-4, 1.3e-3])
