@@ -336,6 +336,13 @@ def main():
         "roofline": roofline,
         "phases": phases,
         # compulsory HBM bytes of one step (x twice, gx once, gy, y, anchors and gradients) over the step time
+        # the paper's own numbers for neighbouring shapes, with their hardware (context, not a baseline for this workload)
+        "paper_context": {
+            "hardware": "NVIDIA H100, fp32 (App. 'Kernel-algebra benchmarks')",
+            "asymmetric_one_axis_1024_forward_ms_at_long_axis_2^20": 7.0,
+            "square_n=k=2^20_batch8_forward_backward_ms": 71.0,
+            "note": "batch 8 there, batch 256 here; vs_baseline stays null",
+        },
         "end_to_end_hbm_frac": round((4 * (n + k) * 2 + 4 * batch * (3 * n + 2 * k)) / (ms_per_step * 1e-3) / 1e9
                                      / HBM_PEAK_GBS, 4),
     }
