@@ -315,9 +315,13 @@ static int apply_impl(const float* a, int64_t k, const float* b, int64_t n,
     p.res_lo = 0; p.res_hi = (uint32_t)k;
     p.out_p = y; p.ld_p = ldy;
     p.out_z = (flags & LAPLEX_SAVE_SCANS) ? P.z : nullptr;
+    float* const pairs = reinterpret_cast<float*>(w + L.off_pair);
+    const bool paired = batch == 1 && p.out_z != nullptr;      // y and the saved scan of a row as one 8-byte slot
+    if (paired) { p.out_p = pairs; p.ld_p = 2; p.out_z = pairs + 1; p.ld_z = 2; }
     p.stage = (flags & LAPLEX_SAVE_SCANS) ? P.xs : P.stage;   // kept for the backward's weights when saving
     p.tag = "fwd";
     LAPLEX_HIP(launch_scan(p, L, w, st));
+    if (paired) LAPLEX_HIP(launch_unpair(pairs, k, y, ldy, P.z, st));
     return LAPLEX_OK;
 }
 
@@ -399,10 +403,14 @@ static int apply_backward_impl(const float* a, int64_t k, const float* b, int64_
         p.res_lo = (uint32_t)k; p.res_hi = (uint32_t)(k + n);
         p.out_p = gx; p.ld_p = ldgx;
         p.out_red = gb; p.w = x; p.ld_w = ldx;
+        float* const pairs = reinterpret_cast<float*>(w + L.off_pair);
+        const bool paired = batch == 1 && gx && gb;        // gx and gb of a row as one 8-byte slot
+        if (paired) { p.out_p = pairs; p.ld_p = 2; p.out_red = pairs + 1; p.ld_red = 2; }
         p.stage = P.stage;
         p.wstage = (gb && have_xs) ? P.xs : nullptr;
         p.tag = "bwd";
         LAPLEX_HIP(launch_scan(p, L, w, st));
+        if (paired) LAPLEX_HIP(launch_unpair(pairs, n, gx, ldgx, gb, st));
     }
     // the scans gave the gradients with respect to the scaled anchors
     if (gtau) LAPLEX_HIP(launch_tau_grad(a, ga, k, b, gb, n, reinterpret_cast<float*>(w + L.off_scratch), gtau, st));
@@ -445,9 +453,13 @@ static int gram_impl(const float* a, int64_t n, const float* x, int64_t ldx, int
     p.res_lo = 0; p.res_hi = (uint32_t)n;
     p.out_p = y; p.ld_p = ldy;
     p.out_z = (flags & LAPLEX_SAVE_SCANS) ? P.z : nullptr;
+    float* const pairs = reinterpret_cast<float*>(w + L.off_pair);
+    const bool paired = batch == 1 && p.out_z != nullptr;
+    if (paired) { p.out_p = pairs; p.ld_p = 2; p.out_z = pairs + 1; p.ld_z = 2; }
     p.stage = (flags & LAPLEX_SAVE_SCANS) ? P.xs : P.stage;
     p.tag = "fwd";
     LAPLEX_HIP(launch_scan(p, L, w, st));
+    if (paired) LAPLEX_HIP(launch_unpair(pairs, n, y, ldy, P.z, st));
     return LAPLEX_OK;
 }
 
@@ -517,10 +529,14 @@ static int gram_backward_impl(const float* a, int64_t n, const float* x, int64_t
         p.res_lo = 0; p.res_hi = (uint32_t)n;
         p.out_p = gx; p.ld_p = ldgx;
         p.out_red = ga; p.w = x; p.ld_w = ldx; p.zs = ga ? P.z : nullptr;
+        float* const pairs = reinterpret_cast<float*>(w + L.off_pair);
+        const bool paired = batch == 1 && gx && ga;
+        if (paired) { p.out_p = pairs; p.ld_p = 2; p.out_red = pairs + 1; p.ld_red = 2; }
         p.stage = P.stage;
         p.wstage = ga ? P.xs : nullptr;     // kept by the forward (SAVE_SCANS) or just written by the re-scan
         p.tag = "bwd";
         LAPLEX_HIP(launch_scan(p, L, w, st));
+        if (paired) LAPLEX_HIP(launch_unpair(pairs, n, gx, ldgx, ga, st));
     }
     if (gtau) LAPLEX_HIP(launch_tau_grad(a, ga, n, nullptr, nullptr, 0, reinterpret_cast<float*>(w + L.off_scratch), gtau, st));
     if (tau != 1.0f && ga) LAPLEX_HIP(launch_scale(ga, n, tau, st));

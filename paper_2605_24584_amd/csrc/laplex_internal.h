@@ -130,6 +130,7 @@ struct Layout {
     int64_t max_tiles = 0, max_blocks = 0, max_chunks = 0;
     // small problems (N <= kSmallMax): f32[N][batch], the strict scans of the backward's second problem
     size_t off_small = 0;
+    size_t off_pair = 0;         // f32[max(result rows)][2], batch 1 only
     size_t total = 0;
 };
 
@@ -185,6 +186,12 @@ inline Layout make_layout(int64_t N, int64_t zrows, int64_t batch)
     L.off_car2_f = c;      c = align_up(c + per2);
     L.off_car2_e = c;      c = align_up(c + per2);
 
+    // batch 1: two outputs of a problem that land on the same rows (y and the saved scans; gx and gb) are written
+    // as pairs and separated afterwards (two random 4-byte stores into one 8-byte slot cost what one costs, two into
+    // two arrays twice that).  The pairs lie behind the scan view, on the sort view's buffers, which are dead by then.
+    L.off_pair = align_up(c);
+    const int64_t pair_rows = zrows > N - zrows ? zrows : N - zrows;
+    if (batch == 1) c = align_up(L.off_pair + sizeof(float) * 2 * (size_t)pair_rows);
     L.total = s > c ? s : c;
     L.off_small = align_up(L.total);
     if (N <= kSmallMax) L.total = align_up(L.off_small + sizeof(float) * (size_t)N * (size_t)batch);
@@ -229,6 +236,8 @@ hipError_t launch_decay(const uint32_t* keys0, const uint32_t* keys1, uint32_t* 
 
 hipError_t launch_fill(float* p, int64_t rows, int64_t cols, int64_t ld, float v, hipStream_t st);
 hipError_t launch_copy_u32(const uint32_t* src, uint32_t* dst, int64_t count, hipStream_t st);
+// first[r * ld_first] = pairs[2r], second[r] = pairs[2r + 1]
+hipError_t launch_unpair(const float* pairs, int64_t rows, float* first, int64_t ld_first, float* second, hipStream_t st);
 
 // One scan problem over the merged sequence: inject rows of `inj` at positions
 // whose id lies in [inj_lo, inj_hi), run the decayed scan in both directions and
@@ -246,6 +255,7 @@ struct ScanProblem {
     float* out_p; int64_t ld_p;
     float* out_z;
     float* out_red; const float* w; int64_t ld_w; const float* zs;
+    int64_t ld_z = 0, ld_red = 0;   // strides of out_z (0: batch) and out_red (0: 1): outputs that share rows with out_p
     int64_t batch;
     float* stage;          // narrow batches: the reduce writes the injected rows here in sorted order, the downsweep reads them back
     const float* wstage;   // narrow batches: the weights w in sorted order (an earlier problem's stage), or null

@@ -54,8 +54,8 @@ struct ScanArgs {
     const float* inj; int64_t ld_inj; uint32_t inj_lo, inj_hi;
     uint32_t res_lo, res_hi;
     float* out_p; int64_t ld_p;
-    float* out_z;
-    float* out_red; const float* w; int64_t ld_w; const float* zs;
+    float* out_z; int64_t ld_z;          // rows of out_z are ld_z floats apart (batch, unless it shares rows with out_p)
+    float* out_red; int64_t ld_red; const float* w; int64_t ld_w; const float* zs;
     float* stage; const float* wstage;   // sorted-order copies of the injected rows / of the weights (narrow batches)
     int64_t batch, bpad;
     int bv, bv_log2, rv, tile_rows, slabs, chunk_tiles;
@@ -1047,7 +1047,7 @@ __device__ __forceinline__ void emit_row_sum(const ScanArgs& A, float acc, int b
 {
     for (int m = 1; m < bv; m <<= 1) acc += __shfl_xor(acc, m);
     if (is_res && c == 0) {
-        if (A.slabs == 1) A.out_red[rr] = acc;
+        if (A.slabs == 1) A.out_red[rr * A.ld_red] = acc;
         else A.red_partial[(int64_t)blockIdx.y * res_rows + rr] = acc;
     }
 }
@@ -1266,10 +1266,10 @@ k_scan_down(const ScanArgs A)
         if (is_res && col_ok) {
             if (kStreamRows<VEC>) {
                 if (A.out_p) store_vec_stream<VEC>(A.out_p + rr * A.ld_p + col0, P);
-                if (STRICT && A.out_z) store_vec_stream<VEC>(A.out_z + rr * A.batch + col0, Z);
+                if (STRICT && A.out_z) store_vec_stream<VEC>(A.out_z + rr * A.ld_z + col0, Z);
             } else {
                 if (A.out_p) store_vec<VEC>(A.out_p + rr * A.ld_p + col0, P);
-                if (STRICT && A.out_z) store_vec<VEC>(A.out_z + rr * A.batch + col0, Z);
+                if (STRICT && A.out_z) store_vec<VEC>(A.out_z + rr * A.ld_z + col0, Z);
             }
         }
         if (want_red) {
@@ -1394,7 +1394,7 @@ k_scan_down_sparse(const ScanArgs A)
         }
         if (is_res && col_ok) {
             if (A.out_p) store_vec<VEC>(A.out_p + rr * A.ld_p + col0, P);
-            if (STRICT && A.out_z) store_vec<VEC>(A.out_z + rr * A.batch + col0, Z);
+            if (STRICT && A.out_z) store_vec<VEC>(A.out_z + rr * A.ld_z + col0, Z);
         }
         if (want_red) {
             float acc = 0.0f;
@@ -1519,7 +1519,7 @@ k_scan_down_fewres(const ScanArgs A)
         }
         if (col_ok) {
             if (A.out_p) store_vec<VEC>(A.out_p + rr * A.ld_p + col0, P);
-            if (STRICT && A.out_z) store_vec<VEC>(A.out_z + rr * A.batch + col0, Z);
+            if (STRICT && A.out_z) store_vec<VEC>(A.out_z + rr * A.ld_z + col0, Z);
         }
         if (want_red) {
             float wrow[VEC];
@@ -1633,7 +1633,7 @@ k_scan_down_sparse_wide(const ScanArgs A)
                 // the result matrix is written once and not read again by this call: streaming stores
                 if (A.out_p)
                     __builtin_nontemporal_store((v4f){P[0], P[1], P[2], P[3]}, reinterpret_cast<v4f*>(A.out_p + rr * A.ld_p + col0));
-                if (STRICT && A.out_z) store_vec<VEC>(A.out_z + rr * A.batch + col0, Z);
+                if (STRICT && A.out_z) store_vec<VEC>(A.out_z + rr * A.ld_z + col0, Z);
             }
             part[i] = 0.0f;
             if (want_red && is_res && col_ok) {
@@ -1670,7 +1670,7 @@ k_scan_down_sparse_wide(const ScanArgs A)
             const uint32_t idr = __shfl(idv, row);
             if (lane < 8 && ((res_mask >> row) & 1ull)) {
                 const int64_t rr = (int64_t)(idr - A.res_lo);
-                if (A.slabs == 1) A.out_red[rr] = sum;
+                if (A.slabs == 1) A.out_red[rr * A.ld_red] = sum;
                 else A.red_partial[(int64_t)blockIdx.y * res_rows + rr] = sum;
             }
         }
@@ -1817,7 +1817,7 @@ hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStrea
     bool v4 = p.batch % 4 == 0 && p.batch >= 4;
     v4 = v4 && aligned16(p.inj) && p.ld_inj % 4 == 0;
     if (p.out_p) v4 = v4 && aligned16(p.out_p) && p.ld_p % 4 == 0;
-    if (p.out_z) v4 = v4 && aligned16(p.out_z);
+    if (p.out_z) v4 = v4 && aligned16(p.out_z) && (p.ld_z == 0 || p.ld_z % 4 == 0);
     if (p.out_red) v4 = v4 && aligned16(p.w) && p.ld_w % 4 == 0 && (!p.zs || aligned16(p.zs));
     const ScanGeom g = scan_geom(p.N, p.batch, v4 ? 4 : 1);
 
@@ -1825,8 +1825,8 @@ hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStrea
     A.ids = p.ids; A.dh = p.dh; A.pk = p.pk; A.N = p.N;
     A.inj = p.inj; A.ld_inj = p.ld_inj; A.inj_lo = p.inj_lo; A.inj_hi = p.inj_hi;
     A.res_lo = p.res_lo; A.res_hi = p.res_hi;
-    A.out_p = p.out_p; A.ld_p = p.ld_p; A.out_z = p.out_z;
-    A.out_red = p.out_red; A.w = p.w; A.ld_w = p.ld_w; A.zs = p.zs;
+    A.out_p = p.out_p; A.ld_p = p.ld_p; A.out_z = p.out_z; A.ld_z = p.ld_z ? p.ld_z : p.batch;
+    A.out_red = p.out_red; A.ld_red = p.ld_red ? p.ld_red : 1; A.w = p.w; A.ld_w = p.ld_w; A.zs = p.zs;
     A.stage = p.stage; A.wstage = p.wstage;
     A.batch = p.batch; A.bpad = L.bpad;
     A.bv = g.bv; A.bv_log2 = ilog2(g.bv); A.rv = g.rv; A.tile_rows = g.tile_rows; A.slabs = g.slabs;

@@ -493,6 +493,17 @@ k_copy_u32(const uint32_t* __restrict__ src, uint32_t* __restrict__ dst, int64_t
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) dst[i] = src[i];
 }
 
+__global__ void __launch_bounds__(256)
+k_unpair(const float2* __restrict__ pairs, int64_t rows, float* __restrict__ first, int64_t ld_first, float* __restrict__ second)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < rows; r += stride) {
+        const float2 p = pairs[r];
+        first[r * ld_first] = p.x;
+        second[r] = p.y;
+    }
+}
+
 inline unsigned grid_for(int64_t work, int threads, int64_t cap = 1 << 16)
 {
     int64_t g = (work + threads - 1) / threads;
@@ -556,6 +567,14 @@ hipError_t launch_fill(float* p, int64_t rows, int64_t cols, int64_t ld, float v
 {
     if (rows <= 0 || cols <= 0) return hipSuccess;
     LAPLEX_TIMED("fill", st, hipLaunchKernelGGL(k_fill, dim3(grid_for(rows * cols, 256)), dim3(256), 0, st, p, rows, cols, ld, v));
+    return hipGetLastError();
+}
+
+hipError_t launch_unpair(const float* pairs, int64_t rows, float* first, int64_t ld_first, float* second, hipStream_t st)
+{
+    if (rows <= 0) return hipSuccess;
+    LAPLEX_TIMED("unpair", st, hipLaunchKernelGGL(k_unpair, dim3(grid_for(rows, 256)), dim3(256), 0, st,
+                                                  reinterpret_cast<const float2*>(pairs), rows, first, ld_first, second));
     return hipGetLastError();
 }
 
