@@ -184,7 +184,8 @@ def other_workload(args, torch, np, B, synth):
 
 
 def paper_sweep(args, torch, np, B, synth):
-    """Square apply n = k = 2^10 .. 2^20, batch 8 (the sizes of the paper's runtime figure; inputs:
+    """The paper's runtime experiments on synthetic inputs of the same shapes.
+    Square apply n = k = 2^10 .. 2^20, batch 8 (the sizes of the paper's runtime figure; inputs:
     synth.paper_square).  Timing as in the paper's protocol: warm-ups, then the best of 3 x 30 calls, sort inside every call."""
     dev = lambda v: torch.from_numpy(np.ascontiguousarray(v)).cuda()
     for e in range(10, 21):
@@ -218,6 +219,50 @@ def paper_sweep(args, torch, np, B, synth):
             out[name] = round(best, 4)
         out["elements_per_s_fwd_bwd"] = (n + k) * batch / (out["forward_backward_ms"] * 1e-3)
         print(json.dumps(out), flush=True)
+
+    def timed(fn):
+        for _ in range(10):
+            fn()
+        best = float("inf")
+        for _ in range(3):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(30):
+                fn()
+            torch.cuda.synchronize()
+            best = min(best, (time.perf_counter() - t0) * 1e3 / 30)
+        return round(best, 4)
+
+    def forward_ms(a, b, x):
+        k, n, batch = a.size, b.size, x.shape[1]
+        ws = torch.empty(B.laplex_workspace_bytes(k, n, batch), dtype=torch.uint8, device="cuda")
+        da, db, dx = dev(a), dev(b), dev(x)
+        y = torch.empty(k, batch, device="cuda")
+        return timed(lambda: B.laplex_apply(da, db, dx, y, ws, 0))
+
+    # App. "Asymmetric kernels: fixed short axis": one axis 1024, the other 2^10 .. 2^20, batch 8
+    for e in range(10, 21, 2):
+        n = 1 << e
+        a = synth.uniform(synth.stream_seed(11, synth.STREAM_A) + e, 1024, 0.0, n / 64.0)
+        b = synth.uniform(synth.stream_seed(11, synth.STREAM_B) + e, n, 0.0, n / 64.0)
+        x = synth.normal(synth.stream_seed(11, synth.STREAM_X) + e, n * 8).reshape(n, 8)
+        print(json.dumps({"experiment": "asymmetric, short axis 1024 (outputs)", "n": n, "k": 1024, "batch": 8,
+                          "forward_ms": forward_ms(a, b, x)}), flush=True)
+    # App. "Batch-size scaling": n = k = 2^14, batch 1 .. 256
+    n = k = 1 << 14
+    a = synth.uniform(synth.stream_seed(12, synth.STREAM_A), k, 0.0, n / 32.0)
+    b = synth.uniform(synth.stream_seed(12, synth.STREAM_B), n, 0.0, n / 32.0)
+    for batch in (1, 2, 4, 8, 16, 32, 64, 128, 256):
+        x = synth.normal(synth.stream_seed(12, synth.STREAM_X) + batch, n * batch).reshape(n, batch)
+        print(json.dumps({"experiment": "batch scaling", "n": n, "k": k, "batch": batch,
+                          "forward_ms": forward_ms(a, b, x)}), flush=True)
+    # Sec. 6 / App. "Random Fourier Features": a single product on irregular anchors a, b ~ N(0, 1), n = k = 2^16, batch 1
+    n = k = 1 << 16
+    a = synth.normal(synth.stream_seed(13, synth.STREAM_A), k)
+    b = synth.normal(synth.stream_seed(13, synth.STREAM_B), n)
+    x = synth.normal(synth.stream_seed(13, synth.STREAM_X), n).reshape(n, 1)
+    print(json.dumps({"experiment": "irregular anchors N(0,1), single product", "n": n, "k": k, "batch": 1,
+                      "forward_ms": forward_ms(a, b, x)}), flush=True)
 
 
 def main():
