@@ -113,49 +113,74 @@ __device__ __forceinline__ uint32_t anchor_key(const float* __restrict__ a, int6
     return float_to_key(tau * (pos < k ? a[pos] : b[pos - k]));
 }
 
+// Digit counters in LDS, kHistCopies times (a lane uses copy lane % kHistCopies, and the copies start
+// 8 banks apart): keys that share a digit value then queue on different words and banks.
+constexpr int kHistCopies = 4;
+constexpr int kHistCopyWords = kSortPasses * kRadix + 8;
+
+__device__ __forceinline__ void hist_count(uint32_t* __restrict__ h, uint32_t key, bool ok)
+{
+    uint32_t* mine = h + (threadIdx.x & (kHistCopies - 1)) * kHistCopyWords;
+    if (ok) {
+#pragma unroll
+        for (int p = 0; p < kSortPasses - 1; ++p) atomicAdd(&mine[p * kRadix + ((key >> (p * kRadixBits)) & (kRadix - 1))], 1u);
+    }
+    // the top digit (sign and high exponent bits) takes few values: count it once per distinct value
+    // in the wavefront instead of letting 64 lanes queue on one LDS word
+    const uint32_t top = key >> ((kSortPasses - 1) * kRadixBits);
+    uint64_t todo = __ballot(ok);
+    while (todo) {
+        const int leader = __ffsll((long long)todo) - 1;
+        const uint32_t v = (uint32_t)__builtin_amdgcn_readlane((int)top, leader);
+        const uint64_t same = __ballot(ok && top == v) & todo;
+        if ((int)(threadIdx.x & 63) == leader) atomicAdd(&mine[(kSortPasses - 1) * kRadix + v], (uint32_t)__popcll(same));
+        todo &= ~same;
+    }
+}
+
+// One anchor array: a scalar head up to the first 16-byte boundary, 16-byte loads (two in flight per lane), a scalar tail.
+__device__ __forceinline__ void hist_stream(uint32_t* __restrict__ h, const float* __restrict__ p, int64_t count, float tau)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t first = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t head = (int64_t)((0u - (uint32_t)(reinterpret_cast<uintptr_t>(p) >> 2)) & 3u);
+    if (head > count) head = count;
+    const int64_t quads = (count - head) >> 2;
+    const float4* __restrict__ p4 = reinterpret_cast<const float4*>(p + head);
+    for (int64_t q0 = first; q0 < quads; q0 += 2 * stride) {
+        const bool ok1 = q0 + stride < quads;
+        const float4 v0 = p4[q0];
+        const float4 v1 = p4[ok1 ? q0 + stride : q0];
+        hist_count(h, float_to_key(tau * v0.x), true); hist_count(h, float_to_key(tau * v0.y), true);
+        hist_count(h, float_to_key(tau * v0.z), true); hist_count(h, float_to_key(tau * v0.w), true);
+        hist_count(h, float_to_key(tau * v1.x), ok1); hist_count(h, float_to_key(tau * v1.y), ok1);
+        hist_count(h, float_to_key(tau * v1.z), ok1); hist_count(h, float_to_key(tau * v1.w), ok1);
+    }
+    // the head and the tail: fewer than 8 keys
+    const int64_t rest = count - 4 * quads;
+    if (first < rest) {
+        const int64_t i = first < head ? first : 4 * quads + first;
+        hist_count(h, float_to_key(tau * p[i]), true);
+    }
+}
+
 __global__ void __launch_bounds__(kSortThreads)
 k_sort_hist(const float* __restrict__ a, int64_t k, const float* __restrict__ b, int64_t n, float tau,
             uint32_t* __restrict__ ghist, unsigned long long* __restrict__ status0, int64_t status_words)
 {
-    __shared__ uint32_t h[kSortPasses][kRadix];
-    for (int i = threadIdx.x; i < kSortPasses * kRadix; i += kSortThreads) (&h[0][0])[i] = 0u;
+    __shared__ uint32_t h[kHistCopies * kHistCopyWords];
+    for (int i = threadIdx.x; i < kHistCopies * kHistCopyWords; i += kSortThreads) h[i] = 0u;
     __syncthreads();
-    const int64_t N = k + n;
+    hist_stream(h, a, k, tau);
+    hist_stream(h, b, n, tau);
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const int64_t first = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    constexpr int U = 8;          // keys in flight per lane
-    for (int64_t i0 = first; i0 < N; i0 += U * stride) {
-        uint32_t keys[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t i = i0 + u * stride;
-            keys[u] = anchor_key(a, k, b, i < N ? i : N - 1, tau);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const bool ok = i0 + u * stride < N;          // false only at the end, for whole wavefronts or their upper lanes
-            const uint32_t key = keys[u];
-            if (ok) {
-#pragma unroll
-                for (int p = 0; p < kSortPasses - 1; ++p) atomicAdd(&h[p][(key >> (p * kRadixBits)) & (kRadix - 1)], 1u);
-            }
-            // the top digit (sign and high exponent bits) takes few values: count it once per distinct value
-            // in the wavefront instead of letting 64 lanes queue on one LDS word
-            const uint32_t top = key >> ((kSortPasses - 1) * kRadixBits);
-            uint64_t todo = __ballot(ok);
-            while (todo) {
-                const int leader = __ffsll((long long)todo) - 1;
-                const uint32_t v = __shfl(top, leader);
-                const uint64_t same = __ballot(ok && top == v) & todo;
-                if ((int)(threadIdx.x & 63) == leader) atomicAdd(&h[kSortPasses - 1][v], (uint32_t)__popcll(same));
-                todo &= ~same;
-            }
-        }
-    }
     for (int64_t i = first; i < status_words; i += stride) status0[i] = 0ull;   // look-back words of pass 0
     __syncthreads();
     for (int i = threadIdx.x; i < kSortPasses * kRadix; i += kSortThreads) {
-        const uint32_t c = (&h[0][0])[i];
+        uint32_t c = 0;
+#pragma unroll
+        for (int r = 0; r < kHistCopies; ++r) c += h[r * kHistCopyWords + i];
         if (c) atomicAdd(&ghist[i], c);
     }
 }
@@ -455,6 +480,9 @@ k_merge(const float* __restrict__ a, int64_t k, const float* __restrict__ b, int
 // lattice-valued, so the rounding of the per-row decays has a systematic sign and a
 // product of tens of thousands of them drifts by 1e-4 and more; key differences
 // telescope exactly.  (App. B.1's pair operator adds log-decays for the same reason.)
+// Each lane takes four consecutive positions: one 16-byte load of the keys (and of the ids, when they
+// have to move to buffer 0), 16-byte stores of the decays and of the anchors.  pk[j] holds the anchor of
+// position j - 1, so the four anchors a lane stores are the key before its quad and the quad's first three.
 __global__ void __launch_bounds__(256)
 k_decay(const uint32_t* __restrict__ keys0, const uint32_t* __restrict__ keys1,
         uint32_t* __restrict__ ids0, const uint32_t* __restrict__ ids1,
@@ -463,17 +491,42 @@ k_decay(const uint32_t* __restrict__ keys0, const uint32_t* __restrict__ keys1,
     // after an odd number of passes the sorted pairs sit in buffer 1 (ghist == nullptr: merge path, buffer 0)
     const bool in1 = ghist != nullptr && (__popc(ghist[kSortMaskWord]) & 1);
     const uint32_t* __restrict__ keys = in1 ? keys1 : keys0;
+    const int64_t quads = (N + 2 + 3) / 4;                       // dh has N + 1 entries, pk N + 2
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j <= N; j += stride) {
-        float d = 0.0f;
-        if (j > 0 && j < N) {
-            const uint32_t k1 = keys[j], k0 = keys[j - 1];
-            d = k1 == k0 ? -1.0f : expf(-(key_to_float(k1) - key_to_float(k0)));
+    for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < quads; q += stride) {
+        const int64_t j0 = 4 * q;
+        uint32_t kk[5];                                          // keys j0 - 1 .. j0 + 3 (0 where there is none)
+        kk[0] = j0 > 0 && j0 - 1 < N ? keys[j0 - 1] : 0u;
+        const bool whole = j0 + 3 < N;
+        if (whole) {
+            const uint4 v = reinterpret_cast<const uint4*>(keys)[q];
+            kk[1] = v.x; kk[2] = v.y; kk[3] = v.z; kk[4] = v.w;
+            if (in1) reinterpret_cast<uint4*>(ids0)[q] = reinterpret_cast<const uint4*>(ids1)[q];   // the plan's ids live in buffer 0
+        } else {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                kk[1 + u] = j0 + u < N ? keys[j0 + u] : 0u;
+                if (in1 && j0 + u < N) ids0[j0 + u] = ids1[j0 + u];
+            }
         }
-        dh[j] = d;
-        pk[j + 1] = j < N ? key_to_float(keys[j]) : __uint_as_float(0x7F800000u);
-        if (j == 0) pk[0] = __uint_as_float(0xFF800000u);
-        if (in1 && j < N) ids0[j] = ids1[j];      // the plan's ids live in buffer 0
+        float d[4], a[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int64_t j = j0 + u;
+            d[u] = 0.0f;
+            if (j > 0 && j < N) d[u] = kk[1 + u] == kk[u] ? -1.0f : expf(-(key_to_float(kk[1 + u]) - key_to_float(kk[u])));
+            a[u] = j == 0 ? __uint_as_float(0xFF800000u) : (j <= N ? key_to_float(kk[u]) : __uint_as_float(0x7F800000u));
+        }
+        if (whole) {
+            reinterpret_cast<float4*>(dh)[q] = make_float4(d[0], d[1], d[2], d[3]);
+            reinterpret_cast<float4*>(pk)[q] = make_float4(a[0], a[1], a[2], a[3]);
+        } else {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (j0 + u <= N) dh[j0 + u] = d[u];
+                if (j0 + u <= N + 1) pk[j0 + u] = a[u];
+            }
+        }
     }
 }
 
@@ -558,7 +611,7 @@ hipError_t launch_merge(const float* a, int64_t k, const float* b, int64_t n, fl
 hipError_t launch_decay(const uint32_t* keys0, const uint32_t* keys1, uint32_t* ids0, const uint32_t* ids1,
                         const uint32_t* ghist, float* dh, float* pk, int64_t N, hipStream_t st)
 {
-    LAPLEX_TIMED("decay", st, hipLaunchKernelGGL(k_decay, dim3(grid_for(N + 1, 256)), dim3(256), 0, st,
+    LAPLEX_TIMED("decay", st, hipLaunchKernelGGL(k_decay, dim3(grid_for((N + 5) / 4, 256)), dim3(256), 0, st,
                                                  keys0, keys1, ids0, ids1, ghist, dh, pk, N));
     return hipGetLastError();
 }

@@ -120,6 +120,25 @@ def test_permutation_bit_exact(oracle, kind, k, n):
     assert np.array_equal(gpu_perm(ws, k + n), oracle.merged_permutation(a, b))
 
 
+@pytest.mark.parametrize("off_a,off_b", [(1, 0), (2, 3), (3, 1), (0, 2)])
+@pytest.mark.parametrize("k,n", [(1, 2), (2, 1), (3, 7), (4100, 4100), (9001, 20003)])
+def test_anchor_arrays_off_a_16_byte_boundary(oracle, off_a, off_b, k, n):
+    """The histogram reads the anchors 16 bytes at a time between a scalar head and a scalar tail."""
+    r = np.random.default_rng(k * 5 + n + off_a * 16 + off_b)
+    a, b = anchors("ties", r, k, n)
+    x = r.normal(size=(n, 1)).astype(np.float32)
+    da = torch.zeros(k + 8, device="cuda")[off_a:off_a + k]; da.copy_(dev(a))
+    db = torch.zeros(n + 8, device="cuda")[off_b:off_b + n]; db.copy_(dev(b))
+    assert da.data_ptr() % 16 == 4 * off_a and db.data_ptr() % 16 == 4 * off_b
+    ws = workspace(k, n, 1)
+    y = torch.full((k, 1), float("nan"), device="cuda")
+    B.laplex_apply(da, db, dev(x), y, ws, 0)
+    torch.cuda.synchronize()
+    assert np.array_equal(gpu_perm(ws, k + n), oracle.merged_permutation(a, b))
+    ref, tol = oracle.apply_scan(a, b, x)
+    assert_close("y", y.cpu().numpy(), ref, tol)
+
+
 @pytest.mark.parametrize("kind", ["uniform", "ties", "all_equal", "signed"])
 @pytest.mark.parametrize("k,n", [(1, 1), (100, 157), (5000, 3), (3, 5000), (20000, 70001)])
 def test_merge_path_when_both_sorted(oracle, kind, k, n):
