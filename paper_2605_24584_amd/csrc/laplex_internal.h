@@ -18,9 +18,10 @@ constexpr int kSortThreads = 512;                       // 8 wavefronts
 constexpr int kSortKeysPerThread = 16;
 constexpr int kSortTile = kSortThreads * kSortKeysPerThread;  // 8192 keys per workgroup
 // Small state of one sort, u32 words: [0, 1024) histogram of the four digits; then the per-pass tile
-// tickets and the error flag in one cache line, and the mask of the passes that run in a line of its own.
+// tickets, the error flag and the histogram's done counter in one cache line, and the mask of the passes that run in a line of its own.
 constexpr int kSortTicketWord = 1024;
 constexpr int kSortErrorWord = 1028;
+constexpr int kSortDoneWord = 1029;                     // histogram workgroups that have added their counts
 constexpr int kSortMaskWord = 1056;
 constexpr int kSortSmallWords = 1088;
 constexpr int kMergeThreads = 256;

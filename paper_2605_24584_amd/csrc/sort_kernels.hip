@@ -171,37 +171,43 @@ k_sort_hist(const float* __restrict__ a, int64_t k, const float* __restrict__ b,
     __shared__ uint32_t h[kHistCopies * kHistCopyWords];
     for (int i = threadIdx.x; i < kHistCopies * kHistCopyWords; i += kSortThreads) h[i] = 0u;
     __syncthreads();
+    const int64_t N = k + n;
     hist_stream(h, a, k, tau);
     hist_stream(h, b, n, tau);
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const int64_t first = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     for (int64_t i = first; i < status_words; i += stride) status0[i] = 0ull;   // look-back words of pass 0
     __syncthreads();
+    uint32_t seen = 0;
     for (int i = threadIdx.x; i < kSortPasses * kRadix; i += kSortThreads) {
         uint32_t c = 0;
 #pragma unroll
         for (int r = 0; r < kHistCopies; ++r) c += h[r * kHistCopyWords + i];
-        if (c) atomicAdd(&ghist[i], c);
+        if (c) seen |= atomicAdd(&ghist[i], c);
     }
-}
-
-// A pass whose digit takes one value over all keys would move every pair to where it already is
-// (relative to the others): it is skipped.  k_sort_plan derives the set of passes that run from the
-// global histogram, once: bit p of small[kSortMaskWord] = pass p runs.  If no pass would run (all keys equal)
-// the last one runs anyway, so that the output buffers get written.
-__global__ void __launch_bounds__(1024)
-k_sort_plan(uint32_t* __restrict__ small, int64_t N)
-{
-    __shared__ uint32_t constant_mask;
-    if (threadIdx.x == 0) constant_mask = 0u;
+    // (the additions return a value, and the value is waited for here: they have been performed where every
+    //  workgroup sees them before this workgroup counts itself as done.  A fence would do too, but a device-wide
+    //  fence writes back the whole L2 of the chiplet, once per workgroup: five times the kernel's run time.)
+    asm volatile("" :: "v"(seen));
+    // The workgroup that finishes last sees the whole histogram and derives the set of passes that run, once:
+    // a pass whose digit takes one value over all keys would move every pair to where it already is (relative
+    // to the others) and is skipped.  Bit p of ghist[kSortMaskWord] = pass p runs; if none would (all keys
+    // equal) the last one runs anyway, so that the output buffers get written.
+    __shared__ uint32_t s_last, constant_mask;
     __syncthreads();
-    for (int i = threadIdx.x; i < kSortPasses * kRadix; i += blockDim.x)
-        if ((int64_t)small[i] == N) atomicOr(&constant_mask, 1u << (i / kRadix));
+    if (threadIdx.x == 0) {
+        s_last = atomicAdd(&ghist[kSortDoneWord], 1u) == gridDim.x - 1 ? 1u : 0u;
+        constant_mask = 0u;
+    }
+    __syncthreads();
+    if (!s_last) return;
+    for (int i = threadIdx.x; i < kSortPasses * kRadix; i += kSortThreads)
+        if ((int64_t)__hip_atomic_load(&ghist[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == N) atomicOr(&constant_mask, 1u << (i / kRadix));
     __syncthreads();
     if (threadIdx.x == 0) {
         uint32_t active = ~constant_mask & ((1u << kSortPasses) - 1u);
         if (active == 0u) active = 1u << (kSortPasses - 1);
-        small[kSortMaskWord] = active;
+        ghist[kSortMaskWord] = active;
     }
 }
 
@@ -580,7 +586,6 @@ hipError_t launch_onesweep_sort(const float* a, int64_t k, const float* b, int64
     if (hgrid > 2048) hgrid = 2048;
     LAPLEX_TIMED("sort_hist", st, hipLaunchKernelGGL(k_sort_hist, dim3((unsigned)hgrid), dim3(kSortThreads), 0, st,
                                                      a, k, b, n, tau, small, region[0], words));
-    LAPLEX_TIMED("sort_hist", st, hipLaunchKernelGGL(k_sort_plan, dim3(1), dim3(1024), 0, st, small, N));
     const dim3 grid((unsigned)tiles), block(kSortThreads);
     auto passes = [&](auto* r0, auto* r1) {
         using WORD = std::remove_pointer_t<decltype(r0)>;
