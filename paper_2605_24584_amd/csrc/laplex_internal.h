@@ -15,8 +15,11 @@ constexpr int kRadixBits = 8;
 constexpr int kRadix = 1 << kRadixBits;
 constexpr int kSortPasses = 4;
 constexpr int kSortThreads = 512;                       // 8 wavefronts
-constexpr int kSortKeysPerThread = 16;
-constexpr int kSortTile = kSortThreads * kSortKeysPerThread;  // 8192 keys per workgroup
+// Keys per thread of a sort pass, hence per tile (512 x 4, 8 or 16).  A short sort is bound by the latency of one
+// tile (its ranking, the hop from tile to tile), not by throughput: it gets smaller tiles, so more of them run side by side.
+inline int sort_keys_per_thread(int64_t N) { return N <= (int64_t(1) << 18) ? 4 : N <= (int64_t(1) << 21) ? 8 : 16; }
+inline int64_t sort_tile(int64_t N) { return (int64_t)kSortThreads * sort_keys_per_thread(N); }
+constexpr int kSortHistTile = kSortThreads * 16;         // keys per workgroup of the histogram kernel (up to its grid limit)
 // Small state of one sort, u32 words: [0, 1024) histogram of the four digits; then the per-pass tile
 // tickets, the error flag and the histogram's done counter in one cache line, and the mask of the passes that run in a line of its own.
 constexpr int kSortTicketWord = 1024;
@@ -151,7 +154,7 @@ inline Layout make_layout(int64_t N, int64_t zrows, int64_t batch)
 
     // sort view
     size_t s = o;
-    L.sort_tiles = (N + kSortTile - 1) / kSortTile;
+    L.sort_tiles = (N + sort_tile(N) - 1) / sort_tile(N);
     L.status_words = L.sort_tiles * kRadix;
     L.off_keys0 = s;  s = align_up(s + sizeof(uint32_t) * (size_t)N);
     L.off_keys1 = s;  s = align_up(s + sizeof(uint32_t) * (size_t)N);

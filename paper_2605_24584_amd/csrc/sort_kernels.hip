@@ -211,7 +211,7 @@ k_sort_hist(const float* __restrict__ a, int64_t k, const float* __restrict__ b,
     }
 }
 
-template <typename WORD>
+template <typename WORD, int KPT>
 __global__ void __launch_bounds__(kSortThreads)
 k_onesweep_pass(const float* __restrict__ a, int64_t k, const float* __restrict__ b, float tau,
                 uint32_t* __restrict__ keys0, uint32_t* __restrict__ ids0,      // four distinct buffers
@@ -222,7 +222,7 @@ k_onesweep_pass(const float* __restrict__ a, int64_t k, const float* __restrict_
     constexpr int SH = StatusBits<WORD>::shift;
     constexpr WORD kMask = (WORD(1) << SH) - WORD(1);
     constexpr int WAVES = kSortThreads / 64;
-    constexpr int KPT = kSortKeysPerThread;
+    constexpr int kSortTile = kSortThreads * KPT;
     __shared__ uint32_t whist[WAVES][kRadix];     // per-wave digit counts, then offsets
     __shared__ uint32_t tile_start[kRadix];       // first local slot of each digit
     __shared__ uint32_t delta[kRadix];            // global slot of digit d = delta[d] + local slot
@@ -578,28 +578,32 @@ hipError_t launch_onesweep_sort(const float* a, int64_t k, const float* b, int64
                                 uint32_t* small, unsigned long long* status, hipStream_t st)
 {
     const int64_t N = k + n;
-    const int64_t tiles = (N + kSortTile - 1) / kSortTile;
+    const int64_t tiles = (N + sort_tile(N) - 1) / sort_tile(N);
     const int64_t words = tiles * kRadix;
     unsigned long long* region[2] = {status, status + words};
     LAPLEX_TIMED("sort_hist", st, hipLaunchKernelGGL(k_sort_reset, dim3(1), dim3(1024), 0, st, small));
-    int64_t hgrid = (N + kSortTile - 1) / kSortTile;
+    int64_t hgrid = (N + kSortHistTile - 1) / kSortHistTile;
     if (hgrid > 2048) hgrid = 2048;
     LAPLEX_TIMED("sort_hist", st, hipLaunchKernelGGL(k_sort_hist, dim3((unsigned)hgrid), dim3(kSortThreads), 0, st,
                                                      a, k, b, n, tau, small, region[0], words));
     const dim3 grid((unsigned)tiles), block(kSortThreads);
-    auto passes = [&](auto* r0, auto* r1) {
+    auto passes = [&](auto kernel, auto* r0, auto* r1) {
         using WORD = std::remove_pointer_t<decltype(r0)>;
         WORD* cur[4] = {r0, r1, r0, r1};
         WORD* nxt[4] = {r1, r0, r1, nullptr};
         for (int p = 0; p < kSortPasses; ++p)
-            LAPLEX_TIMED("radix_scatter", st, hipLaunchKernelGGL((k_onesweep_pass<WORD>), grid, block, 0, st,
+            LAPLEX_TIMED("radix_scatter", st, hipLaunchKernelGGL(kernel, grid, block, 0, st,
                          a, k, b, tau, keys0, ids0, keys1, ids1, N, p, (const uint32_t*)small, small, cur[p], nxt[p]));
     };
     if (N <= (int64_t(1) << 30)) {
         uint32_t* r = reinterpret_cast<uint32_t*>(status);
-        passes(r, r + words);
+        switch (sort_keys_per_thread(N)) {
+            case 4:  passes(k_onesweep_pass<uint32_t, 4>, r, r + words); break;
+            case 8:  passes(k_onesweep_pass<uint32_t, 8>, r, r + words); break;
+            default: passes(k_onesweep_pass<uint32_t, 16>, r, r + words); break;
+        }
     } else {
-        passes(region[0], region[1]);
+        passes(k_onesweep_pass<unsigned long long, 16>, region[0], region[1]);
     }
     return hipGetLastError();
 }

@@ -109,7 +109,9 @@ SHAPES = [(1, 1, 1), (5, 1, 2), (1, 6, 1), (37, 53, 3), (100, 9000, 1), (9000, 1
 # ------------------------------------------------------------------ the sort
 
 @pytest.mark.parametrize("kind", KINDS)
-@pytest.mark.parametrize("k,n", [(1, 1), (3, 0), (0, 5), (100, 157), (9000, 8000), (20000, 70001)])
+# the last three: one size for each tile size of the sort passes (2048, 4096 and 8192 pairs), with ragged last tiles
+@pytest.mark.parametrize("k,n", [(1, 1), (3, 0), (0, 5), (100, 157), (9000, 8000), (20000, 70001),
+                                 (130000, 132001), (300001, 400122), (1500000, 1000003)])
 def test_permutation_bit_exact(oracle, kind, k, n):
     if k == 0 or n == 0:
         pytest.skip("apply with an empty side builds no plan")
