@@ -132,13 +132,14 @@ int build_plan(const float* a, int64_t k, const float* b, int64_t n, float tau, 
     uint32_t* keys1 = reinterpret_cast<uint32_t*>(ws + L.off_keys1);
     uint32_t* ids1 = reinterpret_cast<uint32_t*>(ws + L.off_ids1);
     uint32_t* small = reinterpret_cast<uint32_t*>(ws + L.off_sort_small);
+    uint32_t* counters = reinterpret_cast<uint32_t*>(ws + L.off_counters);
     if (both_sorted) {
         LAPLEX_HIP(launch_merge(a, k, b, n, tau, keys0, P.ids, st));
-        LAPLEX_HIP(launch_decay(keys0, keys1, P.ids, ids1, nullptr, P.dh, P.pk, L.N, st));
+        LAPLEX_HIP(launch_decay(keys0, keys1, P.ids, ids1, nullptr, P.dh, P.pk, counters, L.N, st));
     } else {
         LAPLEX_HIP(launch_onesweep_sort(a, k, b, n, tau, keys0, P.ids, keys1, ids1, small,
                                         reinterpret_cast<unsigned long long*>(ws + L.off_status), st));
-        LAPLEX_HIP(launch_decay(keys0, keys1, P.ids, ids1, small, P.dh, P.pk, L.N, st));
+        LAPLEX_HIP(launch_decay(keys0, keys1, P.ids, ids1, small, P.dh, P.pk, counters, L.N, st));
     }
     return LAPLEX_OK;
 }

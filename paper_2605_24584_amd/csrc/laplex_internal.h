@@ -110,6 +110,8 @@ struct Layout {
     size_t off_ids = 0;      // u32[N]    sorted ids
     size_t off_dh = 0;       // f32[N+1]  decay to the previous sorted key, < 0: same key
     size_t off_pk = 0;       // f32[N+2]  sorted anchors, shifted by one, between -inf and +inf sentinels
+    size_t off_counters = 0; // u32[64]   list lengths of the scans: zero between calls (the plan build clears them, every scan
+                             //           clears them again in its last kernel)
     // saved scans
     size_t off_z = 0;        // f32[zrows][batch]
     size_t off_xs = 0;       // f32[N][batch], narrow batches only: the forward's injected rows in sorted order
@@ -124,7 +126,7 @@ struct Layout {
     size_t off_car_f = 0;        // f32[2][tiles][bpad]         carry F
     size_t off_car_e = 0;        // f32[2][tiles][bpad]         carry E
     size_t off_red = 0;          // f32[slabs][N]               per-slab partial row reductions
-    size_t off_lists = 0;        // u32[tiles] tile list, u32[blocks] block list, u32[64] counters (sparse problems)
+    size_t off_lists = 0;        // u32[tiles] tile list, u32[blocks] block list (sparse problems)
     size_t off_blk_flags = 0;    // u32[blocks]                 what each block holds (injected rows, result rows)
     size_t off_blk_f = 0;        // f32[2][blocks][bpad]        carry F into a block from the start of its tile (wide geometry)
     size_t off_blk_e = 0;        // f32[2][blocks][bpad]        the same, strict
@@ -147,6 +149,7 @@ inline Layout make_layout(int64_t N, int64_t zrows, int64_t batch)
     L.off_ids = o;  o = align_up(o + sizeof(uint32_t) * (size_t)N);
     L.off_dh = o;   o = align_up(o + sizeof(float) * (size_t)(N + 1));
     L.off_pk = o;   o = align_up(o + sizeof(float) * (size_t)(N + 2));
+    L.off_counters = o; o = align_up(o + sizeof(uint32_t) * 64);
     L.off_z = o;    o = align_up(o + sizeof(float) * (size_t)zrows * (size_t)batch);
     const size_t stage_bytes = batch <= kStageMaxBatch ? sizeof(float) * (size_t)N * (size_t)batch : 0;
     L.off_xs = o;   o = align_up(o + stage_bytes);
@@ -177,7 +180,7 @@ inline Layout make_layout(int64_t N, int64_t zrows, int64_t batch)
     L.off_car_e = c;      c = align_up(c + per);
     L.off_red = c;
     if (max_slabs > 1) c = align_up(c + sizeof(float) * (size_t)max_slabs * (size_t)N);
-    L.off_lists = c; c = align_up(c + sizeof(uint32_t) * ((size_t)L.max_tiles + (size_t)L.max_blocks + 64));
+    L.off_lists = c; c = align_up(c + sizeof(uint32_t) * ((size_t)L.max_tiles + (size_t)L.max_blocks));
     L.off_blk_flags = c; c = align_up(c + sizeof(uint32_t) * (size_t)L.max_blocks);
     L.off_blk_f = c;     c = align_up(c + per_blk);
     L.off_blk_e = c;     c = align_up(c + per_blk);
@@ -234,9 +237,10 @@ hipError_t launch_merge(const float* a, int64_t k, const float* b, int64_t n, fl
 // dh[0] = dh[N] = 0 (nothing beyond either end).  pk[j+1] = sorted anchor j, pk[0] = -inf, pk[N+1] = +inf.
 // The sorted pairs are in (keys0, ids0), or, after an odd number of radix passes (ghist tells), in
 // (keys1, ids1); in that case the ids are also copied to ids0, where the plan keeps them.
-// ghist == nullptr: the pairs are in buffer 0 (merge path).
+// ghist == nullptr: the pairs are in buffer 0 (merge path).  The last kernel of every plan build: it also clears
+// the scans' list counters (64 words).
 hipError_t launch_decay(const uint32_t* keys0, const uint32_t* keys1, uint32_t* ids0, const uint32_t* ids1,
-                        const uint32_t* ghist, float* dh, float* pk, int64_t N, hipStream_t st);
+                        const uint32_t* ghist, float* dh, float* pk, uint32_t* counters, int64_t N, hipStream_t st);
 
 hipError_t launch_fill(float* p, int64_t rows, int64_t cols, int64_t ld, float v, hipStream_t st);
 hipError_t launch_copy_u32(const uint32_t* src, uint32_t* dst, int64_t count, hipStream_t st);

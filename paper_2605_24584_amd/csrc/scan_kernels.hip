@@ -497,11 +497,6 @@ k_scan_meta(const ScanArgs A)
     }
 }
 
-__global__ void k_zero_counters(uint32_t* counters)
-{
-    if (threadIdx.x < 64) counters[threadIdx.x] = 0u;
-}
-
 // ---------------------------------------------------------------------------
 // reduce: forward and backward summary of every tile, and the tile's flags
 // ---------------------------------------------------------------------------
@@ -1294,6 +1289,8 @@ __global__ void __launch_bounds__(kScanThreads)
 k_scan_down_sparse(const ScanArgs A)
 {
     constexpr int ITEMS = TileRows<VEC>::ITEMS;
+    // the last kernel of a scan: nothing reads the list lengths any more, and the next scan wants them at zero
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < 2) A.counters[threadIdx.x] = 0u;
     const int64_t tile = blockIdx.x;                // the block this workgroup owns
     const int flags = (int)A.blk_flags[tile];
     // result rows, and nothing injected or (wide geometry) at most kFewRows injected rows
@@ -1547,6 +1544,8 @@ __global__ void __launch_bounds__(kStreamWaves * 64)
 k_scan_down_sparse_wide(const ScanArgs A)
 {
     constexpr int VEC = 4, ROWS = 64, CH = 8, NS = kFewRows;
+    // the last kernel of a scan: nothing reads the list lengths any more, and the next scan wants them at zero
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < 2) A.counters[threadIdx.x] = 0u;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int64_t blk = (int64_t)blockIdx.x * kStreamWaves + wave;
@@ -1768,11 +1767,10 @@ void launch_all(const ScanArgs& A, const ScanGeom& g, const std::string& tag, hi
     const int64_t dcap = both_rows < g.blocks ? both_rows : g.blocks;
     const dim3 rgrid((unsigned)(A.reduce_from_list ? rcap : g.tiles), (unsigned)g.slabs);
     const dim3 dgrid((unsigned)(A.down_from_list ? dcap : g.blocks), (unsigned)g.slabs);
-    if (A.reduce_from_list || A.down_from_list) {
+    // (the list lengths are zero here: the plan build cleared them, and the last kernel of every scan does again)
+    if (A.reduce_from_list) {       // else the reduce sees every tile itself and lists the blocks for the downsweep
         const std::string fm = "scan_meta." + tag;
-        LAPLEX_TIMED(fm.c_str(), st, hipLaunchKernelGGL(k_zero_counters, dim3(1), dim3(64), 0, st, A.counters));
-        if (A.reduce_from_list)     // else the reduce sees every tile itself and lists the blocks for the downsweep
-            LAPLEX_TIMED(fm.c_str(), st, hipLaunchKernelGGL(k_scan_meta, dim3((unsigned)((g.tiles + 3) / 4)), dim3(256), 0, st, A));
+        LAPLEX_TIMED(fm.c_str(), st, hipLaunchKernelGGL(k_scan_meta, dim3((unsigned)((g.tiles + 3) / 4)), dim3(256), 0, st, A));
     }
     const dim3 cgrid((unsigned)g.chunks, (unsigned)g.slabs, 2);
     const dim3 tgrid((unsigned)A.batch, 2);
@@ -1845,7 +1843,7 @@ hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStrea
     A.red_partial = reinterpret_cast<float*>(ws + L.off_red);
     A.list_inj = reinterpret_cast<uint32_t*>(ws + L.off_lists);
     A.list_both = A.list_inj + L.max_tiles;
-    A.counters = A.list_both + L.max_blocks;
+    A.counters = reinterpret_cast<uint32_t*>(ws + L.off_counters);
     {   // list-driven launches pay off when the rows that force a heavy tile are few next to the tiles
         const int64_t inj_rows = (int64_t)p.inj_hi - p.inj_lo, res_rows = (int64_t)p.res_hi - p.res_lo;
         const int64_t both = inj_rows < res_rows ? inj_rows : res_rows;

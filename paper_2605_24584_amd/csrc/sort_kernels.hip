@@ -492,8 +492,10 @@ k_merge(const float* __restrict__ a, int64_t k, const float* __restrict__ b, int
 __global__ void __launch_bounds__(256)
 k_decay(const uint32_t* __restrict__ keys0, const uint32_t* __restrict__ keys1,
         uint32_t* __restrict__ ids0, const uint32_t* __restrict__ ids1,
-        const uint32_t* __restrict__ ghist, float* __restrict__ dh, float* __restrict__ pk, int64_t N)
+        const uint32_t* __restrict__ ghist, float* __restrict__ dh, float* __restrict__ pk,
+        uint32_t* __restrict__ counters, int64_t N)
 {
+    if (blockIdx.x == 0 && threadIdx.x < 64) counters[threadIdx.x] = 0u;      // list lengths of the scans that follow
     // after an odd number of passes the sorted pairs sit in buffer 1 (ghist == nullptr: merge path, buffer 0)
     const bool in1 = ghist != nullptr && (__popc(ghist[kSortMaskWord]) & 1);
     const uint32_t* __restrict__ keys = in1 ? keys1 : keys0;
@@ -618,10 +620,10 @@ hipError_t launch_merge(const float* a, int64_t k, const float* b, int64_t n, fl
 }
 
 hipError_t launch_decay(const uint32_t* keys0, const uint32_t* keys1, uint32_t* ids0, const uint32_t* ids1,
-                        const uint32_t* ghist, float* dh, float* pk, int64_t N, hipStream_t st)
+                        const uint32_t* ghist, float* dh, float* pk, uint32_t* counters, int64_t N, hipStream_t st)
 {
     LAPLEX_TIMED("decay", st, hipLaunchKernelGGL(k_decay, dim3(grid_for((N + 5) / 4, 256)), dim3(256), 0, st,
-                                                 keys0, keys1, ids0, ids1, ghist, dh, pk, N));
+                                                 keys0, keys1, ids0, ids1, ghist, dh, pk, counters, N));
     return hipGetLastError();
 }
 
