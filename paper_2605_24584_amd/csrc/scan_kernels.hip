@@ -76,6 +76,7 @@ struct ScanArgs {
     // list_inj is written by the metadata pass; list_both by the metadata pass if it runs, else by the reduce
     int reduce_from_list, down_from_list;
     int few_inj_ok, few_res_ok;   // the block flags kFlagFewInj / kFlagFewRes may be set
+    int pair_out;                 // batch 1: out_p and the row's second output (out_z, else out_red) are the halves of an 8-byte slot
 };
 
 constexpr int kFlagInj = 1, kFlagRes = 2;
@@ -1258,6 +1259,12 @@ k_scan_down(const ScanArgs A)
         }
         const bool is_res = T.id[i] >= A.res_lo && T.id[i] < A.res_hi;
         const int64_t rr = (int64_t)T.id[i] - (int64_t)A.res_lo;
+        if (VEC == 1 && A.pair_out) {      // uniform; batch 1: both outputs of the row with one 8-byte store
+            float second = Z[0];
+            if (want_red) second = vz[i] + wrow[0] * Z[0];
+            if (is_res && col_ok) *reinterpret_cast<float2*>(A.out_p + rr * 2) = make_float2(P[0], second);
+            continue;
+        }
         if (is_res && col_ok) {
             if (kStreamRows<VEC>) {
                 if (A.out_p) store_vec_stream<VEC>(A.out_p + rr * A.ld_p + col0, P);
@@ -1827,6 +1834,11 @@ hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStrea
     A.out_red = p.out_red; A.ld_red = p.ld_red ? p.ld_red : 1; A.w = p.w; A.ld_w = p.ld_w; A.zs = p.zs;
     A.stage = p.stage; A.wstage = p.wstage;
     A.batch = p.batch; A.bpad = L.bpad;
+    {
+        const bool z_pair = p.out_z && !p.out_red && p.out_z == p.out_p + 1 && p.ld_z == 2;
+        const bool red_pair = p.out_red && !p.out_z && p.out_red == p.out_p + 1 && p.ld_red == 2;
+        A.pair_out = p.batch == 1 && p.out_p && p.ld_p == 2 && (z_pair || red_pair) && (reinterpret_cast<uintptr_t>(p.out_p) & 7u) == 0;
+    }
     A.bv = g.bv; A.bv_log2 = ilog2(g.bv); A.rv = g.rv; A.tile_rows = g.tile_rows; A.slabs = g.slabs;
     A.chunk_tiles = g.chunk_tiles;
     A.waves = g.waves;
