@@ -1092,8 +1092,10 @@ __device__ __forceinline__ void load_block_carries(const ScanArgs& A, int64_t bl
 // ---------------------------------------------------------------------------
 // downsweep: tiles that hold both injected and result rows
 // ---------------------------------------------------------------------------
-// WAVES: wavefronts of the workgroup (sizes the LDS buffer); RED: the row reduction is wanted (out_red).
-template <int VEC, bool STRICT, int WAVES, bool RED>
+// WAVES: wavefronts of the workgroup (sizes the LDS buffer); RED: the row reduction is wanted (out_red);
+// ZS: the reduction takes in the saved strict scans (A.zs) -- without them the kernel fits in 128 registers
+// at scalar lanes, and a compute unit holds two workgroups of eight wavefronts instead of one.
+template <int VEC, bool STRICT, int WAVES, bool RED, bool ZS = RED>
 __global__ void __launch_bounds__(WAVES * 64)
 k_scan_down(const ScanArgs A)
 {
@@ -1146,10 +1148,10 @@ k_scan_down(const ScanArgs A)
     // the walks: their rows are asked for together with the injected rows and folded into one number per
     // row.  The weights of the reduction are fetched one row ahead of their use in the backward walk
     // (holding all rows of them would cost ITEMS * VEC registers).
-    float vz[ITEMS];
+    float vz[ZS ? ITEMS : 1];
 #pragma unroll
-    for (int i = 0; i < ITEMS; ++i) vz[i] = 0.0f;
-    if (want_red && A.zs) {                              // uniform
+    for (int i = 0; i < (ZS ? ITEMS : 1); ++i) vz[i] = 0.0f;
+    if (want_red && ZS && A.zs) {                        // uniform
         float zrow[ITEMS][VEC];
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) {
@@ -1159,7 +1161,7 @@ k_scan_down(const ScanArgs A)
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i)
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) vz[i] += v[i][e] * zrow[i][e];
+            for (int e = 0; e < VEC; ++e) vz[ZS ? i : 0] += v[i][e] * zrow[i][e];
     }
     auto fetch_row = [&](int i, float* wrow) {
         const bool ok = col_ok && T.id[i] >= A.res_lo && T.id[i] < A.res_hi;
@@ -1171,6 +1173,15 @@ k_scan_down(const ScanArgs A)
             else load_vec_or_zero<VEC, kStreamRows<VEC>>(wrow, A.w, rr * A.ld_w + col0, ok);
         }
     };
+
+    // scalar lanes can afford all the weights at once (one register a row): their loads go out here, with the
+    // others, instead of one row ahead of their use, where each would be waited for in turn
+    constexpr bool w_ahead = want_red && VEC == 1;
+    float wall[w_ahead ? ITEMS : 1][VEC];
+    if (w_ahead) {
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) fetch_row(i, wall[i]);
+    }
 
     // carries into the block
     float Fc[VEC], Ec[VEC], Rc[VEC], Gc[VEC];
@@ -1238,13 +1249,13 @@ k_scan_down(const ScanArgs A)
     // backward walk with emission
     const int64_t res_rows = (int64_t)A.res_hi - (int64_t)A.res_lo;
     float wnext[VEC];
-    fetch_row(ITEMS - 1, wnext);
+    if (!w_ahead) fetch_row(ITEMS - 1, wnext);
 #pragma unroll
     for (int i = ITEMS - 1; i >= 0; --i) {
         float wrow[VEC];
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) wrow[e] = wnext[e];
-        if (i > 0) fetch_row(i - 1, wnext);
+        for (int e = 0; e < VEC; ++e) wrow[e] = w_ahead ? wall[w_ahead ? i : 0][e] : wnext[e];
+        if (!w_ahead && i > 0) fetch_row(i - 1, wnext);
         const bool h = head_b<VEC>(T, i);
         float P[VEC], Z[VEC], Efi[VEC];
 #pragma unroll
@@ -1261,7 +1272,7 @@ k_scan_down(const ScanArgs A)
         const int64_t rr = (int64_t)T.id[i] - (int64_t)A.res_lo;
         if (VEC == 1 && A.pair_out) {      // uniform; batch 1: both outputs of the row with one 8-byte store
             float second = Z[0];
-            if (want_red) second = vz[i] + wrow[0] * Z[0];
+            if (want_red) second = (ZS ? vz[ZS ? i : 0] : 0.0f) + wrow[0] * Z[0];
             if (is_res && col_ok) *reinterpret_cast<float2*>(A.out_p + rr * 2) = make_float2(P[0], second);
             continue;
         }
@@ -1275,7 +1286,7 @@ k_scan_down(const ScanArgs A)
             }
         }
         if (want_red) {
-            float acc = vz[i];
+            float acc = ZS ? vz[ZS ? i : 0] : 0.0f;
 #pragma unroll
             for (int e = 0; e < VEC; ++e) acc += wrow[e] * Z[e];     // wrow is 0 off the result rows
             emit_row_sum(A, acc, bv, c, is_res, rr, res_rows);
@@ -1802,8 +1813,16 @@ void launch_all(const ScanArgs& A, const ScanGeom& g, const std::string& tag, hi
     {
         const bool red = STRICT && A.out_red != nullptr;
         auto go = [&](auto kernel) { LAPLEX_TIMED(fd.c_str(), st, hipLaunchKernelGGL(kernel, dgrid, bblock, 0, st, A)); };
-        if (g.waves == kScanWaves) { if (red) go(k_scan_down<VEC, STRICT, kScanWaves, STRICT>); else go(k_scan_down<VEC, STRICT, kScanWaves, false>); }
-        else { if (red) go(k_scan_down<VEC, STRICT, kBlockWavesNarrow, STRICT>); else go(k_scan_down<VEC, STRICT, kBlockWavesNarrow, false>); }
+        const bool zs = red && A.zs != nullptr;
+        if (g.waves == kScanWaves) {
+            if (zs) go(k_scan_down<VEC, STRICT, kScanWaves, STRICT, STRICT>);
+            else if (red) go(k_scan_down<VEC, STRICT, kScanWaves, STRICT, false>);
+            else go(k_scan_down<VEC, STRICT, kScanWaves, false, false>);
+        } else {
+            if (zs) go(k_scan_down<VEC, STRICT, kBlockWavesNarrow, STRICT, STRICT>);
+            else if (red) go(k_scan_down<VEC, STRICT, kBlockWavesNarrow, STRICT, false>);
+            else go(k_scan_down<VEC, STRICT, kBlockWavesNarrow, false, false>);
+        }
     }
     if (VEC == 4 && g.sub_shift) {
         const dim3 sgrid((unsigned)((g.blocks + kStreamWaves - 1) / kStreamWaves), (unsigned)g.slabs);
