@@ -17,7 +17,7 @@ constexpr int kSortPasses = 4;
 constexpr int kSortThreads = 512;                       // 8 wavefronts
 // Keys per thread of a sort pass, hence per tile (512 x 4, 8 or 16).  A short sort is bound by the latency of one
 // tile (its ranking, the hop from tile to tile), not by throughput: it gets smaller tiles, so more of them run side by side.
-inline int sort_keys_per_thread(int64_t N) { return N <= (int64_t(1) << 18) ? 4 : N <= (int64_t(1) << 21) ? 8 : 16; }
+inline int sort_keys_per_thread(int64_t N) { return N <= (int64_t(1) << 18) ? 4 : N <= (int64_t(5) << 18) ? 8 : 16; }
 inline int64_t sort_tile(int64_t N) { return (int64_t)kSortThreads * sort_keys_per_thread(N); }
 constexpr int kSortHistTile = kSortThreads * 16;         // keys per workgroup of the histogram kernel (up to its grid limit)
 // Small state of one sort, u32 words: [0, 1024) histogram of the four digits; then the per-pass tile
