@@ -1001,7 +1001,7 @@ k_spine_down(const ScanArgs A)
     float F[VEC], E[VEC], Fc[VEC], Ec[VEC];
 #pragma unroll
     for (int e = 0; e < VEC; ++e) { F[e] = E[e] = Fc[e] = Ec[e] = 0.0f; }
-    if (col_ok) {
+    if (col_ok && A.l2.count > 1) {     // a single chunk starts from zero: the upper spine kernels have not run
         const int64_t o = ((int64_t)dir * A.l2.count + chunk) * A.bpad + col0;
         load_vec<VEC>(Fc, A.l2.car_f + o);
         if (STRICT) load_vec<VEC>(Ec, A.l2.car_e + o);
@@ -1802,8 +1802,10 @@ void launch_all(const ScanArgs& A, const ScanGeom& g, const std::string& tag, hi
     } else {
         LAPLEX_TIMED(fr.c_str(), st, hipLaunchKernelGGL((k_scan_reduce<VEC, STRICT>), rgrid, bblock, 0, st, A));
     }
-    LAPLEX_TIMED(fs.c_str(), st, hipLaunchKernelGGL((k_spine_reduce<VEC, STRICT>), cgrid, block, 0, st, A));
-    LAPLEX_TIMED(fs.c_str(), st, hipLaunchKernelGGL((k_spine_top<STRICT>), tgrid, dim3(kSpineThreads), 0, st, A.l2, A.bpad));
+    if (g.chunks > 1) {     // one chunk: nothing to carry between chunks, the tiles' carries come from k_spine_down alone
+        LAPLEX_TIMED(fs.c_str(), st, hipLaunchKernelGGL((k_spine_reduce<VEC, STRICT>), cgrid, block, 0, st, A));
+        LAPLEX_TIMED(fs.c_str(), st, hipLaunchKernelGGL((k_spine_top<STRICT>), tgrid, dim3(kSpineThreads), 0, st, A.l2, A.bpad));
+    }
     LAPLEX_TIMED(fs.c_str(), st, hipLaunchKernelGGL((k_spine_down<VEC, STRICT>), cgrid, block, 0, st, A));
     if (VEC == 4 && A.few_res_ok) {
         const std::string ff = "scan_down_fewres." + tag;
