@@ -19,7 +19,9 @@ constexpr int kSortThreads = 512;                       // 8 wavefronts
 // tile (its ranking, the hop from tile to tile), not by throughput: it gets smaller tiles, so more of them run side by side.
 inline int sort_keys_per_thread(int64_t N) { return N <= (int64_t(1) << 18) ? 4 : N <= (int64_t(5) << 18) ? 8 : 16; }
 inline int64_t sort_tile(int64_t N) { return (int64_t)kSortThreads * sort_keys_per_thread(N); }
-constexpr int kSortHistTile = kSortThreads * 16;         // keys per workgroup of the histogram kernel (up to its grid limit)
+// keys per workgroup of the histogram kernel (up to its grid limit): fewer for a short sort, whose histogram is bound by
+// the latency of one workgroup; more for a long one, where every workgroup adds its 1024 counts to the global ones
+inline int64_t sort_hist_tile(int64_t N) { return (int64_t)kSortThreads * (N <= (int64_t(1) << 18) ? 4 : 16); }
 // Small state of one sort, u32 words: [0, 1024) histogram of the four digits; then the per-pass tile
 // tickets, the error flag and the histogram's done counter in one cache line, and the mask of the passes that run in a line of its own.
 constexpr int kSortTicketWord = 1024;

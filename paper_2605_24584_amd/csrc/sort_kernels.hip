@@ -584,7 +584,7 @@ hipError_t launch_onesweep_sort(const float* a, int64_t k, const float* b, int64
     const int64_t words = tiles * kRadix;
     unsigned long long* region[2] = {status, status + words};
     LAPLEX_TIMED("sort_hist", st, hipLaunchKernelGGL(k_sort_reset, dim3(1), dim3(1024), 0, st, small));
-    int64_t hgrid = (N + kSortHistTile - 1) / kSortHistTile;
+    int64_t hgrid = (N + sort_hist_tile(N) - 1) / sort_hist_tile(N);
     if (hgrid > 2048) hgrid = 2048;
     LAPLEX_TIMED("sort_hist", st, hipLaunchKernelGGL(k_sort_hist, dim3((unsigned)hgrid), dim3(kSortThreads), 0, st,
                                                      a, k, b, n, tau, small, region[0], words));
