@@ -263,6 +263,17 @@ def paper_sweep(args, torch, np, B, synth):
     x = synth.normal(synth.stream_seed(13, synth.STREAM_X), n).reshape(n, 1)
     print(json.dumps({"experiment": "irregular anchors N(0,1), single product", "n": n, "k": k, "batch": 1,
                       "forward_ms": forward_ms(a, b, x)}), flush=True)
+    # App. "Weighted Gram matrix": A diag(d) A^T with output dimension 1024, inner dimension 2^10 .. 2^20
+    for e in range(10, 21, 2):
+        n, k = 1 << e, 1024
+        a = synth.uniform(synth.stream_seed(14, synth.STREAM_A) + e, k, 0.0, n / 64.0)
+        b = synth.uniform(synth.stream_seed(14, synth.STREAM_B) + e, n, 0.0, n / 64.0)
+        d = (np.abs(synth.normal(synth.stream_seed(14, synth.STREAM_X) + e, n)) + np.float32(0.5)).astype(np.float32)
+        ws = torch.empty(B.laplex_wgram_workspace_bytes(k, n), dtype=torch.uint8, device="cuda")
+        da, db, dd = dev(a), dev(b), dev(d)
+        m = torch.empty(k, k, device="cuda")
+        print(json.dumps({"experiment": "weighted Gram matrix, output dimension 1024", "n": n, "k": k,
+                          "wgram_ms": timed(lambda: B.laplex_wgram(da, db, dd, m, ws, 0))}), flush=True)
 
 
 def main():
