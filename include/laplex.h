@@ -287,6 +287,17 @@ int laplex_wgram_f64(const float* a, int64_t k, const float* b, int64_t n, const
 int laplex_get_perm(const void* ws, size_t ws_bytes, int64_t count, uint32_t* perm_out,
                     laplex_stream_t stream);
 
+/*
+ * Verification hook: write the status of the plan in `ws` (count as above) to the
+ * device word status_out: 0 = built normally; 1 = a tile of the radix sort gave
+ * up waiting for its predecessors (the wait is bounded so that the device can
+ * never hang; the plan, and every result computed from it, is then invalid and
+ * the call that built it should be repeated).  Plans of at most 8192 positions
+ * and merged plans never wait and always read 0.
+ */
+int laplex_get_plan_status(const void* ws, size_t ws_bytes, int64_t count, uint32_t* status_out,
+                           laplex_stream_t stream);
+
 /* Host: static text for a status code. */
 const char* laplex_status_string(int status);
 

@@ -31,7 +31,7 @@ LAPLEX_MAX_MERGED = 4294967294
 
 EXPORTS = (
     "laplex_workspace_bytes", "laplex_apply", "laplex_apply_backward", "laplex_gram",
-    "laplex_gram_backward", "laplex_get_perm", "laplex_status_string", "laplex_last_hip_error",
+    "laplex_gram_backward", "laplex_get_perm", "laplex_get_plan_status", "laplex_status_string", "laplex_last_hip_error",
     "laplex_profile_begin", "laplex_profile_end", "laplex_scan_tile_rows",
     "laplex_phased_workspace_bytes", "laplex_phased_apply", "laplex_phased_apply_backward",
     "laplex_apply_tau", "laplex_apply_backward_tau", "laplex_gram_tau", "laplex_gram_backward_tau",
@@ -68,6 +68,7 @@ def lib() -> ctypes.CDLL:
         L.laplex_gram.argtypes = [_P, _I, _P, _I, _I, _P, _I, _P, _Z, _U, _P]
         L.laplex_gram_backward.argtypes = [_P, _I, _P, _I, _P, _I, _I, _P, _I, _P, _P, _Z, _U, _P]
         L.laplex_get_perm.argtypes = [_P, _Z, _I, _P, _P]
+        L.laplex_get_plan_status.argtypes = [_P, _Z, _I, _P, _P]
         L.laplex_status_string.argtypes = [ctypes.c_int]
         L.laplex_status_string.restype = ctypes.c_char_p
         L.laplex_last_hip_error.argtypes = []
@@ -92,8 +93,9 @@ def lib() -> ctypes.CDLL:
         L.laplex_mix_apply.argtypes = [_P, _P, _P, _I, _I, _I, _P, _I, _I, _P, _I, _P, _Z, _U, _P]
         L.laplex_mix_apply_backward.argtypes = [_P, _P, _P, _I, _I, _I, _P, _I, _P, _I, _I, _P, _I, _P, _P, _P,
                                                 _P, _Z, _U, _P]
-        for name in EXPORTS[:6] + EXPORTS[8:]:
-            getattr(L, name).restype = ctypes.c_int
+        for name in EXPORTS:
+            if name not in ("laplex_status_string", "laplex_last_hip_error"):
+                getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -164,6 +166,11 @@ def laplex_gram_backward(a, x, gy, gx, ga, ws, flags: int = 0, stream=None) -> N
 def laplex_get_perm(ws, count: int, perm_out, stream=None) -> None:
     """perm_out: int32 tensor of `count` elements (bit pattern of the u32 ids)."""
     _check(lib().laplex_get_perm(_ptr(ws), ws.numel(), count, _ptr(perm_out), _stream(stream)))
+
+
+def laplex_get_plan_status(ws, count: int, status_out, stream=None) -> None:
+    """status_out: int32 tensor of one element: 0 = the plan was built normally, 1 = the radix sort gave up a wait."""
+    _check(lib().laplex_get_plan_status(_ptr(ws), ws.numel(), count, _ptr(status_out), _stream(stream)))
 
 
 def laplex_status_string(status: int) -> str:

@@ -955,6 +955,24 @@ int laplex_get_perm(const void* ws, size_t ws_bytes, int64_t count, uint32_t* pe
     return LAPLEX_OK;
 }
 
+int laplex_get_plan_status(const void* ws, size_t ws_bytes, int64_t count, uint32_t* status_out, laplex_stream_t stream)
+{
+    if (count < 0 || count > LAPLEX_MAX_MERGED) return LAPLEX_ERR_SIZE;
+    if (!status_out) return LAPLEX_ERR_NULL;
+    if (misaligned(status_out, 4)) return LAPLEX_ERR_ALIGN;
+    if (count <= kSmallMax) {       // sorted by counting ranks: nothing ever waits
+        LAPLEX_HIP(launch_fill(reinterpret_cast<float*>(status_out), 1, 1, 1, 0.0f, stream));
+        return LAPLEX_OK;
+    }
+    if (!ws) return LAPLEX_ERR_NULL;
+    if (misaligned(ws, 256)) return LAPLEX_ERR_ALIGN;
+    const Layout L = make_layout(count, 0, 1);          // the plan's offsets depend on the merged length only
+    if (ws_bytes < L.off_counters + sizeof(uint32_t) * 64) return LAPLEX_ERR_WORKSPACE;
+    const uint32_t* word = reinterpret_cast<const uint32_t*>(static_cast<const char*>(ws) + L.off_counters) + kPlanStatusWord;
+    LAPLEX_HIP(launch_copy_u32(word, status_out, 1, stream));
+    return LAPLEX_OK;
+}
+
 const char* laplex_status_string(int status)
 {
     switch (status) {

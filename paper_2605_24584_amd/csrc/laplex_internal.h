@@ -29,6 +29,7 @@ constexpr int kSortErrorWord = 1028;
 constexpr int kSortDoneWord = 1029;                     // histogram workgroups that have added their counts
 constexpr int kSortMaskWord = 1056;
 constexpr int kSortSmallWords = 1088;
+constexpr int kPlanStatusWord = 32;                     // in the plan's 64 counter words: the sort's error flag, kept with the plan
 constexpr int kMergeThreads = 256;
 constexpr int kMergePerThread = 8;
 constexpr int kMergeTile = kMergeThreads * kMergePerThread;
@@ -112,8 +113,8 @@ struct Layout {
     size_t off_ids = 0;      // u32[N]    sorted ids
     size_t off_dh = 0;       // f32[N+1]  decay to the previous sorted key, < 0: same key
     size_t off_pk = 0;       // f32[N+2]  sorted anchors, shifted by one, between -inf and +inf sentinels
-    size_t off_counters = 0; // u32[64]   list lengths of the scans: zero between calls (the plan build clears them, every scan
-                             //           clears them again in its last kernel)
+    size_t off_counters = 0; // u32[64]   words 0, 1: list lengths of the scans: zero between calls (the plan build clears them,
+                             //           every scan clears them again in its last kernel); word kPlanStatusWord: 1 if the sort gave up a wait
     // saved scans
     size_t off_z = 0;        // f32[zrows][batch]
     size_t off_xs = 0;       // f32[N][batch], narrow batches only: the forward's injected rows in sorted order

@@ -495,7 +495,9 @@ k_decay(const uint32_t* __restrict__ keys0, const uint32_t* __restrict__ keys1,
         const uint32_t* __restrict__ ghist, float* __restrict__ dh, float* __restrict__ pk,
         uint32_t* __restrict__ counters, int64_t N)
 {
-    if (blockIdx.x == 0 && threadIdx.x < 64) counters[threadIdx.x] = 0u;      // list lengths of the scans that follow
+    // list lengths of the scans that follow; and the sort's error flag moves to the plan (the sort's own words are scratch)
+    if (blockIdx.x == 0 && threadIdx.x < 64)
+        counters[threadIdx.x] = (threadIdx.x == kPlanStatusWord && ghist != nullptr) ? ghist[kSortErrorWord] : 0u;
     // after an odd number of passes the sorted pairs sit in buffer 1 (ghist == nullptr: merge path, buffer 0)
     const bool in1 = ghist != nullptr && (__popc(ghist[kSortMaskWord]) & 1);
     const uint32_t* __restrict__ keys = in1 ? keys1 : keys0;

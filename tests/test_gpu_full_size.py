@@ -98,6 +98,9 @@ def test_projection_full_size_sampled(oracle):
     B.laplex_apply_backward(da, db, dx, dg, gx, ga, gb, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
     perm = torch.empty(k + n, dtype=torch.int32, device="cuda")
     B.laplex_get_perm(ws, k + n, perm)
+    status = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    B.laplex_get_plan_status(ws, k + n, status)
+    assert int(status.item()) == 0, "a tile of the radix sort gave up waiting for its predecessors"
     torch.cuda.synchronize()
     assert np.array_equal(perm.cpu().numpy().view(np.uint32), oracle.merged_permutation(a, b))
     y, gx, ga, gb = y.cpu().numpy(), gx.cpu().numpy(), ga.cpu().numpy(), gb.cpu().numpy()
@@ -126,6 +129,9 @@ def test_tie_heavy_full_size(oracle):
     B.laplex_apply_backward(da, db, dx, dg, gx, ga, gb, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
     perm = torch.empty(k + n, dtype=torch.int32, device="cuda")
     B.laplex_get_perm(ws, k + n, perm)
+    status = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    B.laplex_get_plan_status(ws, k + n, status)
+    assert int(status.item()) == 0, "a tile of the radix sort gave up waiting for its predecessors"
     torch.cuda.synchronize()
     assert np.array_equal(perm.cpu().numpy().view(np.uint32), oracle.merged_permutation(a, b))   # bit-exact
     ref, tol = oracle.apply_scan(a, b, x)
@@ -150,6 +156,9 @@ def test_gram_images_full_size(oracle):
     B.laplex_gram_backward(da, dx, dg, gx, ga, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
     perm = torch.empty(n, dtype=torch.int32, device="cuda")
     B.laplex_get_perm(ws, n, perm)
+    status = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    B.laplex_get_plan_status(ws, n, status)
+    assert int(status.item()) == 0, "a tile of the radix sort gave up waiting for its predecessors"
     torch.cuda.synchronize()
     assert np.array_equal(perm.cpu().numpy().view(np.uint32), oracle.merged_permutation(a))
     cols = np.arange(0, batch, 8)        # 8 of the 64 columns, every row, for y and gx
@@ -192,6 +201,9 @@ def test_billion_scale(oracle):
         f"device footprint {peak / 2**30:.1f} GiB")
     perm = torch.empty(k + n, dtype=torch.int32, device="cuda")
     B.laplex_get_perm(ws, k + n, perm)
+    status = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    B.laplex_get_plan_status(ws, k + n, status)
+    assert int(status.item()) == 0, "a tile of the radix sort gave up waiting for its predecessors"
     torch.cuda.synchronize()
     del ws
     check_permutation_properties(perm, torch.cat([da, db]))

@@ -62,6 +62,13 @@ def gpu_backward(a, b, x, g, flags=0, ws=None, want=(True, True, True)):
     return tuple(None if t is None else t.cpu().numpy() for t in (gx, ga, gb))
 
 
+def gpu_plan_status(ws, count):
+    out = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    B.laplex_get_plan_status(ws, count, out)
+    torch.cuda.synchronize()
+    return int(out.item())
+
+
 def gpu_perm(ws, count):
     out = torch.empty(count, dtype=torch.int32, device="cuda")
     B.laplex_get_perm(ws, count, out)
@@ -120,6 +127,7 @@ def test_permutation_bit_exact(oracle, kind, k, n):
     x = r.normal(size=(n, 1)).astype(np.float32)
     _, ws = gpu_apply(a, b, x)
     assert np.array_equal(gpu_perm(ws, k + n), oracle.merged_permutation(a, b))
+    assert gpu_plan_status(ws, k + n) == 0       # no tile of the sort gave up waiting for its predecessors
 
 
 @pytest.mark.parametrize("off_a,off_b", [(1, 0), (2, 3), (3, 1), (0, 2)])

@@ -132,6 +132,14 @@ def test_get_perm_rejects_bad_arguments(L):
     assert f(FAKE, 0, 0, None, None) == B.LAPLEX_OK
 
 
+def test_get_plan_status_rejects_bad_arguments(L):
+    f = L.laplex_get_plan_status
+    assert f(FAKE, 1 << 40, -1, FAKE, None) == B.LAPLEX_ERR_SIZE
+    assert f(FAKE, 1 << 40, 100000, None, None) == B.LAPLEX_ERR_NULL
+    assert f(None, 1 << 40, 100000, FAKE, None) == B.LAPLEX_ERR_NULL
+    assert f(FAKE, 1000, 100000, FAKE, None) == B.LAPLEX_ERR_WORKSPACE
+
+
 def test_binding_raises_with_status(L):
     with pytest.raises(B.LaplexError) as e:
         B.laplex_workspace_bytes(-1, 0, 0)
