@@ -1734,6 +1734,20 @@ k_rowdot_narrow(const float* __restrict__ u, int64_t ldu, int64_t op_u, const fl
     // rows of 4 or 8 floats that start on 16-byte boundaries are read with 128-bit loads (same summation order)
     const bool v4 = batch % 4 == 0 && ldu % 4 == 0 && ldv % 4 == 0 &&
                     ((reinterpret_cast<uintptr_t>(u) | reinterpret_cast<uintptr_t>(v)) & 15u) == 0;
+    // two plain vectors (batch 1, contiguous): four rows per lane and load
+    const bool vec1 = batch == 1 && ldu == 1 && ldv == 1 &&
+                      ((reinterpret_cast<uintptr_t>(u) | reinterpret_cast<uintptr_t>(v) | reinterpret_cast<uintptr_t>(out)) & 15u) == 0;
+    if (vec1) {
+        const int64_t quads = rows >> 2;
+        for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < quads; q += stride) {
+            const float4 x = reinterpret_cast<const float4*>(u)[q];
+            const float4 y = reinterpret_cast<const float4*>(v)[q];
+            reinterpret_cast<float4*>(out)[q] = make_float4(x.x * y.x, x.y * y.y, x.z * y.z, x.w * y.w);
+        }
+        const int64_t r = 4 * quads + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;      // the last rows
+        if (r < rows) out[r] = u[r] * v[r];
+        return;
+    }
     for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < rows; r += stride) {
         float s = 0.0f;
         if (v4) {
