@@ -535,6 +535,10 @@ k_scan_reduce(const ScanArgs A)
         mine |= (T.id[i] >= A.inj_lo && T.id[i] < A.inj_hi) ? kFlagInj : 0;
         mine |= (T.id[i] >= A.res_lo && T.id[i] < A.res_hi) ? kFlagRes : 0;
     }
+    // the injected rows are asked for before the flags meet: the gathers travel while the workgroup waits at the
+    // barriers (a row that is not injected is not loaded, it reads as zero)
+    float v[ITEMS][VEC];
+    load_injected<VEC, kStreamRows<VEC>>(A, T, col0, col_ok, v);
     __syncthreads();
     if (c == 0 && mine) atomicOr(&tile_flags, mine);
     __syncthreads();
@@ -543,19 +547,10 @@ k_scan_reduce(const ScanArgs A)
         if (A.down_from_list && !A.reduce_from_list && tile_flags == (kFlagInj | kFlagRes))
             A.list_both[atomicAdd(&A.counters[1], 1u)] = (uint32_t)tile;
     }
-    float v[ITEMS][VEC];
-    if (tile_flags & kFlagInj) {     // uniform: a tile with nothing injected reads no data rows
-        load_injected<VEC, kStreamRows<VEC>>(A, T, col0, col_ok, v);
-        if (A.stage && col_ok) {     // uniform in A.stage
-#pragma unroll
-            for (int i = 0; i < ITEMS; ++i)
-                if (T.id[i] != 0xFFFFFFFFu) store_vec<VEC>(A.stage + (row0 + i) * A.batch + col0, v[i]);
-        }
-    } else {
+    if ((tile_flags & kFlagInj) && A.stage && col_ok) {     // uniform: the downsweep finds the tile's rows in sorted order
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i)
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) v[i][e] = 0.0f;
+            if (T.id[i] != 0xFFFFFFFFu) store_vec<VEC>(A.stage + (row0 + i) * A.batch + col0, v[i]);
     }
 
     {
