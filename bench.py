@@ -365,6 +365,25 @@ def main():
         with open(traffic_file) as fh:
             roofline["traffic"] = json.load(fh).get("hbm_bytes_per_launch")
 
+    # measured ceilings beside the nominal peak (outside the timed region): a kernel that only moves the same rows
+    # of the same matrices, in the order of the plan (x's rows as the sorted anchors visit them)
+    perm = torch.empty(k + n, dtype=torch.int32, device="cuda")
+    B.laplex_get_perm(ws, k + n, perm)
+    rows_of_x = (perm[(perm >= k)] - k).contiguous()       # input positions of the plan -> rows of x, in sorted order
+    ceil = {}
+    for name, dst, moved in (("copy_rows_GBps", gx, 2), ("read_rows_GBps", None, 1)):
+        for _ in range(3):
+            B.laplex_diag_move_rows(dx, dst, rows_of_x)
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        for _ in range(10):
+            B.laplex_diag_move_rows(dx, dst, rows_of_x)
+        torch.cuda.synchronize()
+        ceil[name] = round(moved * 4 * n * batch / ((time.perf_counter() - c0) / 10) / 1e9, 1)
+    roofline["measured_ceiling"] = dict(ceil, note="laplex_diag_move_rows on x (and gx) in the plan's row order: "
+                                        "the dominant kernel reads x and writes gx (copy), the forward reduce reads x")
+    roofline["frac_of_copy_ceiling"] = round(achieved / ceil["copy_rows_GBps"], 4) if ceil["copy_rows_GBps"] else None
+
     # per-phase split of one step (separate loops, outside the timed region)
     phases = {}
     for name, fn in (

@@ -329,6 +329,23 @@ int laplex_profile_end(double* total_ms, int64_t* launches);
  */
 int laplex_scan_tile_rows(int64_t batch, int wide, int64_t* rows);
 
+/*
+ * Diagnostics: the device's ceiling for a kernel that does nothing but move
+ * whole rows at scattered positions, the access pattern of the heavy scan
+ * kernels at wide batches (rows of the batch-minor matrices in sorted-anchor
+ * order).  Row r of the launch is row row_ids[r] of both matrices:
+ *   dst != NULL:  dst[row_ids[r]*cols + c] = src[row_ids[r]*cols + c]   (read + write)
+ *   dst == NULL:  the rows are read and summed into nothing              (read only)
+ * src, dst: (max id + 1) x cols floats, contiguous, 16-byte aligned; cols a
+ * multiple of 4; row_ids: `rows` device words, each below the number of rows of
+ * src and dst (the caller guarantees it; a permutation gives every row once).
+ * Nontemporal 16-byte loads and stores, one wavefront per row, eight rows in
+ * flight per wavefront.  A benchmark times it to put a measured ceiling beside
+ * the nominal HBM peak; it is not part of the method.
+ */
+int laplex_diag_move_rows(const float* src, float* dst, const uint32_t* row_ids, int64_t rows, int64_t cols,
+                          laplex_stream_t stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -32,7 +32,7 @@ LAPLEX_MAX_MERGED = 4294967294
 EXPORTS = (
     "laplex_workspace_bytes", "laplex_apply", "laplex_apply_backward", "laplex_gram",
     "laplex_gram_backward", "laplex_get_perm", "laplex_get_plan_status", "laplex_status_string", "laplex_last_hip_error",
-    "laplex_profile_begin", "laplex_profile_end", "laplex_scan_tile_rows",
+    "laplex_profile_begin", "laplex_profile_end", "laplex_scan_tile_rows", "laplex_diag_move_rows",
     "laplex_phased_workspace_bytes", "laplex_phased_apply", "laplex_phased_apply_backward",
     "laplex_apply_tau", "laplex_apply_backward_tau", "laplex_gram_tau", "laplex_gram_backward_tau",
     "laplex_wgram_workspace_bytes", "laplex_wgram",
@@ -76,6 +76,7 @@ def lib() -> ctypes.CDLL:
         L.laplex_profile_begin.argtypes = [ctypes.c_char_p]
         L.laplex_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
         L.laplex_scan_tile_rows.argtypes = [_I, ctypes.c_int, ctypes.POINTER(_I)]
+        L.laplex_diag_move_rows.argtypes = [_P, _P, _P, _I, _I, _P]
         L.laplex_phased_workspace_bytes.argtypes = [_I, _I, _I, ctypes.POINTER(_Z)]
         L.laplex_phased_apply.argtypes = [_P, _P, _I, _P, _P, _I, _P, _I, _I, _P, _I, _P, _Z, _U, _P]
         L.laplex_phased_apply_backward.argtypes = [_P, _P, _I, _P, _P, _I, _P, _I, _P, _I, _I,
@@ -171,6 +172,11 @@ def laplex_get_perm(ws, count: int, perm_out, stream=None) -> None:
 def laplex_get_plan_status(ws, count: int, status_out, stream=None) -> None:
     """status_out: int32 tensor of one element: 0 = the plan was built normally, 1 = the radix sort gave up a wait."""
     _check(lib().laplex_get_plan_status(_ptr(ws), ws.numel(), count, _ptr(status_out), _stream(stream)))
+
+
+def laplex_diag_move_rows(src, dst, row_ids, stream=None) -> None:
+    """Diagnostics: rows row_ids[r] of src (rows x cols, contiguous) are read (dst None) or copied to the same rows of dst."""
+    _check(lib().laplex_diag_move_rows(_ptr(src), _ptr(dst), _ptr(row_ids), row_ids.numel(), src.shape[1], _stream(stream)))
 
 
 def laplex_status_string(status: int) -> str:

@@ -999,6 +999,17 @@ int laplex_scan_tile_rows(int64_t batch, int wide, int64_t* rows)
     return LAPLEX_OK;
 }
 
+int laplex_diag_move_rows(const float* src, float* dst, const uint32_t* row_ids, int64_t rows, int64_t cols,
+                          laplex_stream_t stream)
+{
+    if (rows < 0 || cols < 0 || cols % 4 != 0) return LAPLEX_ERR_SIZE;
+    if (rows == 0 || cols == 0) return LAPLEX_OK;
+    if (!src || !row_ids) return LAPLEX_ERR_NULL;
+    if (misaligned(src, 16) || (dst && misaligned(dst, 16)) || misaligned(row_ids, 4)) return LAPLEX_ERR_ALIGN;
+    LAPLEX_HIP(launch_diag_move_rows(src, dst, row_ids, rows, cols, stream));
+    return LAPLEX_OK;
+}
+
 int laplex_profile_begin(const char* family)
 {
     if (!family) return LAPLEX_ERR_NULL;

@@ -351,4 +351,7 @@ hipError_t launch_rowdot_ops(const float* u, int64_t ldu, int64_t op_u, const fl
 hipError_t launch_rowdot(const float* u, int64_t ldu, const float* v, int64_t ldv,
                          int64_t rows, int64_t batch, float* out, hipStream_t st);
 
+// Diagnostics: rows row_ids[r] of src are read (dst == nullptr) or copied to the same rows of dst.
+hipError_t launch_diag_move_rows(const float* src, float* dst, const uint32_t* row_ids, int64_t rows, int64_t cols, hipStream_t st);
+
 }  // namespace laplex

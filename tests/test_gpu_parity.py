@@ -808,3 +808,19 @@ def test_regular_grid_equal_decays(oracle, gap, k, n, batch):
     gx, ga, gb = gpu_backward(a, b, x, g, flags=B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN, ws=ws)
     assert_close("y", y, ref, tol)
     assert_close("gx", gx, rgx, tgx); assert_close("ga", ga, rga, tga); assert_close("gb", gb, rgb, tgb)
+
+
+# ------------------------------------------------------------------ diagnostics
+
+def test_diag_move_rows_copies_the_named_rows():
+    r = np.random.default_rng(77)
+    rows, cols = 5000, 256
+    src = torch.from_numpy(r.normal(size=(rows, cols)).astype(np.float32)).cuda()
+    ids = torch.from_numpy(r.permutation(rows)[:3001].astype(np.int32)).cuda()       # a ragged number of rows, each once
+    dst = torch.zeros(rows, cols, device="cuda")
+    B.laplex_diag_move_rows(src, dst, ids)
+    B.laplex_diag_move_rows(src, None, ids)                                          # read only: must just run
+    torch.cuda.synchronize()
+    want = torch.zeros(rows, cols, device="cuda")
+    want[ids.long()] = src[ids.long()]
+    assert torch.equal(dst, want)

@@ -140,6 +140,16 @@ def test_get_plan_status_rejects_bad_arguments(L):
     assert f(FAKE, 1000, 100000, FAKE, None) == B.LAPLEX_ERR_WORKSPACE
 
 
+def test_diag_move_rows_rejects_bad_arguments(L):
+    f = L.laplex_diag_move_rows
+    assert f(FAKE, FAKE, FAKE, -1, 256, None) == B.LAPLEX_ERR_SIZE
+    assert f(FAKE, FAKE, FAKE, 10, 255, None) == B.LAPLEX_ERR_SIZE
+    assert f(None, FAKE, FAKE, 10, 256, None) == B.LAPLEX_ERR_NULL
+    assert f(FAKE, FAKE, None, 10, 256, None) == B.LAPLEX_ERR_NULL
+    assert f(FAKE + 4, FAKE, FAKE, 10, 256, None) == B.LAPLEX_ERR_ALIGN
+    assert f(FAKE, FAKE, FAKE, 0, 256, None) == B.LAPLEX_OK
+
+
 def test_binding_raises_with_status(L):
     with pytest.raises(B.LaplexError) as e:
         B.laplex_workspace_bytes(-1, 0, 0)
