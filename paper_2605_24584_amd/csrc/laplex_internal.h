@@ -54,7 +54,7 @@ constexpr int kItemsVec4 = 8;    // rows per row-lane when a lane holds 4 column
 // A batch row narrower than this many floats is gathered once per problem and staged in sorted
 // order: a random read of a few bytes costs a whole 128-byte line of HBM traffic.
 constexpr int kStageMaxBatch = 8;
-constexpr int kSpineItems = 8;    // tile summaries per row-lane in the chunked spine kernels
+constexpr int kSpineItems = 8;    // tile summaries per row-lane in the chunked spine kernels, at most (ScanGeom::spine_items)
 constexpr int kSpineThreads = 1024;
 
 // The rows a downsweep workgroup owns are a "block" (tile_rows of them).  The spine works on
@@ -74,7 +74,9 @@ struct ScanGeom {
     int sub_shift;    // log2(blocks per tile)
     int64_t blocks;   // ceil(N / tile_rows)
     int64_t tiles;    // ceil(blocks / 2^sub_shift)
-    int chunk_tiles;  // tiles summarised by one workgroup of the chunked spine: kScanWaves * rv * kSpineItems
+    int spine_items;  // tile summaries per row-lane of the spine kernels: 8, or 4 when a summary is a whole wavefront wide
+                      // (rv = 1): twice the workgroups, each done sooner
+    int chunk_tiles;  // tiles summarised by one workgroup of the chunked spine: kScanWaves * rv * spine_items
     int64_t chunks;   // ceil(tiles / chunk_tiles)
 };
 
@@ -95,7 +97,8 @@ inline ScanGeom scan_geom(int64_t N, int64_t batch, int vec)
     g.tile_rows = g.waves * g.rv * g.items;
     g.blocks = (N + g.tile_rows - 1) / g.tile_rows;
     g.tiles = (g.blocks + (int64_t(1) << g.sub_shift) - 1) >> g.sub_shift;
-    g.chunk_tiles = kScanWaves * g.rv * kSpineItems;
+    g.spine_items = g.rv == 1 ? kSpineItems / 2 : kSpineItems;
+    g.chunk_tiles = kScanWaves * g.rv * g.spine_items;
     g.chunks = (g.tiles + g.chunk_tiles - 1) / g.chunk_tiles;
     return g;
 }

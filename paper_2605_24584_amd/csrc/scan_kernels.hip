@@ -58,7 +58,7 @@ struct ScanArgs {
     float* out_red; int64_t ld_red; const float* w; int64_t ld_w; const float* zs;
     float* stage; const float* wstage;   // sorted-order copies of the injected rows / of the weights (narrow batches)
     int64_t batch, bpad;
-    int bv, bv_log2, rv, tile_rows, slabs, chunk_tiles;
+    int bv, bv_log2, rv, tile_rows, slabs, chunk_tiles, spine_items;
     // A downsweep workgroup owns a block of tile_rows rows; the spine's tiles (level 1) are
     // 2^sub_shift consecutive blocks, spine_rows rows (sub_shift > 0 in the wide geometry only).
     int sub_shift; int64_t spine_rows, blocks;
@@ -878,7 +878,7 @@ k_spine_reduce(const ScanArgs A)
     const int c = lane & (bv - 1), r = lane >> A.bv_log2;
     const int dir = blockIdx.z;
     const int64_t chunk = blockIdx.x;
-    const int64_t q0 = chunk * A.chunk_tiles + (int64_t)(wave * rv + r) * kSpineItems;
+    const int64_t q0 = chunk * A.chunk_tiles + (int64_t)(wave * rv + r) * A.spine_items;
     const int64_t col0 = ((int64_t)blockIdx.y * bv + c) * VEC;
     const bool col_ok = col0 < A.batch;
 
@@ -886,7 +886,7 @@ k_spine_reduce(const ScanArgs A)
 #pragma unroll
     for (int i = 0; i < kSpineItems; ++i) {
         const int64_t q = q0 + i;
-        if (q < A.l1.count) {
+        if (i < A.spine_items && q < A.l1.count) {
             const int64_t t = dir == 0 ? q : A.l1.count - 1 - q;
             m = seg_compose<VEC, STRICT>(m, load_level_seg<VEC, STRICT, true>(A.l1, dir, t, A.bpad, col0, col_ok));
         }
@@ -971,7 +971,7 @@ k_spine_down(const ScanArgs A)
     const int c = lane & (bv - 1), r = lane >> A.bv_log2;
     const int dir = blockIdx.z;
     const int64_t chunk = blockIdx.x;
-    const int64_t q0 = chunk * A.chunk_tiles + (int64_t)(wave * rv + r) * kSpineItems;
+    const int64_t q0 = chunk * A.chunk_tiles + (int64_t)(wave * rv + r) * A.spine_items;
     const int64_t col0 = ((int64_t)blockIdx.y * bv + c) * VEC;
     const bool col_ok = col0 < A.batch;
 
@@ -981,7 +981,7 @@ k_spine_down(const ScanArgs A)
     for (int i = 0; i < kSpineItems; ++i) {
         const int64_t q = q0 + i;
         segs[i] = seg_identity<VEC, STRICT>();
-        if (q < A.l1.count) {
+        if (i < A.spine_items && q < A.l1.count) {
             const int64_t t = dir == 0 ? q : A.l1.count - 1 - q;
             segs[i] = load_level_seg<VEC, STRICT, true>(A.l1, dir, t, A.bpad, col0, col_ok);
         }
@@ -1020,7 +1020,7 @@ k_spine_down(const ScanArgs A)
 #pragma unroll
     for (int i = 0; i < kSpineItems; ++i) {
         const int64_t q = q0 + i;
-        if (q < A.l1.count) {
+        if (i < A.spine_items && q < A.l1.count) {
             const int64_t t = dir == 0 ? q : A.l1.count - 1 - q;
             if (col_ok) {
                 const int64_t o = ((int64_t)dir * A.l1.count + t) * A.bpad + col0;
@@ -1870,7 +1870,7 @@ hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStrea
         A.pair_out = p.batch == 1 && p.out_p && p.ld_p == 2 && (z_pair || red_pair) && (reinterpret_cast<uintptr_t>(p.out_p) & 7u) == 0;
     }
     A.bv = g.bv; A.bv_log2 = ilog2(g.bv); A.rv = g.rv; A.tile_rows = g.tile_rows; A.slabs = g.slabs;
-    A.chunk_tiles = g.chunk_tiles;
+    A.chunk_tiles = g.chunk_tiles; A.spine_items = g.spine_items;
     A.waves = g.waves;
     A.sub_shift = g.sub_shift; A.spine_rows = (int64_t)g.tile_rows << g.sub_shift; A.blocks = g.blocks;
     A.blk_flags = reinterpret_cast<uint32_t*>(ws + L.off_blk_flags);
