@@ -195,7 +195,7 @@ int check_phased_sizes(int64_t k, int64_t n, int64_t batch)
 // the fp64 entry point share it.
 // ----------------------------------------------------------------------------
 struct Wgram64Layout {
-    size_t inner = 0, off_u = 0, off_v = 0, off_w = 0, off_summ = 0, total = 0;
+    size_t inner = 0, off_u = 0, off_v = 0, off_w = 0, off_summ = 0, off_pb = 0, total = 0;
 };
 
 Wgram64Layout wgram64_layout(int64_t k, int64_t n)
@@ -206,7 +206,8 @@ Wgram64Layout wgram64_layout(int64_t k, int64_t n)
     G.off_u = o;    o = align_up(o + sizeof(double) * (size_t)k);
     G.off_v = o;    o = align_up(o + sizeof(double) * (size_t)k);
     G.off_w = o;    o = align_up(o + sizeof(double) * (size_t)k);
-    G.off_summ = o; o = align_up(o + sizeof(double) * 5 * (size_t)wgram_tiles(k + n));
+    G.off_summ = o; o = align_up(o + sizeof(double) * 6 * (size_t)wgram_tiles(k + n));
+    G.off_pb = o;   o = align_up(o + sizeof(double) * (size_t)n);
     G.total = o;
     return G;
 }
@@ -737,7 +738,7 @@ int laplex_wgram(const float* a, int64_t k, const float* b, int64_t n, const flo
     LAPLEX_CHECK(build_wgram_plan(a, k, b, n, L, P, w, flags, st));
     LAPLEX_HIP(launch_wgram_f32(P.ids, P.pk, a, d, k, k + n, reinterpret_cast<double*>(w + G.off_summ),
                                 reinterpret_cast<double*>(w + G.off_u), reinterpret_cast<double*>(w + G.off_v),
-                                reinterpret_cast<double*>(w + G.off_w), m, ldm, st));
+                                reinterpret_cast<double*>(w + G.off_w), reinterpret_cast<double*>(w + G.off_pb), m, ldm, st));
     return LAPLEX_OK;
 }
 
@@ -782,7 +783,7 @@ int laplex_wgram_f64(const float* a, int64_t k, const float* b, int64_t n, const
     LAPLEX_CHECK(build_wgram_plan(a, k, b, n, L, P, w, flags, st));
     LAPLEX_HIP(launch_wgram_f64(P.ids, P.pk, a, d, k, k + n, reinterpret_cast<double*>(w + G.off_summ),
                                 reinterpret_cast<double*>(w + G.off_u), reinterpret_cast<double*>(w + G.off_v),
-                                reinterpret_cast<double*>(w + G.off_w), m, ldm, st));
+                                reinterpret_cast<double*>(w + G.off_w), reinterpret_cast<double*>(w + G.off_pb), m, ldm, st));
     return LAPLEX_OK;
 }
 

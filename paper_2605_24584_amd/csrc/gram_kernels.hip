@@ -8,6 +8,11 @@
 //   U = sum over middle anchors before p of  d_t exp(-2 (a - b_t))   (forward scan, doubled decay),
 //   V = sum over middle anchors after  p of  d_t exp(-2 (b_t - a))   (backward scan, doubled decay),
 //   W = sum over middle anchors before p of  d_t                     (plain prefix sum).
+// W enters only through differences W_hi - W_lo, and two Gram anchors with no middle anchor between them must get
+// the SAME number (their entry can be as small as exp(-2 gap) of the nearest middle anchor, next to which a
+// rounding difference of two prefix sums associated differently is enormous).  So the prefix sum is stored once per
+// middle anchor (Pb[t] = d_0 + .. + d_t in merged order), a Gram anchor records how many middle anchors precede it
+// (an exact integer scan), and W is picked up afterwards as Pb[count - 1].
 // The regions are taken by POSITION in the stable merged order, so a middle anchor equal to a Gram
 // anchor lies in exactly one of them, and each region's closed form holds at a tie by continuity.
 // Only non-positive numbers are ever exponentiated (the theorem's interval statistic e^{2(a_i - b_t)}
@@ -138,7 +143,7 @@ __device__ __forceinline__ double decay_right(const Tile64& T, int i, bool live)
     __shared__ uint32_t t_id[kWTile];                   \
     const Tile64 T{t_w, t_p, t_id}
 
-// summ: [5][tiles] = forward (D, S), backward (D, S), sum of the weights
+// summ: [6][tiles] = forward (D, S), backward (D, S), sum of the weights, number of middle anchors
 template <typename TW>
 __global__ void __launch_bounds__(kWThreads)
 k_g64_tiles(const uint32_t* __restrict__ ids, const float* __restrict__ pk, const TW* __restrict__ d,
@@ -148,7 +153,7 @@ k_g64_tiles(const uint32_t* __restrict__ ids, const float* __restrict__ pk, cons
     const int64_t base = (int64_t)blockIdx.x * kWTile;
     stage_tile64(T, ids, pk, d, k, N, base);
     Pair64 f{1.0, 0.0}, b{1.0, 0.0};
-    double wsum = 0.0;
+    double wsum = 0.0, middle = 0.0;
     const int cf = threadIdx.x * kWItems, cb = (kWThreads - 1 - threadIdx.x) * kWItems;
 #pragma unroll
     for (int i = 0; i < kWItems; ++i) {
@@ -157,36 +162,41 @@ k_g64_tiles(const uint32_t* __restrict__ ids, const float* __restrict__ pk, cons
         f = Pair64{f.D * df, df * f.S + T.w[u]};
         b = Pair64{b.D * db, db * b.S + T.w[v]};
         wsum += T.w[u];
+        middle += (base + u < N && T.id[u] >= k) ? 1.0 : 0.0;       // counts stay exact in fp64
     }
     Pair64 tf, tb;
-    double tw;
+    double tw, tc;
     block_exclusive_scan_pair(f, &tf);
     block_exclusive_scan_pair(b, &tb);
     block_exclusive_scan_f64(wsum, &tw);
+    block_exclusive_scan_f64(middle, &tc);
     if (threadIdx.x == 0) {
         summ[0 * tiles + blockIdx.x] = tf.D; summ[1 * tiles + blockIdx.x] = tf.S;
         summ[2 * tiles + blockIdx.x] = tb.D; summ[3 * tiles + blockIdx.x] = tb.S;
         summ[4 * tiles + blockIdx.x] = tw;
+        summ[5 * tiles + blockIdx.x] = tc;
     }
 }
 
 // In place: summ[1][t] <- forward state entering tile t, summ[3][t] <- backward state entering it (from
-// the right), summ[4][t] <- weights before it.  One workgroup, kWThreads tiles at a time.
+// the right), summ[4][t] <- weights before it, summ[5][t] <- middle anchors before it.  One workgroup, kWThreads tiles at a time.
 __global__ void __launch_bounds__(kWThreads)
 k_g64_spine(double* __restrict__ summ, int64_t tiles)
 {
-    double cF = 0.0, cW = 0.0;
+    double cF = 0.0, cW = 0.0, cC = 0.0;
     for (int64_t c0 = 0; c0 < tiles; c0 += kWThreads) {
         const int64_t t = c0 + threadIdx.x;
         const bool ok = t < tiles;
         Pair64 v{ok ? summ[0 * tiles + t] : 1.0, ok ? summ[1 * tiles + t] : 0.0}, tot;
         const Pair64 ex = block_exclusive_scan_pair(v, &tot);
-        double tw;
+        double tw, tc;
         const double w = ok ? summ[4 * tiles + t] : 0.0;
         const double ew = block_exclusive_scan_f64(w, &tw);
-        if (ok) { summ[1 * tiles + t] = ex.D * cF + ex.S; summ[4 * tiles + t] = cW + ew; }
+        const double ec = block_exclusive_scan_f64(ok ? summ[5 * tiles + t] : 0.0, &tc);
+        if (ok) { summ[1 * tiles + t] = ex.D * cF + ex.S; summ[4 * tiles + t] = cW + ew; summ[5 * tiles + t] = cC + ec; }
         cF = tot.D * cF + tot.S;
         cW += tw;
+        cC += tc;
     }
     double cB = 0.0;
     const int64_t chunks = (tiles + kWThreads - 1) / kWThreads;
@@ -204,13 +214,13 @@ template <typename TW>
 __global__ void __launch_bounds__(kWThreads)
 k_g64_down(const uint32_t* __restrict__ ids, const float* __restrict__ pk, const TW* __restrict__ d,
            uint32_t k, int64_t N, int64_t tiles, const double* __restrict__ summ,
-           double* __restrict__ U, double* __restrict__ V, double* __restrict__ W)
+           double* __restrict__ U, double* __restrict__ V, double* __restrict__ W, double* __restrict__ Pb)
 {
     LAPLEX_TILE64_LDS;
     const int64_t base = (int64_t)blockIdx.x * kWTile;
     stage_tile64(T, ids, pk, d, k, N, base);
     Pair64 f{1.0, 0.0}, b{1.0, 0.0};
-    double wsum = 0.0;
+    double wsum = 0.0, middle = 0.0;
     const int cf = threadIdx.x * kWItems, cb = (kWThreads - 1 - threadIdx.x) * kWItems;
 #pragma unroll
     for (int i = 0; i < kWItems; ++i) {
@@ -219,24 +229,39 @@ k_g64_down(const uint32_t* __restrict__ ids, const float* __restrict__ pk, const
         f = Pair64{f.D * df, df * f.S + T.w[u]};
         b = Pair64{b.D * db, db * b.S + T.w[v]};
         wsum += T.w[u];
+        middle += (base + u < N && T.id[u] >= k) ? 1.0 : 0.0;
     }
     Pair64 tot;
-    double tw;
+    double tw, tc;
     const Pair64 ef = block_exclusive_scan_pair(f, &tot);
     const Pair64 eb = block_exclusive_scan_pair(b, &tot);
     double F = ef.D * summ[1 * tiles + blockIdx.x] + ef.S;
     double R = eb.D * summ[3 * tiles + blockIdx.x] + eb.S;
     double run = summ[4 * tiles + blockIdx.x] + block_exclusive_scan_f64(wsum, &tw);
+    int64_t before = (int64_t)(summ[5 * tiles + blockIdx.x] + block_exclusive_scan_f64(middle, &tc));   // middle anchors before this lane's rows
 #pragma unroll
     for (int i = 0; i < kWItems; ++i) {
         const int u = cf + i, v = cb + kWItems - 1 - i;
         F = decay_left(T, u, base + u < N) * F + T.w[u];
         R = decay_right(T, v, base + v < N) * R + T.w[v];
         const uint32_t iu = T.id[u], iv = T.id[v];
-        if (iu < k) { U[iu] = F; W[iu] = run; }       // a Gram anchor carries no weight: F, R are the sums strictly beside it
+        // a Gram anchor carries no weight: F, R are the sums strictly beside it; its W is picked up from Pb
+        // afterwards (k_g64_pick), here it records how many middle anchors precede it
+        if (iu < k) { U[iu] = F; W[iu] = (double)before; }
         if (iv < k) V[iv] = R;
         run += T.w[u];
+        if (base + u < N && iu >= k) { Pb[before] = run; ++before; }      // the prefix sum up to and including this middle anchor
     }
+}
+
+// W[i] <- the prefix sum at the last middle anchor before Gram anchor i (0 if there is none)
+__global__ void __launch_bounds__(256)
+k_g64_pick(double* __restrict__ W, const double* __restrict__ Pb, int64_t k)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= k) return;
+    const int64_t c = (int64_t)W[i];
+    W[i] = c > 0 ? Pb[c - 1] : 0.0;
 }
 
 // The fill: one thread per four consecutive columns of one row; lo / hi of a pair by (anchor, index), the
@@ -277,14 +302,16 @@ int64_t wgram_tiles(int64_t N);
 
 template <typename TW, typename TM>
 hipError_t launch_wgram_t(const uint32_t* ids, const float* pk, const float* a, const TW* d, int64_t k, int64_t N,
-                          double* summ, double* U, double* V, double* W, TM* M, int64_t ldm, hipStream_t st)
+                          double* summ, double* U, double* V, double* W, double* Pb, TM* M, int64_t ldm, hipStream_t st)
 {
     const int64_t tiles = wgram_tiles(N);
     LAPLEX_TIMED("wgram_scan", st, hipLaunchKernelGGL((k_g64_tiles<TW>), dim3((unsigned)tiles), dim3(kWThreads), 0, st,
                                                       ids, pk, d, (uint32_t)k, N, tiles, summ));
     LAPLEX_TIMED("wgram_scan", st, hipLaunchKernelGGL(k_g64_spine, dim3(1), dim3(kWThreads), 0, st, summ, tiles));
     LAPLEX_TIMED("wgram_scan", st, hipLaunchKernelGGL((k_g64_down<TW>), dim3((unsigned)tiles), dim3(kWThreads), 0, st,
-                                                      ids, pk, d, (uint32_t)k, N, tiles, (const double*)summ, U, V, W));
+                                                      ids, pk, d, (uint32_t)k, N, tiles, (const double*)summ, U, V, W, Pb));
+    LAPLEX_TIMED("wgram_scan", st, hipLaunchKernelGGL(k_g64_pick, dim3((unsigned)((k + 255) / 256)), dim3(256), 0, st,
+                                                      W, (const double*)Pb, k));
     const int vec4 = (reinterpret_cast<uintptr_t>(M) & 15u) == 0 && ldm % 4 == 0;
     const dim3 grid((unsigned)k, (unsigned)((k + 1023) / 1024));     // rows on x (up to 2^31 - 1), column chunks on y
     LAPLEX_TIMED("wgram_fill", st, hipLaunchKernelGGL((k_wgram_fill<TM>), grid, dim3(256), 0, st,
@@ -295,15 +322,15 @@ hipError_t launch_wgram_t(const uint32_t* ids, const float* pk, const float* a, 
 int64_t wgram_tiles(int64_t N) { return (N + kWTile - 1) / kWTile; }
 
 hipError_t launch_wgram_f32(const uint32_t* ids, const float* pk, const float* a, const float* d, int64_t k, int64_t N,
-                            double* summ, double* U, double* V, double* W, float* M, int64_t ldm, hipStream_t st)
+                            double* summ, double* U, double* V, double* W, double* Pb, float* M, int64_t ldm, hipStream_t st)
 {
-    return launch_wgram_t<float, float>(ids, pk, a, d, k, N, summ, U, V, W, M, ldm, st);
+    return launch_wgram_t<float, float>(ids, pk, a, d, k, N, summ, U, V, W, Pb, M, ldm, st);
 }
 
 hipError_t launch_wgram_f64(const uint32_t* ids, const float* pk, const float* a, const double* d, int64_t k, int64_t N,
-                            double* summ, double* U, double* V, double* W, double* M, int64_t ldm, hipStream_t st)
+                            double* summ, double* U, double* V, double* W, double* Pb, double* M, int64_t ldm, hipStream_t st)
 {
-    return launch_wgram_t<double, double>(ids, pk, a, d, k, N, summ, U, V, W, M, ldm, st);
+    return launch_wgram_t<double, double>(ids, pk, a, d, k, N, summ, U, V, W, Pb, M, ldm, st);
 }
 
 }  // namespace laplex

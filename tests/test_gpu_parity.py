@@ -632,7 +632,10 @@ def gpu_wgram(a, b, d, flags=0, ws=None, ldm=None):
 
 
 WGRAM_SHAPES = [(1, 1), (2, 3), (5, 1), (1, 700), (37, 53), (100, 9000), (9000 // 8, 100), (1024, 40000), (333, 70001),
-                (700, 700), (3, 150000)]
+                (700, 700), (3, 150000),
+                # runs of equal Gram anchors longer than a lane's 16 positions, with hardly any middle anchor between:
+                # entries far from every middle anchor are tiny and take the difference of two prefix sums exactly
+                (1072, 3), (4500, 40)]
 
 
 @pytest.mark.parametrize("weights", ["signed", "positive"])
@@ -740,7 +743,7 @@ def test_mix_subsets_and_empty(oracle):
 
 @pytest.mark.parametrize("weights", ["signed", "positive"])
 @pytest.mark.parametrize("kind", ["uniform", "ties", "all_equal", "huge_gaps", "clustered"])
-@pytest.mark.parametrize("k,n", [(1, 1), (5, 1), (37, 53), (100, 9000), (1024, 40000), (333, 70001), (3, 150000)])
+@pytest.mark.parametrize("k,n", [(1, 1), (5, 1), (37, 53), (100, 9000), (1024, 40000), (333, 70001), (3, 150000), (1072, 3), (4500, 40)])
 def test_weighted_gram_matrix_fp64(oracle, weights, kind, k, n):
     """The fp64 instantiation: fp32 anchors, fp64 weights and arithmetic.  Tolerance 1e-12 T + 1e-300:
     an entry sums a few thousand non-negligible terms, each a product of at most a few hundred fp64 decays
