@@ -96,6 +96,17 @@ def anchors(kind, r, k, n):
         a, b = 1.0 + r.uniform(0, 1, k), 1.0 + r.uniform(0, 1, n)
     elif kind == "small_ints":      # few mantissa bits: the two low key bytes are zero for every anchor
         a, b = r.integers(0, 8, k).astype(np.float64), r.integers(0, 8, n).astype(np.float64)
+    elif kind == "extreme":         # denormals to 3e38, both signs, exact zeros of both signs (the random-shape tests use it)
+        def draw(m):
+            lo, hi = [(-45, -30), (-45, 38), (30, 38.5), (-3, 3), (-45, 2)][r.integers(5)]
+            with np.errstate(over="ignore", under="ignore"):
+                v = (10.0 ** r.uniform(lo, hi, m)) * r.choice([-1.0, 1.0], m)
+                v[r.integers(0, m, max(1, m // 10))] = 0.0
+                v[r.integers(0, m, max(1, m // 10))] = -0.0
+                v = v.astype(np.float32)
+            v[~np.isfinite(v)] = np.float32(3.0e38)
+            return v
+        a, b = draw(k), draw(n)
     else:
         raise KeyError(kind)
     return a.astype(np.float32), b.astype(np.float32)

@@ -35,7 +35,7 @@ def test_apply_and_gram_random_shapes(oracle, seed):
     r = np.random.default_rng(9100 + seed)
     for lo, hi in ((1, 13.3), (13.0, 16.0)):          # the two-launch path for small problems; the large path
         k, n, batch = draw_shape(r, lo, hi, 3e8)
-        kind = T.KINDS[r.integers(len(T.KINDS))]
+        kind = (T.KINDS + ["extreme"])[r.integers(len(T.KINDS) + 1)]
         body(T.test_apply_forward_backward)(oracle, kind, k, n, batch)
         body(T.test_gram_forward_backward)(oracle, kind, min(k, 9000), batch)
 
