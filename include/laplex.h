@@ -259,7 +259,9 @@ int laplex_mix_apply_backward(const float* a, const float* b, const float* w, in
  * set: merge instead of sort), LAPLEX_REUSE_PLAN (the workspace holds the plan of
  * an earlier laplex_wgram call with the same a, b).  n == 0 gives M = 0.  The
  * workspace is laplex_wgram_workspace_bytes(k, n); its front is a plan of the
- * anchors 2a, 2b (laplex_get_perm reads it).  No gradients are provided.
+ * anchors 2a, 2b (laplex_get_perm reads it): anchors beyond 1.7e38 in magnitude
+ * overflow when doubled and are unsupported like infinite ones.  No gradients
+ * are provided.
  */
 int laplex_wgram_workspace_bytes(int64_t k, int64_t n, size_t* out /* host */);
 
