@@ -542,11 +542,7 @@ k_scan_reduce(const ScanArgs A)
     __syncthreads();
     if (c == 0 && mine) atomicOr(&tile_flags, mine);
     __syncthreads();
-    if (tid == 0 && blockIdx.y == 0) {      // in this geometry a tile is one block
-        A.blk_flags[tile] = (uint32_t)tile_flags;
-        if (A.down_from_list && !A.reduce_from_list && tile_flags == (kFlagInj | kFlagRes))
-            A.list_both[atomicAdd(&A.counters[1], 1u)] = (uint32_t)tile;
-    }
+    if (tid == 0 && blockIdx.y == 0) A.blk_flags[tile] = (uint32_t)tile_flags;      // in this geometry a tile is one block
     if ((tile_flags & kFlagInj) && A.stage && col_ok) {     // uniform: the downsweep finds the tile's rows in sorted order
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i)
@@ -644,7 +640,7 @@ k_scan_reduce_wide(const ScanArgs A)
     constexpr int VEC = 4, ROWS = 64, CH = 8;
     static_assert(kScanWaves * kItemsVec4 == ROWS, "the wide geometry (one row-lane per wavefront) has 64 rows per block");
     __shared__ WaveSegs<VEC> W;
-    __shared__ int tile_flags;
+    __shared__ int tile_flags, blk_flag[kWideWaves];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int64_t col0 = ((int64_t)blockIdx.y * 64 + lane) * VEC;
@@ -720,13 +716,10 @@ k_scan_reduce_wide(const ScanArgs A)
                 if ((inj_mask >> (c * CH)) & 0xFFull) fold(c * CH, buf[c & 1]);
             }
         }
-        if (lane == 0 && blockIdx.y == 0) {
-            A.blk_flags[blk] = (uint32_t)flags;
-            if (A.down_from_list && !A.reduce_from_list && listed_block(flags))
-                A.list_both[atomicAdd(&A.counters[1], 1u)] = (uint32_t)blk;
-        }
         if (lane == 0 && flags) atomicOr(&tile_flags, flags & (kFlagInj | kFlagRes));
     }
+    // The blocks' flags leave as one 32-byte store per tile, below, instead of a 4-byte store per block.
+    if (lane == 0) blk_flag[wave] = flags;
 
     // The eight block summaries meet in LDS: each wavefront folds the ones before (after) its own into
     // the state its block starts from when the tile starts from zero; the last (first) one also takes
@@ -740,6 +733,8 @@ k_scan_reduce_wide(const ScanArgs A)
     put_wave_seg<VEC, STRICT>(W, 1, wave, lane, mb);
     __syncthreads();
     const int tflags = tile_flags;
+    if (wave == 0 && lane < kWideWaves && blockIdx.y == 0 && (tile << kWideSubShift) + lane < A.blocks)
+        A.blk_flags[(tile << kWideSubShift) + lane] = (uint32_t)blk_flag[lane];
 
     float F[VEC], E[VEC], R[VEC], G[VEC];
 #pragma unroll
@@ -847,11 +842,7 @@ k_scan_reduce_wave(const ScanArgs A)
     f = wave_scan<true, VEC, STRICT>(f, lane, bv, rv);
     b = wave_scan<false, VEC, STRICT>(b, lane, bv, rv);
     const int tile_flags = (__ballot(mine & kFlagInj) ? kFlagInj : 0) | (__ballot(mine & kFlagRes) ? kFlagRes : 0);
-    if (lane == 0 && blockIdx.y == 0) {                       // in this geometry a tile is one block
-        A.blk_flags[tile] = (uint32_t)tile_flags;
-        if (A.down_from_list && !A.reduce_from_list && tile_flags == (kFlagInj | kFlagRes))
-            A.list_both[atomicAdd(&A.counters[1], 1u)] = (uint32_t)tile;
-    }
+    if (lane == 0 && blockIdx.y == 0) A.blk_flags[tile] = (uint32_t)tile_flags;     // in this geometry a tile is one block
     const bool sw = c == 0 && blockIdx.y == 0;
     const bool vec_ok = col_ok && (tile_flags & kFlagInj);   // zero vectors are never fetched: not written either
     if (r == rv - 1) {
@@ -971,6 +962,32 @@ k_spine_down(const ScanArgs A)
     const int c = lane & (bv - 1), r = lane >> A.bv_log2;
     const int dir = blockIdx.z;
     const int64_t chunk = blockIdx.x;
+
+    // The list of the blocks the heavy downsweep must visit, when the reduce saw every tile itself (with a
+    // metadata pass the list is already there): one workgroup per chunk compacts its blocks' flags, slots from
+    // a counter in LDS, and takes its stretch of the list with ONE atomic on the shared counter (instead of one
+    // per listed block from inside the reduce, each waited for by a wavefront on its way to the tile's barrier).
+    if (A.down_from_list && !A.reduce_from_list && dir == 0 && blockIdx.y == 0) {
+        __shared__ uint32_t l_count, l_base;
+        constexpr int kMaxPer = 8;                               // a chunk has at most 4096 blocks
+        if (tid == 0) l_count = 0u;
+        __syncthreads();
+        const int64_t b0 = (chunk * A.chunk_tiles) << A.sub_shift;
+        const int64_t nb = (int64_t)A.chunk_tiles << A.sub_shift;
+        uint32_t slot[kMaxPer];
+#pragma unroll
+        for (int q = 0; q < kMaxPer; ++q) {
+            const int64_t o = (int64_t)q * kScanThreads + tid, b = b0 + o;
+            const bool listed = o < nb && b < A.blocks && listed_block((int)A.blk_flags[b]);
+            slot[q] = listed ? atomicAdd(&l_count, 1u) : 0xFFFFFFFFu;
+        }
+        __syncthreads();
+        if (tid == 0) l_base = l_count ? atomicAdd(&A.counters[1], l_count) : 0u;
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < kMaxPer; ++q)
+            if (slot[q] != 0xFFFFFFFFu) A.list_both[l_base + slot[q]] = (uint32_t)(b0 + (int64_t)q * kScanThreads + tid);
+    }
     const int64_t q0 = chunk * A.chunk_tiles + (int64_t)(wave * rv + r) * A.spine_items;
     const int64_t col0 = ((int64_t)blockIdx.y * bv + c) * VEC;
     const bool col_ok = col0 < A.batch;
