@@ -54,3 +54,79 @@ def test_widened_entry_points_random_shapes(oracle, seed):
     kind, weights = kinds[r.integers(len(kinds))], str(r.choice(["signed", "positive"]))
     body(T.test_weighted_gram_matrix)(oracle, weights, kind, k, n)
     body(T.test_weighted_gram_matrix_fp64)(oracle, weights, kind, k, n)
+
+
+def padded(v, ld):
+    """(rows, cols) values in a buffer with leading dimension ld, NaN in the padding."""
+    buf = T.torch.full((v.shape[0], ld), float("nan"), device="cuda")
+    view = buf[:, : v.shape[1]]
+    view.copy_(T.dev(v))
+    return buf, view
+
+
+@pytest.mark.parametrize("seed", range(60))
+def test_flags_strides_and_subsets_random(oracle, seed):
+    """Sorted-anchor flags (merge path / one flag alone), leading dimensions, gradient subsets, saved scans, a fresh or a
+    reused plan in the backward, and the plan reused for another batch size."""
+    B, torch = T.B, T.torch
+    r = np.random.default_rng(9300 + seed)
+    kind = T.KINDS[r.integers(len(T.KINDS))]
+    total = int(2 ** r.uniform(2, 16.2))
+    k = int(r.integers(1, max(2, total))); n = max(1, total - k)
+    if r.integers(4) == 0:
+        k = int(r.integers(1, 50)); n = max(1, total - k)
+    batch = int(r.choice([1, 2, 3, 4, 5, 8, 12, 16, 33, 64, 128, 256, 260]))
+    while k * n * batch > 2e8 and batch > 1:
+        batch = max(1, batch // 2)
+    a, b = T.anchors(kind, r, k, n)
+    flags = 0
+    if r.integers(3) == 0:
+        a.sort(); b.sort(); flags |= B.LAPLEX_A_SORTED | B.LAPLEX_B_SORTED
+    elif r.integers(3) == 0:
+        a.sort(); flags |= B.LAPLEX_A_SORTED
+    if r.integers(2):
+        flags |= B.LAPLEX_SAVE_SCANS
+    ldx, ldy = batch + int(r.choice([0, 0, 1, 3, 4, 8])), batch + int(r.choice([0, 0, 1, 4]))
+    ldg, ldgx = batch + int(r.choice([0, 0, 2, 4])), batch + int(r.choice([0, 0, 4, 5]))
+    x = r.normal(size=(n, batch)).astype(np.float32); g = r.normal(size=(k, batch)).astype(np.float32)
+    small = k * n * batch <= 4e7
+    ws = T.workspace(k, n, batch)
+    da, db = T.dev(a), T.dev(b)
+    _, dx = padded(x, ldx); _, dg = padded(g, ldg)
+    ybuf = torch.full((k, ldy), float("nan"), device="cuda"); y = ybuf[:, :batch]
+    B.laplex_apply(da, db, dx, y, ws, flags)
+    torch.cuda.synchronize()
+    ref, tol = (oracle.apply_brute if small else oracle.apply_scan)(a, b, x)
+    T.assert_close("y", y.cpu().numpy(), ref, tol)
+    assert ldy == batch or bool(torch.isnan(ybuf[:, batch:]).all())
+    assert np.array_equal(T.gpu_perm(ws, k + n), oracle.merged_permutation(a, b))
+    want = [bool(r.integers(4)) for _ in range(3)]
+    if not any(want):
+        want[0] = True
+    gxbuf = torch.full((n, ldgx), float("nan"), device="cuda") if want[0] else None
+    gx = gxbuf[:, :batch] if want[0] else None
+    ga = torch.full((k,), float("nan"), device="cuda") if want[1] else None
+    gb = torch.full((n,), float("nan"), device="cuda") if want[2] else None
+    bflags = flags | (B.LAPLEX_REUSE_PLAN if r.integers(2) else 0)
+    if not bflags & B.LAPLEX_REUSE_PLAN:
+        bflags &= ~B.LAPLEX_SAVE_SCANS          # a fresh plan has no saved scans
+    B.laplex_apply_backward(da, db, dx, dg, gx, ga, gb, ws, bflags)
+    torch.cuda.synchronize()
+    (rgx, rga, rgb), (tgx, tga, tgb) = (oracle.apply_backward_brute if small else oracle.apply_backward_scan)(a, b, x, g)
+    if want[0]:
+        T.assert_close("gx", gx.cpu().numpy(), rgx, tgx)
+        assert ldgx == batch or bool(torch.isnan(gxbuf[:, batch:]).all())
+    if want[1]:
+        T.assert_close("ga", ga.cpu().numpy(), rga, tga)
+    if want[2]:
+        T.assert_close("gb", gb.cpu().numpy(), rgb, tgb)
+    b2 = int(r.choice([1, 4, 7, 64]))
+    while k * n * b2 > 1e8 and b2 > 1:
+        b2 = max(1, b2 // 2)
+    if B.laplex_workspace_bytes(k, n, b2) <= ws.numel():      # the same plan, another batch size
+        x2 = r.normal(size=(n, b2)).astype(np.float32)
+        y2 = torch.full((k, b2), float("nan"), device="cuda")
+        B.laplex_apply(da, db, T.dev(x2), y2, ws, (flags & ~B.LAPLEX_SAVE_SCANS) | B.LAPLEX_REUSE_PLAN)
+        torch.cuda.synchronize()
+        ref2, tol2 = (oracle.apply_brute if k * n * b2 <= 4e7 else oracle.apply_scan)(a, b, x2)
+        T.assert_close("y, plan reused at another batch size", y2.cpu().numpy(), ref2, tol2)
