@@ -242,3 +242,72 @@ def test_weighted_gram_full_size(oracle):
         col = d64[near] * np.exp(-np.abs(a64[i] - b64[near]))
         A = np.exp(-np.abs(a64[:, None] - b64[near][None, :]))
         assert worst_ratio(got[i], A @ col, A @ np.abs(col)) <= 1.0
+
+
+# ------------------------------------------------------------------ the widened entry points at their benchmark sizes
+
+def test_phased_projection_full_size_sampled(oracle):
+    """The phased kernel on the projection layer's shape (n = 2^20, k = 1024, batch 256, phases ~ U(-pi, pi)):
+    every output of 16 sampled batch columns through the angle-sum route of the oracle, and all five gradients
+    on windows of rows against the definition differentiated entry by entry."""
+    w = synth.projection_layer_phased()
+    a, b, x, g, phi, psi = w["a"], w["b"], w["x"], w["g"], w["phi"], w["psi"]
+    k, n, batch = a.size, b.size, x.shape[1]
+    ws = torch.empty(B.laplex_phased_workspace_bytes(k, n, batch), dtype=torch.uint8, device="cuda")
+    log(f"phased projection: workspace {ws.numel() / 2**30:.2f} GiB")
+    da, db, dphi, dpsi, dx, dg = dev(a), dev(b), dev(phi), dev(psi), dev(x), dev(g)
+    y = torch.empty(k, batch, device="cuda"); gx = torch.empty(n, batch, device="cuda")
+    ga = torch.empty(k, device="cuda"); gb = torch.empty(n, device="cuda")
+    gphi = torch.empty(k, device="cuda"); gpsi = torch.empty(n, device="cuda")
+    B.laplex_phased_apply(da, dphi, db, dpsi, dx, y, ws, B.LAPLEX_SAVE_SCANS)
+    B.laplex_phased_apply_backward(da, dphi, db, dpsi, dx, dg, gx, ga, gb, gphi, gpsi, ws,
+                                   B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
+    torch.cuda.synchronize()
+    y, gx, ga, gb, gphi, gpsi = (t.cpu().numpy() for t in (y, gx, ga, gb, gphi, gpsi))
+    del ws
+    cols = np.arange(0, batch, 16)
+    ref, tol = oracle.phased_apply_scan(a, phi, b, psi, x[:, cols])
+    r_y = worst_ratio(y[:, cols], ref, tol)
+    worst = {"y": 0.0, "gx": 0.0, "ga": 0.0, "gb": 0.0, "gphi": 0.0, "gpsi": 0.0}
+    checked = 0
+    centers = [0.0, 1017.25, 4100.5, 8191.0, 12000.75, 16384.0 - 256.0]
+    for a_core, b_halo, b_core, a_halo in window_samples(a, b, centers, core=256.0):
+        if a_core.size and b_halo.size:       # outputs in the core see every input that matters
+            ry, ty = oracle.phased_apply_brute(a[a_core], phi[a_core], b[b_halo], psi[b_halo], x[b_halo])
+            worst["y"] = max(worst["y"], worst_ratio(y[a_core], ry, ty))
+            (_, rga, _, rgphi, _), (_, tga, _, tgphi, _) = oracle.phased_backward_brute(
+                a[a_core], phi[a_core], b[b_halo], psi[b_halo], x[b_halo], g[a_core])
+            worst["ga"] = max(worst["ga"], worst_ratio(ga[a_core], rga, tga))
+            worst["gphi"] = max(worst["gphi"], worst_ratio(gphi[a_core], rgphi, tgphi))
+            checked += a_core.size
+        if b_core.size and a_halo.size:       # inputs in the core see every output that matters
+            (rgx, _, rgb, _, rgpsi), (tgx, _, tgb, _, tgpsi) = oracle.phased_backward_brute(
+                a[a_halo], phi[a_halo], b[b_core], psi[b_core], x[b_core], g[a_halo])
+            worst["gx"] = max(worst["gx"], worst_ratio(gx[b_core], rgx, tgx))
+            worst["gb"] = max(worst["gb"], worst_ratio(gb[b_core], rgb, tgb))
+            worst["gpsi"] = max(worst["gpsi"], worst_ratio(gpsi[b_core], rgpsi, tgpsi))
+            checked += b_core.size
+    log(f"phased projection: y ratio {r_y:.3g} (16 columns, all outputs); windows {worst} over {checked} rows")
+    assert r_y <= 1.0 and max(worst.values()) <= 1.0 and checked > 1000
+
+
+def test_mix_head_full_size(oracle):
+    """LAPLEX^(16) head of 1000 x 2048 at batch 256 (all operators in each launch): every output and every
+    gradient against the sum written out operator by operator with the dense definition."""
+    w = synth.mix_head()
+    a, b, wq, x, g = w["a"], w["b"], w["w"], w["x"], w["g"]
+    r, k, n, batch = w["r"], w["k"], w["n"], w["batch"]
+    ws = torch.empty(B.laplex_mix_workspace_bytes(r, k, n, batch), dtype=torch.uint8, device="cuda")
+    da, db, dw, dx, dg = dev(a), dev(b), dev(wq), dev(x), dev(g)
+    y = torch.empty(k, batch, device="cuda"); gx = torch.empty(n, batch, device="cuda")
+    ga = torch.empty(r, k, device="cuda"); gb = torch.empty(r, n, device="cuda"); gw = torch.empty(r, device="cuda")
+    B.laplex_mix_apply(da, db, dw, dx, y, ws, B.LAPLEX_SAVE_SCANS)
+    B.laplex_mix_apply_backward(da, db, dw, dx, dg, gx, ga, gb, gw, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
+    torch.cuda.synchronize()
+    ref, tol = oracle.mix_apply(a, b, wq, x)
+    (rgx, rga, rgb, rgw), (tgx, tga, tgb, tgw) = oracle.mix_backward(a, b, wq, x, g)
+    ratios = {"y": worst_ratio(y.cpu().numpy(), ref, tol), "gx": worst_ratio(gx.cpu().numpy(), rgx, tgx),
+              "ga": worst_ratio(ga.cpu().numpy(), rga, tga), "gb": worst_ratio(gb.cpu().numpy(), rgb, tgb),
+              "gw": worst_ratio(gw.cpu().numpy(), rgw, tgw)}
+    log(f"mix head r={r} k={k} n={n} batch={batch}: worst ratios {ratios}")
+    assert max(ratios.values()) <= 1.0
