@@ -311,3 +311,35 @@ def test_mix_head_full_size(oracle):
               "gw": worst_ratio(gw.cpu().numpy(), rgw, tgw)}
     log(f"mix head r={r} k={k} n={n} batch={batch}: worst ratios {ratios}")
     assert max(ratios.values()) <= 1.0
+
+
+def test_temperature_projection_full_size_sampled(oracle):
+    """The temperature-scaled kernel exp(-tau |a_i - b_j|) on the projection layer's shape, tau = 0.37: every output
+    of 16 sampled batch columns, gradients on windows (in the scaled anchors tau a, tau b, where the kernel is the
+    plain one), and gtau against its chain-rule identity with the anchor gradients."""
+    tau = 0.37
+    w = synth.projection_layer()
+    a, b, x, g = w["a"], w["b"], w["x"], w["g"]
+    k, n, batch = a.size, b.size, x.shape[1]
+    ws = torch.empty(B.laplex_workspace_bytes(k, n, batch), dtype=torch.uint8, device="cuda")
+    da, db, dx, dg = dev(a), dev(b), dev(x), dev(g)
+    y = torch.empty(k, batch, device="cuda"); gx = torch.empty(n, batch, device="cuda")
+    ga = torch.empty(k, device="cuda"); gb = torch.empty(n, device="cuda"); gtau = torch.empty(1, device="cuda")
+    B.laplex_apply_tau(da, db, tau, dx, y, ws, B.LAPLEX_SAVE_SCANS)
+    B.laplex_apply_backward_tau(da, db, tau, dx, dg, gx, ga, gb, gtau, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
+    torch.cuda.synchronize()
+    y, gx, ga, gb, gtau = y.cpu().numpy(), gx.cpu().numpy(), ga.cpu().numpy(), gb.cpu().numpy(), float(gtau.item())
+    sa, sb = oracle.scaled_anchors(a, tau), oracle.scaled_anchors(b, tau)
+    cols = np.arange(0, batch, 16)
+    ref, tol = oracle.apply_scan(sa, sb, x[:, cols])
+    r_y = worst_ratio(y[:, cols], ref, tol)
+    # windows in the scaled anchors; the anchor gradients of the scaled problem are ga / tau, gb / tau
+    centers = [tau * c for c in (0.0, 1017.25, 4100.5, 8191.0, 12000.75, 16384.0 - 700.0)]
+    worst, checked = check_windows(oracle, sa, sb, x, g, y, gx, ga / tau, gb / tau, centers, core=tau * 256.0)
+    # gtau = sum_i a_i ga'_i + sum_j b_j gb'_j with the scaled problem's gradients ga' = ga / tau
+    a64, b64 = a.astype(np.float64), b.astype(np.float64)
+    want = (np.dot(a64, ga.astype(np.float64)) + np.dot(b64, gb.astype(np.float64))) / tau
+    scale = (np.dot(np.abs(a64), np.abs(ga)) + np.dot(np.abs(b64), np.abs(gb))) / tau
+    log(f"temperature {tau}: y ratio {r_y:.3g}; windows {worst} over {checked} rows; gtau {gtau:.6g} vs {want:.6g}")
+    assert r_y <= 1.0 and max(worst.values()) <= 1.0 and checked > 1000
+    assert abs(gtau - want) <= 1e-5 * scale + 1e-7
