@@ -4,13 +4,15 @@
 One step = one pass of the whole path over one batch of synthetic input:
     laplex_apply          (key build, radix sort, decay, forward + backward scan, scatter)
     laplex_apply_backward (gx, ga, gb; plan and saved scans of the forward reused)
-on the neural-projection workload (n = 2^20 inputs, k = 1024 outputs, batch 256,
-fp32), inputs resident in HBM before the timed region.
+Default workload: the billion-scale square apply (n = k = 2^30, batch 1, fp32), the largest
+configuration that fits one GPU; inputs are resident in HBM before the timed region.
 
-Prints ONE JSON line: throughput in (n + k) * batch elements per second, the
-roofline of the dominant kernel (the sparse backward downsweep, timed with HIP
-events on its own stream during the timed steps) and the CPU oracle timed beside it on a
-bounded sample of the same workload.
+Prints ONE JSON line: throughput in (n + k) * batch elements per second, the roofline of the
+step's dominant kernel family (found by timing every family for one step, then timed with HIP
+events on its own stream during the timed steps), the device footprint, and the CPU oracle
+timed beside it on a bounded sub-problem of the same recipe.  The projection layer
+(n = 2^20, k = 1024, batch 256) and the Gram form (n = 3 * 2^20, batch 64) ride along as
+extra objects of the same line, each with its own roofline.
 """
 import argparse
 import json
@@ -23,7 +25,6 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-DOMINANT = "scan_down_sparse.bwd"
 
 
 def parse():
@@ -35,10 +36,13 @@ def parse():
     ap.add_argument("--batch", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-columns", type=int, default=256)
-    ap.add_argument("--workload", default="projection",
-                    choices=["projection", "square", "tie_heavy", "gram", "billion", "phased", "wgram", "wgram64", "mix", "square_b8"],
-                    help="projection is the benchmark; the others time one forward+backward step of the "
-                         "other workloads (for profiles; no roofline object, no CPU baseline)")
+    ap.add_argument("--steps-extra", type=int, default=20, help="timed steps of the extra workloads")
+    ap.add_argument("--workload", default="billion",
+                    choices=["billion", "projection", "gram", "tie_heavy", "square", "phased", "wgram", "wgram64", "mix", "square_b8"],
+                    help="billion is the benchmark (with projection and gram as extra objects); projection, gram and "
+                         "tie_heavy alone print the same kind of line for that workload; the others time one "
+                         "forward+backward step (for profiles; no roofline object, no CPU baseline)")
+    ap.add_argument("--no-extra", action="store_true", help="billion only: skip the projection and Gram objects")
     ap.add_argument("--paper-sweep", action="store_true",
                     help="instead of the benchmark: the paper's runtime sweep (App. 'GPU runtime'): square apply "
                          "n = k = 2^10 .. 2^20 at batch 8, forward and forward + backward, one JSON line per size")
@@ -47,7 +51,7 @@ def parse():
     return ap.parse_args()
 
 
-def dominant_kernel_bytes(a, b, batch, block_rows, blocks_per_tile=8, few=4):
+def sparse_bwd_bytes(a, b, batch, block_rows, blocks_per_tile=8, few=4):
     """Algorithmic bytes of one launch of the dominant kernel, the streaming backward
     downsweep (one wavefront per block of `block_rows` sorted rows).  It visits the
     blocks that hold at most `few` output anchors (blocks with more go to the generic
@@ -276,6 +280,217 @@ def paper_sweep(args, torch, np, B, synth):
                           "wgram_ms": timed(lambda: B.laplex_wgram(da, db, dd, m, ws, 0))}), flush=True)
 
 
+
+KERNEL_OF = {
+    "scan_down_sparse.bwd": "k_scan_down_sparse_wide<true> (backward downsweep: reads x, writes gx and gb)",
+    "scan_reduce.fwd": "forward reduce (reads the injected rows of x once for both directions)",
+    "scan_reduce.bwd": "backward reduce (reads the injected rows of gy once for both directions)",
+    "scan_down.fwd": "k_scan_down, forward problem (reads x, writes y and the saved scans)",
+    "scan_down.bwd": "k_scan_down, backward problem (reads gy, x and the saved scans, writes gx and the anchor gradient)",
+    "radix_scatter": "k_onesweep_pass (one radix pass: reads the pairs once, writes them once)",
+}
+
+
+def family_bytes(fam, spec, np, B):
+    """Algorithmic bytes of ALL launches of a kernel family in one step (what the method itself must move:
+    4 B per float or id; per merged position the plan's id and decay, per injected / result row its batch
+    columns), and a note saying what was counted."""
+    k, n, batch, gram = spec["k"], spec["n"], spec["batch"], spec["gram"]
+    N = n if gram else k + n
+    inj = {"fwd": n, "bwd": n if gram else k}
+    res = {"fwd": n if gram else k, "bwd": n}
+    if fam == "radix_scatter":
+        return 4 * N + 8 * N + 3 * 16 * N, "4 passes: the first reads the anchors (4 B) and writes pairs (8 B), the others 8 B + 8 B a pair"
+    if fam == "sort_hist":
+        return 4 * N, "the anchors read once"
+    if fam == "decay":
+        return 12 * N, "keys read, decays and sorted anchors written"
+    base, _, tag = fam.partition(".")
+    if tag not in inj:
+        return None, None
+    narrow = batch <= 8
+    if base == "scan_reduce":
+        if batch >= 253 and batch % 4 == 0:
+            return 16 * N + 4 * batch * inj[tag] + 16 * batch * ((N + 511) // 512), "id, two decays and the anchor per row, the injected rows, one summary per tile of 512 rows"
+        total = 8 * N + 4 * batch * inj[tag] + (4 * batch * N if narrow else 0)
+        return total, "id and decay per row, the injected rows gathered" + (", the same rows written in sorted order" if narrow else "")
+    if base == "scan_down":
+        total = 8 * N + 4 * batch * (N if narrow else inj[tag]) + 4 * batch * res[tag]
+        note = "id and decay per row, the injected rows" + (" (from the sorted-order stage)" if narrow else "") + ", the result rows written"
+        if tag == "fwd":
+            total += 4 * batch * res[tag]; note += ", the saved strict scans written"
+        else:
+            total += 4 * batch * (N if narrow else res[tag]) + 4 * res[tag]
+            note += ", the weights of the row reduction read, the anchor gradient written"
+            if gram:
+                total += 4 * batch * res[tag]; note += ", the saved strict scans read"
+        return total, note
+    if fam == "scan_down_sparse.bwd" and not gram and batch >= 253 and batch % 4 == 0:
+        rows = B.laplex_scan_tile_rows(batch, True)
+        total, visited, blocks, all_blocks = sparse_bwd_bytes(spec["a"], spec["b"], batch, rows)
+        return total, f"{visited} input rows in {blocks} of {all_blocks} blocks: 12 B of plan, the x row read, the gx row and gb written, carries per tile"
+    return None, None
+
+
+def make_spec(name, args, torch, np, B, synth):
+    """Inputs on the device, outputs, workspace and the step function of one of the roofline workloads."""
+    dev = lambda v: torch.from_numpy(np.ascontiguousarray(v)).cuda()
+    scale = args.scale
+    if name == "gram":
+        w = synth.gram_images(scale=scale)
+        a, x, g = w["a"], w["x"], w["g"]
+        n, batch, k = a.size, x.shape[1], 0
+        ws = torch.empty(B.laplex_workspace_bytes(0, n, batch), dtype=torch.uint8, device="cuda")
+        da, dx, dg = dev(a), dev(x), dev(g)
+        y = torch.empty(n, batch, device="cuda"); gx = torch.empty(n, batch, device="cuda"); ga = torch.empty(n, device="cuda")
+
+        def step():
+            B.laplex_gram(da, dx, y, ws, B.LAPLEX_SAVE_SCANS)
+            B.laplex_gram_backward(da, dx, dg, gx, ga, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
+        spec = dict(a=a, b=None, x=x, g=g, k=0, n=n, batch=batch, gram=True, anchors="N(0, (2^16)^2)",
+                    compulsory=4 * n * 2 + 4 * batch * 5 * n,       # a, ga; x twice, gy, y, gx
+                    passname="Gram form: forward + backward (gx, ga)")
+    else:
+        make = {"billion": synth.billion_square, "tie_heavy": synth.tie_heavy}.get(name)
+        w = synth.projection_layer(scale=scale, batch=args.batch) if make is None else make(scale=scale)
+        a, b, x, g = w["a"], w["b"], w["x"], w["g"]
+        k, n, batch = a.size, b.size, x.shape[1]
+        ws = torch.empty(B.laplex_workspace_bytes(k, n, batch), dtype=torch.uint8, device="cuda")
+        da, db, dx, dg = dev(a), dev(b), dev(x), dev(g)
+        y = torch.empty(k, batch, device="cuda"); gx = torch.empty(n, batch, device="cuda")
+        ga = torch.empty(k, device="cuda"); gb = torch.empty(n, device="cuda")
+
+        def step():
+            B.laplex_apply(da, db, dx, y, ws, B.LAPLEX_SAVE_SCANS)
+            B.laplex_apply_backward(da, db, dx, dg, gx, ga, gb, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
+        spec = dict(a=a, b=b, x=x, g=g, k=k, n=n, batch=batch, gram=False,
+                    anchors={"billion": "U(0,2^24)", "tie_heavy": "U(0,2^18) on a 1/4 grid"}.get(name, "U(0,2^14)"),
+                    compulsory=4 * (n + k) * 2 + 4 * batch * (3 * n + 2 * k),   # anchors, gradients; x twice, gx, gy, y
+                    passname="forward+backward (gx, ga, gb)")
+    spec.update(name=w["name"] if scale == 1 and (name != "projection" or args.batch == 256) else w["name"] + "/scaled",
+                step=step, ws=ws, outputs=(y, gx, ga), keep=(da, dx, dg))
+    return spec
+
+
+def measure(spec, steps, warmup, torch, np, B):
+    """Warm up, find the step's dominant kernel family (every family timed for one step), then time exactly
+    `steps` steps with one HIP event pair per launch of that family on the stream it is launched on."""
+    step, k, n, batch = spec["step"], spec["k"], spec["n"], spec["batch"]
+    for _ in range(max(warmup, 1)):
+        step()
+    torch.cuda.synchronize()
+    B.laplex_profile_begin("*")
+    step()
+    torch.cuda.synchronize()
+    B.laplex_profile_end()
+    families = B.laplex_profile_families()
+    dominant = max(families, key=lambda f: families[f][0])
+    torch.cuda.synchronize()
+
+    B.laplex_profile_begin(dominant)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    dom_ms, dom_launches = B.laplex_profile_end()
+
+    N = n if spec["gram"] else n + k
+    status = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    B.laplex_get_plan_status(spec["ws"], N, status)
+    assert int(status.item()) == 0, "the plan is marked invalid: a tile of the radix sort gave up its wait"
+    for t in spec["outputs"]:
+        assert bool(torch.isfinite(t.view(-1)[:4096]).all())
+
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    elements = N * batch
+    per_step_launches = dom_launches / steps
+    fam_bytes, note = family_bytes(dominant, spec, np, B)
+    dom_ms_per_step = dom_ms / steps
+    roofline = {"bound": "hbm", "kernel": KERNEL_OF.get(dominant, dominant), "family": dominant,
+                "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None, "traffic": None,
+                "avg_kernel_ms": round(dom_ms / max(dom_launches, 1), 5), "launches": dom_launches,
+                "launches_per_step": per_step_launches, "family_ms_per_step": round(dom_ms_per_step, 5),
+                "algorithmic_bytes_per_step": fam_bytes, "counted": note}
+    if fam_bytes:
+        achieved = fam_bytes / (dom_ms_per_step * 1e-3) / 1e9
+        roofline.update(achieved=round(achieved, 1), frac=round(achieved / HBM_PEAK_GBS, 4))
+    traffic_file = os.path.join(ROOT, "profiles", f"traffic_{dominant.replace('.', '_')}_{spec['name'].split('/')[0]}.json")
+    if os.path.exists(traffic_file) and "/scaled" not in spec["name"]:
+        with open(traffic_file) as fh:
+            rec = json.load(fh)
+            roofline["traffic"] = rec.get("hbm_bytes_per_step", rec.get("hbm_bytes_per_launch"))
+        roofline["traffic_source"] = "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, " + os.path.relpath(traffic_file, ROOT)
+    out = {
+        "ms_per_step": round(ms_per_step, 4), "value": elements / (ms_per_step * 1e-3),
+        "config": {"workload": spec["name"], "k": k, "n": n, "batch": batch, "anchors": spec["anchors"],
+                   "pass": spec["passname"], "sort": "radix sort inside every step",
+                   "workspace_bytes": spec["ws"].numel(), "device_bytes_peak": torch.cuda.max_memory_allocated()},
+        "roofline": roofline,
+        "families_ms_one_step": {f: round(v[0], 4) for f, v in sorted(families.items(), key=lambda kv: -kv[1][0])[:8]},
+        # compulsory HBM bytes of one step over the step time
+        "end_to_end_hbm_frac": round(spec["compulsory"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+    }
+    return out, dominant
+
+
+def projection_ceilings(spec, roofline, torch, B):
+    """Measured ceilings beside the nominal peak: a kernel that only moves the rows of x (and gx) in the order of the plan."""
+    k, n, batch = spec["k"], spec["n"], spec["batch"]
+    _, gx, _ = spec["outputs"]
+    _, dx, _ = spec["keep"]
+    perm = torch.empty(k + n, dtype=torch.int32, device="cuda")
+    B.laplex_get_perm(spec["ws"], k + n, perm)
+    rows_of_x = (perm[(perm >= k)] - k).contiguous()
+    ceil = {}
+    for name, dst, moved in (("copy_rows_GBps", gx, 2), ("read_rows_GBps", None, 1)):
+        for _ in range(3):
+            B.laplex_diag_move_rows(dx, dst, rows_of_x)
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        for _ in range(10):
+            B.laplex_diag_move_rows(dx, dst, rows_of_x)
+        torch.cuda.synchronize()
+        ceil[name] = round(moved * 4 * n * batch / ((time.perf_counter() - c0) / 10) / 1e9, 1)
+    roofline["measured_ceiling"] = dict(ceil, note="laplex_diag_move_rows on x (and gx) in the plan's row order")
+
+
+def cpu_baseline(name, spec, args, np, synth):
+    """The CPU oracle (fp64 sort + dual-theorem scans, forward + backward without the tolerance denominators: the
+    same results the timed GPU step produces) on a bounded sample of the same workload."""
+    from oracle import laplex_oracle as oracle
+    oracle.build()
+    if name == "gram":
+        return None
+    if name in ("billion", "tie_heavy"):
+        # the same recipe (same anchor density and ties) at n = k = 2^23
+        make = synth.billion_square if name == "billion" else synth.tie_heavy
+        shrink = max(1, spec["n"] >> 23)
+        w = make(scale=args.scale * shrink)
+        a, b, xs, gs = w["a"], w["b"], w["x"], w["g"]
+        sample = f"the same recipe at n = k = {a.size} (batch 1), every output"
+    else:
+        a, b = spec["a"], spec["b"]
+        cols = min(args.cpu_sample_columns, spec["batch"])
+        xs = np.ascontiguousarray(spec["x"][:, :cols]); gs = np.ascontiguousarray(spec["g"][:, :cols])
+        sample = f"all n and k, first {cols} of {spec['batch']} batch columns"
+    cols = xs.shape[1]
+    c0 = time.perf_counter()
+    oracle.apply_scan(a, b, xs, with_tol=False)
+    x64 = xs.astype(np.float64); g64 = gs.astype(np.float64)
+    _, ls, rs = oracle._dual(b, x64, a, want=(False, True, True))
+    (g64 * (rs - ls)).sum(axis=1)
+    li, ls, rs = oracle._dual(a, g64, b)
+    (li + rs); (x64 * (rs - ls)).sum(axis=1)
+    c1 = time.perf_counter()
+    threads = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)))
+    return {"value": (a.size + b.size) * cols / (c1 - c0), "unit": "elements/s",
+            # the oracle's scans run one thread per batch column; its sorts and searches use every thread
+            "cores": threads, "kind": "oracle",
+            "sample": "fp64 stable sort + dual-theorem scans, forward + backward; " + sample, "seconds": round(c1 - c0, 3)}
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -311,138 +526,49 @@ def main():
         paper_sweep(args, torch, np, B, synth)
         return
 
-    if args.workload != "projection":
+    if args.workload not in ("billion", "projection", "gram", "tie_heavy"):
         other_workload(args, torch, np, B, synth)
         return
 
-    w = synth.projection_layer(scale=args.scale, batch=args.batch)
-    a, b, x, g = w["a"], w["b"], w["x"], w["g"]
-    k, n, batch = a.size, b.size, x.shape[1]
-    da, db = torch.from_numpy(a).cuda(), torch.from_numpy(b).cuda()
-    dx, dg = torch.from_numpy(x).cuda(), torch.from_numpy(g).cuda()
-    ws_bytes = B.laplex_workspace_bytes(k, n, batch)
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
-    y = torch.empty(k, batch, device="cuda")
-    gx = torch.empty(n, batch, device="cuda")
-    ga = torch.empty(k, device="cuda")
-    gb = torch.empty(n, device="cuda")
-
-    def step():
-        B.laplex_apply(da, db, dx, y, ws, B.LAPLEX_SAVE_SCANS)
-        B.laplex_apply_backward(da, db, dx, dg, gx, ga, gb, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-
-    # the timed region: exactly --steps steps; the dominant kernel carries one HIP event pair per launch
-    B.laplex_profile_begin(DOMINANT)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    dom_ms, dom_launches = B.laplex_profile_end()
-
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    elements = (n + k) * batch
-    value = elements / (ms_per_step * 1e-3)
-
-    dom_avg_ms = dom_ms / max(dom_launches, 1)
-    tile_rows = B.laplex_scan_tile_rows(batch, batch % 4 == 0)
-    dom_bytes, dom_rows, dom_tiles, all_tiles = dominant_kernel_bytes(a, b, batch, tile_rows)
-    achieved = dom_bytes / (dom_avg_ms * 1e-3) / 1e9 if dom_launches else 0.0
-    roofline = {
-        "bound": "hbm", "kernel": "k_scan_down_sparse_wide<true> (backward downsweep: reads x, writes gx and gb)",
-        "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-        "avg_kernel_ms": round(dom_avg_ms, 5), "launches": dom_launches, "algorithmic_bytes": dom_bytes,
-        "rows_visited": dom_rows, "blocks_visited": dom_tiles, "blocks": all_tiles,
-    }
-    traffic_file = os.path.join(ROOT, "profiles", "traffic_scan_down_sparse_bwd_projection.json")
-    if args.scale == 1 and args.batch == 256 and os.path.exists(traffic_file):
-        with open(traffic_file) as fh:
-            roofline["traffic"] = json.load(fh).get("hbm_bytes_per_launch")
-
-    # measured ceilings beside the nominal peak (outside the timed region): a kernel that only moves the same rows
-    # of the same matrices, in the order of the plan (x's rows as the sorted anchors visit them)
-    perm = torch.empty(k + n, dtype=torch.int32, device="cuda")
-    B.laplex_get_perm(ws, k + n, perm)
-    rows_of_x = (perm[(perm >= k)] - k).contiguous()       # input positions of the plan -> rows of x, in sorted order
-    ceil = {}
-    for name, dst, moved in (("copy_rows_GBps", gx, 2), ("read_rows_GBps", None, 1)):
-        for _ in range(3):
-            B.laplex_diag_move_rows(dx, dst, rows_of_x)
-        torch.cuda.synchronize()
-        c0 = time.perf_counter()
-        for _ in range(10):
-            B.laplex_diag_move_rows(dx, dst, rows_of_x)
-        torch.cuda.synchronize()
-        ceil[name] = round(moved * 4 * n * batch / ((time.perf_counter() - c0) / 10) / 1e9, 1)
-    roofline["measured_ceiling"] = dict(ceil, note="laplex_diag_move_rows on x (and gx) in the plan's row order: "
-                                        "the dominant kernel reads x and writes gx (copy), the forward reduce reads x")
-    roofline["frac_of_copy_ceiling"] = round(achieved / ceil["copy_rows_GBps"], 4) if ceil["copy_rows_GBps"] else None
-
-    # per-phase split of one step (separate loops, outside the timed region)
-    phases = {}
-    for name, fn in (
-        ("apply_ms", lambda: B.laplex_apply(da, db, dx, y, ws, B.LAPLEX_SAVE_SCANS)),
-        ("apply_reuse_plan_ms", lambda: B.laplex_apply(da, db, dx, y, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)),
-        ("backward_ms", lambda: B.laplex_apply_backward(da, db, dx, dg, gx, ga, gb, ws,
-                                                        B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)),
-    ):
-        reps = max(5, args.steps // 5)
-        torch.cuda.synchronize()
-        s0 = time.perf_counter()
-        for _ in range(reps):
-            fn()
-        torch.cuda.synchronize()
-        phases[name] = round((time.perf_counter() - s0) * 1e3 / reps, 4)
-
+    spec = make_spec(args.workload, args, torch, np, B, synth)
+    res, dominant = measure(spec, args.steps, args.warmup, torch, np, B)
+    if args.workload == "projection":
+        projection_ceilings(spec, res["roofline"], torch, B)
     out = {
-        "metric": "LAPLEX fwd+bwd (n+k)*batch elements/s", "value": value, "unit": "elements/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "metric": "LAPLEX fwd+bwd (n+k)*batch elements/s", "value": res["value"], "unit": "elements/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": w["name"] if args.scale == 1 and args.batch == 256 else f"{w['name']}/scaled",
-                   "k": k, "n": n, "batch": batch, "anchors": "U(0,2^14)", "pass": "forward+backward (gx, ga, gb)",
-                   "sort": "radix sort inside every step", "workspace_bytes": ws_bytes},
-        "roofline": roofline,
-        "phases": phases,
-        # compulsory HBM bytes of one step (x twice, gx once, gy, y, anchors and gradients) over the step time
+        "config": res["config"], "roofline": res["roofline"],
+        "families_ms_one_step": res["families_ms_one_step"], "end_to_end_hbm_frac": res["end_to_end_hbm_frac"],
         # the paper's own numbers for neighbouring shapes, with their hardware (context, not a baseline for this workload)
         "paper_context": {
-            "hardware": "NVIDIA H100, fp32 (App. 'Kernel-algebra benchmarks')",
+            "hardware": "NVIDIA H100, fp32 (App. 'Kernel-algebra benchmarks', 'GPU runtime')",
+            "square_n=k=2^29_forward_ms": 704.0,
             "asymmetric_one_axis_1024_forward_ms_at_long_axis_2^20": 7.0,
             "square_n=k=2^20_batch8_forward_backward_ms": 71.0,
-            "note": "batch 8 there, batch 256 here; vs_baseline stays null",
+            "note": "other hardware and other sizes; vs_baseline stays null",
         },
-        "end_to_end_hbm_frac": round((4 * (n + k) * 2 + 4 * batch * (3 * n + 2 * k)) / (ms_per_step * 1e-3) / 1e9
-                                     / HBM_PEAK_GBS, 4),
     }
-
     if not args.no_cpu_baseline:
-        from oracle import laplex_oracle as oracle
-        oracle.build()
-        cols = min(args.cpu_sample_columns, batch)
-        xs = np.ascontiguousarray(x[:, :cols]); gs = np.ascontiguousarray(g[:, :cols])
-        c0 = time.perf_counter()
-        oracle.apply_scan(a, b, xs, with_tol=False)
-        # gradients without the tolerance denominators: the same scans the timed GPU step performs
-        x64 = xs.astype(np.float64); g64 = gs.astype(np.float64)
-        _, ls, rs = oracle._dual(b, x64, a, want=(False, True, True))
-        (g64 * (rs - ls)).sum(axis=1)
-        li, ls, rs = oracle._dual(a, g64, b)
-        (li + rs); (x64 * (rs - ls)).sum(axis=1)
-        c1 = time.perf_counter()
-        out["cpu_baseline"] = {
-            "value": (n + k) * cols / (c1 - c0), "unit": "elements/s",
-            "cores": min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)), cols),
-            "kind": "oracle",
-            "sample": f"fp64 sort + dual-theorem scans, forward + backward, all n and k, first {cols} of {batch} batch columns",
-            "seconds": round(c1 - c0, 3),
-        }
+        base = cpu_baseline(args.workload, spec, args, np, synth)
+        if base:
+            out["cpu_baseline"] = base
+    if args.workload == "billion" and not args.no_extra:
+        # the other two single-GPU workloads with a roofline of their own, after the benchmark's memory is released
+        del spec
+        torch.cuda.empty_cache()
+        extra = {}
+        for name in ("projection", "gram"):
+            sp = make_spec(name, args, torch, np, B, synth)
+            r, _ = measure(sp, args.steps_extra, 5, torch, np, B)
+            if name == "projection":
+                projection_ceilings(sp, r["roofline"], torch, B)
+            r["steps"] = args.steps_extra
+            extra[sp["name"]] = r
+            del sp
+            torch.cuda.empty_cache()
+        out["extra_workloads"] = extra
     print(json.dumps(out), flush=True)
 
 

@@ -290,12 +290,22 @@ int laplex_get_perm(const void* ws, size_t ws_bytes, int64_t count, uint32_t* pe
                     laplex_stream_t stream);
 
 /*
- * Verification hook: write the status of the plan in `ws` (count as above) to the
- * device word status_out: 0 = built normally; 1 = a tile of the radix sort gave
- * up waiting for its predecessors (the wait is bounded so that the device can
- * never hang; the plan, and every result computed from it, is then invalid and
- * the call that built it should be repeated).  Plans of at most 8192 positions
- * and merged plans never wait and always read 0.
+ * An invalid plan is never silent.  The radix sort's tiles wait for their
+ * predecessors' digit counts with a bounded spin, so that a lost wake-up can
+ * never hang the device; a tile that gives up marks the plan invalid.  Every
+ * call that computes from an invalid plan (the call that built it and every
+ * later LAPLEX_REUSE_PLAN call on the same workspace) still returns LAPLEX_OK,
+ * since nothing synchronises, but writes NaN to every element of every output
+ * it produces (y, gx, ga, gb, gtau, the weighted Gram matrix, the products and
+ * gradients of the phased and mixed calls): the kernels that store results read
+ * the plan's status word and set every exponent and a mantissa bit of what they
+ * store.  Repeating the call without LAPLEX_REUSE_PLAN rebuilds the plan.
+ * Plans of at most 8192 positions and merged plans (both inputs promised
+ * sorted) never wait and are always valid.
+ *
+ * laplex_get_plan_status writes the status word of the plan in `ws` (count =
+ * k + n for the apply form, n for the Gram form) to the device word
+ * status_out: 0 = valid, 1 = invalid.
  */
 int laplex_get_plan_status(const void* ws, size_t ws_bytes, int64_t count, uint32_t* status_out,
                            laplex_stream_t stream);
@@ -305,48 +315,6 @@ const char* laplex_status_string(int status);
 
 /* Host: text of the last HIP error this thread's calls ran into ("" if none). */
 const char* laplex_last_hip_error(void);
-
-/*
- * Diagnostics for benchmarks (not part of the method).  Between begin and end,
- * every launch of the named kernel family ("sort_hist", "radix_scatter", "merge",
- * "decay", "rowdot", "sum_slabs", "fill", and "scan_meta.T", "scan_reduce.T",
- * "scan_spine.T", "scan_down.T", "scan_down_sparse.T" with T = "fwd" for the
- * forward scans of x, "bwd" for the backward scans of gy, "rescan" for the
- * backward's repeat of the forward scans when they were not saved) is bracketed by a pair of HIP
- * events on the stream it is launched on.  laplex_profile_end waits for those
- * events and returns their summed elapsed time and the number of launches
- * (host pointers).  Creates and destroys HIP events; process-wide; not for
- * use under stream capture.
- */
-int laplex_profile_begin(const char* family /* host string */);
-int laplex_profile_end(double* total_ms, int64_t* launches);
-
-/*
- * Diagnostics: rows of the merged sequence that one workgroup (for batches of
- * 253 columns and more with 128-bit lanes: one wavefront) of the downsweep
- * kernels owns, a "block", for a given batch, with 128-bit lanes (wide != 0:
- * batch and leading dimensions multiples of 4, 16-byte aligned pointers) or
- * scalar lanes.  Lets a benchmark count which blocks a launch visits.  `rows`
- * is a host pointer.
- */
-int laplex_scan_tile_rows(int64_t batch, int wide, int64_t* rows);
-
-/*
- * Diagnostics: the device's ceiling for a kernel that does nothing but move
- * whole rows at scattered positions, the access pattern of the heavy scan
- * kernels at wide batches (rows of the batch-minor matrices in sorted-anchor
- * order).  Row r of the launch is row row_ids[r] of both matrices:
- *   dst != NULL:  dst[row_ids[r]*cols + c] = src[row_ids[r]*cols + c]   (read + write)
- *   dst == NULL:  the rows are read and summed into nothing              (read only)
- * src, dst: (max id + 1) x cols floats, contiguous, 16-byte aligned; cols a
- * multiple of 4; row_ids: `rows` device words, each below the number of rows of
- * src and dst (the caller guarantees it; a permutation gives every row once).
- * Nontemporal 16-byte loads and stores, one wavefront per row, eight rows in
- * flight per wavefront.  A benchmark times it to put a measured ceiling beside
- * the nominal HBM peak; it is not part of the method.
- */
-int laplex_diag_move_rows(const float* src, float* dst, const uint32_t* row_ids, int64_t rows, int64_t cols,
-                          laplex_stream_t stream);
 
 #ifdef __cplusplus
 }

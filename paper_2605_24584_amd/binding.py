@@ -32,12 +32,17 @@ LAPLEX_MAX_MERGED = 4294967294
 EXPORTS = (
     "laplex_workspace_bytes", "laplex_apply", "laplex_apply_backward", "laplex_gram",
     "laplex_gram_backward", "laplex_get_perm", "laplex_get_plan_status", "laplex_status_string", "laplex_last_hip_error",
-    "laplex_profile_begin", "laplex_profile_end", "laplex_scan_tile_rows", "laplex_diag_move_rows",
     "laplex_phased_workspace_bytes", "laplex_phased_apply", "laplex_phased_apply_backward",
     "laplex_apply_tau", "laplex_apply_backward_tau", "laplex_gram_tau", "laplex_gram_backward_tau",
     "laplex_wgram_workspace_bytes", "laplex_wgram",
     "laplex_mix_workspace_bytes", "laplex_mix_apply", "laplex_mix_apply_backward",
     "laplex_wgram_f64_workspace_bytes", "laplex_wgram_f64",
+)
+
+# include/laplex_diag.h: hooks for benchmarks and tests
+DIAG_EXPORTS = (
+    "laplex_profile_begin", "laplex_profile_end", "laplex_profile_family", "laplex_scan_tile_rows",
+    "laplex_diag_move_rows", "laplex_diag_set_plan_status",
 )
 
 _lib = None
@@ -75,8 +80,10 @@ def lib() -> ctypes.CDLL:
         L.laplex_last_hip_error.restype = ctypes.c_char_p
         L.laplex_profile_begin.argtypes = [ctypes.c_char_p]
         L.laplex_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+        L.laplex_profile_family.argtypes = [_I, ctypes.c_char_p, _Z, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
         L.laplex_scan_tile_rows.argtypes = [_I, ctypes.c_int, ctypes.POINTER(_I)]
         L.laplex_diag_move_rows.argtypes = [_P, _P, _P, _I, _I, _P]
+        L.laplex_diag_set_plan_status.argtypes = [_P, _Z, _I, _U, _P]
         L.laplex_phased_workspace_bytes.argtypes = [_I, _I, _I, ctypes.POINTER(_Z)]
         L.laplex_phased_apply.argtypes = [_P, _P, _I, _P, _P, _I, _P, _I, _I, _P, _I, _P, _Z, _U, _P]
         L.laplex_phased_apply_backward.argtypes = [_P, _P, _I, _P, _P, _I, _P, _I, _P, _I, _I,
@@ -94,7 +101,7 @@ def lib() -> ctypes.CDLL:
         L.laplex_mix_apply.argtypes = [_P, _P, _P, _I, _I, _I, _P, _I, _I, _P, _I, _P, _Z, _U, _P]
         L.laplex_mix_apply_backward.argtypes = [_P, _P, _P, _I, _I, _I, _P, _I, _P, _I, _I, _P, _I, _P, _P, _P,
                                                 _P, _Z, _U, _P]
-        for name in EXPORTS:
+        for name in EXPORTS + DIAG_EXPORTS:
             if name not in ("laplex_status_string", "laplex_last_hip_error"):
                 getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -174,6 +181,11 @@ def laplex_get_plan_status(ws, count: int, status_out, stream=None) -> None:
     _check(lib().laplex_get_plan_status(_ptr(ws), ws.numel(), count, _ptr(status_out), _stream(stream)))
 
 
+def laplex_diag_set_plan_status(ws, count: int, value: int, stream=None) -> None:
+    """Test hook: overwrite the status word of the plan in ws (0 = valid, 1 = invalid)."""
+    _check(lib().laplex_diag_set_plan_status(_ptr(ws), ws.numel(), count, value, _stream(stream)))
+
+
 def laplex_diag_move_rows(src, dst, row_ids, stream=None) -> None:
     """Diagnostics: rows row_ids[r] of src (rows x cols, contiguous) are read (dst None) or copied to the same rows of dst."""
     _check(lib().laplex_diag_move_rows(_ptr(src), _ptr(dst), _ptr(row_ids), row_ids.numel(), src.shape[1], _stream(stream)))
@@ -196,6 +208,20 @@ def laplex_profile_end():
     ms, cnt = ctypes.c_double(0.0), ctypes.c_int64(0)
     _check(lib().laplex_profile_end(ctypes.byref(ms), ctypes.byref(cnt)))
     return ms.value, cnt.value
+
+
+def laplex_profile_families():
+    """{family: (summed milliseconds, launches)} of the measurement that laplex_profile_end closed (family "*": all)."""
+    out, i = {}, 0
+    while True:
+        name = ctypes.create_string_buffer(128)
+        ms, cnt = ctypes.c_double(0.0), ctypes.c_int64(0)
+        rc = lib().laplex_profile_family(i, name, 128, ctypes.byref(ms), ctypes.byref(cnt))
+        if rc == LAPLEX_ERR_SIZE:
+            return out
+        _check(rc)
+        out[name.value.decode()] = (ms.value, cnt.value)
+        i += 1
 
 
 def laplex_scan_tile_rows(batch: int, wide: bool) -> int:

@@ -2,6 +2,7 @@
 // carving, and the order in which the kernels are enqueued.  No arithmetic of the
 // method happens here.
 #include "../../include/laplex.h"
+#include "../../include/laplex_diag.h"
 #include "laplex_internal.h"
 
 #include <atomic>
@@ -17,10 +18,13 @@ using namespace laplex;
 // Kernel-family timing (diagnostics for benchmarks).
 // ---------------------------------------------------------------------------
 namespace {
+struct ProfEvent { std::string family; hipEvent_t e0, e1; };
+struct ProfTotal { std::string family; double ms; int64_t launches; };
 std::atomic<bool> g_prof_on{false};
 std::mutex g_prof_mutex;
-std::string g_prof_family;
-std::vector<std::pair<hipEvent_t, hipEvent_t>> g_prof_events;
+std::string g_prof_family;            // the family that is timed, or "*" for every family
+std::vector<ProfEvent> g_prof_events;
+std::vector<ProfTotal> g_prof_totals; // per family, filled by laplex_profile_end
 hipEvent_t g_prof_open = nullptr;
 }  // namespace
 
@@ -28,7 +32,7 @@ void laplex::profile_before(const char* family, hipStream_t st)
 {
     if (!g_prof_on.load(std::memory_order_relaxed)) return;
     std::lock_guard<std::mutex> lock(g_prof_mutex);
-    if (g_prof_family != family) return;
+    if (g_prof_family != "*" && g_prof_family != family) return;
     hipEvent_t e0 = nullptr;
     if (hipEventCreate(&e0) != hipSuccess) return;
     (void)hipEventRecord(e0, st);
@@ -39,11 +43,11 @@ void laplex::profile_after(const char* family, hipStream_t st)
 {
     if (!g_prof_on.load(std::memory_order_relaxed)) return;
     std::lock_guard<std::mutex> lock(g_prof_mutex);
-    if (g_prof_family != family || !g_prof_open) return;
+    if ((g_prof_family != "*" && g_prof_family != family) || !g_prof_open) return;
     hipEvent_t e1 = nullptr;
     if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(g_prof_open); g_prof_open = nullptr; return; }
     (void)hipEventRecord(e1, st);
-    g_prof_events.emplace_back(g_prof_open, e1);
+    g_prof_events.push_back(ProfEvent{family, g_prof_open, e1});
     g_prof_open = nullptr;
 }
 
@@ -154,6 +158,13 @@ SmallArgs small_args(const float* a, int64_t k, const float* b, int64_t n, float
     S.reuse_plan = (flags & LAPLEX_REUSE_PLAN) ? 1 : 0;
     S.batch = L.batch; S.cols = small_cols(L.batch);
     return S;
+}
+
+// The plan's status word (nonzero: the radix sort gave up a wait), or null for plans sorted by counting, which never wait.
+const uint32_t* plan_status_word(const Layout& L, const char* ws)
+{
+    if (L.N <= kSmallMax) return nullptr;
+    return reinterpret_cast<const uint32_t*>(ws + L.off_counters) + kPlanStatusWord;
 }
 
 ScanProblem problem(const Plan& P, const Layout& L)
@@ -277,9 +288,9 @@ int laplex_workspace_bytes(int64_t k, int64_t n, int64_t batch, size_t* out)
     return LAPLEX_OK;
 }
 
-static int apply_impl(const float* a, int64_t k, const float* b, int64_t n,
-                 const float* x, int64_t ldx, int64_t batch, float* y, int64_t ldy,
-                 void* ws, size_t ws_bytes, uint32_t flags, float tau, laplex_stream_t stream)
+// Host checks of the forward apply's arguments (everything but the workspace).
+static int apply_check(const float* a, int64_t k, const float* b, int64_t n,
+                       const float* x, int64_t ldx, int64_t batch, const float* y, int64_t ldy, uint32_t flags)
 {
     const uint32_t known = LAPLEX_A_SORTED | LAPLEX_B_SORTED | LAPLEX_REUSE_PLAN | LAPLEX_SAVE_SCANS;
     if (flags & ~known) return LAPLEX_ERR_FLAGS;
@@ -288,6 +299,14 @@ static int apply_impl(const float* a, int64_t k, const float* b, int64_t n,
     LAPLEX_CHECK(check_vector(b, n, true));
     LAPLEX_CHECK(check_matrix(x, n, ldx, batch, true));
     LAPLEX_CHECK(check_matrix(y, k, ldy, batch, true));
+    return LAPLEX_OK;
+}
+
+static int apply_impl(const float* a, int64_t k, const float* b, int64_t n,
+                 const float* x, int64_t ldx, int64_t batch, float* y, int64_t ldy,
+                 void* ws, size_t ws_bytes, uint32_t flags, float tau, laplex_stream_t stream)
+{
+    LAPLEX_CHECK(apply_check(a, k, b, n, x, ldx, batch, y, ldy, flags));
     if (k == 0 || batch == 0) return LAPLEX_OK;
     const Layout L = make_layout(k + n, k, batch);
     LAPLEX_CHECK(check_ws(ws, ws_bytes, L));
@@ -738,7 +757,8 @@ int laplex_wgram(const float* a, int64_t k, const float* b, int64_t n, const flo
     LAPLEX_CHECK(build_wgram_plan(a, k, b, n, L, P, w, flags, st));
     LAPLEX_HIP(launch_wgram_f32(P.ids, P.pk, a, d, k, k + n, reinterpret_cast<double*>(w + G.off_summ),
                                 reinterpret_cast<double*>(w + G.off_u), reinterpret_cast<double*>(w + G.off_v),
-                                reinterpret_cast<double*>(w + G.off_w), reinterpret_cast<double*>(w + G.off_pb), m, ldm, st));
+                                reinterpret_cast<double*>(w + G.off_w), reinterpret_cast<double*>(w + G.off_pb), m, ldm,
+                                plan_status_word(L, w), st));
     return LAPLEX_OK;
 }
 
@@ -783,7 +803,8 @@ int laplex_wgram_f64(const float* a, int64_t k, const float* b, int64_t n, const
     LAPLEX_CHECK(build_wgram_plan(a, k, b, n, L, P, w, flags, st));
     LAPLEX_HIP(launch_wgram_f64(P.ids, P.pk, a, d, k, k + n, reinterpret_cast<double*>(w + G.off_summ),
                                 reinterpret_cast<double*>(w + G.off_u), reinterpret_cast<double*>(w + G.off_v),
-                                reinterpret_cast<double*>(w + G.off_w), reinterpret_cast<double*>(w + G.off_pb), m, ldm, st));
+                                reinterpret_cast<double*>(w + G.off_w), reinterpret_cast<double*>(w + G.off_pb), m, ldm,
+                                plan_status_word(L, w), st));
     return LAPLEX_OK;
 }
 
@@ -974,6 +995,21 @@ int laplex_get_plan_status(const void* ws, size_t ws_bytes, int64_t count, uint3
     return LAPLEX_OK;
 }
 
+int laplex_diag_set_plan_status(void* ws, size_t ws_bytes, int64_t count, uint32_t value, laplex_stream_t stream)
+{
+    if (count <= kSmallMax || count > LAPLEX_MAX_MERGED) return LAPLEX_ERR_SIZE;
+    if (!ws) return LAPLEX_ERR_NULL;
+    if (misaligned(ws, 256)) return LAPLEX_ERR_ALIGN;
+    const Layout L = make_layout(count, 0, 1);          // the plan's offsets depend on the merged length only
+    if (ws_bytes < L.off_counters + sizeof(uint32_t) * 64) return LAPLEX_ERR_WORKSPACE;
+    float* word = reinterpret_cast<float*>(static_cast<char*>(ws) + L.off_counters) + kPlanStatusWord;
+    float bits;
+    static_assert(sizeof(bits) == sizeof(value), "the word is written as the bit pattern of a float");
+    __builtin_memcpy(&bits, &value, sizeof(bits));
+    LAPLEX_HIP(launch_fill(word, 1, 1, 1, bits, stream));
+    return LAPLEX_OK;
+}
+
 const char* laplex_status_string(int status)
 {
     switch (status) {
@@ -1015,8 +1051,9 @@ int laplex_profile_begin(const char* family)
 {
     if (!family) return LAPLEX_ERR_NULL;
     std::lock_guard<std::mutex> lock(g_prof_mutex);
-    for (auto& ev : g_prof_events) { (void)hipEventDestroy(ev.first); (void)hipEventDestroy(ev.second); }
+    for (auto& ev : g_prof_events) { (void)hipEventDestroy(ev.e0); (void)hipEventDestroy(ev.e1); }
     g_prof_events.clear();
+    g_prof_totals.clear();
     g_prof_family = family;
     g_prof_on.store(true);
     return LAPLEX_OK;
@@ -1027,19 +1064,41 @@ int laplex_profile_end(double* total_ms, int64_t* launches)
     if (!total_ms || !launches) return LAPLEX_ERR_NULL;
     std::lock_guard<std::mutex> lock(g_prof_mutex);
     g_prof_on.store(false);
+    g_prof_totals.clear();
     double sum = 0.0;
     int64_t count = 0;
     int rc = LAPLEX_OK;
     for (auto& ev : g_prof_events) {
         float ms = 0.0f;
-        hipError_t e = hipEventSynchronize(ev.second);
-        if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev.first, ev.second);
-        if (e == hipSuccess) { sum += ms; ++count; } else rc = hip_fail(e);
-        (void)hipEventDestroy(ev.first); (void)hipEventDestroy(ev.second);
+        hipError_t e = hipEventSynchronize(ev.e1);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev.e0, ev.e1);
+        if (e == hipSuccess) {
+            sum += ms; ++count;
+            size_t f = 0;
+            while (f < g_prof_totals.size() && g_prof_totals[f].family != ev.family) ++f;
+            if (f == g_prof_totals.size()) g_prof_totals.push_back(ProfTotal{ev.family, 0.0, 0});
+            g_prof_totals[f].ms += ms; ++g_prof_totals[f].launches;
+        } else {
+            rc = hip_fail(e);
+        }
+        (void)hipEventDestroy(ev.e0); (void)hipEventDestroy(ev.e1);
     }
     g_prof_events.clear();
     *total_ms = sum; *launches = count;
     return rc;
+}
+
+int laplex_profile_family(int64_t index, char* name, size_t name_bytes, double* total_ms, int64_t* launches)
+{
+    if (!name || !total_ms || !launches) return LAPLEX_ERR_NULL;
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    if (index < 0 || (size_t)index >= g_prof_totals.size() || name_bytes == 0) return LAPLEX_ERR_SIZE;
+    const ProfTotal& t = g_prof_totals[(size_t)index];
+    const size_t len = t.family.size() < name_bytes - 1 ? t.family.size() : name_bytes - 1;
+    __builtin_memcpy(name, t.family.data(), len);
+    name[len] = '\0';
+    *total_ms = t.ms; *launches = t.launches;
+    return LAPLEX_OK;
 }
 
 }  // extern "C"

@@ -254,14 +254,17 @@ k_g64_down(const uint32_t* __restrict__ ids, const float* __restrict__ pk, const
     }
 }
 
-// W[i] <- the prefix sum at the last middle anchor before Gram anchor i (0 if there is none)
+// W[i] <- the prefix sum at the last middle anchor before Gram anchor i (0 if there is none).
+// status: the plan's status word, or null for plans that are always valid.  An invalid plan (the radix
+// sort gave up a wait) turns every W[i], and with it every entry of the matrix, into a NaN.
 __global__ void __launch_bounds__(256)
-k_g64_pick(double* __restrict__ W, const double* __restrict__ Pb, int64_t k)
+k_g64_pick(double* __restrict__ W, const double* __restrict__ Pb, int64_t k, const uint32_t* __restrict__ status)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= k) return;
     const int64_t c = (int64_t)W[i];
-    W[i] = c > 0 ? Pb[c - 1] : 0.0;
+    const bool invalid = status != nullptr && *status != 0u;
+    W[i] = invalid ? __longlong_as_double(0x7FF8000000000000LL) : (c > 0 ? Pb[c - 1] : 0.0);
 }
 
 // The fill: one thread per four consecutive columns of one row; lo / hi of a pair by (anchor, index), the
@@ -302,7 +305,8 @@ int64_t wgram_tiles(int64_t N);
 
 template <typename TW, typename TM>
 hipError_t launch_wgram_t(const uint32_t* ids, const float* pk, const float* a, const TW* d, int64_t k, int64_t N,
-                          double* summ, double* U, double* V, double* W, double* Pb, TM* M, int64_t ldm, hipStream_t st)
+                          double* summ, double* U, double* V, double* W, double* Pb, TM* M, int64_t ldm,
+                          const uint32_t* status, hipStream_t st)
 {
     const int64_t tiles = wgram_tiles(N);
     LAPLEX_TIMED("wgram_scan", st, hipLaunchKernelGGL((k_g64_tiles<TW>), dim3((unsigned)tiles), dim3(kWThreads), 0, st,
@@ -311,7 +315,7 @@ hipError_t launch_wgram_t(const uint32_t* ids, const float* pk, const float* a, 
     LAPLEX_TIMED("wgram_scan", st, hipLaunchKernelGGL((k_g64_down<TW>), dim3((unsigned)tiles), dim3(kWThreads), 0, st,
                                                       ids, pk, d, (uint32_t)k, N, tiles, (const double*)summ, U, V, W, Pb));
     LAPLEX_TIMED("wgram_scan", st, hipLaunchKernelGGL(k_g64_pick, dim3((unsigned)((k + 255) / 256)), dim3(256), 0, st,
-                                                      W, (const double*)Pb, k));
+                                                      W, (const double*)Pb, k, status));
     const int vec4 = (reinterpret_cast<uintptr_t>(M) & 15u) == 0 && ldm % 4 == 0;
     const dim3 grid((unsigned)k, (unsigned)((k + 1023) / 1024));     // rows on x (up to 2^31 - 1), column chunks on y
     LAPLEX_TIMED("wgram_fill", st, hipLaunchKernelGGL((k_wgram_fill<TM>), grid, dim3(256), 0, st,
@@ -322,15 +326,17 @@ hipError_t launch_wgram_t(const uint32_t* ids, const float* pk, const float* a, 
 int64_t wgram_tiles(int64_t N) { return (N + kWTile - 1) / kWTile; }
 
 hipError_t launch_wgram_f32(const uint32_t* ids, const float* pk, const float* a, const float* d, int64_t k, int64_t N,
-                            double* summ, double* U, double* V, double* W, double* Pb, float* M, int64_t ldm, hipStream_t st)
+                            double* summ, double* U, double* V, double* W, double* Pb, float* M, int64_t ldm,
+                            const uint32_t* status, hipStream_t st)
 {
-    return launch_wgram_t<float, float>(ids, pk, a, d, k, N, summ, U, V, W, Pb, M, ldm, st);
+    return launch_wgram_t<float, float>(ids, pk, a, d, k, N, summ, U, V, W, Pb, M, ldm, status, st);
 }
 
 hipError_t launch_wgram_f64(const uint32_t* ids, const float* pk, const float* a, const double* d, int64_t k, int64_t N,
-                            double* summ, double* U, double* V, double* W, double* Pb, double* M, int64_t ldm, hipStream_t st)
+                            double* summ, double* U, double* V, double* W, double* Pb, double* M, int64_t ldm,
+                            const uint32_t* status, hipStream_t st)
 {
-    return launch_wgram_t<double, double>(ids, pk, a, d, k, N, summ, U, V, W, Pb, M, ldm, st);
+    return launch_wgram_t<double, double>(ids, pk, a, d, k, N, summ, U, V, W, Pb, M, ldm, status, st);
 }
 
 }  // namespace laplex

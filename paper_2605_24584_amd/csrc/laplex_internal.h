@@ -337,12 +337,15 @@ hipError_t launch_dot_ops(const float* u, int64_t ldu, const float* v, int64_t r
 // Weighted Gram matrix (gram_kernels.hip): U, V, W (fp64, k each) by a scan of its own over the plan (ids, pk) of the
 // doubled anchors, then the fill  M[i*ldm + j] = exp(-|a_i - a_j|) (U[lo] + (W[hi] - W[lo]) + V[hi]),  lo / hi the pair
 // in sorted order.  summ: 6 * wgram_tiles(N) doubles of scratch; Pb: N - k doubles (the prefix sum of the weights at each
-// middle anchor, in merged order).  _f32: fp32 weights and result, _f64: fp64.
+// middle anchor, in merged order).  _f32: fp32 weights and result, _f64: fp64.  status: the plan's status word (an invalid
+// plan makes every entry a NaN), or null for a plan that cannot be invalid.
 int64_t wgram_tiles(int64_t N);
 hipError_t launch_wgram_f32(const uint32_t* ids, const float* pk, const float* a, const float* d, int64_t k, int64_t N,
-                            double* summ, double* U, double* V, double* W, double* Pb, float* M, int64_t ldm, hipStream_t st);
+                            double* summ, double* U, double* V, double* W, double* Pb, float* M, int64_t ldm,
+                            const uint32_t* status, hipStream_t st);
 hipError_t launch_wgram_f64(const uint32_t* ids, const float* pk, const float* a, const double* d, int64_t k, int64_t N,
-                            double* summ, double* U, double* V, double* W, double* Pb, double* M, int64_t ldm, hipStream_t st);
+                            double* summ, double* U, double* V, double* W, double* Pb, double* M, int64_t ldm,
+                            const uint32_t* status, hipStream_t st);
 
 // out[r] = sum_t u[r*ldu+t] * v[r*ldv+t]
 // out[r] = sum_t (u1 v1 + u2 v2)[r, t]

@@ -80,6 +80,12 @@ struct ScanArgs {
 };
 
 constexpr int kFlagInj = 1, kFlagRes = 2;
+
+// An invalid plan (a tile of the radix sort gave up its bounded wait) must never pass for a result: the
+// kernels that store results OR this word into every value they store.  It is 0 for a valid plan and
+// turns any float into a NaN (all exponent bits and a mantissa bit) for an invalid one.
+__device__ __forceinline__ uint32_t plan_poison(const uint32_t* counters) { return counters[kPlanStatusWord] ? 0x7FC00000u : 0u; }
+__device__ __forceinline__ float taint(float v, uint32_t poison) { return __uint_as_float(__float_as_uint(v) | poison); }
 // Block flags only (wide geometry, injected and result rows from different matrices): the block holds
 // injected (result) rows, but at most kFewRows of them.  Such a block does not need the scan inside
 // it: each result row is the carries' closed form plus a handful of direct terms exp(-|p_i - p_s|) v_s.
@@ -1124,6 +1130,7 @@ k_scan_down(const ScanArgs A)
     const int64_t tile = A.down_from_list ? A.list_both[blockIdx.x] : blockIdx.x;     // the block this workgroup owns
     const int flags = (int)A.blk_flags[tile];
     if ((flags & (kFlagInj | kFlagRes | kFlagFewInj | kFlagFewRes)) != (kFlagInj | kFlagRes)) return;
+    const uint32_t poison = plan_poison(A.counters);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int bv = A.bv, rv = A.rv;
@@ -1277,8 +1284,8 @@ k_scan_down(const ScanArgs A)
         for (int e = 0; e < VEC; ++e) {
             G[e] = h ? T.dh[i + 1] * R[e] : G[e];
             R[e] = (h ? G[e] : R[e]) + v[i][e];
-            P[e] = Ff[i][e] + R[e] - v[i][e];
-            Z[e] = G[e] - Efi[e];
+            P[e] = taint(Ff[i][e] + R[e] - v[i][e], poison);
+            Z[e] = taint(G[e] - Efi[e], poison);
         }
         const bool is_res = T.id[i] >= A.res_lo && T.id[i] < A.res_hi;
         const int64_t rr = (int64_t)T.id[i] - (int64_t)A.res_lo;
@@ -1323,8 +1330,9 @@ k_scan_down_sparse(const ScanArgs A)
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < 2) A.counters[threadIdx.x] = 0u;
     const int64_t tile = blockIdx.x;                // the block this workgroup owns
     const int flags = (int)A.blk_flags[tile];
-    // result rows, and nothing injected or (wide geometry) at most kFewRows injected rows
-    if (!(flags & kFlagRes) || ((flags & kFlagInj) && !(flags & kFlagFewInj))) return;
+    // result rows and nothing injected (blocks with a few injected rows exist in the wide geometry only, which has a kernel of its own)
+    if (!(flags & kFlagRes) || (flags & kFlagInj)) return;
+    const uint32_t poison = plan_poison(A.counters);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int bv = A.bv, rv = A.rv;
@@ -1346,37 +1354,6 @@ k_scan_down_sparse(const ScanArgs A)
     load_weights<VEC>(A, T, row0, col0, col_ok, want_red, wv);
     float Fin[VEC], Ein[VEC], Rin[VEC], Gin[VEC];
     load_block_carries<VEC, STRICT>(A, tile, col0, col_ok, Fin, Ein, Rin, Gin);
-
-    // The few rows injected inside the block (wide geometry: every lane sees the same rows, its own
-    // columns): row i gets exp(-|p_i - p_s|) v_s from source s directly, on both channels (the strict
-    // one with the sign of p_s - p_i, nothing at a tie).  Lane 8 i + s holds the weight of (row i of this
-    // wavefront, source s).
-    float vs[kFewRows][VEC], w_src = 0.0f, wz_src = 0.0f;
-    const bool sources = VEC == 4 && (flags & kFlagFewInj);      // uniform
-    if (VEC == 4 && sources) {
-        const int64_t jb = tile * 64 + lane;
-        const bool live = jb < A.N;
-        const int64_t jc = live ? jb : A.N - 1;
-        const uint32_t idl = A.ids[jc];
-        const float pl = A.pk[jc + 1];
-        uint64_t m = __ballot(live && idl >= A.inj_lo && idl < A.inj_hi);
-        const float pi = __shfl(pl, wave * 8 + (lane >> 3));
-        float ps = 0.0f; bool valid = false;
-#pragma unroll
-        for (int q = 0; q < kFewRows; ++q) {
-            const bool have = m != 0;
-            const int rs = have ? __ffsll((long long)m) - 1 : 0;
-            m &= m - 1;
-            const float pq = lane_f(pl, rs);
-            const uint32_t idq = lane_u(idl, rs);
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) vs[q][e] = 0.0f;
-            if (have && col_ok) load_vec<VEC>(vs[q], A.inj + (int64_t)(idq - A.inj_lo) * A.ld_inj + col0);
-            if ((lane & 7) == q) { ps = pq; valid = have; }
-        }
-        w_src = valid ? expf(-fabsf(pi - ps)) : 0.0f;
-        wz_src = ps > pi ? w_src : (ps < pi ? -w_src : 0.0f);
-    }
 
     // per-row cumulative decays inside this row-lane, from the left and from the right (at most ITEMS factors)
     float cf[ITEMS], cb[ITEMS];
@@ -1408,16 +1385,8 @@ k_scan_down_sparse(const ScanArgs A)
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
             const float Fj = kf * Fin[e], Rj = kb * Rin[e];
-            P[e] = Fj + Rj;
-            Z[e] = (seen_b ? Rj : Gin[e]) - (seen_f ? Fj : Ein[e]);
-        }
-        if (VEC == 4 && sources) {
-#pragma unroll
-            for (int q = 0; q < kFewRows; ++q) {
-                const float a = lane_f(w_src, i * 8 + q), z = lane_f(wz_src, i * 8 + q);
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) { P[e] += a * vs[q][e]; Z[e] += z * vs[q][e]; }
-            }
+            P[e] = taint(Fj + Rj, poison);
+            Z[e] = taint((seen_b ? Rj : Gin[e]) - (seen_f ? Fj : Ein[e]), poison);
         }
         if (is_res && col_ok) {
             if (A.out_p) store_vec<VEC>(A.out_p + rr * A.ld_p + col0, P);
@@ -1454,6 +1423,7 @@ k_scan_down_fewres(const ScanArgs A)
     const int64_t blk = A.down_from_list ? (int64_t)lane_u(A.list_both[slot], 0) : slot;
     const int flags = (int)A.blk_flags[blk];
     if ((flags & (kFlagInj | kFlagRes | kFlagFewInj | kFlagFewRes)) != (kFlagInj | kFlagRes | kFlagFewRes)) return;
+    const uint32_t poison = plan_poison(A.counters);
     const int64_t col0 = ((int64_t)blockIdx.y * 64 + lane) * VEC;
     const bool col_ok = col0 < A.batch;
     const float* const base = A.inj + (col_ok ? col0 : 0);
@@ -1541,8 +1511,8 @@ k_scan_down_fewres(const ScanArgs A)
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
             const float Fj = kf * Fc[e], Rj = kb * Rc[e];
-            P[e] = aP[q][e] + Fj + Rj;
-            Z[e] = aZ[q][e] + ((seen_b ? Rj : Gc[e]) - (seen_f ? Fj : Ec[e]));
+            P[e] = taint(aP[q][e] + Fj + Rj, poison);
+            Z[e] = taint(aZ[q][e] + ((seen_b ? Rj : Gc[e]) - (seen_f ? Fj : Ec[e])), poison);
         }
         if (col_ok) {
             if (A.out_p) store_vec<VEC>(A.out_p + rr * A.ld_p + col0, P);
@@ -1583,6 +1553,7 @@ k_scan_down_sparse_wide(const ScanArgs A)
     const int flags = (int)A.blk_flags[blk];
     // result rows, and nothing injected or at most kFewRows injected rows
     if (!(flags & kFlagRes) || ((flags & kFlagInj) && !(flags & kFlagFewInj))) return;
+    const uint32_t poison = plan_poison(A.counters);
     const int64_t col0 = ((int64_t)blockIdx.y * 64 + lane) * VEC;
     const bool col_ok = col0 < A.batch;
     const int64_t colc = col_ok ? col0 : 0;      // lanes past the last column read (and drop) columns 0..3
@@ -1657,6 +1628,8 @@ k_scan_down_sparse_wide(const ScanArgs A)
                     for (int e = 0; e < VEC; ++e) { P[e] += a * vs[q][e]; Z[e] += z * vs[q][e]; }
                 }
             }
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) { P[e] = taint(P[e], poison); Z[e] = taint(Z[e], poison); }
             if (is_res && col_ok) {
                 const int64_t rr = (int64_t)(lane_u(idv, row) - A.res_lo);
                 // the result matrix is written once and not read again by this call: streaming stores

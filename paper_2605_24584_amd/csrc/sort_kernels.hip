@@ -1,5 +1,5 @@
-// Sorting the merged anchors (Sec. 3: "sorting raises the total cost to
-// O(n log n)"; App. B "Combined complexity").  Hand-written for gfx950:
+// Sorting the merged anchors (Sec. 3 "Complexity": the O(n log n) term of the method;
+// App. B "Combined complexity").  Hand-written for gfx950:
 // 64-wide wavefronts, ballot-based stable ranking, LDS-staged scatter.
 //
 //   radix sort  one-sweep LSD sort, up to 4 passes of 8 bits (a pass whose digit is the same

@@ -86,7 +86,7 @@ def check_windows(oracle, a, b, x, g, y, gx, ga, gb, centers, core=4.0):
 
 # ------------------------------------------------------------------ projection layer, the benchmark's workload
 
-def test_projection_full_size_sampled(oracle):
+def test_projection_full_size_every_element(oracle):
     w = synth.projection_layer()
     a, b, x, g = w["a"], w["b"], w["x"], w["g"]
     k, n, batch = a.size, b.size, x.shape[1]
@@ -104,15 +104,16 @@ def test_projection_full_size_sampled(oracle):
     torch.cuda.synchronize()
     assert np.array_equal(perm.cpu().numpy().view(np.uint32), oracle.merged_permutation(a, b))
     y, gx, ga, gb = y.cpu().numpy(), gx.cpu().numpy(), ga.cpu().numpy(), gb.cpu().numpy()
-    # every output of 16 sampled batch columns through the dual-theorem route ...
-    cols = np.arange(0, batch, 16)
-    ref, tol = oracle.apply_scan(a, b, x[:, cols])
-    r_y = worst_ratio(y[:, cols], ref, tol)
-    # ... and sampled rows through windows (all batch columns; ga and gb sum over the batch)
+    # every element of y, gx, ga and gb (all 256 batch columns) through the dual-theorem route
+    ref, tol = oracle.apply_scan(a, b, x)
+    (rgx, rga, rgb), (tgx, tga, tgb) = oracle.apply_backward_scan(a, b, x, g)
+    r = {"y": worst_ratio(y, ref, tol), "gx": worst_ratio(gx, rgx, tgx),
+         "ga": worst_ratio(ga, rga, tga), "gb": worst_ratio(gb, rgb, tgb)}
+    # ... and the definition itself on windows of rows
     centers = [0.0, 1017.25, 4100.5, 8191.0, 12000.75, 16384.0 - 256.0]
     worst, checked = check_windows(oracle, a, b, x, g, y, gx, ga, gb, centers, core=256.0)
-    log(f"projection full: y ratio {r_y:.3g} (16 columns, all outputs); windows {worst} over {checked} rows")
-    assert r_y <= 1.0 and max(worst.values()) <= 1.0 and checked > 1000
+    log(f"projection full: worst ratios over every element {r}; windows (definition) {worst} over {checked} rows")
+    assert max(r.values()) <= 1.0 and max(worst.values()) <= 1.0 and checked > 1000
 
 
 # ------------------------------------------------------------------ tie-heavy square apply, n = k = 2^24
@@ -161,11 +162,12 @@ def test_gram_images_full_size(oracle):
     assert int(status.item()) == 0, "a tile of the radix sort gave up waiting for its predecessors"
     torch.cuda.synchronize()
     assert np.array_equal(perm.cpu().numpy().view(np.uint32), oracle.merged_permutation(a))
-    cols = np.arange(0, batch, 8)        # 8 of the 64 columns, every row, for y and gx
-    ref, tol = oracle.gram_scan(a, x[:, cols])
-    r_y = worst_ratio(y.cpu().numpy()[:, cols], ref, tol)
-    refg, tolg = oracle.gram_scan(a, g[:, cols])
-    r_gx = worst_ratio(gx.cpu().numpy()[:, cols], refg, tolg)
+    ref, tol = oracle.gram_scan(a, x)    # every row, all 64 columns
+    r_y = worst_ratio(y.cpu().numpy(), ref, tol)
+    del ref, tol
+    refg, tolg = oracle.gram_scan(a, g)
+    r_gx = worst_ratio(gx.cpu().numpy(), refg, tolg)
+    del refg, tolg
     (_, rga), (_, tga) = oracle.gram_backward_scan(a, x, g)      # ga sums over all 64 columns
     r_ga = worst_ratio(ga.cpu().numpy(), rga, tga)
     dup = n - np.unique(a).size
@@ -208,13 +210,127 @@ def test_billion_scale(oracle):
     del ws
     check_permutation_properties(perm, torch.cat([da, db]))
     log("permutation properties hold")
+    N = k + n
+    # sorted copies of (b, x) and (a, g) for the windowed route, gathered on the device along the verified permutation
+    # (the oracle sorts for itself; inputs that arrive sorted only make its sort quick)
+    def sorted_side(lo, hi, anchors_dev, values_dev):
+        out_a, out_v = [], []
+        step = 1 << 27
+        for c0 in range(0, N, step):
+            p = perm[c0:c0 + step].to(torch.int64) & 0xFFFFFFFF
+            sel = p[(p >= lo) & (p < hi)] - lo
+            out_a.append(anchors_dev[sel].cpu()); out_v.append(values_dev.view(-1)[sel].cpu())
+        return torch.cat(out_a).numpy(), torch.cat(out_v).numpy()
+    bs, xs = sorted_side(k, N, db, dx)
+    as_, gs = sorted_side(0, k, da, dg)
     y, gx, ga, gb = y.cpu().numpy(), gx.cpu().numpy(), ga.cpu().numpy(), gb.cpu().numpy()
-    hi = float(1 << 24) / scale
-    # windows at both ends, in the dense-fraction region and where fp32 spacing is 0.5 / 1.0 (many exact ties)
-    centers = [0.0, 3.5, hi / 1024, hi / 16 + 0.25, hi / 4, hi / 2 + 1.0, 0.75 * hi, hi - 70.0, hi - 4.0]
+
+    # (1) rows on both sides of the boundaries of the launch geometry, taken from the plan itself: at batch 1 a scan
+    # block is 8192 rows, a chunk of the two-level spine 4096 blocks = 2^25 rows (a chunk carry matters only within
+    # ~100 units of anchor distance of a chunk boundary), a sort tile 8192 pairs.  Every chunk boundary, and block
+    # boundaries spread over the sequence, 192 rows on either side, against the definition over a halo of >= 64 units.
+    block, chunk, core, halo = 8192, 1 << 25, 192, 12288
+    bounds = [m * chunk for m in range(1, (N + chunk - 1) // chunk)]
+    rb = np.random.default_rng(30)
+    bounds += [int(m) * block for m in rb.integers(1, N // block, 24)] + [block, N - block, core, N - core]
+    worst = {"y": 0.0, "gx": 0.0, "ga": 0.0, "gb": 0.0}
+    checked = 0
+    for j0 in bounds:
+        lo, hi = max(0, j0 - core - halo), min(N, j0 + core + halo)
+        ids = (perm[lo:hi].cpu().numpy().view(np.uint32)).astype(np.int64)
+        pos = np.arange(lo, hi)
+        in_core = (pos >= j0 - core) & (pos < j0 + core)
+        is_out = ids < k
+        anchor = np.where(is_out, a[np.minimum(ids, k - 1)], b[np.maximum(ids - k, 0)]).astype(np.float64)
+        c_lo, c_hi = anchor[in_core].min(), anchor[in_core].max()
+        # the halo reaches 64 units beyond the core on both sides, or the end of the sequence
+        assert lo == 0 or anchor[0] <= c_lo - 64.0, "halo too short on the left"
+        assert hi == N or anchor[-1] >= c_hi + 64.0, "halo too short on the right"
+        a_core, b_halo = ids[in_core & is_out], ids[~is_out] - k
+        b_core, a_halo = ids[in_core & ~is_out] - k, ids[is_out]
+        ref, tol = oracle.apply_brute(a[a_core], b[b_halo], x[b_halo])
+        worst["y"] = max(worst["y"], worst_ratio(y[a_core], ref, tol))
+        (_, rga, _), (_, tga, _) = oracle.apply_backward_brute(a[a_core], b[b_halo], x[b_halo], g[a_core])
+        worst["ga"] = max(worst["ga"], worst_ratio(ga[a_core], rga, tga))
+        (rgx, _, rgb), (tgx, _, tgb) = oracle.apply_backward_brute(a[a_halo], b[b_core], x[b_core], g[a_halo])
+        worst["gx"] = max(worst["gx"], worst_ratio(gx[b_core], rgx, tgx))
+        worst["gb"] = max(worst["gb"], worst_ratio(gb[b_core], rgb, tgb))
+        checked += a_core.size + b_core.size
+    log(f"billion workload: {len(bounds)} chunk / block boundaries from the plan: ratios {worst} over {checked} rows")
+    assert max(worst.values()) <= 1.0 and checked >= 2 * core * len(bounds) - 4 * core
+    del perm
+
+    # (2) windows at fixed anchor values: both ends, the dense-fraction region, where fp32 spacing is 0.5 / 1.0 (many exact ties)
+    hi_a = float(1 << 24) / scale
+    centers = [0.0, 3.5, hi_a / 1024, hi_a / 16 + 0.25, hi_a / 4, hi_a / 2 + 1.0, 0.75 * hi_a, hi_a - 70.0, hi_a - 4.0]
     worst, checked = check_windows(oracle, a, b, x, g, y, gx, ga, gb, centers)
     log(f"billion workload: window ratios {worst} over {checked} rows")
     assert max(worst.values()) <= 1.0 and checked > 2000
+
+    # (3) 2^20 seeded random outputs and 2^20 random inputs through the windowed definition (|a - b| <= 64; what is
+    # dropped is below exp(-64) sum|x|)
+    rs = np.random.default_rng(31)
+    pick = np.sort(rs.choice(k, 1 << 20, replace=False))
+    log("windowed definition on 2^20 random outputs")
+    ref, tol = oracle.apply_window(a[pick], bs, xs)
+    r_y = worst_ratio(y[pick, 0], ref, tol)
+    del bs, xs
+    pick = np.sort(rs.choice(n, 1 << 20, replace=False))
+    log("windowed definition on 2^20 random inputs (gx through the transposed operator)")
+    ref, tol = oracle.apply_window(b[pick], as_, gs)
+    r_gx = worst_ratio(gx[pick, 0], ref, tol)
+    log(f"billion workload: random samples: y ratio {r_y:.3g}, gx ratio {r_gx:.3g}")
+    assert r_y <= 1.0 and r_gx <= 1.0
+
+
+def test_two_level_spine_every_output(oracle):
+    """Batch 1 with more than 2^25 merged positions: the tile summaries no longer fit one chunk of the spine, so its
+    upper level runs (at the benchmark's size it always does; here on a size where the oracle's scan route can produce
+    EVERY output: n = k = 2^25, the billion workload's recipe with the same density and ties).  Always run."""
+    w = synth.billion_square(scale=32)
+    a, b, x, g = w["a"], w["b"], w["x"], w["g"]
+    k, n = a.size, b.size
+    assert k + n > (1 << 25)
+    ws = torch.empty(B.laplex_workspace_bytes(k, n, 1), dtype=torch.uint8, device="cuda")
+    da, db, dx, dg = dev(a), dev(b), dev(x), dev(g)
+    y = torch.empty(k, 1, device="cuda"); gx = torch.empty(n, 1, device="cuda")
+    ga = torch.empty(k, device="cuda"); gb = torch.empty(n, device="cuda")
+    B.laplex_apply(da, db, dx, y, ws, B.LAPLEX_SAVE_SCANS)
+    B.laplex_apply_backward(da, db, dx, dg, gx, ga, gb, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
+    perm = torch.empty(k + n, dtype=torch.int32, device="cuda")
+    B.laplex_get_perm(ws, k + n, perm)
+    torch.cuda.synchronize()
+    log("two-level spine, n = k = 2^25: permutation")
+    assert np.array_equal(perm.cpu().numpy().view(np.uint32), oracle.merged_permutation(a, b))   # bit-exact
+    del ws, perm
+    log("forward through the scan route")
+    ref, tol = oracle.apply_scan(a, b, x)
+    r_y = worst_ratio(y.cpu().numpy(), ref, tol)
+    log(f"y ratio {r_y:.3g}; backward through the scan route")
+    (rgx, rga, rgb), (tgx, tga, tgb) = oracle.apply_backward_scan(a, b, x, g)
+    r = (r_y, worst_ratio(gx.cpu().numpy(), rgx, tgx), worst_ratio(ga.cpu().numpy(), rga, tga),
+         worst_ratio(gb.cpu().numpy(), rgb, tgb))
+    log(f"two-level spine, n = k = 2^25, every output: worst ratios y, gx, ga, gb = {r}")
+    assert max(r) <= 1.0
+
+
+def test_two_level_spine_dense_anchors_every_output(oracle):
+    """The same size with all anchors inside 24 units (and many exact ties): no decay is ever small, so every
+    carry, the chunks' included, reaches every output.  Forward, every output against the scan route."""
+    k = n = 1 << 25
+    a = synth.uniform(synth.stream_seed(21, synth.STREAM_A), k, 0.0, 24.0)
+    b = synth.uniform(synth.stream_seed(21, synth.STREAM_B), n, 0.0, 24.0)
+    x = synth.normal(synth.stream_seed(21, synth.STREAM_X), n).reshape(n, 1)
+    ws = torch.empty(B.laplex_workspace_bytes(k, n, 1), dtype=torch.uint8, device="cuda")
+    y = torch.empty(k, 1, device="cuda")
+    B.laplex_apply(dev(a), dev(b), dev(x), y, ws, 0)
+    torch.cuda.synchronize()
+    del ws
+    log("dense anchors, n = k = 2^25: forward through the scan route")
+    ref, tol = oracle.apply_scan(a, b, x)
+    r_y = worst_ratio(y.cpu().numpy(), ref, tol)
+    log(f"dense anchors, n = k = 2^25: y ratio {r_y:.3g}")
+    assert r_y <= 1.0
 
 
 def test_weighted_gram_full_size(oracle):

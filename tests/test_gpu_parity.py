@@ -596,6 +596,30 @@ def test_temperature_forward_backward(oracle, tau, kind, k, n, batch):
             assert np.array_equal(u.cpu().numpy(), v)
 
 
+@pytest.mark.parametrize("top,tau", [(2.0 ** 14, 5.0), (2.0 ** 14, 0.37), (2.0 ** 14, 1.0 / 3.0), (64.0, 5.0), (64.0, 0.37)])
+@pytest.mark.parametrize("k,n,batch", [(400, 30000, 4), (2000, 9000, 1)])
+def test_temperature_against_the_definition(oracle, top, tau, k, n, batch):
+    """laplex_apply_tau against exp(-tau |a_i - b_j|) itself (App. A), fp64, nothing rounded on the way in.
+    The library scales the anchors in fp32: each product tau*a is off by at most 2^-24 of itself, so every
+    exponent is off by at most delta = 2^-24 tau (|a_i| + |b_j|) <= 2^-23 tau `top`, every term by a factor of at
+    most e^delta, and the bound becomes (e^delta - 1) T + 1e-5 e^delta T + 1e-7: the input-rounding term and
+    the bar of every other parity test."""
+    r = np.random.default_rng(int(top) + int(100 * tau) + k)
+    a = r.uniform(0, top, k).astype(np.float32); b = r.uniform(0, top, n).astype(np.float32)
+    b[: n // 8] = a[r.integers(0, k, n // 8)] + r.uniform(-0.5, 0.5, n // 8).astype(np.float32)   # near neighbours
+    x = r.normal(size=(n, batch)).astype(np.float32)
+    ref, tol = oracle.tau_apply_dense(a, b, tau, x)
+    ws = workspace(k, n, batch)
+    y = torch.full((k, batch), float("nan"), device="cuda")
+    B.laplex_apply_tau(dev(a), dev(b), tau, dev(x), y, ws, 0)
+    torch.cuda.synchronize()
+    got = y.cpu().numpy().astype(np.float64)
+    delta = 2.0 ** -23 * tau * top
+    bound = np.expm1(delta) * tol + RTOL * np.exp(delta) * tol + ATOL
+    worst = float((np.abs(got - ref) / bound).max())
+    assert np.all(np.isfinite(got)) and worst <= 1.0, f"{worst:.3g}x the bound (delta = {delta:.3g})"
+
+
 @pytest.mark.parametrize("tau", [0.25, 3.0])
 def test_temperature_merge_path_and_gram(oracle, tau):
     r = np.random.default_rng(901)
@@ -838,3 +862,67 @@ def test_diag_move_rows_copies_the_named_rows():
     want = torch.zeros(rows, cols, device="cuda")
     want[ids.long()] = src[ids.long()]
     assert torch.equal(dst, want)
+
+
+# ------------------------------------------------------------------ an invalid plan is never silent
+
+@pytest.mark.parametrize("k,n,batch", [(3000, 21000, 1), (40, 70000, 256), (2500, 9000, 8), (5000, 6000, 64)])
+def test_invalid_plan_poisons_every_output(k, n, batch):
+    """The radix sort's bounded wait can, in principle, give up; the plan is then marked invalid.  The mark is
+    planted here through the test hook (no kernel is made to wait): every output of every call that computes
+    from such a plan must be NaN, and a call that rebuilds the plan must be clean again."""
+    r = np.random.default_rng(k + n + batch)
+    a, b = anchors("uniform", r, k, n)
+    x = r.normal(size=(n, batch)).astype(np.float32); g = r.normal(size=(k, batch)).astype(np.float32)
+    da, db, dx, dg = dev(a), dev(b), dev(x), dev(g)
+    ws = workspace(k, n, batch)
+    y = torch.zeros(k, batch, device="cuda")
+    B.laplex_apply(da, db, dx, y, ws, B.LAPLEX_SAVE_SCANS)
+    torch.cuda.synchronize()
+    good = y.clone()
+    assert gpu_plan_status(ws, k + n) == 0 and bool(torch.isfinite(y).all())
+    B.laplex_diag_set_plan_status(ws, k + n, 1)
+    assert gpu_plan_status(ws, k + n) == 1
+    y.zero_()
+    gx = torch.zeros(n, batch, device="cuda"); ga = torch.zeros(k, device="cuda"); gb = torch.zeros(n, device="cuda")
+    B.laplex_apply(da, db, dx, y, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
+    B.laplex_apply_backward(da, db, dx, dg, gx, ga, gb, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
+    torch.cuda.synchronize()
+    for name, t in (("y", y), ("gx", gx), ("ga", ga), ("gb", gb)):
+        assert bool(torch.isnan(t).all()), f"{name}: a value computed from an invalid plan is not NaN"
+    # without saved scans (the backward scans x itself) and for the Gram form on the same workspace size
+    B.laplex_apply_backward(da, db, dx, dg, gx, ga, gb, ws, B.LAPLEX_REUSE_PLAN)
+    torch.cuda.synchronize()
+    assert bool(torch.isnan(ga).all()) and bool(torch.isnan(gx).all()) and bool(torch.isnan(gb).all())
+    # a call that builds the plan again clears the mark
+    B.laplex_apply(da, db, dx, y, ws, 0)
+    torch.cuda.synchronize()
+    assert gpu_plan_status(ws, k + n) == 0 and torch.equal(y, good)
+
+
+def test_invalid_plan_poisons_gram_and_weighted_gram():
+    r = np.random.default_rng(77)
+    n, batch = 20000, 4
+    a, _ = anchors("uniform", r, n, 1)
+    x = r.normal(size=(n, batch)).astype(np.float32); g = r.normal(size=(n, batch)).astype(np.float32)
+    da, dx, dg = dev(a), dev(x), dev(g)
+    ws = workspace(0, n, batch)
+    y = torch.zeros(n, batch, device="cuda"); gx = torch.zeros(n, batch, device="cuda"); ga = torch.zeros(n, device="cuda")
+    B.laplex_gram(da, dx, y, ws, B.LAPLEX_SAVE_SCANS)
+    B.laplex_diag_set_plan_status(ws, n, 1)
+    B.laplex_gram(da, dx, y, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
+    B.laplex_gram_backward(da, dx, dg, gx, ga, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
+    torch.cuda.synchronize()
+    assert bool(torch.isnan(y).all()) and bool(torch.isnan(gx).all()) and bool(torch.isnan(ga).all())
+    k, n = 300, 12000
+    a, b = anchors("uniform", r, k, n)
+    d = r.normal(size=n).astype(np.float32)
+    wsg = torch.empty(B.laplex_wgram_workspace_bytes(k, n), dtype=torch.uint8, device="cuda")
+    m = torch.zeros(k, k, device="cuda")
+    B.laplex_wgram(dev(a), dev(b), dev(d), m, wsg, 0)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(m).all())
+    B.laplex_diag_set_plan_status(wsg, k + n, 1)
+    B.laplex_wgram(dev(a), dev(b), dev(d), m, wsg, B.LAPLEX_REUSE_PLAN)
+    torch.cuda.synchronize()
+    assert bool(torch.isnan(m).all())

@@ -21,11 +21,12 @@ def L():
 
 
 def test_every_declared_symbol_is_exported(L):
-    header = open(os.path.join(ROOT, "include", "laplex.h")).read()
-    declared = set(re.findall(r"\b(laplex_[a-z0-9_]+)\s*\(", header))
-    assert declared == set(B.EXPORTS)
-    for name in declared:
-        assert getattr(L, name) is not None
+    for header_name, names in (("laplex.h", B.EXPORTS), ("laplex_diag.h", B.DIAG_EXPORTS)):
+        header = open(os.path.join(ROOT, "include", header_name)).read()
+        declared = set(re.findall(r"\b(laplex_[a-z0-9_]+)\s*\(", header))
+        assert declared == set(names), header_name
+        for name in declared:
+            assert getattr(L, name) is not None
 
 
 def test_status_strings(L):
@@ -138,6 +139,14 @@ def test_get_plan_status_rejects_bad_arguments(L):
     assert f(FAKE, 1 << 40, 100000, None, None) == B.LAPLEX_ERR_NULL
     assert f(None, 1 << 40, 100000, FAKE, None) == B.LAPLEX_ERR_NULL
     assert f(FAKE, 1000, 100000, FAKE, None) == B.LAPLEX_ERR_WORKSPACE
+
+
+def test_set_plan_status_rejects_bad_arguments(L):
+    f = L.laplex_diag_set_plan_status
+    assert f(FAKE, 1 << 40, 100, 1, None) == B.LAPLEX_ERR_SIZE            # plans sorted by counting have no status word
+    assert f(None, 1 << 40, 100000, 1, None) == B.LAPLEX_ERR_NULL
+    assert f(FAKE + 64, 1 << 40, 100000, 1, None) == B.LAPLEX_ERR_ALIGN
+    assert f(FAKE, 1000, 100000, 1, None) == B.LAPLEX_ERR_WORKSPACE
 
 
 def test_diag_move_rows_rejects_bad_arguments(L):

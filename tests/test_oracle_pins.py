@@ -519,6 +519,59 @@ def test_temperature_gram_gradient_central_difference(oracle):
         assert ga[i] == pytest.approx((loss(a + d, tau) - loss(a - d, tau)) / (2 * h), rel=1e-6, abs=1e-8)
 
 
+def test_scaled_anchors_fp32_is_the_correctly_rounded_product(oracle):
+    """scaled_anchors(fp32=True) is fl32(fl32(tau) * a_i): pinned against the product formed exactly (two 24-bit
+    significands multiply exactly in fp64) and rounded to fp32 once; it is monotone, so equal anchors stay equal
+    and the order of distinct ones is never reversed."""
+    r = rng(55)
+    a = np.concatenate([r.uniform(0, 2.0 ** 14, 4000), -r.uniform(0, 3, 500), [0.0, -0.0, 2.0 ** 14, 1e-30]]).astype(np.float32)
+    for tau in (0.37, 1.0, 5.0, 1.0 / 3.0):
+        got = oracle.scaled_anchors(a, tau)
+        assert got.dtype == np.float32
+        exact = np.float64(np.float32(tau)) * a.astype(np.float64)          # exact: 48 significant bits at most
+        np.testing.assert_array_equal(got, exact.astype(np.float32))
+        order = np.argsort(a, kind="stable")
+        assert np.all(np.diff(got[order].astype(np.float64)) >= 0)
+        np.testing.assert_array_equal(oracle.scaled_anchors(a, tau, fp32=False), float(tau) * a.astype(np.float64))
+
+
+def test_temperature_fp32_route_is_within_the_input_rounding_of_the_definition(oracle):
+    """How far the route on fp32-rounded products tau*a, tau*b (the one the GPU parity tests use) can be from
+    the definition exp(-tau |a_i - b_j|) (App. A): each rounded product is off by at most 2^-24 of itself, so an
+    exponent moves by at most delta = 2^-24 tau (|a_i| + |b_j|) and the sum by at most (e^delta - 1) T."""
+    r = rng(56)
+    k, n, batch = 60, 900, 3
+    for top, tau in ((2.0 ** 14, 5.0), (2.0 ** 14, 0.37), (64.0, 5.0)):
+        a = r.uniform(0, top, k).astype(np.float32); b = r.uniform(0, top, n).astype(np.float32)
+        b[:50] = a[r.integers(0, k, 50)] + np.float32(0.001)               # near neighbours: terms of order one
+        x = r.normal(size=(n, batch))
+        y_def, t_def = oracle.tau_apply_dense(a, b, tau, x)
+        y_32, _ = oracle.tau_apply(a, b, tau, x, fp32=True)
+        delta = 2.0 ** -24 * tau * 2 * top
+        assert np.all(np.abs(y_32 - y_def) <= np.expm1(delta) * t_def + 1e-300)
+        assert np.abs(y_32 - y_def).max() > 0                                  # and the routes do differ
+
+
+def test_gram_gradient_denominators_against_numpy(oracle):
+    """tgx, tga of both Gram backward routes are the sums over absolute values of the summands of gx, ga
+    (the dense kernel matrix formed with numpy, duplicates included)."""
+    r = rng(57)
+    n, batch = 40, 3
+    a = r.uniform(0, 6, n); a[7] = a[3]; a[20] = a[21]
+    x = r.normal(size=(n, batch)); g = r.normal(size=(n, batch))
+    K = np.exp(-np.abs(a[:, None] - a[None, :]))
+    want_tgx = K @ np.abs(g)
+    want_tga = np.sum(np.abs(g) * (K @ np.abs(x)) + np.abs(x) * (K @ np.abs(g)), axis=1)
+    S = -np.sign(a[:, None] - a[None, :])
+    want_ga = np.sum(g * ((S * K) @ x) + x * ((S * K) @ g), axis=1)
+    for f in (oracle.gram_backward_brute, oracle.gram_backward_scan):
+        (gx, ga), (tgx, tga) = f(a, x, g)
+        np.testing.assert_allclose(tgx, want_tgx, rtol=1e-12)
+        np.testing.assert_allclose(tga, want_tga, rtol=1e-12)
+        np.testing.assert_allclose(gx, K @ g, rtol=1e-11, atol=1e-13)
+        assert np.all(np.abs(ga - want_ga) <= 1e-12 * want_tga)
+
+
 # ---------------------------------------------------------------- weighted Gram matrix
 
 @pytest.mark.parametrize("route", ["dense", "scan"])
