@@ -129,6 +129,30 @@ int laplex_apply_backward(const float* a, int64_t k, const float* b, int64_t n,
                           void* ws, size_t ws_bytes, uint32_t flags, laplex_stream_t stream);
 
 /*
+ * For callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  The forward apply with
+ * its workspace inside the library: a file-scope device array of
+ * LAPLEX_STATIC_WORKSPACE_BYTES that every GPU the library runs on holds until
+ * the process ends.  Same arguments, layout, limits and results (bit for bit) as
+ * laplex_apply without `ws`; flags: A_SORTED, B_SORTED only (there is no plan or
+ * saved scan to hand to a later call: LAPLEX_ERR_FLAGS).  Problems whose
+ * laplex_workspace_bytes(k, n, batch) exceeds LAPLEX_STATIC_WORKSPACE_BYTES are
+ * rejected with LAPLEX_ERR_WORKSPACE before anything is enqueued.  The call
+ * allocates and frees nothing; it works on the device that is current when it is
+ * called, which must be the device of `stream`.  The first call on a device looks
+ * the array's address up (no allocation; make that call outside graph capture).
+ * All calls on one device share that device's array: calls that may overlap on
+ * one device (different streams, or threads) race and must be ordered by the
+ * caller.  Nothing in the array has to survive from one call to the next; every
+ * call rebuilds what it reads.
+ */
+#define LAPLEX_STATIC_WORKSPACE_BYTES 33554432ULL /* 32 MiB */
+
+int laplex_apply_static(const float* a, int64_t k, const float* b, int64_t n,
+                        const float* x, int64_t ldx, int64_t batch,
+                        float* y, int64_t ldy, uint32_t flags, laplex_stream_t stream);
+
+/*
  * Square (Gram) form K = L(a,a) (Sec. 3 "Symmetric case": sorted a, a prefix
  * and a suffix scan):  y[m*ldy+t] = sum_j exp(-|a[m]-a[j]|) x[j*ldx+t].
  * Flags: A_SORTED, REUSE_PLAN, SAVE_SCANS.

@@ -32,6 +32,7 @@ LAPLEX_MAX_MERGED = 4294967294
 EXPORTS = (
     "laplex_workspace_bytes", "laplex_apply", "laplex_apply_backward", "laplex_gram",
     "laplex_gram_backward", "laplex_get_perm", "laplex_get_plan_status", "laplex_status_string", "laplex_last_hip_error",
+    "laplex_apply_static",
     "laplex_phased_workspace_bytes", "laplex_phased_apply", "laplex_phased_apply_backward",
     "laplex_apply_tau", "laplex_apply_backward_tau", "laplex_gram_tau", "laplex_gram_backward_tau",
     "laplex_wgram_workspace_bytes", "laplex_wgram",
@@ -44,6 +45,7 @@ DIAG_EXPORTS = (
     "laplex_profile_begin", "laplex_profile_end", "laplex_profile_family", "laplex_scan_tile_rows",
     "laplex_diag_move_rows", "laplex_diag_set_plan_status",
 )
+LAPLEX_STATIC_WORKSPACE_BYTES = 32 << 20
 
 _lib = None
 _P, _I, _Z, _U = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t, ctypes.c_uint32
@@ -84,6 +86,7 @@ def lib() -> ctypes.CDLL:
         L.laplex_scan_tile_rows.argtypes = [_I, ctypes.c_int, ctypes.POINTER(_I)]
         L.laplex_diag_move_rows.argtypes = [_P, _P, _P, _I, _I, _P]
         L.laplex_diag_set_plan_status.argtypes = [_P, _Z, _I, _U, _P]
+        L.laplex_apply_static.argtypes = [_P, _I, _P, _I, _P, _I, _I, _P, _I, _U, _P]
         L.laplex_phased_workspace_bytes.argtypes = [_I, _I, _I, ctypes.POINTER(_Z)]
         L.laplex_phased_apply.argtypes = [_P, _P, _I, _P, _P, _I, _P, _I, _I, _P, _I, _P, _Z, _U, _P]
         L.laplex_phased_apply_backward.argtypes = [_P, _P, _I, _P, _P, _I, _P, _I, _P, _I, _I,
@@ -151,6 +154,12 @@ def laplex_apply(a, b, x, y, ws, flags: int = 0, stream=None) -> None:
     """y (k, batch) <- L(a, b) x, x (n, batch); ws a uint8 workspace tensor."""
     _check(lib().laplex_apply(_ptr(a), a.numel(), _ptr(b), b.numel(), _ptr(x), _ld(x), _batch(x),
                               _ptr(y), _ld(y), _ptr(ws), ws.numel(), flags, _stream(stream)))
+
+
+def laplex_apply_static(a, b, x, y, flags: int = 0, stream=None) -> None:
+    """laplex_apply with the workspace inside the library (problems up to LAPLEX_STATIC_WORKSPACE_BYTES of it)."""
+    _check(lib().laplex_apply_static(_ptr(a), a.numel(), _ptr(b), b.numel(), _ptr(x), _ld(x), _batch(x),
+                                     _ptr(y), _ld(y), flags, _stream(stream)))
 
 
 def laplex_apply_backward(a, b, x, gy, gx, ga, gb, ws, flags: int = 0, stream=None) -> None:

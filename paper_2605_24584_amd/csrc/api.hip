@@ -574,6 +574,48 @@ int laplex_apply(const float* a, int64_t k, const float* b, int64_t n,
     return apply_impl(a, k, b, n, x, ldx, batch, y, ldy, ws, ws_bytes, flags, 1.0f, stream);
 }
 
+// The workspace of laplex_apply_static: one copy per device, held from the moment the library is loaded on it.
+// In host code the array's name is only a handle; its device address is looked up once per device.
+static __device__ __align__(256) unsigned char scratch[LAPLEX_STATIC_WORKSPACE_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Address of the current device's copy of `scratch` (looked up on the first call on that device).
+int static_scratch(void** out)
+{
+    int dev = -1;
+    LAPLEX_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return hip_fail(hipErrorInvalidDevice);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        LAPLEX_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return hip_fail(hipErrorInvalidSymbol);
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return LAPLEX_OK;
+}
+}  // namespace
+
+int laplex_apply_static(const float* a, int64_t k, const float* b, int64_t n,
+                        const float* x, int64_t ldx, int64_t batch, float* y, int64_t ldy,
+                        uint32_t flags, laplex_stream_t stream)
+{
+    if (flags & ~(uint32_t)(LAPLEX_A_SORTED | LAPLEX_B_SORTED)) return LAPLEX_ERR_FLAGS;
+    // every argument error, and a problem that does not fit the array, is reported before any HIP call
+    LAPLEX_CHECK(apply_check(a, k, b, n, x, ldx, batch, y, ldy, flags));
+    if (k == 0 || batch == 0) return LAPLEX_OK;
+    if (make_layout(k + n, k, batch).total > LAPLEX_STATIC_WORKSPACE_BYTES) return LAPLEX_ERR_WORKSPACE;
+    void* ws = nullptr;
+    LAPLEX_CHECK(static_scratch(&ws));
+    // every kernel takes the looked-up address, as it takes the caller's workspace in laplex_apply
+    return apply_impl(a, k, b, n, x, ldx, batch, y, ldy, ws, LAPLEX_STATIC_WORKSPACE_BYTES, flags, 1.0f, stream);
+}
+
 int laplex_apply_backward(const float* a, int64_t k, const float* b, int64_t n,
                           const float* x, int64_t ldx, const float* gy, int64_t ldgy, int64_t batch,
                           float* gx, int64_t ldgx, float* ga, float* gb,

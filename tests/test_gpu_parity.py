@@ -895,7 +895,7 @@ def test_invalid_plan_poisons_every_output(k, n, batch):
     torch.cuda.synchronize()
     assert bool(torch.isnan(ga).all()) and bool(torch.isnan(gx).all()) and bool(torch.isnan(gb).all())
     # a call that builds the plan again clears the mark
-    B.laplex_apply(da, db, dx, y, ws, 0)
+    B.laplex_apply(da, db, dx, y, ws, B.LAPLEX_SAVE_SCANS)
     torch.cuda.synchronize()
     assert gpu_plan_status(ws, k + n) == 0 and torch.equal(y, good)
 

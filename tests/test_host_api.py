@@ -149,6 +149,33 @@ def test_set_plan_status_rejects_bad_arguments(L):
     assert f(FAKE, 1000, 100000, 1, None) == B.LAPLEX_ERR_WORKSPACE
 
 
+def test_apply_static_rejects_bad_arguments_before_touching_the_gpu(L):
+    """The entry point without a workspace argument: every argument error, and a problem larger than the
+    library's own array, is reported on the host (no device is looked at)."""
+    f = L.laplex_apply_static
+
+    def args(k=8, n=8, batch=4, a=FAKE, b=FAKE, x=FAKE, y=FAKE, ldx=None, ldy=None, flags=0):
+        return (a, k, b, n, x, batch if ldx is None else ldx, batch, y, batch if ldy is None else ldy, flags, None)
+
+    assert f(*args(a=None)) == B.LAPLEX_ERR_NULL
+    assert f(*args(x=None)) == B.LAPLEX_ERR_NULL
+    assert f(*args(y=None)) == B.LAPLEX_ERR_NULL
+    assert f(*args(k=-1)) == B.LAPLEX_ERR_SIZE
+    assert f(*args(ldx=3)) == B.LAPLEX_ERR_LD
+    assert f(*args(a=FAKE + 2)) == B.LAPLEX_ERR_ALIGN
+    assert f(*args(flags=B.LAPLEX_REUSE_PLAN)) == B.LAPLEX_ERR_FLAGS     # no plan is handed from call to call
+    assert f(*args(flags=B.LAPLEX_SAVE_SCANS)) == B.LAPLEX_ERR_FLAGS
+    assert f(*args(flags=64)) == B.LAPLEX_ERR_FLAGS
+    # the size limit follows laplex_workspace_bytes: the first problem that does not fit is rejected
+    assert ws_bytes(L, 1000, 100000, 8)[1] <= B.LAPLEX_STATIC_WORKSPACE_BYTES
+    assert ws_bytes(L, 1000, 4000000, 8)[1] > B.LAPLEX_STATIC_WORKSPACE_BYTES
+    assert f(*args(k=1000, n=4000000, batch=8)) == B.LAPLEX_ERR_WORKSPACE
+    assert f(*args(k=0, a=None, y=None)) == B.LAPLEX_OK
+    assert f(*args(batch=0, x=None, y=None)) == B.LAPLEX_OK
+    header = open(os.path.join(ROOT, "include", "laplex.h")).read()
+    assert re.search(r"#define LAPLEX_STATIC_WORKSPACE_BYTES (\d+)ULL", header).group(1) == str(B.LAPLEX_STATIC_WORKSPACE_BYTES)
+
+
 def test_diag_move_rows_rejects_bad_arguments(L):
     f = L.laplex_diag_move_rows
     assert f(FAKE, FAKE, FAKE, -1, 256, None) == B.LAPLEX_ERR_SIZE
