@@ -43,7 +43,7 @@ EXPORTS = (
 # include/laplex_diag.h: hooks for benchmarks and tests
 DIAG_EXPORTS = (
     "laplex_profile_begin", "laplex_profile_end", "laplex_profile_family", "laplex_scan_tile_rows",
-    "laplex_diag_move_rows", "laplex_diag_set_plan_status",
+    "laplex_diag_move_rows", "laplex_diag_set_plan_status", "laplex_diag_set_route_min",
 )
 LAPLEX_STATIC_WORKSPACE_BYTES = 32 << 20
 
@@ -86,6 +86,7 @@ def lib() -> ctypes.CDLL:
         L.laplex_scan_tile_rows.argtypes = [_I, ctypes.c_int, ctypes.POINTER(_I)]
         L.laplex_diag_move_rows.argtypes = [_P, _P, _P, _I, _I, _P]
         L.laplex_diag_set_plan_status.argtypes = [_P, _Z, _I, _U, _P]
+        L.laplex_diag_set_route_min.argtypes = [_I]
         L.laplex_apply_static.argtypes = [_P, _I, _P, _I, _P, _I, _I, _P, _I, _U, _P]
         L.laplex_phased_workspace_bytes.argtypes = [_I, _I, _I, ctypes.POINTER(_Z)]
         L.laplex_phased_apply.argtypes = [_P, _P, _I, _P, _P, _I, _P, _I, _I, _P, _I, _P, _Z, _U, _P]
@@ -193,6 +194,11 @@ def laplex_get_plan_status(ws, count: int, status_out, stream=None) -> None:
 def laplex_diag_set_plan_status(ws, count: int, value: int, stream=None) -> None:
     """Test hook: overwrite the status word of the plan in ws (0 = valid, 1 = invalid)."""
     _check(lib().laplex_diag_set_plan_status(_ptr(ws), ws.numel(), count, value, _stream(stream)))
+
+
+def laplex_diag_set_route_min(merged_positions: int) -> None:
+    """Test hook: batch-1 problems from this many merged positions on take the routes without random accesses."""
+    _check(lib().laplex_diag_set_route_min(merged_positions))
 
 
 def laplex_diag_move_rows(src, dst, row_ids, stream=None) -> None:

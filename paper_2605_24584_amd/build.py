@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblaplex.so")
-SOURCES = ["api.hip", "sort_kernels.hip", "scan_kernels.hip", "phase_kernels.hip", "gram_kernels.hip", "small_kernels.hip"]
+SOURCES = ["api.hip", "sort_kernels.hip", "scan_kernels.hip", "phase_kernels.hip", "gram_kernels.hip", "small_kernels.hip", "permute_kernels.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",

@@ -126,6 +126,61 @@ Plan plan_of(const Layout& L, char* ws)
                 narrow ? reinterpret_cast<float*>(ws + L.off_stage) : nullptr};
 }
 
+// ----------------------------------------------------------------------------
+// Batch 1 with many rows: x and gy reach the sorted order, and the results the caller's order, as records through
+// partition passes (permute_kernels.hip) instead of by one random access per value.  Below g_permute_min merged
+// positions the tables fit the device's caches and the random accesses are as fast.
+// ----------------------------------------------------------------------------
+std::atomic<int64_t> g_permute_min{int64_t(1) << 26};
+
+bool use_permute(const Layout& L) { return L.permute && L.N >= g_permute_min.load(std::memory_order_relaxed); }
+
+PermuteJob permute_job(const Layout& L, char* ws, const char* tag)
+{
+    PermuteJob J;
+    for (int lv = 0; lv < 2; ++lv) {
+        J.rec_d[lv] = reinterpret_cast<uint32_t*>(ws + L.off_rec_d[lv]);
+        J.rec_v0[lv] = reinterpret_cast<float*>(ws + L.off_rec_v0[lv]);
+        J.rec_v1[lv] = reinterpret_cast<float*>(ws + L.off_rec_v1[lv]);
+    }
+    J.status = reinterpret_cast<uint32_t*>(ws + L.off_pt_status);
+    J.tickets = reinterpret_cast<uint32_t*>(ws + L.off_pt_tickets);
+    J.error = reinterpret_cast<uint32_t*>(ws + L.off_counters) + kPlanStatusWord;
+    J.poison = J.error;
+    J.tag = tag;
+    return J;
+}
+
+// dst[rank[first_id + i]] = src[i * ld] for i < count, zero at every other sorted position: rows of the caller's matrix
+// (the inputs: first_id = k; the outputs: first_id = 0) into sorted order.
+int rows_to_sorted(const Layout& L, char* ws, const float* src, int64_t ld, int64_t first_id, int64_t count, float* dst,
+                   const char* tag, hipStream_t st)
+{
+    PermuteJob J = permute_job(L, ws, tag);
+    J.source = PermuteJob::kValues;
+    J.rank = reinterpret_cast<const uint32_t*>(ws + L.off_rank) + first_id;
+    J.val0 = src; J.ld_val = ld; J.source_count = count; J.dest_count = L.N;
+    J.values = 1; J.out0 = dst; J.ld0 = 1;
+    LAPLEX_HIP(launch_permute(J, st));
+    return LAPLEX_OK;
+}
+
+// The outputs of the sorted rows whose id lies in [lo, hi) go home: out0[(id - lo) * ld0] = sorted2[j][first],
+// out1[(id - lo) * ld1] = sorted2[j][1] (out1 may be null).
+int sorted_to_rows(const Layout& L, char* ws, uint32_t lo, uint32_t hi, int first, float* out0, int64_t ld0,
+                   float* out1, int64_t ld1, const char* tag, hipStream_t st)
+{
+    const float* sorted2 = reinterpret_cast<const float*>(ws + L.off_sorted2);
+    PermuteJob J = permute_job(L, ws, tag);
+    J.source = PermuteJob::kRows;
+    J.ids = reinterpret_cast<const uint32_t*>(ws + L.off_ids); J.lo = lo; J.hi = hi;
+    J.val0 = sorted2 + first; J.val1 = sorted2 + 1; J.ld_val = 2;
+    J.source_count = L.N; J.dest_count = (int64_t)hi - (int64_t)lo;
+    J.values = out1 ? 2 : 1; J.out0 = out0; J.ld0 = ld0; J.out1 = out1; J.ld1 = ld1;
+    LAPLEX_HIP(launch_permute(J, st));
+    return LAPLEX_OK;
+}
+
 // Sort (or merge) the anchors and compute the neighbour decays, unless the plan is reused.
 int build_plan(const float* a, int64_t k, const float* b, int64_t n, float tau, const Layout& L, char* ws,
                uint32_t flags, bool both_sorted, hipStream_t st)
@@ -144,6 +199,14 @@ int build_plan(const float* a, int64_t k, const float* b, int64_t n, float tau, 
         LAPLEX_HIP(launch_onesweep_sort(a, k, b, n, tau, keys0, P.ids, keys1, ids1, small,
                                         reinterpret_cast<unsigned long long*>(ws + L.off_status), st));
         LAPLEX_HIP(launch_decay(keys0, keys1, P.ids, ids1, small, P.dh, P.pk, counters, L.N, st));
+    }
+    if (use_permute(L)) {        // the inverse permutation, part of the plan: rank[ids[j]] = j
+        PermuteJob J = permute_job(L, ws, "rank");
+        J.source = PermuteJob::kRowIndex;
+        J.ids = P.ids; J.source_count = L.N; J.dest_count = L.N;
+        J.values = 1; J.out0 = reinterpret_cast<float*>(ws + L.off_rank); J.ld0 = 1;
+        J.poison = nullptr;          // positions, not values: an invalid plan shows in the results
+        LAPLEX_HIP(launch_permute(J, st));
     }
     return LAPLEX_OK;
 }
@@ -212,7 +275,7 @@ struct Wgram64Layout {
 Wgram64Layout wgram64_layout(int64_t k, int64_t n)
 {
     Wgram64Layout G;
-    G.inner = make_layout(k + n, k, 1).total;
+    G.inner = make_layout(k + n, k, 1, false).total;
     size_t o = align_up(G.inner);
     G.off_u = o;    o = align_up(o + sizeof(double) * (size_t)k);
     G.off_v = o;    o = align_up(o + sizeof(double) * (size_t)k);
@@ -336,11 +399,21 @@ static int apply_impl(const float* a, int64_t k, const float* b, int64_t n,
     p.res_lo = 0; p.res_hi = (uint32_t)k;
     p.out_p = y; p.ld_p = ldy;
     p.out_z = (flags & LAPLEX_SAVE_SCANS) ? P.z : nullptr;
+    p.stage = (flags & LAPLEX_SAVE_SCANS) ? P.xs : P.stage;   // kept for the backward's weights when saving
+    p.tag = "fwd";
+    if (use_permute(L)) {          // x into sorted order, both outputs of a row by its sorted position, then home
+        float* const sorted2 = reinterpret_cast<float*>(w + L.off_sorted2);
+        LAPLEX_CHECK(rows_to_sorted(L, w, x, ldx, k, n, p.stage, "fwd", st));
+        p.inj_sorted = p.out_sorted = true;
+        p.out_p = sorted2; p.ld_p = 2;
+        if (p.out_z) { p.out_z = sorted2 + 1; p.ld_z = 2; }
+        LAPLEX_HIP(launch_scan(p, L, w, st));
+        LAPLEX_CHECK(sorted_to_rows(L, w, 0, (uint32_t)k, 0, y, ldy, p.out_z ? P.z : nullptr, 1, "fwd", st));
+        return LAPLEX_OK;
+    }
     float* const pairs = reinterpret_cast<float*>(w + L.off_pair);
     const bool paired = batch == 1 && p.out_z != nullptr;      // y and the saved scan of a row as one 8-byte slot
     if (paired) { p.out_p = pairs; p.ld_p = 2; p.out_z = pairs + 1; p.ld_z = 2; }
-    p.stage = (flags & LAPLEX_SAVE_SCANS) ? P.xs : P.stage;   // kept for the backward's weights when saving
-    p.tag = "fwd";
     LAPLEX_HIP(launch_scan(p, L, w, st));
     if (paired) LAPLEX_HIP(launch_unpair(pairs, k, y, ldy, P.z, st));
     return LAPLEX_OK;
@@ -404,6 +477,8 @@ static int apply_backward_impl(const float* a, int64_t k, const float* b, int64_
     }
     const bool sorted = (flags & LAPLEX_A_SORTED) && (flags & LAPLEX_B_SORTED);
     LAPLEX_CHECK(build_plan(a, k, b, n, tau, L, w, flags, sorted, st));
+    const bool routed = use_permute(L);        // batch 1, many rows: no random accesses (see rows_to_sorted)
+    float* const sorted2 = reinterpret_cast<float*>(w + L.off_sorted2);
     if (ga) {
         if (!(flags & LAPLEX_SAVE_SCANS)) {   // strict scans of x at the outputs, not kept by the forward
             ScanProblem p = problem(P, L);
@@ -412,13 +487,32 @@ static int apply_backward_impl(const float* a, int64_t k, const float* b, int64_
             p.out_z = P.z;
             p.stage = P.xs;
             p.tag = "rescan";
+            if (routed) {
+                LAPLEX_CHECK(rows_to_sorted(L, w, x, ldx, k, n, P.xs, "rescan", st));
+                p.inj_sorted = p.out_sorted = true;
+                p.out_z = sorted2 + 1; p.ld_z = 2;
+            }
             LAPLEX_HIP(launch_scan(p, L, w, st));
+            if (routed) LAPLEX_CHECK(sorted_to_rows(L, w, 0, (uint32_t)k, 1, P.z, 1, nullptr, 1, "rescan", st));
         }
         LAPLEX_HIP(launch_rowdot(gy, ldgy, P.z, batch, k, batch, ga, st));
     }
     // sorted-order x is in the saved region if the forward kept it or the re-scan above just wrote it
     const bool have_xs = (flags & LAPLEX_SAVE_SCANS) || ga;
-    if (gx || gb) {
+    if (routed && (gx || gb)) {
+        if (gb && !have_xs) LAPLEX_CHECK(rows_to_sorted(L, w, x, ldx, k, n, P.xs, "bwd_x", st));    // the weights of gb
+        LAPLEX_CHECK(rows_to_sorted(L, w, gy, ldgy, 0, k, P.stage, "bwd", st));
+        ScanProblem p = problem(P, L);
+        p.inj = gy; p.ld_inj = ldgy; p.inj_lo = 0; p.inj_hi = (uint32_t)k;
+        p.res_lo = (uint32_t)k; p.res_hi = (uint32_t)(k + n);
+        p.stage = P.stage; p.inj_sorted = p.out_sorted = true;
+        if (gx) { p.out_p = sorted2; p.ld_p = 2; }
+        if (gb) { p.out_red = sorted2 + 1; p.ld_red = 2; p.w = x; p.ld_w = ldx; p.wstage = P.xs; }
+        p.tag = "bwd";
+        LAPLEX_HIP(launch_scan(p, L, w, st));
+        if (gx) LAPLEX_CHECK(sorted_to_rows(L, w, (uint32_t)k, (uint32_t)(k + n), 0, gx, ldgx, gb, 1, "bwd", st));
+        else LAPLEX_CHECK(sorted_to_rows(L, w, (uint32_t)k, (uint32_t)(k + n), 1, gb, 1, nullptr, 1, "bwd", st));
+    } else if (gx || gb) {
         ScanProblem p = problem(P, L);
         p.inj = gy; p.ld_inj = ldgy; p.inj_lo = 0; p.inj_hi = (uint32_t)k;
         p.res_lo = (uint32_t)k; p.res_hi = (uint32_t)(k + n);
@@ -793,7 +887,7 @@ int laplex_wgram(const float* a, int64_t k, const float* b, int64_t n, const flo
     if (misaligned(ws, 256)) return LAPLEX_ERR_ALIGN;
     if (ws_bytes < G.total) return LAPLEX_ERR_WORKSPACE;
     char* w = static_cast<char*>(ws);
-    const Layout L = make_layout(k + n, k, 1);
+    const Layout L = make_layout(k + n, k, 1, false);
     const Plan P = plan_of(L, w);
     // the plan of the doubled anchors: its decays are exp(-2 gap), the kernel K = L(2a) of the theorem
     LAPLEX_CHECK(build_wgram_plan(a, k, b, n, L, P, w, flags, st));
@@ -840,7 +934,7 @@ int laplex_wgram_f64(const float* a, int64_t k, const float* b, int64_t n, const
     if (misaligned(ws, 256)) return LAPLEX_ERR_ALIGN;
     if (ws_bytes < G.total) return LAPLEX_ERR_WORKSPACE;
     char* w = static_cast<char*>(ws);
-    const Layout L = make_layout(k + n, k, 1);
+    const Layout L = make_layout(k + n, k, 1, false);
     const Plan P = plan_of(L, w);
     LAPLEX_CHECK(build_wgram_plan(a, k, b, n, L, P, w, flags, st));
     LAPLEX_HIP(launch_wgram_f64(P.ids, P.pk, a, d, k, k + n, reinterpret_cast<double*>(w + G.off_summ),
@@ -1049,6 +1143,13 @@ int laplex_diag_set_plan_status(void* ws, size_t ws_bytes, int64_t count, uint32
     static_assert(sizeof(bits) == sizeof(value), "the word is written as the bit pattern of a float");
     __builtin_memcpy(&bits, &value, sizeof(bits));
     LAPLEX_HIP(launch_fill(word, 1, 1, 1, bits, stream));
+    return LAPLEX_OK;
+}
+
+int laplex_diag_set_route_min(int64_t merged_positions)
+{
+    if (merged_positions < 0) return LAPLEX_ERR_SIZE;
+    g_permute_min.store(merged_positions);
     return LAPLEX_OK;
 }
 

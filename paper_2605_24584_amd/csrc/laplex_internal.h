@@ -57,6 +57,22 @@ constexpr int kStageMaxBatch = 8;
 constexpr int kSpineItems = 8;    // tile summaries per row-lane in the chunked spine kernels, at most (ScanGeom::spine_items)
 constexpr int kSpineThreads = 1024;
 
+// ----------------------------------------------------------------------------
+// Batch 1, many rows: values move between the caller's order and the sorted order as records through
+// partition passes instead of by random accesses (permute_kernels.hip).  A window is the stretch of
+// destinations that the last pass places inside LDS; a partition level has at most 2^9 buckets.
+// ----------------------------------------------------------------------------
+constexpr int kPermuteWindowBits = 13;
+constexpr int kPermuteMaxBucketBits = 9;
+bool permute_supported(int64_t source_count, int64_t dest_count);      // destinations fit two partition levels
+size_t permute_status_words(int64_t source_count, int64_t dest_count);  // look-back words of both levels
+// records that a level's output array must hold for `dest_count` destinations: whole bucket regions
+inline int64_t permute_capacity(int64_t dest_count)
+{
+    const int64_t region = (int64_t)1 << (kPermuteWindowBits + kPermuteMaxBucketBits);
+    return (dest_count + region - 1) / region * region;
+}
+
 // The rows a downsweep workgroup owns are a "block" (tile_rows of them).  The spine works on
 // "tiles": one block each, except in the wide geometry (64 lanes across the batch, 4 columns per
 // lane, 64 rows per block), where a tile is 2^kWideSubShift consecutive blocks: a summary or a carry
@@ -143,10 +159,17 @@ struct Layout {
     // small problems (N <= kSmallMax): f32[N][batch], the strict scans of the backward's second problem
     size_t off_small = 0;
     size_t off_pair = 0;         // f32[max(result rows)][2], batch 1 only
+    // batch 1 beyond the small path: the routes through sorted order without random accesses
+    bool permute = false;        // the regions below exist
+    size_t off_rank = 0;         // u32[N]     plan: rank[id] = sorted position of anchor id
+    size_t off_sorted2 = 0;      // f32[N][2]  scratch: the (up to) two outputs of a scan problem per sorted row
+    size_t off_rec_d[2] = {0, 0}, off_rec_v0[2] = {0, 0}, off_rec_v1[2] = {0, 0};   // records of the two partition levels
+    size_t off_pt_status = 0;    // u32[permute_status_words]  look-back words
+    size_t off_pt_tickets = 0;   // u32[64]    tile tickets of the two levels
     size_t total = 0;
 };
 
-inline Layout make_layout(int64_t N, int64_t zrows, int64_t batch)
+inline Layout make_layout(int64_t N, int64_t zrows, int64_t batch, bool permute_regions = true)
 {
     Layout L;
     L.N = N; L.zrows = zrows; L.batch = batch;
@@ -159,6 +182,9 @@ inline Layout make_layout(int64_t N, int64_t zrows, int64_t batch)
     L.off_z = o;    o = align_up(o + sizeof(float) * (size_t)zrows * (size_t)batch);
     const size_t stage_bytes = batch <= kStageMaxBatch ? sizeof(float) * (size_t)N * (size_t)batch : 0;
     L.off_xs = o;   o = align_up(o + stage_bytes);
+    L.permute = permute_regions && batch == 1 && N > kSmallMax && permute_supported(N, N);
+    L.off_rank = o;
+    if (L.permute) o = align_up(o + sizeof(uint32_t) * (size_t)N);
     L.off_scratch = o;
 
     // sort view
@@ -206,6 +232,20 @@ inline Layout make_layout(int64_t N, int64_t zrows, int64_t batch)
     const int64_t pair_rows = zrows > N - zrows ? zrows : N - zrows;
     if (batch == 1) c = align_up(L.off_pair + sizeof(float) * 2 * (size_t)pair_rows);
     L.total = s > c ? s : c;
+    if (L.permute) {
+        size_t q = align_up(L.total);
+        const int64_t side = zrows > N - zrows ? zrows : N - zrows;      // result rows of a problem: at most this many
+        const size_t cap1 = (size_t)permute_capacity(N), cap2 = (size_t)permute_capacity(side);
+        L.off_sorted2 = q; q = align_up(q + sizeof(float) * 2 * (size_t)N);
+        for (int lv = 0; lv < 2; ++lv) {
+            L.off_rec_d[lv] = q;  q = align_up(q + sizeof(uint32_t) * cap1);
+            L.off_rec_v0[lv] = q; q = align_up(q + sizeof(float) * cap1);
+            L.off_rec_v1[lv] = q; q = align_up(q + sizeof(float) * cap2);
+        }
+        L.off_pt_status = q;  q = align_up(q + sizeof(uint32_t) * permute_status_words(N, N));
+        L.off_pt_tickets = q; q = align_up(q + sizeof(uint32_t) * 64);
+        L.total = q;
+    }
     L.off_small = align_up(L.total);
     if (N <= kSmallMax) L.total = align_up(L.off_small + sizeof(float) * (size_t)N * (size_t)batch);
     return L;
@@ -262,6 +302,29 @@ hipError_t launch_unpair(const float* pairs, int64_t rows, float* first, int64_t
 //                              + (zs ? v * zs[(id-res_lo)*batch + t] : 0) )
 // Any of out_p / out_z / out_red may be null; strict scans run only if out_z or
 // out_red is wanted.
+// One move of values between the caller's order and the sorted order (launch_permute).
+//   kRows:     source row j of the sorted sequence goes to destination ids[j] - lo if lo <= ids[j] < hi (results back to
+//              the caller's order); its values are val0[j * ld_val] (and val1[j * ld_val])
+//   kRowIndex: destination ids[j], value j itself (as a 32-bit word): the inverse permutation
+//   kValues:   source element i goes to destination rank[i] with value val0[i * ld_val] (the caller's rows into sorted order)
+// The last pass writes out0[d * ld0] (and out1[d * ld1]) for EVERY destination d < dest_count: zero where no record arrived.
+struct PermuteJob {
+    enum Source { kRows = 0, kRowIndex = 1, kValues = 2 };
+    int source = kRows;
+    const uint32_t* ids = nullptr; uint32_t lo = 0, hi = 0;
+    const uint32_t* rank = nullptr;
+    const float* val0 = nullptr; const float* val1 = nullptr; int64_t ld_val = 1;
+    int64_t source_count = 0, dest_count = 0;
+    int values = 1;                                    // values per record: 1 or 2
+    float* out0 = nullptr; int64_t ld0 = 1; float* out1 = nullptr; int64_t ld1 = 1;
+    uint32_t* rec_d[2] = {nullptr, nullptr}; float* rec_v0[2] = {nullptr, nullptr}; float* rec_v1[2] = {nullptr, nullptr};
+    uint32_t* status = nullptr; uint32_t* tickets = nullptr;
+    uint32_t* error = nullptr;                         // set to 1 if a tile gives up its bounded wait (the plan's status word)
+    const uint32_t* poison = nullptr;                  // nonzero: every value written becomes a NaN (null: never)
+    const char* tag = "move";                          // names the timing families permute_part.<tag>, permute_final.<tag>
+};
+hipError_t launch_permute(const PermuteJob& J, hipStream_t st);
+
 struct ScanProblem {
     const uint32_t* ids; const float* dh; const float* pk; int64_t N;
     const float* inj; int64_t ld_inj; uint32_t inj_lo, inj_hi;
@@ -274,6 +337,9 @@ struct ScanProblem {
     float* stage;          // narrow batches: the reduce writes the injected rows here in sorted order, the downsweep reads them back
     const float* wstage;   // narrow batches: the weights w in sorted order (an earlier problem's stage), or null
     const char* tag;   // names the timing families: scan_reduce.<tag>, scan_spine.<tag>, scan_down.<tag>
+    // batch 1, routes without random accesses: `stage` already holds the injected rows in sorted order (zero elsewhere), and
+    // the outputs of result row j of the sorted sequence go to out_p[j * ld_p], out_z[j * ld_z], out_red[j * ld_red]
+    bool inj_sorted = false, out_sorted = false;
 };
 hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStream_t st);
 

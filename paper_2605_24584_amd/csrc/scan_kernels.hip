@@ -77,6 +77,8 @@ struct ScanArgs {
     int reduce_from_list, down_from_list;
     int few_inj_ok, few_res_ok;   // the block flags kFlagFewInj / kFlagFewRes may be set
     int pair_out;                 // batch 1: out_p and the row's second output (out_z, else out_red) are the halves of an 8-byte slot
+    int inj_sorted;               // batch 1: `stage` already holds the injected rows in sorted order: nothing is gathered
+    int out_sorted;               // batch 1: outputs are indexed by the sorted row, not by the id (a later pass takes them home)
 };
 
 constexpr int kFlagInj = 1, kFlagRes = 2;
@@ -544,12 +546,18 @@ k_scan_reduce(const ScanArgs A)
     // the injected rows are asked for before the flags meet: the gathers travel while the workgroup waits at the
     // barriers (a row that is not injected is not loaded, it reads as zero)
     float v[ITEMS][VEC];
-    load_injected<VEC, kStreamRows<VEC>>(A, T, col0, col_ok, v);
+    if (A.inj_sorted) {     // uniform: the rows arrive in sorted order (zero where nothing is injected)
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i)
+            load_vec_or_zero<VEC>(v[i], A.stage, (row0 + i) * A.batch + col0, col_ok && T.id[i] != 0xFFFFFFFFu);
+    } else {
+        load_injected<VEC, kStreamRows<VEC>>(A, T, col0, col_ok, v);
+    }
     __syncthreads();
     if (c == 0 && mine) atomicOr(&tile_flags, mine);
     __syncthreads();
     if (tid == 0 && blockIdx.y == 0) A.blk_flags[tile] = (uint32_t)tile_flags;      // in this geometry a tile is one block
-    if ((tile_flags & kFlagInj) && A.stage && col_ok) {     // uniform: the downsweep finds the tile's rows in sorted order
+    if (!A.inj_sorted && (tile_flags & kFlagInj) && A.stage && col_ok) {     // uniform: the downsweep finds the tile's rows in sorted order
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i)
             if (T.id[i] != 0xFFFFFFFFu) store_vec<VEC>(A.stage + (row0 + i) * A.batch + col0, v[i]);
@@ -1288,10 +1296,11 @@ k_scan_down(const ScanArgs A)
             Z[e] = taint(G[e] - Efi[e], poison);
         }
         const bool is_res = T.id[i] >= A.res_lo && T.id[i] < A.res_hi;
-        const int64_t rr = (int64_t)T.id[i] - (int64_t)A.res_lo;
+        // where the row's outputs go: by its id, or (routes through sorted order) by its position in the sorted sequence
+        const int64_t rr = A.out_sorted ? row0 + i : (int64_t)T.id[i] - (int64_t)A.res_lo;
         if (VEC == 1 && A.pair_out) {      // uniform; batch 1: both outputs of the row with one 8-byte store
             float second = Z[0];
-            if (want_red) second = (ZS ? vz[ZS ? i : 0] : 0.0f) + wrow[0] * Z[0];
+            if (want_red) second = taint((ZS ? vz[ZS ? i : 0] : 0.0f) + wrow[0] * Z[0], poison);
             if (is_res && col_ok) *reinterpret_cast<float2*>(A.out_p + rr * 2) = make_float2(P[0], second);
             continue;
         }
@@ -1378,7 +1387,7 @@ k_scan_down_sparse(const ScanArgs A)
 #pragma unroll
     for (int i = 0; i < ITEMS; ++i) {
         const bool is_res = T.id[i] >= A.res_lo && T.id[i] < A.res_hi;
-        const int64_t rr = (int64_t)T.id[i] - (int64_t)A.res_lo;
+        const int64_t rr = A.out_sorted ? row0 + i : (int64_t)T.id[i] - (int64_t)A.res_lo;
         const float kf = Df * cf[i], kb = Db * cb[i];
         const bool seen_f = Hf | ((hf >> i) & 1), seen_b = Hb | ((hb >> i) & 1);
         float P[VEC], Z[VEC];
@@ -1853,6 +1862,7 @@ hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStrea
     A.out_p = p.out_p; A.ld_p = p.ld_p; A.out_z = p.out_z; A.ld_z = p.ld_z ? p.ld_z : p.batch;
     A.out_red = p.out_red; A.ld_red = p.ld_red ? p.ld_red : 1; A.w = p.w; A.ld_w = p.ld_w; A.zs = p.zs;
     A.stage = p.stage; A.wstage = p.wstage;
+    A.inj_sorted = p.inj_sorted ? 1 : 0; A.out_sorted = p.out_sorted ? 1 : 0;
     A.batch = p.batch; A.bpad = L.bpad;
     {
         const bool z_pair = p.out_z && !p.out_red && p.out_z == p.out_p + 1 && p.ld_z == 2;

@@ -926,3 +926,102 @@ def test_invalid_plan_poisons_gram_and_weighted_gram():
     B.laplex_wgram(dev(a), dev(b), dev(d), m, wsg, B.LAPLEX_REUSE_PLAN)
     torch.cuda.synchronize()
     assert bool(torch.isnan(m).all())
+
+
+# ------------------------------------------------------------------ batch 1: the routes without random accesses
+
+@pytest.fixture
+def routed():
+    """Batch-1 problems of any size (beyond the small path) take the partition routes while the test runs."""
+    B.laplex_diag_set_route_min(0)
+    yield
+    B.laplex_diag_set_route_min(1 << 26)
+
+
+def _apply_both_ways(a, b, x, g, save, want=(True, True, True), merge=False):
+    """forward + backward at batch 1, on the current route; returns (y, gx, ga, gb) as numpy arrays (None where not wanted)"""
+    k, n = a.size, b.size
+    ws = workspace(k, n, 1)
+    da, db, dx, dg = dev(a), dev(b), dev(x), dev(g)
+    y = torch.full((k, 1), float("nan"), device="cuda")
+    gx = torch.full((n, 1), float("nan"), device="cuda") if want[0] else None
+    ga = torch.full((k,), float("nan"), device="cuda") if want[1] else None
+    gb = torch.full((n,), float("nan"), device="cuda") if want[2] else None
+    f = (B.LAPLEX_A_SORTED | B.LAPLEX_B_SORTED) if merge else 0
+    if save:
+        B.laplex_apply(da, db, dx, y, ws, f | B.LAPLEX_SAVE_SCANS)
+        B.laplex_apply_backward(da, db, dx, dg, gx, ga, gb, ws, f | B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
+    else:
+        B.laplex_apply(da, db, dx, y, ws, f)
+        B.laplex_apply_backward(da, db, dx, dg, gx, ga, gb, ws, f)        # stands alone: builds its own plan, scans x itself
+    torch.cuda.synchronize()
+    assert gpu_plan_status(ws, k + n) == 0
+    perm = gpu_perm(ws, k + n)
+    return [None if t is None else t.cpu().numpy() for t in (y, gx, ga, gb)], perm
+
+
+ROUTE_SHAPES = [(100, 9000), (9000, 100), (1, 20000), (20000, 1), (3000, 21000), (50000, 70000), (8192, 8192 * 3),
+                (300000, 500000), (2200000, 2400000)]
+
+
+@pytest.mark.parametrize("kind", ["uniform", "ties", "all_equal", "clustered", "ascending"])
+@pytest.mark.parametrize("k,n", ROUTE_SHAPES)
+def test_routes_without_random_access_match_the_gathers(oracle, routed, kind, k, n):
+    """At batch 1 x and gy reach sorted order, and y, the saved scans, gx and gb the caller's order, through partition
+    passes when there are many rows.  Same kernels in between, same values in: the results must equal those of the
+    gather / scatter route bit for bit (one and two partition levels, ragged windows, a single output or input,
+    sources that arrive in order), and sit within the bar of the oracle."""
+    if kind != "uniform" and k + n > 1000000:
+        pytest.skip("the largest shape runs once")
+    r = np.random.default_rng(k * 7 + n)
+    if kind == "ascending":
+        a = np.sort(r.uniform(0, (k + n) / 64.0, k)).astype(np.float32); b = np.sort(r.uniform(0, (k + n) / 64.0, n)).astype(np.float32)
+    else:
+        a, b = anchors(kind, r, k, n)
+    x = r.normal(size=(n, 1)).astype(np.float32); g = r.normal(size=(k, 1)).astype(np.float32)
+    for save in (True, False):
+        got, perm = _apply_both_ways(a, b, x, g, save)
+        B.laplex_diag_set_route_min(1 << 40)
+        want, perm0 = _apply_both_ways(a, b, x, g, save)
+        B.laplex_diag_set_route_min(0)
+        assert np.array_equal(perm, perm0)
+        for name, u, v in zip(("y", "gx", "ga", "gb"), got, want):
+            assert np.array_equal(u, v), f"{name} differs between the routes (save={save})"
+    if k * n <= 4e7 or kind == "uniform":
+        ref, tol = (oracle.apply_brute if k * n <= 4e7 else oracle.apply_scan)(a, b, x)
+        assert_close("y", got[0], ref, tol)
+        (rgx, rga, rgb), (tgx, tga, tgb) = (oracle.apply_backward_brute if k * n <= 4e7 else oracle.apply_backward_scan)(a, b, x, g)
+        assert_close("gx", got[1], rgx, tgx); assert_close("ga", got[2], rga, tga); assert_close("gb", got[3], rgb, tgb)
+
+
+@pytest.mark.parametrize("want", [(True, False, False), (False, True, False), (False, False, True), (True, False, True), (False, True, True)])
+def test_routes_gradient_subsets_and_merge_path(oracle, routed, want):
+    r = np.random.default_rng(sum(want) * 11 + want[0])
+    k, n = 30000, 41000
+    a = np.sort(r.uniform(0, 900, k)).astype(np.float32); b = np.sort(r.uniform(0, 900, n)).astype(np.float32)
+    b[::7] = a[r.integers(0, k, b[::7].size)]; b.sort()                   # exact ties between the two sets
+    x = r.normal(size=(n, 1)).astype(np.float32); g = r.normal(size=(k, 1)).astype(np.float32)
+    (rgx, rga, rgb), (tgx, tga, tgb) = oracle.apply_backward_scan(a, b, x, g)
+    for save in (True, False):
+        for merge in (False, True):
+            got, _ = _apply_both_ways(a, b, x, g, save, want=want, merge=merge)
+            if want[0]: assert_close("gx", got[1], rgx, tgx)
+            if want[1]: assert_close("ga", got[2], rga, tga)
+            if want[2]: assert_close("gb", got[3], rgb, tgb)
+
+
+def test_routes_invalid_plan_poisons(routed):
+    r = np.random.default_rng(5)
+    k, n = 20000, 30000
+    a, b = anchors("uniform", r, k, n)
+    x = r.normal(size=(n, 1)).astype(np.float32); g = r.normal(size=(k, 1)).astype(np.float32)
+    da, db, dx, dg = dev(a), dev(b), dev(x), dev(g)
+    ws = workspace(k, n, 1)
+    y = torch.zeros(k, 1, device="cuda"); gx = torch.zeros(n, 1, device="cuda"); ga = torch.zeros(k, device="cuda"); gb = torch.zeros(n, device="cuda")
+    B.laplex_apply(da, db, dx, y, ws, B.LAPLEX_SAVE_SCANS)
+    B.laplex_diag_set_plan_status(ws, k + n, 1)
+    B.laplex_apply(da, db, dx, y, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
+    B.laplex_apply_backward(da, db, dx, dg, gx, ga, gb, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
+    torch.cuda.synchronize()
+    for name, t in (("y", y), ("gx", gx), ("ga", ga), ("gb", gb)):
+        assert bool(torch.isnan(t).all()), name

@@ -277,9 +277,8 @@ def test_weighted_gram_argument_checks(L):
     assert L.laplex_wgram_workspace_bytes(-1, 8, ctypes.byref(out)) == B.LAPLEX_ERR_SIZE
     assert L.laplex_wgram_workspace_bytes((1 << 20) + 1, 8, ctypes.byref(out)) == B.LAPLEX_ERR_SIZE
     assert L.laplex_wgram_workspace_bytes(1024, 1 << 20, ctypes.byref(out)) == 0
-    plain = ctypes.c_size_t(0)
-    assert L.laplex_workspace_bytes(1024, 1 << 20, 1, ctypes.byref(plain)) == 0
-    assert out.value % 256 == 0 and out.value >= plain.value + 12 * 1024       # + U (4 B) and W (8 B) per anchor
+    # at least the plan (12 B per merged position) and the sort's buffers (12 B more), + U, V, W (24 B) per anchor
+    assert out.value % 256 == 0 and out.value >= 24 * ((1 << 20) + 1024) + 24 * 1024
     k, n = 8, 16
     good = dict(a=FAKE, k=k, b=FAKE, n=n, d=FAKE, m=FAKE, ldm=k, ws=FAKE, wsb=1 << 40, flags=0)
     call = lambda **kw: L.laplex_wgram(*[{**good, **kw}[key] for key in
