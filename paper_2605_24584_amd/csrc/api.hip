@@ -139,14 +139,11 @@ PermuteJob permute_job(const Layout& L, char* ws, const char* tag)
 {
     PermuteJob J;
     for (int lv = 0; lv < 2; ++lv) {
-        J.rec_d[lv] = reinterpret_cast<uint32_t*>(ws + L.off_rec_d[lv]);
-        J.rec_v0[lv] = reinterpret_cast<float*>(ws + L.off_rec_v0[lv]);
+        J.rec_dv[lv] = reinterpret_cast<uint2*>(ws + L.off_rec_dv[lv]);
         J.rec_v1[lv] = reinterpret_cast<float*>(ws + L.off_rec_v1[lv]);
     }
-    J.status = reinterpret_cast<uint32_t*>(ws + L.off_pt_status);
-    J.tickets = reinterpret_cast<uint32_t*>(ws + L.off_pt_tickets);
-    J.error = reinterpret_cast<uint32_t*>(ws + L.off_counters) + kPlanStatusWord;
-    J.poison = J.error;
+    J.cursors = reinterpret_cast<uint32_t*>(ws + L.off_pt_cursors);
+    J.poison = reinterpret_cast<const uint32_t*>(ws + L.off_counters) + kPlanStatusWord;
     J.tag = tag;
     return J;
 }

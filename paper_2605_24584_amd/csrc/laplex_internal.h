@@ -62,10 +62,10 @@ constexpr int kSpineThreads = 1024;
 // partition passes instead of by random accesses (permute_kernels.hip).  A window is the stretch of
 // destinations that the last pass places inside LDS; a partition level has at most 2^9 buckets.
 // ----------------------------------------------------------------------------
-constexpr int kPermuteWindowBits = 13;
+constexpr int kPermuteWindowBits = 14;
 constexpr int kPermuteMaxBucketBits = 9;
 bool permute_supported(int64_t source_count, int64_t dest_count);      // destinations fit two partition levels
-size_t permute_status_words(int64_t source_count, int64_t dest_count);  // look-back words of both levels
+size_t permute_cursor_words(int64_t dest_count);                        // the buckets' cursors of both levels
 // records that a level's output array must hold for `dest_count` destinations: whole bucket regions
 inline int64_t permute_capacity(int64_t dest_count)
 {
@@ -163,9 +163,8 @@ struct Layout {
     bool permute = false;        // the regions below exist
     size_t off_rank = 0;         // u32[N]     plan: rank[id] = sorted position of anchor id
     size_t off_sorted2 = 0;      // f32[N][2]  scratch: the (up to) two outputs of a scan problem per sorted row
-    size_t off_rec_d[2] = {0, 0}, off_rec_v0[2] = {0, 0}, off_rec_v1[2] = {0, 0};   // records of the two partition levels
-    size_t off_pt_status = 0;    // u32[permute_status_words]  look-back words
-    size_t off_pt_tickets = 0;   // u32[64]    tile tickets of the two levels
+    size_t off_rec_dv[2] = {0, 0}, off_rec_v1[2] = {0, 0};   // records of the two partition levels: (destination, value) pairs, second values
+    size_t off_pt_cursors = 0;   // u32[permute_cursor_words]  records placed per bucket, both levels
     size_t total = 0;
 };
 
@@ -238,12 +237,10 @@ inline Layout make_layout(int64_t N, int64_t zrows, int64_t batch, bool permute_
         const size_t cap1 = (size_t)permute_capacity(N), cap2 = (size_t)permute_capacity(side);
         L.off_sorted2 = q; q = align_up(q + sizeof(float) * 2 * (size_t)N);
         for (int lv = 0; lv < 2; ++lv) {
-            L.off_rec_d[lv] = q;  q = align_up(q + sizeof(uint32_t) * cap1);
-            L.off_rec_v0[lv] = q; q = align_up(q + sizeof(float) * cap1);
+            L.off_rec_dv[lv] = q; q = align_up(q + 2 * sizeof(uint32_t) * cap1);
             L.off_rec_v1[lv] = q; q = align_up(q + sizeof(float) * cap2);
         }
-        L.off_pt_status = q;  q = align_up(q + sizeof(uint32_t) * permute_status_words(N, N));
-        L.off_pt_tickets = q; q = align_up(q + sizeof(uint32_t) * 64);
+        L.off_pt_cursors = q; q = align_up(q + sizeof(uint32_t) * permute_cursor_words(N));
         L.total = q;
     }
     L.off_small = align_up(L.total);
@@ -317,9 +314,8 @@ struct PermuteJob {
     int64_t source_count = 0, dest_count = 0;
     int values = 1;                                    // values per record: 1 or 2
     float* out0 = nullptr; int64_t ld0 = 1; float* out1 = nullptr; int64_t ld1 = 1;
-    uint32_t* rec_d[2] = {nullptr, nullptr}; float* rec_v0[2] = {nullptr, nullptr}; float* rec_v1[2] = {nullptr, nullptr};
-    uint32_t* status = nullptr; uint32_t* tickets = nullptr;
-    uint32_t* error = nullptr;                         // set to 1 if a tile gives up its bounded wait (the plan's status word)
+    uint2* rec_dv[2] = {nullptr, nullptr}; float* rec_v1[2] = {nullptr, nullptr};   // records of the two levels
+    uint32_t* cursors = nullptr;                       // permute_cursor_words(dest_count) words of scratch
     const uint32_t* poison = nullptr;                  // nonzero: every value written becomes a NaN (null: never)
     const char* tag = "move";                          // names the timing families permute_part.<tag>, permute_final.<tag>
 };

@@ -6,7 +6,7 @@
 // per float, and storing a result at y[id] a partial line; both are bound by the number of memory
 // transactions, not by bytes.  Here every value travels as a record (destination, value[, value]) through
 // at most two partition passes, each of which reads its records once and writes them once in runs, and a
-// last pass that places the records of one window of 8192 consecutive destinations inside LDS and writes
+// last pass that places the records of one window of 16384 consecutive destinations inside LDS and writes
 // the window out whole:
 //
 //   level 1   records -> up to 512 buckets by the top bits of the destination (only when there are more
@@ -17,10 +17,11 @@
 //
 // Destinations are positions of a permutation, so a bucket that covers C destinations receives at most C
 // records: its region in the record arrays is simply the stretch [first destination, first + C).  No
-// histogram pass is needed and nothing has to be stable; a tile ranks its records with returning LDS
-// atomics and learns where its runs start from a chained look-back over per-tile status words, the
-// protocol of the radix sort's passes (tiles numbered by a ticket, so every predecessor of a running tile
-// is running; bounded spin, so that a lost wake-up marks the plan invalid instead of hanging the device).
+// histogram pass is needed, nothing has to be stable and no tile waits for another: a tile ranks its records
+// with returning LDS atomics and reserves the stretch for each of its runs with ONE returning atomic on the
+// bucket's cursor (device scope).  Measured on this device: 512 such atomics per tile of 64 KB, all tiles on
+// the same 512 words, cost 15 % on top of a plain copy of the tile.  The order of the records inside a bucket
+// depends on the order in which the atomics land; the result does not (every destination is written once).
 #include "laplex_internal.h"
 
 #include <string>
@@ -29,32 +30,29 @@ namespace laplex {
 
 namespace {
 
-constexpr int kPtThreads = 512;
+constexpr int kPtThreads = 1024;
 constexpr int kPtPer = 16;                               // records per thread
-constexpr int kPtTile = kPtThreads * kPtPer;             // 8192 records per tile
+constexpr int kPtTile = kPtThreads * kPtPer;             // 16384 records per tile: a run is 32 records on average with 512 buckets
 static_assert(kPtTile == (1 << kPermuteWindowBits), "a tile of level 2 is one window's worth of records");
-constexpr int kPtSpinLimit = 1 << 24;
-constexpr uint32_t kCountMask = (1u << 30) - 1u;         // status word: state in the top two bits, a record count below
+constexpr int kFromRecords = 3;                          // source of level 2 (beside PermuteJob::Source)
 
 struct PartArgs {
-    int mode;                      // PermuteJob::Source, or kFromRecords for the second level
+    int mode;                      // PermuteJob::Source, or kFromRecords
     // sources
     const uint32_t* ids; uint32_t lo, hi;               // rows: destination = ids[j] - lo for lo <= ids[j] < hi
     const uint32_t* rank;                               // values: destination = rank[i]
     const float* val0; const float* val1; int64_t ld_val;
     int64_t count;                                      // source rows / values
-    const uint32_t* in_d; const float* in_v0; const float* in_v1;   // records of the level before
-    const uint32_t* prev_status; int64_t prev_last_tile; int prev_buckets;   // where that level left its bucket lengths
+    const uint2* in_dv; const float* in_v1;             // records of the level before: (destination, first value), second value ...
+    const uint32_t* in_len;                             // ... and how many each of its buckets holds (its cursors)
     // this level
-    int chain_bits;                // a chain is 2^chain_bits consecutive tickets (one bucket of the level before); -1: one chain
+    int chain_bits;                // level 2: a bucket of the level before is read by 2^chain_bits consecutive tiles; -1: tiles over the source
     int bucket_bits, shift;        // digit = (destination >> shift) & (2^bucket_bits - 1)
     int region_shift;              // a bucket's region holds 2^region_shift records
-    uint32_t* out_d; float* out_v0; float* out_v1;
-    uint32_t* status; uint32_t* ticket; uint32_t* error;
+    uint2* out_dv; float* out_v1;
+    uint32_t* cursor;              // records placed so far, per bucket of this level (zero when the level starts)
     int64_t dest_count;            // destinations are below this
 };
-
-constexpr int kFromRecords = 3;
 
 __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* wsum /* kPtThreads / 64 words of LDS */)
 {
@@ -80,38 +78,34 @@ __global__ void __launch_bounds__(kPtThreads)
 k_part(const PartArgs A)
 {
     constexpr int kMaxBuckets = 1 << kPermuteMaxBucketBits;
+    static_assert(kMaxBuckets <= kPtThreads, "one thread per bucket");
     __shared__ uint32_t hist[kMaxBuckets];          // records of the tile per bucket
     __shared__ uint32_t lstart[kMaxBuckets];        // first LDS slot of each bucket's run
     __shared__ uint32_t delta[kMaxBuckets];         // slot in the chain's output = delta[bucket] + LDS slot
     __shared__ uint32_t wsum[kPtThreads / 64];
-    __shared__ uint32_t sd[kPtTile];
-    __shared__ float sv0[kPtTile];
-    __shared__ float sv1[NV == 2 ? kPtTile : 1];
-    __shared__ uint32_t s_ticket;
+    __shared__ uint2 sdv[kPtTile];                  // the tile's records, bucket by bucket: (destination, first value); then the second values
 
     const int tid = threadIdx.x;
     const int buckets = 1 << A.bucket_bits;
-    if (tid == 0) s_ticket = atomicAdd(A.ticket, 1u);
-    for (int b = tid; b < buckets; b += kPtThreads) hist[b] = 0u;
-    __syncthreads();
-    const int64_t ticket = (int64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)s_ticket);
-    const int64_t chain = A.chain_bits < 0 ? 0 : ticket >> A.chain_bits;
-    const int64_t chunk = A.chain_bits < 0 ? ticket : ticket & (((int64_t)1 << A.chain_bits) - 1);
+    if (tid < buckets) hist[tid] = 0u;
+    const int64_t tile = blockIdx.x;
+    const int64_t chain = A.chain_bits < 0 ? 0 : tile >> A.chain_bits;
+    const int64_t chunk = A.chain_bits < 0 ? tile : tile & (((int64_t)1 << A.chain_bits) - 1);
 
     // the tile's source records
     int64_t src0, src1;
     if (MODE == kFromRecords) {
-        uint32_t len = A.prev_status[A.prev_last_tile * A.prev_buckets + chain] & kCountMask;   // records of this bucket
+        uint32_t len = A.in_len[chain];                         // records of this bucket of the level before
         const uint32_t cap = 1u << (A.chain_bits + kPermuteWindowBits);
         len = len < cap ? len : cap;                            // (a valid plan never fills a region beyond its size)
-        const int64_t base = chain << A.chain_bits << kPermuteWindowBits;     // a chain of 2^chain_bits tiles covers its bucket's region
+        const int64_t base = chain << A.chain_bits << kPermuteWindowBits;     // 2^chain_bits tiles cover the bucket's region
         src0 = base + chunk * kPtTile;
         src1 = base + len < src0 + kPtTile ? base + len : src0 + kPtTile;
     } else {
-        src0 = ticket * kPtTile;
+        src0 = tile * kPtTile;
         src1 = A.count < src0 + kPtTile ? A.count : src0 + kPtTile;
     }
-    if (src0 >= src1) return;        // nothing here, and nothing in any later tile of the chain: no one looks at this tile's words
+    if (src0 >= src1) return;
 
     uint32_t dest[kPtPer], slot[kPtPer];
     float v0[kPtPer], v1[NV == 2 ? kPtPer : 1];
@@ -122,7 +116,8 @@ k_part(const PartArgs A)
         const bool in = j < src1;
         const int64_t jc = in ? j : src0;
         if (MODE == kFromRecords) {
-            dest[i] = A.in_d[jc]; v0[i] = A.in_v0[jc];
+            const uint2 dv = A.in_dv[jc];
+            dest[i] = dv.x; v0[i] = __uint_as_float(dv.y);
             if (NV == 2) v1[i] = A.in_v1[jc];
             ok[i] = in;
         } else if (MODE == PermuteJob::kRows) {
@@ -143,6 +138,7 @@ k_part(const PartArgs A)
         }
         ok[i] = ok[i] && (int64_t)dest[i] < A.dest_count;      // always true for a valid plan; keeps every store inside the arrays
     }
+    __syncthreads();
     const uint32_t digit_mask = (uint32_t)buckets - 1u;
 #pragma unroll
     for (int i = 0; i < kPtPer; ++i) {
@@ -151,98 +147,64 @@ k_part(const PartArgs A)
     }
     __syncthreads();
 
-    // runs in LDS: bucket order; each thread owns `per` consecutive buckets
-    const int per = (buckets + kPtThreads - 1) / kPtThreads;      // 1 or 2
-    uint32_t cnt[2] = {0u, 0u};
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-        const int b = tid * per + q;
-        if (q < per && b < buckets) cnt[q] = hist[b];
-    }
-    // publish the counts as soon as they are known: the tiles after this one wait for them
-    uint32_t* const words = A.status + ticket * buckets;
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-        const int b = tid * per + q;
-        if (q < per && b < buckets)
-            __hip_atomic_store(words + b, ((chunk == 0 ? 2u : 1u) << 30) | cnt[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    const uint32_t ex = block_exclusive_scan(cnt[0] + cnt[1], wsum);
-    uint32_t before[2] = {0u, 0u};
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-        const int b = tid * per + q;
-        if (q < per && b < buckets) lstart[b] = ex + (q ? cnt[0] : 0u);
-    }
+    // thread b reserves the stretch of bucket b's region for this tile's run: one returning atomic, whose answer
+    // travels while the runs are laid out in LDS
+    const uint32_t cnt = tid < buckets ? hist[tid] : 0u;
+    uint32_t before = 0u;
+    if (cnt) before = atomicAdd(A.cursor + (chain << A.bucket_bits) + tid, cnt);
+    const uint32_t ex = block_exclusive_scan(cnt, wsum);
+    if (tid < buckets) lstart[tid] = ex;
     __syncthreads();
-
+    uint32_t place[kPtPer];
 #pragma unroll
     for (int i = 0; i < kPtPer; ++i) {
-        if (ok[i]) {
-            const uint32_t s = lstart[(dest[i] >> A.shift) & digit_mask] + slot[i];
-            sd[s] = dest[i]; sv0[s] = v0[i];
-            if (NV == 2) sv1[s] = v1[i];
-        }
+        place[i] = lstart[(dest[i] >> A.shift) & digit_mask] + slot[i];
+        if (ok[i]) sdv[place[i]] = make_uint2(dest[i], __float_as_uint(v0[i]));
     }
-
-    // look-back: records of this bucket in the earlier tiles of the chain
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-        const int b = tid * per + q;
-        if (!(q < per && b < buckets)) continue;
-        uint32_t sum = 0;
-        bool done = chunk == 0;
-        for (int64_t t = ticket - 1; !done; --t) {
-            uint32_t x = __hip_atomic_load(A.status + t * buckets + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            int spins = 0;
-            while ((x >> 30) == 0 && spins < kPtSpinLimit) {
-                __builtin_amdgcn_s_sleep(1);
-                x = __hip_atomic_load(A.status + t * buckets + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                ++spins;
-            }
-            if ((x >> 30) == 0) { *A.error = 1u; break; }       // gave up: the plan is marked invalid, nothing hangs
-            sum += x & kCountMask;
-            done = (x >> 30) == 2 || t == ticket - chunk;
-        }
-        before[q] = sum;
-        if (chunk != 0)
-            __hip_atomic_store(words + b, (2u << 30) | ((sum + cnt[q]) & kCountMask), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        // first record of the bucket's region, relative to the chain's first region, minus the run's LDS slot
-        delta[b] = ((uint32_t)b << A.region_shift) + sum - lstart[b];
-    }
+    // first record of the bucket's region, relative to the chain's first region, minus the run's LDS slot
+    if (tid < buckets) delta[tid] = ((uint32_t)tid << A.region_shift) + before - ex;
     __syncthreads();
 
     const uint32_t total = lstart[buckets - 1] + hist[buckets - 1];
     const int64_t chain_base = (chain << A.bucket_bits) << A.region_shift;
     const uint32_t region = 1u << A.region_shift;
+    int64_t where[kPtPer];
 #pragma unroll
     for (int i = 0; i < kPtPer; ++i) {
         const uint32_t s = (uint32_t)(i * kPtThreads + tid);
+        where[i] = -1;
         if (s < total) {
-            const uint32_t d = sd[s];
-            const uint32_t b = (d >> A.shift) & digit_mask;
+            const uint2 dv = sdv[s];
+            const uint32_t b = (dv.x >> A.shift) & digit_mask;
             const uint32_t off = delta[b] + s;                                  // inside the chain's output
             if (off - (b << A.region_shift) < region) {                         // a region never overflows for a permutation
-                const int64_t g = chain_base + off;
-                A.out_d[g] = d; A.out_v0[g] = sv0[s];
-                if (NV == 2) A.out_v1[g] = sv1[s];
+                where[i] = chain_base + off;
+                A.out_dv[where[i]] = dv;
             }
         }
+    }
+    if (NV == 2) {          // the second values through the same LDS array
+        float* const sv = reinterpret_cast<float*>(sdv);
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < kPtPer; ++i)
+            if (ok[i]) sv[place[i]] = v1[i];
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < kPtPer; ++i)
+            if (where[i] >= 0) A.out_v1[where[i]] = sv[i * kPtThreads + tid];
     }
 }
 
 struct FinalArgs {
-    const uint32_t* in_d; const float* in_v0; const float* in_v1;
-    const uint32_t* status; int buckets;           // the level that filled the windows: its status words, 2^bucket_bits per tile
-    int chain_bits;                                // its chains (-1: one chain of `tiles` tiles)
-    int64_t tiles;
-    const uint32_t* prev_status; int64_t prev_last_tile; int prev_buckets;   // the level before it (chains only)
+    const uint2* in_dv; const float* in_v1;
+    const uint32_t* in_len;                        // records of each window (the cursors of the level that filled them)
     float* out0; int64_t ld0; float* out1; int64_t ld1;
     int64_t dest_count;
     const uint32_t* poison;                        // the plan's status word, or null (never for the plan's own arrays)
 };
 
-// The last pass: one workgroup per window of 8192 consecutive destinations.
+// The last pass: one workgroup per window of 16384 consecutive destinations.
 template <int NV>
 __global__ void __launch_bounds__(kPtThreads)
 k_part_final(const FinalArgs A)
@@ -252,28 +214,15 @@ k_part_final(const FinalArgs A)
     __shared__ float s1[NV == 2 ? W : 1];
     const int tid = threadIdx.x;
     const int64_t w = blockIdx.x;
-    // records of this window: the inclusive count that the last tile of its chain published
-    int64_t last_tile;
-    int bucket;
-    if (A.chain_bits < 0) {
-        last_tile = A.tiles - 1; bucket = (int)w;
-    } else {
-        const int64_t chain = w >> A.chain_bits;             // chains of level 2 have as many tiles as windows
-        uint32_t len = A.prev_status[A.prev_last_tile * A.prev_buckets + chain] & kCountMask;
-        const uint32_t cap = 1u << (A.chain_bits + kPermuteWindowBits);
-        len = len < cap ? len : cap;
-        last_tile = (chain << A.chain_bits) + ((int64_t)len + kPtTile - 1) / kPtTile - 1;
-        bucket = (int)(w & (((int64_t)1 << A.chain_bits) - 1));
-        if (len == 0) last_tile = -1;
-    }
-    uint32_t count = last_tile < 0 ? 0u : (A.status[last_tile * A.buckets + bucket] & kCountMask);
+    uint32_t count = A.in_len[w];
     if (count > (uint32_t)W) count = (uint32_t)W;
     for (int i = tid; i < W; i += kPtThreads) { s0[i] = 0.0f; if (NV == 2) s1[i] = 0.0f; }
     __syncthreads();
     const int64_t base = w << kPermuteWindowBits;
     for (uint32_t i = tid; i < count; i += kPtThreads) {
-        const uint32_t d = A.in_d[base + i] & (uint32_t)(W - 1);
-        s0[d] = A.in_v0[base + i];
+        const uint2 dv = A.in_dv[base + i];
+        const uint32_t d = dv.x & (uint32_t)(W - 1);
+        s0[d] = __uint_as_float(dv.y);
         if (NV == 2) s1[d] = A.in_v1[base + i];
     }
     __syncthreads();
@@ -288,9 +237,8 @@ k_part_final(const FinalArgs A)
 }
 
 __global__ void __launch_bounds__(256)
-k_zero_words(uint32_t* __restrict__ p, int64_t count, uint32_t* __restrict__ tickets)
+k_zero_words(uint32_t* __restrict__ p, int64_t count)
 {
-    if (blockIdx.x == 0 && threadIdx.x < 2) tickets[threadIdx.x] = 0u;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x * 4;
     for (int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4; i < count; i += stride) {
         if (i + 4 <= count) *reinterpret_cast<uint4*>(p + i) = make_uint4(0u, 0u, 0u, 0u);
@@ -321,13 +269,11 @@ bool permute_supported(int64_t source_count, int64_t dest_count)
     return ceil_log2(windows) <= 2 * kPermuteMaxBucketBits;
 }
 
-size_t permute_status_words(int64_t source_count, int64_t dest_count)
+size_t permute_cursor_words(int64_t dest_count)
 {
-    // an upper bound for every job with at most this many sources and destinations: level 1 has one tile per 8192
-    // sources, level 2 one per window (padded to a power of two), and a tile has at most 2^9 words
-    const int64_t tiles1 = (source_count + kPtTile - 1) / kPtTile;
+    // level 1: at most 2^9 buckets; level 2 (or the only level): one cursor per window, padded to a power of two
     const int64_t windows = (dest_count + (1 << kPermuteWindowBits) - 1) >> kPermuteWindowBits;
-    return (size_t)((tiles1 + ((int64_t)1 << ceil_log2(windows))) << kPermuteMaxBucketBits);
+    return (size_t)(((int64_t)1 << kPermuteMaxBucketBits) + ((int64_t)1 << ceil_log2(windows)));
 }
 
 hipError_t launch_permute(const PermuteJob& J, hipStream_t st)
@@ -339,51 +285,45 @@ hipError_t launch_permute(const PermuteJob& J, hipStream_t st)
     const int p1 = lw - p2;
     const int64_t tiles1 = (J.source_count + kPtTile - 1) / kPtTile;
     const int64_t tiles2 = (int64_t)1 << (p1 + p2);
-    const int64_t words1 = tiles1 * ((int64_t)1 << (p1 > 0 ? p1 : p2));
-    const int64_t words2 = p1 > 0 ? tiles2 * ((int64_t)1 << p2) : 0;
-    uint32_t* const status1 = J.status;
-    uint32_t* const status2 = J.status + words1;
-
-    {   // status words of both levels and the two ticket counters
-        const int64_t words = words1 + words2;
-        int64_t g = (words / 4 + 255) / 256; if (g < 1) g = 1; if (g > 65536) g = 65536;
-        LAPLEX_TIMED("permute_zero", st, hipLaunchKernelGGL(k_zero_words, dim3((unsigned)g), dim3(256), 0, st, J.status, words, J.tickets));
+    uint32_t* const cursor1 = J.cursors;                                          // level 1's buckets
+    uint32_t* const cursor2 = J.cursors + ((int64_t)1 << kPermuteMaxBucketBits);  // the windows
+    {
+        const int64_t words = ((int64_t)1 << kPermuteMaxBucketBits) + ((int64_t)1 << lw);
+        int64_t g = (words / 4 + 255) / 256; if (g < 1) g = 1;
+        LAPLEX_TIMED("permute_zero", st, hipLaunchKernelGGL(k_zero_words, dim3((unsigned)g), dim3(256), 0, st, J.cursors, words));
     }
 
     PartArgs A{};
     A.mode = J.source;
     A.ids = J.ids; A.lo = J.lo; A.hi = J.hi; A.rank = J.rank;
     A.val0 = J.val0; A.val1 = J.val1; A.ld_val = J.ld_val; A.count = J.source_count;
-    A.error = J.error; A.dest_count = J.dest_count;
+    A.dest_count = J.dest_count;
     FinalArgs F{};
     F.dest_count = J.dest_count; F.out0 = J.out0; F.ld0 = J.ld0; F.out1 = J.out1; F.ld1 = J.ld1; F.poison = J.poison;
+    F.in_len = cursor2;
     const std::string f1 = std::string("permute_part.") + J.tag, f2 = std::string("permute_final.") + J.tag;
+    A.chain_bits = -1;
+    A.out_dv = J.rec_dv[0]; A.out_v1 = J.rec_v1[0];
     if (p1 > 0) {
-        // level 1: the source -> 2^p1 buckets of 2^p2 windows each, records into buffer A
-        A.chain_bits = -1; A.bucket_bits = p1; A.shift = kPermuteWindowBits + p2; A.region_shift = kPermuteWindowBits + p2;
-        A.out_d = J.rec_d[0]; A.out_v0 = J.rec_v0[0]; A.out_v1 = J.rec_v1[0];
-        A.status = status1; A.ticket = J.tickets;
+        // level 1: the source -> 2^p1 buckets of 2^p2 windows each, records into buffer 0
+        A.bucket_bits = p1; A.shift = kPermuteWindowBits + p2; A.region_shift = kPermuteWindowBits + p2;
+        A.cursor = cursor1;
         if (J.values == 2) launch_level<2>(A, tiles1, f1.c_str(), st); else launch_level<1>(A, tiles1, f1.c_str(), st);
-        // level 2: each bucket -> its windows, records into buffer B
+        // level 2: each bucket -> its windows, records into buffer 1
         PartArgs B2 = A;
         B2.mode = kFromRecords;
-        B2.in_d = J.rec_d[0]; B2.in_v0 = J.rec_v0[0]; B2.in_v1 = J.rec_v1[0];
-        B2.prev_status = status1; B2.prev_last_tile = tiles1 - 1; B2.prev_buckets = 1 << p1;
+        B2.in_dv = J.rec_dv[0]; B2.in_v1 = J.rec_v1[0]; B2.in_len = cursor1;
         B2.chain_bits = p2; B2.bucket_bits = p2; B2.shift = kPermuteWindowBits; B2.region_shift = kPermuteWindowBits;
-        B2.out_d = J.rec_d[1]; B2.out_v0 = J.rec_v0[1]; B2.out_v1 = J.rec_v1[1];
-        B2.status = status2; B2.ticket = J.tickets + 1;
+        B2.out_dv = J.rec_dv[1]; B2.out_v1 = J.rec_v1[1];
+        B2.cursor = cursor2;
         if (J.values == 2) launch_level<2>(B2, tiles2, f1.c_str(), st); else launch_level<1>(B2, tiles2, f1.c_str(), st);
-        F.in_d = J.rec_d[1]; F.in_v0 = J.rec_v0[1]; F.in_v1 = J.rec_v1[1];
-        F.status = status2; F.buckets = 1 << p2; F.chain_bits = p2; F.tiles = tiles2;
-        F.prev_status = status1; F.prev_last_tile = tiles1 - 1; F.prev_buckets = 1 << p1;
+        F.in_dv = J.rec_dv[1]; F.in_v1 = J.rec_v1[1];
     } else {
         // one level: the source -> windows
-        A.chain_bits = -1; A.bucket_bits = p2; A.shift = kPermuteWindowBits; A.region_shift = kPermuteWindowBits;
-        A.out_d = J.rec_d[0]; A.out_v0 = J.rec_v0[0]; A.out_v1 = J.rec_v1[0];
-        A.status = status1; A.ticket = J.tickets;
+        A.bucket_bits = p2; A.shift = kPermuteWindowBits; A.region_shift = kPermuteWindowBits;
+        A.cursor = cursor2;
         if (J.values == 2) launch_level<2>(A, tiles1, f1.c_str(), st); else launch_level<1>(A, tiles1, f1.c_str(), st);
-        F.in_d = J.rec_d[0]; F.in_v0 = J.rec_v0[0]; F.in_v1 = J.rec_v1[0];
-        F.status = status1; F.buckets = 1 << p2; F.chain_bits = -1; F.tiles = tiles1;
+        F.in_dv = J.rec_dv[0]; F.in_v1 = J.rec_v1[0];
     }
     if (J.values == 2) LAPLEX_TIMED(f2.c_str(), st, hipLaunchKernelGGL((k_part_final<2>), dim3((unsigned)windows), dim3(kPtThreads), 0, st, F));
     else LAPLEX_TIMED(f2.c_str(), st, hipLaunchKernelGGL((k_part_final<1>), dim3((unsigned)windows), dim3(kPtThreads), 0, st, F));
