@@ -487,6 +487,7 @@ static int apply_backward_impl(const float* a, int64_t k, const float* b, int64_
             if (routed) {
                 LAPLEX_CHECK(rows_to_sorted(L, w, x, ldx, k, n, P.xs, "rescan", st));
                 p.inj_sorted = p.out_sorted = true;
+                p.out_p = sorted2; p.ld_p = 2;            // (every sorted row gets its pair written; only the second half is wanted)
                 p.out_z = sorted2 + 1; p.ld_z = 2;
             }
             LAPLEX_HIP(launch_scan(p, L, w, st));
@@ -503,7 +504,7 @@ static int apply_backward_impl(const float* a, int64_t k, const float* b, int64_
         p.inj = gy; p.ld_inj = ldgy; p.inj_lo = 0; p.inj_hi = (uint32_t)k;
         p.res_lo = (uint32_t)k; p.res_hi = (uint32_t)(k + n);
         p.stage = P.stage; p.inj_sorted = p.out_sorted = true;
-        if (gx) { p.out_p = sorted2; p.ld_p = 2; }
+        p.out_p = sorted2; p.ld_p = 2;
         if (gb) { p.out_red = sorted2 + 1; p.ld_red = 2; p.w = x; p.ld_w = ldx; p.wstage = P.xs; }
         p.tag = "bwd";
         LAPLEX_HIP(launch_scan(p, L, w, st));

@@ -1688,6 +1688,220 @@ k_scan_down_sparse_wide(const ScanArgs A)
     }
 }
 
+// ---------------------------------------------------------------------------
+// Batch 1, everything in sorted order (the routes through partition passes): the injected values
+// arrive as a plain array over the sorted rows (zero where nothing is injected), the outputs of
+// row j leave as the pair out[2j], out[2j + 1], and the weights of the row reduction are another plain
+// array (zero off the result rows).  Nothing depends on the ids any more: a row that is not a result
+// row still gets its pair written (the pass that takes results home skips it), every block is
+// treated as holding injected and result rows, and the kernels read 8 bytes per row and array in
+// 16-byte pieces.  Same summaries, carries and walks as k_scan_reduce / k_scan_down at one column per
+// lane: 64 row-lanes per wavefront, 16 rows per row-lane, 8 wavefronts per block of 8192 rows.
+// ---------------------------------------------------------------------------
+constexpr int kSeqItems = kItemsVec1;
+static_assert(kSeqItems % 4 == 0, "a row-lane's rows are read in 16-byte pieces");
+
+struct SeqRows {
+    float dh[kSeqItems + 1];      // dh[i]: decay into row i from the left; dh[i + 1]: from the right
+    bool live[kSeqItems];
+};
+
+// dst[0..16) = src[row0..row0+16), zero past the end of the sequence
+__device__ __forceinline__ void seq_load(const float* __restrict__ src, int64_t row0, int64_t N, float* dst)
+{
+    if (row0 + kSeqItems <= N) {
+#pragma unroll
+        for (int q = 0; q < kSeqItems / 4; ++q) {
+            const float4 t = reinterpret_cast<const float4*>(src + row0)[q];
+            dst[4 * q] = t.x; dst[4 * q + 1] = t.y; dst[4 * q + 2] = t.z; dst[4 * q + 3] = t.w;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < kSeqItems; ++i) {
+            const int64_t j = row0 + i;
+            const float t = src[j < N ? j : N - 1];
+            dst[i] = j < N ? t : 0.0f;
+        }
+    }
+}
+
+__device__ __forceinline__ void seq_meta(const ScanArgs& A, int64_t row0, SeqRows& T)
+{
+    if (row0 + kSeqItems <= A.N) {          // dh has N + 1 entries
+#pragma unroll
+        for (int q = 0; q < kSeqItems / 4; ++q) {
+            const float4 t = reinterpret_cast<const float4*>(A.dh + row0)[q];
+            T.dh[4 * q] = t.x; T.dh[4 * q + 1] = t.y; T.dh[4 * q + 2] = t.z; T.dh[4 * q + 3] = t.w;
+        }
+        T.dh[kSeqItems] = A.dh[row0 + kSeqItems];
+#pragma unroll
+        for (int i = 0; i < kSeqItems; ++i) T.live[i] = true;
+    } else {
+#pragma unroll
+        for (int i = 0; i <= kSeqItems; ++i) {
+            const int64_t j = row0 + i;
+            const float d = A.dh[j <= A.N ? j : A.N];
+            T.dh[i] = j <= A.N ? d : -1.0f;
+        }
+#pragma unroll
+        for (int i = 0; i < kSeqItems; ++i) T.live[i] = row0 + i < A.N;
+    }
+}
+
+template <bool STRICT>
+__global__ void __launch_bounds__(kScanThreads)
+k_seq_reduce(const ScanArgs A)
+{
+    constexpr int ITEMS = kSeqItems;
+    __shared__ WaveSegs<1> W;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t tile = blockIdx.x;
+    const int64_t tile_base = tile * (kScanWaves * 64 * ITEMS);
+    const int64_t wave_row0 = tile_base + (int64_t)wave * 64 * ITEMS;
+    const int64_t row0 = wave_row0 + (int64_t)lane * ITEMS;
+    // decays over this row-lane's rows, this wavefront's rows and the whole tile, from the anchors
+    const float lane_df = span_decay_f(A, row0, ITEMS), lane_db = span_decay_b(A, row0, ITEMS);
+    const float wave_df = span_decay_f(A, wave_row0, 64 * ITEMS), wave_db = span_decay_b(A, wave_row0, 64 * ITEMS);
+    SeqRows T;
+    seq_meta(A, row0, T);
+    float v[ITEMS][1];
+    {
+        float t[ITEMS];
+        seq_load(A.stage, row0, A.N, t);
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) v[i][0] = t[i];
+    }
+    {
+        Seg<1, STRICT> f = seg_identity<1, STRICT>();
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) seg_push<1, STRICT>(f, T.live[i] && T.dh[i] >= 0.0f, T.dh[i], v[i]);
+        f.D = lane_df;
+        f = wave_scan<true, 1, STRICT>(f, lane, 1, 64);
+        if (lane == 63) { f.D = wave_df; put_wave_seg<1, STRICT>(W, 0, wave, 0, f); }
+    }
+    {
+        Seg<1, STRICT> b = seg_identity<1, STRICT>();
+#pragma unroll
+        for (int i = ITEMS - 1; i >= 0; --i) seg_push<1, STRICT>(b, T.live[i] && T.dh[i + 1] >= 0.0f, T.dh[i + 1], v[i]);
+        b.D = lane_db;
+        b = wave_scan<false, 1, STRICT>(b, lane, 1, 64);
+        if (lane == 0) { b.D = wave_db; put_wave_seg<1, STRICT>(W, 1, wave, 0, b); }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        Seg<1, STRICT> tf = seg_identity<1, STRICT>(), tb = seg_identity<1, STRICT>();
+#pragma unroll 1
+        for (int w = 0; w < kScanWaves; ++w) tf = seg_compose<1, STRICT>(tf, get_wave_seg<1, STRICT>(W, 0, w, 0));
+#pragma unroll 1
+        for (int w = kScanWaves - 1; w >= 0; --w) tb = seg_compose<1, STRICT>(tb, get_wave_seg<1, STRICT>(W, 1, w, 0));
+        tf.D = tf.C = span_decay_f(A, tile_base, A.tile_rows);
+        tb.D = tb.C = span_decay_b(A, tile_base, A.tile_rows);
+        const float flags = (float)(kFlagInj | kFlagRes);
+        store_level_seg<1, STRICT>(A.l1, 0, tile, A.bpad, 0, true, true, tf, flags);
+        store_level_seg<1, STRICT>(A.l1, 1, tile, A.bpad, 0, true, true, tb, flags);
+    }
+}
+
+// RED: the second output of a row is w * Z (w = A.wstage, sorted order), else Z itself (STRICT) or nothing.
+template <bool STRICT, bool RED>
+__global__ void __launch_bounds__(kScanThreads)
+k_seq_down(const ScanArgs A)
+{
+    constexpr int ITEMS = kSeqItems;
+    constexpr size_t kEfBytes = STRICT ? sizeof(float) * ITEMS * kScanThreads : 0;
+    constexpr size_t kSmem = sizeof(WaveSegs<1>) > kEfBytes ? sizeof(WaveSegs<1>) : kEfBytes;
+    __shared__ __align__(16) unsigned char smem[kSmem];
+    WaveSegs<1>& W = *reinterpret_cast<WaveSegs<1>*>(smem);
+    float* const ef = reinterpret_cast<float*>(smem) + threadIdx.x;        // row i at ef[i * kScanThreads]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t tile = blockIdx.x;
+    const uint32_t poison = plan_poison(A.counters);
+    const int64_t tile_base = tile * (kScanWaves * 64 * ITEMS);
+    const int64_t wave_row0 = tile_base + (int64_t)wave * 64 * ITEMS;
+    const int64_t row0 = wave_row0 + (int64_t)lane * ITEMS;
+    const float lane_df = span_decay_f(A, row0, ITEMS), lane_db = span_decay_b(A, row0, ITEMS);
+    const float wave_df = span_decay_f(A, wave_row0, 64 * ITEMS), wave_db = span_decay_b(A, wave_row0, 64 * ITEMS);
+    const int64_t rows_after = row0 + ITEMS;
+    const float enter_df = span_decay_f(A, tile_base, row0 - tile_base);
+    const float enter_db = span_decay_b(A, rows_after, tile_base + A.tile_rows - rows_after);
+    const bool enter_hf = span_head_f(A, tile_base, row0 - tile_base);
+    const bool enter_hb = span_head_b(A, rows_after, tile_base + A.tile_rows - rows_after);
+
+    SeqRows T;
+    seq_meta(A, row0, T);
+    float v[ITEMS][1], wt[RED ? ITEMS : 1];
+    {
+        float t[ITEMS];
+        seq_load(A.stage, row0, A.N, t);
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) v[i][0] = t[i];
+        if (RED) seq_load(A.wstage, row0, A.N, wt);
+    }
+    float Fc[1], Ec[1], Rc[1], Gc[1];
+    load_block_carries<1, STRICT>(A, tile, 0, true, Fc, Ec, Rc, Gc);
+    Seg<1, STRICT> fe, be;
+    {
+        Seg<1, STRICT> f = seg_identity<1, STRICT>();
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) seg_push<1, STRICT>(f, T.live[i] && T.dh[i] >= 0.0f, T.dh[i], v[i]);
+        f.D = lane_df;
+        f = wave_scan<true, 1, STRICT>(f, lane, 1, 64);
+        if (lane == 63) { Seg<1, STRICT> tot = f; tot.D = wave_df; put_wave_seg<1, STRICT>(W, 0, wave, 0, tot); }
+        fe = seg_shfl<1, STRICT>(f, (lane - 1) & 63);
+        if (lane == 0) fe = seg_identity<1, STRICT>();
+    }
+    {
+        Seg<1, STRICT> b = seg_identity<1, STRICT>();
+#pragma unroll
+        for (int i = ITEMS - 1; i >= 0; --i) seg_push<1, STRICT>(b, T.live[i] && T.dh[i + 1] >= 0.0f, T.dh[i + 1], v[i]);
+        b.D = lane_db;
+        b = wave_scan<false, 1, STRICT>(b, lane, 1, 64);
+        if (lane == 0) { Seg<1, STRICT> tot = b; tot.D = wave_db; put_wave_seg<1, STRICT>(W, 1, wave, 0, tot); }
+        be = seg_shfl<1, STRICT>(b, (lane + 1) & 63);
+        if (lane == 63) be = seg_identity<1, STRICT>();
+    }
+    __syncthreads();
+    float F[1] = {0.0f}, E[1] = {0.0f}, R[1] = {0.0f}, G[1] = {0.0f};
+#pragma unroll 1
+    for (int w = 0; w < wave; ++w) seg_apply<1, STRICT>(get_wave_seg<1, STRICT>(W, 0, w, 0), F, E);
+#pragma unroll 1
+    for (int w = kScanWaves - 1; w > wave; --w) seg_apply<1, STRICT>(get_wave_seg<1, STRICT>(W, 1, w, 0), R, G);
+    seg_apply<1, STRICT>(fe, F, E);
+    seg_apply<1, STRICT>(be, R, G);
+    enter_state<1, STRICT>(F, E, Fc, Ec, enter_df, enter_hf);
+    enter_state<1, STRICT>(R, G, Rc, Gc, enter_db, enter_hb);
+    if (STRICT) __syncthreads();      // every wavefront is done with the summaries: the buffer now holds E per row
+
+    float Ff[ITEMS];
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        const bool h = T.live[i] && T.dh[i] >= 0.0f;
+        E[0] = h ? T.dh[i] * F[0] : E[0];
+        F[0] = (h ? E[0] : F[0]) + v[i][0];
+        Ff[i] = F[0];
+        if (STRICT) ef[(size_t)i * kScanThreads] = E[0];
+    }
+    float2* const out = reinterpret_cast<float2*>(A.out_p);
+    float2 later = make_float2(0.0f, 0.0f);     // the pair of row i + 1, stored together with row i's (i even)
+#pragma unroll
+    for (int i = ITEMS - 1; i >= 0; --i) {
+        const bool h = T.live[i] && T.dh[i + 1] >= 0.0f;
+        const float Efi = STRICT ? ef[(size_t)i * kScanThreads] : 0.0f;
+        G[0] = h ? T.dh[i + 1] * R[0] : G[0];
+        R[0] = (h ? G[0] : R[0]) + v[i][0];
+        const float P = taint(Ff[i] + R[0] - v[i][0], poison);
+        const float Z = taint(G[0] - Efi, poison);
+        const float2 mine = make_float2(P, STRICT ? (RED ? taint(wt[RED ? i : 0] * Z, poison) : Z) : 0.0f);
+        if (i & 1) {
+            later = mine;
+        } else {
+            const int64_t j = row0 + i;
+            if (j + 1 < A.N) *reinterpret_cast<float4*>(out + j) = make_float4(mine.x, mine.y, later.x, later.y);
+            else if (j < A.N) out[j] = mine;
+        }
+    }
+}
+
 __global__ void __launch_bounds__(256)
 k_sum_slabs(const float* __restrict__ partial, int64_t rows, int slabs, float* __restrict__ out)
 {
@@ -1802,6 +2016,17 @@ void launch_all(const ScanArgs& A, const ScanGeom& g, const std::string& tag, hi
     const dim3 tgrid((unsigned)A.batch, 2);
     const std::string fr = "scan_reduce." + tag, fs = "scan_spine." + tag, fd = "scan_down." + tag,
                       fp = "scan_down_sparse." + tag;
+    if (VEC == 1 && A.inj_sorted && A.out_sorted) {     // batch 1, everything in sorted order: the ids are not looked at
+        LAPLEX_TIMED(fr.c_str(), st, hipLaunchKernelGGL((k_seq_reduce<STRICT>), dim3((unsigned)g.tiles), block, 0, st, A));
+        if (g.chunks > 1) {
+            LAPLEX_TIMED(fs.c_str(), st, hipLaunchKernelGGL((k_spine_reduce<VEC, STRICT>), cgrid, block, 0, st, A));
+            LAPLEX_TIMED(fs.c_str(), st, hipLaunchKernelGGL((k_spine_top<STRICT>), tgrid, dim3(kSpineThreads), 0, st, A.l2, A.bpad));
+        }
+        LAPLEX_TIMED(fs.c_str(), st, hipLaunchKernelGGL((k_spine_down<VEC, STRICT>), cgrid, block, 0, st, A));
+        if (STRICT && A.wstage) LAPLEX_TIMED(fd.c_str(), st, hipLaunchKernelGGL((k_seq_down<STRICT, STRICT>), dim3((unsigned)g.tiles), block, 0, st, A));
+        else LAPLEX_TIMED(fd.c_str(), st, hipLaunchKernelGGL((k_seq_down<STRICT, false>), dim3((unsigned)g.tiles), block, 0, st, A));
+        return;
+    }
     if (VEC == 4 && g.sub_shift) {    // wide geometry: a workgroup per tile, a wavefront per block
         LAPLEX_TIMED(fr.c_str(), st, hipLaunchKernelGGL((k_scan_reduce_wide<STRICT>), rgrid, dim3(kWideWaves * 64), 0, st, A));
     } else if (!A.stage) {            // one wavefront per tile
@@ -1891,6 +2116,7 @@ hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStrea
         const int64_t both = inj_rows < res_rows ? inj_rows : res_rows;
         A.reduce_from_list = inj_rows * 4 <= g.tiles;
         A.down_from_list = both * 4 <= g.blocks;
+        if (p.inj_sorted && p.out_sorted) A.reduce_from_list = A.down_from_list = 0;   // every block is visited
         // blocks with a handful of injected (result) rows skip the scan inside the block: wide geometry,
         // injected and result rows from different matrices, and few such rows overall
         const bool disjoint = p.inj_hi <= p.res_lo || p.res_hi <= p.inj_lo;

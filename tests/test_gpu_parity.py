@@ -966,11 +966,11 @@ ROUTE_SHAPES = [(100, 9000), (9000, 100), (1, 20000), (20000, 1), (3000, 21000),
 
 @pytest.mark.parametrize("kind", ["uniform", "ties", "all_equal", "clustered", "ascending"])
 @pytest.mark.parametrize("k,n", ROUTE_SHAPES)
-def test_routes_without_random_access_match_the_gathers(oracle, routed, kind, k, n):
+def test_routes_without_random_access(oracle, routed, kind, k, n):
     """At batch 1 x and gy reach sorted order, and y, the saved scans, gx and gb the caller's order, through partition
-    passes when there are many rows.  Same kernels in between, same values in: the results must equal those of the
-    gather / scatter route bit for bit (one and two partition levels, ragged windows, a single output or input,
-    sources that arrive in order), and sit within the bar of the oracle."""
+    passes when there are many rows, with scan kernels that work on plain arrays in sorted order in between.  One and
+    two partition levels, ragged windows, a single output or input, sources that arrive in order: the permutation equals
+    the other route's bit for bit, every value sits within the bar of the oracle, and the two routes agree to rounding."""
     if kind != "uniform" and k + n > 1000000:
         pytest.skip("the largest shape runs once")
     r = np.random.default_rng(k * 7 + n)
@@ -979,19 +979,20 @@ def test_routes_without_random_access_match_the_gathers(oracle, routed, kind, k,
     else:
         a, b = anchors(kind, r, k, n)
     x = r.normal(size=(n, 1)).astype(np.float32); g = r.normal(size=(k, 1)).astype(np.float32)
+    brute = k * n <= 4e7
+    ref, tol = (oracle.apply_brute if brute else oracle.apply_scan)(a, b, x)
+    refs, tols = (oracle.apply_backward_brute if brute else oracle.apply_backward_scan)(a, b, x, g)
+    refs, tols = (ref,) + tuple(refs), (tol,) + tuple(tols)
     for save in (True, False):
         got, perm = _apply_both_ways(a, b, x, g, save)
         B.laplex_diag_set_route_min(1 << 40)
-        want, perm0 = _apply_both_ways(a, b, x, g, save)
+        other, perm0 = _apply_both_ways(a, b, x, g, save)
         B.laplex_diag_set_route_min(0)
         assert np.array_equal(perm, perm0)
-        for name, u, v in zip(("y", "gx", "ga", "gb"), got, want):
-            assert np.array_equal(u, v), f"{name} differs between the routes (save={save})"
-    if k * n <= 4e7 or kind == "uniform":
-        ref, tol = (oracle.apply_brute if k * n <= 4e7 else oracle.apply_scan)(a, b, x)
-        assert_close("y", got[0], ref, tol)
-        (rgx, rga, rgb), (tgx, tga, tgb) = (oracle.apply_backward_brute if k * n <= 4e7 else oracle.apply_backward_scan)(a, b, x, g)
-        assert_close("gx", got[1], rgx, tgx); assert_close("ga", got[2], rga, tga); assert_close("gb", got[3], rgb, tgb)
+        for name, u, v, rf, tl in zip(("y", "gx", "ga", "gb"), got, other, refs, tols):
+            assert_close(name, u, rf, tl)
+            tl = np.asarray(tl).reshape(u.shape)
+            assert np.all(np.abs(u.astype(np.float64) - v) <= 2e-6 * tl + 1e-7), f"{name}: the routes disagree (save={save})"
 
 
 @pytest.mark.parametrize("want", [(True, False, False), (False, True, False), (False, False, True), (True, False, True), (False, True, True)])
