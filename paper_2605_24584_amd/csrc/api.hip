@@ -162,19 +162,23 @@ int rows_to_sorted(const Layout& L, char* ws, const float* src, int64_t ld, int6
     return LAPLEX_OK;
 }
 
-// The outputs of the sorted rows whose id lies in [lo, hi) go home: out0[(id - lo) * ld0] = sorted2[j][first],
-// out1[(id - lo) * ld1] = sorted2[j][1] (out1 may be null).
-int sorted_to_rows(const Layout& L, char* ws, uint32_t lo, uint32_t hi, int first, float* out0, int64_t ld0,
-                   float* out1, int64_t ld1, const char* tag, hipStream_t st)
+// One scan problem with everything in sorted order (`p.stage` holds the injected rows already): its results leave the
+// downsweep as records on their way home, out0[(id - res_lo) * ld0] = the first output of the row (if want_first) or
+// its second, out1[(id - res_lo) * ld1] = the second when both are wanted.
+int scan_and_send_home(ScanProblem& p, const Layout& L, char* ws, bool want_first, bool want_second,
+                       float* out0, int64_t ld0, float* out1, int64_t ld1, hipStream_t st)
 {
-    const float* sorted2 = reinterpret_cast<const float*>(ws + L.off_sorted2);
-    PermuteJob J = permute_job(L, ws, tag);
+    PermuteJob J = permute_job(L, ws, p.tag);
     J.source = PermuteJob::kRows;
-    J.ids = reinterpret_cast<const uint32_t*>(ws + L.off_ids); J.lo = lo; J.hi = hi;
-    J.val0 = sorted2 + first; J.val1 = sorted2 + 1; J.ld_val = 2;
-    J.source_count = L.N; J.dest_count = (int64_t)hi - (int64_t)lo;
-    J.values = out1 ? 2 : 1; J.out0 = out0; J.ld0 = ld0; J.out1 = out1; J.ld1 = ld1;
-    LAPLEX_HIP(launch_permute(J, st));
+    J.source_count = L.N; J.dest_count = (int64_t)p.res_hi - (int64_t)p.res_lo;
+    J.values = (want_first && want_second) ? 2 : 1;
+    J.out0 = out0; J.ld0 = ld0; J.out1 = out1; J.ld1 = ld1;
+    PartEmit E;
+    LAPLEX_HIP(permute_begin(J, &E, st));
+    p.inj_sorted = p.out_sorted = true;
+    p.emit = &E; p.emit_values = J.values; p.emit_first = want_first; p.emit_strict = want_second;
+    LAPLEX_HIP(launch_scan(p, L, ws, st));
+    LAPLEX_HIP(permute_finish(J, st));
     return LAPLEX_OK;
 }
 
@@ -398,15 +402,11 @@ static int apply_impl(const float* a, int64_t k, const float* b, int64_t n,
     p.out_z = (flags & LAPLEX_SAVE_SCANS) ? P.z : nullptr;
     p.stage = (flags & LAPLEX_SAVE_SCANS) ? P.xs : P.stage;   // kept for the backward's weights when saving
     p.tag = "fwd";
-    if (use_permute(L)) {          // x into sorted order, both outputs of a row by its sorted position, then home
-        float* const sorted2 = reinterpret_cast<float*>(w + L.off_sorted2);
+    if (use_permute(L)) {          // x into sorted order, the scans there, y (and the saved scans) home
         LAPLEX_CHECK(rows_to_sorted(L, w, x, ldx, k, n, p.stage, "fwd", st));
-        p.inj_sorted = p.out_sorted = true;
-        p.out_p = sorted2; p.ld_p = 2;
-        if (p.out_z) { p.out_z = sorted2 + 1; p.ld_z = 2; }
-        LAPLEX_HIP(launch_scan(p, L, w, st));
-        LAPLEX_CHECK(sorted_to_rows(L, w, 0, (uint32_t)k, 0, y, ldy, p.out_z ? P.z : nullptr, 1, "fwd", st));
-        return LAPLEX_OK;
+        const bool save = p.out_z != nullptr;
+        p.out_p = nullptr; p.out_z = nullptr;
+        return scan_and_send_home(p, L, w, true, save, y, ldy, save ? P.z : nullptr, 1, st);
     }
     float* const pairs = reinterpret_cast<float*>(w + L.off_pair);
     const bool paired = batch == 1 && p.out_z != nullptr;      // y and the saved scan of a row as one 8-byte slot
@@ -475,7 +475,6 @@ static int apply_backward_impl(const float* a, int64_t k, const float* b, int64_
     const bool sorted = (flags & LAPLEX_A_SORTED) && (flags & LAPLEX_B_SORTED);
     LAPLEX_CHECK(build_plan(a, k, b, n, tau, L, w, flags, sorted, st));
     const bool routed = use_permute(L);        // batch 1, many rows: no random accesses (see rows_to_sorted)
-    float* const sorted2 = reinterpret_cast<float*>(w + L.off_sorted2);
     if (ga) {
         if (!(flags & LAPLEX_SAVE_SCANS)) {   // strict scans of x at the outputs, not kept by the forward
             ScanProblem p = problem(P, L);
@@ -486,12 +485,11 @@ static int apply_backward_impl(const float* a, int64_t k, const float* b, int64_
             p.tag = "rescan";
             if (routed) {
                 LAPLEX_CHECK(rows_to_sorted(L, w, x, ldx, k, n, P.xs, "rescan", st));
-                p.inj_sorted = p.out_sorted = true;
-                p.out_p = sorted2; p.ld_p = 2;            // (every sorted row gets its pair written; only the second half is wanted)
-                p.out_z = sorted2 + 1; p.ld_z = 2;
+                p.out_z = nullptr;
+                LAPLEX_CHECK(scan_and_send_home(p, L, w, false, true, P.z, 1, nullptr, 1, st));
+            } else {
+                LAPLEX_HIP(launch_scan(p, L, w, st));
             }
-            LAPLEX_HIP(launch_scan(p, L, w, st));
-            if (routed) LAPLEX_CHECK(sorted_to_rows(L, w, 0, (uint32_t)k, 1, P.z, 1, nullptr, 1, "rescan", st));
         }
         LAPLEX_HIP(launch_rowdot(gy, ldgy, P.z, batch, k, batch, ga, st));
     }
@@ -503,13 +501,11 @@ static int apply_backward_impl(const float* a, int64_t k, const float* b, int64_
         ScanProblem p = problem(P, L);
         p.inj = gy; p.ld_inj = ldgy; p.inj_lo = 0; p.inj_hi = (uint32_t)k;
         p.res_lo = (uint32_t)k; p.res_hi = (uint32_t)(k + n);
-        p.stage = P.stage; p.inj_sorted = p.out_sorted = true;
-        p.out_p = sorted2; p.ld_p = 2;
-        if (gb) { p.out_red = sorted2 + 1; p.ld_red = 2; p.w = x; p.ld_w = ldx; p.wstage = P.xs; }
+        p.stage = P.stage;
+        if (gb) { p.w = x; p.ld_w = ldx; p.wstage = P.xs; }      // the second output of an input row: x * Z = its gb
         p.tag = "bwd";
-        LAPLEX_HIP(launch_scan(p, L, w, st));
-        if (gx) LAPLEX_CHECK(sorted_to_rows(L, w, (uint32_t)k, (uint32_t)(k + n), 0, gx, ldgx, gb, 1, "bwd", st));
-        else LAPLEX_CHECK(sorted_to_rows(L, w, (uint32_t)k, (uint32_t)(k + n), 1, gb, 1, nullptr, 1, "bwd", st));
+        if (gx) LAPLEX_CHECK(scan_and_send_home(p, L, w, true, gb != nullptr, gx, ldgx, gb, 1, st));
+        else LAPLEX_CHECK(scan_and_send_home(p, L, w, false, true, gb, 1, nullptr, 1, st));
     } else if (gx || gb) {
         ScanProblem p = problem(P, L);
         p.inj = gy; p.ld_inj = ldgy; p.inj_lo = 0; p.inj_hi = (uint32_t)k;

@@ -162,7 +162,6 @@ struct Layout {
     // batch 1 beyond the small path: the routes through sorted order without random accesses
     bool permute = false;        // the regions below exist
     size_t off_rank = 0;         // u32[N]     plan: rank[id] = sorted position of anchor id
-    size_t off_sorted2 = 0;      // f32[N][2]  scratch: the (up to) two outputs of a scan problem per sorted row
     size_t off_rec_dv[2] = {0, 0}, off_rec_v1[2] = {0, 0};   // records of the two partition levels: (destination, value) pairs, second values
     size_t off_pt_cursors = 0;   // u32[permute_cursor_words]  records placed per bucket, both levels
     size_t total = 0;
@@ -235,7 +234,6 @@ inline Layout make_layout(int64_t N, int64_t zrows, int64_t batch, bool permute_
         size_t q = align_up(L.total);
         const int64_t side = zrows > N - zrows ? zrows : N - zrows;      // result rows of a problem: at most this many
         const size_t cap1 = (size_t)permute_capacity(N), cap2 = (size_t)permute_capacity(side);
-        L.off_sorted2 = q; q = align_up(q + sizeof(float) * 2 * (size_t)N);
         for (int lv = 0; lv < 2; ++lv) {
             L.off_rec_dv[lv] = q; q = align_up(q + 2 * sizeof(uint32_t) * cap1);
             L.off_rec_v1[lv] = q; q = align_up(q + sizeof(float) * cap2);
@@ -299,6 +297,16 @@ hipError_t launch_unpair(const float* pairs, int64_t rows, float* first, int64_t
 //                              + (zs ? v * zs[(id-res_lo)*batch + t] : 0) )
 // Any of out_p / out_z / out_red may be null; strict scans run only if out_z or
 // out_red is wanted.
+// Where a tile places its records in one partition level (permute_tile.h).
+struct PartEmit {
+    int bucket_bits = 0, shift = 0;   // bucket of a record = (destination >> shift) & (2^bucket_bits - 1)
+    int region_shift = 0;             // a bucket's region holds 2^region_shift records
+    uint2* out_dv = nullptr;          // (destination, first value) pairs
+    float* out_v1 = nullptr;          // second values
+    uint32_t* cursor = nullptr;       // records placed so far, per bucket (zero when the level starts)
+    int64_t dest_count = 0;           // destinations are below this
+};
+
 // One move of values between the caller's order and the sorted order (launch_permute).
 //   kRows:     source row j of the sorted sequence goes to destination ids[j] - lo if lo <= ids[j] < hi (results back to
 //              the caller's order); its values are val0[j * ld_val] (and val1[j * ld_val])
@@ -320,6 +328,10 @@ struct PermuteJob {
     const char* tag = "move";                          // names the timing families permute_part.<tag>, permute_final.<tag>
 };
 hipError_t launch_permute(const PermuteJob& J, hipStream_t st);
+// The same in two halves, for a producer that places the records of the first level itself (the batch-1 downsweep):
+// permute_begin clears the cursors and says where the first level's records go; permute_finish runs what follows it.
+hipError_t permute_begin(const PermuteJob& J, PartEmit* first_level, hipStream_t st);
+hipError_t permute_finish(const PermuteJob& J, hipStream_t st);
 
 struct ScanProblem {
     const uint32_t* ids; const float* dh; const float* pk; int64_t N;
@@ -336,6 +348,10 @@ struct ScanProblem {
     // batch 1, routes without random accesses: `stage` already holds the injected rows in sorted order (zero elsewhere), and
     // the outputs of result row j of the sorted sequence go to out_p[j * ld_p], out_z[j * ld_z], out_red[j * ld_red]
     bool inj_sorted = false, out_sorted = false;
+    // ... and with both set the results leave as records of a partition level (k_seq_down): `emit` says where they go,
+    // emit_values how many outputs a record carries (2: F + R - v and the second output; 1: emit_first says which),
+    // emit_strict that the second output is wanted (the strict scans Z, or w * Z when wstage is given)
+    const PartEmit* emit = nullptr; int emit_values = 1; bool emit_first = true, emit_strict = false;
 };
 hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStream_t st);
 

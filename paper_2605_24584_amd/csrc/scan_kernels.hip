@@ -32,6 +32,7 @@
 // Lanes: bv lanes across the batch (vec columns each) x rv row-lanes per
 // wavefront; each row-lane walks `items` consecutive rows sequentially.
 #include "laplex_internal.h"
+#include "permute_tile.h"
 
 #include <string>
 
@@ -79,6 +80,8 @@ struct ScanArgs {
     int pair_out;                 // batch 1: out_p and the row's second output (out_z, else out_red) are the halves of an 8-byte slot
     int inj_sorted;               // batch 1: `stage` already holds the injected rows in sorted order: nothing is gathered
     int out_sorted;               // batch 1: outputs are indexed by the sorted row, not by the id (a later pass takes them home)
+    PartEmit emit;                // batch 1, sorted order: the results leave as records of a partition level (k_seq_down)
+    int emit_first;               // one value per record: the first output of a row (F + R - v), else its second
 };
 
 constexpr int kFlagInj = 1, kFlagRes = 2;
@@ -1690,34 +1693,42 @@ k_scan_down_sparse_wide(const ScanArgs A)
 
 // ---------------------------------------------------------------------------
 // Batch 1, everything in sorted order (the routes through partition passes): the injected values
-// arrive as a plain array over the sorted rows (zero where nothing is injected), the outputs of
-// row j leave as the pair out[2j], out[2j + 1], and the weights of the row reduction are another plain
-// array (zero off the result rows).  Nothing depends on the ids any more: a row that is not a result
-// row still gets its pair written (the pass that takes results home skips it), every block is
-// treated as holding injected and result rows, and the kernels read 8 bytes per row and array in
-// 16-byte pieces.  Same summaries, carries and walks as k_scan_reduce / k_scan_down at one column per
+// arrive as a plain array over the sorted rows (zero where nothing is injected) and the weights of
+// the row reduction as another (zero off the result rows); the outputs of the result rows leave as
+// records (id - first result id, first output[, second output]) of the first partition level on their
+// way home (permute_tile.h), so they are never written in sorted order and read again.  Every block is
+// treated as holding injected and result rows, the reduce does not look at the ids at all, and the
+// kernels read each array in 16-byte pieces.  Same summaries, carries and walks as k_scan_reduce / k_scan_down at one column per
 // lane: 64 row-lanes per wavefront, 16 rows per row-lane, 8 wavefronts per block of 8192 rows.
 // ---------------------------------------------------------------------------
+// The reduce keeps the geometry of the generic kernels (8 wavefronts, 16 rows per row-lane); the downsweep, which holds
+// its rows' results in registers until they leave as records, takes 16 wavefronts with 8 rows per row-lane: the same
+// block of 8192 rows, half the registers per lane, one workgroup of 16 wavefronts per compute unit.
 constexpr int kSeqItems = kItemsVec1;
-static_assert(kSeqItems % 4 == 0, "a row-lane's rows are read in 16-byte pieces");
+constexpr int kSeqDownItems = 8, kSeqDownWaves = 16, kSeqDownThreads = kSeqDownWaves * 64;
+static_assert(kSeqDownItems * kSeqDownThreads == kSeqItems * kScanThreads, "both kernels own blocks of the same rows");
 
+template <int ITEMS>
 struct SeqRows {
-    float dh[kSeqItems + 1];      // dh[i]: decay into row i from the left; dh[i + 1]: from the right
-    bool live[kSeqItems];
+    static_assert(ITEMS % 4 == 0 && ITEMS <= 32, "a row-lane's rows are read in 16-byte pieces; one bit per row");
+    float dh[ITEMS + 1];          // dh[i]: decay into row i from the left; dh[i + 1]: from the right
+    uint32_t live;                // bit i: row i lies inside the sequence
+    __device__ __forceinline__ bool alive(int i) const { return (live >> i) & 1u; }
 };
 
-// dst[0..16) = src[row0..row0+16), zero past the end of the sequence
+// dst[0..ITEMS) = src[row0..row0+ITEMS), zero past the end of the sequence
+template <int ITEMS>
 __device__ __forceinline__ void seq_load(const float* __restrict__ src, int64_t row0, int64_t N, float* dst)
 {
-    if (row0 + kSeqItems <= N) {
+    if (row0 + ITEMS <= N) {
 #pragma unroll
-        for (int q = 0; q < kSeqItems / 4; ++q) {
+        for (int q = 0; q < ITEMS / 4; ++q) {
             const float4 t = reinterpret_cast<const float4*>(src + row0)[q];
             dst[4 * q] = t.x; dst[4 * q + 1] = t.y; dst[4 * q + 2] = t.z; dst[4 * q + 3] = t.w;
         }
     } else {
 #pragma unroll
-        for (int i = 0; i < kSeqItems; ++i) {
+        for (int i = 0; i < ITEMS; ++i) {
             const int64_t j = row0 + i;
             const float t = src[j < N ? j : N - 1];
             dst[i] = j < N ? t : 0.0f;
@@ -1725,28 +1736,49 @@ __device__ __forceinline__ void seq_load(const float* __restrict__ src, int64_t 
     }
 }
 
-__device__ __forceinline__ void seq_meta(const ScanArgs& A, int64_t row0, SeqRows& T)
+template <int ITEMS>
+__device__ __forceinline__ void seq_meta(const ScanArgs& A, int64_t row0, SeqRows<ITEMS>& T)
 {
-    if (row0 + kSeqItems <= A.N) {          // dh has N + 1 entries
+    if (row0 + ITEMS <= A.N) {          // dh has N + 1 entries
 #pragma unroll
-        for (int q = 0; q < kSeqItems / 4; ++q) {
+        for (int q = 0; q < ITEMS / 4; ++q) {
             const float4 t = reinterpret_cast<const float4*>(A.dh + row0)[q];
             T.dh[4 * q] = t.x; T.dh[4 * q + 1] = t.y; T.dh[4 * q + 2] = t.z; T.dh[4 * q + 3] = t.w;
         }
-        T.dh[kSeqItems] = A.dh[row0 + kSeqItems];
-#pragma unroll
-        for (int i = 0; i < kSeqItems; ++i) T.live[i] = true;
+        T.dh[ITEMS] = A.dh[row0 + ITEMS];
+        T.live = (1u << ITEMS) - 1u;
     } else {
 #pragma unroll
-        for (int i = 0; i <= kSeqItems; ++i) {
+        for (int i = 0; i <= ITEMS; ++i) {
             const int64_t j = row0 + i;
             const float d = A.dh[j <= A.N ? j : A.N];
             T.dh[i] = j <= A.N ? d : -1.0f;
         }
-#pragma unroll
-        for (int i = 0; i < kSeqItems; ++i) T.live[i] = row0 + i < A.N;
+        const int64_t left = A.N - row0;
+        T.live = left <= 0 ? 0u : (left >= ITEMS ? (1u << ITEMS) - 1u : (1u << left) - 1u);
     }
 }
+
+// LDS exchange of the wavefronts' summaries of one block (one column): [direction][wavefront]
+template <int WAVES>
+struct SeqSegs {
+    float D[2][WAVES], C[2][WAVES], S[2][WAVES], Q[2][WAVES];
+    int H[2][WAVES];
+    template <bool STRICT>
+    __device__ __forceinline__ void put(int dir, int wave, const Seg<1, STRICT>& s)
+    {
+        D[dir][wave] = s.D; S[dir][wave] = s.S[0];
+        if (STRICT) { C[dir][wave] = s.C; H[dir][wave] = s.H; Q[dir][wave] = s.Q[0]; }
+    }
+    template <bool STRICT>
+    __device__ __forceinline__ Seg<1, STRICT> get(int dir, int wave) const
+    {
+        Seg<1, STRICT> s;
+        s.D = D[dir][wave]; s.S[0] = S[dir][wave];
+        s.C = STRICT ? C[dir][wave] : 0.0f; s.H = STRICT ? H[dir][wave] : 0; s.Q[0] = STRICT ? Q[dir][wave] : 0.0f;
+        return s;
+    }
+};
 
 template <bool STRICT>
 __global__ void __launch_bounds__(kScanThreads)
@@ -1762,19 +1794,19 @@ k_seq_reduce(const ScanArgs A)
     // decays over this row-lane's rows, this wavefront's rows and the whole tile, from the anchors
     const float lane_df = span_decay_f(A, row0, ITEMS), lane_db = span_decay_b(A, row0, ITEMS);
     const float wave_df = span_decay_f(A, wave_row0, 64 * ITEMS), wave_db = span_decay_b(A, wave_row0, 64 * ITEMS);
-    SeqRows T;
-    seq_meta(A, row0, T);
+    SeqRows<ITEMS> T;
+    seq_meta<ITEMS>(A, row0, T);
     float v[ITEMS][1];
     {
         float t[ITEMS];
-        seq_load(A.stage, row0, A.N, t);
+        seq_load<ITEMS>(A.stage, row0, A.N, t);
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) v[i][0] = t[i];
     }
     {
         Seg<1, STRICT> f = seg_identity<1, STRICT>();
 #pragma unroll
-        for (int i = 0; i < ITEMS; ++i) seg_push<1, STRICT>(f, T.live[i] && T.dh[i] >= 0.0f, T.dh[i], v[i]);
+        for (int i = 0; i < ITEMS; ++i) seg_push<1, STRICT>(f, T.alive(i) && T.dh[i] >= 0.0f, T.dh[i], v[i]);
         f.D = lane_df;
         f = wave_scan<true, 1, STRICT>(f, lane, 1, 64);
         if (lane == 63) { f.D = wave_df; put_wave_seg<1, STRICT>(W, 0, wave, 0, f); }
@@ -1782,7 +1814,7 @@ k_seq_reduce(const ScanArgs A)
     {
         Seg<1, STRICT> b = seg_identity<1, STRICT>();
 #pragma unroll
-        for (int i = ITEMS - 1; i >= 0; --i) seg_push<1, STRICT>(b, T.live[i] && T.dh[i + 1] >= 0.0f, T.dh[i + 1], v[i]);
+        for (int i = ITEMS - 1; i >= 0; --i) seg_push<1, STRICT>(b, T.alive(i) && T.dh[i + 1] >= 0.0f, T.dh[i + 1], v[i]);
         b.D = lane_db;
         b = wave_scan<false, 1, STRICT>(b, lane, 1, 64);
         if (lane == 0) { b.D = wave_db; put_wave_seg<1, STRICT>(W, 1, wave, 0, b); }
@@ -1803,20 +1835,24 @@ k_seq_reduce(const ScanArgs A)
 }
 
 // RED: the second output of a row is w * Z (w = A.wstage, sorted order), else Z itself (STRICT) or nothing.
-template <bool STRICT, bool RED>
-__global__ void __launch_bounds__(kScanThreads)
+// NV: values per record that leaves (2: both outputs; 1: A.emit_first says which).
+template <bool STRICT, bool RED, int NV>
+__global__ void __launch_bounds__(kSeqDownThreads)
 k_seq_down(const ScanArgs A)
 {
-    constexpr int ITEMS = kSeqItems;
-    constexpr size_t kEfBytes = STRICT ? sizeof(float) * ITEMS * kScanThreads : 0;
-    constexpr size_t kSmem = sizeof(WaveSegs<1>) > kEfBytes ? sizeof(WaveSegs<1>) : kEfBytes;
+    constexpr int ITEMS = kSeqDownItems, WAVES = kSeqDownWaves, THREADS = kSeqDownThreads;
+    // One LDS buffer, used three times: the exchange of wavefront summaries, the strict forward values per row,
+    // and at the end the records of the block on their way out.
+    constexpr size_t kSmem = sizeof(uint2) * ITEMS * THREADS;
+    static_assert(kSmem >= sizeof(SeqSegs<WAVES>) && kSmem >= sizeof(float) * ITEMS * THREADS, "the records need the most room");
     __shared__ __align__(16) unsigned char smem[kSmem];
-    WaveSegs<1>& W = *reinterpret_cast<WaveSegs<1>*>(smem);
-    float* const ef = reinterpret_cast<float*>(smem) + threadIdx.x;        // row i at ef[i * kScanThreads]
+    __shared__ PartShared<THREADS> S;
+    SeqSegs<WAVES>& W = *reinterpret_cast<SeqSegs<WAVES>*>(smem);
+    float* const ef = reinterpret_cast<float*>(smem) + threadIdx.x;        // row i at ef[i * THREADS]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t tile = blockIdx.x;
     const uint32_t poison = plan_poison(A.counters);
-    const int64_t tile_base = tile * (kScanWaves * 64 * ITEMS);
+    const int64_t tile_base = tile * (int64_t)(THREADS * ITEMS);
     const int64_t wave_row0 = tile_base + (int64_t)wave * 64 * ITEMS;
     const int64_t row0 = wave_row0 + (int64_t)lane * ITEMS;
     const float lane_df = span_decay_f(A, row0, ITEMS), lane_db = span_decay_b(A, row0, ITEMS);
@@ -1827,45 +1863,67 @@ k_seq_down(const ScanArgs A)
     const bool enter_hf = span_head_f(A, tile_base, row0 - tile_base);
     const bool enter_hb = span_head_b(A, rows_after, tile_base + A.tile_rows - rows_after);
 
-    SeqRows T;
-    seq_meta(A, row0, T);
+    SeqRows<ITEMS> T;
+    seq_meta<ITEMS>(A, row0, T);
     float v[ITEMS][1], wt[RED ? ITEMS : 1];
     {
         float t[ITEMS];
-        seq_load(A.stage, row0, A.N, t);
+        seq_load<ITEMS>(A.stage, row0, A.N, t);
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) v[i][0] = t[i];
-        if (RED) seq_load(A.wstage, row0, A.N, wt);
+        if (RED) seq_load<ITEMS>(A.wstage, row0, A.N, wt);
     }
     float Fc[1], Ec[1], Rc[1], Gc[1];
     load_block_carries<1, STRICT>(A, tile, 0, true, Fc, Ec, Rc, Gc);
+    // The result rows will leave as records of the first partition level (destination = id - first result id).  Where
+    // they go depends on the ids alone, so the stretches are reserved now, and the answers travel during the walks.
+    uint32_t dest[ITEMS];
+    uint32_t ok = 0u;
+    if (row0 + ITEMS <= A.N) {
+#pragma unroll
+        for (int q = 0; q < ITEMS / 4; ++q) {
+            const uint4 t = reinterpret_cast<const uint4*>(A.ids + row0)[q];
+            dest[4 * q] = t.x; dest[4 * q + 1] = t.y; dest[4 * q + 2] = t.z; dest[4 * q + 3] = t.w;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) dest[i] = A.ids[row0 + i < A.N ? row0 + i : A.N - 1];
+    }
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        const bool res = T.alive(i) && dest[i] >= A.res_lo && dest[i] < A.res_hi;
+        dest[i] -= A.res_lo;
+        ok |= (res && (int64_t)dest[i] < A.emit.dest_count) ? 1u << i : 0u;
+    }
+    PartTicket<ITEMS> K;
+    partition_reserve<THREADS, ITEMS>(A.emit, 0, dest, ok, S, K);
     Seg<1, STRICT> fe, be;
     {
         Seg<1, STRICT> f = seg_identity<1, STRICT>();
 #pragma unroll
-        for (int i = 0; i < ITEMS; ++i) seg_push<1, STRICT>(f, T.live[i] && T.dh[i] >= 0.0f, T.dh[i], v[i]);
+        for (int i = 0; i < ITEMS; ++i) seg_push<1, STRICT>(f, T.alive(i) && T.dh[i] >= 0.0f, T.dh[i], v[i]);
         f.D = lane_df;
         f = wave_scan<true, 1, STRICT>(f, lane, 1, 64);
-        if (lane == 63) { Seg<1, STRICT> tot = f; tot.D = wave_df; put_wave_seg<1, STRICT>(W, 0, wave, 0, tot); }
+        if (lane == 63) { Seg<1, STRICT> tot = f; tot.D = wave_df; W.template put<STRICT>(0, wave, tot); }
         fe = seg_shfl<1, STRICT>(f, (lane - 1) & 63);
         if (lane == 0) fe = seg_identity<1, STRICT>();
     }
     {
         Seg<1, STRICT> b = seg_identity<1, STRICT>();
 #pragma unroll
-        for (int i = ITEMS - 1; i >= 0; --i) seg_push<1, STRICT>(b, T.live[i] && T.dh[i + 1] >= 0.0f, T.dh[i + 1], v[i]);
+        for (int i = ITEMS - 1; i >= 0; --i) seg_push<1, STRICT>(b, T.alive(i) && T.dh[i + 1] >= 0.0f, T.dh[i + 1], v[i]);
         b.D = lane_db;
         b = wave_scan<false, 1, STRICT>(b, lane, 1, 64);
-        if (lane == 0) { Seg<1, STRICT> tot = b; tot.D = wave_db; put_wave_seg<1, STRICT>(W, 1, wave, 0, tot); }
+        if (lane == 0) { Seg<1, STRICT> tot = b; tot.D = wave_db; W.template put<STRICT>(1, wave, tot); }
         be = seg_shfl<1, STRICT>(b, (lane + 1) & 63);
         if (lane == 63) be = seg_identity<1, STRICT>();
     }
     __syncthreads();
     float F[1] = {0.0f}, E[1] = {0.0f}, R[1] = {0.0f}, G[1] = {0.0f};
 #pragma unroll 1
-    for (int w = 0; w < wave; ++w) seg_apply<1, STRICT>(get_wave_seg<1, STRICT>(W, 0, w, 0), F, E);
+    for (int w = 0; w < wave; ++w) seg_apply<1, STRICT>(W.template get<STRICT>(0, w), F, E);
 #pragma unroll 1
-    for (int w = kScanWaves - 1; w > wave; --w) seg_apply<1, STRICT>(get_wave_seg<1, STRICT>(W, 1, w, 0), R, G);
+    for (int w = WAVES - 1; w > wave; --w) seg_apply<1, STRICT>(W.template get<STRICT>(1, w), R, G);
     seg_apply<1, STRICT>(fe, F, E);
     seg_apply<1, STRICT>(be, R, G);
     enter_state<1, STRICT>(F, E, Fc, Ec, enter_df, enter_hf);
@@ -1875,31 +1933,28 @@ k_seq_down(const ScanArgs A)
     float Ff[ITEMS];
 #pragma unroll
     for (int i = 0; i < ITEMS; ++i) {
-        const bool h = T.live[i] && T.dh[i] >= 0.0f;
+        const bool h = T.alive(i) && T.dh[i] >= 0.0f;
         E[0] = h ? T.dh[i] * F[0] : E[0];
         F[0] = (h ? E[0] : F[0]) + v[i][0];
         Ff[i] = F[0];
-        if (STRICT) ef[(size_t)i * kScanThreads] = E[0];
+        if (STRICT) ef[(size_t)i * THREADS] = E[0];
     }
-    float2* const out = reinterpret_cast<float2*>(A.out_p);
-    float2 later = make_float2(0.0f, 0.0f);     // the pair of row i + 1, stored together with row i's (i even)
+    float second[STRICT ? ITEMS : 1];           // (the first outputs take the place of Ff)
 #pragma unroll
     for (int i = ITEMS - 1; i >= 0; --i) {
-        const bool h = T.live[i] && T.dh[i + 1] >= 0.0f;
-        const float Efi = STRICT ? ef[(size_t)i * kScanThreads] : 0.0f;
+        const bool h = T.alive(i) && T.dh[i + 1] >= 0.0f;
+        const float Efi = STRICT ? ef[(size_t)i * THREADS] : 0.0f;
         G[0] = h ? T.dh[i + 1] * R[0] : G[0];
         R[0] = (h ? G[0] : R[0]) + v[i][0];
-        const float P = taint(Ff[i] + R[0] - v[i][0], poison);
+        Ff[i] = taint(Ff[i] + R[0] - v[i][0], poison);
         const float Z = taint(G[0] - Efi, poison);
-        const float2 mine = make_float2(P, STRICT ? (RED ? taint(wt[RED ? i : 0] * Z, poison) : Z) : 0.0f);
-        if (i & 1) {
-            later = mine;
-        } else {
-            const int64_t j = row0 + i;
-            if (j + 1 < A.N) *reinterpret_cast<float4*>(out + j) = make_float4(mine.x, mine.y, later.x, later.y);
-            else if (j < A.N) out[j] = mine;
-        }
+        if (STRICT) second[i] = RED ? taint(wt[RED ? i : 0] * Z, poison) : Z;
     }
+    if (STRICT && NV == 1 && !A.emit_first) {      // uniform: the second output is the one that travels
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) Ff[i] = second[i];
+    }
+    partition_place<THREADS, ITEMS, NV>(A.emit, 0, dest, ok, Ff, STRICT ? second : Ff, S, reinterpret_cast<uint2*>(smem), K);
 }
 
 __global__ void __launch_bounds__(256)
@@ -1994,7 +2049,7 @@ int ilog2(int v) { int l = 0; while ((1 << l) < v) ++l; return l; }
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 template <int VEC, bool STRICT>
-void launch_all(const ScanArgs& A, const ScanGeom& g, const std::string& tag, hipStream_t st)
+void launch_all(const ScanArgs& A, const ScanGeom& g, const std::string& tag, bool two, hipStream_t st)
 {
     const dim3 block(kScanThreads);                 // spine kernels
     const dim3 bblock((unsigned)g.waves * 64);      // block kernels
@@ -2023,8 +2078,13 @@ void launch_all(const ScanArgs& A, const ScanGeom& g, const std::string& tag, hi
             LAPLEX_TIMED(fs.c_str(), st, hipLaunchKernelGGL((k_spine_top<STRICT>), tgrid, dim3(kSpineThreads), 0, st, A.l2, A.bpad));
         }
         LAPLEX_TIMED(fs.c_str(), st, hipLaunchKernelGGL((k_spine_down<VEC, STRICT>), cgrid, block, 0, st, A));
-        if (STRICT && A.wstage) LAPLEX_TIMED(fd.c_str(), st, hipLaunchKernelGGL((k_seq_down<STRICT, STRICT>), dim3((unsigned)g.tiles), block, 0, st, A));
-        else LAPLEX_TIMED(fd.c_str(), st, hipLaunchKernelGGL((k_seq_down<STRICT, false>), dim3((unsigned)g.tiles), block, 0, st, A));
+        const dim3 tiles((unsigned)g.tiles), dblock(kSeqDownThreads);
+        const bool red = STRICT && A.wstage != nullptr;
+        if (!STRICT) LAPLEX_TIMED(fd.c_str(), st, hipLaunchKernelGGL((k_seq_down<false, false, 1>), tiles, dblock, 0, st, A));
+        else if (red && two) LAPLEX_TIMED(fd.c_str(), st, hipLaunchKernelGGL((k_seq_down<STRICT, STRICT, 2>), tiles, dblock, 0, st, A));
+        else if (red) LAPLEX_TIMED(fd.c_str(), st, hipLaunchKernelGGL((k_seq_down<STRICT, STRICT, 1>), tiles, dblock, 0, st, A));
+        else if (two) LAPLEX_TIMED(fd.c_str(), st, hipLaunchKernelGGL((k_seq_down<STRICT, false, 2>), tiles, dblock, 0, st, A));
+        else LAPLEX_TIMED(fd.c_str(), st, hipLaunchKernelGGL((k_seq_down<STRICT, false, 1>), tiles, dblock, 0, st, A));
         return;
     }
     if (VEC == 4 && g.sub_shift) {    // wide geometry: a workgroup per tile, a wavefront per block
@@ -2071,7 +2131,7 @@ void launch_all(const ScanArgs& A, const ScanGeom& g, const std::string& tag, hi
 
 hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStream_t st)
 {
-    const bool strict = p.out_z != nullptr || p.out_red != nullptr;
+    const bool strict = p.out_z != nullptr || p.out_red != nullptr || p.emit_strict;
     // 128-bit lanes need every row start of every matrix touched to be 16-byte aligned
     bool v4 = p.batch % 4 == 0 && p.batch >= 4;
     v4 = v4 && aligned16(p.inj) && p.ld_inj % 4 == 0;
@@ -2088,6 +2148,8 @@ hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStrea
     A.out_red = p.out_red; A.ld_red = p.ld_red ? p.ld_red : 1; A.w = p.w; A.ld_w = p.ld_w; A.zs = p.zs;
     A.stage = p.stage; A.wstage = p.wstage;
     A.inj_sorted = p.inj_sorted ? 1 : 0; A.out_sorted = p.out_sorted ? 1 : 0;
+    if (p.emit) A.emit = *p.emit;
+    A.emit_first = p.emit_first ? 1 : 0;
     A.batch = p.batch; A.bpad = L.bpad;
     {
         const bool z_pair = p.out_z && !p.out_red && p.out_z == p.out_p + 1 && p.ld_z == 2;
@@ -2127,8 +2189,9 @@ hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStrea
     }
 
     const std::string tag = p.tag ? p.tag : "scan";
-    if (v4) { if (strict) launch_all<4, true>(A, g, tag, st); else launch_all<4, false>(A, g, tag, st); }
-    else    { if (strict) launch_all<1, true>(A, g, tag, st); else launch_all<1, false>(A, g, tag, st); }
+    const bool two = p.emit_values == 2;
+    if (v4) { if (strict) launch_all<4, true>(A, g, tag, two, st); else launch_all<4, false>(A, g, tag, two, st); }
+    else    { if (strict) launch_all<1, true>(A, g, tag, two, st); else launch_all<1, false>(A, g, tag, two, st); }
     if (p.out_red && g.slabs > 1) {
         const int64_t rows = (int64_t)p.res_hi - (int64_t)p.res_lo;
         int64_t gsz = (rows + 255) / 256; if (gsz > 65536) gsz = 65536; if (gsz < 1) gsz = 1;
