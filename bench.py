@@ -288,6 +288,9 @@ KERNEL_OF = {
     "scan_down.fwd": "k_scan_down, forward problem (reads x, writes y and the saved scans)",
     "scan_down.bwd": "k_scan_down, backward problem (reads gy, x and the saved scans, writes gx and the anchor gradient)",
     "radix_scatter": "k_onesweep_pass (one radix pass: reads the pairs once, writes them once)",
+    "permute_part.fwd": "k_part (partition levels: x into sorted order, y and the saved scans home)",
+    "permute_part.bwd": "k_part (partition levels: gy into sorted order, gx and gb home)",
+    "permute_part.rank": "k_part (partition levels of the inverse permutation)",
 }
 
 
@@ -306,8 +309,28 @@ def family_bytes(fam, spec, np, B):
     if fam == "decay":
         return 12 * N, "keys read, decays and sorted anchors written"
     base, _, tag = fam.partition(".")
+    # batch 1 from 2^26 merged positions on: values travel between the caller's order and the sorted order as records
+    # (destination, value[, value]) through partition levels, and the scans work on plain arrays in sorted order
+    routed = batch == 1 and N >= (1 << 26) and not gram
+    if routed and base == "permute_part":
+        if tag == "rank":
+            return 12 * N + 16 * N, "level 1: ids read, (id, position) pairs written; level 2: pairs read and written"
+        m_in, m_out = inj.get(tag, 0), res.get(tag, 0)
+        return 32 * m_in + 24 * m_out, ("the injected values: rank and value read, pairs written, pairs read and written (two levels); "
+                                        "the results: level 2 only (12 B records read and written; level 1 is the downsweep's)")
+    if routed and base == "permute_final":
+        if tag == "rank":
+            return 8 * N + 4 * N, "pairs read, rank written"
+        m_in, m_out = inj.get(tag, 0), res.get(tag, 0)
+        return 8 * m_in + 4 * N + 12 * m_out + 8 * m_out, "pairs read, the sorted-order array written whole; result records read, both outputs written"
     if tag not in inj:
         return None, None
+    if routed and base == "scan_reduce":
+        return 8 * N, "decay and injected value per sorted row"
+    if routed and base == "scan_down":
+        extra = 4 * N if tag == "bwd" else 0
+        return 12 * N + extra + 12 * res[tag], ("decay, injected value and id per sorted row" + (", the weight of the row reduction" if extra else "")
+                                                + ", one 12-byte record per result row written")
     narrow = batch <= 8
     if base == "scan_reduce":
         if batch >= 253 and batch % 4 == 0:
@@ -428,7 +451,7 @@ def measure(spec, steps, warmup, torch, np, B):
                    "pass": spec["passname"], "sort": "radix sort inside every step",
                    "workspace_bytes": spec["ws"].numel(), "device_bytes_peak": torch.cuda.max_memory_allocated()},
         "roofline": roofline,
-        "families_ms_one_step": {f: round(v[0], 4) for f, v in sorted(families.items(), key=lambda kv: -kv[1][0])[:8]},
+        "families_ms_one_step": {f: round(v[0], 4) for f, v in sorted(families.items(), key=lambda kv: -kv[1][0])[:16]},
         # compulsory HBM bytes of one step over the step time
         "end_to_end_hbm_frac": round(spec["compulsory"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
     }

@@ -66,10 +66,15 @@ constexpr int kPermuteWindowBits = 14;
 constexpr int kPermuteMaxBucketBits = 9;
 bool permute_supported(int64_t source_count, int64_t dest_count);      // destinations fit two partition levels
 size_t permute_cursor_words(int64_t dest_count);                        // the buckets' cursors of both levels
-// records that a level's output array must hold for `dest_count` destinations: whole bucket regions
+// records that a level's output array must hold for `dest_count` destinations: whole windows when one level fills
+// the windows directly (at most 2^9 of them), else whole regions of 2^9 windows; and whether there are two levels
+inline bool permute_two_levels(int64_t dest_count)
+{
+    return ((dest_count + ((int64_t)1 << kPermuteWindowBits) - 1) >> kPermuteWindowBits) > ((int64_t)1 << kPermuteMaxBucketBits);
+}
 inline int64_t permute_capacity(int64_t dest_count)
 {
-    const int64_t region = (int64_t)1 << (kPermuteWindowBits + kPermuteMaxBucketBits);
+    const int64_t region = (int64_t)1 << (kPermuteWindowBits + (permute_two_levels(dest_count) ? kPermuteMaxBucketBits : 0));
     return (dest_count + region - 1) / region * region;
 }
 
@@ -234,9 +239,9 @@ inline Layout make_layout(int64_t N, int64_t zrows, int64_t batch, bool permute_
         size_t q = align_up(L.total);
         const int64_t side = zrows > N - zrows ? zrows : N - zrows;      // result rows of a problem: at most this many
         const size_t cap1 = (size_t)permute_capacity(N), cap2 = (size_t)permute_capacity(side);
-        for (int lv = 0; lv < 2; ++lv) {
-            L.off_rec_dv[lv] = q; q = align_up(q + 2 * sizeof(uint32_t) * cap1);
-            L.off_rec_v1[lv] = q; q = align_up(q + sizeof(float) * cap2);
+        for (int lv = 0; lv < 2; ++lv) {     // (the second level's buffers only where some move has two levels)
+            L.off_rec_dv[lv] = q; if (lv == 0 || permute_two_levels(N)) q = align_up(q + 2 * sizeof(uint32_t) * cap1);
+            L.off_rec_v1[lv] = q; if (lv == 0 || permute_two_levels(side)) q = align_up(q + sizeof(float) * cap2);
         }
         L.off_pt_cursors = q; q = align_up(q + sizeof(uint32_t) * permute_cursor_words(N));
         L.total = q;
