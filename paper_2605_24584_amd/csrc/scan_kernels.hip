@@ -1708,6 +1708,87 @@ constexpr int kSeqItems = kItemsVec1;
 constexpr int kSeqDownItems = 8, kSeqDownWaves = 16, kSeqDownThreads = kSeqDownWaves * 64;
 static_assert(kSeqDownItems * kSeqDownThreads == kSeqItems * kScanThreads, "both kernels own blocks of the same rows");
 
+// exp(-x) by the hardware's base-2 exponential after one multiplication.  Only for decays that multiply a carry over a
+// span of rows inside a block: the relative error is about |x| * 6e-8 (the product x * log2(e) is rounded) plus one
+// unit in the last place, i.e. at most 0.37 * 6e-8 of the carry in absolute terms, whatever x; the per-row decays of
+// the plan and every decay that enters a summary of the spine stay on the accurate exponential.
+__device__ __forceinline__ float decay_fast(float x) { return __builtin_amdgcn_exp2f(x * -1.44269504088896340736f); }
+__device__ __forceinline__ float seq_decay_f(const ScanArgs& A, int64_t row0, int64_t count)
+{
+    const int64_t lo = row0 < A.N ? row0 : A.N;
+    int64_t hi = row0 + (count > 0 ? count : 0);
+    hi = hi < A.N ? hi : A.N;
+    const float d = decay_fast(A.pk[hi] - A.pk[lo]);
+    return hi > lo ? d : 1.0f;
+}
+__device__ __forceinline__ float seq_decay_b(const ScanArgs& A, int64_t row0, int64_t count)
+{
+    const int64_t lo = row0 < A.N ? row0 : A.N;
+    int64_t hi = row0 + (count > 0 ? count : 0);
+    hi = hi < A.N ? hi : A.N;
+    const float d = decay_fast(A.pk[hi + 1] - A.pk[lo + 1]);
+    return hi > lo ? d : 1.0f;
+}
+
+// Inclusive scan of summaries over the 64 lanes of a wavefront (one column, one row-lane per lane), forward (lane 0
+// first) or backward (lane 63 first): four steps inside each row of 16 lanes with data-parallel-primitive moves (a lane
+// whose source lies outside its row receives the identity, so no select is needed), then the three row totals reach
+// every lane through the scalar unit.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float identity, float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(identity), __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+template <int CTRL, bool STRICT>
+__device__ __forceinline__ Seg<1, STRICT> seg_dpp(const Seg<1, STRICT>& s)
+{
+    Seg<1, STRICT> r = seg_identity<1, STRICT>();
+    r.D = dpp_move<CTRL>(1.0f, s.D);
+    r.S[0] = dpp_move<CTRL>(0.0f, s.S[0]);
+    if (STRICT) {
+        r.Q[0] = dpp_move<CTRL>(0.0f, s.Q[0]);
+        r.H = __builtin_amdgcn_update_dpp(0, s.H, CTRL, 0xF, 0xF, false);
+    }
+    return r;
+}
+template <bool STRICT>
+__device__ __forceinline__ Seg<1, STRICT> seg_of_lane(const Seg<1, STRICT>& s, int l)     // l: uniform
+{
+    Seg<1, STRICT> r = seg_identity<1, STRICT>();
+    r.D = lane_f(s.D, l);
+    r.S[0] = lane_f(s.S[0], l);
+    if (STRICT) { r.Q[0] = lane_f(s.Q[0], l); r.H = __builtin_amdgcn_readlane(s.H, l); }
+    return r;
+}
+template <bool FWD, bool STRICT>
+__device__ __forceinline__ Seg<1, STRICT> row_scan16(Seg<1, STRICT> s)
+{
+    // row_shr:n = 0x110 + n (lane i takes lane i - n of its row), row_shl:n = 0x100 + n
+    s = seg_compose<1, STRICT>(seg_dpp<FWD ? 0x111 : 0x101, STRICT>(s), s);
+    s = seg_compose<1, STRICT>(seg_dpp<FWD ? 0x112 : 0x102, STRICT>(s), s);
+    s = seg_compose<1, STRICT>(seg_dpp<FWD ? 0x114 : 0x104, STRICT>(s), s);
+    s = seg_compose<1, STRICT>(seg_dpp<FWD ? 0x118 : 0x108, STRICT>(s), s);
+    return s;
+}
+template <bool FWD, bool STRICT>
+__device__ __forceinline__ Seg<1, STRICT> wave_scan64(Seg<1, STRICT> s, int lane)
+{
+    s = row_scan16<FWD, STRICT>(s);
+    // totals of the first three rows in scan order sit in the row's last lane in scan order
+    const Seg<1, STRICT> t0 = seg_of_lane<STRICT>(s, FWD ? 15 : 48), t1 = seg_of_lane<STRICT>(s, FWD ? 31 : 32),
+                         t2 = seg_of_lane<STRICT>(s, FWD ? 47 : 16);
+    const Seg<1, STRICT> p2 = seg_compose<1, STRICT>(t0, t1), p3 = seg_compose<1, STRICT>(p2, t2);
+    const int before = FWD ? lane >> 4 : 3 - (lane >> 4);       // rows ahead of this lane's in scan order
+    Seg<1, STRICT> pre = seg_identity<1, STRICT>();
+    pre.D = before == 1 ? t0.D : before == 2 ? p2.D : before == 3 ? p3.D : 1.0f;
+    pre.S[0] = before == 1 ? t0.S[0] : before == 2 ? p2.S[0] : before == 3 ? p3.S[0] : 0.0f;
+    if (STRICT) {
+        pre.Q[0] = before == 1 ? t0.Q[0] : before == 2 ? p2.Q[0] : before == 3 ? p3.Q[0] : 0.0f;
+        pre.H = before == 1 ? t0.H : before == 2 ? p2.H : before == 3 ? p3.H : 0;
+    }
+    return seg_compose<1, STRICT>(pre, s);
+}
+
 template <int ITEMS>
 struct SeqRows {
     static_assert(ITEMS % 4 == 0 && ITEMS <= 32, "a row-lane's rows are read in 16-byte pieces; one bit per row");
@@ -1764,6 +1845,7 @@ template <int WAVES>
 struct SeqSegs {
     float D[2][WAVES], C[2][WAVES], S[2][WAVES], Q[2][WAVES];
     int H[2][WAVES];
+    float preF[2][WAVES], preE[2][WAVES];     // state a wavefront starts from when its block starts from zero, per direction
     template <bool STRICT>
     __device__ __forceinline__ void put(int dir, int wave, const Seg<1, STRICT>& s)
     {
@@ -1792,8 +1874,8 @@ k_seq_reduce(const ScanArgs A)
     const int64_t wave_row0 = tile_base + (int64_t)wave * 64 * ITEMS;
     const int64_t row0 = wave_row0 + (int64_t)lane * ITEMS;
     // decays over this row-lane's rows, this wavefront's rows and the whole tile, from the anchors
-    const float lane_df = span_decay_f(A, row0, ITEMS), lane_db = span_decay_b(A, row0, ITEMS);
-    const float wave_df = span_decay_f(A, wave_row0, 64 * ITEMS), wave_db = span_decay_b(A, wave_row0, 64 * ITEMS);
+    const float lane_df = seq_decay_f(A, row0, ITEMS), lane_db = seq_decay_b(A, row0, ITEMS);
+    const float wave_df = seq_decay_f(A, wave_row0, 64 * ITEMS), wave_db = seq_decay_b(A, wave_row0, 64 * ITEMS);
     SeqRows<ITEMS> T;
     seq_meta<ITEMS>(A, row0, T);
     float v[ITEMS][1];
@@ -1808,7 +1890,7 @@ k_seq_reduce(const ScanArgs A)
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) seg_push<1, STRICT>(f, T.alive(i) && T.dh[i] >= 0.0f, T.dh[i], v[i]);
         f.D = lane_df;
-        f = wave_scan<true, 1, STRICT>(f, lane, 1, 64);
+        f = wave_scan64<true, STRICT>(f, lane);
         if (lane == 63) { f.D = wave_df; put_wave_seg<1, STRICT>(W, 0, wave, 0, f); }
     }
     {
@@ -1816,7 +1898,7 @@ k_seq_reduce(const ScanArgs A)
 #pragma unroll
         for (int i = ITEMS - 1; i >= 0; --i) seg_push<1, STRICT>(b, T.alive(i) && T.dh[i + 1] >= 0.0f, T.dh[i + 1], v[i]);
         b.D = lane_db;
-        b = wave_scan<false, 1, STRICT>(b, lane, 1, 64);
+        b = wave_scan64<false, STRICT>(b, lane);
         if (lane == 0) { b.D = wave_db; put_wave_seg<1, STRICT>(W, 1, wave, 0, b); }
     }
     __syncthreads();
@@ -1855,11 +1937,11 @@ k_seq_down(const ScanArgs A)
     const int64_t tile_base = tile * (int64_t)(THREADS * ITEMS);
     const int64_t wave_row0 = tile_base + (int64_t)wave * 64 * ITEMS;
     const int64_t row0 = wave_row0 + (int64_t)lane * ITEMS;
-    const float lane_df = span_decay_f(A, row0, ITEMS), lane_db = span_decay_b(A, row0, ITEMS);
-    const float wave_df = span_decay_f(A, wave_row0, 64 * ITEMS), wave_db = span_decay_b(A, wave_row0, 64 * ITEMS);
+    const float lane_df = seq_decay_f(A, row0, ITEMS), lane_db = seq_decay_b(A, row0, ITEMS);
+    const float wave_df = seq_decay_f(A, wave_row0, 64 * ITEMS), wave_db = seq_decay_b(A, wave_row0, 64 * ITEMS);
     const int64_t rows_after = row0 + ITEMS;
-    const float enter_df = span_decay_f(A, tile_base, row0 - tile_base);
-    const float enter_db = span_decay_b(A, rows_after, tile_base + A.tile_rows - rows_after);
+    const float enter_df = seq_decay_f(A, tile_base, row0 - tile_base);
+    const float enter_db = seq_decay_b(A, rows_after, tile_base + A.tile_rows - rows_after);
     const bool enter_hf = span_head_f(A, tile_base, row0 - tile_base);
     const bool enter_hb = span_head_b(A, rows_after, tile_base + A.tile_rows - rows_after);
 
@@ -1903,7 +1985,7 @@ k_seq_down(const ScanArgs A)
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) seg_push<1, STRICT>(f, T.alive(i) && T.dh[i] >= 0.0f, T.dh[i], v[i]);
         f.D = lane_df;
-        f = wave_scan<true, 1, STRICT>(f, lane, 1, 64);
+        f = wave_scan64<true, STRICT>(f, lane);
         if (lane == 63) { Seg<1, STRICT> tot = f; tot.D = wave_df; W.template put<STRICT>(0, wave, tot); }
         fe = seg_shfl<1, STRICT>(f, (lane - 1) & 63);
         if (lane == 0) fe = seg_identity<1, STRICT>();
@@ -1913,17 +1995,27 @@ k_seq_down(const ScanArgs A)
 #pragma unroll
         for (int i = ITEMS - 1; i >= 0; --i) seg_push<1, STRICT>(b, T.alive(i) && T.dh[i + 1] >= 0.0f, T.dh[i + 1], v[i]);
         b.D = lane_db;
-        b = wave_scan<false, 1, STRICT>(b, lane, 1, 64);
+        b = wave_scan64<false, STRICT>(b, lane);
         if (lane == 0) { Seg<1, STRICT> tot = b; tot.D = wave_db; W.template put<STRICT>(1, wave, tot); }
         be = seg_shfl<1, STRICT>(b, (lane + 1) & 63);
         if (lane == 63) be = seg_identity<1, STRICT>();
     }
     __syncthreads();
-    float F[1] = {0.0f}, E[1] = {0.0f}, R[1] = {0.0f}, G[1] = {0.0f};
-#pragma unroll 1
-    for (int w = 0; w < wave; ++w) seg_apply<1, STRICT>(W.template get<STRICT>(0, w), F, E);
-#pragma unroll 1
-    for (int w = WAVES - 1; w > wave; --w) seg_apply<1, STRICT>(W.template get<STRICT>(1, w), R, G);
+    // the state each wavefront starts from when the block starts from zero: one wavefront scans the 16 wavefront summaries
+    // of each direction (lane l holds the l-th in scan order) and leaves what precedes every wavefront
+    static_assert(WAVES == 16, "the wavefront summaries fill one row of 16 lanes");
+    if (wave == 0) {
+        const int l = lane & 15;
+        Seg<1, STRICT> sf = row_scan16<true, STRICT>(W.template get<STRICT>(0, l));              // lane l: wavefronts 0 .. l
+        Seg<1, STRICT> sb = row_scan16<true, STRICT>(W.template get<STRICT>(1, WAVES - 1 - l));   // lane l: wavefronts 15 .. 15 - l
+        if (lane < WAVES - 1) {
+            W.preF[0][lane + 1] = sf.S[0]; W.preE[0][lane + 1] = (STRICT && sf.H) ? sf.Q[0] : 0.0f;                      // before wavefront l + 1
+            W.preF[1][WAVES - 2 - lane] = sb.S[0]; W.preE[1][WAVES - 2 - lane] = (STRICT && sb.H) ? sb.Q[0] : 0.0f;      // after wavefront 14 - l
+        }
+        if (lane == 0) { W.preF[0][0] = W.preE[0][0] = 0.0f; W.preF[1][WAVES - 1] = W.preE[1][WAVES - 1] = 0.0f; }
+    }
+    __syncthreads();
+    float F[1] = {W.preF[0][wave]}, E[1] = {W.preE[0][wave]}, R[1] = {W.preF[1][wave]}, G[1] = {W.preE[1][wave]};
     seg_apply<1, STRICT>(fe, F, E);
     seg_apply<1, STRICT>(be, R, G);
     enter_state<1, STRICT>(F, E, Fc, Ec, enter_df, enter_hf);
