@@ -307,6 +307,8 @@ def family_bytes(fam, spec, np, B):
     if fam == "sort_hist":
         return 4 * N, "the anchors read once"
     if fam == "decay":
+        if batch == 1 and N >= (1 << 26) and not gram:
+            return 13 * N, "keys read, decays and sorted anchors written, every eighth anchor pair once more"
         return 12 * N, "keys read, decays and sorted anchors written"
     base, _, tag = fam.partition(".")
     # batch 1 from 2^26 merged positions on: values travel between the caller's order and the sorted order as records

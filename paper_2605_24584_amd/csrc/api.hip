@@ -113,6 +113,7 @@ int check_ws(const void* ws, size_t ws_bytes, const Layout& L)
 
 struct Plan {
     uint32_t* ids; float* dh; float* pk; float* z;
+    float2* pk8;    // every eighth sorted anchor with its successor (batch 1 with the sorted-order routes, else null)
     float* xs;      // saved region: the forward's injected rows in sorted order (narrow batches, else null)
     float* stage;   // scratch: the current problem's injected rows in sorted order (narrow batches, else null)
 };
@@ -122,6 +123,7 @@ Plan plan_of(const Layout& L, char* ws)
     const bool narrow = L.batch <= kStageMaxBatch;
     return Plan{reinterpret_cast<uint32_t*>(ws + L.off_ids), reinterpret_cast<float*>(ws + L.off_dh),
                 reinterpret_cast<float*>(ws + L.off_pk), reinterpret_cast<float*>(ws + L.off_z),
+                L.permute ? reinterpret_cast<float2*>(ws + L.off_pk8) : nullptr,
                 narrow ? reinterpret_cast<float*>(ws + L.off_xs) : nullptr,
                 narrow ? reinterpret_cast<float*>(ws + L.off_stage) : nullptr};
 }
@@ -195,11 +197,11 @@ int build_plan(const float* a, int64_t k, const float* b, int64_t n, float tau, 
     uint32_t* counters = reinterpret_cast<uint32_t*>(ws + L.off_counters);
     if (both_sorted) {
         LAPLEX_HIP(launch_merge(a, k, b, n, tau, keys0, P.ids, st));
-        LAPLEX_HIP(launch_decay(keys0, keys1, P.ids, ids1, nullptr, P.dh, P.pk, counters, L.N, st));
+        LAPLEX_HIP(launch_decay(keys0, keys1, P.ids, ids1, nullptr, P.dh, P.pk, P.pk8, counters, L.N, st));
     } else {
         LAPLEX_HIP(launch_onesweep_sort(a, k, b, n, tau, keys0, P.ids, keys1, ids1, small,
                                         reinterpret_cast<unsigned long long*>(ws + L.off_status), st));
-        LAPLEX_HIP(launch_decay(keys0, keys1, P.ids, ids1, small, P.dh, P.pk, counters, L.N, st));
+        LAPLEX_HIP(launch_decay(keys0, keys1, P.ids, ids1, small, P.dh, P.pk, P.pk8, counters, L.N, st));
     }
     if (use_permute(L)) {        // the inverse permutation, part of the plan: rank[ids[j]] = j
         PermuteJob J = permute_job(L, ws, "rank");
@@ -234,7 +236,7 @@ const uint32_t* plan_status_word(const Layout& L, const char* ws)
 ScanProblem problem(const Plan& P, const Layout& L)
 {
     ScanProblem p{};
-    p.ids = P.ids; p.dh = P.dh; p.pk = P.pk; p.N = L.N; p.batch = L.batch;
+    p.ids = P.ids; p.dh = P.dh; p.pk = P.pk; p.pk8 = P.pk8; p.N = L.N; p.batch = L.batch;
     return p;
 }
 

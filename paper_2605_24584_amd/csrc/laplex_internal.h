@@ -167,6 +167,7 @@ struct Layout {
     // batch 1 beyond the small path: the routes through sorted order without random accesses
     bool permute = false;        // the regions below exist
     size_t off_rank = 0;         // u32[N]     plan: rank[id] = sorted position of anchor id
+    size_t off_pk8 = 0;          // float2[(N+2)/8 + 1]  plan: (pk[8m], pk[8m + 1]), the anchors the sorted-order kernels need
     size_t off_rec_dv[2] = {0, 0}, off_rec_v1[2] = {0, 0};   // records of the two partition levels: (destination, value) pairs, second values
     size_t off_pt_cursors = 0;   // u32[permute_cursor_words]  records placed per bucket, both levels
     size_t total = 0;
@@ -188,6 +189,8 @@ inline Layout make_layout(int64_t N, int64_t zrows, int64_t batch, bool permute_
     L.permute = permute_regions && batch == 1 && N > kSmallMax && permute_supported(N, N);
     L.off_rank = o;
     if (L.permute) o = align_up(o + sizeof(uint32_t) * (size_t)N);
+    L.off_pk8 = o;
+    if (L.permute) o = align_up(o + 2 * sizeof(float) * ((size_t)(N + 2) / 8 + 1));
     L.off_scratch = o;
 
     // sort view
@@ -286,7 +289,7 @@ hipError_t launch_merge(const float* a, int64_t k, const float* b, int64_t n, fl
 // ghist == nullptr: the pairs are in buffer 0 (merge path).  The last kernel of every plan build: it also clears
 // the scans' list counters (64 words).
 hipError_t launch_decay(const uint32_t* keys0, const uint32_t* keys1, uint32_t* ids0, const uint32_t* ids1,
-                        const uint32_t* ghist, float* dh, float* pk, uint32_t* counters, int64_t N, hipStream_t st);
+                        const uint32_t* ghist, float* dh, float* pk, float2* pk8, uint32_t* counters, int64_t N, hipStream_t st);
 
 hipError_t launch_fill(float* p, int64_t rows, int64_t cols, int64_t ld, float v, hipStream_t st);
 hipError_t launch_copy_u32(const uint32_t* src, uint32_t* dst, int64_t count, hipStream_t st);
@@ -340,6 +343,7 @@ hipError_t permute_finish(const PermuteJob& J, hipStream_t st);
 
 struct ScanProblem {
     const uint32_t* ids; const float* dh; const float* pk; int64_t N;
+    const float2* pk8 = nullptr;     // (pk[8m], pk[8m + 1]) per 8 rows, or null (batch 1 in sorted order only)
     const float* inj; int64_t ld_inj; uint32_t inj_lo, inj_hi;
     uint32_t res_lo, res_hi;
     float* out_p; int64_t ld_p;

@@ -52,6 +52,7 @@ struct Level {            // summaries of one level (tiles, or chunks of tiles) 
 
 struct ScanArgs {
     const uint32_t* ids; const float* dh; const float* pk; int64_t N;
+    const float2* pk8;                   // (pk[8m], pk[8m + 1]), or null
     const float* inj; int64_t ld_inj; uint32_t inj_lo, inj_hi;
     uint32_t res_lo, res_hi;
     float* out_p; int64_t ld_p;
@@ -1713,21 +1714,33 @@ static_assert(kSeqDownItems * kSeqDownThreads == kSeqItems * kScanThreads, "both
 // unit in the last place, i.e. at most 0.37 * 6e-8 of the carry in absolute terms, whatever x; the per-row decays of
 // the plan and every decay that enters a summary of the spine stay on the accurate exponential.
 __device__ __forceinline__ float decay_fast(float x) { return __builtin_amdgcn_exp2f(x * -1.44269504088896340736f); }
-__device__ __forceinline__ float seq_decay_f(const ScanArgs& A, int64_t row0, int64_t count)
+// The sorted anchors at a position that is a multiple of 8 rows (or the end of the sequence): (pk[pos], pk[pos + 1]),
+// from the packed copy of every eighth pair where the plan has one.  A lane that owns 8 or 16 consecutive rows would
+// otherwise touch every 32-byte sector of pk for two values, and the kernel would fetch the whole array.
+__device__ __forceinline__ float2 seq_anchor(const ScanArgs& A, int64_t pos)
 {
-    const int64_t lo = row0 < A.N ? row0 : A.N;
-    int64_t hi = row0 + (count > 0 ? count : 0);
-    hi = hi < A.N ? hi : A.N;
-    const float d = decay_fast(A.pk[hi] - A.pk[lo]);
-    return hi > lo ? d : 1.0f;
+    pos = pos < A.N ? pos : A.N;
+    if (A.pk8 != nullptr && (pos & 7) == 0) return A.pk8[pos >> 3];
+    return make_float2(A.pk[pos], A.pk[pos + 1]);
 }
-__device__ __forceinline__ float seq_decay_b(const ScanArgs& A, int64_t row0, int64_t count)
+// Decays and head flags over the rows between two such positions lo <= hi (clamped to the sequence like seq_anchor's),
+// forward sense (.x: from the anchor before the rows to their last) and backward sense (.y).
+struct SeqSpan {
+    float df, db;
+    bool hf, hb;
+};
+__device__ __forceinline__ SeqSpan seq_span(const ScanArgs& A, int64_t lo, const float2& plo, int64_t hi, const float2& phi)
 {
-    const int64_t lo = row0 < A.N ? row0 : A.N;
-    int64_t hi = row0 + (count > 0 ? count : 0);
+    lo = lo < A.N ? lo : A.N;
     hi = hi < A.N ? hi : A.N;
-    const float d = decay_fast(A.pk[hi + 1] - A.pk[lo + 1]);
-    return hi > lo ? d : 1.0f;
+    SeqSpan r;
+    const bool any = hi > lo;
+    const float f = decay_fast(phi.x - plo.x), b = decay_fast(phi.y - plo.y);
+    r.df = any ? f : 1.0f;
+    r.db = any ? b : 1.0f;
+    r.hf = any && phi.x != plo.x;
+    r.hb = any && phi.y != plo.y;
+    return r;
 }
 
 // Inclusive scan of summaries over the 64 lanes of a wavefront (one column, one row-lane per lane), forward (lane 0
@@ -1873,9 +1886,12 @@ k_seq_reduce(const ScanArgs A)
     const int64_t tile_base = tile * (kScanWaves * 64 * ITEMS);
     const int64_t wave_row0 = tile_base + (int64_t)wave * 64 * ITEMS;
     const int64_t row0 = wave_row0 + (int64_t)lane * ITEMS;
-    // decays over this row-lane's rows, this wavefront's rows and the whole tile, from the anchors
-    const float lane_df = seq_decay_f(A, row0, ITEMS), lane_db = seq_decay_b(A, row0, ITEMS);
-    const float wave_df = seq_decay_f(A, wave_row0, 64 * ITEMS), wave_db = seq_decay_b(A, wave_row0, 64 * ITEMS);
+    // decays over this row-lane's rows and over this wavefront's rows, from the anchors
+    const float2 p_lane0 = seq_anchor(A, row0), p_lane1 = seq_anchor(A, row0 + ITEMS);
+    const float2 p_wave0 = seq_anchor(A, wave_row0), p_wave1 = seq_anchor(A, wave_row0 + 64 * ITEMS);
+    const SeqSpan lane_span = seq_span(A, row0, p_lane0, row0 + ITEMS, p_lane1);
+    const SeqSpan wave_span = seq_span(A, wave_row0, p_wave0, wave_row0 + 64 * ITEMS, p_wave1);
+    const float lane_df = lane_span.df, lane_db = lane_span.db, wave_df = wave_span.df, wave_db = wave_span.db;
     SeqRows<ITEMS> T;
     seq_meta<ITEMS>(A, row0, T);
     float v[ITEMS][1];
@@ -1937,13 +1953,17 @@ k_seq_down(const ScanArgs A)
     const int64_t tile_base = tile * (int64_t)(THREADS * ITEMS);
     const int64_t wave_row0 = tile_base + (int64_t)wave * 64 * ITEMS;
     const int64_t row0 = wave_row0 + (int64_t)lane * ITEMS;
-    const float lane_df = seq_decay_f(A, row0, ITEMS), lane_db = seq_decay_b(A, row0, ITEMS);
-    const float wave_df = seq_decay_f(A, wave_row0, 64 * ITEMS), wave_db = seq_decay_b(A, wave_row0, 64 * ITEMS);
-    const int64_t rows_after = row0 + ITEMS;
-    const float enter_df = seq_decay_f(A, tile_base, row0 - tile_base);
-    const float enter_db = seq_decay_b(A, rows_after, tile_base + A.tile_rows - rows_after);
-    const bool enter_hf = span_head_f(A, tile_base, row0 - tile_base);
-    const bool enter_hb = span_head_b(A, rows_after, tile_base + A.tile_rows - rows_after);
+    const int64_t rows_after = row0 + ITEMS, tile_end = tile_base + A.tile_rows;
+    const float2 p_lane0 = seq_anchor(A, row0), p_lane1 = seq_anchor(A, rows_after);
+    const float2 p_wave0 = seq_anchor(A, wave_row0), p_wave1 = seq_anchor(A, wave_row0 + 64 * ITEMS);
+    const float2 p_tile0 = seq_anchor(A, tile_base), p_tile1 = seq_anchor(A, tile_end);
+    const SeqSpan lane_span = seq_span(A, row0, p_lane0, rows_after, p_lane1);
+    const SeqSpan wave_span = seq_span(A, wave_row0, p_wave0, wave_row0 + 64 * ITEMS, p_wave1);
+    const SeqSpan ahead = seq_span(A, tile_base, p_tile0, row0, p_lane0);          // the rows of the block before this row-lane's
+    const SeqSpan behind = seq_span(A, rows_after, p_lane1, tile_end, p_tile1);    // and after them
+    const float lane_df = lane_span.df, lane_db = lane_span.db, wave_df = wave_span.df, wave_db = wave_span.db;
+    const float enter_df = ahead.df, enter_db = behind.db;
+    const bool enter_hf = ahead.hf, enter_hb = behind.hb;
 
     SeqRows<ITEMS> T;
     seq_meta<ITEMS>(A, row0, T);
@@ -2233,7 +2253,7 @@ hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStrea
     const ScanGeom g = scan_geom(p.N, p.batch, v4 ? 4 : 1);
 
     ScanArgs A;
-    A.ids = p.ids; A.dh = p.dh; A.pk = p.pk; A.N = p.N;
+    A.ids = p.ids; A.dh = p.dh; A.pk = p.pk; A.pk8 = p.pk8; A.N = p.N;
     A.inj = p.inj; A.ld_inj = p.ld_inj; A.inj_lo = p.inj_lo; A.inj_hi = p.inj_hi;
     A.res_lo = p.res_lo; A.res_hi = p.res_hi;
     A.out_p = p.out_p; A.ld_p = p.ld_p; A.out_z = p.out_z; A.ld_z = p.ld_z ? p.ld_z : p.batch;

@@ -495,7 +495,7 @@ k_merge(const float* __restrict__ a, int64_t k, const float* __restrict__ b, int
 __global__ void __launch_bounds__(256)
 k_decay(const uint32_t* __restrict__ keys0, const uint32_t* __restrict__ keys1,
         uint32_t* __restrict__ ids0, const uint32_t* __restrict__ ids1,
-        const uint32_t* __restrict__ ghist, float* __restrict__ dh, float* __restrict__ pk,
+        const uint32_t* __restrict__ ghist, float* __restrict__ dh, float* __restrict__ pk, float2* __restrict__ pk8,
         uint32_t* __restrict__ counters, int64_t N)
 {
     // list lengths of the scans that follow; and the sort's error flag moves to the plan (the sort's own words are scratch)
@@ -540,6 +540,9 @@ k_decay(const uint32_t* __restrict__ keys0, const uint32_t* __restrict__ keys1,
                 if (j0 + u <= N + 1) pk[j0 + u] = a[u];
             }
         }
+        // every eighth anchor with its successor once more, packed (the kernels of the sorted order of batch 1 take their
+        // span decays from these instead of touching every sector of pk)
+        if (pk8 != nullptr && (q & 1) == 0 && j0 <= N + 1) pk8[q >> 1] = make_float2(a[0], a[1]);
     }
 }
 
@@ -625,10 +628,10 @@ hipError_t launch_merge(const float* a, int64_t k, const float* b, int64_t n, fl
 }
 
 hipError_t launch_decay(const uint32_t* keys0, const uint32_t* keys1, uint32_t* ids0, const uint32_t* ids1,
-                        const uint32_t* ghist, float* dh, float* pk, uint32_t* counters, int64_t N, hipStream_t st)
+                        const uint32_t* ghist, float* dh, float* pk, float2* pk8, uint32_t* counters, int64_t N, hipStream_t st)
 {
     LAPLEX_TIMED("decay", st, hipLaunchKernelGGL(k_decay, dim3(grid_for((N + 5) / 4, 256)), dim3(256), 0, st,
-                                                 keys0, keys1, ids0, ids1, ghist, dh, pk, counters, N));
+                                                 keys0, keys1, ids0, ids1, ghist, dh, pk, pk8, counters, N));
     return hipGetLastError();
 }
 
