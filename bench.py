@@ -361,6 +361,7 @@ def make_spec(name, args, torch, np, B, synth):
     """Inputs on the device, outputs, workspace and the step function of one of the roofline workloads."""
     dev = lambda v: torch.from_numpy(np.ascontiguousarray(v)).cuda()
     scale = args.scale
+    torch.cuda.reset_peak_memory_stats()       # device_bytes_peak is this workload's own
     if name == "gram":
         w = synth.gram_images(scale=scale)
         a, x, g = w["a"], w["x"], w["g"]
@@ -437,15 +438,22 @@ def measure(spec, steps, warmup, torch, np, B):
                 "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None, "traffic": None,
                 "avg_kernel_ms": round(dom_ms / max(dom_launches, 1), 5), "launches": dom_launches,
                 "launches_per_step": per_step_launches, "family_ms_per_step": round(dom_ms_per_step, 5),
-                "algorithmic_bytes_per_step": fam_bytes, "counted": note}
+                "algorithmic_bytes_per_step": fam_bytes,
+                "algorithmic_bytes_per_launch": (fam_bytes / per_step_launches) if fam_bytes and per_step_launches else None,
+                "counted": note}
     if fam_bytes:
         achieved = fam_bytes / (dom_ms_per_step * 1e-3) / 1e9
         roofline.update(achieved=round(achieved, 1), frac=round(achieved / HBM_PEAK_GBS, 4))
-    traffic_file = os.path.join(ROOT, "profiles", f"traffic_{dominant.replace('.', '_')}_{spec['name'].split('/')[0]}.json")
+    traffic_file = os.path.join(ROOT, "profiles", f"traffic_{dominant.replace('.', '_')}_{spec['name'].split('/')[0].replace('^', 'p')}.json")
     if os.path.exists(traffic_file) and "/scaled" not in spec["name"]:
         with open(traffic_file) as fh:
             rec = json.load(fh)
-            roofline["traffic"] = rec.get("hbm_bytes_per_step", rec.get("hbm_bytes_per_launch"))
+            # per launch, like avg_kernel_ms (a family with several launches per step: the step's bytes over its launches)
+            if "hbm_bytes_per_step" in rec:
+                roofline["traffic"] = rec["hbm_bytes_per_step"] / max(per_step_launches, 1)
+                roofline["traffic_per_step"] = rec["hbm_bytes_per_step"]
+            else:
+                roofline["traffic"] = rec.get("hbm_bytes_per_launch")
         roofline["traffic_source"] = "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, " + os.path.relpath(traffic_file, ROOT)
     out = {
         "ms_per_step": round(ms_per_step, 4), "value": elements / (ms_per_step * 1e-3),
