@@ -260,6 +260,18 @@ PhasedLayout phased_layout(int64_t k, int64_t n, int64_t batch)
     return P;
 }
 
+// Can the phased backward leave the merge of the two halves to the streaming downsweep (PhaseFuse)?  The inner problem must
+// take the wide geometry with one wavefront across a half-row, and every row the kernel touches must allow 16-byte accesses.
+bool phase_fusable(int64_t k, int64_t n, int64_t batch, const float* x, int64_t ldx, const float* gx, int64_t ldgx)
+{
+    if (k + n <= kSmallMax || batch % 4 != 0 || batch > 256) return false;
+    const ScanGeom g = scan_geom(k + n, 2 * batch, 4);
+    if (!g.sub_shift || g.slabs > 2) return false;
+    if (x && (misaligned(x, 16) || ldx % 4 != 0)) return false;
+    if (gx && (misaligned(gx, 16) || ldgx % 4 != 0)) return false;
+    return true;
+}
+
 int check_phased_sizes(int64_t k, int64_t n, int64_t batch)
 {
     if (batch < 0 || batch > INT64_MAX / 4) return LAPLEX_ERR_SIZE;
@@ -421,7 +433,8 @@ static int apply_impl(const float* a, int64_t k, const float* b, int64_t n,
 static int apply_backward_impl(const float* a, int64_t k, const float* b, int64_t n,
                           const float* x, int64_t ldx, const float* gy, int64_t ldgy, int64_t batch,
                           float* gx, int64_t ldgx, float* ga, float* gb,
-                          void* ws, size_t ws_bytes, uint32_t flags, float tau, float* gtau, laplex_stream_t stream)
+                          void* ws, size_t ws_bytes, uint32_t flags, float tau, float* gtau, laplex_stream_t stream,
+                          const PhaseFuse* fuse = nullptr)
 {
     const uint32_t known = LAPLEX_A_SORTED | LAPLEX_B_SORTED | LAPLEX_REUSE_PLAN | LAPLEX_SAVE_SCANS;
     if (flags & ~known) return LAPLEX_ERR_FLAGS;
@@ -520,6 +533,7 @@ static int apply_backward_impl(const float* a, int64_t k, const float* b, int64_
         p.stage = P.stage;
         p.wstage = (gb && have_xs) ? P.xs : nullptr;
         p.tag = "bwd";
+        p.phase = fuse;           // phased backward: the streaming downsweep merges the two halves (see phase_fusable)
         LAPLEX_HIP(launch_scan(p, L, w, st));
         if (paired) LAPLEX_HIP(launch_unpair(pairs, n, gx, ldgx, gb, st));
     }
@@ -847,9 +861,14 @@ int laplex_phased_apply_backward(const float* a, const float* phi, int64_t k, co
         inner = flags | LAPLEX_SAVE_SCANS | LAPLEX_REUSE_PLAN;
     }
     const bool want_gx2 = gx || gpsi;
-    LAPLEX_CHECK(laplex_apply_backward(a, k, b, n, x ? x2 : nullptr, 2 * batch, g2, 2 * batch, 2 * batch,
-                                       want_gx2 ? gx2 : nullptr, 2 * batch, ga, gb, ws, P.inner, inner, stream));
-    if (want_gx2) LAPLEX_HIP(launch_phase_merge(gx2, psi, n, batch, gx, ldgx, x, ldx, gpsi, st));
+    // With a wide batch the streaming downsweep forms gx and gpsi itself (and takes gb's weights from x): the doubled
+    // result matrix is then written only for the blocks the other downsweeps own, and merged there.
+    const bool fused = want_gx2 && phase_fusable(k, n, batch, x, ldx, gx, ldgx);
+    const PhaseFuse fuse{psi, (gb || gpsi) ? x : nullptr, ldx, gx, ldgx, gpsi, batch};
+    LAPLEX_CHECK(apply_backward_impl(a, k, b, n, x ? x2 : nullptr, 2 * batch, g2, 2 * batch, 2 * batch,
+                                     want_gx2 ? gx2 : nullptr, 2 * batch, ga, gb, ws, P.inner, inner, 1.0f, nullptr, stream,
+                                     fused ? &fuse : nullptr));
+    if (want_gx2 && !fused) LAPLEX_HIP(launch_phase_merge(gx2, psi, n, batch, gx, ldgx, x, ldx, gpsi, st));
     if (gphi) LAPLEX_HIP(launch_phase_merge(y2, phi, k, batch, nullptr, 0, gy, ldgy, gphi, st));
     return LAPLEX_OK;
 }

@@ -341,6 +341,20 @@ hipError_t launch_permute(const PermuteJob& J, hipStream_t st);
 hipError_t permute_begin(const PermuteJob& J, PartEmit* first_level, hipStream_t st);
 hipError_t permute_finish(const PermuteJob& J, hipStream_t st);
 
+// Phased backward, fused (Sec. 3 "Phased Laplace kernels"): the scan problem runs on the doubled batch
+// [gy cos phi | gy sin phi] (2 * half columns) and its result rows are the inputs.  With this set, the streaming
+// downsweep of the wide geometry forms, per input row j, both halves GX_c, GX_s of the plain result in registers and writes
+//   gx[j]   = cos(psi_j) GX_c + sin(psi_j) GX_s,          gpsi[j] = sum_t x[j][t] (cos(psi_j) GX_s - sin(psi_j) GX_c)[t]
+// and takes the weights of the row reduction (gb) from x itself, as x cos(psi_j) and x sin(psi_j); the doubled result
+// matrix is only written (to out_p) for the few blocks the other downsweeps own, and a pass over those blocks merges them.
+struct PhaseFuse {
+    const float* psi;           // [result rows] phases of the result rows
+    const float* x; int64_t ldx;    // [result rows][half] or null (no gb, no gpsi)
+    float* gx; int64_t ldgx;        // [result rows][half] or null
+    float* gpsi;                    // [result rows] or null
+    int64_t half;                   // columns of one half; 0: off
+};
+
 struct ScanProblem {
     const uint32_t* ids; const float* dh; const float* pk; int64_t N;
     const float2* pk8 = nullptr;     // (pk[8m], pk[8m + 1]) per 8 rows, or null (batch 1 in sorted order only)
@@ -361,6 +375,7 @@ struct ScanProblem {
     // emit_values how many outputs a record carries (2: F + R - v and the second output; 1: emit_first says which),
     // emit_strict that the second output is wanted (the strict scans Z, or w * Z when wstage is given)
     const PartEmit* emit = nullptr; int emit_values = 1; bool emit_first = true, emit_strict = false;
+    const PhaseFuse* phase = nullptr;      // wide geometry, at most 256 columns per half (see PhaseFuse)
 };
 hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStream_t st);
 

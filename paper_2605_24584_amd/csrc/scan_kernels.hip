@@ -83,6 +83,7 @@ struct ScanArgs {
     int out_sorted;               // batch 1: outputs are indexed by the sorted row, not by the id (a later pass takes them home)
     PartEmit emit;                // batch 1, sorted order: the results leave as records of a partition level (k_seq_down)
     int emit_first;               // one value per record: the first output of a row (F + R - v), else its second
+    PhaseFuse ph;                 // ph.half != 0: the phased backward's streaming downsweep merges the two halves itself
 };
 
 constexpr int kFlagInj = 1, kFlagRes = 2;
@@ -1692,6 +1693,228 @@ k_scan_down_sparse_wide(const ScanArgs A)
     }
 }
 
+// Eight row sums over the 64 lanes of a wavefront (part[i]: this lane's share of row i): three butterfly steps leave lane l
+// with the sum of row (l & 7) over its group of eight lanes, three more add the groups up.  Every lane returns the total of
+// row (lane & 7).
+__device__ __forceinline__ float row_sums8(const float* part, int lane)
+{
+    float h4[4], h2[2];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const bool up = (lane & 4) != 0;
+        const float keep = up ? part[j + 4] : part[j], send = up ? part[j] : part[j + 4];
+        h4[j] = keep + __shfl_xor(send, 4);
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const bool up = (lane & 2) != 0;
+        const float keep = up ? h4[j + 2] : h4[j], send = up ? h4[j] : h4[j + 2];
+        h2[j] = keep + __shfl_xor(send, 2);
+    }
+    const bool up = (lane & 1) != 0;
+    const float keep = up ? h2[1] : h2[0], send = up ? h2[0] : h2[1];
+    float sum = keep + __shfl_xor(send, 1);
+    sum += __shfl_xor(sum, 8);
+    sum += __shfl_xor(sum, 16);
+    sum += __shfl_xor(sum, 32);
+    return sum;
+}
+
+// ---------------------------------------------------------------------------
+// The streaming downsweep of the wide geometry for the phased backward (Sec. 3, "Phased Laplace kernels":
+// cos(phi - psi) = cos phi cos psi + sin phi sin psi makes the phased product two plain ones on a doubled batch).
+// The scan problem runs on [gy cos phi | gy sin phi]; a lane owns four columns of BOTH halves, so that per input row j
+//   gx[j]   = cos(psi_j) GX_c[j] + sin(psi_j) GX_s[j]
+//   gpsi[j] = sum_t x[j][t] (cos(psi_j) GX_s - sin(psi_j) GX_c)[j][t]
+//   gb[j]   = sum_t x[j][t] cos(psi_j) Z_c[j][t] + sum_t x[j][t] sin(psi_j) Z_s[j][t]
+// come out of one read of x and one write of gx: the doubled result matrix and the doubled copy of x are not touched.
+// Same blocks, closed forms and direct terms as k_scan_down_sparse_wide; the products x cos(psi), x sin(psi) are rounded
+// before they are used, as the split pass would have stored them.  One slab: a half has at most 256 columns.
+// ---------------------------------------------------------------------------
+template <bool STRICT>
+__global__ void __launch_bounds__(kStreamWaves * 64)
+k_scan_down_sparse_wide_phased(const ScanArgs A)
+{
+    constexpr int VEC = 4, ROWS = 64, CH = 8, NS = kFewRows;
+    // the last kernel of a scan that looks at the list lengths: the next scan wants them at zero
+    if (blockIdx.x == 0 && threadIdx.x < 2) A.counters[threadIdx.x] = 0u;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int64_t blk = (int64_t)blockIdx.x * kStreamWaves + wave;
+    if (blk >= A.blocks) return;
+    const int flags = (int)A.blk_flags[blk];
+    if (!(flags & kFlagRes) || ((flags & kFlagInj) && !(flags & kFlagFewInj))) return;
+    const uint32_t poison = plan_poison(A.counters);
+    const int64_t half = A.ph.half;
+    const int64_t col0 = (int64_t)lane * VEC;
+    const bool col_ok = col0 < half;
+    const int64_t colc = col_ok ? col0 : 0;      // lanes past the last column read (and drop) columns 0..3
+
+    WideMeta M;
+    M.fetch(A, blk, lane);
+    float Fin[2][VEC], Ein[2][VEC], Rin[2][VEC], Gin[2][VEC];
+    load_block_carries<VEC, STRICT>(A, blk, col0, col_ok, Fin[0], Ein[0], Rin[0], Gin[0]);
+    load_block_carries<VEC, STRICT>(A, blk, col0 + half, col_ok, Fin[1], Ein[1], Rin[1], Gin[1]);
+    const uint32_t idv = M.live ? M.id : 0xFFFFFFFFu;
+    const bool my_res = idv >= A.res_lo && idv < A.res_hi;
+    const uint64_t res_mask = __ballot(my_res);
+    const uint64_t hf_mask = __ballot(M.live && M.dl >= 0.0f), hb_mask = __ballot(M.live && M.dr >= 0.0f);
+    const float kf = expf(-(M.p - M.p_before)), kb = expf(-(M.p_after - M.p));
+    // lane l holds the cosine and sine of the phase of row l
+    float cph = 1.0f, sph = 0.0f;
+    if (my_res) sincosf(A.ph.psi[idv - A.res_lo], &sph, &cph);
+
+    const bool sources = (flags & kFlagFewInj) != 0;       // uniform
+    float vs[2][NS][VEC], ws[NS], wz[NS];
+#pragma unroll
+    for (int q = 0; q < NS; ++q) {
+        ws[q] = wz[q] = 0.0f;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) vs[0][q][e] = vs[1][q][e] = 0.0f;
+    }
+    if (sources) {
+        uint64_t m = __ballot(idv >= A.inj_lo && idv < A.inj_hi);
+#pragma unroll
+        for (int q = 0; q < NS; ++q) {
+            const bool have = m != 0;
+            const int rs = have ? __ffsll((long long)m) - 1 : 0;
+            m &= m - 1;
+            const float pq = lane_f(M.p, rs);
+            const uint32_t idq = lane_u(idv, rs);
+            if (have && col_ok) {
+                const float* row = A.inj + (int64_t)(idq - A.inj_lo) * A.ld_inj + col0;
+                load_vec<VEC>(vs[0][q], row);
+                load_vec<VEC>(vs[1][q], row + half);
+            }
+            ws[q] = have ? expf(-fabsf(M.p - pq)) : 0.0f;
+            wz[q] = pq > M.p ? ws[q] : (pq < M.p ? -ws[q] : 0.0f);
+        }
+    }
+
+    const bool want_x = A.ph.x != nullptr;
+    const bool want_red = STRICT && A.out_red != nullptr && want_x;
+    const bool want_gpsi = A.ph.gpsi != nullptr && want_x;
+    const int64_t res_rows = (int64_t)A.res_hi - (int64_t)A.res_lo;
+#pragma unroll
+    for (int c = 0; c < ROWS / CH; ++c) {
+        if (!((res_mask >> (c * CH)) & 0xFFull)) continue;          // uniform: no result row among these eight
+        v4f x[CH];
+        if (want_x) {       // (no branch around a load: rows that are not wanted read row 0)
+#pragma unroll
+            for (int i = 0; i < CH; ++i) {
+                const int row = c * CH + i;
+                const int64_t rr = ((res_mask >> row) & 1ull) ? (int64_t)(lane_u(idv, row) - A.res_lo) : 0;
+                x[i] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(A.ph.x + rr * A.ph.ldx + colc));
+            }
+        }
+        float part_c[CH], part_s[CH], part_p[CH];
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int row = c * CH + i;
+            const bool is_res = ((res_mask >> row) & 1ull) != 0;                  // uniform
+            const float f = lane_f(kf, row), b = lane_f(kb, row);
+            const float cr = lane_f(cph, row), sr = lane_f(sph, row);
+            const bool seen_f = (hf_mask & ((2ull << row) - 1ull)) != 0;          // a run head at or before the row
+            const bool seen_b = (hb_mask >> row) != 0;                            // ... at or after it, seen from the right
+            float P[2][VEC], Z[2][VEC];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    const float Fj = f * Fin[h][e], Rj = b * Rin[h][e];
+                    P[h][e] = Fj + Rj;
+                    Z[h][e] = (seen_b ? Rj : Gin[h][e]) - (seen_f ? Fj : Ein[h][e]);
+                }
+            }
+            if (sources) {
+#pragma unroll
+                for (int q = 0; q < NS; ++q) {
+                    const float a = lane_f(ws[q], row), z = lane_f(wz[q], row);
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) { P[h][e] += a * vs[h][q][e]; Z[h][e] += z * vs[h][q][e]; }
+                    }
+                }
+            }
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) { P[h][e] = taint(P[h][e], poison); Z[h][e] = taint(Z[h][e], poison); }
+            }
+            part_c[i] = part_s[i] = part_p[i] = 0.0f;
+            if (is_res && col_ok) {
+                const int64_t rr = (int64_t)(lane_u(idv, row) - A.res_lo);
+                if (A.ph.gx) {
+                    v4f o;
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) o[e] = cr * P[0][e] + sr * P[1][e];
+                    __builtin_nontemporal_store(o, reinterpret_cast<v4f*>(A.ph.gx + rr * A.ph.ldgx + col0));
+                }
+                if (want_x) {
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) {
+                        const float xc = x[i][e] * cr, xs = x[i][e] * sr;      // the two halves of the modulated row
+                        if (want_red) { part_c[i] += xc * Z[0][e]; part_s[i] += xs * Z[1][e]; }
+                        part_p[i] += x[i][e] * (cr * P[1][e] - sr * P[0][e]);
+                    }
+                }
+            }
+        }
+        const int row = c * CH + (lane & 7);
+        const uint32_t idr = __shfl(idv, row);
+        const bool writer = lane < 8 && ((res_mask >> row) & 1ull);
+        const int64_t rr = (int64_t)(idr - A.res_lo);
+        if (want_red) {
+            const float sum_c = row_sums8(part_c, lane), sum_s = row_sums8(part_s, lane);
+            if (writer) {
+                if (A.slabs == 1) A.out_red[rr * A.ld_red] = sum_c + sum_s;
+                else { A.red_partial[rr] = sum_c; A.red_partial[res_rows + rr] = sum_s; }     // two slabs: summed with the others'
+            }
+        }
+        if (want_gpsi) {
+            const float sum_p = row_sums8(part_p, lane);
+            if (writer) A.ph.gpsi[rr] = sum_p;
+        }
+    }
+}
+
+// The result rows of the blocks that the kernel above does not own (blocks with more than a few injected rows: the other
+// downsweeps wrote both halves of their rows to out_p): the same merge, one wavefront per block, row by row.
+__global__ void __launch_bounds__(kStreamWaves * 64)
+k_phase_merge_blocks(const ScanArgs A)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int64_t blk = (int64_t)blockIdx.x * kStreamWaves + wave;
+    if (blk >= A.blocks) return;
+    const int flags = (int)A.blk_flags[blk];
+    if (!(flags & kFlagRes) || !(flags & kFlagInj) || (flags & kFlagFewInj)) return;
+    const int64_t j = blk * 64 + lane;
+    const uint32_t idv = j < A.N ? A.ids[j] : 0xFFFFFFFFu;
+    uint64_t m = __ballot(idv >= A.res_lo && idv < A.res_hi);
+    const int64_t half = A.ph.half;
+    while (m) {
+        const int row = __ffsll((long long)m) - 1;
+        m &= m - 1;
+        const int64_t r = (int64_t)(lane_u(idv, row) - A.res_lo);
+        float s, c;
+        sincosf(A.ph.psi[r], &s, &c);
+        const float* in = A.out_p + r * A.ld_p;
+        float acc = 0.0f;
+        for (int64_t t = lane; t < half; t += 64) {
+            const float u = in[t], v = in[half + t];
+            if (A.ph.gx) A.ph.gx[r * A.ph.ldgx + t] = c * u + s * v;
+            if (A.ph.gpsi && A.ph.x) acc += A.ph.x[r * A.ph.ldx + t] * (c * v - s * u);
+        }
+        if (A.ph.gpsi && A.ph.x) {
+#pragma unroll
+            for (int k = 32; k >= 1; k >>= 1) acc += __shfl_xor(acc, k);
+            if (lane == 0) A.ph.gpsi[r] = acc;
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Batch 1, everything in sorted order (the routes through partition passes): the injected values
 // arrive as a plain array over the sorted rows (zero where nothing is injected) and the weights of
@@ -2233,7 +2456,14 @@ void launch_all(const ScanArgs& A, const ScanGeom& g, const std::string& tag, bo
     }
     if (VEC == 4 && g.sub_shift) {
         const dim3 sgrid((unsigned)((g.blocks + kStreamWaves - 1) / kStreamWaves), (unsigned)g.slabs);
-        LAPLEX_TIMED(fp.c_str(), st, hipLaunchKernelGGL((k_scan_down_sparse_wide<STRICT>), sgrid, dim3(kStreamWaves * 64), 0, st, A));
+        if (A.ph.half) {     // phased backward: one wavefront merges both halves of its block's rows; the other blocks' rows after it
+            const dim3 pgrid(sgrid.x);
+            LAPLEX_TIMED(fp.c_str(), st, hipLaunchKernelGGL((k_scan_down_sparse_wide_phased<STRICT>), pgrid, dim3(kStreamWaves * 64), 0, st, A));
+            const std::string fm = "phase_merge_blocks." + tag;
+            LAPLEX_TIMED(fm.c_str(), st, hipLaunchKernelGGL(k_phase_merge_blocks, pgrid, dim3(kStreamWaves * 64), 0, st, A));
+        } else {
+            LAPLEX_TIMED(fp.c_str(), st, hipLaunchKernelGGL((k_scan_down_sparse_wide<STRICT>), sgrid, dim3(kStreamWaves * 64), 0, st, A));
+        }
     } else {
         LAPLEX_TIMED(fp.c_str(), st, hipLaunchKernelGGL((k_scan_down_sparse<VEC, STRICT>), grid, bblock, 0, st, A));
     }
@@ -2262,6 +2492,12 @@ hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStrea
     A.inj_sorted = p.inj_sorted ? 1 : 0; A.out_sorted = p.out_sorted ? 1 : 0;
     if (p.emit) A.emit = *p.emit;
     A.emit_first = p.emit_first ? 1 : 0;
+    A.ph = PhaseFuse{};
+    if (p.phase) {
+        // one wavefront must span a whole half-row: wide geometry, at most 256 columns per half, two slabs at most
+        if (!v4 || !g.sub_shift || !p.out_p || p.phase->half * 2 != p.batch || p.phase->half > 256 || g.slabs > 2) return hipErrorInvalidValue;
+        A.ph = *p.phase;
+    }
     A.batch = p.batch; A.bpad = L.bpad;
     {
         const bool z_pair = p.out_z && !p.out_red && p.out_z == p.out_p + 1 && p.ld_z == 2;

@@ -559,6 +559,69 @@ def test_phased_subsets_and_empty_sides(oracle):
     assert np.all(y == 0) and all(np.all(t == 0) for t in grads)
 
 
+def clustered_outputs(r, k, n):
+    """Inputs spread out, outputs bunched into a few narrow clusters: some 64-row blocks of the merged order hold many
+    outputs (the downsweeps with a scan inside the block own them), most hold none or a handful."""
+    span = (k + n) / 128.0
+    b = r.uniform(0, span, n)
+    centres = r.uniform(0, span, 6)
+    a = centres[r.integers(0, 6, k)] + r.normal(size=k) * 0.02
+    a[: k // 3] = r.uniform(0, span, k // 3)
+    return a.astype(np.float32), b.astype(np.float32)
+
+
+@pytest.mark.parametrize("kind", ["uniform", "ties", "clustered_outputs"])
+@pytest.mark.parametrize("k,n,batch", [(3000, 20000, 128), (1500, 30000, 192), (40, 30000, 256), (6000, 9000, 68)])
+def test_phased_backward_merges_in_the_downsweep(oracle, kind, k, n, batch):
+    """Wide batches on the large path: the streaming downsweep of the backward forms gx, gpsi and gb from both halves in
+    registers; blocks with many outputs go through the doubled result matrix and are merged afterwards."""
+    r = np.random.default_rng(6100 + k + n + batch)
+    a, b = clustered_outputs(r, k, n) if kind == "clustered_outputs" else anchors(kind, r, k, n)
+    phi = r.uniform(-7, 7, k).astype(np.float32); psi = r.uniform(-7, 7, n).astype(np.float32)
+    x = r.normal(size=(n, batch)).astype(np.float32); g = r.normal(size=(k, batch)).astype(np.float32)
+    ref, tol = oracle.phased_apply_scan(a, phi, b, psi, x)
+    want, tols = oracle.phased_backward_scan(a, phi, b, psi, x, g)
+    y, grads, ws = gpu_phased(a, phi, b, psi, x, g)
+    assert_close("y", y, ref, tol)
+    names = ("gx", "ga", "gb", "gphi", "gpsi")
+    for name, got, rv, tv in zip(names, grads, want, tols):
+        assert_close(name, got, rv, tv)
+    _, alone, _ = gpu_phased(a, phi, b, psi, x, g, flags_bwd=0, forward=False)
+    for name, u, v in zip(names, grads, alone):
+        assert np.array_equal(u, v), name
+    # subsets of the gradients (gx needs no x; gpsi alone; gb alone)
+    for pick in ((True, False, False, False, False), (False, False, False, False, True), (False, False, True, False, False),
+                 (True, False, True, False, False)):
+        _, part, _ = gpu_phased(a, phi, b, psi, x, g, flags_bwd=0, want=pick, forward=False)
+        for name, got, rv, tv, w in zip(names, part, want, tols, pick):
+            if w:
+                assert_close(name, got, rv, tv)
+    # rows that do not allow 16-byte accesses take the route through the doubled result matrix: same results within the bar
+    da, dphi, db, dpsi, dg = dev(a), dev(phi), dev(b), dev(psi), dev(g)
+    xp = torch.zeros(n, batch + 1, device="cuda"); xp[:, :batch] = dev(x)
+    outs = [torch.full(s_, float("nan"), device="cuda") for s_ in ((n, batch), (k,), (n,), (k,), (n,))]
+    B.laplex_phased_apply_backward(da, dphi, db, dpsi, xp, dg, *outs, ws, 0)
+    torch.cuda.synchronize()
+    for name, got, rv, tv in zip(names, outs, want, tols):
+        assert_close(name, got.cpu().numpy(), rv, tv)
+
+
+def test_phased_backward_invalid_plan_poisons():
+    r = np.random.default_rng(6200)
+    k, n, batch = 2000, 24000, 128
+    a, b = clustered_outputs(r, k, n)
+    phi = r.uniform(-7, 7, k).astype(np.float32); psi = r.uniform(-7, 7, n).astype(np.float32)
+    x = r.normal(size=(n, batch)).astype(np.float32); g = r.normal(size=(k, batch)).astype(np.float32)
+    y, grads, ws = gpu_phased(a, phi, b, psi, x, g)
+    assert all(np.isfinite(t).all() for t in grads)
+    B.laplex_diag_set_plan_status(ws, k + n, 1)
+    # (the forward runs again on the marked plan: ga and gphi are formed from what it saves)
+    y, grads, _ = gpu_phased(a, phi, b, psi, x, g, ws=ws, flags_fwd=B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
+    assert np.isnan(y).all()
+    for name, t in zip(("gx", "ga", "gb", "gphi", "gpsi"), grads):
+        assert np.isnan(t).all(), f"{name}: a value computed from an invalid plan is not NaN"
+
+
 # ------------------------------------------------------------------ temperature
 
 @pytest.mark.parametrize("tau", [0.37, 1.0, 5.0])
