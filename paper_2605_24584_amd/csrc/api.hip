@@ -382,7 +382,8 @@ static int apply_check(const float* a, int64_t k, const float* b, int64_t n,
 
 static int apply_impl(const float* a, int64_t k, const float* b, int64_t n,
                  const float* x, int64_t ldx, int64_t batch, float* y, int64_t ldy,
-                 void* ws, size_t ws_bytes, uint32_t flags, float tau, laplex_stream_t stream)
+                 void* ws, size_t ws_bytes, uint32_t flags, float tau, laplex_stream_t stream,
+                 const PhaseIn* pin = nullptr)
 {
     LAPLEX_CHECK(apply_check(a, k, b, n, x, ldx, batch, y, ldy, flags));
     if (k == 0 || batch == 0) return LAPLEX_OK;
@@ -416,6 +417,7 @@ static int apply_impl(const float* a, int64_t k, const float* b, int64_t n,
     p.out_z = (flags & LAPLEX_SAVE_SCANS) ? P.z : nullptr;
     p.stage = (flags & LAPLEX_SAVE_SCANS) ? P.xs : P.stage;   // kept for the backward's weights when saving
     p.tag = "fwd";
+    p.phase_in = pin;             // phased: x is modulated on the way into the reduce (see phase_fusable)
     if (use_permute(L)) {          // x into sorted order, the scans there, y (and the saved scans) home
         LAPLEX_CHECK(rows_to_sorted(L, w, x, ldx, k, n, p.stage, "fwd", st));
         const bool save = p.out_z != nullptr;
@@ -434,7 +436,7 @@ static int apply_backward_impl(const float* a, int64_t k, const float* b, int64_
                           const float* x, int64_t ldx, const float* gy, int64_t ldgy, int64_t batch,
                           float* gx, int64_t ldgx, float* ga, float* gb,
                           void* ws, size_t ws_bytes, uint32_t flags, float tau, float* gtau, laplex_stream_t stream,
-                          const PhaseFuse* fuse = nullptr)
+                          const PhaseFuse* fuse = nullptr, const PhaseIn* pin_fwd = nullptr, const PhaseIn* pin_bwd = nullptr)
 {
     const uint32_t known = LAPLEX_A_SORTED | LAPLEX_B_SORTED | LAPLEX_REUSE_PLAN | LAPLEX_SAVE_SCANS;
     if (flags & ~known) return LAPLEX_ERR_FLAGS;
@@ -498,6 +500,7 @@ static int apply_backward_impl(const float* a, int64_t k, const float* b, int64_
             p.out_z = P.z;
             p.stage = P.xs;
             p.tag = "rescan";
+            p.phase_in = pin_fwd;
             if (routed) {
                 LAPLEX_CHECK(rows_to_sorted(L, w, x, ldx, k, n, P.xs, "rescan", st));
                 p.out_z = nullptr;
@@ -534,6 +537,7 @@ static int apply_backward_impl(const float* a, int64_t k, const float* b, int64_
         p.wstage = (gb && have_xs) ? P.xs : nullptr;
         p.tag = "bwd";
         p.phase = fuse;           // phased backward: the streaming downsweep merges the two halves (see phase_fusable)
+        p.phase_in = pin_bwd;     // ... and the other downsweeps' blocks get their doubled weight rows
         LAPLEX_HIP(launch_scan(p, L, w, st));
         if (paired) LAPLEX_HIP(launch_unpair(pairs, n, gx, ldgx, gb, st));
     }
@@ -807,8 +811,13 @@ int laplex_phased_apply(const float* a, const float* phi, int64_t k, const float
     char* w = static_cast<char*>(ws);
     float* x2 = reinterpret_cast<float*>(w + P.off_x2);
     float* y2 = reinterpret_cast<float*>(w + P.off_y2);
-    LAPLEX_HIP(launch_phase_split(x, ldx, psi, n, batch, x2, st));
-    LAPLEX_CHECK(laplex_apply(a, k, b, n, x2, 2 * batch, 2 * batch, y2, 2 * batch, ws, P.inner, flags, stream));
+    // With a wide batch the reduce reads x itself and modulates it on the way in; only the rows of blocks that hold outputs
+    // are written in doubled form (the other kernels read those).  Otherwise: one pass that writes both halves of x.
+    const bool fus_in = phase_fusable(k, n, batch, x, ldx, nullptr, 0);
+    const PhaseIn pin{psi, x, ldx, x2, batch, 1, true};
+    if (!fus_in) LAPLEX_HIP(launch_phase_split(x, ldx, psi, n, batch, x2, st));
+    LAPLEX_CHECK(apply_impl(a, k, b, n, x2, 2 * batch, 2 * batch, y2, 2 * batch, ws, P.inner, flags, 1.0f, stream,
+                            fus_in ? &pin : nullptr));
     LAPLEX_HIP(launch_phase_merge(y2, phi, k, batch, y, ldy, nullptr, 0, nullptr, st));
     return LAPLEX_OK;
 }
@@ -851,23 +860,30 @@ int laplex_phased_apply_backward(const float* a, const float* phi, int64_t k, co
     float* y2 = reinterpret_cast<float*>(w + P.off_y2);
     float* g2 = reinterpret_cast<float*>(w + P.off_g2);
     float* gx2 = reinterpret_cast<float*>(w + P.off_gx2);
-    const bool saved = (flags & LAPLEX_SAVE_SCANS) != 0;      // the forward left x's halves, its product and its scans
-    if (x && !saved) LAPLEX_HIP(launch_phase_split(x, ldx, psi, n, batch, x2, st));
+    const bool saved = (flags & LAPLEX_SAVE_SCANS) != 0;      // the forward left x's halves (see below), its product and its scans
+    const bool want_gx2 = gx || gpsi;
+    // With a wide batch (phase_fusable) nothing reads the doubled copy of x as a whole: the reduce of a forward problem
+    // modulates x on the way in (fus_in), and the streaming downsweep of the backward problem forms gx and gpsi itself and
+    // takes gb's weights from x (fused); the doubled rows and the doubled result matrix exist only for the blocks the other
+    // downsweeps own.  One consumer is left that needs all of it: the row reduction for gb when neither gx nor gpsi is asked for.
+    const bool fus_in = x != nullptr && phase_fusable(k, n, batch, x, ldx, nullptr, 0);
+    const bool fused = want_gx2 && phase_fusable(k, n, batch, x, ldx, gx, ldgx);
+    const bool full_split = x != nullptr && (fus_in ? (gb != nullptr && !fused) : !saved);
+    if (full_split) LAPLEX_HIP(launch_phase_split(x, ldx, psi, n, batch, x2, st));
     LAPLEX_HIP(launch_phase_split(gy, ldgy, phi, k, batch, g2, st));
+    const PhaseIn pin_fwd{psi, x, ldx, x2, batch, 1, true};
+    const PhaseIn pin_bwd{psi, x, ldx, x2, batch, 2, false};
     uint32_t inner = flags;
     if (gphi && !saved) {       // the phase gradient of the outputs needs the two halves of the product
-        LAPLEX_CHECK(laplex_apply(a, k, b, n, x2, 2 * batch, 2 * batch, y2, 2 * batch, ws, P.inner,
-                                  flags | LAPLEX_SAVE_SCANS, stream));
+        LAPLEX_CHECK(apply_impl(a, k, b, n, x2, 2 * batch, 2 * batch, y2, 2 * batch, ws, P.inner,
+                                flags | LAPLEX_SAVE_SCANS, 1.0f, stream, fus_in ? &pin_fwd : nullptr));
         inner = flags | LAPLEX_SAVE_SCANS | LAPLEX_REUSE_PLAN;
     }
-    const bool want_gx2 = gx || gpsi;
-    // With a wide batch the streaming downsweep forms gx and gpsi itself (and takes gb's weights from x): the doubled
-    // result matrix is then written only for the blocks the other downsweeps own, and merged there.
-    const bool fused = want_gx2 && phase_fusable(k, n, batch, x, ldx, gx, ldgx);
     const PhaseFuse fuse{psi, (gb || gpsi) ? x : nullptr, ldx, gx, ldgx, gpsi, batch};
     LAPLEX_CHECK(apply_backward_impl(a, k, b, n, x ? x2 : nullptr, 2 * batch, g2, 2 * batch, 2 * batch,
                                      want_gx2 ? gx2 : nullptr, 2 * batch, ga, gb, ws, P.inner, inner, 1.0f, nullptr, stream,
-                                     fused ? &fuse : nullptr));
+                                     fused ? &fuse : nullptr, fus_in ? &pin_fwd : nullptr,
+                                     (fused && gb && x && !full_split) ? &pin_bwd : nullptr));
     if (want_gx2 && !fused) LAPLEX_HIP(launch_phase_merge(gx2, psi, n, batch, gx, ldgx, x, ldx, gpsi, st));
     if (gphi) LAPLEX_HIP(launch_phase_merge(y2, phi, k, batch, nullptr, 0, gy, ldgy, gphi, st));
     return LAPLEX_OK;

@@ -355,6 +355,23 @@ struct PhaseFuse {
     int64_t half;                   // columns of one half; 0: off
 };
 
+// Phased kernel, input side: the injected matrix of the scan problem is [x cos psi | x sin psi] (2 * half columns) without
+// being stored.  The reduce of the wide geometry reads x itself, one wavefront across both halves of a row, and forms the two
+// products (rounded, as a split pass would store them) on the way in.  The downsweeps that read injected rows, or the weights
+// of a row reduction, only do so in blocks that also hold rows of the other side; for those blocks the doubled rows are
+// written to `x2` by a pass over the block flags after the spine:
+//   split_blocks = 1: the rows of x in blocks that hold result rows (x is the injected matrix: forward, re-scan);
+//   split_blocks = 2: the rows of x in blocks with more than a few injected rows (x holds the weights of the row
+//                     reduction, the streaming downsweep of PhaseFuse takes them from x: backward).
+struct PhaseIn {
+    const float* psi;               // [rows of x] phases
+    const float* x; int64_t ldx;    // [rows of x][half]
+    float* x2;                      // [rows of x][2 * half] contiguous: written for the blocks named above
+    int64_t half;                   // columns of one half; 0: off
+    int split_blocks;               // 0: none
+    bool virtual_inj;               // the reduce reads x with the modulation instead of the injected matrix
+};
+
 struct ScanProblem {
     const uint32_t* ids; const float* dh; const float* pk; int64_t N;
     const float2* pk8 = nullptr;     // (pk[8m], pk[8m + 1]) per 8 rows, or null (batch 1 in sorted order only)
@@ -376,6 +393,7 @@ struct ScanProblem {
     // emit_strict that the second output is wanted (the strict scans Z, or w * Z when wstage is given)
     const PartEmit* emit = nullptr; int emit_values = 1; bool emit_first = true, emit_strict = false;
     const PhaseFuse* phase = nullptr;      // wide geometry, at most 256 columns per half (see PhaseFuse)
+    const PhaseIn* phase_in = nullptr;     // the same geometry (see PhaseIn)
 };
 hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStream_t st);
 

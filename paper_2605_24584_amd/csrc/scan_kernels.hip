@@ -84,6 +84,7 @@ struct ScanArgs {
     PartEmit emit;                // batch 1, sorted order: the results leave as records of a partition level (k_seq_down)
     int emit_first;               // one value per record: the first output of a row (F + R - v), else its second
     PhaseFuse ph;                 // ph.half != 0: the phased backward's streaming downsweep merges the two halves itself
+    PhaseIn pin;                  // pin.half != 0: the injected matrix (or the weights) is x modulated by its rows' phases
 };
 
 constexpr int kFlagInj = 1, kFlagRes = 2;
@@ -650,21 +651,26 @@ struct WideMeta {
 };
 
 constexpr int kWideWaves = 1 << kWideSubShift;     // one wavefront per block of the tile
+constexpr int kStreamWaves = 4;                    // wavefronts (blocks) per workgroup of the kernels with one wavefront per block
 static_assert(kWideWaves <= kScanWaves, "the LDS exchange has room for kScanWaves summaries");
 
-template <bool STRICT>
+// HALVES = 2 (phased kernel, PhaseIn): the injected matrix is [x cos psi | x sin psi]; a lane owns four columns of both
+// halves, x is read once, and the two products are formed (and rounded) on the way in.  One slab then: blockIdx.y = 0.
+template <bool STRICT, int HALVES>
 __global__ void __launch_bounds__(kWideWaves * 64)
 k_scan_reduce_wide(const ScanArgs A)
 {
     constexpr int VEC = 4, ROWS = 64, CH = 8;
     static_assert(kScanWaves * kItemsVec4 == ROWS, "the wide geometry (one row-lane per wavefront) has 64 rows per block");
-    __shared__ WaveSegs<VEC> W;
+    __shared__ WaveSegs<VEC> W[HALVES];
     __shared__ int tile_flags, blk_flag[kWideWaves];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int64_t col0 = ((int64_t)blockIdx.y * 64 + lane) * VEC;
-    const bool col_ok = col0 < A.batch;
-    const float* const base = A.inj + (col_ok ? col0 : 0);     // lanes past the last column read (and drop) columns 0..3
+    const int64_t half = HALVES == 2 ? A.pin.half : 0;
+    const int64_t col0 = ((int64_t)(HALVES == 2 ? 0 : blockIdx.y) * 64 + lane) * VEC;
+    const bool col_ok = col0 < (HALVES == 2 ? half : A.batch);
+    const int64_t ld_in = HALVES == 2 ? A.pin.ldx : A.ld_inj;
+    const float* const base = (HALVES == 2 ? A.pin.x : A.inj) + (col_ok ? col0 : 0);     // lanes past the last column read (and drop) columns 0..3
 
     if (A.reduce_from_list && blockIdx.x >= A.counters[0]) return;
     const int64_t tile = A.reduce_from_list ? (int64_t)A.list_inj[blockIdx.x] : (int64_t)blockIdx.x;
@@ -673,9 +679,12 @@ k_scan_reduce_wide(const ScanArgs A)
     if (threadIdx.x == 0) tile_flags = 0;
     __syncthreads();
 
-    float Sf[VEC], Qf[VEC], Sb[VEC], Qb[VEC];
+    float Sf[HALVES][VEC], Qf[HALVES][VEC], Sb[HALVES][VEC], Qb[HALVES][VEC];
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) { Sf[e] = Qf[e] = Sb[e] = Qb[e] = 0.0f; }
+    for (int h = 0; h < HALVES; ++h) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) { Sf[h][e] = Qf[h][e] = Sb[h][e] = Qb[h][e] = 0.0f; }
+    }
     float blk_df = 1.0f, blk_db = 1.0f;
     int Hf = 0, Hb = 0, flags = 0;
     if (blk_live) {
@@ -695,6 +704,9 @@ k_scan_reduce_wide(const ScanArgs A)
         const int cut_b = hb_mask ? __ffsll((long long)hb_mask) - 1 : 63;      // rows i > cut_b count
         // the strict sums as weighted sums of their own: the same weights, zero outside their rows
         const float wqf = lane < cut_f ? wf : 0.0f, wqb = lane > cut_b ? wb : 0.0f;
+        // phased: lane l holds the cosine and sine of the phase of row l
+        float cph = 1.0f, sph = 0.0f;
+        if (HALVES == 2 && inj) sincosf(A.pin.psi[idv - A.inj_lo], &sph, &cph);
 
         if (inj_mask) {
             // Straight-line code inside a group of eight rows: no branch around a load (a row that is not
@@ -706,7 +718,7 @@ k_scan_reduce_wide(const ScanArgs A)
                     const int row = c0 + i;
                     const uint32_t id = lane_u(idv, row);
                     const int64_t r = ((inj_mask >> row) & 1ull) ? (int64_t)(id - A.inj_lo) : 0;
-                    dst[i] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(base + r * A.ld_inj));
+                    dst[i] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(base + r * ld_in));
                 }
             };
             auto fold = [&](int c0, const v4f* src) {
@@ -715,15 +727,26 @@ k_scan_reduce_wide(const ScanArgs A)
                     const int row = c0 + i;
                     const uint32_t keep = ((inj_mask >> row) & 1ull) ? 0xFFFFFFFFu : 0u;     // scalar
                     const float f = lane_f(wf, row), b = lane_f(wb, row);
-                    float x[VEC];
+                    float x[HALVES][VEC];
 #pragma unroll
-                    for (int e = 0; e < VEC; ++e) x[e] = __uint_as_float(__float_as_uint(src[i][e]) & keep);
+                    for (int e = 0; e < VEC; ++e) x[0][e] = __uint_as_float(__float_as_uint(src[i][e]) & keep);
+                    if (HALVES == 2) {
+                        const float cr = lane_f(cph, row), sr = lane_f(sph, row);
 #pragma unroll
-                    for (int e = 0; e < VEC; ++e) { Sf[e] += f * x[e]; Sb[e] += b * x[e]; }
+                        for (int e = 0; e < VEC; ++e) { const float v = x[0][e]; x[0][e] = v * cr; x[HALVES - 1][e] = v * sr; }
+                    }
+#pragma unroll
+                    for (int h = 0; h < HALVES; ++h) {
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) { Sf[h][e] += f * x[h][e]; Sb[h][e] += b * x[h][e]; }
+                    }
                     if (STRICT) {
                         const float qf = lane_f(wqf, row), qb = lane_f(wqb, row);
 #pragma unroll
-                        for (int e = 0; e < VEC; ++e) { Qf[e] += qf * x[e]; Qb[e] += qb * x[e]; }
+                        for (int h = 0; h < HALVES; ++h) {
+#pragma unroll
+                            for (int e = 0; e < VEC; ++e) { Qf[h][e] += qf * x[h][e]; Qb[h][e] += qb * x[h][e]; }
+                        }
                     }
                 }
             };
@@ -743,59 +766,107 @@ k_scan_reduce_wide(const ScanArgs A)
     // The eight block summaries meet in LDS: each wavefront folds the ones before (after) its own into
     // the state its block starts from when the tile starts from zero; the last (first) one also takes
     // the tile's summary.
-    Seg<VEC, STRICT> mf = seg_identity<VEC, STRICT>(), mb = seg_identity<VEC, STRICT>();
+    Seg<VEC, STRICT> mf[HALVES], mb[HALVES];
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) { mf.S[e] = Sf[e]; mb.S[e] = Sb[e]; if (STRICT) { mf.Q[e] = Qf[e]; mb.Q[e] = Qb[e]; } }
-    mf.D = mf.C = blk_df; mb.D = mb.C = blk_db;
-    if (STRICT) { mf.H = Hf; mb.H = Hb; }
-    put_wave_seg<VEC, STRICT>(W, 0, wave, lane, mf);
-    put_wave_seg<VEC, STRICT>(W, 1, wave, lane, mb);
+    for (int h = 0; h < HALVES; ++h) {
+        mf[h] = seg_identity<VEC, STRICT>(); mb[h] = seg_identity<VEC, STRICT>();
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) { mf[h].S[e] = Sf[h][e]; mb[h].S[e] = Sb[h][e]; if (STRICT) { mf[h].Q[e] = Qf[h][e]; mb[h].Q[e] = Qb[h][e]; } }
+        mf[h].D = mf[h].C = blk_df; mb[h].D = mb[h].C = blk_db;
+        if (STRICT) { mf[h].H = Hf; mb[h].H = Hb; }
+        put_wave_seg<VEC, STRICT>(W[h], 0, wave, lane, mf[h]);
+        put_wave_seg<VEC, STRICT>(W[h], 1, wave, lane, mb[h]);
+    }
     __syncthreads();
     const int tflags = tile_flags;
     if (wave == 0 && lane < kWideWaves && blockIdx.y == 0 && (tile << kWideSubShift) + lane < A.blocks)
         A.blk_flags[(tile << kWideSubShift) + lane] = (uint32_t)blk_flag[lane];
 
-    float F[VEC], E[VEC], R[VEC], G[VEC];
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) { F[e] = E[e] = R[e] = G[e] = 0.0f; }
     const bool want_local = blk_live && (flags & kFlagRes) && (tflags & kFlagInj);     // uniform per wavefront
-    if (want_local || wave == kWideWaves - 1) {
-#pragma unroll 1
-        for (int w = 0; w < wave; ++w) seg_apply<VEC, STRICT>(get_wave_seg<VEC, STRICT>(W, 0, w, lane), F, E);
-    }
-    if (want_local || wave == 0) {
-#pragma unroll 1
-        for (int w = kWideWaves - 1; w > wave; --w) seg_apply<VEC, STRICT>(get_wave_seg<VEC, STRICT>(W, 1, w, lane), R, G);
-    }
-    if (want_local && col_ok) {
-        const int64_t o0 = blk * A.bpad + col0, o1 = (A.blocks + blk) * A.bpad + col0;
-        store_vec<VEC>(A.blk_f + o0, F);
-        store_vec<VEC>(A.blk_f + o1, R);
-        if (STRICT) { store_vec<VEC>(A.blk_e + o0, E); store_vec<VEC>(A.blk_e + o1, G); }
-    }
     const int64_t tile_base = tile * A.spine_rows;
     const bool sw = lane == 0 && blockIdx.y == 0;
-    if (wave == kWideWaves - 1) {           // the tile's forward summary = the state after the last block, from zero
-        int Ht = 0;
-        if (STRICT) { for (int w = 0; w < kWideWaves; ++w) Ht |= W.H[0][w]; }
-        seg_apply<VEC, STRICT>(mf, F, E);
-        Seg<VEC, STRICT> tf = seg_identity<VEC, STRICT>();
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) { tf.S[e] = F[e]; if (STRICT) tf.Q[e] = E[e]; }
-        tf.D = tf.C = span_decay_f(A, tile_base, A.spine_rows);     // from the anchors
-        if (STRICT) tf.H = Ht;
-        store_level_seg<VEC, STRICT>(A.l1, 0, tile, A.bpad, col0, col_ok && (tflags & kFlagInj), sw, tf, (float)tflags);
+    for (int h = 0; h < HALVES; ++h) {
+        const int64_t colh = col0 + h * half;
+        float F[VEC], E[VEC], R[VEC], G[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) { F[e] = E[e] = R[e] = G[e] = 0.0f; }
+        if (want_local || wave == kWideWaves - 1) {
+#pragma unroll 1
+            for (int w = 0; w < wave; ++w) seg_apply<VEC, STRICT>(get_wave_seg<VEC, STRICT>(W[h], 0, w, lane), F, E);
+        }
+        if (want_local || wave == 0) {
+#pragma unroll 1
+            for (int w = kWideWaves - 1; w > wave; --w) seg_apply<VEC, STRICT>(get_wave_seg<VEC, STRICT>(W[h], 1, w, lane), R, G);
+        }
+        if (want_local && col_ok) {
+            const int64_t o0 = blk * A.bpad + colh, o1 = (A.blocks + blk) * A.bpad + colh;
+            store_vec<VEC>(A.blk_f + o0, F);
+            store_vec<VEC>(A.blk_f + o1, R);
+            if (STRICT) { store_vec<VEC>(A.blk_e + o0, E); store_vec<VEC>(A.blk_e + o1, G); }
+        }
+        if (wave == kWideWaves - 1) {           // the tile's forward summary = the state after the last block, from zero
+            int Ht = 0;
+            if (STRICT) { for (int w = 0; w < kWideWaves; ++w) Ht |= W[h].H[0][w]; }
+            seg_apply<VEC, STRICT>(mf[h], F, E);
+            Seg<VEC, STRICT> tf = seg_identity<VEC, STRICT>();
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) { tf.S[e] = F[e]; if (STRICT) tf.Q[e] = E[e]; }
+            tf.D = tf.C = span_decay_f(A, tile_base, A.spine_rows);     // from the anchors
+            if (STRICT) tf.H = Ht;
+            store_level_seg<VEC, STRICT>(A.l1, 0, tile, A.bpad, colh, col_ok && (tflags & kFlagInj), sw && h == 0, tf, (float)tflags);
+        }
+        if (wave == 0) {
+            int Ht = 0;
+            if (STRICT) { for (int w = 0; w < kWideWaves; ++w) Ht |= W[h].H[1][w]; }
+            seg_apply<VEC, STRICT>(mb[h], R, G);
+            Seg<VEC, STRICT> tb = seg_identity<VEC, STRICT>();
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) { tb.S[e] = R[e]; if (STRICT) tb.Q[e] = G[e]; }
+            tb.D = tb.C = span_decay_b(A, tile_base, A.spine_rows);
+            if (STRICT) tb.H = Ht;
+            store_level_seg<VEC, STRICT>(A.l1, 1, tile, A.bpad, colh, col_ok && (tflags & kFlagInj), sw && h == 0, tb, (float)tflags);
+        }
     }
-    if (wave == 0) {
-        int Ht = 0;
-        if (STRICT) { for (int w = 0; w < kWideWaves; ++w) Ht |= W.H[1][w]; }
-        seg_apply<VEC, STRICT>(mb, R, G);
-        Seg<VEC, STRICT> tb = seg_identity<VEC, STRICT>();
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) { tb.S[e] = R[e]; if (STRICT) tb.Q[e] = G[e]; }
-        tb.D = tb.C = span_decay_b(A, tile_base, A.spine_rows);
-        if (STRICT) tb.H = Ht;
-        store_level_seg<VEC, STRICT>(A.l1, 1, tile, A.bpad, col0, col_ok && (tflags & kFlagInj), sw, tb, (float)tflags);
+}
+
+// Phased kernel, PhaseIn::split_blocks: the doubled rows [x cos psi | x sin psi] of the blocks whose rows the downsweeps
+// will read (mode 1: blocks that hold result rows, x injected; mode 2: blocks with more than a few injected rows, x the
+// weights of the result rows), one wavefront per block, row by row; the same products as k_phase_split.
+__global__ void __launch_bounds__(kStreamWaves * 64)
+k_phase_split_blocks(const ScanArgs A)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int64_t blk = (int64_t)blockIdx.x * kStreamWaves + wave;
+    if (blk >= A.blocks) return;
+    const int flags = (int)A.blk_flags[blk];
+    const int mode = A.pin.split_blocks;
+    uint32_t lo, hi;          // ids of the rows of x
+    if (mode == 1) {
+        if (!(flags & kFlagRes) || !(flags & kFlagInj)) return;
+        lo = A.inj_lo; hi = A.inj_hi;
+    } else {
+        if (!(flags & kFlagRes) || !(flags & kFlagInj) || (flags & kFlagFewInj)) return;
+        lo = A.res_lo; hi = A.res_hi;
+    }
+    const int64_t j = blk * 64 + lane;
+    const uint32_t idv = j < A.N ? A.ids[j] : 0xFFFFFFFFu;
+    uint64_t m = __ballot(idv >= lo && idv < hi);
+    const int64_t half = A.pin.half;
+    while (m) {
+        const int row = __ffsll((long long)m) - 1;
+        m &= m - 1;
+        const int64_t r = (int64_t)(lane_u(idv, row) - lo);
+        float s, c;
+        sincosf(A.pin.psi[r], &s, &c);
+        const float* in = A.pin.x + r * A.pin.ldx;
+        float* out = A.pin.x2 + r * 2 * half;
+        for (int64_t t = lane; t < half; t += 64) {
+            const float v = in[t];
+            out[t] = v * c;
+            out[half + t] = v * s;
+        }
     }
 }
 
@@ -1551,7 +1622,6 @@ k_scan_down_fewres(const ScanArgs A)
 // the scalar unit with readlane; the few rows injected inside the block add their direct terms.
 // The batch reduction of eight rows at a time is a butterfly: 10 cross-lane steps for 8 row sums.
 // ---------------------------------------------------------------------------
-constexpr int kStreamWaves = 4;
 
 template <bool STRICT>
 __global__ void __launch_bounds__(kStreamWaves * 64)
@@ -2423,7 +2493,10 @@ void launch_all(const ScanArgs& A, const ScanGeom& g, const std::string& tag, bo
         return;
     }
     if (VEC == 4 && g.sub_shift) {    // wide geometry: a workgroup per tile, a wavefront per block
-        LAPLEX_TIMED(fr.c_str(), st, hipLaunchKernelGGL((k_scan_reduce_wide<STRICT>), rgrid, dim3(kWideWaves * 64), 0, st, A));
+        if (A.pin.half && A.pin.virtual_inj)      // phased: x read once for both halves
+            LAPLEX_TIMED(fr.c_str(), st, hipLaunchKernelGGL((k_scan_reduce_wide<STRICT, 2>), dim3(rgrid.x), dim3(kWideWaves * 64), 0, st, A));
+        else
+            LAPLEX_TIMED(fr.c_str(), st, hipLaunchKernelGGL((k_scan_reduce_wide<STRICT, 1>), rgrid, dim3(kWideWaves * 64), 0, st, A));
     } else if (!A.stage) {            // one wavefront per tile
         const dim3 lgrid((rgrid.x + kLoneWaves - 1) / kLoneWaves, rgrid.y);
         LAPLEX_TIMED(fr.c_str(), st, hipLaunchKernelGGL((k_scan_reduce_wave<VEC, STRICT>), lgrid, dim3(kLoneWaves * 64), 0, st, A));
@@ -2435,6 +2508,11 @@ void launch_all(const ScanArgs& A, const ScanGeom& g, const std::string& tag, bo
         LAPLEX_TIMED(fs.c_str(), st, hipLaunchKernelGGL((k_spine_top<STRICT>), tgrid, dim3(kSpineThreads), 0, st, A.l2, A.bpad));
     }
     LAPLEX_TIMED(fs.c_str(), st, hipLaunchKernelGGL((k_spine_down<VEC, STRICT>), cgrid, block, 0, st, A));
+    if (VEC == 4 && g.sub_shift && A.pin.half && A.pin.split_blocks) {     // phased: the doubled rows the downsweeps will read
+        const std::string fx = "phase_split_blocks." + tag;
+        LAPLEX_TIMED(fx.c_str(), st, hipLaunchKernelGGL(k_phase_split_blocks, dim3((unsigned)((g.blocks + kStreamWaves - 1) / kStreamWaves)),
+                                                        dim3(kStreamWaves * 64), 0, st, A));
+    }
     if (VEC == 4 && A.few_res_ok) {
         const std::string ff = "scan_down_fewres." + tag;
         const dim3 fgrid((dgrid.x + kFewWaves - 1) / kFewWaves, dgrid.y);
@@ -2497,6 +2575,11 @@ hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStrea
         // one wavefront must span a whole half-row: wide geometry, at most 256 columns per half, two slabs at most
         if (!v4 || !g.sub_shift || !p.out_p || p.phase->half * 2 != p.batch || p.phase->half > 256 || g.slabs > 2) return hipErrorInvalidValue;
         A.ph = *p.phase;
+    }
+    A.pin = PhaseIn{};
+    if (p.phase_in) {
+        if (!v4 || !g.sub_shift || p.phase_in->half * 2 != p.batch || p.phase_in->half > 256 || g.slabs > 2) return hipErrorInvalidValue;
+        A.pin = *p.phase_in;
     }
     A.batch = p.batch; A.bpad = L.bpad;
     {
