@@ -832,13 +832,14 @@ k_scan_reduce_wide(const ScanArgs A)
 
 // Phased kernel, PhaseIn::split_blocks: the doubled rows [x cos psi | x sin psi] of the blocks whose rows the downsweeps
 // will read (mode 1: blocks that hold result rows, x injected; mode 2: blocks with more than a few injected rows, x the
-// weights of the result rows), one wavefront per block, row by row; the same products as k_phase_split.
+// weights of the result rows), one wavefront per eight rows of a block, row by row; the same products as k_phase_split.
 __global__ void __launch_bounds__(kStreamWaves * 64)
 k_phase_split_blocks(const ScanArgs A)
 {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int64_t blk = (int64_t)blockIdx.x * kStreamWaves + wave;
+    const int64_t part = (int64_t)blockIdx.x * kStreamWaves + wave;       // eight rows of a block per wavefront
+    const int64_t blk = part >> 3;
     if (blk >= A.blocks) return;
     const int flags = (int)A.blk_flags[blk];
     const int mode = A.pin.split_blocks;
@@ -852,7 +853,7 @@ k_phase_split_blocks(const ScanArgs A)
     }
     const int64_t j = blk * 64 + lane;
     const uint32_t idv = j < A.N ? A.ids[j] : 0xFFFFFFFFu;
-    uint64_t m = __ballot(idv >= lo && idv < hi);
+    uint64_t m = __ballot(idv >= lo && idv < hi) & (0xFFull << (8 * (int)(part & 7)));
     const int64_t half = A.pin.half;
     while (m) {
         const int row = __ffsll((long long)m) - 1;
@@ -1950,19 +1951,20 @@ k_scan_down_sparse_wide_phased(const ScanArgs A)
 }
 
 // The result rows of the blocks that the kernel above does not own (blocks with more than a few injected rows: the other
-// downsweeps wrote both halves of their rows to out_p): the same merge, one wavefront per block, row by row.
+// downsweeps wrote both halves of their rows to out_p): the same merge, one wavefront per eight rows of a block, row by row.
 __global__ void __launch_bounds__(kStreamWaves * 64)
 k_phase_merge_blocks(const ScanArgs A)
 {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int64_t blk = (int64_t)blockIdx.x * kStreamWaves + wave;
+    const int64_t part = (int64_t)blockIdx.x * kStreamWaves + wave;       // eight rows of a block per wavefront
+    const int64_t blk = part >> 3;
     if (blk >= A.blocks) return;
     const int flags = (int)A.blk_flags[blk];
     if (!(flags & kFlagRes) || !(flags & kFlagInj) || (flags & kFlagFewInj)) return;
     const int64_t j = blk * 64 + lane;
     const uint32_t idv = j < A.N ? A.ids[j] : 0xFFFFFFFFu;
-    uint64_t m = __ballot(idv >= A.res_lo && idv < A.res_hi);
+    uint64_t m = __ballot(idv >= A.res_lo && idv < A.res_hi) & (0xFFull << (8 * (int)(part & 7)));
     const int64_t half = A.ph.half;
     while (m) {
         const int row = __ffsll((long long)m) - 1;
@@ -2510,7 +2512,7 @@ void launch_all(const ScanArgs& A, const ScanGeom& g, const std::string& tag, bo
     LAPLEX_TIMED(fs.c_str(), st, hipLaunchKernelGGL((k_spine_down<VEC, STRICT>), cgrid, block, 0, st, A));
     if (VEC == 4 && g.sub_shift && A.pin.half && A.pin.split_blocks) {     // phased: the doubled rows the downsweeps will read
         const std::string fx = "phase_split_blocks." + tag;
-        LAPLEX_TIMED(fx.c_str(), st, hipLaunchKernelGGL(k_phase_split_blocks, dim3((unsigned)((g.blocks + kStreamWaves - 1) / kStreamWaves)),
+        LAPLEX_TIMED(fx.c_str(), st, hipLaunchKernelGGL(k_phase_split_blocks, dim3((unsigned)((8 * g.blocks + kStreamWaves - 1) / kStreamWaves)),
                                                         dim3(kStreamWaves * 64), 0, st, A));
     }
     if (VEC == 4 && A.few_res_ok) {
@@ -2538,7 +2540,8 @@ void launch_all(const ScanArgs& A, const ScanGeom& g, const std::string& tag, bo
             const dim3 pgrid(sgrid.x);
             LAPLEX_TIMED(fp.c_str(), st, hipLaunchKernelGGL((k_scan_down_sparse_wide_phased<STRICT>), pgrid, dim3(kStreamWaves * 64), 0, st, A));
             const std::string fm = "phase_merge_blocks." + tag;
-            LAPLEX_TIMED(fm.c_str(), st, hipLaunchKernelGGL(k_phase_merge_blocks, pgrid, dim3(kStreamWaves * 64), 0, st, A));
+            LAPLEX_TIMED(fm.c_str(), st, hipLaunchKernelGGL(k_phase_merge_blocks, dim3((unsigned)((8 * g.blocks + kStreamWaves - 1) / kStreamWaves)),
+                                                            dim3(kStreamWaves * 64), 0, st, A));
         } else {
             LAPLEX_TIMED(fp.c_str(), st, hipLaunchKernelGGL((k_scan_down_sparse_wide<STRICT>), sgrid, dim3(kStreamWaves * 64), 0, st, A));
         }
