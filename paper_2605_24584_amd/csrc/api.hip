@@ -587,6 +587,12 @@ static int gram_impl(const float* a, int64_t n, const float* x, int64_t ldx, int
     if (paired) { p.out_p = pairs; p.ld_p = 2; p.out_z = pairs + 1; p.ld_z = 2; }
     p.stage = (flags & LAPLEX_SAVE_SCANS) ? P.xs : P.stage;
     p.tag = "fwd";
+    if (use_permute(L)) {          // batch 1, many rows: x into sorted order, the scans there, y (and the saved scans) home
+        const bool save = (flags & LAPLEX_SAVE_SCANS) != 0;
+        LAPLEX_CHECK(rows_to_sorted(L, w, x, ldx, 0, n, p.stage, "fwd", st));
+        p.out_p = nullptr; p.out_z = nullptr; p.ld_p = 0; p.ld_z = 0;
+        return scan_and_send_home(p, L, w, true, save, y, ldy, save ? P.z : nullptr, 1, st);
+    }
     LAPLEX_HIP(launch_scan(p, L, w, st));
     if (paired) LAPLEX_HIP(launch_unpair(pairs, n, y, ldy, P.z, st));
     return LAPLEX_OK;
@@ -643,6 +649,7 @@ static int gram_backward_impl(const float* a, int64_t n, const float* x, int64_t
         return LAPLEX_OK;
     }
     LAPLEX_CHECK(build_plan(a, n, nullptr, 0, tau, L, w, flags, (flags & LAPLEX_A_SORTED) != 0, st));
+    const bool routed = use_permute(L);        // batch 1, many rows: no random accesses (see rows_to_sorted)
     if (ga && !(flags & LAPLEX_SAVE_SCANS)) {
         ScanProblem p = problem(P, L);
         p.inj = x; p.ld_inj = ldx; p.inj_lo = 0; p.inj_hi = (uint32_t)n;
@@ -650,9 +657,28 @@ static int gram_backward_impl(const float* a, int64_t n, const float* x, int64_t
         p.out_z = P.z;
         p.stage = P.xs;
         p.tag = "rescan";
-        LAPLEX_HIP(launch_scan(p, L, w, st));
+        if (routed) {
+            LAPLEX_CHECK(rows_to_sorted(L, w, x, ldx, 0, n, P.xs, "rescan", st));
+            p.out_z = nullptr;
+            LAPLEX_CHECK(scan_and_send_home(p, L, w, false, true, P.z, 1, nullptr, 1, st));
+        } else {
+            LAPLEX_HIP(launch_scan(p, L, w, st));
+        }
     }
-    if (gx || ga) {
+    if (routed && (gx || ga)) {
+        // gx and x * Z^g leave the downsweep together (the second as the row's second output, into ga); the saved scans of x
+        // are in the caller's order already, so  ga = x Z^g + gy Z^x  is completed by one pointwise pass
+        LAPLEX_CHECK(rows_to_sorted(L, w, gy, ldgy, 0, n, P.stage, "bwd", st));
+        ScanProblem p = problem(P, L);
+        p.inj = gy; p.ld_inj = ldgy; p.inj_lo = 0; p.inj_hi = (uint32_t)n;
+        p.res_lo = 0; p.res_hi = (uint32_t)n;
+        p.stage = P.stage;
+        if (ga) { p.w = x; p.ld_w = ldx; p.wstage = P.xs; }     // (sorted-order x: kept by the forward or just written by the re-scan)
+        p.tag = "bwd";
+        if (gx) LAPLEX_CHECK(scan_and_send_home(p, L, w, true, ga != nullptr, gx, ldgx, ga, 1, st));
+        else LAPLEX_CHECK(scan_and_send_home(p, L, w, false, true, ga, 1, nullptr, 1, st));
+        if (ga) LAPLEX_HIP(launch_add_rowdot(gy, ldgy, P.z, batch, n, batch, ga, st));
+    } else if (gx || ga) {
         ScanProblem p = problem(P, L);
         p.inj = gy; p.ld_inj = ldgy; p.inj_lo = 0; p.inj_hi = (uint32_t)n;
         p.res_lo = 0; p.res_hi = (uint32_t)n;

@@ -469,6 +469,9 @@ hipError_t launch_wgram_f64(const uint32_t* ids, const float* pk, const float* a
 
 // out[r] = sum_t u[r*ldu+t] * v[r*ldv+t]
 // out[r] = sum_t (u1 v1 + u2 v2)[r, t]
+// out[r] += sum_t u[r, t] * v[r, t]
+hipError_t launch_add_rowdot(const float* u, int64_t ldu, const float* v, int64_t ldv, int64_t rows, int64_t batch, float* out,
+                             hipStream_t st);
 hipError_t launch_rowdot2(const float* u1, int64_t ldu1, const float* v1, int64_t ldv1,
                           const float* u2, int64_t ldu2, const float* v2, int64_t ldv2,
                           int64_t rows, int64_t batch, float* out, hipStream_t st);

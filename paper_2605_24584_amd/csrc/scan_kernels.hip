@@ -2433,6 +2433,19 @@ k_rowdot_narrow(const float* __restrict__ u, int64_t ldu, int64_t op_u, const fl
     }
 }
 
+// out[r] += sum_t u[r, t] * v[r, t]: one thread per row (narrow batches)
+__global__ void __launch_bounds__(256)
+k_add_rowdot(const float* __restrict__ u, int64_t ldu, const float* __restrict__ v, int64_t ldv, int64_t rows, int64_t batch,
+             float* __restrict__ out)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < rows; r += stride) {
+        float s = 0.0f;
+        for (int64_t t = 0; t < batch; ++t) s += u[r * ldu + t] * v[r * ldv + t];
+        out[r] += s;
+    }
+}
+
 // out[r] = sum_t (u1[r, t] * v1[r, t] + u2[r, t] * v2[r, t]): one wavefront per row, fixed summation order
 __global__ void __launch_bounds__(256)
 k_rowdot2(const float* __restrict__ u1, int64_t ldu1, const float* __restrict__ v1, int64_t ldv1,
@@ -2648,6 +2661,15 @@ hipError_t launch_rowdot_ops(const float* u, int64_t ldu, int64_t op_u, const fl
     int64_t gsz = (rows + 3) / 4; if (gsz > 65536) gsz = 65536;
     LAPLEX_TIMED("rowdot", st, hipLaunchKernelGGL(k_rowdot, dim3((unsigned)gsz, (unsigned)operators), dim3(256), 0, st,
                                                   u, ldu, op_u, v, ldv, op_v, rows, batch, out, op_out));
+    return hipGetLastError();
+}
+
+hipError_t launch_add_rowdot(const float* u, int64_t ldu, const float* v, int64_t ldv, int64_t rows, int64_t batch, float* out,
+                             hipStream_t st)
+{
+    if (rows <= 0) return hipSuccess;
+    int64_t g = (rows + 255) / 256; if (g > 65536) g = 65536;
+    LAPLEX_TIMED("rowdot", st, hipLaunchKernelGGL(k_add_rowdot, dim3((unsigned)g), dim3(256), 0, st, u, ldu, v, ldv, rows, batch, out));
     return hipGetLastError();
 }
 

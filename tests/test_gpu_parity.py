@@ -1074,6 +1074,43 @@ def test_routes_gradient_subsets_and_merge_path(oracle, routed, want):
             if want[2]: assert_close("gb", got[3], rgb, tgb)
 
 
+@pytest.mark.parametrize("kind", ["uniform", "ties", "clustered"])
+@pytest.mark.parametrize("n", [8193, 20000, 70001, 300000])
+def test_routes_gram_form(oracle, routed, kind, n):
+    """The square form at batch 1 on the same routes: every row is injected and read; ga = gy Z^x + x Z^g is completed
+    from the saved scans in the caller's order."""
+    r = np.random.default_rng(9100 + n)
+    a, _ = anchors(kind, r, n, 1)
+    x = r.normal(size=(n, 1)).astype(np.float32); g = r.normal(size=(n, 1)).astype(np.float32)
+    small = n * n <= 4e7
+    ref, tol = (oracle.gram_brute if small else oracle.gram_scan)(a, x)
+    (rgx, rga), (tgx, tga) = (oracle.gram_backward_brute if small else oracle.gram_backward_scan)(a, x, g)
+    y, ws = gpu_gram(a, x, flags=B.LAPLEX_SAVE_SCANS)
+    assert_close("y", y, ref, tol)
+    assert np.array_equal(gpu_perm(ws, n), oracle.merged_permutation(a))
+    gx, ga = gpu_gram_backward(a, x, g, flags=B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN, ws=ws)
+    assert_close("gx", gx, rgx, tgx); assert_close("ga", ga, rga, tga)
+    gx2, ga2 = gpu_gram_backward(a, x, g)                       # standing alone: scans x itself
+    assert np.array_equal(gx, gx2) and np.array_equal(ga, ga2)
+    _, ga3 = gpu_gram_backward(a, x, g, want=(False, True))
+    assert np.array_equal(ga, ga3)
+    gx4, _ = gpu_gram_backward(a, x, g, want=(True, False))
+    assert np.array_equal(gx, gx4)
+    # the other route: the same within rounding
+    B.laplex_diag_set_route_min(1 << 40)
+    y0, ws0 = gpu_gram(a, x, flags=B.LAPLEX_SAVE_SCANS)
+    gx0, ga0 = gpu_gram_backward(a, x, g, flags=B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN, ws=ws0)
+    B.laplex_diag_set_route_min(0)
+    for name, u, v, tl in (("y", y, y0, tol), ("gx", gx, gx0, tgx), ("ga", ga, ga0, tga)):
+        tl = np.asarray(tl).reshape(u.shape)
+        assert np.all(np.abs(u.astype(np.float64) - v) <= 2e-6 * tl + 1e-7), f"{name}: the routes disagree"
+    # an invalid plan poisons every result of this route too
+    B.laplex_diag_set_plan_status(ws, n, 1)
+    y5, _ = gpu_gram(a, x, flags=B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN, ws=ws)
+    gx5, ga5 = gpu_gram_backward(a, x, g, flags=B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN, ws=ws)
+    assert np.isnan(y5).all() and np.isnan(gx5).all() and np.isnan(ga5).all()
+
+
 def test_routes_invalid_plan_poisons(routed):
     r = np.random.default_rng(5)
     k, n = 20000, 30000
