@@ -307,13 +307,13 @@ def family_bytes(fam, spec, np, B):
     if fam == "sort_hist":
         return 4 * N, "the anchors read once"
     if fam == "decay":
-        if batch == 1 and N >= (1 << 26) and not gram:
+        if batch == 1 and N >= (1 << 22):
             return 13 * N, "keys read, decays and sorted anchors written, every eighth anchor pair once more"
         return 12 * N, "keys read, decays and sorted anchors written"
     base, _, tag = fam.partition(".")
-    # batch 1 from 2^26 merged positions on: values travel between the caller's order and the sorted order as records
+    # batch 1 from 2^22 merged positions on: values travel between the caller's order and the sorted order as records
     # (destination, value[, value]) through partition levels, and the scans work on plain arrays in sorted order
-    routed = batch == 1 and N >= (1 << 26) and not gram
+    routed = batch == 1 and N >= (1 << 22)
     if routed and base == "permute_part":
         if tag == "rank":
             return 12 * N + 16 * N, "level 1: ids read, (id, position) pairs written; level 2: pairs read and written"

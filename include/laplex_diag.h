@@ -73,7 +73,7 @@ int laplex_diag_set_plan_status(void* ws, size_t ws_bytes, int64_t count, uint32
 /*
  * Test hook (host, process-wide): batch-1 problems with at least this many merged positions k + n (and more
  * than 8192) move x, gy and the results between the caller's order and the sorted order through partition
- * passes instead of random accesses (default 2^26: below, the tables fit the device's caches).  Lets tests
+ * passes instead of random accesses (default 2^22: below, the tables fit the device's caches and the random accesses are as fast).  Lets tests
  * run that route on small problems.  A plan must be reused under the setting it was built with.
  */
 int laplex_diag_set_route_min(int64_t merged_positions);

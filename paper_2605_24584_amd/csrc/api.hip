@@ -133,7 +133,7 @@ Plan plan_of(const Layout& L, char* ws)
 // partition passes (permute_kernels.hip) instead of by one random access per value.  Below g_permute_min merged
 // positions the tables fit the device's caches and the random accesses are as fast.
 // ----------------------------------------------------------------------------
-std::atomic<int64_t> g_permute_min{int64_t(1) << 26};
+std::atomic<int64_t> g_permute_min{int64_t(1) << 22};
 
 bool use_permute(const Layout& L) { return L.permute && L.N >= g_permute_min.load(std::memory_order_relaxed); }
 

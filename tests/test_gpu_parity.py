@@ -998,7 +998,7 @@ def routed():
     """Batch-1 problems of any size (beyond the small path) take the partition routes while the test runs."""
     B.laplex_diag_set_route_min(0)
     yield
-    B.laplex_diag_set_route_min(1 << 26)
+    B.laplex_diag_set_route_min(1 << 22)
 
 
 def _apply_both_ways(a, b, x, g, save, want=(True, True, True), merge=False):
