@@ -175,6 +175,12 @@ def other_workload(args, torch, np, B, synth):
         step()
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    # an invalid plan (a sort tile that gave up its wait) turns every result into NaN: none may be here
+    results = locals()
+    for name in ("y", "gx", "ga", "gb", "gw", "gphi", "gpsi", "m"):
+        t = results.get(name)
+        if t is not None:
+            assert bool(torch.isfinite(t.reshape(-1)[:65536]).all()), f"{name} holds non-finite values (invalid plan?)"
     print(json.dumps({
         "metric": "LAPLEX fwd+bwd (n+k)*batch elements/s", "value": elements / (ms * 1e-3), "unit": "elements/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
