@@ -130,3 +130,106 @@ def test_flags_strides_and_subsets_random(oracle, seed):
         torch.cuda.synchronize()
         ref2, tol2 = (oracle.apply_brute if k * n * b2 <= 4e7 else oracle.apply_scan)(a, b, x2)
         T.assert_close("y, plan reused at another batch size", y2.cpu().numpy(), ref2, tol2)
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_batch_one_routes_random(oracle, seed):
+    """Batch 1 on the routes through partition passes (switched on for every size beyond the small path while the test
+    runs): random shapes from 2^13 to 2^18.5 merged positions, sorted-anchor flags, leading dimensions, gradient subsets,
+    saved scans or a re-scan, a fresh or a reused plan; the square form on the same routes."""
+    B, torch = T.B, T.torch
+    r = np.random.default_rng(9400 + seed)
+    kind = T.KINDS[r.integers(len(T.KINDS))]
+    total = int(2 ** r.uniform(13.05, 18.5))
+    k = int(r.integers(1, total)); n = max(1, total - k)
+    if r.integers(4) == 0:
+        k = int(r.integers(1, 50)); n = total - k
+    a, b = T.anchors(kind, r, k, n)
+    flags = 0
+    if r.integers(3) == 0:
+        a.sort(); b.sort(); flags |= B.LAPLEX_A_SORTED | B.LAPLEX_B_SORTED
+    if r.integers(2):
+        flags |= B.LAPLEX_SAVE_SCANS
+    ldx, ldy, ldg, ldgx = (1 + int(r.choice([0, 0, 1, 3])) for _ in range(4))
+    x = r.normal(size=(n, 1)).astype(np.float32); g = r.normal(size=(k, 1)).astype(np.float32)
+    small = k * n <= 4e7
+    B.laplex_diag_set_route_min(0)
+    try:
+        ws = T.workspace(k, n, 1)
+        da, db = T.dev(a), T.dev(b)
+        _, dx = padded(x, ldx); _, dg = padded(g, ldg)
+        ybuf = torch.full((k, ldy), float("nan"), device="cuda"); y = ybuf[:, :1]
+        B.laplex_apply(da, db, dx, y, ws, flags)
+        torch.cuda.synchronize()
+        ref, tol = (oracle.apply_brute if small else oracle.apply_scan)(a, b, x)
+        T.assert_close("y", y.cpu().numpy(), ref, tol)
+        assert ldy == 1 or bool(torch.isnan(ybuf[:, 1:]).all())
+        assert np.array_equal(T.gpu_perm(ws, k + n), oracle.merged_permutation(a, b))
+        want = [bool(r.integers(4)) for _ in range(3)]
+        if not any(want):
+            want[0] = True
+        gxbuf = torch.full((n, ldgx), float("nan"), device="cuda") if want[0] else None
+        gx = gxbuf[:, :1] if want[0] else None
+        ga = torch.full((k,), float("nan"), device="cuda") if want[1] else None
+        gb = torch.full((n,), float("nan"), device="cuda") if want[2] else None
+        bflags = flags | (B.LAPLEX_REUSE_PLAN if r.integers(2) else 0)
+        if not bflags & B.LAPLEX_REUSE_PLAN:
+            bflags &= ~B.LAPLEX_SAVE_SCANS          # a fresh plan has no saved scans
+        B.laplex_apply_backward(da, db, dx, dg, gx, ga, gb, ws, bflags)
+        torch.cuda.synchronize()
+        (rgx, rga, rgb), (tgx, tga, tgb) = (oracle.apply_backward_brute if small else oracle.apply_backward_scan)(a, b, x, g)
+        if want[0]:
+            T.assert_close("gx", gx.cpu().numpy(), rgx, tgx)
+            assert ldgx == 1 or bool(torch.isnan(gxbuf[:, 1:]).all())
+        if want[1]:
+            T.assert_close("ga", ga.cpu().numpy(), rga, tga)
+        if want[2]:
+            T.assert_close("gb", gb.cpu().numpy(), rgb, tgb)
+        # the square form on the anchors of the larger side
+        m = min(max(k, n), 120000)
+        if m > 8192:
+            body(T.test_routes_gram_form)(oracle, None, kind, m)
+    finally:
+        B.laplex_diag_set_route_min(1 << 22)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_phased_wide_batches_random(oracle, seed):
+    """The phased kernel with the modulation inside the wide kernels: batches of 68 to 256 columns, shapes from 2^13.1 to
+    2^15.3 merged positions, outputs spread out or bunched (blocks with many outputs take the other downsweeps and the
+    block-wise split and merge), gradient subsets, and leading dimensions that do or do not allow 16-byte rows."""
+    B, torch = T.B, T.torch
+    r = np.random.default_rng(9500 + seed)
+    batch = 4 * int(r.integers(17, 65))
+    total = int(2 ** r.uniform(13.1, 15.3))
+    k = int(r.integers(1, total // 2)); n = total - k
+    if r.integers(3) == 0:
+        k = int(r.integers(1, 40)); n = total - k
+    kind = str(r.choice(["uniform", "ties", "clustered_outputs", "clustered"]))
+    a, b = T.clustered_outputs(r, k, n) if kind == "clustered_outputs" else T.anchors(kind, r, k, n)
+    phi = r.uniform(-7, 7, k).astype(np.float32); psi = r.uniform(-7, 7, n).astype(np.float32)
+    x = r.normal(size=(n, batch)).astype(np.float32); g = r.normal(size=(k, batch)).astype(np.float32)
+    ref, tol = oracle.phased_apply_scan(a, phi, b, psi, x)
+    refs, tols = oracle.phased_backward_scan(a, phi, b, psi, x, g)
+    ldx = batch + int(r.choice([0, 0, 4, 8, 1])); ldgx = batch + int(r.choice([0, 0, 4, 3]))
+    ws = T.phased_workspace(k, n, batch)
+    da, dphi, db, dpsi = T.dev(a), T.dev(phi), T.dev(b), T.dev(psi)
+    _, dx = padded(x, ldx); dg = T.dev(g)
+    y = torch.full((k, batch), float("nan"), device="cuda")
+    save = bool(r.integers(2))
+    B.laplex_phased_apply(da, dphi, db, dpsi, dx, y, ws, B.LAPLEX_SAVE_SCANS if save else 0)
+    torch.cuda.synchronize()
+    T.assert_close("y", y.cpu().numpy(), ref, tol)
+    want = [bool(r.integers(3)) for _ in range(5)]
+    if not any(want):
+        want[0] = True
+    gxbuf = torch.full((n, ldgx), float("nan"), device="cuda") if want[0] else None
+    outs = [gxbuf[:, :batch] if want[0] else None] + [torch.full((m,), float("nan"), device="cuda") if w else None
+                                                      for m, w in zip((k, n, k, n), want[1:])]
+    bflags = (B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN) if save and r.integers(2) else 0
+    B.laplex_phased_apply_backward(da, dphi, db, dpsi, dx, dg, *outs, ws, bflags)
+    torch.cuda.synchronize()
+    for name, got, rv, tv, w in zip(("gx", "ga", "gb", "gphi", "gpsi"), outs, refs, tols, want):
+        if w:
+            T.assert_close(name, got.cpu().numpy(), rv, tv)
+    assert not want[0] or ldgx == batch or bool(torch.isnan(gxbuf[:, batch:]).all())
