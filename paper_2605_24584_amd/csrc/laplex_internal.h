@@ -144,7 +144,7 @@ struct Layout {
     size_t off_xs = 0;       // f32[N][batch], narrow batches only: the forward's injected rows in sorted order
     size_t off_scratch = 0;
     // scratch, sort view
-    size_t off_keys0 = 0, off_keys1 = 0, off_ids1 = 0, off_status = 0, off_sort_small = 0;
+    size_t off_pair0 = 0, off_pair1 = 0, off_status = 0, off_sort_small = 0;   // two buffers of (key, id) pairs
     int64_t sort_tiles = 0, status_words = 0;
     // scratch, scan view (sized for the larger of the two lane geometries)
     size_t off_agg_scalar = 0;   // float4[2][tiles]            (D, C, H, -)
@@ -197,9 +197,8 @@ inline Layout make_layout(int64_t N, int64_t zrows, int64_t batch, bool permute_
     size_t s = o;
     L.sort_tiles = (N + sort_tile(N) - 1) / sort_tile(N);
     L.status_words = L.sort_tiles * kRadix;
-    L.off_keys0 = s;  s = align_up(s + sizeof(uint32_t) * (size_t)N);
-    L.off_keys1 = s;  s = align_up(s + sizeof(uint32_t) * (size_t)N);
-    L.off_ids1 = s;   s = align_up(s + sizeof(uint32_t) * (size_t)N);
+    L.off_pair0 = s;  s = align_up(s + 2 * sizeof(uint32_t) * (size_t)N);
+    L.off_pair1 = s;  s = align_up(s + 2 * sizeof(uint32_t) * (size_t)N);
     L.off_status = s;     s = align_up(s + sizeof(uint64_t) * 2 * (size_t)L.status_words);   // look-back words, two passes' worth
     L.off_sort_small = s; s = align_up(s + sizeof(uint32_t) * kSortSmallWords);            // global histogram, tickets, error, pass mask
 
@@ -272,10 +271,12 @@ void profile_after(const char* family, hipStream_t st);
 // ----------------------------------------------------------------------------
 
 // The anchors enter every plan scaled by the inverse temperature tau (1 = as they are).
-// Stable ascending sort of the anchors a ++ b by one-sweep LSD passes; keys and ids end in keys0/ids0.
+// Stable ascending sort of the anchors a ++ b by one-sweep LSD passes.  Between passes the (key, id) pairs travel
+// interleaved through the two pair buffers; the last pass that runs writes the sorted ids to `ids` (the plan's) and the
+// sorted keys alone to the front of the pair buffer it would have written (k_decay finds them from the pass mask).
 // small: u32[kSortSmallWords] (global histogram, tickets, error word, pass mask); status: u64[2][tiles*256] look-back words.
 hipError_t launch_onesweep_sort(const float* a, int64_t k, const float* b, int64_t n, float tau,
-                                uint32_t* keys0, uint32_t* ids0, uint32_t* keys1, uint32_t* ids1,
+                                uint2* pair0, uint2* pair1, uint32_t* ids,
                                 uint32_t* small, unsigned long long* status, hipStream_t st);
 
 // Both inputs ascending: merged keys/ids in one pass (ties: a first).
@@ -284,11 +285,10 @@ hipError_t launch_merge(const float* a, int64_t k, const float* b, int64_t n, fl
 
 // dh[j] = decay from sorted key j-1 to j (>= 0), or -1 if the two keys are equal;
 // dh[0] = dh[N] = 0 (nothing beyond either end).  pk[j+1] = sorted anchor j, pk[0] = -inf, pk[N+1] = +inf.
-// The sorted pairs are in (keys0, ids0), or, after an odd number of radix passes (ghist tells), in
-// (keys1, ids1); in that case the ids are also copied to ids0, where the plan keeps them.
-// ghist == nullptr: the pairs are in buffer 0 (merge path).  The last kernel of every plan build: it also clears
-// the scans' list counters (64 words).
-hipError_t launch_decay(const uint32_t* keys0, const uint32_t* keys1, uint32_t* ids0, const uint32_t* ids1,
+// The sorted keys are in keys0, or, after an odd number of radix passes (ghist tells), in keys1 (the fronts of the two
+// pair buffers); ghist == nullptr: keys0 (merge path).  The last kernel of every plan build: it also clears the scans'
+// list counters (64 words).
+hipError_t launch_decay(const uint32_t* keys0, const uint32_t* keys1,
                         const uint32_t* ghist, float* dh, float* pk, float2* pk8, uint32_t* counters, int64_t N, hipStream_t st);
 
 hipError_t launch_fill(float* p, int64_t rows, int64_t cols, int64_t ld, float v, hipStream_t st);
