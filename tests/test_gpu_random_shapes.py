@@ -207,6 +207,9 @@ def test_phased_wide_batches_random(oracle, seed):
         k = int(r.integers(1, 40)); n = total - k
     kind = str(r.choice(["uniform", "ties", "clustered_outputs", "clustered"]))
     a, b = T.clustered_outputs(r, k, n) if kind == "clustered_outputs" else T.anchors(kind, r, k, n)
+    sorted_flags = 0
+    if r.integers(3) == 0:          # both anchor sets ascending: the merge path
+        a = np.sort(a); b = np.sort(b); sorted_flags = B.LAPLEX_A_SORTED | B.LAPLEX_B_SORTED
     phi = r.uniform(-7, 7, k).astype(np.float32); psi = r.uniform(-7, 7, n).astype(np.float32)
     x = r.normal(size=(n, batch)).astype(np.float32); g = r.normal(size=(k, batch)).astype(np.float32)
     ref, tol = oracle.phased_apply_scan(a, phi, b, psi, x)
@@ -217,7 +220,7 @@ def test_phased_wide_batches_random(oracle, seed):
     _, dx = padded(x, ldx); dg = T.dev(g)
     y = torch.full((k, batch), float("nan"), device="cuda")
     save = bool(r.integers(2))
-    B.laplex_phased_apply(da, dphi, db, dpsi, dx, y, ws, B.LAPLEX_SAVE_SCANS if save else 0)
+    B.laplex_phased_apply(da, dphi, db, dpsi, dx, y, ws, sorted_flags | (B.LAPLEX_SAVE_SCANS if save else 0))
     torch.cuda.synchronize()
     T.assert_close("y", y.cpu().numpy(), ref, tol)
     want = [bool(r.integers(3)) for _ in range(5)]
@@ -226,7 +229,7 @@ def test_phased_wide_batches_random(oracle, seed):
     gxbuf = torch.full((n, ldgx), float("nan"), device="cuda") if want[0] else None
     outs = [gxbuf[:, :batch] if want[0] else None] + [torch.full((m,), float("nan"), device="cuda") if w else None
                                                       for m, w in zip((k, n, k, n), want[1:])]
-    bflags = (B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN) if save and r.integers(2) else 0
+    bflags = sorted_flags | ((B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN) if save and r.integers(2) else 0)
     B.laplex_phased_apply_backward(da, dphi, db, dpsi, dx, dg, *outs, ws, bflags)
     torch.cuda.synchronize()
     for name, got, rv, tv, w in zip(("gx", "ga", "gb", "gphi", "gpsi"), outs, refs, tols, want):
