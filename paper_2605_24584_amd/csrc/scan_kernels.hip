@@ -535,9 +535,6 @@ k_scan_reduce(const ScanArgs A)
 
     // decays over this row-lane's rows, this wavefront's rows and the whole tile, from the anchors
     // (not products of the rows' decays: see k_decay); asked for first so the loads go out early
-    const float lane_df = span_decay_f(A, row0, ITEMS), lane_db = span_decay_b(A, row0, ITEMS);
-    const float wave_df = rv == 1 ? lane_df : span_decay_f(A, wave_row0, rv * ITEMS);
-    const float wave_db = rv == 1 ? lane_db : span_decay_b(A, wave_row0, rv * ITEMS);
     const float tile_df = span_decay_f(A, tile * A.tile_rows, A.tile_rows);
     const float tile_db = span_decay_b(A, tile * A.tile_rows, A.tile_rows);
 
@@ -569,36 +566,71 @@ k_scan_reduce(const ScanArgs A)
             if (T.id[i] != 0xFFFFFFFFu) store_vec<VEC>(A.stage + (row0 + i) * A.batch + col0, v[i]);
     }
 
-    {
-        Seg<VEC, STRICT> f = seg_identity<VEC, STRICT>();
+    // The tile's summary as a weighted sum of the row-lanes' own (each from zero over its ITEMS rows): a row-lane's forward
+    // state reaches the tile's last row through ONE exponential of an anchor difference, its backward state the tile's first
+    // row likewise.  (Composing the row-lanes' summaries pairwise would multiply up to rv * waves decays of equal spans; on a
+    // regular grid those carry equal rounding errors, and every far term of every output passes through a tile summary.)
+    // Strict channel: the rows before the tile's last run head, seen from the left, are the row-lanes before the last one
+    // that holds a head, whole, plus that row-lane's own strict sum (rows after the last head have decay 1).
+    const int64_t tile_row0 = tile * A.tile_rows;
+    const float wf = span_decay_f(A, row0 + ITEMS, tile_row0 + A.tile_rows - (row0 + ITEMS));
+    const float wb = span_decay_b(A, tile_row0, row0 - tile_row0);
+    Seg<VEC, STRICT> f = seg_identity<VEC, STRICT>(), b = seg_identity<VEC, STRICT>();
 #pragma unroll
-        for (int i = 0; i < ITEMS; ++i) seg_push<VEC, STRICT>(f, head_f<VEC>(T, i), T.dh[i], v[i]);
-        f.D = lane_df;
-        f = wave_scan<true, VEC, STRICT>(f, lane, bv, rv);
-        if (r == rv - 1) {
-            f.D = wave_df;
-            put_wave_seg<VEC, STRICT>(W, 0, wave, c, f);
+    for (int i = 0; i < ITEMS; ++i) seg_push<VEC, STRICT>(f, head_f<VEC>(T, i), T.dh[i], v[i]);
+#pragma unroll
+    for (int i = ITEMS - 1; i >= 0; --i) seg_push<VEC, STRICT>(b, head_b<VEC>(T, i), T.dh[i + 1], v[i]);
+    {
+        const uint64_t hf = STRICT ? __ballot(f.H != 0) : 0ull, hb = STRICT ? __ballot(b.H != 0) : 0ull;
+        const int last_f = hf ? (63 - __clzll((long long)hf)) >> A.bv_log2 : -1;        // last row-lane with a head, from the left
+        const int first_b = hb ? (__ffsll((long long)hb) - 1) >> A.bv_log2 : rv;        // first one, i.e. the last seen from the right
+        float sf[VEC], qf[VEC], sb[VEC], qb[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            sf[e] = wf * f.S[e]; sb[e] = wb * b.S[e];
+            qf[e] = r < last_f ? sf[e] : (r == last_f ? f.Q[e] : 0.0f);
+            qb[e] = r > first_b ? sb[e] : (r == first_b ? b.Q[e] : 0.0f);
         }
-    }
-    {
-        Seg<VEC, STRICT> b = seg_identity<VEC, STRICT>();
+        for (int m = bv; m < 64; m <<= 1) {
 #pragma unroll
-        for (int i = ITEMS - 1; i >= 0; --i) seg_push<VEC, STRICT>(b, head_b<VEC>(T, i), T.dh[i + 1], v[i]);
-        b.D = lane_db;
-        b = wave_scan<false, VEC, STRICT>(b, lane, bv, rv);
+            for (int e = 0; e < VEC; ++e) {
+                sf[e] += __shfl_xor(sf[e], m); sb[e] += __shfl_xor(sb[e], m);
+                if (STRICT) { qf[e] += __shfl_xor(qf[e], m); qb[e] += __shfl_xor(qb[e], m); }
+            }
+        }
         if (r == 0) {
-            b.D = wave_db;
-            put_wave_seg<VEC, STRICT>(W, 1, wave, c, b);
+            if (c == 0 && STRICT) { W.H[0][wave] = hf != 0; W.H[1][wave] = hb != 0; }
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                W.S[0][wave][c * VEC + e] = sf[e]; W.S[1][wave][c * VEC + e] = sb[e];
+                if (STRICT) { W.Q[0][wave][c * VEC + e] = qf[e]; W.Q[1][wave][c * VEC + e] = qb[e]; }
+            }
         }
     }
     __syncthreads();
 
     if (tid < bv) {   // wavefront 0, row-lane 0: one lane per column group
         Seg<VEC, STRICT> tf = seg_identity<VEC, STRICT>(), tb = seg_identity<VEC, STRICT>();
-#pragma unroll 1   // sequential on purpose: unrolling would hold every wavefront's summary in registers at once
-        for (int w = 0; w < A.waves; ++w) tf = seg_compose<VEC, STRICT>(tf, get_wave_seg<VEC, STRICT>(W, 0, w, c));
 #pragma unroll 1
-        for (int w = A.waves - 1; w >= 0; --w) tb = seg_compose<VEC, STRICT>(tb, get_wave_seg<VEC, STRICT>(W, 1, w, c));
+        for (int w = 0; w < A.waves; ++w) {
+            const bool h = STRICT && W.H[0][w] != 0;
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                if (h) tf.Q[e] = tf.S[e] + W.Q[0][w][c * VEC + e];      // everything before this wavefront, and its own share
+                tf.S[e] += W.S[0][w][c * VEC + e];
+            }
+            tf.H |= h ? 1 : 0;
+        }
+#pragma unroll 1
+        for (int w = A.waves - 1; w >= 0; --w) {
+            const bool h = STRICT && W.H[1][w] != 0;
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                if (h) tb.Q[e] = tb.S[e] + W.Q[1][w][c * VEC + e];
+                tb.S[e] += W.S[1][w][c * VEC + e];
+            }
+            tb.H |= h ? 1 : 0;
+        }
         tf.D = tf.C = tile_df;
         tb.D = tb.C = tile_db;
         const bool sw = c == 0 && blockIdx.y == 0;
@@ -1083,6 +1115,22 @@ k_spine_down(const ScanArgs A)
     const int64_t col0 = ((int64_t)blockIdx.y * bv + c) * VEC;
     const bool col_ok = col0 < A.batch;
 
+    // Decay and head flag over the tiles with scan indices [qa, qb) (clipped to the tiles there are), from the anchors:
+    // a composite summary never keeps the product of its parts' decays.  (Equal spans have equal decays with equal rounding
+    // errors -- on a regular grid every tile's is the same -- and a chain of m of them carries m times that error.)
+    const int64_t count = A.l1.count, SR = A.spine_rows;
+    auto span = [&](int64_t qa, int64_t qb, float& D, bool& H) {
+        qb = qb < count ? qb : count;
+        D = 1.0f; H = false;
+        if (qa >= qb) return;
+        if (dir == 0) {
+            D = span_decay_f(A, qa * SR, (qb - qa) * SR);
+            H = span_head_f(A, qa * SR, (qb - qa) * SR);
+        } else {                          // scan index q is tile count - 1 - q
+            D = span_decay_b(A, (count - qb) * SR, (qb - qa) * SR);
+            H = span_head_b(A, (count - qb) * SR, (qb - qa) * SR);
+        }
+    };
     Seg<VEC, STRICT> segs[kSpineItems];
     Seg<VEC, STRICT> m = seg_identity<VEC, STRICT>();
 #pragma unroll
@@ -1095,7 +1143,24 @@ k_spine_down(const ScanArgs A)
         }
         m = seg_compose<VEC, STRICT>(m, segs[i]);
     }
-    const Seg<VEC, STRICT> inc = wave_scan<true, VEC, STRICT>(m, lane, bv, rv);
+    {
+        float D; bool H;
+        span(q0, q0 + A.spine_items, D, H);
+        if (q0 < count) m.D = m.C = D;
+    }
+    // inclusive scan over the row-lanes of the wavefront; after every step a row-lane's summary covers the row-lanes
+    // [r - 2 step + 1, r], and its decay is taken over exactly those tiles
+    Seg<VEC, STRICT> inc = m;
+    for (int step = 1; step < rv; step <<= 1) {
+        const Seg<VEC, STRICT> o = seg_shfl<VEC, STRICT>(inc, (lane - step * bv) & 63);
+        if (r >= step) {
+            inc = seg_compose<VEC, STRICT>(o, inc);
+            const int r_lo = r - 2 * step + 1 > 0 ? r - 2 * step + 1 : 0;
+            float D; bool H;
+            span(q0 - (int64_t)(r - r_lo) * A.spine_items, q0 + A.spine_items, D, H);
+            inc.D = inc.C = D;
+        }
+    }
     if (r == rv - 1) put_wave_seg<VEC, STRICT>(W, 0, wave, c, inc);
     Seg<VEC, STRICT> exc = seg_shfl<VEC, STRICT>(inc, (lane - bv) & 63);
     if (r == 0) exc = seg_identity<VEC, STRICT>();
@@ -1114,28 +1179,32 @@ k_spine_down(const ScanArgs A)
     seg_apply<VEC, STRICT>(exc, F, E);
     // the chunk's carry reaches this row-lane's first tile through one exponential of an anchor difference
     if (q0 < A.l1.count) {
-        const int64_t before = q0 - chunk * A.chunk_tiles;               // tiles of the chunk ahead of q0 in scan order
-        if (dir == 0) {
-            const int64_t r0 = chunk * A.chunk_tiles * A.spine_rows;
-            enter_state<VEC, STRICT>(F, E, Fc, Ec, span_decay_f(A, r0, before * A.spine_rows),
-                                     span_head_f(A, r0, before * A.spine_rows));
-        } else {
-            const int64_t r0 = (A.l1.count - q0) * A.spine_rows;           // first row after this row-lane's first tile
-            enter_state<VEC, STRICT>(F, E, Fc, Ec, span_decay_b(A, r0, before * A.spine_rows),
-                                     span_head_b(A, r0, before * A.spine_rows));
-        }
+        float D; bool H;
+        span(chunk * A.chunk_tiles, q0, D, H);
+        enter_state<VEC, STRICT>(F, E, Fc, Ec, D, H);
     }
+    // ... and the state at the row-lane's first tile reaches each of its tiles the same way: what the tiles in between
+    // add (from zero) plus the entering state decayed over them by one exponential
+    float Fl[VEC], El[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) { Fl[e] = El[e] = 0.0f; }
 #pragma unroll
     for (int i = 0; i < kSpineItems; ++i) {
         const int64_t q = q0 + i;
         if (i < A.spine_items && q < A.l1.count) {
             const int64_t t = dir == 0 ? q : A.l1.count - 1 - q;
+            float Ft[VEC], Et[VEC];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) { Ft[e] = Fl[e]; Et[e] = El[e]; }
+            float D; bool H;
+            span(q0, q, D, H);
+            enter_state<VEC, STRICT>(Ft, Et, F, E, D, H);
             if (col_ok) {
                 const int64_t o = ((int64_t)dir * A.l1.count + t) * A.bpad + col0;
-                store_vec<VEC>(A.l1.car_f + o, F);
-                if (STRICT) store_vec<VEC>(A.l1.car_e + o, E);
+                store_vec<VEC>(A.l1.car_f + o, Ft);
+                if (STRICT) store_vec<VEC>(A.l1.car_e + o, Et);
             }
-            seg_apply<VEC, STRICT>(segs[i], F, E);
+            seg_apply<VEC, STRICT>(segs[i], Fl, El);
         }
     }
 }
