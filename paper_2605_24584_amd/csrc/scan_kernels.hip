@@ -2250,12 +2250,13 @@ k_seq_reduce(const ScanArgs A)
     const int64_t tile_base = tile * (kScanWaves * 64 * ITEMS);
     const int64_t wave_row0 = tile_base + (int64_t)wave * 64 * ITEMS;
     const int64_t row0 = wave_row0 + (int64_t)lane * ITEMS;
-    // decays over this row-lane's rows and over this wavefront's rows, from the anchors
+    // from this row-lane's last row to the tile's last, and from its first row back to the tile's first: one exponential of
+    // an anchor difference each (the tile's summary is the weighted sum of the row-lanes' own: see k_scan_reduce)
+    const int64_t tile_end = tile_base + (int64_t)kScanWaves * 64 * ITEMS;
     const float2 p_lane0 = seq_anchor(A, row0), p_lane1 = seq_anchor(A, row0 + ITEMS);
-    const float2 p_wave0 = seq_anchor(A, wave_row0), p_wave1 = seq_anchor(A, wave_row0 + 64 * ITEMS);
-    const SeqSpan lane_span = seq_span(A, row0, p_lane0, row0 + ITEMS, p_lane1);
-    const SeqSpan wave_span = seq_span(A, wave_row0, p_wave0, wave_row0 + 64 * ITEMS, p_wave1);
-    const float lane_df = lane_span.df, lane_db = lane_span.db, wave_df = wave_span.df, wave_db = wave_span.db;
+    const float2 p_tile0 = seq_anchor(A, tile_base), p_tile1 = seq_anchor(A, tile_end);
+    const float wf = seq_span(A, row0 + ITEMS, p_lane1, tile_end, p_tile1).df;
+    const float wb = seq_span(A, tile_base, p_tile0, row0, p_lane0).db;
     SeqRows<ITEMS> T;
     seq_meta<ITEMS>(A, row0, T);
     float v[ITEMS][1];
@@ -2265,29 +2266,45 @@ k_seq_reduce(const ScanArgs A)
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) v[i][0] = t[i];
     }
-    {
-        Seg<1, STRICT> f = seg_identity<1, STRICT>();
+    Seg<1, STRICT> f = seg_identity<1, STRICT>(), b = seg_identity<1, STRICT>();
 #pragma unroll
-        for (int i = 0; i < ITEMS; ++i) seg_push<1, STRICT>(f, T.alive(i) && T.dh[i] >= 0.0f, T.dh[i], v[i]);
-        f.D = lane_df;
-        f = wave_scan64<true, STRICT>(f, lane);
-        if (lane == 63) { f.D = wave_df; put_wave_seg<1, STRICT>(W, 0, wave, 0, f); }
-    }
-    {
-        Seg<1, STRICT> b = seg_identity<1, STRICT>();
+    for (int i = 0; i < ITEMS; ++i) seg_push<1, STRICT>(f, T.alive(i) && T.dh[i] >= 0.0f, T.dh[i], v[i]);
 #pragma unroll
-        for (int i = ITEMS - 1; i >= 0; --i) seg_push<1, STRICT>(b, T.alive(i) && T.dh[i + 1] >= 0.0f, T.dh[i + 1], v[i]);
-        b.D = lane_db;
-        b = wave_scan64<false, STRICT>(b, lane);
-        if (lane == 0) { b.D = wave_db; put_wave_seg<1, STRICT>(W, 1, wave, 0, b); }
+    for (int i = ITEMS - 1; i >= 0; --i) seg_push<1, STRICT>(b, T.alive(i) && T.dh[i + 1] >= 0.0f, T.dh[i + 1], v[i]);
+    {
+        const uint64_t hf = STRICT ? __ballot(f.H != 0) : 0ull, hb = STRICT ? __ballot(b.H != 0) : 0ull;
+        const int last_f = hf ? 63 - __clzll((long long)hf) : -1;          // last row-lane with a run head, from the left
+        const int first_b = hb ? __ffsll((long long)hb) - 1 : 64;          // first one: the last seen from the right
+        float sf = wf * f.S[0], sb = wb * b.S[0];
+        float qf = lane < last_f ? sf : (lane == last_f ? f.Q[0] : 0.0f);
+        float qb = lane > first_b ? sb : (lane == first_b ? b.Q[0] : 0.0f);
+#pragma unroll
+        for (int m = 1; m < 64; m <<= 1) {
+            sf += __shfl_xor(sf, m); sb += __shfl_xor(sb, m);
+            if (STRICT) { qf += __shfl_xor(qf, m); qb += __shfl_xor(qb, m); }
+        }
+        if (lane == 0) {
+            W.S[0][wave][0] = sf; W.S[1][wave][0] = sb;
+            if (STRICT) { W.Q[0][wave][0] = qf; W.Q[1][wave][0] = qb; W.H[0][wave] = hf != 0; W.H[1][wave] = hb != 0; }
+        }
     }
     __syncthreads();
     if (tid == 0) {
         Seg<1, STRICT> tf = seg_identity<1, STRICT>(), tb = seg_identity<1, STRICT>();
 #pragma unroll 1
-        for (int w = 0; w < kScanWaves; ++w) tf = seg_compose<1, STRICT>(tf, get_wave_seg<1, STRICT>(W, 0, w, 0));
+        for (int w = 0; w < kScanWaves; ++w) {
+            const bool h = STRICT && W.H[0][w] != 0;
+            if (h) tf.Q[0] = tf.S[0] + W.Q[0][w][0];       // everything before this wavefront, and its own share
+            tf.S[0] += W.S[0][w][0];
+            tf.H |= h ? 1 : 0;
+        }
 #pragma unroll 1
-        for (int w = kScanWaves - 1; w >= 0; --w) tb = seg_compose<1, STRICT>(tb, get_wave_seg<1, STRICT>(W, 1, w, 0));
+        for (int w = kScanWaves - 1; w >= 0; --w) {
+            const bool h = STRICT && W.H[1][w] != 0;
+            if (h) tb.Q[0] = tb.S[0] + W.Q[1][w][0];
+            tb.S[0] += W.S[1][w][0];
+            tb.H |= h ? 1 : 0;
+        }
         tf.D = tf.C = span_decay_f(A, tile_base, A.tile_rows);
         tb.D = tb.C = span_decay_b(A, tile_base, A.tile_rows);
         const float flags = (float)(kFlagInj | kFlagRes);
