@@ -466,6 +466,74 @@ def test_hip_graph_replays_match_eager(n):
             assert torch.equal(got, ref), f"replay {rep}: {name} differs from the eager result"
 
 
+def _replay_check(run, inputs, outputs, fresh, reps=4):
+    """capture `run` in a HIP graph; every replay on fresh inputs must give the eager bits"""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run()                                   # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        run()
+    for rep in range(reps):
+        for t, f in zip(inputs, fresh()):
+            t.copy_(f)
+        run(); torch.cuda.synchronize()
+        want = [t.clone() for t in outputs]
+        for t in outputs:
+            t.fill_(float("nan"))
+        graph.replay(); torch.cuda.synchronize()
+        for i, (got, ref) in enumerate(zip(outputs, want)):
+            assert torch.equal(got, ref), f"replay {rep}: output {i} differs from the eager result"
+
+
+def test_hip_graph_replays_batch_one_routes(routed):
+    """The routes through partition passes under capture: cursors are cleared by a kernel, the reservations are atomics
+    whose order changes nothing in the results."""
+    r = np.random.default_rng(22)
+    k, n = 21000, 47000
+    a, b = anchors("ties", r, k, n)
+    da, db = dev(a), dev(b)
+    dx = torch.empty(n, 1, device="cuda"); dg = torch.empty(k, 1, device="cuda")
+    y = torch.empty(k, 1, device="cuda"); gx = torch.empty(n, 1, device="cuda")
+    ga = torch.empty(k, device="cuda"); gb = torch.empty(n, device="cuda")
+    ws = workspace(k, n, 1)
+
+    def run():
+        B.laplex_apply(da, db, dx, y, ws, B.LAPLEX_SAVE_SCANS)
+        B.laplex_apply_backward(da, db, dx, dg, gx, ga, gb, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
+
+    dx.normal_(); dg.normal_()
+    fresh = lambda: (torch.from_numpy(r.normal(size=(n, 1)).astype(np.float32)).cuda(),
+                     torch.from_numpy(r.normal(size=(k, 1)).astype(np.float32)).cuda())
+    _replay_check(run, (dx, dg), (y, gx, ga, gb), fresh)
+
+
+def test_hip_graph_replays_phased_wide_batch():
+    r = np.random.default_rng(23)
+    k, n, batch = 900, 26000, 128
+    a, b = clustered_outputs(r, k, n)
+    da, db = dev(a), dev(b)
+    dphi = dev(r.uniform(-3, 3, k).astype(np.float32)); dpsi = dev(r.uniform(-3, 3, n).astype(np.float32))
+    dx = torch.empty(n, batch, device="cuda"); dg = torch.empty(k, batch, device="cuda")
+    y = torch.empty(k, batch, device="cuda"); gx = torch.empty(n, batch, device="cuda")
+    ga = torch.empty(k, device="cuda"); gb = torch.empty(n, device="cuda")
+    gphi = torch.empty(k, device="cuda"); gpsi = torch.empty(n, device="cuda")
+    ws = phased_workspace(k, n, batch)
+
+    def run():
+        B.laplex_phased_apply(da, dphi, db, dpsi, dx, y, ws, B.LAPLEX_SAVE_SCANS)
+        B.laplex_phased_apply_backward(da, dphi, db, dpsi, dx, dg, gx, ga, gb, gphi, gpsi, ws,
+                                       B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
+
+    dx.normal_(); dg.normal_()
+    fresh = lambda: (torch.from_numpy(r.normal(size=(n, batch)).astype(np.float32)).cuda(),
+                     torch.from_numpy(r.normal(size=(k, batch)).astype(np.float32)).cuda())
+    _replay_check(run, (dx, dg), (y, gx, ga, gb, gphi, gpsi), fresh, reps=3)
+
+
 # ------------------------------------------------------------------ non-finite anchors
 
 @pytest.mark.parametrize("sorted_flags", [0, B.LAPLEX_A_SORTED | B.LAPLEX_B_SORTED])
