@@ -244,7 +244,7 @@ ScanProblem problem(const Plan& P, const Layout& L)
 // Workspace of the phased entry points: the workspace of the plain apply on the doubled batch
 // (so the plan stays at the front), then the cosine / sine halves of x, y, gy and gx.
 struct PhasedLayout {
-    size_t inner = 0, off_x2 = 0, off_y2 = 0, off_g2 = 0, off_gx2 = 0, total = 0;
+    size_t inner = 0, off_x2 = 0, off_y2 = 0, off_g2 = 0, off_gx2 = 0, off_state = 0, total = 0;
 };
 
 PhasedLayout phased_layout(int64_t k, int64_t n, int64_t batch)
@@ -257,6 +257,7 @@ PhasedLayout phased_layout(int64_t k, int64_t n, int64_t batch)
     P.off_y2 = o;  o = align_up(o + out_bytes);
     P.off_g2 = o;  o = align_up(o + out_bytes);
     P.off_gx2 = o; o = align_up(o + in_bytes);
+    P.off_state = o; o = align_up(o + sizeof(uint32_t) * 64);      // word 0: the doubled copy of x holds every row
     P.total = o;
     return P;
 }
@@ -841,8 +842,9 @@ int laplex_phased_apply(const float* a, const float* phi, int64_t k, const float
     // With a wide batch the reduce reads x itself and modulates it on the way in; only the rows of blocks that hold outputs
     // are written in doubled form (the other kernels read those).  Otherwise: one pass that writes both halves of x.
     const bool fus_in = phase_fusable(k, n, batch, x, ldx, nullptr, 0);
-    const PhaseIn pin{psi, x, ldx, x2, batch, 1, true};
-    if (!fus_in) LAPLEX_HIP(launch_phase_split(x, ldx, psi, n, batch, x2, st));
+    uint32_t* const whole = reinterpret_cast<uint32_t*>(w + P.off_state);
+    const PhaseIn pin{psi, x, ldx, x2, whole, batch, 1, true};
+    if (!fus_in) LAPLEX_HIP(launch_phase_split(x, ldx, psi, n, batch, x2, st, whole));
     LAPLEX_CHECK(apply_impl(a, k, b, n, x2, 2 * batch, 2 * batch, y2, 2 * batch, ws, P.inner, flags, 1.0f, stream,
                             fus_in ? &pin : nullptr));
     LAPLEX_HIP(launch_phase_merge(y2, phi, k, batch, y, ldy, nullptr, 0, nullptr, st));
@@ -896,10 +898,18 @@ int laplex_phased_apply_backward(const float* a, const float* phi, int64_t k, co
     const bool fus_in = x != nullptr && phase_fusable(k, n, batch, x, ldx, nullptr, 0);
     const bool fused = want_gx2 && phase_fusable(k, n, batch, x, ldx, gx, ldgx);
     const bool full_split = x != nullptr && (fus_in ? (gb != nullptr && !fused) : !saved);
-    if (full_split) LAPLEX_HIP(launch_phase_split(x, ldx, psi, n, batch, x2, st));
+    uint32_t* const whole = reinterpret_cast<uint32_t*>(w + P.off_state);
+    if (full_split) {
+        LAPLEX_HIP(launch_phase_split(x, ldx, psi, n, batch, x2, st, whole));
+    } else if (x != nullptr && !fus_in) {
+        // The forward left its doubled copy of x -- all of it, unless it was given rows that allowed it to read x itself
+        // (another pointer or leading dimension than this call's): the copy's own word says which, and the pass runs if needed.
+        LAPLEX_HIP(launch_phase_split(x, ldx, psi, n, batch, x2, st, whole, true));
+        LAPLEX_HIP(launch_set_word(whole, 1u, st));
+    }
     LAPLEX_HIP(launch_phase_split(gy, ldgy, phi, k, batch, g2, st));
-    const PhaseIn pin_fwd{psi, x, ldx, x2, batch, 1, true};
-    const PhaseIn pin_bwd{psi, x, ldx, x2, batch, 2, false};
+    const PhaseIn pin_fwd{psi, x, ldx, x2, whole, batch, 1, true};
+    const PhaseIn pin_bwd{psi, x, ldx, x2, nullptr, batch, 2, false};
     uint32_t inner = flags;
     if (gphi && !saved) {       // the phase gradient of the outputs needs the two halves of the product
         LAPLEX_CHECK(apply_impl(a, k, b, n, x2, 2 * batch, 2 * batch, y2, 2 * batch, ws, P.inner,

@@ -367,6 +367,7 @@ struct PhaseIn {
     const float* psi;               // [rows of x] phases
     const float* x; int64_t ldx;    // [rows of x][half]
     float* x2;                      // [rows of x][2 * half] contiguous: written for the blocks named above
+    uint32_t* whole;                // set to 0 by the block-wise split: x2 does not hold every row (see launch_phase_split)
     int64_t half;                   // columns of one half; 0: off
     int split_blocks;               // 0: none
     bool virtual_inj;               // the reduce reads x with the modulation instead of the injected matrix
@@ -400,8 +401,11 @@ hipError_t launch_scan(const ScanProblem& p, const Layout& L, char* ws, hipStrea
 // Phase modulation of the phased kernel (phase_kernels.hip): split a (rows, batch) matrix into its
 // cosine and sine halves, dst (rows, 2*batch) contiguous; merge two halves back and, if wanted, form
 //   gphase[r] = sum_t other[r][t] (cos(phase_r) src2[r][batch+t] - sin(phase_r) src2[r][t]).
+// `whole` (may be null): a word that says whether dst holds every row (1) or only those of some blocks (0, written by the
+// block-wise split of PhaseIn); the pass sets it to 1, and with unless_whole it does nothing when the word is 1 already.
 hipError_t launch_phase_split(const float* src, int64_t ld_src, const float* phase, int64_t rows, int64_t batch,
-                              float* dst, hipStream_t st);
+                              float* dst, hipStream_t st, uint32_t* whole = nullptr, bool unless_whole = false);
+hipError_t launch_set_word(uint32_t* p, uint32_t v, hipStream_t st);      // *p = v
 hipError_t launch_phase_merge(const float* src2, const float* phase, int64_t rows, int64_t batch,
                               float* dst, int64_t ld_dst, const float* other, int64_t ld_other, float* gphase,
                               hipStream_t st);

@@ -14,10 +14,20 @@ namespace laplex {
 namespace {
 
 // dst[r][t] = src[r][t] cos(phase_r),  dst[r][batch + t] = src[r][t] sin(phase_r);  dst rows are 2 * batch wide
+__global__ void k_set_word(uint32_t* __restrict__ p, uint32_t v)
+{
+    if (threadIdx.x == 0) *p = v;
+}
+
+// `whole` (may be null) records whether dst holds every row: the pass sets it to 1; with `unless_whole` it first looks at the
+// word and does nothing if the rows are all there already (a pass that wrote only some of them had set it to 0).
 __global__ void __launch_bounds__(256)
 k_phase_split(const float* __restrict__ src, int64_t ld_src, const float* __restrict__ phase,
-              int64_t rows, int64_t batch, float* __restrict__ dst)
+              int64_t rows, int64_t batch, float* __restrict__ dst, uint32_t* __restrict__ whole, int unless_whole)
 {
+    if (whole != nullptr && unless_whole && *whole == 1u) return;
+    // (set by a later launch when this one decided by the word: other workgroups may still have to read it)
+    if (whole != nullptr && !unless_whole && blockIdx.x == 0 && threadIdx.x == 0) *whole = 1u;
     const int lane = threadIdx.x & 63;
     const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
@@ -234,12 +244,18 @@ inline unsigned rows_grid(int64_t rows)
 
 }  // namespace
 
+hipError_t launch_set_word(uint32_t* p, uint32_t v, hipStream_t st)
+{
+    LAPLEX_TIMED("phase", st, hipLaunchKernelGGL(k_set_word, dim3(1), dim3(64), 0, st, p, v));
+    return hipGetLastError();
+}
+
 hipError_t launch_phase_split(const float* src, int64_t ld_src, const float* phase, int64_t rows, int64_t batch,
-                              float* dst, hipStream_t st)
+                              float* dst, hipStream_t st, uint32_t* whole, bool unless_whole)
 {
     if (rows <= 0 || batch <= 0) return hipSuccess;
     LAPLEX_TIMED("phase", st, hipLaunchKernelGGL(k_phase_split, dim3(rows_grid(rows)), dim3(256), 0, st,
-                                                 src, ld_src, phase, rows, batch, dst));
+                                                 src, ld_src, phase, rows, batch, dst, whole, unless_whole ? 1 : 0));
     return hipGetLastError();
 }
 

@@ -873,6 +873,7 @@ k_phase_split_blocks(const ScanArgs A)
     const int64_t part = (int64_t)blockIdx.x * kStreamWaves + wave;       // eight rows of a block per wavefront
     const int64_t blk = part >> 3;
     if (blk >= A.blocks) return;
+    if (part == 0 && lane == 0 && A.pin.whole != nullptr) *A.pin.whole = 0u;       // x2 holds the rows of some blocks only
     const int flags = (int)A.blk_flags[blk];
     const int mode = A.pin.split_blocks;
     uint32_t lo, hi;          // ids of the rows of x

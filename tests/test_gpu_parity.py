@@ -672,6 +672,18 @@ def test_phased_backward_merges_in_the_downsweep(oracle, kind, k, n, batch):
     torch.cuda.synchronize()
     for name, got, rv, tv in zip(names, outs, want, tols):
         assert_close(name, got.cpu().numpy(), rv, tv)
+    # ... also when it continues a forward that was given rows it could read directly (the doubled copy of x that the
+    # forward left holds the rows of some blocks only: the backward finds that out and completes it), and the other way round
+    y2 = torch.full((k, batch), float("nan"), device="cuda")
+    xv = xp[:, :batch]              # the same rows, 4 * (batch + 1) bytes apart
+    for fwd_x, bwd_x in ((dev(x), xv), (xv, dev(x))):
+        B.laplex_phased_apply(da, dphi, db, dpsi, fwd_x, y2, ws, B.LAPLEX_SAVE_SCANS)
+        outs = [torch.full(s_, float("nan"), device="cuda") for s_ in ((n, batch), (k,), (n,), (k,), (n,))]
+        B.laplex_phased_apply_backward(da, dphi, db, dpsi, bwd_x, dg, *outs, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
+        torch.cuda.synchronize()
+        assert_close("y", y2.cpu().numpy(), ref, tol)
+        for name, got, rv, tv in zip(names, outs, want, tols):
+            assert_close(name, got.cpu().numpy(), rv, tv)
 
 
 def test_phased_backward_invalid_plan_poisons():
