@@ -2167,6 +2167,55 @@ __device__ __forceinline__ Seg<1, STRICT> wave_scan64(Seg<1, STRICT> s, int lane
     return seg_compose<1, STRICT>(pre, s);
 }
 
+// The same scans with the decay of every composite summary re-taken from the anchors (equal spans have equal decays with
+// equal rounding errors; a chain of them, as on a regular grid, multiplies the error by its length).  A lane brings the
+// anchor its span starts from in scan order (pb) and the one it ends at (pe): forward the sorted anchor before its first row
+// and at its last row, backward the anchor after its last row and at its first.  The decay over the lanes [lo .. lane] of a
+// composite is then exp(-|pe(lane) - pb(lo)|), one fast exponential.
+template <bool FWD>
+__device__ __forceinline__ float anchored_decay(float pb_of_start, float pe_of_end)
+{
+    // (lanes past the end of the sequence bring the +inf sentinel at both ends: an empty span, decay 1)
+    return pb_of_start == pe_of_end ? 1.0f : decay_fast(FWD ? pe_of_end - pb_of_start : pb_of_start - pe_of_end);
+}
+template <bool FWD, bool STRICT, int STEP>      // one step of the scan inside a row of 16 lanes: partners 2 * STEP - 1 .. STEP lanes back
+__device__ __forceinline__ void row_step_anchored(Seg<1, STRICT>& s, float pb, float pe, float pb_row)
+{
+    constexpr int kBack = 2 * STEP - 1;         // after this step a lane's summary starts this many lanes back (or at the row's start)
+    s = seg_compose<1, STRICT>(seg_dpp<(FWD ? 0x110 : 0x100) + STEP, STRICT>(s), s);
+    const float pb_start = dpp_move<(FWD ? 0x110 : 0x100) + kBack>(pb_row, pb);
+    s.D = anchored_decay<FWD>(pb_start, pe);
+    if (STRICT) s.C = s.D;
+}
+template <bool FWD, bool STRICT>
+__device__ __forceinline__ Seg<1, STRICT> wave_scan64_anchored(Seg<1, STRICT> s, float pb, float pe, int lane)
+{
+    const float pb_row = __shfl(pb, FWD ? lane & ~15 : lane | 15);     // where this lane's row of 16 starts in scan order
+    row_step_anchored<FWD, STRICT, 1>(s, pb, pe, pb_row);
+    row_step_anchored<FWD, STRICT, 2>(s, pb, pe, pb_row);
+    row_step_anchored<FWD, STRICT, 4>(s, pb, pe, pb_row);
+    row_step_anchored<FWD, STRICT, 8>(s, pb, pe, pb_row);
+    // totals of the first three rows in scan order sit in the row's last lane in scan order
+    const int l0 = FWD ? 15 : 48, l1 = FWD ? 31 : 32, l2 = FWD ? 47 : 16, first = FWD ? 0 : 63;
+    const Seg<1, STRICT> t0 = seg_of_lane<STRICT>(s, l0), t1 = seg_of_lane<STRICT>(s, l1), t2 = seg_of_lane<STRICT>(s, l2);
+    const float pb_first = lane_f(pb, first);
+    Seg<1, STRICT> p2 = seg_compose<1, STRICT>(t0, t1);
+    p2.D = anchored_decay<FWD>(pb_first, lane_f(pe, l1)); if (STRICT) p2.C = p2.D;
+    Seg<1, STRICT> p3 = seg_compose<1, STRICT>(p2, t2);
+    p3.D = anchored_decay<FWD>(pb_first, lane_f(pe, l2)); if (STRICT) p3.C = p3.D;
+    const int before = FWD ? lane >> 4 : 3 - (lane >> 4);       // rows ahead of this lane's in scan order
+    Seg<1, STRICT> pre = seg_identity<1, STRICT>();
+    pre.D = before == 1 ? t0.D : before == 2 ? p2.D : before == 3 ? p3.D : 1.0f;
+    pre.S[0] = before == 1 ? t0.S[0] : before == 2 ? p2.S[0] : before == 3 ? p3.S[0] : 0.0f;
+    if (STRICT) {
+        pre.Q[0] = before == 1 ? t0.Q[0] : before == 2 ? p2.Q[0] : before == 3 ? p3.Q[0] : 0.0f;
+        pre.H = before == 1 ? t0.H : before == 2 ? p2.H : before == 3 ? p3.H : 0;
+    }
+    Seg<1, STRICT> r = seg_compose<1, STRICT>(pre, s);
+    r.D = anchored_decay<FWD>(pb_first, pe); if (STRICT) r.C = r.D;
+    return r;
+}
+
 template <int ITEMS>
 struct SeqRows {
     static_assert(ITEMS % 4 == 0 && ITEMS <= 32, "a row-lane's rows are read in 16-byte pieces; one bit per row");
@@ -2387,7 +2436,7 @@ k_seq_down(const ScanArgs A)
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) seg_push<1, STRICT>(f, T.alive(i) && T.dh[i] >= 0.0f, T.dh[i], v[i]);
         f.D = lane_df;
-        f = wave_scan64<true, STRICT>(f, lane);
+        f = wave_scan64_anchored<true, STRICT>(f, p_lane0.x, p_lane1.x, lane);
         if (lane == 63) { Seg<1, STRICT> tot = f; tot.D = wave_df; W.template put<STRICT>(0, wave, tot); }
         fe = seg_shfl<1, STRICT>(f, (lane - 1) & 63);
         if (lane == 0) fe = seg_identity<1, STRICT>();
@@ -2397,7 +2446,7 @@ k_seq_down(const ScanArgs A)
 #pragma unroll
         for (int i = ITEMS - 1; i >= 0; --i) seg_push<1, STRICT>(b, T.alive(i) && T.dh[i + 1] >= 0.0f, T.dh[i + 1], v[i]);
         b.D = lane_db;
-        b = wave_scan64<false, STRICT>(b, lane);
+        b = wave_scan64_anchored<false, STRICT>(b, p_lane1.y, p_lane0.y, lane);
         if (lane == 0) { Seg<1, STRICT> tot = b; tot.D = wave_db; W.template put<STRICT>(1, wave, tot); }
         be = seg_shfl<1, STRICT>(b, (lane + 1) & 63);
         if (lane == 63) be = seg_identity<1, STRICT>();
