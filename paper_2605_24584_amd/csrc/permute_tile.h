@@ -129,4 +129,79 @@ __device__ __forceinline__ void partition_place(const PartEmit& E, int64_t chain
     }
 }
 
+// The same two steps for a producer that is short of registers between them: the destinations go to their LDS slots at
+// once (sd: THREADS * PER words that nobody touches until partition_place_split is through) and a thread keeps only its
+// records' slots; the values follow through sv (THREADS * PER floats, which may alias LDS the caller is done with when it
+// calls partition_place_split).
+template <int PER>
+struct PartSplitTicket {
+    static_assert(PER % 2 == 0, "two slots per word");
+    uint32_t slot2[PER / 2];  // LDS slots of records 2i (low half) and 2i + 1 (high half)
+    uint32_t before, ex;
+    __device__ __forceinline__ uint32_t slot(int i) const { return (i & 1) ? slot2[i >> 1] >> 16 : slot2[i >> 1] & 0xFFFFu; }
+};
+
+template <int THREADS, int PER>
+__device__ __forceinline__ void partition_reserve_split(const PartEmit& E, int64_t chain, const uint32_t* dest, uint32_t ok,
+                                                        PartShared<THREADS>& S, uint32_t* sd, PartSplitTicket<PER>& K)
+{
+    static_assert(THREADS * PER <= 65536, "a slot fits 16 bits");
+    PartTicket<PER> T;
+    partition_reserve<THREADS, PER>(E, chain, dest, ok, S, T);
+    K.before = T.before; K.ex = T.ex;
+    const uint32_t digit_mask = (1u << E.bucket_bits) - 1u;
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        const uint32_t slot = ((ok >> i) & 1u) ? T.slot[i] + S.lstart[(dest[i] >> E.shift) & digit_mask] : 0u;
+        if ((ok >> i) & 1u) sd[slot] = dest[i];
+        if (i & 1) K.slot2[i >> 1] |= slot << 16; else K.slot2[i >> 1] = slot;
+    }
+}
+
+template <int THREADS, int PER, int NV>
+__device__ __forceinline__ void partition_place_split(const PartEmit& E, int64_t chain, uint32_t ok, const float* v0, const float* v1,
+                                                      PartShared<THREADS>& S, const uint32_t* sd, float* sv, const PartSplitTicket<PER>& K)
+{
+    const int tid = threadIdx.x;
+    const int buckets = 1 << E.bucket_bits;
+    const uint32_t digit_mask = (uint32_t)buckets - 1u;
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < PER; ++i)
+        if ((ok >> i) & 1u) sv[K.slot(i)] = v0[i];
+    if (tid < buckets) S.delta[tid] = ((uint32_t)tid << E.region_shift) + K.before - K.ex;
+    __syncthreads();
+
+    const uint32_t total = S.lstart[buckets - 1] + S.hist[buckets - 1];
+    const int64_t chain_base = (chain << E.bucket_bits) << E.region_shift;
+    const uint32_t region = 1u << E.region_shift;
+    uint32_t where[PER];
+    constexpr uint32_t kNone = 0xFFFFFFFFu;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        const uint32_t s = (uint32_t)(i * THREADS + tid);
+        where[i] = kNone;
+        if (s < total) {
+            const uint32_t d = sd[s];
+            const uint32_t b = (d >> E.shift) & digit_mask;
+            const uint32_t off = S.delta[b] + s;
+            if (off - (b << E.region_shift) < region) {
+                where[i] = off;
+                E.out_dv[chain_base + off] = make_uint2(d, __float_as_uint(sv[s]));
+            }
+        }
+    }
+    if (NV == 2) {
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < PER; ++i)
+            if ((ok >> i) & 1u) sv[K.slot(i)] = v1[i];
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < PER; ++i)
+            if (where[i] != kNone) E.out_v1[chain_base + where[i]] = sv[i * THREADS + tid];
+    }
+}
+
 }  // namespace laplex

@@ -2067,11 +2067,14 @@ k_phase_merge_blocks(const ScanArgs A)
 // kernels read each array in 16-byte pieces.  Same summaries, carries and walks as k_scan_reduce / k_scan_down at one column per
 // lane: 64 row-lanes per wavefront, 16 rows per row-lane, 8 wavefronts per block of 8192 rows.
 // ---------------------------------------------------------------------------
-// The reduce keeps the geometry of the generic kernels (8 wavefronts, 16 rows per row-lane); the downsweep, which holds
-// its rows' results in registers until they leave as records, takes 16 wavefronts with 8 rows per row-lane: the same
-// block of 8192 rows, half the registers per lane, one workgroup of 16 wavefronts per compute unit.
+// Both kernels keep the geometry of the generic ones (8 wavefronts, 16 rows per row-lane, blocks of 8192 rows).  The
+// downsweep holds its rows' results in registers until they leave as records and has to stay within 128 registers for
+// two workgroups to share a compute unit (one of them loads or stores while the other scans: with a single workgroup of
+// 16 wavefronts and 8 rows per row-lane, which needs no care about registers, the kernel's phases simply add up — 15 ms
+// instead of 9.5 at 2^31 rows): the records' destinations wait in LDS, the rows' slots are packed two to a register,
+// and the variant with a row reduction asks for its rows only after the reservation.
 constexpr int kSeqItems = kItemsVec1;
-constexpr int kSeqDownItems = 8, kSeqDownWaves = 16, kSeqDownThreads = kSeqDownWaves * 64;
+constexpr int kSeqDownItems = 16, kSeqDownWaves = 8, kSeqDownThreads = kSeqDownWaves * 64;
 static_assert(kSeqDownItems * kSeqDownThreads == kSeqItems * kScanThreads, "both kernels own blocks of the same rows");
 
 // exp(-x) by the hardware's base-2 exponential after one multiplication.  Only for decays that multiply a carry over a
@@ -2366,7 +2369,7 @@ k_seq_reduce(const ScanArgs A)
 // RED: the second output of a row is w * Z (w = A.wstage, sorted order), else Z itself (STRICT) or nothing.
 // NV: values per record that leaves (2: both outputs; 1: A.emit_first says which).
 template <bool STRICT, bool RED, int NV>
-__global__ void __launch_bounds__(kSeqDownThreads)
+__global__ void __launch_bounds__(kSeqDownThreads, 4)
 k_seq_down(const ScanArgs A)
 {
     constexpr int ITEMS = kSeqDownItems, WAVES = kSeqDownWaves, THREADS = kSeqDownThreads;
@@ -2396,18 +2399,21 @@ k_seq_down(const ScanArgs A)
     const float enter_df = ahead.df, enter_db = behind.db;
     const bool enter_hf = ahead.hf, enter_hb = behind.hb;
 
+    // The rows' decays and values are asked for at once, before the ids, unless the weights of a row reduction have to fit
+    // in the registers as well: then they follow the reservation, when the ids have left (asked for early, that variant
+    // spills; the others lose 10 % when they ask late).
     SeqRows<ITEMS> T;
-    seq_meta<ITEMS>(A, row0, T);
     float v[ITEMS][1], wt[RED ? ITEMS : 1];
-    {
+    float Fc[1], Ec[1], Rc[1], Gc[1];
+    auto load_rows = [&]() {
+        seq_meta<ITEMS>(A, row0, T);
         float t[ITEMS];
         seq_load<ITEMS>(A.stage, row0, A.N, t);
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) v[i][0] = t[i];
-        if (RED) seq_load<ITEMS>(A.wstage, row0, A.N, wt);
-    }
-    float Fc[1], Ec[1], Rc[1], Gc[1];
-    load_block_carries<1, STRICT>(A, tile, 0, true, Fc, Ec, Rc, Gc);
+        load_block_carries<1, STRICT>(A, tile, 0, true, Fc, Ec, Rc, Gc);
+    };
+    if (!RED) load_rows();
     // The result rows will leave as records of the first partition level (destination = id - first result id).  Where
     // they go depends on the ids alone, so the stretches are reserved now, and the answers travel during the walks.
     uint32_t dest[ITEMS];
@@ -2424,12 +2430,14 @@ k_seq_down(const ScanArgs A)
     }
 #pragma unroll
     for (int i = 0; i < ITEMS; ++i) {
-        const bool res = T.alive(i) && dest[i] >= A.res_lo && dest[i] < A.res_hi;
+        const bool res = row0 + i < A.N && dest[i] >= A.res_lo && dest[i] < A.res_hi;
         dest[i] -= A.res_lo;
         ok |= (res && (int64_t)dest[i] < A.emit.dest_count) ? 1u << i : 0u;
     }
-    PartTicket<ITEMS> K;
-    partition_reserve<THREADS, ITEMS>(A.emit, 0, dest, ok, S, K);
+    PartSplitTicket<ITEMS> K;
+    uint32_t* const sd = reinterpret_cast<uint32_t*>(smem) + ITEMS * THREADS;    // upper half: the records' destinations
+    partition_reserve_split<THREADS, ITEMS>(A.emit, 0, dest, ok, S, sd, K);
+    if (RED) load_rows();
     Seg<1, STRICT> fe, be;
     {
         Seg<1, STRICT> f = seg_identity<1, STRICT>();
@@ -2454,11 +2462,13 @@ k_seq_down(const ScanArgs A)
     __syncthreads();
     // the state each wavefront starts from when the block starts from zero: one wavefront scans the 16 wavefront summaries
     // of each direction (lane l holds the l-th in scan order) and leaves what precedes every wavefront
-    static_assert(WAVES == 16, "the wavefront summaries fill one row of 16 lanes");
+    static_assert(WAVES <= 16, "the wavefront summaries fit one row of 16 lanes");
     if (wave == 0) {
-        const int l = lane & 15;
-        Seg<1, STRICT> sf = row_scan16<true, STRICT>(W.template get<STRICT>(0, l));              // lane l: wavefronts 0 .. l
-        Seg<1, STRICT> sb = row_scan16<true, STRICT>(W.template get<STRICT>(1, WAVES - 1 - l));   // lane l: wavefronts 15 .. 15 - l
+        const int l = lane & 15, lw = l < WAVES ? l : WAVES - 1;
+        Seg<1, STRICT> sf = W.template get<STRICT>(0, lw), sb = W.template get<STRICT>(1, WAVES - 1 - lw);
+        if (l >= WAVES) sf = sb = seg_identity<1, STRICT>();
+        sf = row_scan16<true, STRICT>(sf);      // lane l: wavefronts 0 .. l
+        sb = row_scan16<true, STRICT>(sb);      // lane l: wavefronts WAVES - 1 .. WAVES - 1 - l
         if (lane < WAVES - 1) {
             W.preF[0][lane + 1] = sf.S[0]; W.preE[0][lane + 1] = (STRICT && sf.H) ? sf.Q[0] : 0.0f;                      // before wavefront l + 1
             W.preF[1][WAVES - 2 - lane] = sb.S[0]; W.preE[1][WAVES - 2 - lane] = (STRICT && sb.H) ? sb.Q[0] : 0.0f;      // after wavefront 14 - l
@@ -2472,6 +2482,7 @@ k_seq_down(const ScanArgs A)
     enter_state<1, STRICT>(F, E, Fc, Ec, enter_df, enter_hf);
     enter_state<1, STRICT>(R, G, Rc, Gc, enter_db, enter_hb);
     if (STRICT) __syncthreads();      // every wavefront is done with the summaries: the buffer now holds E per row
+    if (RED) seq_load<ITEMS>(A.wstage, row0, A.N, wt);      // (late: the weights are needed by the last loop only)
 
     float Ff[ITEMS];
 #pragma unroll
@@ -2497,7 +2508,7 @@ k_seq_down(const ScanArgs A)
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) Ff[i] = second[i];
     }
-    partition_place<THREADS, ITEMS, NV>(A.emit, 0, dest, ok, Ff, STRICT ? second : Ff, S, reinterpret_cast<uint2*>(smem), K);
+    partition_place_split<THREADS, ITEMS, NV>(A.emit, 0, ok, Ff, STRICT ? second : Ff, S, sd, reinterpret_cast<float*>(smem), K);
 }
 
 __global__ void __launch_bounds__(256)
