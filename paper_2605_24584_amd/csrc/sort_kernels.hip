@@ -19,9 +19,8 @@ namespace {
 
 __device__ __forceinline__ uint32_t float_to_key(float f)
 {
-    uint32_t u = __float_as_uint(f);
-    if (u == 0x80000000u) u = 0u;                       // -0.0 sorts as +0.0
-    return u ^ ((u >> 31) ? 0xFFFFFFFFu : 0x80000000u);
+    const uint32_t u = __float_as_uint(f + 0.0f);       // -0.0 sorts as +0.0: the sum is +0.0, every other value is itself
+    return u ^ ((uint32_t)((int32_t)u >> 31) | 0x80000000u);
 }
 
 __device__ __forceinline__ float key_to_float(uint32_t key)
@@ -113,36 +112,65 @@ __device__ __forceinline__ uint32_t anchor_key(const float* __restrict__ a, int6
     return float_to_key(tau * (pos < k ? a[pos] : b[pos - k]));
 }
 
-// Digit counters in LDS, kHistCopies times (a lane uses copy lane % kHistCopies, and the copies start
-// 8 banks apart): keys that share a digit value then queue on different words and banks.
+// Digit counters in LDS.  Two layouts:
+//   plain    kHistCopies copies of the 4 x 256 counters (a lane uses copy lane % kHistCopies, and the copies start 8
+//            banks apart): keys that share a digit value queue on different words.  64 lanes with unrelated digit
+//            values still land 5-6 deep on the busiest of the 32 banks, and an LDS atomic is a read and a write: the
+//            kernel runs at ~13 clocks per atomic instruction, which is what bounds it.
+//   banked   (many keys per workgroup) every counter of the three low digits 32 times, one per bank: lane l adds to
+//            word (counter << 5) + (l & 31), so an instruction touches each bank exactly twice whatever the digit
+//            values are.  96 KB of LDS, one workgroup of 16 wavefronts per compute unit.
+// The top digit (sign and high exponent bits) takes few values, and consecutive keys of a lane mostly share one: a lane
+// counts its current run in a register and adds it to a counter (kHistCopies copies in both layouts) when the value
+// changes, and once at the end.
 constexpr int kHistCopies = 4;
 constexpr int kHistCopyWords = kSortPasses * kRadix + 8;
+constexpr int kHistBankedThreads = 1024;
+constexpr int64_t kHistBankedMin = int64_t(1) << 22;     // merged positions from which the banked layout is used
+constexpr int kHistBankedLowWords = (kSortPasses - 1) * kRadix * 32;
+constexpr int kHistTopCopyWords = kRadix + 8;
 
-__device__ __forceinline__ void hist_count(uint32_t* __restrict__ h, uint32_t key, bool ok)
+template <bool BANKED> struct HistLds;
+template <> struct HistLds<false> { uint32_t h[kHistCopies * kHistCopyWords]; };
+template <> struct HistLds<true> { uint32_t low[kHistBankedLowWords]; uint32_t top[kHistCopies * kHistTopCopyWords]; };
+
+struct TopRun {
+    uint32_t cur = 0u, cnt = 0u;
+};
+template <bool BANKED>
+__device__ __forceinline__ uint32_t* hist_top_word(HistLds<BANKED>& L, uint32_t value)
 {
-    uint32_t* mine = h + (threadIdx.x & (kHistCopies - 1)) * kHistCopyWords;
+    const int copy = threadIdx.x & (kHistCopies - 1);
+    if constexpr (BANKED) return &L.top[copy * kHistTopCopyWords + value];
+    else return &L.h[copy * kHistCopyWords + (kSortPasses - 1) * kRadix + value];
+}
+template <bool BANKED>
+__device__ __forceinline__ void hist_flush(HistLds<BANKED>& L, TopRun& run)
+{
+    if (run.cnt) atomicAdd(hist_top_word<BANKED>(L, run.cur), run.cnt);
+    run.cnt = 0u;
+}
+template <bool BANKED>
+__device__ __forceinline__ void hist_count(HistLds<BANKED>& L, uint32_t key, bool ok, TopRun& run)
+{
     if (ok) {
 #pragma unroll
-        for (int p = 0; p < kSortPasses - 1; ++p) atomicAdd(&mine[p * kRadix + ((key >> (p * kRadixBits)) & (kRadix - 1))], 1u);
-    }
-    // The top digit (sign and high exponent bits) takes few values, and most keys of a wavefront share one: the lanes
-    // that hold the first lane's value are counted with one ballot and added by one lane; the others (few, on few
-    // words) add themselves.  (A loop over the distinct values of the wavefront cost a dozen instructions per value
-    // and key and made the kernel compute-bound; the same treatment for the three low digits, whose values are spread
-    // out, only added instructions: 2.6 -> 3.2 ms at 2^31 keys.)
-    const uint32_t top = key >> ((kSortPasses - 1) * kRadixBits);
-    const uint64_t live = __ballot(ok);
-    if (live) {         // uniform
-        const int leader = __ffsll((long long)live) - 1;
-        const uint32_t v = (uint32_t)__builtin_amdgcn_readlane((int)top, leader);
-        const uint64_t same = __ballot(ok && top == v);
-        if ((int)(threadIdx.x & 63) == leader) atomicAdd(&mine[(kSortPasses - 1) * kRadix + v], (uint32_t)__popcll(same));
-        else if (ok && top != v) atomicAdd(&mine[(kSortPasses - 1) * kRadix + top], 1u);
+        for (int p = 0; p < kSortPasses - 1; ++p) {
+            const uint32_t counter = p * kRadix + ((key >> (p * kRadixBits)) & (kRadix - 1));
+            if constexpr (BANKED) atomicAdd(&L.low[(counter << 5) + (threadIdx.x & 31)], 1u);
+            else atomicAdd(&L.h[(threadIdx.x & (kHistCopies - 1)) * kHistCopyWords + counter], 1u);
+        }
+        const uint32_t top = key >> ((kSortPasses - 1) * kRadixBits);
+        const uint32_t diff = top ^ run.cur;
+        if (diff != 0u && run.cnt) atomicAdd(hist_top_word<BANKED>(L, run.cur), run.cnt);
+        run.cnt = (run.cnt & ((diff != 0u) ? 0u : 0xFFFFFFFFu)) + 1u;       // 1 after a change, one more otherwise
+        run.cur = top;
     }
 }
 
 // One anchor array: a scalar head up to the first 16-byte boundary, 16-byte loads (two in flight per lane), a scalar tail.
-__device__ __forceinline__ void hist_stream(uint32_t* __restrict__ h, const float* __restrict__ p, int64_t count, float tau)
+template <bool BANKED>
+__device__ __forceinline__ void hist_stream(HistLds<BANKED>& h, const float* __restrict__ p, int64_t count, float tau, TopRun& run)
 {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const int64_t first = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -154,38 +182,55 @@ __device__ __forceinline__ void hist_stream(uint32_t* __restrict__ h, const floa
         const bool ok1 = q0 + stride < quads;
         const float4 v0 = p4[q0];
         const float4 v1 = p4[ok1 ? q0 + stride : q0];
-        hist_count(h, float_to_key(tau * v0.x), true); hist_count(h, float_to_key(tau * v0.y), true);
-        hist_count(h, float_to_key(tau * v0.z), true); hist_count(h, float_to_key(tau * v0.w), true);
-        hist_count(h, float_to_key(tau * v1.x), ok1); hist_count(h, float_to_key(tau * v1.y), ok1);
-        hist_count(h, float_to_key(tau * v1.z), ok1); hist_count(h, float_to_key(tau * v1.w), ok1);
+        hist_count<BANKED>(h, float_to_key(tau * v0.x), true, run); hist_count<BANKED>(h, float_to_key(tau * v0.y), true, run);
+        hist_count<BANKED>(h, float_to_key(tau * v0.z), true, run); hist_count<BANKED>(h, float_to_key(tau * v0.w), true, run);
+        hist_count<BANKED>(h, float_to_key(tau * v1.x), ok1, run); hist_count<BANKED>(h, float_to_key(tau * v1.y), ok1, run);
+        hist_count<BANKED>(h, float_to_key(tau * v1.z), ok1, run); hist_count<BANKED>(h, float_to_key(tau * v1.w), ok1, run);
     }
     // the head and the tail: fewer than 8 keys
     const int64_t rest = count - 4 * quads;
     if (first < rest) {
         const int64_t i = first < head ? first : 4 * quads + first;
-        hist_count(h, float_to_key(tau * p[i]), true);
+        hist_count<BANKED>(h, float_to_key(tau * p[i]), true, run);
     }
 }
 
-__global__ void __launch_bounds__(kSortThreads)
+template <bool BANKED>
+__global__ void __launch_bounds__(BANKED ? kHistBankedThreads : kSortThreads)
 k_sort_hist(const float* __restrict__ a, int64_t k, const float* __restrict__ b, int64_t n, float tau,
             uint32_t* __restrict__ ghist, unsigned long long* __restrict__ status0, int64_t status_words)
 {
-    __shared__ uint32_t h[kHistCopies * kHistCopyWords];
-    for (int i = threadIdx.x; i < kHistCopies * kHistCopyWords; i += kSortThreads) h[i] = 0u;
+    constexpr int THREADS = BANKED ? kHistBankedThreads : kSortThreads;
+    __shared__ HistLds<BANKED> L;
+    {
+        uint32_t* const words = reinterpret_cast<uint32_t*>(&L);
+        for (int i = threadIdx.x; i < (int)(sizeof(L) / sizeof(uint32_t)); i += THREADS) words[i] = 0u;
+    }
     __syncthreads();
     const int64_t N = k + n;
-    hist_stream(h, a, k, tau);
-    hist_stream(h, b, n, tau);
+    TopRun run;
+    hist_stream<BANKED>(L, a, k, tau, run);
+    hist_stream<BANKED>(L, b, n, tau, run);
+    hist_flush<BANKED>(L, run);
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const int64_t first = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     for (int64_t i = first; i < status_words; i += stride) status0[i] = 0ull;   // look-back words of pass 0
     __syncthreads();
     uint32_t seen = 0;
-    for (int i = threadIdx.x; i < kSortPasses * kRadix; i += kSortThreads) {
+    for (int i = threadIdx.x; i < kSortPasses * kRadix; i += THREADS) {
         uint32_t c = 0;
+        if constexpr (BANKED) {
+            if (i < (kSortPasses - 1) * kRadix) {
 #pragma unroll
-        for (int r = 0; r < kHistCopies; ++r) c += h[r * kHistCopyWords + i];
+                for (int r = 0; r < 32; ++r) c += L.low[(i << 5) + ((r + threadIdx.x) & 31)];      // (rotated: each lane on a bank of its own)
+            } else {
+#pragma unroll
+                for (int r = 0; r < kHistCopies; ++r) c += L.top[r * kHistTopCopyWords + i - (kSortPasses - 1) * kRadix];
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < kHistCopies; ++r) c += L.h[r * kHistCopyWords + i];
+        }
         if (c) seen |= atomicAdd(&ghist[i], c);
     }
     // (the additions return a value, and the value is waited for here: they have been performed where every
@@ -204,7 +249,7 @@ k_sort_hist(const float* __restrict__ a, int64_t k, const float* __restrict__ b,
     }
     __syncthreads();
     if (!s_last) return;
-    for (int i = threadIdx.x; i < kSortPasses * kRadix; i += kSortThreads)
+    for (int i = threadIdx.x; i < kSortPasses * kRadix; i += THREADS)
         if ((int64_t)__hip_atomic_load(&ghist[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == N) atomicOr(&constant_mask, 1u << (i / kRadix));
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -600,10 +645,17 @@ hipError_t launch_onesweep_sort(const float* a, int64_t k, const float* b, int64
     const int64_t words = tiles * kRadix;
     unsigned long long* region[2] = {status, status + words};
     LAPLEX_TIMED("sort_hist", st, hipLaunchKernelGGL(k_sort_reset, dim3(1), dim3(1024), 0, st, small));
-    int64_t hgrid = (N + sort_hist_tile(N) - 1) / sort_hist_tile(N);
-    if (hgrid > 2048) hgrid = 2048;
-    LAPLEX_TIMED("sort_hist", st, hipLaunchKernelGGL(k_sort_hist, dim3((unsigned)hgrid), dim3(kSortThreads), 0, st,
-                                                     a, k, b, n, tau, small, region[0], words));
+    if (N >= kHistBankedMin) {      // one workgroup per compute unit, twice over: each clears and sums 100 KB of counters once
+        int64_t hgrid = (N + (int64_t(1) << 16) - 1) >> 16;
+        if (hgrid > 256) hgrid = 256;
+        LAPLEX_TIMED("sort_hist", st, hipLaunchKernelGGL(k_sort_hist<true>, dim3((unsigned)hgrid), dim3(kHistBankedThreads), 0, st,
+                                                         a, k, b, n, tau, small, region[0], words));
+    } else {
+        int64_t hgrid = (N + sort_hist_tile(N) - 1) / sort_hist_tile(N);
+        if (hgrid > 2048) hgrid = 2048;
+        LAPLEX_TIMED("sort_hist", st, hipLaunchKernelGGL(k_sort_hist<false>, dim3((unsigned)hgrid), dim3(kSortThreads), 0, st,
+                                                         a, k, b, n, tau, small, region[0], words));
+    }
     const dim3 grid((unsigned)tiles), block(kSortThreads);
     auto passes = [&](auto kernel, auto* r0, auto* r1) {
         using WORD = std::remove_pointer_t<decltype(r0)>;

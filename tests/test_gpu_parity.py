@@ -127,9 +127,10 @@ SHAPES = [(1, 1, 1), (5, 1, 2), (1, 6, 1), (37, 53, 3), (100, 9000, 1), (9000, 1
 # ------------------------------------------------------------------ the sort
 
 @pytest.mark.parametrize("kind", KINDS)
-# the last three: one size for each tile size of the sort passes (2048, 4096 and 8192 pairs), with ragged last tiles
+# the last four: one size for each tile size of the sort passes (2048, 4096 and 8192 pairs), with ragged last tiles, and one
+# beyond 2^22 merged positions, where the histogram keeps its counters once per LDS bank
 @pytest.mark.parametrize("k,n", [(1, 1), (3, 0), (0, 5), (100, 157), (9000, 8000), (20000, 70001),
-                                 (130000, 132001), (300001, 400122), (1500000, 1000003)])
+                                 (130000, 132001), (300001, 400122), (1500000, 1000003), (2300001, 2100003)])
 def test_permutation_bit_exact(oracle, kind, k, n):
     if k == 0 or n == 0:
         pytest.skip("apply with an empty side builds no plan")
@@ -142,7 +143,7 @@ def test_permutation_bit_exact(oracle, kind, k, n):
 
 
 @pytest.mark.parametrize("off_a,off_b", [(1, 0), (2, 3), (3, 1), (0, 2)])
-@pytest.mark.parametrize("k,n", [(1, 2), (2, 1), (3, 7), (4100, 4100), (9001, 20003)])
+@pytest.mark.parametrize("k,n", [(1, 2), (2, 1), (3, 7), (4100, 4100), (9001, 20003), (2100001, 2100002)])
 def test_anchor_arrays_off_a_16_byte_boundary(oracle, off_a, off_b, k, n):
     """The histogram reads the anchors 16 bytes at a time between a scalar head and a scalar tail."""
     r = np.random.default_rng(k * 5 + n + off_a * 16 + off_b)
