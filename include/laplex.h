@@ -256,6 +256,13 @@ int laplex_phased_apply_backward(const float* a, const float* phi, int64_t k,
  * LAPLEX_SAVE_SCANS the forward call (same flag, same workspace) has left what the
  * backward needs; without it the products needed for gw are recomputed.  x may be
  * NULL if only gx is wanted.  r == 0 gives y = 0.
+ * Streams: everything is ordered after the work already in `stream`, and work put
+ * into `stream` afterwards is ordered after everything these calls do.  In between,
+ * operators with more than 8192 merged positions and small matrices may run on up to
+ * four streams that the library creates once per device (default priority) and keeps;
+ * while `stream` is being captured into a graph they stay on it.  The results do not
+ * depend on which of the two happens.  Calls on different host threads take turns
+ * while they enqueue.
  */
 int laplex_mix_workspace_bytes(int64_t r, int64_t k, int64_t n, int64_t batch, size_t* out /* host */);
 

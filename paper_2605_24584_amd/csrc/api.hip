@@ -331,22 +331,88 @@ int check_wgram_sizes(int64_t k, int64_t n)
 // the operator at hand, its gx, and the partial sums of the inner products.
 // ----------------------------------------------------------------------------
 struct MixLayout {
-    size_t inner = 0, off_parts = 0, off_gyq = 0, off_gxq = 0, off_partial = 0, total = 0;
+    size_t inner = 0, off_parts = 0, off_gyq = 0, off_gxq = 0, off_gxp = 0, off_partial = 0, total = 0;
+    int lanes = 1;      // operators in flight at a time on the large path (each on a stream of its own)
 };
+
+// Beyond the small path an operator is a chain of two dozen launches; while the matrices are small each of them fills a
+// fraction of the device for a few microseconds, and the chains of different operators share nothing but x and gy: up to
+// kMixLanes of them run side by side, each on a stream of the library's own, with its own copy of the per-operator scratch.
+constexpr int kMixLanes = 4;
+constexpr int64_t kMixLanesMaxElements = int64_t(1) << 24;      // (k + n) * batch up to which that pays
+
+int mix_lanes(int64_t r, int64_t k, int64_t n, int64_t batch)
+{
+    if (k + n <= kSmallMax || r < 2 || (k + n) * batch > kMixLanesMaxElements) return 1;
+    return r < kMixLanes ? (int)r : kMixLanes;
+}
 
 MixLayout mix_layout(int64_t r, int64_t k, int64_t n, int64_t batch)
 {
     MixLayout M;
+    M.lanes = mix_lanes(r, k, n, batch);
     M.inner = align_up(make_layout(k + n, k, batch).total);
     size_t o = M.inner * (size_t)r;
     M.off_parts = o;   o = align_up(o + sizeof(float) * (size_t)r * (size_t)k * (size_t)batch);
-    // small problems run all operators in one launch and need these per operator
-    const size_t per_op = (k + n <= kSmallMax) ? (size_t)r : 1;
+    // small problems run all operators in one launch and need these per operator; the large path per lane
+    const size_t per_op = (k + n <= kSmallMax) ? (size_t)r : (size_t)M.lanes;
     M.off_gyq = o;     o = align_up(o + sizeof(float) * per_op * (size_t)k * (size_t)batch);
     M.off_gxq = o;     o = align_up(o + sizeof(float) * per_op * (size_t)n * (size_t)batch);
-    M.off_partial = o; o = align_up(o + sizeof(float) * (kTauPartials > (size_t)r * kDotGroups ? kTauPartials : (size_t)r * kDotGroups));
+    M.off_gxp = o;     if (M.lanes > 1) o = align_up(o + sizeof(float) * (size_t)M.lanes * (size_t)n * (size_t)batch);   // the lanes' sums of gx
+    const size_t dots = (size_t)M.lanes * kTauPartials > (size_t)r * kDotGroups ? (size_t)M.lanes * kTauPartials : (size_t)r * kDotGroups;
+    M.off_partial = o; o = align_up(o + sizeof(float) * dots);
     M.total = o;
     return M;
+}
+
+constexpr int kMaxDevices = 64;
+
+// The lanes' streams (default priority, not synchronising with the null stream) and the events that fork them from the
+// caller's stream and join them back: created on a device's first use, kept until the process ends.
+struct MixStreams {
+    hipStream_t lane[kMixLanes];
+    hipEvent_t fork, join[kMixLanes];
+};
+std::mutex g_mix_mutex;             // held while a call enqueues on the lanes: the events are shared
+MixStreams* g_mix_streams[kMaxDevices] = {};
+
+// The current device's lanes, or null when the work has to stay on the caller's stream: a stream that is being captured
+// (the lanes are not part of the caller's graph), or streams that could not be created.  Call with g_mix_mutex held.
+MixStreams* mix_streams(hipStream_t caller)
+{
+    hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(caller, &capture) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+    if (capture != hipStreamCaptureStatusNone) return nullptr;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { (void)hipGetLastError(); return nullptr; }
+    if (!g_mix_streams[dev]) {
+        MixStreams* m = new MixStreams();
+        bool ok = hipEventCreateWithFlags(&m->fork, hipEventDisableTiming) == hipSuccess;
+        for (int l = 0; ok && l < kMixLanes; ++l)
+            ok = hipStreamCreateWithFlags(&m->lane[l], hipStreamNonBlocking) == hipSuccess &&
+                 hipEventCreateWithFlags(&m->join[l], hipEventDisableTiming) == hipSuccess;
+        if (!ok) { (void)hipGetLastError(); delete m; return nullptr; }      // (what was created stays: a handful of handles, once)
+        g_mix_streams[dev] = m;
+    }
+    return g_mix_streams[dev];
+}
+
+// The lanes start after everything the caller's stream holds so far ...
+hipError_t mix_fork(MixStreams* m, int lanes, hipStream_t caller)
+{
+    hipError_t e = hipEventRecord(m->fork, caller);
+    for (int l = 0; e == hipSuccess && l < lanes; ++l) e = hipStreamWaitEvent(m->lane[l], m->fork, 0);
+    return e;
+}
+// ... and the caller's stream goes on after everything the lanes hold.
+hipError_t mix_join(MixStreams* m, int lanes, hipStream_t caller)
+{
+    hipError_t e = hipSuccess;
+    for (int l = 0; e == hipSuccess && l < lanes; ++l) {
+        e = hipEventRecord(m->join[l], m->lane[l]);
+        if (e == hipSuccess) e = hipStreamWaitEvent(caller, m->join[l], 0);
+    }
+    return e;
 }
 
 int check_mix_sizes(int64_t r, int64_t k, int64_t n, int64_t batch)
@@ -715,7 +781,6 @@ int laplex_apply(const float* a, int64_t k, const float* b, int64_t n,
 static __device__ __align__(256) unsigned char scratch[LAPLEX_STATIC_WORKSPACE_BYTES];
 
 namespace {
-constexpr int kMaxDevices = 64;
 std::mutex g_scratch_mutex;
 void* g_scratch_ptr[kMaxDevices] = {};
 
@@ -1059,9 +1124,14 @@ int laplex_mix_apply(const float* a, const float* b, const float* w, int64_t r, 
         q.out_z = (flags & LAPLEX_SAVE_SCANS) ? P.z : nullptr; q.op_z = (int64_t)(M.inner / sizeof(float));
         LAPLEX_HIP(launch_small(S, r, st));
     } else {
+        std::unique_lock<std::mutex> lock(g_mix_mutex, std::defer_lock);
+        MixStreams* lanes = nullptr;
+        if (M.lanes > 1) { lock.lock(); lanes = mix_streams(st); }
+        if (lanes) LAPLEX_HIP(mix_fork(lanes, M.lanes, st));
         for (int64_t q = 0; q < r; ++q)
             LAPLEX_CHECK(laplex_apply(a + q * k, k, b + q * n, n, x, ldx, batch, parts + q * k * batch, batch,
-                                      base + (size_t)q * M.inner, M.inner, flags, stream));
+                                      base + (size_t)q * M.inner, M.inner, flags, lanes ? lanes->lane[q % M.lanes] : stream));
+        if (lanes) LAPLEX_HIP(mix_join(lanes, M.lanes, st));
     }
     LAPLEX_HIP(launch_mix_combine(parts, w, r, k, batch, y, ldy, st));
     return LAPLEX_OK;
@@ -1149,24 +1219,42 @@ int laplex_mix_apply_backward(const float* a, const float* b, const float* w, in
         if (gw) LAPLEX_HIP(launch_dot_ops(gy, ldgy, parts, r, k, batch, partial, gw, st));
         return LAPLEX_OK;
     }
+    std::unique_lock<std::mutex> lock(g_mix_mutex, std::defer_lock);
+    MixStreams* lanes = nullptr;
+    if (M.lanes > 1) { lock.lock(); lanes = mix_streams(st); }
+    if (lanes) LAPLEX_HIP(mix_fork(lanes, M.lanes, st));
+    // The arithmetic follows the lanes whether or not their streams are used (a captured stream keeps everything to
+    // itself): each lane sums the gx of its operators, the lanes' sums are added at the end.
+    const bool split = M.lanes > 1;
+    float* gxp = reinterpret_cast<float*>(base + M.off_gxp);
     for (int64_t q = 0; q < r; ++q) {
+        const int l = split ? (int)(q % M.lanes) : 0;
+        hipStream_t sq = lanes ? lanes->lane[l] : st;
         char* wq = base + (size_t)q * M.inner;
         float* part = parts + q * k * batch;
+        float* gy_l = gyq + (size_t)l * k * batch;
+        float* gx_l = gxq + (size_t)l * n * batch;
+        float* sum_l = gxp + (size_t)l * n * batch;
         uint32_t inner = flags;
         if (gw && !saved) {        // the weight's gradient needs the operator's own product
             LAPLEX_CHECK(laplex_apply(a + q * k, k, b + q * n, n, x, ldx, batch, part, batch, wq, M.inner,
-                                      flags | LAPLEX_SAVE_SCANS, stream));
+                                      flags | LAPLEX_SAVE_SCANS, sq));
             inner = flags | LAPLEX_SAVE_SCANS | LAPLEX_REUSE_PLAN;
         }
         if (gx || ga || gb) {      // the operator's gradients are linear in the upstream gradient: scale it by w_q
-            LAPLEX_HIP(launch_scale_by_device_scalar(gy, ldgy, w + q, k, batch, gyq, st));
-            LAPLEX_CHECK(laplex_apply_backward(a + q * k, k, b + q * n, n, x, ldx, gyq, batch, batch,
-                                               gx ? gxq : nullptr, batch, ga ? ga + q * k : nullptr,
-                                               gb ? gb + q * n : nullptr, wq, M.inner, inner, stream));
-            if (gx) LAPLEX_HIP(launch_accumulate(gxq, n, batch, gx, ldgx, q == 0, st));
+            LAPLEX_HIP(launch_scale_by_device_scalar(gy, ldgy, w + q, k, batch, gy_l, sq));
+            // a lane's first operator writes the lane's sum itself, the later ones are added to it
+            float* gx_out = !gx ? nullptr : (split && q < M.lanes) ? sum_l : gx_l;
+            LAPLEX_CHECK(laplex_apply_backward(a + q * k, k, b + q * n, n, x, ldx, gy_l, batch, batch,
+                                               gx_out, batch, ga ? ga + q * k : nullptr,
+                                               gb ? gb + q * n : nullptr, wq, M.inner, inner, sq));
+            if (gx && !split) LAPLEX_HIP(launch_accumulate(gx_l, n, batch, gx, ldgx, q == 0, sq));
+            else if (gx && q >= M.lanes) LAPLEX_HIP(launch_accumulate(gx_l, n, batch, sum_l, batch, false, sq));
         }
-        if (gw) LAPLEX_HIP(launch_dot(gy, ldgy, part, k, batch, partial, gw + q, st));
+        if (gw) LAPLEX_HIP(launch_dot(gy, ldgy, part, k, batch, partial + (size_t)l * kTauPartials, gw + q, sq));
     }
+    if (lanes) LAPLEX_HIP(mix_join(lanes, M.lanes, st));
+    if (split && gx) LAPLEX_HIP(launch_mix_combine(gxp, nullptr, M.lanes, n, batch, gx, ldgx, st));
     return LAPLEX_OK;
 }
 

@@ -535,6 +535,29 @@ def test_hip_graph_replays_phased_wide_batch():
     _replay_check(run, (dx, dg), (y, gx, ga, gb, gphi, gpsi), fresh, reps=3)
 
 
+def test_hip_graph_replays_mix_on_the_large_path():
+    """Under capture the operators of a sum stay on the captured stream; the arithmetic (a sum of gx per lane, then the
+    lanes' sums) is the one of the eager call on the lanes' streams, so every replay gives the eager bits."""
+    r = np.random.default_rng(24)
+    ops, k, n, batch = 6, 400, 8400, 8
+    ab = [anchors("ties", r, k, n) for _ in range(ops)]
+    da = dev(np.stack([u for u, _ in ab])); db = dev(np.stack([v for _, v in ab]))
+    dw = dev(r.normal(size=ops).astype(np.float32))
+    dx = torch.empty(n, batch, device="cuda"); dg = torch.empty(k, batch, device="cuda")
+    y = torch.empty(k, batch, device="cuda"); gx = torch.empty(n, batch, device="cuda")
+    ga = torch.empty(ops, k, device="cuda"); gb = torch.empty(ops, n, device="cuda"); gw = torch.empty(ops, device="cuda")
+    ws = torch.empty(B.laplex_mix_workspace_bytes(ops, k, n, batch), dtype=torch.uint8, device="cuda")
+
+    def run():
+        B.laplex_mix_apply(da, db, dw, dx, y, ws, B.LAPLEX_SAVE_SCANS)
+        B.laplex_mix_apply_backward(da, db, dw, dx, dg, gx, ga, gb, gw, ws, B.LAPLEX_SAVE_SCANS | B.LAPLEX_REUSE_PLAN)
+
+    dx.normal_(); dg.normal_()
+    fresh = lambda: (torch.from_numpy(r.normal(size=(n, batch)).astype(np.float32)).cuda(),
+                     torch.from_numpy(r.normal(size=(k, batch)).astype(np.float32)).cuda())
+    _replay_check(run, (dx, dg), (y, gx, ga, gb, gw), fresh, reps=3)
+
+
 # ------------------------------------------------------------------ non-finite anchors
 
 @pytest.mark.parametrize("sorted_flags", [0, B.LAPLEX_A_SORTED | B.LAPLEX_B_SORTED])
@@ -876,8 +899,9 @@ def gpu_mix(a, b, w, x, g, flags_fwd, flags_bwd, want=(True, True, True, True), 
 @pytest.mark.parametrize("kind", ["uniform", "ties"])
 @pytest.mark.parametrize("r,k,n,batch", [(1, 5, 1, 2), (3, 37, 53, 3), (4, 10, 512, 64), (16, 100, 768, 128),
                                          (2, 1000, 2048, 256), (5, 300, 2100, 1),
-                                         # more than 8192 merged positions: one operator after the other on the large path
-                                         (2, 500, 9000, 4), (3, 40, 8200, 64)])
+                                         # more than 8192 merged positions: the large path, up to four operators side by
+                                         # side on streams of the library's own (the last case: two rounds of them)
+                                         (2, 500, 9000, 4), (3, 40, 8200, 64), (6, 300, 8300, 16)])
 def test_mix_forward_backward(oracle, kind, r, k, n, batch):
     """y = sum_q w_q L(a_q, b_q) x and the gradients (gx, ga, gb, gw), the classification-head shapes
     (classes x features) among them."""
