@@ -314,8 +314,8 @@ def family_bytes(fam, spec, np, B):
         return 4 * N, "the anchors read once"
     if fam == "decay":
         if batch == 1 and N >= (1 << 22):
-            return 13 * N, "keys read, decays and sorted anchors written, every eighth anchor pair once more"
-        return 12 * N, "keys read, decays and sorted anchors written"
+            return 9 * N, "sorted anchors read (the sort's last pass wrote them), decays written, every eighth anchor pair once more"
+        return 8 * N, "sorted anchors read (the sort's last pass wrote them), decays written"
     base, _, tag = fam.partition(".")
     # batch 1 from 2^22 merged positions on: values travel between the caller's order and the sorted order as records
     # (destination, value[, value]) through partition levels, and the scans work on plain arrays in sorted order

@@ -192,17 +192,16 @@ int build_plan(const float* a, int64_t k, const float* b, int64_t n, float tau, 
     const Plan P = plan_of(L, ws);
     uint2* pair0 = reinterpret_cast<uint2*>(ws + L.off_pair0);
     uint2* pair1 = reinterpret_cast<uint2*>(ws + L.off_pair1);
-    uint32_t* keys0 = reinterpret_cast<uint32_t*>(pair0);      // sorted keys alone: the front of one of the pair buffers
-    uint32_t* keys1 = reinterpret_cast<uint32_t*>(pair1);
+    uint32_t* keys0 = reinterpret_cast<uint32_t*>(pair0);      // the merge leaves its sorted keys here
     uint32_t* small = reinterpret_cast<uint32_t*>(ws + L.off_sort_small);
     uint32_t* counters = reinterpret_cast<uint32_t*>(ws + L.off_counters);
     if (both_sorted) {
         LAPLEX_HIP(launch_merge(a, k, b, n, tau, keys0, P.ids, st));
-        LAPLEX_HIP(launch_decay(keys0, keys1, nullptr, P.dh, P.pk, P.pk8, counters, L.N, st));
+        LAPLEX_HIP(launch_decay(keys0, nullptr, P.dh, P.pk, P.pk8, counters, L.N, st));
     } else {
-        LAPLEX_HIP(launch_onesweep_sort(a, k, b, n, tau, pair0, pair1, P.ids, small,
+        LAPLEX_HIP(launch_onesweep_sort(a, k, b, n, tau, pair0, pair1, P.ids, P.pk, small,
                                         reinterpret_cast<unsigned long long*>(ws + L.off_status), st));
-        LAPLEX_HIP(launch_decay(keys0, keys1, small, P.dh, P.pk, P.pk8, counters, L.N, st));
+        LAPLEX_HIP(launch_decay(nullptr, small, P.dh, P.pk, P.pk8, counters, L.N, st));
     }
     if (use_permute(L)) {        // the inverse permutation, part of the plan: rank[ids[j]] = j
         PermuteJob J = permute_job(L, ws, "rank");

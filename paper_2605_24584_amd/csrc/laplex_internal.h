@@ -272,11 +272,11 @@ void profile_after(const char* family, hipStream_t st);
 
 // The anchors enter every plan scaled by the inverse temperature tau (1 = as they are).
 // Stable ascending sort of the anchors a ++ b by one-sweep LSD passes.  Between passes the (key, id) pairs travel
-// interleaved through the two pair buffers; the last pass that runs writes the sorted ids to `ids` (the plan's) and the
-// sorted keys alone to the front of the pair buffer it would have written (k_decay finds them from the pass mask).
+// interleaved through the two pair buffers; the last pass that runs writes the sorted ids to `ids` and the sorted anchors
+// to pk[1 .. N] (both the plan's).
 // small: u32[kSortSmallWords] (global histogram, tickets, error word, pass mask); status: u64[2][tiles*256] look-back words.
 hipError_t launch_onesweep_sort(const float* a, int64_t k, const float* b, int64_t n, float tau,
-                                uint2* pair0, uint2* pair1, uint32_t* ids,
+                                uint2* pair0, uint2* pair1, uint32_t* ids, float* pk,
                                 uint32_t* small, unsigned long long* status, hipStream_t st);
 
 // Both inputs ascending: merged keys/ids in one pass (ties: a first).
@@ -285,11 +285,11 @@ hipError_t launch_merge(const float* a, int64_t k, const float* b, int64_t n, fl
 
 // dh[j] = decay from sorted key j-1 to j (>= 0), or -1 if the two keys are equal;
 // dh[0] = dh[N] = 0 (nothing beyond either end).  pk[j+1] = sorted anchor j, pk[0] = -inf, pk[N+1] = +inf.
-// The sorted keys are in keys0, or, after an odd number of radix passes (ghist tells), in keys1 (the fronts of the two
-// pair buffers); ghist == nullptr: keys0 (merge path).  The last kernel of every plan build: it also clears the scans'
-// list counters (64 words).
-hipError_t launch_decay(const uint32_t* keys0, const uint32_t* keys1,
-                        const uint32_t* ghist, float* dh, float* pk, float2* pk8, uint32_t* counters, int64_t N, hipStream_t st);
+// After the radix sort (ghist = its small words) the anchors are in pk[1 .. N] already and the kernel adds the sentinels;
+// ghist == nullptr: the merge path, which leaves sorted keys in `keys`.  The last kernel of every plan build: it also
+// clears the scans' list counters (64 words).
+hipError_t launch_decay(const uint32_t* keys, const uint32_t* ghist, float* dh, float* pk, float2* pk8, uint32_t* counters,
+                        int64_t N, hipStream_t st);
 
 hipError_t launch_fill(float* p, int64_t rows, int64_t cols, int64_t ld, float v, hipStream_t st);
 hipError_t launch_copy_u32(const uint32_t* src, uint32_t* dst, int64_t count, hipStream_t st);

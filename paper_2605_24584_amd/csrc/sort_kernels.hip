@@ -263,7 +263,7 @@ template <typename WORD, int KPT>
 __global__ void __launch_bounds__(kSortThreads)
 k_onesweep_pass(const float* __restrict__ a, int64_t k, const float* __restrict__ b, float tau,
                 uint2* __restrict__ pair0, uint2* __restrict__ pair1,           // (key, id) pairs between passes
-                uint32_t* __restrict__ ids_final,                               // the last pass's ids (the plan's)
+                uint32_t* __restrict__ ids_final, float* __restrict__ pk_final,  // the last pass's ids and anchors (the plan's)
                 int64_t N, int pass, const uint32_t* __restrict__ ghist, uint32_t* __restrict__ small,
                 WORD* status, WORD* status_next)
 {
@@ -298,14 +298,13 @@ k_onesweep_pass(const float* __restrict__ a, int64_t k, const float* __restrict_
     // reads buffer 1 and writes buffer 0, and so on.  Between passes key and id travel as one 8-byte pair: a
     // digit's run of a tile is then 256 bytes on average instead of 128 in each of two arrays (a copy with nothing
     // but this write pattern runs at 3.1 TB/s on two arrays, as fast as the pass itself used to, and at 4.1 TB/s on
-    // pairs), one load and one store per key instead of two.  The last pass that runs writes the ids to the plan and
-    // the keys alone to the front of the buffer it would have written (k_decay knows from the same rule where they are).
+    // pairs), one load and one store per key instead of two.  The last pass that runs writes the ids and the sorted
+    // anchors themselves straight into the plan (k_decay adds the sentinels and the decays).
     const int before = __popc(active & ((1u << pass) - 1u));
     const bool first = before == 0;
     const bool last = (active >> pass) == 1u;            // no pass after this one runs
     const uint2* __restrict__ pairs_in = (before & 1) ? pair1 : pair0;
     uint2* __restrict__ pairs_out = (before & 1) ? pair0 : pair1;
-    uint32_t* __restrict__ keys_final = reinterpret_cast<uint32_t*>(pairs_out);
 
     const int64_t tile = s_tile;
     if (status_next && tid < kRadix) status_next[tile * kRadix + tid] = WORD(0);   // words of the pass after this one
@@ -446,7 +445,7 @@ k_onesweep_pass(const float* __restrict__ a, int64_t k, const float* __restrict_
                 const uint2 kv = spairs[slot];
                 const uint32_t dst = delta[(kv.x >> shift) & (kRadix - 1)] + slot;
                 if ((int64_t)dst < N) {   // always true for consistent offsets; keeps a fault impossible
-                    keys_final[dst] = kv.x;
+                    pk_final[dst + 1] = key_to_float(kv.x);      // pk[j + 1]: the anchor of sorted position j
                     ids_final[dst] = kv.y;
                 }
             }
@@ -550,48 +549,65 @@ k_merge(const float* __restrict__ a, int64_t k, const float* __restrict__ b, int
 // Each lane takes four consecutive positions: one 16-byte load of the keys, 16-byte stores of the decays and of
 // the anchors (the sorted ids are in the plan already: the sort's last pass, or the merge, wrote them there).  pk[j] holds the anchor of
 // position j - 1, so the four anchors a lane stores are the key before its quad and the quad's first three.
+// FROM_PK: the sort's last pass has written the sorted anchors into pk[1 .. N] already; this kernel reads them there and
+// adds the two sentinels.  Otherwise (the merge of two sorted anchor sets) it starts from the sorted keys.
+template <bool FROM_PK>
 __global__ void __launch_bounds__(256)
-k_decay(const uint32_t* __restrict__ keys0, const uint32_t* __restrict__ keys1,
-        const uint32_t* __restrict__ ghist, float* __restrict__ dh, float* __restrict__ pk, float2* __restrict__ pk8,
-        uint32_t* __restrict__ counters, int64_t N)
+k_decay(const uint32_t* __restrict__ keys, const uint32_t* __restrict__ ghist, float* __restrict__ dh, float* __restrict__ pk,
+        float2* __restrict__ pk8, uint32_t* __restrict__ counters, int64_t N)
 {
     // list lengths of the scans that follow; and the sort's error flag moves to the plan (the sort's own words are scratch)
     if (blockIdx.x == 0 && threadIdx.x < 64)
         counters[threadIdx.x] = (threadIdx.x == kPlanStatusWord && ghist != nullptr) ? ghist[kSortErrorWord] : 0u;
-    // after an odd number of passes the sorted keys sit at the front of buffer 1 (ghist == nullptr: merge path, buffer 0)
-    const bool in1 = ghist != nullptr && (__popc(ghist[kSortMaskWord]) & 1);
-    const uint32_t* __restrict__ keys = in1 ? keys1 : keys0;
     const int64_t quads = (N + 2 + 3) / 4;                       // dh has N + 1 entries, pk N + 2
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < quads; q += stride) {
         const int64_t j0 = 4 * q;
-        uint32_t kk[5];                                          // keys j0 - 1 .. j0 + 3 (0 where there is none)
-        kk[0] = j0 > 0 && j0 - 1 < N ? keys[j0 - 1] : 0u;
-        const bool whole = j0 + 3 < N;
-        if (whole) {
-            const uint4 v = reinterpret_cast<const uint4*>(keys)[q];
-            kk[1] = v.x; kk[2] = v.y; kk[3] = v.z; kk[4] = v.w;
-        } else {
+        uint32_t kk[5];                                          // bits of the anchors of positions j0 - 1 .. j0 + 3 (0 where there is none)
+        if (FROM_PK) {
+            const uint32_t* __restrict__ bits = reinterpret_cast<const uint32_t*>(pk);      // bits[j + 1]: position j
+            if (j0 > 0 && j0 + 4 <= N) {
+                const uint4 v = reinterpret_cast<const uint4*>(bits)[q];
+                kk[0] = v.x; kk[1] = v.y; kk[2] = v.z; kk[3] = v.w; kk[4] = bits[j0 + 4];
+            } else {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) kk[1 + u] = j0 + u < N ? keys[j0 + u] : 0u;
+                for (int u = 0; u < 5; ++u) kk[u] = (j0 + u >= 1 && j0 + u <= N) ? bits[j0 + u] : 0u;
+            }
+        } else {
+            kk[0] = j0 > 0 && j0 - 1 < N ? keys[j0 - 1] : 0u;
+            if (j0 + 3 < N) {
+                const uint4 v = reinterpret_cast<const uint4*>(keys)[q];
+                kk[1] = v.x; kk[2] = v.y; kk[3] = v.z; kk[4] = v.w;
+            } else {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) kk[1 + u] = j0 + u < N ? keys[j0 + u] : 0u;
+            }
         }
+        float an[5];
+#pragma unroll
+        for (int u = 0; u < 5; ++u) an[u] = FROM_PK ? __uint_as_float(kk[u]) : key_to_float(kk[u]);
         float d[4], a[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int64_t j = j0 + u;
             d[u] = 0.0f;
-            if (j > 0 && j < N) d[u] = kk[1 + u] == kk[u] ? -1.0f : expf(-(key_to_float(kk[1 + u]) - key_to_float(kk[u])));
-            a[u] = j == 0 ? __uint_as_float(0xFF800000u) : (j <= N ? key_to_float(kk[u]) : __uint_as_float(0x7F800000u));
+            if (j > 0 && j < N) d[u] = kk[1 + u] == kk[u] ? -1.0f : expf(-(an[1 + u] - an[u]));
+            a[u] = j == 0 ? __uint_as_float(0xFF800000u) : (j <= N ? an[u] : __uint_as_float(0x7F800000u));
         }
+        const bool whole = j0 + 3 < N;
         if (whole) {
             reinterpret_cast<float4*>(dh)[q] = make_float4(d[0], d[1], d[2], d[3]);
-            reinterpret_cast<float4*>(pk)[q] = make_float4(a[0], a[1], a[2], a[3]);
+            if (!FROM_PK) reinterpret_cast<float4*>(pk)[q] = make_float4(a[0], a[1], a[2], a[3]);
         } else {
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 if (j0 + u <= N) dh[j0 + u] = d[u];
-                if (j0 + u <= N + 1) pk[j0 + u] = a[u];
+                if (!FROM_PK && j0 + u <= N + 1) pk[j0 + u] = a[u];
             }
+        }
+        if (FROM_PK) {      // the sentinels before the first and after the last anchor
+            if (j0 == 0) pk[0] = a[0];
+            if (j0 <= N + 1 && N + 1 < j0 + 4) pk[N + 1] = __uint_as_float(0x7F800000u);
         }
         // every eighth anchor with its successor once more, packed (the kernels of the sorted order of batch 1 take their
         // span decays from these instead of touching every sector of pk)
@@ -637,7 +653,7 @@ inline unsigned grid_for(int64_t work, int threads, int64_t cap = 1 << 16)
 }  // namespace
 
 hipError_t launch_onesweep_sort(const float* a, int64_t k, const float* b, int64_t n, float tau,
-                                uint2* pair0, uint2* pair1, uint32_t* ids,
+                                uint2* pair0, uint2* pair1, uint32_t* ids, float* pk,
                                 uint32_t* small, unsigned long long* status, hipStream_t st)
 {
     const int64_t N = k + n;
@@ -663,7 +679,7 @@ hipError_t launch_onesweep_sort(const float* a, int64_t k, const float* b, int64
         WORD* nxt[4] = {r1, r0, r1, nullptr};
         for (int p = 0; p < kSortPasses; ++p)
             LAPLEX_TIMED("radix_scatter", st, hipLaunchKernelGGL(kernel, grid, block, 0, st,
-                         a, k, b, tau, pair0, pair1, ids, N, p, (const uint32_t*)small, small, cur[p], nxt[p]));
+                         a, k, b, tau, pair0, pair1, ids, pk, N, p, (const uint32_t*)small, small, cur[p], nxt[p]));
     };
     if (N <= (int64_t(1) << 30)) {
         uint32_t* r = reinterpret_cast<uint32_t*>(status);
@@ -687,11 +703,12 @@ hipError_t launch_merge(const float* a, int64_t k, const float* b, int64_t n, fl
     return hipGetLastError();
 }
 
-hipError_t launch_decay(const uint32_t* keys0, const uint32_t* keys1,
-                        const uint32_t* ghist, float* dh, float* pk, float2* pk8, uint32_t* counters, int64_t N, hipStream_t st)
+hipError_t launch_decay(const uint32_t* keys, const uint32_t* ghist, float* dh, float* pk, float2* pk8, uint32_t* counters,
+                        int64_t N, hipStream_t st)
 {
-    LAPLEX_TIMED("decay", st, hipLaunchKernelGGL(k_decay, dim3(grid_for((N + 5) / 4, 256)), dim3(256), 0, st,
-                                                 keys0, keys1, ghist, dh, pk, pk8, counters, N));
+    const dim3 grid(grid_for((N + 5) / 4, 256)), block(256);
+    if (ghist != nullptr) LAPLEX_TIMED("decay", st, hipLaunchKernelGGL(k_decay<true>, grid, block, 0, st, keys, ghist, dh, pk, pk8, counters, N));
+    else LAPLEX_TIMED("decay", st, hipLaunchKernelGGL(k_decay<false>, grid, block, 0, st, keys, ghist, dh, pk, pk8, counters, N));
     return hipGetLastError();
 }
 
